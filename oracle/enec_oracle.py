@@ -1,0 +1,191 @@
+"""ctypes front end of the plain-C ENEC oracle (oracle/enec_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and
+by the cpu_baseline leg of bench.py.  The GPU library never imports it.
+
+`build()` compiles the C file with gcc into oracle/libenec_oracle.so; the
+wrappers below only marshal numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "enec_oracle.c")
+_LIB = os.path.join(_HERE, "libenec_oracle.so")
+
+OK, E_ARG, E_DTYPE, E_BLOCK, E_PARAMS, E_CAPACITY, E_RANGE, E_FORMAT = range(8)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle.  -ffp-contract=off keeps Eq. 4 in plain IEEE double."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        u8p, u16p, u64p = C.POINTER(C.c_uint8), C.POINTER(C.c_uint16), C.POINTER(C.c_uint64)
+        L.orc_hh_pack.restype = C.c_size_t
+        L.orc_hh_pack.argtypes = [u16p, C.c_size_t, C.c_int, u8p]
+        L.orc_hh_unpack.restype = C.c_size_t
+        L.orc_hh_unpack.argtypes = [u8p, C.c_size_t, C.c_int, u16p]
+        for f in (L.orc_transform, L.orc_inverse_transform):
+            f.restype = C.c_uint
+            f.argtypes = [C.c_uint, C.c_uint, C.c_uint]
+        L.orc_in_range.restype = C.c_int
+        L.orc_in_range.argtypes = [C.c_uint, C.c_uint, C.c_uint]
+        L.orc_width_for.restype = C.c_uint
+        L.orc_width_for.argtypes = [C.c_uint, C.c_uint, C.c_uint]
+        L.orc_histogram.restype = None
+        L.orc_histogram.argtypes = [u16p, C.c_size_t, u64p]
+        L.orc_tune_hist.restype = None
+        L.orc_tune_hist.argtypes = [u64p, u8p, u64p, C.POINTER(C.c_double)]
+        L.orc_tune.restype = None
+        L.orc_tune.argtypes = [u16p, C.c_size_t, u8p, u64p, C.POINTER(C.c_double)]
+        L.orc_default_block.restype = C.c_uint32
+        L.orc_default_block.argtypes = [C.c_size_t]
+        L.orc_num_blocks.restype = C.c_size_t
+        L.orc_num_blocks.argtypes = [C.c_size_t, C.c_uint32]
+        L.orc_payload_base.restype = C.c_size_t
+        L.orc_payload_base.argtypes = [C.c_size_t, C.c_uint32]
+        L.orc_compress_bound.restype = C.c_size_t
+        L.orc_compress_bound.argtypes = [C.c_size_t, C.c_uint32]
+        L.orc_compress.restype = C.c_int
+        L.orc_compress.argtypes = [u16p, C.c_size_t, C.c_uint32, u8p, u8p, C.c_size_t,
+                                   C.POINTER(C.c_size_t)]
+        L.orc_stream_info.restype = C.c_int
+        L.orc_stream_info.argtypes = [u8p, u8p, u64p, C.POINTER(C.c_uint32), u64p,
+                                      C.POINTER(C.c_uint32)]
+        L.orc_decompress.restype = C.c_int
+        L.orc_decompress.argtypes = [u8p, C.c_size_t, u16p, C.c_size_t]
+        _lib = L
+    return _lib
+
+
+def _p(arr, ctype):
+    return arr.ctypes.data_as(C.POINTER(ctype))
+
+
+def _u16(w) -> np.ndarray:
+    w = np.ascontiguousarray(w)
+    assert w.dtype == np.uint16, "bf16 values are passed as their uint16 bit patterns"
+    return w.reshape(-1)
+
+
+def hh_pack(values, a: int) -> np.ndarray:
+    v = np.ascontiguousarray(values, dtype=np.uint16)
+    out = np.zeros(2 * v.size + 2, dtype=np.uint8)
+    n = lib().orc_hh_pack(_p(v, C.c_uint16), v.size, a, _p(out, C.c_uint8))
+    return out[:n].copy()
+
+
+def hh_unpack(stream, N: int, a: int) -> np.ndarray:
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    out = np.zeros(N, dtype=np.uint16)
+    lib().orc_hh_unpack(_p(s, C.c_uint8), N, a, _p(out, C.c_uint16))
+    return out
+
+
+def transform(x: int, b: int, n: int) -> int:
+    return int(lib().orc_transform(x, b, n))
+
+
+def inverse_transform(y: int, b: int, n: int) -> int:
+    return int(lib().orc_inverse_transform(y, b, n))
+
+
+def in_range(x: int, b: int, n: int) -> bool:
+    return bool(lib().orc_in_range(x, b, n))
+
+
+def width_for(b: int, l: int, h: int) -> int:
+    return int(lib().orc_width_for(b, l, h))
+
+
+def histogram(w) -> np.ndarray:
+    w = _u16(w)
+    hist = np.zeros(256, dtype=np.uint64)
+    lib().orc_histogram(_p(w, C.c_uint16), w.size, _p(hist, C.c_uint64))
+    return hist
+
+
+def tune_hist(hist):
+    """-> ((b, n, m, L), D_integer, B_exp)"""
+    hist = np.ascontiguousarray(hist, dtype=np.uint64)
+    params = np.zeros(4, dtype=np.uint8)
+    D = C.c_uint64(0)
+    bexp = C.c_double(0)
+    lib().orc_tune_hist(_p(hist, C.c_uint64), _p(params, C.c_uint8), C.byref(D), C.byref(bexp))
+    return tuple(int(v) for v in params), int(D.value), float(bexp.value)
+
+
+def tune(w):
+    """-> (b, n, m, L) for a tensor of bf16 bit patterns."""
+    return tune_hist(histogram(w))[0]
+
+
+def default_block(n_elems: int) -> int:
+    return int(lib().orc_default_block(n_elems))
+
+
+def num_blocks(n_elems: int, B: int) -> int:
+    return int(lib().orc_num_blocks(n_elems, B))
+
+
+def payload_base(n_elems: int, B: int) -> int:
+    return int(lib().orc_payload_base(n_elems, B))
+
+
+def compress_bound(n_elems: int, B: int) -> int:
+    return int(lib().orc_compress_bound(n_elems, B))
+
+
+def compress(w, params, B: int = 16384, capacity: int | None = None):
+    """-> (status, stream bytes as uint8 array).  On E_RANGE the array holds header+table only."""
+    w = _u16(w)
+    cap = compress_bound(w.size, B) if capacity is None else capacity
+    out = np.zeros(max(cap, 1), dtype=np.uint8)
+    prm = np.asarray(params, dtype=np.uint8)
+    nbytes = C.c_size_t(0)
+    rc = lib().orc_compress(_p(w, C.c_uint16), w.size, B, _p(prm, C.c_uint8), _p(out, C.c_uint8),
+                            cap, C.byref(nbytes))
+    if rc == OK:
+        return rc, out[:nbytes.value].copy()
+    if rc == E_RANGE:
+        return rc, out[:payload_base(w.size, B)].copy()
+    return rc, None
+
+
+def stream_info(stream) -> dict:
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    params = np.zeros(4, dtype=np.uint8)
+    n = C.c_uint64(0)
+    B = C.c_uint32(0)
+    total = C.c_uint64(0)
+    status = C.c_uint32(0)
+    rc = lib().orc_stream_info(_p(s, C.c_uint8), _p(params, C.c_uint8), C.byref(n), C.byref(B),
+                               C.byref(total), C.byref(status))
+    return dict(rc=rc, params=tuple(int(v) for v in params), n_elems=int(n.value),
+                block_size=int(B.value), total_bytes=int(total.value), status=int(status.value))
+
+
+def decompress(stream, n_elems: int):
+    """-> (status, uint16 array)"""
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    out = np.zeros(n_elems, dtype=np.uint16)
+    rc = lib().orc_decompress(_p(s, C.c_uint8), s.size, _p(out, C.c_uint16), n_elems)
+    return rc, out

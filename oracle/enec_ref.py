@@ -1,0 +1,220 @@
+"""Pure-Python twin of the ENEC oracle, for brute force on tiny inputs.
+
+TEST INFRASTRUCTURE ONLY (see oracle/enec_oracle.c for the scope of the oracle).
+It is written separately from the C file and prefers the *definitions* over the
+vectorised forms, so that the two can check each other:
+
+  * the packer is the recursive description of Sec. V-B (fold lanes until a byte
+    is full, split into a storable byte and an overflow sub-block, recurse);
+  * the unpacker does not replay the packer backwards: it learns, from one-hot
+    inputs, where every input bit lands (the packer is a bit permutation) and
+    gathers the bits back;
+  * the group test uses the definition "largest bit width in the group > m"
+    instead of the bitwise OR the paper substitutes for it (Sec. V-B);
+  * record positions come from a running count of mask bits (Alg. 1,
+    decompression part).
+
+Everything works on Python integers; use it for blocks of 128-2048 elements.
+"""
+from __future__ import annotations
+
+import struct
+from functools import lru_cache
+
+L = 16
+HEADER = 64
+
+
+# --------------------------------------------------------------------------
+# Sec. V-B / Alg. 2
+# --------------------------------------------------------------------------
+def _normalized_bytes(lanes, width):
+    """Recursive form: returns the 'normalized bytes' of Alg. 2 (before the final join)."""
+    if width <= 0:
+        return []
+    lanes = list(lanes)
+    while len(lanes) > 1 and width < 8:
+        half = len(lanes) // 2
+        lanes = [lanes[i] | (lanes[i + half] << width) for i in range(half)]
+        width *= 2
+    storable = [v & 0xFF for v in lanes]
+    overflow = [v >> 8 for v in lanes]
+    return storable + _normalized_bytes(overflow, width - 8)
+
+
+def hh_pack(values, a):
+    assert 0 < a <= 8 and len(values) & (len(values) - 1) == 0
+    assert all(0 <= v < (1 << a) for v in values)
+    nb = _normalized_bytes(values, a)
+    if len(nb) % 2:
+        nb.append(0)
+    half = len(nb) // 2
+    out = bytearray()
+    for i in range(half):
+        out += struct.pack("<H", nb[i] | (nb[i + half] << 8))
+    return bytes(out)
+
+
+@lru_cache(maxsize=None)
+def _bit_map(N, a):
+    """(element, bit) -> output bit position, learnt from one-hot inputs."""
+    where = {}
+    for e in range(N):
+        for bit in range(a):
+            v = [0] * N
+            v[e] = 1 << bit
+            s = hh_pack(v, a)
+            ones = [8 * i + k for i, byte in enumerate(s) for k in range(8) if (byte >> k) & 1]
+            assert len(ones) == 1, "packer is not a bit permutation"
+            where[(e, bit)] = ones[0]
+    assert len(set(where.values())) == N * a
+    return where
+
+
+def hh_unpack(stream, N, a):
+    where = _bit_map(N, a)
+    out = [0] * N
+    for (e, bit), pos in where.items():
+        if (stream[pos // 8] >> (pos % 8)) & 1:
+            out[e] |= 1 << bit
+    return out
+
+
+# --------------------------------------------------------------------------
+# Sec. V-C / Sec. V-E
+# --------------------------------------------------------------------------
+def transform(x, b, n):
+    return (b - x) % (1 << n)          # Python's % is already non-negative
+
+
+def in_range(x, b, n):
+    return n >= 8 or -(1 << (n - 1)) <= b - x <= (1 << (n - 1)) - 1
+
+
+def inverse_transform(y, b, n):
+    s = y - (1 << n) if y >= (1 << (n - 1)) else y
+    return (b - s) % 256
+
+
+def width_for(b, l, h):
+    pos = (b - l).bit_length()
+    neg = (h - b - 1).bit_length() if h > b else 0
+    return min(8, max(pos, neg) + 1)
+
+
+def tune_hist(hist):
+    """Phases 2-3 of Sec. V-E on a 256-bin histogram -> ((b, n, m, L), D, B_exp)."""
+    occupied = [x for x in range(256) if hist[x]]
+    if not occupied:
+        return (0, 1, 0, L), 0, 1.0 / 16.0
+    l, h = occupied[0], occupied[-1]
+    total = sum(int(hist[x]) for x in occupied)
+    best = None
+    for b in range(l, h + 1):
+        n = width_for(b, l, h)
+        D = sum(int(hist[x]) * transform(x, b, n) for x in occupied)
+        key = (D, n, b)
+        if best is None or key < best:
+            best = key
+    D, n, b = best
+    best_m = None
+    for m in range(0, n + 1):
+        cnt = sum(int(hist[x]) for x in occupied if transform(x, b, n) < (1 << m))
+        p = cnt / total
+        p2 = p * p
+        p4 = p2 * p2
+        p8 = p4 * p4
+        p16 = p8 * p8
+        bexp = (1.0 / 16.0 + float(n)) + (float(m) - float(n)) * p16
+        if best_m is None or bexp < best_m[0]:
+            best_m = (bexp, m)
+    return (b, n, best_m[1], L), D, best_m[0]
+
+
+def tune(words):
+    hist = [0] * 256
+    for w in words:
+        hist[(int(w) >> 7) & 0xFF] += 1
+    return tune_hist(hist)[0]
+
+
+# --------------------------------------------------------------------------
+# container
+# --------------------------------------------------------------------------
+def _align16(v):
+    return (v + 15) & ~15
+
+
+def compress(words, params, B):
+    """-> (range_ok, bytes)"""
+    b, n, m, Lp = params
+    assert Lp == L and 1 <= n <= 8 and 0 <= m <= n
+    a = n - m
+    words = [int(w) for w in words]
+    N = len(words)
+    nb = (N + B - 1) // B
+    G = B // L
+    payloads, offsets, ok = [], [0], True
+    for k in range(nb):
+        blk = list(words[k * B:(k + 1) * B])
+        real = len(blk)
+        sm = [((w >> 8) & 0x80) | (w & 0x7F) for w in blk] + [0] * (B - real)
+        xs = [(w >> 7) & 0xFF for w in blk]
+        ok = ok and all(in_range(x, b, n) for x in xs)
+        y = [transform(x, b, n) for x in xs] + [0] * (B - real)
+        anomalous = [max(v.bit_length() for v in y[g * L:(g + 1) * L]) > m for g in range(G)]
+        mask = bytearray(G // 8)
+        for g, flag in enumerate(anomalous):
+            if flag:
+                mask[g // 8] |= 1 << (g % 8)
+        low = hh_pack([v & ((1 << m) - 1) for v in y], m) if m else b""
+        high = b"".join(hh_pack([v >> m for v in y[g * L:(g + 1) * L]], a)
+                        for g in range(G) if anomalous[g])
+        p = bytes(sm) + bytes(mask) + low + high
+        p += bytes(_align16(len(p)) - len(p))
+        payloads.append(p)
+        offsets.append(offsets[-1] + len(p))
+    base = _align16(HEADER + 8 * (nb + 1))
+    total = base + offsets[-1]
+    status = 0 if ok else 6
+    hdr = struct.pack("<4sHBBQIIBBBBIQ", b"ENEC", 1, 0, L, N, B, nb, b, n, m, 8, status,
+                      total if ok else 0)
+    hdr += bytes(HEADER - len(hdr))
+    table = b"".join(struct.pack("<Q", o) for o in offsets)
+    head = hdr + table
+    head += bytes(base - len(head))
+    return ok, head + b"".join(payloads)
+
+
+def decompress(stream, N):
+    stream = bytes(stream)
+    magic, ver, dtype, Lp, n_elems, B, nb, b, n, m, ebits, status, total = struct.unpack_from(
+        "<4sHBBQIIBBBBIQ", stream, 0)
+    assert magic == b"ENEC" and ver == 1 and dtype == 0 and Lp == L and ebits == 8
+    assert n_elems == N and status == 0
+    a = n - m
+    G = B // L
+    base = _align16(HEADER + 8 * (nb + 1))
+    out = []
+    for k in range(nb):
+        off = struct.unpack_from("<Q", stream, HEADER + 8 * k)[0]
+        p = stream[base + off:]
+        sm = p[:B]
+        mask = p[B:B + G // 8]
+        lowplane = p[B + G // 8:B + G // 8 + m * B // 8]
+        highplane = p[B + G // 8 + m * B // 8:]
+        low = hh_unpack(lowplane, B, m) if m else [0] * B
+        seen = 0                                   # running count of mask bits
+        for g in range(G):
+            bit = (mask[g // 8] >> (g % 8)) & 1
+            high = hh_unpack(highplane[2 * a * seen:2 * a * (seen + 1)], L, a) if bit else [0] * L
+            seen += bit
+            for i in range(L):
+                e = k * B + g * L + i
+                if e >= N:
+                    break
+                y = low[g * L + i] | (high[i] << m)
+                x = inverse_transform(y, b, n)
+                s = sm[g * L + i]
+                out.append(((s & 0x80) << 8) | (x << 7) | (s & 0x7F))
+    return out

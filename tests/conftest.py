@@ -1,0 +1,33 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with gpurun)")
+
+
+def golden_lines(name):
+    """Non-comment, non-empty lines of a fixture under tests/golden/."""
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [ln.strip() for ln in f if ln.strip() and not ln.lstrip().startswith("#")]
+
+
+@pytest.fixture(scope="session")
+def oracle():
+    from oracle import enec_oracle
+    enec_oracle.build()
+    return enec_oracle
+
+
+@pytest.fixture(scope="session")
+def ref():
+    from oracle import enec_ref
+    return enec_ref
