@@ -1,0 +1,159 @@
+/*
+ * libenec -- ENEC lossless codec for bf16 model weights on AMD MI355X (gfx950).
+ *
+ * C ABI.  Every entry point takes plain pointers and sizes; the doc of each argument
+ * says whether it is a HOST or a DEVICE pointer.  The library allocates no device
+ * memory: inputs, outputs and the workspace are the caller's.  All work is enqueued
+ * on the HIP stream passed as `stream` (a hipStream_t handed over as void*, NULL =
+ * the default stream).  Unless stated otherwise a call returns as soon as its work
+ * is enqueued.
+ *
+ * The codec (paper sections in brackets):
+ *   bf16 word -> exponent x (8 bit) and a raw sign+mantissa byte       [Sec. IV-B; Sec. V-A step 1]
+ *   y = (b - x) mod 2^n, the branch-free integer transformation        [Sec. V-C; Eq. 2]
+ *   per group of L = 16 consecutive elements: OR of the y; the group is
+ *   stored with m bits per element if OR < 2^m, else with n bits       [Sec. V-B]
+ *   fixed-length fields are packed with hierarchical halving
+ *   bit-packing with byte normalisation                                 [Sec. V-B, Alg. 2]
+ *   a prefix sum over per-data-block compressed sizes places each data
+ *   block in the output stream                                          [Fig. 4]
+ *   decompression: offset lookup, prefix sum over mask bits, unpack,
+ *   x = b - sext_n(y), recombine                                        [Sec. IV-B Alg. 1 (decompression); Sec. V-A]
+ *   parameters (b, n, m, L) from the exponent histogram                 [Sec. V-E, Eq. 1-4]
+ *
+ * Stream format, version 1 (all integers little-endian):
+ *   0   "ENEC"                 4   u16 version = 1      6  u8 dtype (0 = bf16)   7  u8 L (= 16)
+ *   8   u64 n_elems            16  u32 block_size B     20 u32 n_blocks nb = ceil(n_elems / B)
+ *   24  u8 b   25 u8 n   26 u8 m   27 u8 exponent bits (= 8)
+ *   28  u32 status (ENEC_OK or ENEC_E_RANGE)            32 u64 total_bytes (0 if status != OK)
+ *   40..63 zero
+ *   64  (nb + 1) x u64: offset of each data block's payload relative to the payload base,
+ *       i.e. the exclusive prefix sums of payload sizes; entry nb is their total
+ *   zero bytes up to payload base = align16(64 + 8 (nb + 1))
+ *   per data block, at payload base + offset[k] (always 16-byte aligned):
+ *       B bytes            sign<<7 | mantissa of every element, element order
+ *       B/128 bytes        group mask: group g is bit (g mod 8), LSB first, of byte (g div 8);
+ *                          1 = stored with n bits
+ *       m*B/8 bytes        Alg. 2 over (y mod 2^m) of all B elements
+ *       2(n-m) bytes per masked group, in group order: Alg. 2 over (y >> m) of its 16 elements
+ *       zero bytes up to a multiple of 16
+ *   The last data block is completed with elements that encode as y = 0 and a zero
+ *   sign/mantissa byte.
+ */
+#ifndef ENEC_H
+#define ENEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ENEC_OK = 0,
+    ENEC_E_ARG = 1,       /* null / misaligned pointer, size out of range */
+    ENEC_E_DTYPE = 2,     /* only ENEC_BF16 is implemented */
+    ENEC_E_BLOCK = 3,     /* block_size not a power of two in [2048, 32768] */
+    ENEC_E_PARAMS = 4,    /* need 1 <= n <= 8, 0 <= m <= n, L == 16 */
+    ENEC_E_CAPACITY = 5,  /* out_capacity < enec_compress_bound() or workspace too small */
+    ENEC_E_RANGE = 6,     /* an exponent lies outside [b - 2^(n-1) + 1, b + 2^(n-1)] while n < 8 */
+    ENEC_E_FORMAT = 7,    /* not an ENEC stream, or header does not match the call */
+    ENEC_E_HIP = 8        /* a HIP runtime call failed */
+} enec_status;
+
+typedef enum { ENEC_BF16 = 0 } enec_dtype;
+
+/* Codec parameters [Sec. V-E; Table VI]: mapping centre b, stored width n, threshold width m,
+ * group length L (must be 16). */
+typedef struct { uint8_t b, n, m, L; } enec_params;
+
+#define ENEC_HEADER_BYTES 64u
+#define ENEC_DEFAULT_BLOCK 16384u
+
+uint32_t enec_version(void);                 /* stream format version this library writes (1) */
+const char *enec_strerror(int status);       /* static string, never NULL */
+
+/* Data-block size used when block_size = 0 is passed: 16384 [Sec. VI-D "Data Block Size"], or for
+ * tensors shorter than that the largest power of two <= n_elems, but at least 2048. */
+uint32_t enec_default_block_size(size_t n_elems);
+
+/* Worst-case stream size in bytes for n_elems elements (every group stored with 8 bits).
+ * Returns 0 on invalid dtype / block_size.  block_size = 0 means the default. */
+size_t enec_compress_bound(size_t n_elems, int dtype, uint32_t block_size);
+
+/* Size in bytes of the DEVICE workspace enec_compress / enec_tune need for a tensor of n_elems
+ * elements (inter-block scan state, ticket counters, histogram).  A workspace sized for a larger
+ * tensor serves smaller ones.  Returns 0 on invalid block_size. */
+size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size);
+
+/* Enqueues a fill kernel that zeroes `bytes` bytes of the DEVICE workspace.  Must run once after
+ * the workspace is allocated; every later library call leaves the workspace zeroed again, so one
+ * workspace can be reused by any number of calls that do not overlap in time.  16-byte aligned. */
+int enec_workspace_init(void *workspace, size_t bytes, void *stream);
+
+/* Compress n_elems bf16 values [Sec. V-A compression path; Sec. V-B; Sec. V-C; Fig. 4].
+ *   in            DEVICE, n_elems * 2 bytes, 16-byte aligned, read only
+ *   dtype         ENEC_BF16
+ *   block_size    data-block size B in elements: power of two in [2048, 32768], 0 = default
+ *   params        HOST, read before return.  NULL = tune on the device first (this makes the call
+ *                 synchronous: it waits for the histogram, see enec_tune)
+ *   out           DEVICE, out_capacity bytes, 16-byte aligned, must not overlap in / workspace
+ *   out_capacity  must be >= enec_compress_bound(n_elems, dtype, block_size)
+ *   out_bytes     NULL, or a DEVICE-ACCESSIBLE pointer (device memory, or pinned host memory from
+ *                 hipHostMalloc), 8-byte aligned: the kernel stores the stream size there
+ *                 (0 on ENEC_E_RANGE); valid once the stream has been synchronised.  Pageable
+ *                 host memory is rejected with ENEC_E_ARG.
+ *   workspace     DEVICE, zeroed by enec_workspace_init; calls sharing one workspace must not
+ *                 run concurrently
+ *   workspace_bytes  its size; ENEC_E_CAPACITY if < enec_workspace_bytes(n_elems, block_size)
+ *   stream        hipStream_t
+ * One kernel launch.  The stream written is a pure function of (input bytes, params, block_size).
+ * Errors detectable on the host return at once with nothing enqueued.  The data-dependent
+ * ENEC_E_RANGE is found by the kernel: header.status = ENEC_E_RANGE, header.total_bytes = 0,
+ * *out_bytes = 0, payload undefined. */
+int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size,
+                  const enec_params *params, void *out, size_t out_capacity,
+                  uint64_t *out_bytes, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Decompress [Sec. V-A decompression path; Alg. 1 decompression part].
+ *   in        DEVICE, a stream written by enec_compress, 16-byte aligned
+ *   out       DEVICE, n_elems * 2 bytes, 16-byte aligned
+ *   n_elems   must equal the header's n_elems
+ * This variant copies the 64-byte header to the host first (one small synchronous copy on
+ * `stream`), validates it (ENEC_E_FORMAT / ENEC_E_DTYPE), then enqueues one kernel. */
+int enec_decompress(const void *in, void *out, size_t n_elems, void *stream);
+
+/* Same, fully asynchronous: `host_header` is a HOST copy of the stream's first 64 bytes that the
+ * caller already holds (kept from compression, or read from a file).  The kernel compares it with
+ * the header in device memory and writes nothing if they differ. */
+int enec_decompress_with_header(const void *in, const void *host_header, void *out,
+                                size_t n_elems, void *stream);
+
+/* Parameter tuning [Sec. V-E phases 1-3]: exponent histogram on the device (one read of the
+ * tensor), then the search for (b, n) by Eq. 1-3 and for m by Eq. 4 (L = 16) on the host.
+ *   in         DEVICE, n_elems * 2 bytes, 16-byte aligned
+ *   params     HOST, written before return
+ *   histogram  NULL, or HOST array of 256 u64 that receives the exponent counts
+ *   workspace  DEVICE, as for enec_compress (workspace_bytes: its size)
+ * Synchronous: returns after the histogram has been copied back. */
+int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params,
+              uint64_t *histogram, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Host-only search of Sec. V-E phases 2-3 on a given 256-bin exponent histogram (HOST). */
+int enec_tune_histogram(const uint64_t *histogram, enec_params *params);
+
+/* Parse a HOST copy of a stream's first 64 bytes.  Any output pointer may be NULL.
+ * Returns ENEC_E_FORMAT if it is not a version-1 ENEC header. */
+int enec_stream_info(const void *host_header, enec_params *params, uint64_t *n_elems,
+                     uint32_t *block_size, uint64_t *total_bytes, int *dtype, uint32_t *status);
+
+/* Measurement aid: a plain 128-bit grid-stride copy of `bytes` bytes (multiple of 16) between two
+ * 16-byte aligned DEVICE buffers.  Its achieved bandwidth is the practical ceiling the codec
+ * kernels are compared with, and the scale for the HBM traffic counters. */
+int enec_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ENEC_H */

@@ -1,0 +1,333 @@
+// Host side of libenec: argument checks, kernel dispatch, the parameter search.
+// See include/enec.h for the contract of every entry point.
+#include "enec.h"
+#include "enec_device.hpp"
+
+#include <cstring>
+
+namespace {
+
+using namespace enec;
+
+constexpr size_t WS_TICKET = 0, WS_DONE = 128, WS_HIST = 256, WS_STATE = 256 + 256 * 8;
+constexpr size_t MAX_ELEMS = (size_t)1 << 34;      // keeps every offset below 2^36 bytes
+
+inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
+inline bool block_ok(uint32_t B) { return B >= 2048 && B <= 32768 && (B & (B - 1)) == 0; }
+inline uint32_t ilog2(uint32_t v) { uint32_t r = 0; while ((1u << r) < v) ++r; return r; }
+inline size_t num_blocks(size_t n, uint32_t B) { return (n + B - 1) / B; }
+inline size_t payload_base(size_t n, uint32_t B) { return align16(ENEC_HEADER_BYTES + 8 * (num_blocks(n, B) + 1)); }
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+using CompressFn = void (*)(const CompressArgs);
+using DecompressFn = void (*)(const DecompressArgs);
+
+template <int M, int A> constexpr CompressFn cfn() { return &compress_kernel<M, A>; }
+template <int M, int A> constexpr DecompressFn dfn() { return &decompress_kernel<M, A>; }
+
+// every (m, a = n - m) with 1 <= m + a <= 8
+template <int M, int A> struct Pick {
+    static CompressFn c(int m, int a)
+    {
+        if (m == M && a == A) return cfn<M, A>();
+        if constexpr (A < 8 - M) return Pick<M, A + 1>::c(m, a);
+        else if constexpr (M < 8) return Pick<M + 1, 0>::c(m, a);
+        else return nullptr;
+    }
+    static DecompressFn d(int m, int a)
+    {
+        if (m == M && a == A) return dfn<M, A>();
+        if constexpr (A < 8 - M) return Pick<M, A + 1>::d(m, a);
+        else if constexpr (M < 8) return Pick<M + 1, 0>::d(m, a);
+        else return nullptr;
+    }
+};
+
+inline CompressFn pick_compress(int m, int a) { return Pick<0, 1>::c(m, a); }
+inline DecompressFn pick_decompress(int m, int a) { return Pick<0, 1>::d(m, a); }
+
+bool device_accessible(const void *p)
+{
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeHost ||
+           attr.type == hipMemoryTypeManaged;
+}
+
+unsigned bit_length(unsigned v) { unsigned r = 0; for (; v; v >>= 1) ++r; return r; }
+
+struct Header {
+    enec_params prm;
+    uint64_t n_elems, total;
+    uint32_t B, nb, status;
+    int dtype;
+};
+
+int parse_header(const void *host_header, Header *h)
+{
+    const uint8_t *p = static_cast<const uint8_t *>(host_header);
+    if (std::memcmp(p, "ENEC", 4) != 0) return ENEC_E_FORMAT;
+    uint16_t ver; std::memcpy(&ver, p + 4, 2);
+    if (ver != 1 || p[7] != 16 || p[27] != 8) return ENEC_E_FORMAT;
+    h->dtype = p[6];
+    std::memcpy(&h->n_elems, p + 8, 8);
+    std::memcpy(&h->B, p + 16, 4);
+    std::memcpy(&h->nb, p + 20, 4);
+    h->prm.b = p[24]; h->prm.n = p[25]; h->prm.m = p[26]; h->prm.L = p[7];
+    std::memcpy(&h->status, p + 28, 4);
+    std::memcpy(&h->total, p + 32, 8);
+    return ENEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t enec_version(void) { return 1; }
+
+const char *enec_strerror(int status)
+{
+    switch (status) {
+    case ENEC_OK: return "ok";
+    case ENEC_E_ARG: return "invalid argument (null or misaligned pointer, size out of range)";
+    case ENEC_E_DTYPE: return "unsupported dtype (only bf16)";
+    case ENEC_E_BLOCK: return "block_size must be a power of two in [2048, 32768]";
+    case ENEC_E_PARAMS: return "invalid parameters (need 1 <= n <= 8, 0 <= m <= n, L == 16)";
+    case ENEC_E_CAPACITY: return "output capacity or workspace too small";
+    case ENEC_E_RANGE: return "an exponent lies outside the window of (b, n)";
+    case ENEC_E_FORMAT: return "not an ENEC stream or header mismatch";
+    case ENEC_E_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+uint32_t enec_default_block_size(size_t n_elems)
+{
+    uint32_t B = ENEC_DEFAULT_BLOCK;
+    while (B > 2048 && B > n_elems) B >>= 1;
+    return B;
+}
+
+size_t enec_compress_bound(size_t n_elems, int dtype, uint32_t block_size)
+{
+    if (dtype != ENEC_BF16) return 0;
+    const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
+    if (!block_ok(B)) return 0;
+    return payload_base(n_elems, B) + num_blocks(n_elems, B) * align16((size_t)B + B / 128 + B);
+}
+
+size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size)
+{
+    const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
+    if (!block_ok(B)) return 0;
+    size_t nb = num_blocks(n_elems, B);
+    return (WS_STATE + 8 * (nb ? nb : 1) + 255) & ~(size_t)255;
+}
+
+int enec_workspace_init(void *workspace, size_t bytes, void *stream)
+{
+    if (!workspace || !aligned16(workspace) || (bytes & 15)) return ENEC_E_ARG;
+    if (bytes == 0) return ENEC_OK;
+    const uint64_t nvec = bytes / 16;
+    const unsigned grid = (unsigned)((nvec + 255) / 256 < 1024 ? (nvec + 255) / 256 : 1024);
+    fill_zero_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(static_cast<uint4 *>(workspace), nvec);
+    return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+}
+
+int enec_tune_histogram(const uint64_t *hist, enec_params *params)
+{
+    if (!hist || !params) return ENEC_E_ARG;
+    // Sec. V-E phase 1: occupied range [l, h] and the element count
+    int l = -1, h = -1;
+    uint64_t total = 0;
+    for (int x = 0; x < 256; ++x)
+        if (hist[x]) { if (l < 0) l = x; h = x; total += hist[x]; }
+    if (total == 0) { *params = enec_params{0, 1, 0, 16}; return ENEC_OK; }
+    // phase 2: every centre b in [l, h]; width from Eq. 1, cost from Eq. 2-3 in exact integers
+    uint64_t bestD = ~0ull;
+    unsigned bestN = 0, bestB = 0;
+    for (int b = l; b <= h; ++b) {
+        unsigned below = bit_length((unsigned)(b - l));
+        unsigned above = h > b ? bit_length((unsigned)(h - b - 1)) : 0;
+        unsigned n = (below > above ? below : above) + 1;
+        if (n > 8) n = 8;
+        const unsigned wrap = (1u << n) - 1u;
+        uint64_t D = 0;
+        for (int x = l; x <= h; ++x) D += hist[x] * (uint64_t)(((unsigned)(b - x)) & wrap);
+        if (D < bestD || (D == bestD && n < bestN)) { bestD = D; bestN = n; bestB = (unsigned)b; }
+    }
+    // phase 3: threshold m by Eq. 4 with L = 16 (p^16 by four squarings), ties to the smaller m
+    const unsigned wrap = (1u << bestN) - 1u;
+    double bestE = 0.0;
+    unsigned bestM = 0;
+    for (unsigned m = 0; m <= bestN; ++m) {
+        uint64_t cnt = 0;
+        for (int x = l; x <= h; ++x)
+            if (((bestB - (unsigned)x) & wrap) < (1u << m)) cnt += hist[x];
+        const double pm = (double)cnt / (double)total;
+        const double p2 = pm * pm, p4 = p2 * p2, p8 = p4 * p4, p16 = p8 * p8;
+        const double e = (1.0 / 16.0 + (double)bestN) + ((double)m - (double)bestN) * p16;
+        if (m == 0 || e < bestE) { bestE = e; bestM = m; }
+    }
+    *params = enec_params{(uint8_t)bestB, (uint8_t)bestN, (uint8_t)bestM, 16};
+    return ENEC_OK;
+}
+
+int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params, uint64_t *histogram,
+              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (dtype != ENEC_BF16) return ENEC_E_DTYPE;
+    if (workspace_bytes < WS_STATE) return ENEC_E_CAPACITY;
+    if (!params || !workspace || (!in && n_elems) || !aligned16(in) || !aligned16(workspace) ||
+        n_elems > MAX_ELEMS)
+        return ENEC_E_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    uint64_t host_hist[256];
+    std::memset(host_hist, 0, sizeof host_hist);
+    if (n_elems) {
+        auto *dhist = reinterpret_cast<unsigned long long *>(static_cast<uint8_t *>(workspace) + WS_HIST);
+        fill_zero_kernel<<<1, 256, 0, s>>>(reinterpret_cast<uint4 *>(dhist), 256 * 8 / 16);
+        const uint64_t nvec = n_elems / 8;
+        uint64_t want = (nvec + 255) / 256;
+        const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+        histogram_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t *>(in), n_elems, dhist);
+        if (hipMemcpyAsync(host_hist, dhist, sizeof host_hist, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            return ENEC_E_HIP;
+    }
+    if (histogram) std::memcpy(histogram, host_hist, sizeof host_hist);
+    return enec_tune_histogram(host_hist, params);
+}
+
+int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size,
+                  const enec_params *params, void *out, size_t out_capacity, uint64_t *out_bytes,
+                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (dtype != ENEC_BF16) return ENEC_E_DTYPE;
+    if (!out || !workspace || (!in && n_elems) || !aligned16(in) || !aligned16(out) ||
+        !aligned16(workspace) || n_elems > MAX_ELEMS || ((uintptr_t)out_bytes & 7))
+        return ENEC_E_ARG;
+    const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
+    if (!block_ok(B)) return ENEC_E_BLOCK;
+    if (workspace_bytes < enec_workspace_bytes(n_elems, B)) return ENEC_E_CAPACITY;
+    enec_params prm;
+    if (params) {
+        prm = *params;
+    } else {
+        int rc = enec_tune(in, n_elems, dtype, &prm, nullptr, workspace, workspace_bytes, stream);
+        if (rc != ENEC_OK) return rc;
+    }
+    if (prm.n < 1 || prm.n > 8 || prm.m > prm.n || prm.L != 16) return ENEC_E_PARAMS;
+    if (out_capacity < enec_compress_bound(n_elems, dtype, B)) return ENEC_E_CAPACITY;
+    if (out_bytes && !device_accessible(out_bytes)) return ENEC_E_ARG;
+
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    CompressArgs a;
+    a.in = static_cast<const uint16_t *>(in);
+    a.out = static_cast<uint8_t *>(out);
+    a.n_elems = n_elems;
+    a.payload_base = payload_base(n_elems, B);
+    a.ws_state = reinterpret_cast<uint64_t *>(ws + WS_STATE);
+    a.ws_ticket = reinterpret_cast<uint32_t *>(ws + WS_TICKET);
+    a.ws_done = reinterpret_cast<uint32_t *>(ws + WS_DONE);
+    a.out_bytes = out_bytes;
+    a.B = B;
+    a.logB = ilog2(B);
+    a.nb = (uint32_t)num_blocks(n_elems, B);
+    a.b = prm.b;
+    const unsigned c = prm.b + (1u << (prm.n - 1));
+    const bool plain = c <= 255 && c >= (1u << prm.n) - 1u;
+    a.mode = plain ? 0u : (prm.n == 8 ? 1u : 2u);
+
+    hipStream_t s = (hipStream_t)stream;
+    if (a.nb == 0) {
+        compress_empty_kernel<<<1, 64, 0, s>>>(a, prm.n, prm.m);
+    } else {
+        CompressFn fn = pick_compress(prm.m, prm.n - prm.m);
+        if (!fn) return ENEC_E_PARAMS;
+        const unsigned threads = B / 64 < 64 ? 64 : B / 64;
+        const size_t lds = (size_t)prm.n * B / 8;
+        hipLaunchKernelGGL(fn, dim3(a.nb), dim3(threads), lds, s, a);
+    }
+    return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+}
+
+int enec_decompress_with_header(const void *in, const void *host_header, void *out, size_t n_elems,
+                                void *stream)
+{
+    if (!in || !host_header || (!out && n_elems) || !aligned16(in) || !aligned16(out)) return ENEC_E_ARG;
+    Header h;
+    int rc = parse_header(host_header, &h);
+    if (rc != ENEC_OK) return rc;
+    if (h.dtype != ENEC_BF16) return ENEC_E_DTYPE;
+    if (h.status != ENEC_OK || h.n_elems != n_elems || !block_ok(h.B) || n_elems > MAX_ELEMS ||
+        h.nb != num_blocks(n_elems, h.B) || h.prm.n < 1 || h.prm.n > 8 || h.prm.m > h.prm.n ||
+        h.total < payload_base(n_elems, h.B))
+        return ENEC_E_FORMAT;
+    if (h.nb == 0) return ENEC_OK;
+
+    DecompressArgs a;
+    a.in = static_cast<const uint8_t *>(in);
+    a.out = static_cast<uint16_t *>(out);
+    a.n_elems = n_elems;
+    a.payload_base = payload_base(n_elems, h.B);
+    a.B = h.B;
+    a.logB = ilog2(h.B);
+    a.nb = h.nb;
+    a.b = h.prm.b;
+    const unsigned c = h.prm.b + (1u << (h.prm.n - 1));
+    a.mode = (c <= 255 && c >= (1u << h.prm.n) - 1u) ? 0u : 1u;
+    std::memcpy(a.hdr, host_header, sizeof a.hdr);
+
+    DecompressFn fn = pick_decompress(h.prm.m, h.prm.n - h.prm.m);
+    if (!fn) return ENEC_E_FORMAT;
+    const unsigned threads = h.B / 64 < 64 ? 64 : h.B / 64;
+    const size_t lds = (size_t)h.prm.n * h.B / 8;
+    hipLaunchKernelGGL(fn, dim3(a.nb), dim3(threads), lds, (hipStream_t)stream, a);
+    return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+}
+
+int enec_decompress(const void *in, void *out, size_t n_elems, void *stream)
+{
+    if (!in || !aligned16(in)) return ENEC_E_ARG;
+    uint8_t hdr[ENEC_HEADER_BYTES];
+    hipStream_t s = (hipStream_t)stream;
+    if (hipMemcpyAsync(hdr, in, sizeof hdr, hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess) {
+        (void)hipGetLastError();
+        return ENEC_E_HIP;
+    }
+    return enec_decompress_with_header(in, hdr, out, n_elems, stream);
+}
+
+int enec_stream_info(const void *host_header, enec_params *params, uint64_t *n_elems,
+                     uint32_t *block_size, uint64_t *total_bytes, int *dtype, uint32_t *status)
+{
+    if (!host_header) return ENEC_E_ARG;
+    Header h;
+    int rc = parse_header(host_header, &h);
+    if (rc != ENEC_OK) return rc;
+    if (params) *params = h.prm;
+    if (n_elems) *n_elems = h.n_elems;
+    if (block_size) *block_size = h.B;
+    if (total_bytes) *total_bytes = h.total;
+    if (dtype) *dtype = h.dtype;
+    if (status) *status = h.status;
+    return ENEC_OK;
+}
+
+int enec_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || !aligned16(dst) || !aligned16(src) || (bytes & 15)) return ENEC_E_ARG;
+    const uint64_t nvec = bytes / 16;
+    if (nvec == 0) return ENEC_OK;
+    uint64_t want = (nvec + 255) / 256;
+    const unsigned grid = (unsigned)(want > 8192 ? 8192 : want);
+    copy_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), nvec);
+    return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,722 @@
+// Device code of libenec: the ENEC bf16 codec on CDNA4 (gfx950), wave64.
+//
+// Thread mapping (both directions).  A data block of B elements is seen as 8 rows of
+// C = B/8 columns: element c + t*C is row t, column c.  Alg. 2 (hierarchical halving
+// bit-packing, Sec. V-B) over a whole block only ever combines elements of one column,
+// and the a bytes it produces for a column do not depend on B: its "normalized bytes"
+// are a planes of C bytes, plane-major.  So a thread that owns 8 adjacent columns
+//   * reads / writes, for each row, one 128-bit vector of 8 bf16 (fully coalesced),
+//   * packs its 8 columns in registers with byte-lane SIMD-within-a-register
+//     arithmetic (4 columns per 32-bit register),
+//   * owns half of a group of 16 consecutive elements per row; the two halves sit in
+//     adjacent lanes and are combined with one DPP operation.
+// A workgroup has B/64 threads (256 for the default B = 16384) and handles one block.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace enec {
+
+// ---------------------------------------------------------------------------------
+// Compile-time bit map of Alg. 2 for one column (8 values of W bits -> W bytes).
+// A "field" says: bits of row t land in byte `plane` at a constant bit offset.
+// ---------------------------------------------------------------------------------
+struct HHTable {
+    int count;
+    int plane[64];
+    int row[64];
+    int shift[64];        // destination bit - source bit (may be negative)
+    unsigned dmask[64];   // destination bits inside the byte
+    bool clean[64];       // whole W-bit value fits without spilling into the next byte
+};
+
+template <int W>
+constexpr HHTable make_hh_table()
+{
+    HHTable T{};
+    int lab[8][16] = {};
+    for (int i = 0; i < 8; ++i)
+        for (int k = 0; k < 16; ++k) lab[i][k] = (k < W) ? i * 8 + k : -1;
+    int width = W, length = 8, planes = 0, n = 0;
+    while (width > 0) {
+        while (length > 1 && width < 8) {
+            length /= 2;
+            for (int i = 0; i < length; ++i)
+                for (int k = 0; k < width; ++k) lab[i][width + k] = lab[i + length][k];
+            width *= 2;
+        }
+        for (int j = 0; j < length; ++j) {
+            for (int t = 0; t < 8; ++t) {
+                int shift = 0;
+                unsigned dmask = 0, smask = 0;
+                for (int k = 0; k < 8; ++k)
+                    if (lab[j][k] >= 0 && lab[j][k] / 8 == t) {
+                        int sb = lab[j][k] % 8;
+                        shift = k - sb;
+                        dmask |= 1u << k;
+                        smask |= 1u << sb;
+                    }
+                if (dmask) {
+                    T.plane[n] = planes + j;
+                    T.row[n] = t;
+                    T.shift[n] = shift;
+                    T.dmask[n] = dmask;
+                    T.clean[n] = (smask == ((1u << W) - 1u)) && shift >= 0 && shift + W <= 8;
+                    ++n;
+                }
+            }
+            for (int k = 0; k < 8; ++k) lab[j][k] = lab[j][k + 8];
+            for (int k = 8; k < 16; ++k) lab[j][k] = -1;
+        }
+        planes += length;
+        width -= 8;
+    }
+    T.count = n;
+    return T;
+}
+
+template <int W> struct HH { static constexpr HHTable table = make_hh_table<W>(); };
+
+__device__ __forceinline__ uint32_t shl_or_shr(uint32_t v, int s)
+{
+    return s >= 0 ? (v << s) : (v >> (-s));
+}
+
+// ---------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t sel)
+{
+    // selector byte i picks output byte i: 0-3 = bytes of lo, 4-7 = bytes of hi
+    return __builtin_amdgcn_perm(hi, lo, sel);
+}
+
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b)
+{
+    return (a & mask) | (b & ~mask);
+}
+
+// per-byte (a - b) mod 256 without borrows between bytes
+__device__ __forceinline__ uint32_t bytesub_safe(uint32_t a, uint32_t b)
+{
+    const uint32_t H = 0x80808080u;
+    return ((a | H) - (b & ~H)) ^ ((a ^ ~b) & H);
+}
+
+// value of the neighbouring lane (lane ^ 1), one DPP move
+__device__ __forceinline__ uint32_t swap_pair(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false);
+}
+
+// keep the even bits of x, packed into 32 bits (wave-uniform: runs on the scalar unit)
+__device__ __forceinline__ uint32_t compact_even_bits(uint64_t x)
+{
+    x &= 0x5555555555555555ull;
+    x = (x | (x >> 1)) & 0x3333333333333333ull;
+    x = (x | (x >> 2)) & 0x0F0F0F0F0F0F0F0Full;
+    x = (x | (x >> 4)) & 0x00FF00FF00FF00FFull;
+    x = (x | (x >> 8)) & 0x0000FFFF0000FFFFull;
+    x = (x | (x >> 16)) & 0x00000000FFFFFFFFull;
+    return (uint32_t)x;
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t o = __shfl_up(v, d, 64);
+        if (lane >= (uint32_t)d) v += o;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint64_t wave_sum(uint64_t v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)v, d, 64);
+        const uint32_t hi = __shfl_xor((uint32_t)(v >> 32), d, 64);
+        v += ((uint64_t)hi << 32) | lo;
+    }
+    return v;
+}
+
+// Scan-state word of one data block (single 64-bit word, so no fences are needed):
+//   bits 63:62  0 = not published, 1 = this block's size only, 2 = inclusive prefix
+//   bit  61     a range error was seen in the blocks covered by the word
+//   bits 39:0   size / prefix in units of 16 bytes
+constexpr uint64_t ST_AGGREGATE = 1ull << 62;
+constexpr uint64_t ST_INCLUSIVE = 2ull << 62;
+constexpr uint64_t ST_ERR = 1ull << 61;
+constexpr uint64_t ST_VALUE = (1ull << 40) - 1;
+constexpr uint32_t SPIN_LIMIT = 1u << 22;
+
+__device__ __forceinline__ uint64_t ld_state(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_state(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct CompressArgs {
+    const uint16_t *in;
+    uint8_t *out;
+    uint64_t n_elems;
+    uint64_t payload_base;
+    uint64_t *ws_state;     // nb scan-state words
+    uint32_t *ws_ticket;
+    uint32_t *ws_done;
+    uint64_t *out_bytes;    // device-accessible or null
+    uint32_t B, logB, nb;
+    uint32_t b, mode;       // mode 0: window clear of 0 and 255; 1: n = 8; 2: window touches an end
+};
+
+struct DecompressArgs {
+    const uint8_t *in;
+    uint16_t *out;
+    uint64_t n_elems;
+    uint64_t payload_base;
+    uint32_t B, logB, nb;
+    uint32_t b, mode;       // mode 0: plain byte subtract is exact; 1: borrow-safe subtract
+    uint32_t hdr[10];       // first 40 bytes of the expected header
+};
+
+// ---------------------------------------------------------------------------------
+// compression: split, transform, group test, packing, inter-block scan, store
+// (Sec. V-A compression path; Sec. V-B; Sec. V-C; Fig. 4)
+// ---------------------------------------------------------------------------------
+template <int M, int A>
+__global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
+{
+    constexpr int N = M + A;
+    constexpr uint32_t NMASK = ((1u << N) - 1u) * 0x01010101u;
+    constexpr uint32_t LMASK = ((1u << M) - 1u) * 0x01010101u;
+    constexpr uint32_t AMASK = ((1u << A) - 1u) * 0x01010101u;
+    constexpr uint32_t SREP = (1u << (N - 1)) * 0x01010101u;
+    constexpr int MP = M > 0 ? M : 1;
+    constexpr int AP = A > 0 ? A : 1;
+
+    extern __shared__ __align__(16) uint8_t smem[];
+    __shared__ __align__(16) uint32_t s_maskw[64];
+    __shared__ uint32_t s_pre[64];
+    __shared__ uint32_t s_u32[8];   // 0 ticket, 1 count of masked groups, 2 error, 3/4 offset, 5 last, 6 prefix error
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t B = p.B, logC = p.logB - 3u, C = 1u << logC;
+    const uint32_t nact = B >> 6;
+    const bool active = tid < nact;
+    uint8_t *lds_low = smem;
+    uint8_t *lds_high = smem + (((size_t)M * B) >> 3);
+
+    if (tid == 0) {
+        s_u32[0] = atomicAdd(p.ws_ticket, 1u);
+        s_u32[2] = 0;
+    }
+    __syncthreads();
+    const uint32_t k = s_u32[0];
+    if (k >= p.nb) return;              // workspace was not zeroed: refuse to touch memory
+    const uint64_t blk0 = (uint64_t)k << p.logB;
+    const uint32_t padw = (p.b << 7) * 0x00010001u;   // a pad element has exponent b: y = 0, sm = 0
+
+    // ---- a1: 128-bit loads of the 8 rows ---------------------------------------
+    uint4 raw[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
+        if (active && e0 + 8 <= p.n_elems) {
+            raw[t] = *reinterpret_cast<const uint4 *>(p.in + e0);
+        } else {
+            uint32_t d[4] = {padw, padw, padw, padw};
+            if (active && e0 < p.n_elems) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (e0 + i < p.n_elems) {
+                        const uint32_t v = p.in[e0 + i];
+                        d[i >> 1] = (i & 1) ? ((d[i >> 1] & 0x0000FFFFu) | (v << 16))
+                                            : ((d[i >> 1] & 0xFFFF0000u) | v);
+                    }
+            }
+            raw[t] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
+    }
+
+    const uint32_t crep = ((p.b + (1u << (N - 1))) & 0xFFu) * 0x01010101u;
+    const uint32_t xlo = p.b + 1u > (1u << (N - 1)) ? p.b + 1u - (1u << (N - 1)) : 0u;
+    const uint32_t xhi = p.b + (1u << (N - 1)) < 255u ? p.b + (1u << (N - 1)) : 255u;
+
+    uint32_t SM[8][2], HI[8][2], accP[MP][2], mw[8];
+    uint32_t err_acc = 0;
+    bool bad = false;
+#pragma unroll
+    for (int q = 0; q < MP; ++q) accP[q][0] = accP[q][1] = 0;
+
+    constexpr HHTable TL = HH<M>::table;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        uint32_t gor = 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t d0 = h ? raw[t].z : raw[t].x;
+            const uint32_t d1 = h ? raw[t].w : raw[t].y;
+            // a1 split: low / high bytes of four bf16 words
+            const uint32_t Lb = byte_perm(d1, d0, 0x06040200u);
+            const uint32_t Hb = byte_perm(d1, d0, 0x07050301u);
+            SM[t][h] = bfi(0x7F7F7F7Fu, Lb, Hb);
+            const uint32_t X = bfi(0xFEFEFEFEu, Hb << 1, Lb >> 7);
+            // a2 transform: z = (b + 2^(n-1) - x) mod 256 per byte, y = z with the sign bit flipped
+            uint32_t Z;
+            if (p.mode == 0) {
+                Z = crep - X;
+                if (N < 8) err_acc |= Z;
+            } else {
+                Z = bytesub_safe(crep, X);
+                if (p.mode == 2) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t xb = (X >> (8 * i)) & 0xFFu;
+                        bad |= (xb < xlo) | (xb > xhi);
+                    }
+                }
+            }
+            uint32_t Y = Z ^ SREP;
+            if (N < 8) Y &= NMASK;
+            // a3: high parts decide the group; a4: low parts go to the column packer
+            const uint32_t hi = A > 0 ? ((Y >> M) & AMASK) : 0u;
+            HI[t][h] = hi;
+            gor |= hi;
+            if (M > 0) {
+                const uint32_t low = Y & LMASK;
+#pragma unroll
+                for (int f = 0; f < TL.count; ++f)
+                    if (TL.row[f] == t) {
+                        uint32_t s = shl_or_shr(low, TL.shift[f]);
+                        if (!TL.clean[f]) s &= TL.dmask[f] * 0x01010101u;
+                        accP[TL.plane[f]][h] |= s;
+                    }
+            }
+        }
+        gor |= swap_pair(gor);
+        mw[t] = compact_even_bits(__builtin_amdgcn_ballot_w64(gor != 0));
+    }
+    if (N < 8 && p.mode == 0) bad = (err_acc & ~NMASK) != 0;
+    if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(&s_u32[2], 1u);
+
+    if (lane == 0 && 64u * wave < nact) {
+        if (logC >= 9) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) s_maskw[((uint32_t)t << (logC - 9)) + wave] = mw[t];
+        } else {      // B = 2048: 16 groups per row, one wave
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s_maskw[u] = mw[2 * u] | (mw[2 * u + 1] << 16);
+        }
+    }
+    if (M > 0 && active) {
+#pragma unroll
+        for (int q = 0; q < M; ++q)
+            *reinterpret_cast<uint2 *>(lds_low + ((size_t)q << logC) + 8u * tid) =
+                make_uint2(accP[q][0], accP[q][1]);
+    }
+    __syncthreads();
+
+    // ---- a5 (positions): exclusive popcount prefix over the block's mask words ----
+    const uint32_t nwords = B >> 9;
+    if (wave == 0) {
+        const uint32_t wv = lane < nwords ? s_maskw[lane] : 0u;
+        const uint32_t pc = __popc(wv);
+        const uint32_t incl = wave_incl_scan(pc, lane);
+        s_pre[lane] = incl - pc;
+        if (lane == 63) s_u32[1] = incl;
+    }
+    __syncthreads();
+    const uint32_t cnt = s_u32[1];
+    const uint64_t err = s_u32[2] ? ST_ERR : 0ull;
+    const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
+    const uint32_t S = (fixed + 2u * A * cnt + 15u) & ~15u;
+
+    // ---- a6: publish this block's size at once, so successors can look back -------
+    if (tid == 0)
+        st_state(p.ws_state + k, (k == 0 ? ST_INCLUSIVE : ST_AGGREGATE) | err | (uint64_t)(S >> 4));
+
+    // ---- a5: one record per masked group ------------------------------------------
+    if (A > 0) {
+        constexpr HHTable TH = HH<A>::table;
+        const uint32_t par = tid & 1u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            // even lanes pack the group of row 2u, odd lanes the group of row 2u+1
+            const uint32_t own0 = par ? HI[2 * u + 1][0] : HI[2 * u][0];
+            const uint32_t own1 = par ? HI[2 * u + 1][1] : HI[2 * u][1];
+            const uint32_t snd0 = par ? HI[2 * u][0] : HI[2 * u + 1][0];
+            const uint32_t snd1 = par ? HI[2 * u][1] : HI[2 * u + 1][1];
+            const uint32_t rcv0 = swap_pair(snd0);
+            const uint32_t rcv1 = swap_pair(snd1);
+            uint32_t F[4];
+            F[0] = par ? rcv0 : own0;
+            F[1] = par ? rcv1 : own1;
+            F[2] = par ? own0 : rcv0;
+            F[3] = par ? own1 : rcv1;
+            const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
+            const uint32_t wv = s_maskw[g >> 5];
+            const uint32_t bit = (wv >> (g & 31u)) & 1u;
+            if (active && bit) {
+                const uint32_t rank = s_pre[g >> 5] + __popc(wv & ((1u << (g & 31u)) - 1u));
+                // the group's 16 values are 2 columns of 8 rows: row r = bytes (2r, 2r+1)
+                uint32_t P[AP];
+#pragma unroll
+                for (int q = 0; q < AP; ++q) P[q] = 0;
+#pragma unroll
+                for (int f = 0; f < TH.count; ++f) {
+                    const int r = TH.row[f];
+                    const uint32_t s = shl_or_shr(F[r >> 1], TH.shift[f] - 16 * (r & 1));
+                    P[TH.plane[f]] |= s & (TH.dmask[f] * 0x0101u);
+                }
+                // normalized byte j = byte (j & 1) of P[j >> 1]; stream word i = nb[i] | nb[i + A] << 8
+                uint16_t *dst = reinterpret_cast<uint16_t *>(lds_high + 2u * A * rank);
+#pragma unroll
+                for (int i = 0; i < A; ++i) {
+                    const uint32_t lo = (P[i >> 1] >> (8 * (i & 1))) & 0xFFu;
+                    const uint32_t hi = (P[(i + A) >> 1] >> (8 * ((i + A) & 1))) & 0xFFu;
+                    dst[i] = (uint16_t)(lo | (hi << 8));
+                }
+            }
+        }
+    }
+
+    // ---- a6: decoupled look-back over the predecessors' scan-state words ----------
+    if (wave == 0) {
+        uint64_t excl = 0, err_all = err;
+        if (k > 0) {
+            int64_t base = (int64_t)k - 1;
+            bool done = false;
+            uint32_t spins = 0;
+            while (!done) {
+                const int64_t idx = base - (int64_t)lane;
+                uint64_t s = idx >= 0 ? ld_state(p.ws_state + idx) : ST_INCLUSIVE;
+                const uint64_t incl = __builtin_amdgcn_ballot_w64((s >> 62) == 2);
+                const uint64_t notready = __builtin_amdgcn_ballot_w64((s >> 62) == 0);
+                const uint64_t need = incl ? (((incl & (~incl + 1)) << 1) - 1) : ~0ull;
+                if (notready & need) {
+                    if (++spins > SPIN_LIMIT) { err_all |= ST_ERR; break; }   // never hang
+                    __builtin_amdgcn_s_sleep(1);
+                    continue;
+                }
+                const bool take = (need >> lane) & 1ull;
+                excl += wave_sum(take ? (s & ST_VALUE) : 0ull);
+                if (__builtin_amdgcn_ballot_w64(take && (s & ST_ERR))) err_all |= ST_ERR;
+                if (incl) done = true;
+                else base -= 64;
+            }
+            if (lane == 0)
+                st_state(p.ws_state + k, ST_INCLUSIVE | err_all | ((excl + (S >> 4)) & ST_VALUE));
+        }
+        if (lane == 0) {
+            const uint64_t off = excl << 4;
+            s_u32[3] = (uint32_t)off;
+            s_u32[4] = (uint32_t)(off >> 32);
+            s_u32[6] = err_all ? 1u : 0u;
+            s_u32[5] = (atomicAdd(p.ws_done, 1u) == p.nb - 1u) ? 1u : 0u;
+        }
+    }
+    __syncthreads();
+
+    // ---- a7: stores -----------------------------------------------------------------
+    const uint64_t off = ((uint64_t)s_u32[4] << 32) | s_u32[3];
+    uint8_t *dst = p.out + p.payload_base + off;
+    if (active) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SM[t][0], SM[t][1]);
+    }
+    if (tid < (B >> 11))
+        *reinterpret_cast<uint4 *>(dst + B + 16u * tid) = *reinterpret_cast<const uint4 *>(&s_maskw[4 * tid]);
+    if (M > 0) {
+        uint8_t *dlow = dst + B + (B >> 7);
+        const uint32_t T2 = (M * B) >> 4;                 // half of the plane's length
+        for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
+            const uint2 a = *reinterpret_cast<const uint2 *>(lds_low + 8u * v);
+            const uint2 c = *reinterpret_cast<const uint2 *>(lds_low + 8u * v + T2);
+            uint4 o;   // stream byte 2i = normalized byte i, stream byte 2i+1 = normalized byte i + T/2
+            o.x = byte_perm(c.x, a.x, 0x05010400u);
+            o.y = byte_perm(c.x, a.x, 0x07030602u);
+            o.z = byte_perm(c.y, a.y, 0x05010400u);
+            o.w = byte_perm(c.y, a.y, 0x07030602u);
+            *reinterpret_cast<uint4 *>(dlow + 16u * v) = o;
+        }
+    }
+    if (A > 0) {
+        uint8_t *dhigh = dst + fixed;
+        const uint32_t hbytes = 2u * A * cnt;             // even
+        for (uint32_t v = tid; 16u * v < hbytes; v += blockDim.x) {
+            uint4 o = *reinterpret_cast<const uint4 *>(lds_high + 16u * v);
+            uint32_t w[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {                 // zero the padding behind the last record
+                const uint32_t at = 16u * v + 4u * i;
+                if (at >= hbytes) w[i] = 0;
+                else if (at + 2 >= hbytes) w[i] &= 0xFFFFu;
+            }
+            *reinterpret_cast<uint4 *>(dhigh + 16u * v) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+    if (tid == 0) {
+        uint64_t *table = reinterpret_cast<uint64_t *>(p.out + 64);
+        table[k] = off;
+        if (k == p.nb - 1u) {
+            const uint64_t end = off + S;
+            const bool fail = s_u32[6] != 0;
+            const uint64_t total = fail ? 0ull : p.payload_base + end;
+            table[p.nb] = end;
+            if (((uint64_t)(p.nb + 1u) & 1ull)) table[p.nb + 1u] = 0;   // pad up to the payload base
+            uint32_t *h = reinterpret_cast<uint32_t *>(p.out);
+            h[0] = 0x43454E45u;                              // "ENEC"
+            h[1] = 1u | (0u << 16) | (16u << 24);            // version, dtype bf16, L
+            h[2] = (uint32_t)p.n_elems; h[3] = (uint32_t)(p.n_elems >> 32);
+            h[4] = B; h[5] = p.nb;
+            h[6] = p.b | ((uint32_t)N << 8) | ((uint32_t)M << 16) | (8u << 24);
+            h[7] = fail ? 6u : 0u;
+            h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
+#pragma unroll
+            for (int i = 10; i < 16; ++i) h[i] = 0;
+            if (p.out_bytes) *p.out_bytes = total;
+        }
+    }
+    // the workgroup that finished last hands the workspace back zeroed
+    if (s_u32[5]) {
+        for (uint32_t i = tid; i < p.nb; i += blockDim.x) p.ws_state[i] = 0;
+        if (tid == 0) { *p.ws_ticket = 0; *p.ws_done = 0; }
+    }
+}
+
+// Header-only stream for an empty tensor.
+__global__ void compress_empty_kernel(const CompressArgs p, uint32_t n, uint32_t m)
+{
+    if (threadIdx.x != 0) return;
+    uint32_t *h = reinterpret_cast<uint32_t *>(p.out);
+    h[0] = 0x43454E45u;
+    h[1] = 1u | (16u << 24);
+    h[2] = h[3] = 0;
+    h[4] = p.B; h[5] = 0;
+    h[6] = p.b | (n << 8) | (m << 16) | (8u << 24);
+    h[7] = 0;
+    h[8] = 80; h[9] = 0;
+    for (int i = 10; i < 16; ++i) h[i] = 0;
+    h[16] = h[17] = h[18] = h[19] = 0;      // table[0] = 0 and the pad to 80 bytes
+    if (p.out_bytes) *p.out_bytes = 80;
+}
+
+// ---------------------------------------------------------------------------------
+// decompression: offset lookup, mask prefix, unpack, inverse transform, recombine
+// (Sec. V-A decompression path; Alg. 1 decompression part)
+// ---------------------------------------------------------------------------------
+template <int M, int A>
+__global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
+{
+    constexpr int N = M + A;
+    constexpr uint32_t SREP = (1u << (N - 1)) * 0x01010101u;
+    constexpr int MP = M > 0 ? M : 1;
+    constexpr int AP = A > 0 ? A : 1;
+
+    extern __shared__ __align__(16) uint8_t smem[];
+    __shared__ uint32_t s_maskw[64];
+    __shared__ uint32_t s_pre[64];
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t B = p.B, logC = p.logB - 3u;
+    const uint32_t nact = B >> 6;
+    const bool active = tid < nact;
+    const uint32_t k = blockIdx.x;
+    uint8_t *lds_low = smem;
+    uint8_t *lds_high = smem + (((size_t)M * B) >> 3);
+
+    // d1: the header in memory must be the one the launch was configured from
+    {
+        const uint32_t *h = reinterpret_cast<const uint32_t *>(p.in);
+        bool same = true;
+#pragma unroll
+        for (int i = 0; i < 10; ++i) same &= (h[i] == p.hdr[i]);
+        if (!same) return;
+    }
+    const uint64_t *table = reinterpret_cast<const uint64_t *>(p.in + 64);
+    const uint64_t off = table[k];
+    const uint64_t size = table[k + 1] - off;
+    const uint8_t *src = p.in + p.payload_base + off;
+    const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
+    if (size < fixed || size > fixed + 2u * A * (B >> 4) + 15u) return;      // corrupt table: touch nothing
+
+    // sign/mantissa bytes: 64-bit loads, issued first
+    uint2 smv[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        smv[t] = active ? *reinterpret_cast<const uint2 *>(src + ((size_t)t << logC) + 8u * tid) : make_uint2(0, 0);
+
+    // d2: mask words and their exclusive popcount prefix
+    const uint32_t nwords = B >> 9;
+    if (wave == 0) {
+        const uint32_t wv = lane < nwords ? reinterpret_cast<const uint32_t *>(src + B)[lane] : 0u;
+        const uint32_t pc = __popc(wv);
+        const uint32_t incl = wave_incl_scan(pc, lane);
+        s_maskw[lane] = wv;
+        s_pre[lane] = incl - pc;
+    }
+    // low plane -> normalized bytes in LDS (undo the final byte interleave of Alg. 2)
+    if (M > 0) {
+        const uint8_t *slow = src + B + (B >> 7);
+        const uint32_t T2 = (M * B) >> 4;
+        for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
+            const uint4 q = *reinterpret_cast<const uint4 *>(slow + 16u * v);
+            uint2 ev, od;
+            ev.x = byte_perm(q.y, q.x, 0x06040200u);
+            ev.y = byte_perm(q.w, q.z, 0x06040200u);
+            od.x = byte_perm(q.y, q.x, 0x07050301u);
+            od.y = byte_perm(q.w, q.z, 0x07050301u);
+            *reinterpret_cast<uint2 *>(lds_low + 8u * v) = ev;
+            *reinterpret_cast<uint2 *>(lds_low + 8u * v + T2) = od;
+        }
+    }
+    if (A > 0) {
+        const uint8_t *shigh = src + fixed;
+        const uint32_t hbytes = (uint32_t)size - fixed;   // multiple of 16 by construction of `size` checks below
+        for (uint32_t v = tid; 16u * v + 16u <= hbytes; v += blockDim.x)
+            *reinterpret_cast<uint4 *>(lds_high + 16u * v) = *reinterpret_cast<const uint4 *>(shigh + 16u * v);
+    }
+    __syncthreads();
+    if (!active) return;
+
+    uint32_t Pl[MP][2];
+#pragma unroll
+    for (int q = 0; q < MP; ++q) {
+        if (M > 0) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(lds_low + ((size_t)q << logC) + 8u * tid);
+            Pl[q][0] = v.x; Pl[q][1] = v.y;
+        } else {
+            Pl[q][0] = Pl[q][1] = 0;
+        }
+    }
+
+    const uint32_t crep = ((p.b + (1u << (N - 1))) & 0xFFu) * 0x01010101u;
+    const uint64_t blk0 = (uint64_t)k << p.logB;
+    const uint32_t par = tid & 1u;
+    constexpr HHTable TL = HH<M>::table;
+
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        uint32_t Y[2] = {0u, 0u};
+        // d3: low m bits of the 8 columns of this row
+        if (M > 0) {
+#pragma unroll
+            for (int f = 0; f < TL.count; ++f)
+                if (TL.row[f] == t) {
+                    const uint32_t smask = (TL.shift[f] >= 0 ? (TL.dmask[f] >> TL.shift[f])
+                                                            : (TL.dmask[f] << (-TL.shift[f]))) * 0x01010101u;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        Y[h] |= shl_or_shr(Pl[TL.plane[f]][h], -TL.shift[f]) & smask;
+                }
+        }
+        // d2/d3: high bits of masked groups, found through the mask prefix
+        if (A > 0) {
+            constexpr HHTable TH = HH<A>::table;
+            const uint32_t g = ((uint32_t)t << (logC - 4)) + (tid >> 1);
+            const uint32_t wv = s_maskw[g >> 5];
+            if ((wv >> (g & 31u)) & 1u) {
+                const uint32_t rank = s_pre[g >> 5] + __popc(wv & ((1u << (g & 31u)) - 1u));
+                const uint16_t *rec = reinterpret_cast<const uint16_t *>(lds_high + 2u * A * rank);
+                uint32_t nbyte[2 * AP];
+#pragma unroll
+                for (int i = 0; i < A; ++i) {
+                    const uint32_t w = rec[i];
+                    nbyte[i] = w & 0xFFu;
+                    nbyte[i + A] = w >> 8;
+                }
+                uint32_t P[AP];
+#pragma unroll
+                for (int q = 0; q < A; ++q) P[q] = 0;
+#pragma unroll
+                for (int j = 0; j < 2 * A; ++j) P[j >> 1] |= nbyte[j] << (8 * (j & 1));
+                uint32_t E[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) E[r] = 0;
+#pragma unroll
+                for (int f = 0; f < TH.count; ++f) {
+                    const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
+                                                            : (TH.dmask[f] << (-TH.shift[f]))) * 0x0101u;
+                    E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
+                }
+                // this lane's 8 elements are rows 4*par .. 4*par+3 of the two-column view
+                const uint32_t h0 = par ? (E[4] | (E[5] << 16)) : (E[0] | (E[1] << 16));
+                const uint32_t h1 = par ? (E[6] | (E[7] << 16)) : (E[2] | (E[3] << 16));
+                Y[0] |= h0 << M;
+                Y[1] |= h1 << M;
+            }
+        }
+        // d4: x = b - sext_n(y) = (b + 2^(n-1)) - (y ^ 2^(n-1)); recombine with sign/mantissa
+        uint32_t o[4];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t Z = Y[h] ^ SREP;
+            const uint32_t X = p.mode == 0 ? crep - Z : bytesub_safe(crep, Z);
+            const uint32_t sm = h ? smv[t].y : smv[t].x;
+            const uint32_t Hi = bfi(0x7F7F7F7Fu, X >> 1, sm);
+            const uint32_t Lo = bfi(0x7F7F7F7Fu, sm, X << 7);
+            o[2 * h] = byte_perm(Hi, Lo, 0x05010400u);
+            o[2 * h + 1] = byte_perm(Hi, Lo, 0x07030602u);
+        }
+        const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
+        if (e0 + 8 <= p.n_elems) {
+            *reinterpret_cast<uint4 *>(p.out + e0) = make_uint4(o[0], o[1], o[2], o[3]);
+        } else if (e0 < p.n_elems) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (e0 + i < p.n_elems) p.out[e0 + i] = (uint16_t)(o[i >> 1] >> (16 * (i & 1)));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// exponent histogram (Sec. V-E phase 1), zero fill, plain copy
+// ---------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) histogram_kernel(const uint16_t *in, uint64_t n_elems,
+                                                        unsigned long long *hist)
+{
+    __shared__ uint32_t s_h[4][256];
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t i = tid; i < 1024; i += 256) (&s_h[0][0])[i] = 0;
+    __syncthreads();
+    uint32_t *mine = s_h[tid >> 6];
+    const uint64_t nvec = n_elems >> 3;
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    // a wave's LDS counters cannot overflow: each thread adds at most 8 per iteration and the
+    // launch keeps iterations * 64 * 8 below 2^32
+    for (uint64_t v = (uint64_t)blockIdx.x * 256u + tid; v < nvec; v += stride) {
+        const uint4 q = reinterpret_cast<const uint4 *>(in)[v];
+        const uint32_t d[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            atomicAdd(&mine[(d[i] >> 7) & 0xFFu], 1u);
+            atomicAdd(&mine[(d[i] >> 23) & 0xFFu], 1u);
+        }
+    }
+    if (blockIdx.x == 0 && tid < (uint32_t)(n_elems & 7u))
+        atomicAdd(&mine[(in[(nvec << 3) + tid] >> 7) & 0xFFu], 1u);
+    __syncthreads();
+    const uint32_t c = s_h[0][tid] + s_h[1][tid] + s_h[2][tid] + s_h[3][tid];
+    if (c) atomicAdd(&hist[tid], (unsigned long long)c);
+}
+
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint4 *p, uint64_t nvec)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t v = (uint64_t)blockIdx.x * 256u + threadIdx.x; v < nvec; v += stride)
+        p[v] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ void __launch_bounds__(256) copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, uint64_t nvec)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t v = (uint64_t)blockIdx.x * 256u + threadIdx.x; v < nvec; v += stride) dst[v] = src[v];
+}
+
+}  // namespace enec

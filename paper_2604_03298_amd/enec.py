@@ -1,0 +1,202 @@
+"""Thin Python binding of libenec's C ABI (include/enec.h).
+
+Argument marshalling only: every step of the codec runs in the library's HIP kernels.
+PyTorch is used for device memory and streams, nothing else.  There is no CPU fallback:
+if libenec.so has not been built, or there is no GPU, the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libenec.so")
+
+OK, E_ARG, E_DTYPE, E_BLOCK, E_PARAMS, E_CAPACITY, E_RANGE, E_FORMAT, E_HIP = range(9)
+BF16 = 0
+HEADER_BYTES = 64
+
+EXPORTS = [
+    "enec_version", "enec_strerror", "enec_default_block_size", "enec_compress_bound",
+    "enec_workspace_bytes", "enec_workspace_init", "enec_compress", "enec_decompress",
+    "enec_decompress_with_header", "enec_tune", "enec_tune_histogram", "enec_stream_info",
+    "enec_copy",
+]
+
+
+class Params(C.Structure):
+    _fields_ = [("b", C.c_uint8), ("n", C.c_uint8), ("m", C.c_uint8), ("L", C.c_uint8)]
+
+    def astuple(self):
+        return (self.b, self.n, self.m, self.L)
+
+
+class EnecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib():
+    """Loads libenec.so (built in-tree by paper_2604_03298_amd.build) or raises."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2604_03298_amd.build` "
+                "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, sz, u32, u64p = C.c_void_p, C.c_size_t, C.c_uint32, C.POINTER(C.c_uint64)
+        L.enec_version.restype = u32
+        L.enec_version.argtypes = []
+        L.enec_strerror.restype = C.c_char_p
+        L.enec_strerror.argtypes = [C.c_int]
+        L.enec_default_block_size.restype = u32
+        L.enec_default_block_size.argtypes = [sz]
+        L.enec_compress_bound.restype = sz
+        L.enec_compress_bound.argtypes = [sz, C.c_int, u32]
+        L.enec_workspace_bytes.restype = sz
+        L.enec_workspace_bytes.argtypes = [sz, u32]
+        L.enec_workspace_init.restype = C.c_int
+        L.enec_workspace_init.argtypes = [vp, sz, vp]
+        L.enec_compress.restype = C.c_int
+        L.enec_compress.argtypes = [vp, sz, C.c_int, u32, C.POINTER(Params), vp, sz, vp, vp, sz, vp]
+        L.enec_decompress.restype = C.c_int
+        L.enec_decompress.argtypes = [vp, vp, sz, vp]
+        L.enec_decompress_with_header.restype = C.c_int
+        L.enec_decompress_with_header.argtypes = [vp, vp, vp, sz, vp]
+        L.enec_tune.restype = C.c_int
+        L.enec_tune.argtypes = [vp, sz, C.c_int, C.POINTER(Params), u64p, vp, sz, vp]
+        L.enec_tune_histogram.restype = C.c_int
+        L.enec_tune_histogram.argtypes = [u64p, C.POINTER(Params)]
+        L.enec_stream_info.restype = C.c_int
+        L.enec_stream_info.argtypes = [vp, C.POINTER(Params), u64p, C.POINTER(u32), u64p,
+                                       C.POINTER(C.c_int), C.POINTER(u32)]
+        L.enec_copy.restype = C.c_int
+        L.enec_copy.argtypes = [vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, where: str):
+    if rc != OK:
+        raise EnecError(rc, where)
+
+
+def _stream_handle(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _params(p) -> Params:
+    return p if isinstance(p, Params) else Params(*[int(v) for v in p])
+
+
+# ---- host-only entry points -------------------------------------------------------
+def version() -> int:
+    return int(lib().enec_version())
+
+
+def strerror(status: int) -> str:
+    return lib().enec_strerror(int(status)).decode()
+
+
+def default_block_size(n_elems: int) -> int:
+    return int(lib().enec_default_block_size(n_elems))
+
+
+def compress_bound(n_elems: int, dtype: int = BF16, block_size: int = 0) -> int:
+    return int(lib().enec_compress_bound(n_elems, dtype, block_size))
+
+
+def workspace_bytes(n_elems: int, block_size: int = 0) -> int:
+    return int(lib().enec_workspace_bytes(n_elems, block_size))
+
+
+def tune_histogram(hist) -> tuple:
+    h = np.ascontiguousarray(hist, dtype=np.uint64)
+    assert h.size == 256
+    p = Params()
+    _check(lib().enec_tune_histogram(h.ctypes.data_as(C.POINTER(C.c_uint64)), C.byref(p)),
+           "enec_tune_histogram")
+    return p.astuple()
+
+
+def stream_info(header) -> dict:
+    """header: bytes / numpy uint8 array holding at least the first 64 bytes of a stream."""
+    buf = np.frombuffer(bytes(header[:HEADER_BYTES]), dtype=np.uint8).copy()
+    p, n, B, total = Params(), C.c_uint64(0), C.c_uint32(0), C.c_uint64(0)
+    dtype, status = C.c_int(0), C.c_uint32(0)
+    rc = lib().enec_stream_info(buf.ctypes.data, C.byref(p), C.byref(n), C.byref(B), C.byref(total),
+                                C.byref(dtype), C.byref(status))
+    return dict(rc=rc, params=p.astuple(), n_elems=int(n.value), block_size=int(B.value),
+                total_bytes=int(total.value), dtype=int(dtype.value), status=int(status.value))
+
+
+# ---- device entry points (torch tensors carry the pointers) ------------------------
+def workspace_init(workspace, stream=None):
+    _check(lib().enec_workspace_init(C.c_void_p(workspace.data_ptr()),
+                                     workspace.numel() * workspace.element_size(),
+                                     _stream_handle(stream)), "enec_workspace_init")
+
+
+def new_workspace(n_elems: int, block_size: int = 0, device="cuda", stream=None):
+    """Allocates (torch) and zeroes (library fill kernel) a workspace for tensors up to n_elems."""
+    import torch
+    ws = torch.empty(workspace_bytes(n_elems, block_size), dtype=torch.uint8, device=device)
+    workspace_init(ws, stream)
+    return ws
+
+
+def compress(src, params, out, workspace, block_size: int = 0, out_bytes=None, stream=None,
+             n_elems: int | None = None) -> int:
+    """Enqueues enec_compress.  src: device tensor of 2-byte elements; params: (b, n, m, L) or
+    None (tune first); out: device uint8 tensor of >= compress_bound bytes; out_bytes: None or a
+    device / pinned-host tensor with room for one u64.  Returns the status code (range errors
+    are reported through the stream header, not here)."""
+    n = src.numel() if n_elems is None else n_elems
+    assert src.element_size() == 2
+    pp = C.byref(_params(params)) if params is not None else None
+    ob = C.c_void_p(out_bytes.data_ptr()) if out_bytes is not None else None
+    return int(lib().enec_compress(
+        C.c_void_p(src.data_ptr()), n, BF16, block_size, pp, C.c_void_p(out.data_ptr()),
+        out.numel() * out.element_size(), ob, C.c_void_p(workspace.data_ptr()),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+def decompress(stream_buf, out, n_elems: int | None = None, stream=None) -> int:
+    n = out.numel() if n_elems is None else n_elems
+    return int(lib().enec_decompress(C.c_void_p(stream_buf.data_ptr()), C.c_void_p(out.data_ptr()), n,
+                                     _stream_handle(stream)))
+
+
+def decompress_with_header(stream_buf, host_header, out, n_elems: int | None = None, stream=None) -> int:
+    n = out.numel() if n_elems is None else n_elems
+    hdr = np.frombuffer(bytes(host_header[:HEADER_BYTES]), dtype=np.uint8).copy()
+    return int(lib().enec_decompress_with_header(
+        C.c_void_p(stream_buf.data_ptr()), hdr.ctypes.data, C.c_void_p(out.data_ptr()), n,
+        _stream_handle(stream)))
+
+
+def tune(src, workspace, stream=None, want_histogram: bool = False):
+    """-> (b, n, m, L) [, histogram]; synchronous."""
+    p = Params()
+    hist = np.zeros(256, dtype=np.uint64)
+    _check(lib().enec_tune(C.c_void_p(src.data_ptr()), src.numel(), BF16, C.byref(p),
+                           hist.ctypes.data_as(C.POINTER(C.c_uint64)),
+                           C.c_void_p(workspace.data_ptr()),
+                           workspace.numel() * workspace.element_size(), _stream_handle(stream)),
+           "enec_tune")
+    return (p.astuple(), hist) if want_histogram else p.astuple()
+
+
+def copy(dst, src, nbytes: int | None = None, stream=None) -> int:
+    nb = src.numel() * src.element_size() if nbytes is None else nbytes
+    return int(lib().enec_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nb,
+                               _stream_handle(stream)))

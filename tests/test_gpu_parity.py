@@ -1,0 +1,259 @@
+"""GPU parity: libenec (through its C ABI) against the CPU oracle, byte for byte.
+
+The compressed stream is a pure function of (input, params, block size), so the GPU
+stream must equal the oracle's stream exactly, and both decompressors must give back
+the input bit for bit.  Integer / byte work only: the bar is bit-exact everywhere.
+"""
+import numpy as np
+import pytest
+
+from paper_2604_03298_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2604_03298_amd import enec
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    enec.lib()      # raises if libenec.so is missing: there is no fallback
+
+    class G:
+        pass
+    g = G()
+    g.torch, g.enec = torch, enec
+    g.ws = enec.new_workspace(1 << 28)
+    g.size_pinned = torch.zeros(1, dtype=torch.int64).pin_memory()
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda() if a.size else \
+            torch.empty(8, dtype=torch.int16, device="cuda")
+
+    def compress(w, params, B=0, src=None):
+        src = to_dev(w) if src is None else src
+        cap = enec.compress_bound(w.size, block_size=B)
+        out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device="cuda")   # poison
+        g.size_pinned.fill_(-1)
+        rc = enec.compress(src, params, out, g.ws, block_size=B, out_bytes=g.size_pinned, n_elems=w.size)
+        torch.cuda.synchronize()
+        return rc, out.cpu().numpy(), int(g.size_pinned.item()), cap
+
+    def decompress(stream, n, with_header=True):
+        buf = torch.from_numpy(np.ascontiguousarray(stream)).cuda()
+        out = torch.full((max(n, 8),), 0x5A5A, dtype=torch.int16, device="cuda")
+        if with_header:
+            rc = enec.decompress_with_header(buf, stream[:64].tobytes(), out, n_elems=n)
+        else:
+            rc = enec.decompress(buf, out, n_elems=n)
+        torch.cuda.synchronize()
+        return rc, out.cpu().numpy().view(np.uint16)[:n]
+
+    g.to_dev, g.compress, g.decompress = to_dev, compress, decompress
+    return g
+
+
+def check_both_ways(gpu, oracle, w, params, B=0, label=""):
+    Bo = B if B else oracle.default_block(w.size)
+    rc_o, s_o = oracle.compress(w, params, Bo)
+    assert rc_o == oracle.OK, label
+    rc, out, nbytes, cap = gpu.compress(w, params, B)
+    assert rc == 0, label
+    assert nbytes == s_o.size, f"{label}: size {nbytes} vs oracle {s_o.size}"
+    assert np.array_equal(out[:nbytes], s_o), f"{label}: compressed stream differs from the oracle's"
+    assert (out[cap:] == 0xA5).all(), f"{label}: wrote past the bound"
+    rc, d = gpu.decompress(s_o, w.size)                     # GPU decodes the oracle's stream
+    assert rc == 0 and np.array_equal(d, w), f"{label}: GPU decompress(oracle stream) != input"
+    rc_d, d_o = oracle.decompress(out[:nbytes], w.size)     # oracle decodes the GPU's stream
+    assert rc_d == 0 and np.array_equal(d_o, w), label
+    return s_o
+
+
+def in_window_tensor(rng, b, n, size, quiet_frac=0.6, m=0):
+    lo, hi = max(0, b - (1 << (n - 1)) + 1), min(255, b + (1 << (n - 1)))
+    x = rng.integers(lo, hi + 1, size=size).astype(np.uint16)
+    groups = size // 16
+    quiet = np.nonzero(rng.random(groups) < quiet_frac)[0]
+    small = max(1, min(1 << m, 1 << (n - 1), b - lo + 1))
+    for g in quiet:
+        x[g * 16:(g + 1) * 16] = b - rng.integers(0, small, size=16)
+    return ((rng.integers(0, 2, size=size).astype(np.uint16) << 15) | (x << 7)
+            | rng.integers(0, 128, size=size).astype(np.uint16)).astype(np.uint16)
+
+
+def test_config1_full(gpu, oracle):
+    w = W.config1()
+    params = oracle.tune(w)
+    s = check_both_ways(gpu, oracle, w, params, 16384, "config1")
+    assert 1.33 < 2 * w.size / s.size < 1.40
+
+
+@pytest.mark.parametrize("n", range(1, 9))
+def test_every_width_pair(gpu, oracle, n):
+    rng = np.random.default_rng(900 + n)
+    for m in range(0, n + 1):
+        for B, size in [(2048, 3 * 2048 + 517), (16384, 2 * 16384 + 4099)]:
+            w = in_window_tensor(rng, 128, n, size, m=m)
+            check_both_ways(gpu, oracle, w, (128, n, m, 16), B, f"n={n} m={m} B={B}")
+
+
+@pytest.mark.parametrize("B", [2048, 4096, 8192, 16384, 32768])
+def test_block_sizes(gpu, oracle, B):
+    w = W.gaussian(7 * B + 1234, 0.02, 31 + B)
+    check_both_ways(gpu, oracle, w, oracle.tune(w), B, f"B={B}")
+    w = W.gaussian(3 * B, 0.02, 32 + B)                     # no ragged tail
+    check_both_ways(gpu, oracle, w, oracle.tune(w), B, f"B={B} exact")
+
+
+@pytest.mark.parametrize("n_elems", [0, 1, 7, 8, 15, 16, 17, 2047, 2048, 2049, 16383, 16384, 16385, 50001])
+def test_ragged_and_tiny(gpu, oracle, n_elems):
+    w = W.gaussian(n_elems, 0.02, 2000 + n_elems) if n_elems else np.zeros(0, np.uint16)
+    assert gpu.enec.default_block_size(n_elems) == oracle.default_block(n_elems)
+    check_both_ways(gpu, oracle, w, oracle.tune(w), 0, f"n_elems={n_elems}")
+
+
+def test_window_at_the_ends_of_the_exponent_range(gpu, oracle):
+    rng = np.random.default_rng(5)
+    for (b, n, m) in [(3, 6, 2), (0, 1, 0), (0, 4, 1), (250, 6, 3), (255, 3, 1), (255, 8, 4),
+                      (0, 8, 3), (127, 8, 4), (128, 8, 0), (100, 8, 8), (31, 6, 3), (223, 6, 3),
+                      (30, 6, 3), (224, 6, 3)]:
+        w = in_window_tensor(rng, b, n, 2 * 16384 + 77, m=m)
+        check_both_ways(gpu, oracle, w, (b, n, m, 16), 16384, f"b={b} n={n} m={m}")
+
+
+def test_config2_reduced_and_norm_vectors(gpu, oracle):
+    for name, w in W.config2(hidden=1024, ffn=2752):
+        check_both_ways(gpu, oracle, w, oracle.tune(w), 0, name)
+
+
+def test_config3_edge_mix(gpu, oracle):
+    w, cat = W.config3(n_blocks=256)
+    p = oracle.tune(w)
+    check_both_ways(gpu, oracle, w, p, 16384, "mix")
+    for c, t in enumerate(W.config3_by_category(n_blocks=256)):
+        check_both_ways(gpu, oracle, t, oracle.tune(t), 16384, f"category {c}")
+
+
+def test_special_bit_patterns(gpu, oracle):
+    specials = np.array([0x0000, 0x8000, 0x7F80, 0xFF80, 0x7FC0, 0xFFFF, 0x7F81, 0x0001, 0x807F,
+                         0x0080, 0x3F80, 0xBF80], np.uint16)
+    w = np.tile(specials, 5000)
+    check_both_ways(gpu, oracle, w, oracle.tune(w), 0, "specials")
+    w = np.full(40000, 0xFFFF, np.uint16)
+    check_both_ways(gpu, oracle, w, oracle.tune(w), 0, "all ones")
+
+
+def test_range_error_is_reported_in_the_header(gpu, oracle):
+    w = W.gaussian(5 * 16384, 0.02, 77)
+    for params in [(122, 3, 1, 16), (3, 4, 2, 16), (250, 5, 2, 16)]:
+        rc_o, s_o = oracle.compress(w, params, 16384)
+        assert rc_o == oracle.E_RANGE
+        rc, out, nbytes, cap = gpu.compress(w, params, 16384)
+        assert rc == 0 and nbytes == 0
+        assert np.array_equal(out[:64], s_o[:64])
+        info = gpu.enec.stream_info(out[:64])
+        assert info["status"] == gpu.enec.E_RANGE and info["total_bytes"] == 0
+        rc, d = gpu.decompress(out, w.size)
+        assert rc == gpu.enec.E_FORMAT
+    # a single offending element in the last block is enough
+    w = W.gaussian(3 * 16384, 0.02, 78)
+    p = oracle.tune(w)
+    w[-1] = 0x7F80
+    assert gpu.compress(w, p, 16384)[2] == 0
+
+
+def test_workspace_is_reusable_and_results_are_deterministic(gpu, oracle):
+    big = W.gaussian(300 * 16384 + 5, 0.02, 81)
+    small = W.gaussian(3 * 16384, 0.01, 82)
+    pb, ps = oracle.tune(big), oracle.tune(small)
+    sb, ss = oracle.compress(big, pb, 16384)[1], oracle.compress(small, ps, 16384)[1]
+    src_b, src_s = gpu.to_dev(big), gpu.to_dev(small)
+    for i in range(6):
+        rc, out, nbytes, _ = gpu.compress(big, pb, 16384, src=src_b)
+        assert rc == 0 and nbytes == sb.size and np.array_equal(out[:nbytes], sb), f"run {i}"
+        rc, out, nbytes, _ = gpu.compress(small, ps, 16384, src=src_s)
+        assert rc == 0 and nbytes == ss.size and np.array_equal(out[:nbytes], ss), f"run {i}"
+    assert int(gpu.ws.cpu().numpy()[:256].view(np.uint32).sum()) == 0      # counters handed back zeroed
+
+
+def test_back_to_back_calls_without_sync(gpu, oracle):
+    torch, enec = gpu.torch, gpu.enec
+    tensors = [W.gaussian(n, 0.02, 90 + i) for i, n in enumerate([70000, 16384 * 40, 4096, 16384 * 9 + 1])]
+    params = [oracle.tune(t) for t in tensors]
+    srcs = [gpu.to_dev(t) for t in tensors]
+    outs = [torch.zeros(enec.compress_bound(t.size), dtype=torch.uint8, device="cuda") for t in tensors]
+    sizes = torch.zeros(len(tensors), dtype=torch.int64, device="cuda")
+    for i, t in enumerate(tensors):
+        assert enec.compress(srcs[i], params[i], outs[i], gpu.ws, out_bytes=sizes[i:i + 1], n_elems=t.size) == 0
+    torch.cuda.synchronize()
+    for i, t in enumerate(tensors):
+        s_o = oracle.compress(t, params[i], oracle.default_block(t.size))[1]
+        assert int(sizes[i]) == s_o.size
+        assert np.array_equal(outs[i].cpu().numpy()[:s_o.size], s_o)
+    # and decompress all of them back to back
+    backs = [torch.zeros(max(t.size, 8), dtype=torch.int16, device="cuda") for t in tensors]
+    for i, t in enumerate(tensors):
+        hdr = outs[i][:64].cpu().numpy()
+        assert enec.decompress_with_header(outs[i], hdr.tobytes(), backs[i], n_elems=t.size) == 0
+    torch.cuda.synchronize()
+    for i, t in enumerate(tensors):
+        assert np.array_equal(backs[i].cpu().numpy().view(np.uint16)[:t.size], t)
+
+
+def test_decompress_variants_and_header_mismatch(gpu, oracle):
+    w = W.gaussian(5 * 16384 + 3, 0.02, 99)
+    p = oracle.tune(w)
+    s = oracle.compress(w, p, 16384)[1]
+    rc, d = gpu.decompress(s, w.size, with_header=False)          # reads the header itself
+    assert rc == 0 and np.array_equal(d, w)
+    assert gpu.decompress(s, w.size + 1)[0] == gpu.enec.E_FORMAT
+    bad = s.copy(); bad[0] = ord("X")
+    assert gpu.decompress(bad, w.size, with_header=False)[0] == gpu.enec.E_FORMAT
+    # a host header that does not match the device stream: the kernel must write nothing
+    other = oracle.compress(w, (p[0], 8, 4, 16), 16384)[1]
+    torch, enec = gpu.torch, gpu.enec
+    buf = torch.from_numpy(s).cuda()
+    out = torch.full((w.size,), 0x5A5A, dtype=torch.int16, device="cuda")
+    assert enec.decompress_with_header(buf, other[:64].tobytes(), out, n_elems=w.size) == 0
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy() == 0x5A5A).all()
+
+
+def test_tuner_matches_oracle(gpu, oracle):
+    cases = [W.config1(), W.gaussian(100003, 0.003, 5), np.zeros(70000, np.uint16),
+             np.full(33333, 0x3D12, np.uint16), W.config3(n_blocks=64)[0],
+             W.layer_matrix(512, 1376, 24), W.norm_vector(4096, 27), W.gaussian(5, 0.02, 1)]
+    for i, w in enumerate(cases):
+        params, hist = gpu.enec.tune(gpu.to_dev(w), gpu.ws, want_histogram=True)
+        assert np.array_equal(hist, oracle.histogram(w)), f"case {i}"
+        assert params == oracle.tune(w), f"case {i}"
+    # params = None: tune inside enec_compress
+    w = cases[0]
+    torch, enec = gpu.torch, gpu.enec
+    out = torch.zeros(enec.compress_bound(w.size), dtype=torch.uint8, device="cuda")
+    assert enec.compress(gpu.to_dev(w), None, out, gpu.ws, out_bytes=gpu.size_pinned) == 0
+    torch.cuda.synchronize()
+    s_o = oracle.compress(w, oracle.tune(w), 16384)[1]
+    assert np.array_equal(out.cpu().numpy()[:s_o.size], s_o)
+
+
+def test_host_argument_errors_on_device_pointers(gpu):
+    torch, enec = gpu.torch, gpu.enec
+    src = torch.zeros(16384, dtype=torch.int16, device="cuda")
+    out = torch.zeros(enec.compress_bound(16384), dtype=torch.uint8, device="cuda")
+    assert enec.compress(src, (122, 6, 3, 16), out[:1000], gpu.ws) == enec.E_CAPACITY
+    assert enec.compress(src, (122, 6, 3, 16), out, gpu.ws, block_size=3000) == enec.E_BLOCK
+    assert enec.compress(src, (122, 9, 3, 16), out, gpu.ws) == enec.E_PARAMS
+    assert enec.compress(src, (122, 6, 3, 8), out, gpu.ws) == enec.E_PARAMS
+    assert enec.compress(src[1:], (122, 6, 3, 16), out, gpu.ws, n_elems=100) == enec.E_ARG   # misaligned
+    pageable = torch.zeros(1, dtype=torch.int64)
+    assert enec.compress(src, (122, 6, 3, 16), out, gpu.ws, out_bytes=pageable) == enec.E_ARG
+
+
+def test_full_size_layer_and_large_tensor(gpu, oracle):
+    # configuration 2 at full size (the benchmark workload), whole streams compared
+    for name, w in W.config2():
+        check_both_ways(gpu, oracle, w, oracle.tune(w), 0, name)
+    # one tensor of the large-layer stream (8192 x 28672)
+    w = W.config4_tensor(0)
+    check_both_ways(gpu, oracle, w, oracle.tune(w), 16384, "config4[0]")

@@ -1,0 +1,118 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and its pure host functions agree with the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from conftest import ROOT
+from paper_2604_03298_amd import workloads as W
+
+
+@pytest.fixture(scope="module")
+def enec():
+    from paper_2604_03298_amd import enec as E
+    if not os.path.exists(E.LIB_PATH):
+        from paper_2604_03298_amd import build
+        build.build()
+    E.lib()
+    return E
+
+
+def test_library_exports_every_declared_symbol(enec):
+    text = open(os.path.join(ROOT, "include", "enec.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(enec_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(enec.EXPORTS), declared ^ set(enec.EXPORTS)
+    lib = ctypes.CDLL(enec.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_strerror(enec):
+    assert enec.version() == 1
+    msgs = {enec.strerror(i) for i in range(9)}
+    assert len(msgs) == 9 and enec.strerror(99) == "unknown status"
+
+
+def test_bounds_and_block_sizes_match_oracle(enec, oracle):
+    for n in [0, 1, 100, 2047, 2048, 2049, 4096, 5000, 16383, 16384, 16385, 1 << 20, (1 << 26) + 3]:
+        assert enec.default_block_size(n) == oracle.default_block(n)
+        for B in [2048, 4096, 8192, 16384, 32768]:
+            assert enec.compress_bound(n, block_size=B) == oracle.compress_bound(n, B)
+        assert enec.compress_bound(n) == oracle.compress_bound(n, oracle.default_block(n))
+        assert enec.workspace_bytes(n) >= 2304 + 8 * max(1, oracle.num_blocks(n, oracle.default_block(n)))
+    assert enec.compress_bound(100, block_size=3000) == 0
+    assert enec.compress_bound(100, dtype=1) == 0
+    assert enec.workspace_bytes(100, block_size=1000) == 0
+
+
+def test_host_tuner_matches_oracle(enec, oracle, ref):
+    rng = np.random.default_rng(17)
+    hists = [oracle.histogram(W.config1()), oracle.histogram(W.gaussian(100000, 0.3, 2)),
+             oracle.histogram(np.zeros(100, np.uint16)), np.zeros(256, np.uint64),
+             oracle.histogram(W.config3(n_blocks=16)[0]),
+             oracle.histogram(W.norm_vector(4096, 27))]
+    for _ in range(200):
+        h = np.zeros(256, np.uint64)
+        lo = int(rng.integers(0, 250)); width = int(rng.integers(1, 256 - lo))
+        idx = rng.integers(lo, lo + width, size=int(rng.integers(1, 40)))
+        h[idx] = rng.integers(1, 1 << int(rng.integers(1, 40)), size=idx.size).astype(np.uint64)
+        hists.append(h)
+    for h in hists:
+        assert enec.tune_histogram(h) == oracle.tune_hist(h)[0]
+    for h in hists[:20]:
+        assert enec.tune_histogram(h) == ref.tune_hist([int(v) for v in h])[0]
+
+
+def test_stream_info_parses_oracle_headers(enec, oracle):
+    w = W.gaussian(40000, 0.02, 3)
+    p = oracle.tune(w)
+    rc, s = oracle.compress(w, p, 16384)
+    info = enec.stream_info(s[:64])
+    assert info == dict(rc=0, params=p, n_elems=w.size, block_size=16384, total_bytes=s.size,
+                        dtype=0, status=0)
+    bad = s[:64].copy(); bad[1] = 0
+    assert enec.stream_info(bad)["rc"] == enec.E_FORMAT
+    bad = s[:64].copy(); bad[4] = 2
+    assert enec.stream_info(bad)["rc"] == enec.E_FORMAT
+
+
+def test_null_and_misaligned_arguments_are_rejected_on_the_host(enec):
+    L = enec.lib()
+    p = enec.Params(122, 6, 3, 16)
+    fake = ctypes.c_void_p(0x1000)       # never dereferenced: every call below fails its checks first
+    odd = ctypes.c_void_p(0x1008)
+    assert L.enec_compress(None, 10, 0, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_ARG
+    assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(p), None, 1 << 20, None, fake, 1 << 20, None) == enec.E_ARG
+    assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(p), fake, 1 << 20, None, None, 1 << 20, None) == enec.E_ARG
+    assert L.enec_compress(odd, 10, 0, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_ARG
+    assert L.enec_compress(fake, 10, 1, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_DTYPE
+    assert L.enec_compress(fake, 10, 0, 1000, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_BLOCK
+    assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(p), fake, 10, None, fake, 1 << 20, None) == enec.E_CAPACITY
+    assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 16, None) == enec.E_CAPACITY
+    assert L.enec_compress(fake, 1 << 35, 0, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_ARG
+    for bad in [(122, 0, 0, 16), (122, 9, 3, 16), (122, 6, 7, 16), (122, 6, 3, 32)]:
+        q = enec.Params(*bad)
+        assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(q), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_PARAMS
+    hdr = (ctypes.c_uint8 * 64)()
+    assert L.enec_decompress_with_header(fake, hdr, fake, 10, None) == enec.E_FORMAT
+    assert L.enec_decompress_with_header(None, hdr, fake, 10, None) == enec.E_ARG
+    assert L.enec_decompress_with_header(fake, None, fake, 10, None) == enec.E_ARG
+    assert L.enec_workspace_init(None, 16, None) == enec.E_ARG
+    assert L.enec_workspace_init(fake, 17, None) == enec.E_ARG
+    assert L.enec_copy(fake, odd, 16, None) == enec.E_ARG
+    assert L.enec_tune_histogram(None, ctypes.byref(p)) == enec.E_ARG
+    assert L.enec_stream_info(None, None, None, None, None, None, None) == enec.E_ARG
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2604_03298_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                for needle in ("import oracle", "from oracle", "enec_oracle", "enec_ref", "orc_"):
+                    assert needle not in src, (f, needle)
