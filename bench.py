@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the ENEC codec hot path on one MI355X.
+
+Workload (default): the synthetic 7B-style decoder layer (nine bf16 tensors, 404.8 MB), resident
+in HBM.  One step = compress all nine tensors, then decompress all nine (18 kernel launches, every
+row of the hot path).  Throughput counts uncompressed bytes, as the paper does (Sec. VI-B).
+
+Prints ONE JSON line.  `value` is the whole-step throughput: uncompressed bytes through the codec
+(compress pass + decompress pass) per second.  `compress_GBps` / `decompress_GBps` are the two
+passes alone, from HIP events on the launch stream inside the same timed region.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "decompress & compress GB/s (uncompressed bf16) + compression ratio, 1 MI355X"
+HBM_PEAK_GBPS = 8000.0
+
+# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE, scaled by what the same counters read for enec_copy of known size); filled in from
+# the summaries under profiles/.  None = not measured yet.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2604_03298_amd import enec, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    enec.lib()
+    torch.cuda.set_device(0)
+
+    # ---- inputs: generated on the host, resident in HBM before anything is timed --------
+    if args.workload == "config2":
+        host = list(workloads.config2())
+        wl_name = "config2: 7B-style decoder layer, q/k/v/o 4096x4096, gate/up 4096x11008, down 11008x4096, 2 norm vectors"
+    else:
+        host = [("matrix", workloads.config1())]
+        wl_name = "config1: 1024x4096 N(0,0.02^2)"
+    names = [n for n, _ in host]
+    srcs = [torch.from_numpy(w.view(np.int16)).cuda() for _, w in host]
+    n_el = [w.size for _, w in host]
+    raw_bytes = 2 * sum(n_el)
+    ws = enec.new_workspace(max(n_el))
+    params = [enec.tune(s, ws) for s in srcs]                      # library tuner, not timed
+    outs = [torch.zeros(enec.compress_bound(n), dtype=torch.uint8, device="cuda") for n in n_el]
+    backs = [torch.zeros_like(s) for s in srcs]
+    sizes = torch.zeros(len(srcs), dtype=torch.int64, device="cuda")
+    nt = len(srcs)
+
+    def compress_all(ev=None):
+        for i in range(nt):
+            if ev:
+                ev[0][i].record()
+            rc = enec.compress(srcs[i], params[i], outs[i], ws, out_bytes=sizes[i:i + 1])
+            if ev:
+                ev[1][i].record()
+            assert rc == 0, enec.strerror(rc)
+
+    compress_all()
+    torch.cuda.synchronize()
+    stream_bytes = [int(v) for v in sizes.cpu()]
+    assert all(v > 0 for v in stream_bytes)
+    headers = [outs[i][:64].cpu().numpy().tobytes() for i in range(nt)]
+
+    def decompress_all(ev=None):
+        for i in range(nt):
+            if ev:
+                ev[0][i].record()
+            rc = enec.decompress_with_header(outs[i], headers[i], backs[i])
+            if ev:
+                ev[1][i].record()
+            assert rc == 0, enec.strerror(rc)
+
+    decompress_all()
+    torch.cuda.synchronize()
+    for i in range(nt):
+        assert torch.equal(backs[i], srcs[i]), f"round trip of {names[i]} is not bit-exact"
+
+    def new_events():
+        return [[torch.cuda.Event(enable_timing=True) for _ in range(nt)] for _ in range(2)]
+
+    evc = [new_events() for _ in range(args.steps)]
+    evd = [new_events() for _ in range(args.steps)]
+
+    for _ in range(args.warmup):
+        compress_all()
+        decompress_all()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        compress_all(evc[k])
+        decompress_all(evd[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = 2 * raw_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # per-launch durations from the events recorded inside the timed region
+    dur_c = np.array([[evc[k][0][i].elapsed_time(evc[k][1][i]) for i in range(nt)] for k in range(args.steps)])
+    dur_d = np.array([[evd[k][0][i].elapsed_time(evd[k][1][i]) for i in range(nt)] for k in range(args.steps)])
+    # whole pass: first launch start to last launch end
+    pass_c = np.array([evc[k][0][0].elapsed_time(evc[k][1][nt - 1]) for k in range(args.steps)])
+    pass_d = np.array([evd[k][0][0].elapsed_time(evd[k][1][nt - 1]) for k in range(args.steps)])
+    comp_gbps = raw_bytes / (np.median(pass_c) * 1e-3) / 1e9
+    decomp_gbps = raw_bytes / (np.median(pass_d) * 1e-3) / 1e9
+
+    # ---- roofline of the dominant kernel ------------------------------------------------
+    # algorithmic bytes of one launch = bf16 tensor (2 bytes/element) + its whole stream
+    # (sign/mantissa plane, mask, packed planes, offset table, header), read or written once
+    groups = {}
+    for i in range(nt):
+        m, a = params[i][2], params[i][1] - params[i][2]
+        for kind, dur in (("compress", dur_c), ("decompress", dur_d)):
+            g = groups.setdefault(f"enec::{kind}_kernel<{m},{a}>", dict(ms=0.0, bytes=0, launches=0))
+            g["ms"] += float(dur[:, i].sum())
+            g["bytes"] += (2 * n_el[i] + stream_bytes[i]) * args.steps
+            g["launches"] += args.steps
+    dom = max(groups, key=lambda k: groups[k]["ms"])
+    gd = groups[dom]
+    achieved = gd["bytes"] / (gd["ms"] * 1e-3) / 1e9
+    roofline = {
+        "kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "avg_launch_us": round(gd["ms"] * 1e3 / gd["launches"], 2),
+        "algorithmic_bytes_per_launch": gd["bytes"] // gd["launches"],
+        "traffic": MEASURED_TRAFFIC_BYTES.get(dom),
+    }
+    per_kernel = {k: {"GBps_moved": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1),
+                      "frac_of_hbm_peak": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                      "avg_launch_us": round(v["ms"] * 1e3 / v["launches"], 2), "launches": v["launches"]}
+                  for k, v in sorted(groups.items())}
+
+    # practical ceiling: the library's plain 128-bit copy on a buffer of the layer's size
+    cp_src, cp_dst = srcs[4].view(torch.uint8), backs[4].view(torch.uint8)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        enec.copy(cp_dst, cp_src)
+    e0.record()
+    for _ in range(10):
+        enec.copy(cp_dst, cp_src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * cp_src.numel() * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    # ---- the CPU oracle timed beside it (a baseline, not the target) ----------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import enec_oracle
+        done_bytes, t_cpu, i = 0, 0.0, 0
+        order = sorted(range(nt), key=lambda j: -n_el[j])
+        while t_cpu < 10.0 and i < 3 * nt:
+            j = order[i % nt]
+            w = host[j][1]
+            B = enec_oracle.default_block(w.size)
+            ts = time.perf_counter()
+            rc, s = enec_oracle.compress(w, params[j], B)
+            rc2, d = enec_oracle.decompress(s, w.size)
+            t_cpu += time.perf_counter() - ts
+            assert rc == 0 and rc2 == 0
+            done_bytes += 2 * 2 * w.size
+            i += 1
+        cpu = {"value": round(done_bytes / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"{i} tensors of the same layer, largest first, compress + decompress each, "
+                         f"{done_bytes / 2e6:.0f} MB of bf16, {t_cpu:.1f} s of CPU time"}
+
+    ratio = raw_bytes / sum(stream_bytes)
+    line = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": wl_name, "tensors": nt, "uncompressed_bytes": raw_bytes,
+                   "block_size": 16384, "params": {names[i]: list(params[i]) for i in range(nt)}},
+        "compress_GBps": round(comp_gbps, 1), "decompress_GBps": round(decomp_gbps, 1),
+        "compression_ratio": round(ratio, 4),
+        "compress_ms": round(float(np.median(pass_c)), 4), "decompress_ms": round(float(np.median(pass_d)), 4),
+        "copy_kernel_GBps_moved": round(copy_gbps, 1),
+        "roofline": roofline, "kernels": per_kernel, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
