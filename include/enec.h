@@ -83,7 +83,7 @@ uint32_t enec_default_block_size(size_t n_elems);
 size_t enec_compress_bound(size_t n_elems, int dtype, uint32_t block_size);
 
 /* Size in bytes of the DEVICE workspace enec_compress / enec_tune need for a tensor of n_elems
- * elements (inter-block scan state, ticket counters, histogram).  A workspace sized for a larger
+ * elements (inter-block scan state, completion counters, histogram).  A workspace sized for a larger
  * tensor serves smaller ones.  Returns 0 on invalid block_size. */
 size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size);
 
@@ -118,16 +118,18 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
 
 /* Decompress [Sec. V-A decompression path; Alg. 1 decompression part].
  *   in        DEVICE, a stream written by enec_compress, 16-byte aligned
+ *   in_bytes  size of the buffer behind `in`; ENEC_E_FORMAT if the header's total_bytes exceeds it.
+ *             The kernel never reads past the header's total_bytes.
  *   out       DEVICE, n_elems * 2 bytes, 16-byte aligned
  *   n_elems   must equal the header's n_elems
  * This variant copies the 64-byte header to the host first (one small synchronous copy on
  * `stream`), validates it (ENEC_E_FORMAT / ENEC_E_DTYPE), then enqueues one kernel. */
-int enec_decompress(const void *in, void *out, size_t n_elems, void *stream);
+int enec_decompress(const void *in, size_t in_bytes, void *out, size_t n_elems, void *stream);
 
 /* Same, fully asynchronous: `host_header` is a HOST copy of the stream's first 64 bytes that the
  * caller already holds (kept from compression, or read from a file).  The kernel compares it with
  * the header in device memory and writes nothing if they differ. */
-int enec_decompress_with_header(const void *in, const void *host_header, void *out,
+int enec_decompress_with_header(const void *in, size_t in_bytes, const void *host_header, void *out,
                                 size_t n_elems, void *stream);
 
 /* Parameter tuning [Sec. V-E phases 1-3]: exponent histogram on the device (one read of the

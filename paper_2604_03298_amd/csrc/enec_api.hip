@@ -9,7 +9,12 @@ namespace {
 
 using namespace enec;
 
-constexpr size_t WS_TICKET = 0, WS_DONE = 128, WS_HIST = 256, WS_STATE = 256 + 256 * 8;
+// workspace: [0] finished-group counter | [256, 2304) histogram | group words | per-group
+// finished-block counters | block words (the last three sized by the call's block count)
+constexpr size_t WS_DONE = 0, WS_HIST = 256, WS_STATE = 256 + 256 * 8;
+inline size_t ws_groups(size_t nb) { return (nb + 63) / 64; }
+inline size_t ws_gdone_off(size_t nb) { return WS_STATE + 8 * ws_groups(nb); }
+inline size_t ws_block_off(size_t nb) { return (ws_gdone_off(nb) + 4 * ws_groups(nb) + 7) & ~(size_t)7; }
 constexpr size_t MAX_ELEMS = (size_t)1 << 34;      // keeps every offset below 2^36 bytes
 
 inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
@@ -124,7 +129,8 @@ size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size)
     const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
     if (!block_ok(B)) return 0;
     size_t nb = num_blocks(n_elems, B);
-    return (WS_STATE + 8 * (nb ? nb : 1) + 255) & ~(size_t)255;
+    if (nb == 0) nb = 1;
+    return (ws_block_off(nb) + 8 * nb + 255) & ~(size_t)255;
 }
 
 int enec_workspace_init(void *workspace, size_t bytes, void *stream)
@@ -230,13 +236,14 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
     a.out = static_cast<uint8_t *>(out);
     a.n_elems = n_elems;
     a.payload_base = payload_base(n_elems, B);
-    a.ws_state = reinterpret_cast<uint64_t *>(ws + WS_STATE);
-    a.ws_ticket = reinterpret_cast<uint32_t *>(ws + WS_TICKET);
+    a.nb = (uint32_t)num_blocks(n_elems, B);
+    a.ws_group = reinterpret_cast<uint64_t *>(ws + WS_STATE);
+    a.ws_gdone = reinterpret_cast<uint32_t *>(ws + ws_gdone_off(a.nb));
+    a.ws_block = reinterpret_cast<uint64_t *>(ws + ws_block_off(a.nb));
     a.ws_done = reinterpret_cast<uint32_t *>(ws + WS_DONE);
     a.out_bytes = out_bytes;
     a.B = B;
     a.logB = ilog2(B);
-    a.nb = (uint32_t)num_blocks(n_elems, B);
     a.b = prm.b;
     const unsigned c = prm.b + (1u << (prm.n - 1));
     const bool plain = c <= 255 && c >= (1u << prm.n) - 1u;
@@ -255,8 +262,8 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 
-int enec_decompress_with_header(const void *in, const void *host_header, void *out, size_t n_elems,
-                                void *stream)
+int enec_decompress_with_header(const void *in, size_t in_bytes, const void *host_header, void *out,
+                                size_t n_elems, void *stream)
 {
     if (!in || !host_header || (!out && n_elems) || !aligned16(in) || !aligned16(out)) return ENEC_E_ARG;
     Header h;
@@ -265,7 +272,7 @@ int enec_decompress_with_header(const void *in, const void *host_header, void *o
     if (h.dtype != ENEC_BF16) return ENEC_E_DTYPE;
     if (h.status != ENEC_OK || h.n_elems != n_elems || !block_ok(h.B) || n_elems > MAX_ELEMS ||
         h.nb != num_blocks(n_elems, h.B) || h.prm.n < 1 || h.prm.n > 8 || h.prm.m > h.prm.n ||
-        h.total < payload_base(n_elems, h.B))
+        h.total < payload_base(n_elems, h.B) || h.total > in_bytes)
         return ENEC_E_FORMAT;
     if (h.nb == 0) return ENEC_OK;
 
@@ -274,6 +281,7 @@ int enec_decompress_with_header(const void *in, const void *host_header, void *o
     a.out = static_cast<uint16_t *>(out);
     a.n_elems = n_elems;
     a.payload_base = payload_base(n_elems, h.B);
+    a.payload_bytes = h.total - a.payload_base;
     a.B = h.B;
     a.logB = ilog2(h.B);
     a.nb = h.nb;
@@ -290,9 +298,10 @@ int enec_decompress_with_header(const void *in, const void *host_header, void *o
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 
-int enec_decompress(const void *in, void *out, size_t n_elems, void *stream)
+int enec_decompress(const void *in, size_t in_bytes, void *out, size_t n_elems, void *stream)
 {
     if (!in || !aligned16(in)) return ENEC_E_ARG;
+    if (in_bytes < ENEC_HEADER_BYTES) return ENEC_E_FORMAT;
     uint8_t hdr[ENEC_HEADER_BYTES];
     hipStream_t s = (hipStream_t)stream;
     if (hipMemcpyAsync(hdr, in, sizeof hdr, hipMemcpyDeviceToHost, s) != hipSuccess ||
@@ -300,7 +309,7 @@ int enec_decompress(const void *in, void *out, size_t n_elems, void *stream)
         (void)hipGetLastError();
         return ENEC_E_HIP;
     }
-    return enec_decompress_with_header(in, hdr, out, n_elems, stream);
+    return enec_decompress_with_header(in, in_bytes, hdr, out, n_elems, stream);
 }
 
 int enec_stream_info(const void *host_header, enec_params *params, uint64_t *n_elems,

@@ -142,15 +142,20 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
     return v;
 }
 
-// Scan-state word of one data block (single 64-bit word, so no fences are needed):
-//   bits 63:62  0 = not published, 1 = this block's size only, 2 = inclusive prefix
-//   bit  61     a range error was seen in the blocks covered by the word
-//   bits 39:0   size / prefix in units of 16 bytes
-constexpr uint64_t ST_AGGREGATE = 1ull << 62;
-constexpr uint64_t ST_INCLUSIVE = 2ull << 62;
-constexpr uint64_t ST_ERR = 1ull << 61;
+// Inter-block scan state (Fig. 4: prefix sums of per-block compressed sizes).  Every word is
+// self-contained, so relaxed device-scope loads and stores are enough and no fence is needed.
+//   block word  (one per data block):     bit 63 valid | bit 62 range error | bits 39:0 size / 16
+//   group word  (one per 64 data blocks): bits 55:48 blocks published | bits 47:40 blocks with a
+//                                         range error | bits 39:0 sum of their sizes / 16
+// Block k = blockIdx.x publishes its size as soon as it is known, then adds up the group words of
+// all earlier groups and the block words of the earlier blocks of its own group: at most
+// nb/64 + 63 words, read in parallel by the whole workgroup, whatever the tensor size.
+constexpr uint64_t ST_VALID = 1ull << 63;
+constexpr uint64_t ST_ERR = 1ull << 62;
 constexpr uint64_t ST_VALUE = (1ull << 40) - 1;
-constexpr uint32_t SPIN_LIMIT = 1u << 22;
+constexpr uint64_t GS_ONE = 1ull << 48;
+constexpr uint64_t GS_ERR = 1ull << 40;
+constexpr uint32_t SPIN_LIMIT = 1u << 21;
 
 __device__ __forceinline__ uint64_t ld_state(const uint64_t *p)
 {
@@ -166,9 +171,10 @@ struct CompressArgs {
     uint8_t *out;
     uint64_t n_elems;
     uint64_t payload_base;
-    uint64_t *ws_state;     // nb scan-state words
-    uint32_t *ws_ticket;
-    uint32_t *ws_done;
+    uint64_t *ws_block;     // nb block words
+    uint64_t *ws_group;     // ceil(nb / 64) group words
+    uint32_t *ws_gdone;     // per group: blocks that have finished reading scan state
+    uint32_t *ws_done;      // groups that have finished
     uint64_t *out_bytes;    // device-accessible or null
     uint32_t B, logB, nb;
     uint32_t b, mode;       // mode 0: window clear of 0 and 255; 1: n = 8; 2: window touches an end
@@ -179,6 +185,7 @@ struct DecompressArgs {
     uint16_t *out;
     uint64_t n_elems;
     uint64_t payload_base;
+    uint64_t payload_bytes; // total_bytes - payload_base
     uint32_t B, logB, nb;
     uint32_t b, mode;       // mode 0: plain byte subtract is exact; 1: borrow-safe subtract
     uint32_t hdr[10];       // first 40 bytes of the expected header
@@ -201,25 +208,21 @@ __global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
 
     extern __shared__ __align__(16) uint8_t smem[];
     __shared__ __align__(16) uint32_t s_maskw[64];
-    __shared__ uint32_t s_pre[64];
-    __shared__ uint32_t s_u32[8];   // 0 ticket, 1 count of masked groups, 2 error, 3/4 offset, 5 last, 6 prefix error
+    __shared__ unsigned long long s_excl;      // sum of the sizes of all earlier blocks, / 16
+    __shared__ uint32_t s_flags;               // bit 0 range error in this block, bit 1 in an earlier
+                                               // block, bit 2 the scan gave up waiting
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const uint32_t B = p.B, logC = p.logB - 3u, C = 1u << logC;
+    const uint32_t B = p.B, logC = p.logB - 3u;
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
+    const uint32_t k = blockIdx.x;
     uint8_t *lds_low = smem;
     uint8_t *lds_high = smem + (((size_t)M * B) >> 3);
-
-    if (tid == 0) {
-        s_u32[0] = atomicAdd(p.ws_ticket, 1u);
-        s_u32[2] = 0;
-    }
-    __syncthreads();
-    const uint32_t k = s_u32[0];
-    if (k >= p.nb) return;              // workspace was not zeroed: refuse to touch memory
     const uint64_t blk0 = (uint64_t)k << p.logB;
     const uint32_t padw = (p.b << 7) * 0x00010001u;   // a pad element has exponent b: y = 0, sm = 0
+
+    if (tid == 0) { s_excl = 0; s_flags = 0; }
 
     // ---- a1: 128-bit loads of the 8 rows ---------------------------------------
     uint4 raw[8];
@@ -302,8 +305,10 @@ __global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
         mw[t] = compact_even_bits(__builtin_amdgcn_ballot_w64(gor != 0));
     }
     if (N < 8 && p.mode == 0) bad = (err_acc & ~NMASK) != 0;
-    if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(&s_u32[2], 1u);
+    const bool wave_bad = __builtin_amdgcn_ballot_w64(bad) != 0;
 
+    __syncthreads();                       // s_excl / s_flags initialised
+    if (wave_bad && lane == 0) atomicOr(&s_flags, 1u);
     if (lane == 0 && 64u * wave < nact) {
         if (logC >= 9) {
 #pragma unroll
@@ -321,24 +326,25 @@ __global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
     }
     __syncthreads();
 
-    // ---- a5 (positions): exclusive popcount prefix over the block's mask words ----
+    // ---- a5 (positions): exclusive popcount prefix over the block's mask words; every wave
+    // computes it for itself (a wave scan of at most 64 words) ---------------------------
     const uint32_t nwords = B >> 9;
-    if (wave == 0) {
-        const uint32_t wv = lane < nwords ? s_maskw[lane] : 0u;
-        const uint32_t pc = __popc(wv);
-        const uint32_t incl = wave_incl_scan(pc, lane);
-        s_pre[lane] = incl - pc;
-        if (lane == 63) s_u32[1] = incl;
-    }
-    __syncthreads();
-    const uint32_t cnt = s_u32[1];
-    const uint64_t err = s_u32[2] ? ST_ERR : 0ull;
+    const uint32_t my_word = lane < nwords ? s_maskw[lane] : 0u;
+    const uint32_t my_pc = __popc(my_word);
+    const uint32_t my_incl = wave_incl_scan(my_pc, lane);
+    const uint32_t my_excl = my_incl - my_pc;
+    const uint32_t cnt = __shfl(my_incl, 63, 64);
+    const bool own_err = (s_flags & 1u) != 0;
     const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
     const uint32_t S = (fixed + 2u * A * cnt + 15u) & ~15u;
 
-    // ---- a6: publish this block's size at once, so successors can look back -------
-    if (tid == 0)
-        st_state(p.ws_state + k, (k == 0 ? ST_INCLUSIVE : ST_AGGREGATE) | err | (uint64_t)(S >> 4));
+    // ---- a6: publish this block's size at once ---------------------------------------
+    const uint32_t gk = k >> 6, rk = k & 63u;
+    if (tid == 0) {
+        st_state(p.ws_block + k, ST_VALID | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
+        __hip_atomic_fetch_add(p.ws_group + gk, GS_ONE | (own_err ? GS_ERR : 0ull) | (uint64_t)(S >> 4),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 
     // ---- a5: one record per masked group ------------------------------------------
     if (A > 0) {
@@ -359,10 +365,11 @@ __global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
             F[2] = par ? own0 : rcv0;
             F[3] = par ? own1 : rcv1;
             const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
-            const uint32_t wv = s_maskw[g >> 5];
+            const uint32_t wv = __shfl(my_word, g >> 5, 64);
+            const uint32_t pre = __shfl(my_excl, g >> 5, 64);
             const uint32_t bit = (wv >> (g & 31u)) & 1u;
             if (active && bit) {
-                const uint32_t rank = s_pre[g >> 5] + __popc(wv & ((1u << (g & 31u)) - 1u));
+                const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
                 // the group's 16 values are 2 columns of 8 rows: row r = bytes (2r, 2r+1)
                 uint32_t P[AP];
 #pragma unroll
@@ -385,45 +392,38 @@ __global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
         }
     }
 
-    // ---- a6: decoupled look-back over the predecessors' scan-state words ----------
-    if (wave == 0) {
-        uint64_t excl = 0, err_all = err;
-        if (k > 0) {
-            int64_t base = (int64_t)k - 1;
-            bool done = false;
+    // ---- a6: sum of the sizes of all earlier blocks ------------------------------------
+    {
+        uint64_t part = 0;
+        uint32_t flags = 0;
+        for (uint32_t e = tid; e < gk + rk; e += blockDim.x) {
             uint32_t spins = 0;
-            while (!done) {
-                const int64_t idx = base - (int64_t)lane;
-                uint64_t s = idx >= 0 ? ld_state(p.ws_state + idx) : ST_INCLUSIVE;
-                const uint64_t incl = __builtin_amdgcn_ballot_w64((s >> 62) == 2);
-                const uint64_t notready = __builtin_amdgcn_ballot_w64((s >> 62) == 0);
-                const uint64_t need = incl ? (((incl & (~incl + 1)) << 1) - 1) : ~0ull;
-                if (notready & need) {
-                    if (++spins > SPIN_LIMIT) { err_all |= ST_ERR; break; }   // never hang
-                    __builtin_amdgcn_s_sleep(1);
-                    continue;
+            uint64_t v;
+            if (e < gk) {
+                while ((((v = ld_state(p.ws_group + e)) >> 48) & 0xFFu) != 64u) {
+                    if (++spins > SPIN_LIMIT) { flags |= 4u; break; }      // never hang
+                    __builtin_amdgcn_s_sleep(2);
                 }
-                const bool take = (need >> lane) & 1ull;
-                excl += wave_sum(take ? (s & ST_VALUE) : 0ull);
-                if (__builtin_amdgcn_ballot_w64(take && (s & ST_ERR))) err_all |= ST_ERR;
-                if (incl) done = true;
-                else base -= 64;
+                if ((v >> 40) & 0xFFu) flags |= 2u;
+            } else {
+                const uint64_t *q = p.ws_block + ((uint64_t)gk << 6) + (e - gk);
+                while (!((v = ld_state(q)) & ST_VALID)) {
+                    if (++spins > SPIN_LIMIT) { flags |= 4u; break; }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+                if (v & ST_ERR) flags |= 2u;
             }
-            if (lane == 0)
-                st_state(p.ws_state + k, ST_INCLUSIVE | err_all | ((excl + (S >> 4)) & ST_VALUE));
+            part += v & ST_VALUE;
         }
-        if (lane == 0) {
-            const uint64_t off = excl << 4;
-            s_u32[3] = (uint32_t)off;
-            s_u32[4] = (uint32_t)(off >> 32);
-            s_u32[6] = err_all ? 1u : 0u;
-            s_u32[5] = (atomicAdd(p.ws_done, 1u) == p.nb - 1u) ? 1u : 0u;
-        }
+        part = wave_sum(part);
+        const uint64_t any = __builtin_amdgcn_ballot_w64(flags != 0);
+        if (any) atomicOr(&s_flags, flags);
+        if (lane == 0 && part) atomicAdd(&s_excl, (unsigned long long)part);
     }
     __syncthreads();
 
     // ---- a7: stores -----------------------------------------------------------------
-    const uint64_t off = ((uint64_t)s_u32[4] << 32) | s_u32[3];
+    const uint64_t off = (uint64_t)s_excl << 4;
     uint8_t *dst = p.out + p.payload_base + off;
     if (active) {
 #pragma unroll
@@ -466,8 +466,9 @@ __global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
         table[k] = off;
         if (k == p.nb - 1u) {
             const uint64_t end = off + S;
-            const bool fail = s_u32[6] != 0;
-            const uint64_t total = fail ? 0ull : p.payload_base + end;
+            const uint32_t fl = s_flags;
+            const uint32_t status = (fl & 4u) ? 8u : ((fl & 3u) ? 6u : 0u);
+            const uint64_t total = status ? 0ull : p.payload_base + end;
             table[p.nb] = end;
             if (((uint64_t)(p.nb + 1u) & 1ull)) table[p.nb + 1u] = 0;   // pad up to the payload base
             uint32_t *h = reinterpret_cast<uint32_t *>(p.out);
@@ -476,17 +477,36 @@ __global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
             h[2] = (uint32_t)p.n_elems; h[3] = (uint32_t)(p.n_elems >> 32);
             h[4] = B; h[5] = p.nb;
             h[6] = p.b | ((uint32_t)N << 8) | ((uint32_t)M << 16) | (8u << 24);
-            h[7] = fail ? 6u : 0u;
+            h[7] = status;
             h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
 #pragma unroll
             for (int i = 10; i < 16; ++i) h[i] = 0;
             if (p.out_bytes) *p.out_bytes = total;
         }
     }
-    // the workgroup that finished last hands the workspace back zeroed
-    if (s_u32[5]) {
-        for (uint32_t i = tid; i < p.nb; i += blockDim.x) p.ws_state[i] = 0;
-        if (tid == 0) { *p.ws_ticket = 0; *p.ws_done = 0; }
+
+    // ---- hand the workspace back zeroed: the last block of each group to finish reading
+    // clears the group's block words, the last group to finish clears the group words ----
+    if (wave == 0) {
+        uint32_t last = 0;
+        if (lane == 0) {
+            const uint32_t ng = (p.nb + 63u) >> 6;
+            const uint32_t gsize = (gk == ng - 1u) ? p.nb - (gk << 6) : 64u;
+            if (atomicAdd(p.ws_gdone + gk, 1u) == gsize - 1u) {
+                last = 1;
+                if (atomicAdd(p.ws_done, 1u) == ng - 1u) last = 2;
+            }
+        }
+        last = __shfl(last, 0, 64);
+        if (last) {
+            const uint32_t idx = (gk << 6) + lane;
+            if (idx < p.nb) p.ws_block[idx] = 0;
+        }
+        if (last == 2) {
+            const uint32_t ng = (p.nb + 63u) >> 6;
+            for (uint32_t i = lane; i < ng; i += 64) { p.ws_group[i] = 0; p.ws_gdone[i] = 0; }
+            if (lane == 0) *p.ws_done = 0;
+        }
     }
 }
 
@@ -531,7 +551,12 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
     uint8_t *lds_low = smem;
     uint8_t *lds_high = smem + (((size_t)M * B) >> 3);
 
-    // d1: the header in memory must be the one the launch was configured from
+    // d1: offset lookup.  The header in memory must be the one the launch was configured from
+    // (the host has checked that header and table lie inside the buffer), and the block's
+    // payload must lie inside the stream: otherwise touch nothing.
+    const uint64_t *table = reinterpret_cast<const uint64_t *>(p.in + 64);
+    const uint64_t off = table[k];
+    const uint64_t size = table[k + 1] - off;
     {
         const uint32_t *h = reinterpret_cast<const uint32_t *>(p.in);
         bool same = true;
@@ -539,12 +564,11 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
         for (int i = 0; i < 10; ++i) same &= (h[i] == p.hdr[i]);
         if (!same) return;
     }
-    const uint64_t *table = reinterpret_cast<const uint64_t *>(p.in + 64);
-    const uint64_t off = table[k];
-    const uint64_t size = table[k + 1] - off;
     const uint8_t *src = p.in + p.payload_base + off;
     const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
-    if (size < fixed || size > fixed + 2u * A * (B >> 4) + 15u) return;      // corrupt table: touch nothing
+    if (size < fixed || size > fixed + 2u * A * (B >> 4) + 15u || off > p.payload_bytes ||
+        size > p.payload_bytes - off)
+        return;
 
     // sign/mantissa bytes: 64-bit loads, issued first
     uint2 smv[8];

@@ -67,9 +67,9 @@ def lib():
         L.enec_compress.restype = C.c_int
         L.enec_compress.argtypes = [vp, sz, C.c_int, u32, C.POINTER(Params), vp, sz, vp, vp, sz, vp]
         L.enec_decompress.restype = C.c_int
-        L.enec_decompress.argtypes = [vp, vp, sz, vp]
+        L.enec_decompress.argtypes = [vp, sz, vp, sz, vp]
         L.enec_decompress_with_header.restype = C.c_int
-        L.enec_decompress_with_header.argtypes = [vp, vp, vp, sz, vp]
+        L.enec_decompress_with_header.argtypes = [vp, sz, vp, vp, sz, vp]
         L.enec_tune.restype = C.c_int
         L.enec_tune.argtypes = [vp, sz, C.c_int, C.POINTER(Params), u64p, vp, sz, vp]
         L.enec_tune_histogram.restype = C.c_int
@@ -172,16 +172,17 @@ def compress(src, params, out, workspace, block_size: int = 0, out_bytes=None, s
 
 def decompress(stream_buf, out, n_elems: int | None = None, stream=None) -> int:
     n = out.numel() if n_elems is None else n_elems
-    return int(lib().enec_decompress(C.c_void_p(stream_buf.data_ptr()), C.c_void_p(out.data_ptr()), n,
-                                     _stream_handle(stream)))
+    return int(lib().enec_decompress(C.c_void_p(stream_buf.data_ptr()),
+                                     stream_buf.numel() * stream_buf.element_size(),
+                                     C.c_void_p(out.data_ptr()), n, _stream_handle(stream)))
 
 
 def decompress_with_header(stream_buf, host_header, out, n_elems: int | None = None, stream=None) -> int:
     n = out.numel() if n_elems is None else n_elems
     hdr = np.frombuffer(bytes(host_header[:HEADER_BYTES]), dtype=np.uint8).copy()
     return int(lib().enec_decompress_with_header(
-        C.c_void_p(stream_buf.data_ptr()), hdr.ctypes.data, C.c_void_p(out.data_ptr()), n,
-        _stream_handle(stream)))
+        C.c_void_p(stream_buf.data_ptr()), stream_buf.numel() * stream_buf.element_size(),
+        hdr.ctypes.data, C.c_void_p(out.data_ptr()), n, _stream_handle(stream)))
 
 
 def tune(src, workspace, stream=None, want_histogram: bool = False):

@@ -44,6 +44,7 @@ def test_bounds_and_block_sizes_match_oracle(enec, oracle):
             assert enec.compress_bound(n, block_size=B) == oracle.compress_bound(n, B)
         assert enec.compress_bound(n) == oracle.compress_bound(n, oracle.default_block(n))
         assert enec.workspace_bytes(n) >= 2304 + 8 * max(1, oracle.num_blocks(n, oracle.default_block(n)))
+        assert enec.workspace_bytes(n) % 256 == 0
     assert enec.compress_bound(100, block_size=3000) == 0
     assert enec.compress_bound(100, dtype=1) == 0
     assert enec.workspace_bytes(100, block_size=1000) == 0
@@ -98,9 +99,10 @@ def test_null_and_misaligned_arguments_are_rejected_on_the_host(enec):
         q = enec.Params(*bad)
         assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(q), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_PARAMS
     hdr = (ctypes.c_uint8 * 64)()
-    assert L.enec_decompress_with_header(fake, hdr, fake, 10, None) == enec.E_FORMAT
-    assert L.enec_decompress_with_header(None, hdr, fake, 10, None) == enec.E_ARG
-    assert L.enec_decompress_with_header(fake, None, fake, 10, None) == enec.E_ARG
+    assert L.enec_decompress_with_header(fake, 1 << 20, hdr, fake, 10, None) == enec.E_FORMAT
+    assert L.enec_decompress_with_header(None, 1 << 20, hdr, fake, 10, None) == enec.E_ARG
+    assert L.enec_decompress_with_header(fake, 1 << 20, None, fake, 10, None) == enec.E_ARG
+    assert L.enec_decompress(fake, 10, fake, 10, None) == enec.E_FORMAT
     assert L.enec_workspace_init(None, 16, None) == enec.E_ARG
     assert L.enec_workspace_init(fake, 17, None) == enec.E_ARG
     assert L.enec_copy(fake, odd, 16, None) == enec.E_ARG
