@@ -3,18 +3,19 @@
 #include "enec.h"
 #include "enec_device.hpp"
 
+#include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 namespace {
 
 using namespace enec;
 
-// workspace: [0] finished-group counter | [256, 2304) histogram | group words | per-group
-// finished-block counters | block words (the last three sized by the call's block count)
-constexpr size_t WS_DONE = 0, WS_HIST = 256, WS_STATE = 256 + 256 * 8;
+// workspace: [0, 1024) control records of the block classes | [1024, 3072) histogram |
+// group words | block words (the last two sized by the call's block count)
+constexpr size_t WS_CTL = 0, WS_HIST = 1024, WS_STATE = WS_HIST + 256 * 8;
 inline size_t ws_groups(size_t nb) { return (nb + 63) / 64; }
-inline size_t ws_gdone_off(size_t nb) { return WS_STATE + 8 * ws_groups(nb); }
-inline size_t ws_block_off(size_t nb) { return (ws_gdone_off(nb) + 4 * ws_groups(nb) + 7) & ~(size_t)7; }
+inline size_t ws_block_off(size_t nb) { return WS_STATE + 8 * ws_groups(nb); }
 constexpr size_t MAX_ELEMS = (size_t)1 << 34;      // keeps every offset below 2^36 bytes
 
 inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
@@ -60,6 +61,36 @@ bool device_accessible(const void *p)
     }
     return attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeHost ||
            attr.type == hipMemoryTypeManaged;
+}
+
+// Number of workgroups of `fn` the current device holds at once (cached per kernel and shape).
+// The environment variable named by `env_cap` caps the per-CU figure (a tuning aid).
+unsigned resident_workgroups(const void *fn, unsigned threads, size_t lds, const char *env_cap)
+{
+    struct Entry { const void *fn; unsigned threads; size_t lds; int dev; unsigned value; };
+    static Entry cache[256];
+    static int used = 0;
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < used; ++i)
+        if (cache[i].fn == fn && cache[i].threads == threads && cache[i].lds == lds && cache[i].dev == dev)
+            return cache[i].value;
+    if (lds > 65536 &&
+        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return 0;
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, (int)threads, lds) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || per_cu < 1 || cus < 1)
+        return 0;
+    if (const char *e = std::getenv(env_cap)) {
+        const int cap = std::atoi(e);
+        if (cap >= 1 && cap < per_cu) per_cu = cap;
+    }
+    const unsigned value = (unsigned)per_cu * (unsigned)cus;
+    if (used < 256) cache[used++] = Entry{fn, threads, lds, dev, value};
+    return value;
 }
 
 unsigned bit_length(unsigned v) { unsigned r = 0; for (; v; v >>= 1) ++r; return r; }
@@ -238,9 +269,8 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
     a.payload_base = payload_base(n_elems, B);
     a.nb = (uint32_t)num_blocks(n_elems, B);
     a.ws_group = reinterpret_cast<uint64_t *>(ws + WS_STATE);
-    a.ws_gdone = reinterpret_cast<uint32_t *>(ws + ws_gdone_off(a.nb));
     a.ws_block = reinterpret_cast<uint64_t *>(ws + ws_block_off(a.nb));
-    a.ws_done = reinterpret_cast<uint32_t *>(ws + WS_DONE);
+    a.ws_ctl = reinterpret_cast<uint32_t *>(ws + WS_CTL);
     a.out_bytes = out_bytes;
     a.B = B;
     a.logB = ilog2(B);
@@ -256,8 +286,13 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
         CompressFn fn = pick_compress(prm.m, prm.n - prm.m);
         if (!fn) return ENEC_E_PARAMS;
         const unsigned threads = B / 64 < 64 ? 64 : B / 64;
-        const size_t lds = (size_t)prm.n * B / 8;
-        hipLaunchKernelGGL(fn, dim3(a.nb), dim3(threads), lds, s, a);
+        const size_t lds = 2 * ((size_t)B / 128 + (size_t)prm.n * B / 8);    // two images of the packed part
+        const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_COMPRESS_WGS_PER_CU");
+        if (resident == 0) return ENEC_E_HIP;
+        const unsigned grid = a.nb < resident ? a.nb : resident;
+        a.ncls = grid < 8 ? grid : 8;
+        a.lookahead = a.nb >= 2 * grid ? 1u : 0u;
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
     }
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }

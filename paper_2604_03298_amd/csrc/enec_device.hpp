@@ -15,6 +15,18 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Phase-timestamp hook for bench experiments; expands to nothing in the library.
+// Three waves per SIMD for the compression kernel: the register budget (168) that lets three
+// workgroups of 256 threads share a CU.
+#ifndef ENEC_COMPRESS_OCCUPANCY
+#define ENEC_COMPRESS_OCCUPANCY __attribute__((amdgpu_waves_per_eu(3, 3)))
+#endif
+#ifndef ENEC_TP
+#define ENEC_TP_DECL
+#define ENEC_TP(point)
+#define ENEC_TP_FLUSH
+#endif
+
 namespace enec {
 
 // ---------------------------------------------------------------------------------
@@ -142,20 +154,44 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
     return v;
 }
 
-// Inter-block scan state (Fig. 4: prefix sums of per-block compressed sizes).  Every word is
-// self-contained, so relaxed device-scope loads and stores are enough and no fence is needed.
-//   block word  (one per data block):     bit 63 valid | bit 62 range error | bits 39:0 size / 16
-//   group word  (one per 64 data blocks): bits 55:48 blocks published | bits 47:40 blocks with a
-//                                         range error | bits 39:0 sum of their sizes / 16
-// Block k = blockIdx.x publishes its size as soon as it is known, then adds up the group words of
-// all earlier groups and the block words of the earlier blocks of its own group: at most
-// nb/64 + 63 words, read in parallel by the whole workgroup, whatever the tensor size.
-constexpr uint64_t ST_VALID = 1ull << 63;
-constexpr uint64_t ST_ERR = 1ull << 62;
-constexpr uint64_t ST_VALUE = (1ull << 40) - 1;
-constexpr uint64_t GS_ONE = 1ull << 48;
-constexpr uint64_t GS_ERR = 1ull << 40;
-constexpr uint32_t SPIN_LIMIT = 1u << 21;
+// ---------------------------------------------------------------------------------
+// Inter-block scan (Fig. 4: prefix sums of per-block compressed sizes) and work distribution.
+//
+// Scan state.  Every word is self-contained: [63:24] tag of the call that wrote it, [23] range
+// error, [22:0] a size in units of 16 bytes.  Relaxed device-scope loads and stores are enough,
+// no fence is needed, and nothing has to be cleared between calls: a word whose tag is not the
+// current call's tag is simply "not published yet".
+//   block word k   size of data block k, stored as soon as the block's mask is known
+//   group word g   sum of the sizes of blocks 64g .. 64g+63, stored by the workgroup that owns
+//                  block 64g+63 once the other 63 block words of the group are there
+// The start of block k is the sum of the group words below k/64 plus the block words of the
+// earlier blocks of its own group: few words, read by one wave.
+//
+// Work distribution.  The grid is persistent (at most as many workgroups as the device holds at
+// once).  Data blocks are dealt into `ncls` classes, block k belongs to class k mod ncls, and
+// class c is served only by the workgroups with blockIdx mod ncls == c, which draw its blocks
+// in increasing order from the class's ticket counter.  A workgroup therefore holds blocks in
+// increasing order and publishes a block's size before it waits for anything, so the lowest
+// unpublished block is always held by (or next in line for) a workgroup that is not waiting for
+// it: the scan cannot deadlock.  Eight classes keep the rate of atomics on one address (about
+// 12 ns each on MI355X) far below the block rate.
+//
+// Pipelining.  A workgroup stores block i-1 only while it is working on block i: by then the
+// sizes of all earlier blocks were published an iteration ago, so the reads of the scan state
+// succeed at the first attempt and nobody spins on hot cache lines in the steady state.
+//
+// Control record of class c (WS_STRIDE words apart): [0] ticket counter, never reset; [1] value
+// of the counter when the current call started; [2..3] tag of the last finished call.  A class
+// with L blocks and W workgroups sees exactly L + W draws per call (every workgroup draws until
+// its first draw beyond L), so the workgroup that receives draw number L + W - 1 knows that
+// nobody will touch the record again in this call and writes the next call's base and tag.
+// ---------------------------------------------------------------------------------
+constexpr uint64_t ST_ERR = 1ull << 23;
+constexpr uint64_t ST_VALUE = (1ull << 23) - 1;
+constexpr uint32_t SPIN_LIMIT = 1u << 20;
+constexpr uint32_t NO_BLOCK = 0xFFFFFFFFu;
+constexpr uint32_t WS_STRIDE = 32;            // control records sit 128 bytes apart
+constexpr uint32_t WS_CLASSES = 8;
 
 __device__ __forceinline__ uint64_t ld_state(const uint64_t *p)
 {
@@ -165,6 +201,12 @@ __device__ __forceinline__ void st_state(uint64_t *p, uint64_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void spin_pause(uint32_t spins)
+{
+    if (spins < 4) __builtin_amdgcn_s_sleep(4);
+    else if (spins < 16) __builtin_amdgcn_s_sleep(16);
+    else __builtin_amdgcn_s_sleep(64);
+}
 
 struct CompressArgs {
     const uint16_t *in;
@@ -173,11 +215,12 @@ struct CompressArgs {
     uint64_t payload_base;
     uint64_t *ws_block;     // nb block words
     uint64_t *ws_group;     // ceil(nb / 64) group words
-    uint32_t *ws_gdone;     // per group: blocks that have finished reading scan state
-    uint32_t *ws_done;      // groups that have finished
+    uint32_t *ws_ctl;       // WS_CLASSES control records
     uint64_t *out_bytes;    // device-accessible or null
     uint32_t B, logB, nb;
     uint32_t b, mode;       // mode 0: window clear of 0 and 255; 1: n = 8; 2: window touches an end
+    uint32_t ncls;          // number of block classes = min(8, gridDim.x)
+    uint32_t lookahead;     // draw the next ticket while working on the current block
 };
 
 struct DecompressArgs {
@@ -191,12 +234,41 @@ struct DecompressArgs {
     uint32_t hdr[10];       // first 40 bytes of the expected header
 };
 
+// a1: 128-bit loads of the 8 rows of data block k (pad elements beyond the tensor's end)
+__device__ __forceinline__ void load_block_rows(const CompressArgs &p, uint32_t k, uint32_t tid, bool active,
+                                                uint32_t logC, uint32_t padw, uint4 (&raw)[8])
+{
+    const uint64_t blk0 = (uint64_t)k << p.logB;
+    if (blk0 + p.B <= p.n_elems) {               // whole block inside the tensor: no per-row tests
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            raw[t] = active ? *reinterpret_cast<const uint4 *>(p.in + blk0 + ((uint64_t)t << logC) + 8u * tid)
+                            : make_uint4(padw, padw, padw, padw);
+        return;
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
+        uint32_t d[4] = {padw, padw, padw, padw};
+        if (active && e0 < p.n_elems) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (e0 + i < p.n_elems) {
+                    const uint32_t v = p.in[e0 + i];
+                    d[i >> 1] = (i & 1) ? ((d[i >> 1] & 0x0000FFFFu) | (v << 16))
+                                        : ((d[i >> 1] & 0xFFFF0000u) | v);
+                }
+        }
+        raw[t] = make_uint4(d[0], d[1], d[2], d[3]);
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // compression: split, transform, group test, packing, inter-block scan, store
 // (Sec. V-A compression path; Sec. V-B; Sec. V-C; Fig. 4)
 // ---------------------------------------------------------------------------------
 template <int M, int A>
-__global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
+__global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(const CompressArgs p)
 {
     constexpr int N = M + A;
     constexpr uint32_t NMASK = ((1u << N) - 1u) * 0x01010101u;
@@ -206,307 +278,378 @@ __global__ void __launch_bounds__(512) compress_kernel(const CompressArgs p)
     constexpr int MP = M > 0 ? M : 1;
     constexpr int AP = A > 0 ? A : 1;
 
+    // two LDS images of the packed part of a payload: mask | low plane (as normalized bytes,
+    // interleaved on the way out) | high records
     extern __shared__ __align__(16) uint8_t smem[];
-    __shared__ __align__(16) uint32_t s_maskw[64];
-    __shared__ unsigned long long s_excl;      // sum of the sizes of all earlier blocks, / 16
-    __shared__ uint32_t s_flags;               // bit 0 range error in this block, bit 1 in an earlier
-                                               // block, bit 2 the scan gave up waiting
+    __shared__ uint32_t s_k[2];                // block index of this / the next iteration
+    __shared__ unsigned long long s_tag;       // tag of this call
+    __shared__ unsigned long long s_off;       // start of the block being stored, bytes
+    __shared__ uint32_t s_status;              // header status found by the scan for that block
+    __shared__ uint32_t s_err[2];              // range error in the block of image 0 / 1
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t B = p.B, logC = p.logB - 3u;
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
-    const uint32_t k = blockIdx.x;
-    uint8_t *lds_low = smem;
-    uint8_t *lds_high = smem + (((size_t)M * B) >> 3);
-    const uint64_t blk0 = (uint64_t)k << p.logB;
+    const uint32_t img_bytes = (B >> 7) + (((uint32_t)N * B) >> 3);
     const uint32_t padw = (p.b << 7) * 0x00010001u;   // a pad element has exponent b: y = 0, sm = 0
+    const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
 
-    if (tid == 0) { s_excl = 0; s_flags = 0; }
-
-    // ---- a1: 128-bit loads of the 8 rows ---------------------------------------
-    uint4 raw[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
-        if (active && e0 + 8 <= p.n_elems) {
-            raw[t] = *reinterpret_cast<const uint4 *>(p.in + e0);
-        } else {
-            uint32_t d[4] = {padw, padw, padw, padw};
-            if (active && e0 < p.n_elems) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (e0 + i < p.n_elems) {
-                        const uint32_t v = p.in[e0 + i];
-                        d[i >> 1] = (i & 1) ? ((d[i >> 1] & 0x0000FFFFu) | (v << 16))
-                                            : ((d[i >> 1] & 0xFFFF0000u) | v);
-                    }
-            }
-            raw[t] = make_uint4(d[0], d[1], d[2], d[3]);
+    // ---- control record of this workgroup's class (thread 0) ---------------------------
+    const uint32_t home = blockIdx.x % p.ncls;
+    uint32_t *ctl = p.ws_ctl + WS_STRIDE * home;
+    const uint32_t class_blocks = home < p.nb ? (p.nb - home + p.ncls - 1u) / p.ncls : 0u;
+    const uint32_t class_wgs = (gridDim.x - home + p.ncls - 1u) / p.ncls;
+    uint32_t ticket_base = 0, zero = 0;
+    uint64_t tag0 = 0;
+    bool drawing = true;
+    // decode a draw; the last draw of the class hands the record over to the next call
+    auto decode_draw = [&](uint32_t raw) -> uint32_t {
+        const uint32_t t = raw - ticket_base;
+        if (t == class_blocks + class_wgs - 1u) {
+            ctl[1] = raw + 1u;
+            for (uint32_t c = home; c < WS_CLASSES; c += p.ncls)
+                *reinterpret_cast<uint64_t *>(p.ws_ctl + WS_STRIDE * c + 2) = tag0;
         }
+        if (t >= class_blocks) { drawing = false; return NO_BLOCK; }
+        return t * p.ncls + home;
+    };
+    if (tid == 0) {
+        ticket_base = ctl[1];
+        tag0 = *reinterpret_cast<const uint64_t *>(ctl + 2) + 1u;
+        // the record must have been read before this workgroup's first draw can be counted
+        zero = ticket_base ^ (uint32_t)tag0;
+        asm volatile("v_and_b32 %0, 0, %0" : "+v"(zero));
+        s_k[0] = decode_draw(atomicAdd(ctl + zero, 1u));
+        s_tag = tag0;
+        s_err[0] = s_err[1] = 0;
+        s_status = 0;
     }
+    __syncthreads();
+    uint32_t k = s_k[0];
+    const uint64_t tag = (uint64_t)s_tag << 24;
+    uint32_t slot = 0;
+    uint4 raw[8];
+    if (k != NO_BLOCK) load_block_rows(p, k, tid, active, logC, padw, raw);
 
     const uint32_t crep = ((p.b + (1u << (N - 1))) & 0xFFu) * 0x01010101u;
     const uint32_t xlo = p.b + 1u > (1u << (N - 1)) ? p.b + 1u - (1u << (N - 1)) : 0u;
     const uint32_t xhi = p.b + (1u << (N - 1)) < 255u ? p.b + (1u << (N - 1)) : 255u;
-
-    uint32_t SM[8][2], HI[8][2], accP[MP][2], mw[8];
-    uint32_t err_acc = 0;
-    bool bad = false;
-#pragma unroll
-    for (int q = 0; q < MP; ++q) accP[q][0] = accP[q][1] = 0;
-
     constexpr HHTable TL = HH<M>::table;
+
+    // wave 0 carries the scan: sum of the group words [0, groups_summed) and errors seen so far
+    uint64_t groups_sum = 0;
+    uint32_t groups_summed = 0, scan_flags = 0;       // bit 1 earlier range error, bit 2 gave up
+
+    // sum of the (valid) words base[0 .. count), count <= 64, one word per lane; waits for them
+    auto sum_words = [&](const uint64_t *base, uint32_t count) -> uint64_t {
+        const bool need = lane < count;
+        uint64_t v = 0;
+        bool ok = !need;
+        uint32_t spins = 0;
+        for (;;) {
+            if (!ok) {
+                v = ld_state(base + lane);
+                ok = (v & ~0xFFFFFFull) == tag;
+            }
+            if (__builtin_amdgcn_ballot_w64(!ok) == 0) break;
+            if (++spins > SPIN_LIMIT) { scan_flags |= 4u; v = 0; break; }      // never hang
+            spin_pause(spins);
+        }
+        if (__builtin_amdgcn_ballot_w64(need && (v & ST_ERR))) scan_flags |= 2u;
+        return wave_sum(need ? (v & ST_VALUE) : 0ull);
+    };
+    // start of block kb (wave 0; own_group = sum of the earlier block words of its group if known)
+    auto block_start = [&](uint32_t kb, bool have_own, uint64_t own_group) -> uint64_t {
+        const uint32_t g = kb >> 6;
+        while (groups_summed < g) {
+            const uint32_t c = g - groups_summed < 64u ? g - groups_summed : 64u;
+            groups_sum += sum_words(p.ws_group + groups_summed, c);
+            groups_summed += c;
+        }
+        if (!have_own) own_group = sum_words(p.ws_block + ((uint64_t)g << 6), kb & 63u);
+        return (groups_sum + own_group) << 4;
+    };
+
+    // the block waiting to be stored
+    uint32_t pend = NO_BLOCK, pend_cnt = 0, pend_S = 0, pend_err = 0;
+    bool pend_have_own = false;
+    uint64_t pend_own = 0;
+    uint32_t SMp[8][2];
+
+    // stores block `kb` whose packed part sits in image `img` and whose sign/mantissa bytes sit in SMp
+    auto store_block = [&](uint32_t kb, uint32_t cnt, uint32_t S, const uint8_t *img, uint32_t err_own) {
+        const uint64_t off = s_off;
+        uint8_t *dst = p.out + p.payload_base + off;
+        if (active) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        uint32_t gor = 0;
+            for (int t = 0; t < 8; ++t)
+                *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SMp[t][0], SMp[t][1]);
+        }
+        if (tid < (B >> 11))
+            *reinterpret_cast<uint4 *>(dst + B + 16u * tid) = *reinterpret_cast<const uint4 *>(img + 16u * tid);
+        if (M > 0) {
+            const uint8_t *ilow = img + (B >> 7);
+            uint8_t *dlow = dst + B + (B >> 7);
+            const uint32_t T2 = (M * B) >> 4;                 // half of the plane's length
+            for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
+                const uint2 a = *reinterpret_cast<const uint2 *>(ilow + 8u * v);
+                const uint2 c = *reinterpret_cast<const uint2 *>(ilow + 8u * v + T2);
+                uint4 o;   // stream byte 2i = normalized byte i, stream byte 2i+1 = normalized byte i + T/2
+                o.x = byte_perm(c.x, a.x, 0x05010400u);
+                o.y = byte_perm(c.x, a.x, 0x07030602u);
+                o.z = byte_perm(c.y, a.y, 0x05010400u);
+                o.w = byte_perm(c.y, a.y, 0x07030602u);
+                *reinterpret_cast<uint4 *>(dlow + 16u * v) = o;
+            }
+        }
+        if (A > 0) {
+            const uint8_t *ihigh = img + (B >> 7) + ((M * B) >> 3);
+            uint8_t *dhigh = dst + fixed;
+            const uint32_t hbytes = 2u * A * cnt;             // even
+            for (uint32_t v = tid; 16u * v < hbytes; v += blockDim.x) {
+                uint4 o = *reinterpret_cast<const uint4 *>(ihigh + 16u * v);
+                uint32_t w[4] = {o.x, o.y, o.z, o.w};
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t d0 = h ? raw[t].z : raw[t].x;
-            const uint32_t d1 = h ? raw[t].w : raw[t].y;
-            // a1 split: low / high bytes of four bf16 words
-            const uint32_t Lb = byte_perm(d1, d0, 0x06040200u);
-            const uint32_t Hb = byte_perm(d1, d0, 0x07050301u);
-            SM[t][h] = bfi(0x7F7F7F7Fu, Lb, Hb);
-            const uint32_t X = bfi(0xFEFEFEFEu, Hb << 1, Lb >> 7);
-            // a2 transform: z = (b + 2^(n-1) - x) mod 256 per byte, y = z with the sign bit flipped
-            uint32_t Z;
-            if (p.mode == 0) {
-                Z = crep - X;
-                if (N < 8) err_acc |= Z;
-            } else {
-                Z = bytesub_safe(crep, X);
-                if (p.mode == 2) {
+                for (int i = 0; i < 4; ++i) {                 // zero the padding behind the last record
+                    const uint32_t at = 16u * v + 4u * i;
+                    if (at >= hbytes) w[i] = 0;
+                    else if (at + 2 >= hbytes) w[i] &= 0xFFFFu;
+                }
+                *reinterpret_cast<uint4 *>(dhigh + 16u * v) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+        if (tid == 0) {
+            uint64_t *table = reinterpret_cast<uint64_t *>(p.out + 64);
+            table[kb] = off;
+            if (kb == p.nb - 1u) {
+                const uint64_t end = off + S;
+                const uint32_t fl = s_status | err_own;
+                const uint32_t status = (fl & 4u) ? 8u : ((fl & 3u) ? 6u : 0u);
+                const uint64_t total = status ? 0ull : p.payload_base + end;
+                table[p.nb] = end;
+                if (((uint64_t)(p.nb + 1u) & 1ull)) table[p.nb + 1u] = 0;   // pad up to the payload base
+                uint32_t *h = reinterpret_cast<uint32_t *>(p.out);
+                h[0] = 0x43454E45u;                              // "ENEC"
+                h[1] = 1u | (0u << 16) | (16u << 24);            // version, dtype bf16, L
+                h[2] = (uint32_t)p.n_elems; h[3] = (uint32_t)(p.n_elems >> 32);
+                h[4] = B; h[5] = p.nb;
+                h[6] = p.b | ((uint32_t)N << 8) | ((uint32_t)M << 16) | (8u << 24);
+                h[7] = status;
+                h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const uint32_t xb = (X >> (8 * i)) & 0xFFu;
-                        bad |= (xb < xlo) | (xb > xhi);
+                for (int i = 10; i < 16; ++i) h[i] = 0;
+                if (p.out_bytes) *p.out_bytes = total;
+            }
+        }
+    };
+
+    ENEC_TP_DECL;
+    while (k != NO_BLOCK) {
+        ENEC_TP(0);
+        uint8_t *img = smem + slot * img_bytes;
+        uint32_t *img_maskw = reinterpret_cast<uint32_t *>(img);
+        uint8_t *img_low = img + (B >> 7);
+        uint8_t *img_high = img_low + (((size_t)M * B) >> 3);
+
+        // the ticket for the following block is drawn now and looked at after the arithmetic
+        uint32_t next_raw = 0;
+        const bool draw_now = tid == 0 && p.lookahead && drawing;
+        if (draw_now) next_raw = atomicAdd(ctl + zero, 1u);
+
+        uint32_t SMc[8][2], HI[8][2], accP[MP][2], mw[8];
+        uint32_t err_acc = 0;
+        bool bad = false;
+#pragma unroll
+        for (int q = 0; q < MP; ++q) accP[q][0] = accP[q][1] = 0;
+
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            uint32_t gor = 0;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t d0 = h ? raw[t].z : raw[t].x;
+                const uint32_t d1 = h ? raw[t].w : raw[t].y;
+                // a1 split: low / high bytes of four bf16 words
+                const uint32_t Lb = byte_perm(d1, d0, 0x06040200u);
+                const uint32_t Hb = byte_perm(d1, d0, 0x07050301u);
+                SMc[t][h] = bfi(0x7F7F7F7Fu, Lb, Hb);
+                const uint32_t X = bfi(0xFEFEFEFEu, Hb << 1, Lb >> 7);
+                // a2 transform: z = (b + 2^(n-1) - x) mod 256 per byte, y = z with the sign bit flipped
+                uint32_t Z;
+                if (p.mode == 0) {
+                    Z = crep - X;
+                    if (N < 8) err_acc |= Z;
+                } else {
+                    Z = bytesub_safe(crep, X);
+                    if (p.mode == 2) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const uint32_t xb = (X >> (8 * i)) & 0xFFu;
+                            bad |= (xb < xlo) | (xb > xhi);
+                        }
+                    }
+                }
+                uint32_t Y = Z ^ SREP;
+                if (N < 8) Y &= NMASK;
+                // a3: high parts decide the group; a4: low parts go to the column packer
+                const uint32_t hi = A > 0 ? ((Y >> M) & AMASK) : 0u;
+                HI[t][h] = hi;
+                gor |= hi;
+                if (M > 0) {
+                    const uint32_t low = Y & LMASK;
+#pragma unroll
+                    for (int f = 0; f < TL.count; ++f)
+                        if (TL.row[f] == t) {
+                            uint32_t s = shl_or_shr(low, TL.shift[f]);
+                            if (!TL.clean[f]) s &= TL.dmask[f] * 0x01010101u;
+                            accP[TL.plane[f]][h] |= s;
+                        }
+                }
+            }
+            gor |= swap_pair(gor);
+            mw[t] = compact_even_bits(__builtin_amdgcn_ballot_w64(gor != 0));
+        }
+        if (N < 8 && p.mode == 0) bad = (err_acc & ~NMASK) != 0;
+        if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(&s_err[slot], 1u);
+        ENEC_TP(1);
+
+        if (lane == 0 && 64u * wave < nact) {
+            if (logC >= 9) {
+#pragma unroll
+                for (int t = 0; t < 8; ++t) img_maskw[((uint32_t)t << (logC - 9)) + wave] = mw[t];
+            } else {      // B = 2048: 16 groups per row, one wave
+#pragma unroll
+                for (int u = 0; u < 4; ++u) img_maskw[u] = mw[2 * u] | (mw[2 * u + 1] << 16);
+            }
+        }
+        if (M > 0 && active) {
+#pragma unroll
+            for (int q = 0; q < M; ++q)
+                *reinterpret_cast<uint2 *>(img_low + ((size_t)q << logC) + 8u * tid) =
+                    make_uint2(accP[q][0], accP[q][1]);
+        }
+        if (tid == 0) s_k[slot ^ 1u] = draw_now ? decode_draw(next_raw) : NO_BLOCK;
+        __syncthreads();                                                     // barrier 1
+        ENEC_TP(2);
+
+        // ---- a5 (positions): exclusive popcount prefix over the block's mask words; every wave
+        // computes it for itself (a wave scan of at most 64 words) -----------------------
+        const uint32_t nwords = B >> 9;
+        const uint32_t my_word = lane < nwords ? img_maskw[lane] : 0u;
+        const uint32_t my_pc = __popc(my_word);
+        const uint32_t my_incl = wave_incl_scan(my_pc, lane);
+        const uint32_t my_excl = my_incl - my_pc;
+        const uint32_t cnt = __shfl(my_incl, 63, 64);
+        const uint32_t own_err = s_err[slot] & 1u;
+        const uint32_t S = (fixed + 2u * A * cnt + 15u) & ~15u;
+
+        // ---- a6: publish this block's size at once -----------------------------------
+        if (tid == 0) st_state(p.ws_block + k, tag | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
+
+        // ---- a5: one record per masked group ------------------------------------------
+        if (A > 0) {
+            constexpr HHTable TH = HH<A>::table;
+            const uint32_t par = tid & 1u;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                // even lanes pack the group of row 2u, odd lanes the group of row 2u+1
+                const uint32_t own0 = par ? HI[2 * u + 1][0] : HI[2 * u][0];
+                const uint32_t own1 = par ? HI[2 * u + 1][1] : HI[2 * u][1];
+                const uint32_t snd0 = par ? HI[2 * u][0] : HI[2 * u + 1][0];
+                const uint32_t snd1 = par ? HI[2 * u][1] : HI[2 * u + 1][1];
+                const uint32_t rcv0 = swap_pair(snd0);
+                const uint32_t rcv1 = swap_pair(snd1);
+                uint32_t F[4];
+                F[0] = par ? rcv0 : own0;
+                F[1] = par ? rcv1 : own1;
+                F[2] = par ? own0 : rcv0;
+                F[3] = par ? own1 : rcv1;
+                const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
+                const uint32_t wv = __shfl(my_word, g >> 5, 64);
+                const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+                const uint32_t bit = (wv >> (g & 31u)) & 1u;
+                if (active && bit) {
+                    const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+                    // the group's 16 values are 2 columns of 8 rows: row r = bytes (2r, 2r+1)
+                    uint32_t P[AP];
+#pragma unroll
+                    for (int q = 0; q < AP; ++q) P[q] = 0;
+#pragma unroll
+                    for (int f = 0; f < TH.count; ++f) {
+                        const int r = TH.row[f];
+                        const uint32_t s = shl_or_shr(F[r >> 1], TH.shift[f] - 16 * (r & 1));
+                        P[TH.plane[f]] |= s & (TH.dmask[f] * 0x0101u);
+                    }
+                    // normalized byte j = byte (j & 1) of P[j >> 1]; stream word i = nb[i] | nb[i + A] << 8
+                    uint16_t *dst = reinterpret_cast<uint16_t *>(img_high + 2u * A * rank);
+#pragma unroll
+                    for (int i = 0; i < A; ++i) {
+                        const uint32_t lo = (P[i >> 1] >> (8 * (i & 1))) & 0xFFu;
+                        const uint32_t hi = (P[(i + A) >> 1] >> (8 * ((i + A) & 1))) & 0xFFu;
+                        dst[i] = (uint16_t)(lo | (hi << 8));
                     }
                 }
             }
-            uint32_t Y = Z ^ SREP;
-            if (N < 8) Y &= NMASK;
-            // a3: high parts decide the group; a4: low parts go to the column packer
-            const uint32_t hi = A > 0 ? ((Y >> M) & AMASK) : 0u;
-            HI[t][h] = hi;
-            gor |= hi;
-            if (M > 0) {
-                const uint32_t low = Y & LMASK;
-#pragma unroll
-                for (int f = 0; f < TL.count; ++f)
-                    if (TL.row[f] == t) {
-                        uint32_t s = shl_or_shr(low, TL.shift[f]);
-                        if (!TL.clean[f]) s &= TL.dmask[f] * 0x01010101u;
-                        accP[TL.plane[f]][h] |= s;
-                    }
+        }
+        ENEC_TP(3);
+
+        // ---- a6 (wave 0): the owner of the last block of a group adds the group up; then the
+        // start of the block stored in this iteration ------------------------------------
+        bool cur_have_own = false;
+        uint64_t cur_own = 0;
+        if (wave == 0) {
+            if ((k & 63u) == 63u) {
+                cur_own = sum_words(p.ws_block + ((uint64_t)(k >> 6) << 6), 63u);
+                cur_have_own = true;
+                if (lane == 0 && !(scan_flags & 4u))
+                    st_state(p.ws_group + (k >> 6), tag | ((scan_flags & 2u) || own_err ? ST_ERR : 0ull) |
+                                                        (cur_own + (S >> 4)));
+            }
+            if (pend != NO_BLOCK) {
+                const uint64_t off = block_start(pend, pend_have_own, pend_own);
+                if (lane == 0) { s_off = off; s_status = scan_flags; }
             }
         }
-        gor |= swap_pair(gor);
-        mw[t] = compact_even_bits(__builtin_amdgcn_ballot_w64(gor != 0));
-    }
-    if (N < 8 && p.mode == 0) bad = (err_acc & ~NMASK) != 0;
-    const bool wave_bad = __builtin_amdgcn_ballot_w64(bad) != 0;
+        ENEC_TP(4);
+        __syncthreads();                                                     // barrier 2
+        ENEC_TP(5);
+        if (tid == 0) s_err[slot] = 0;          // read by everybody before barrier 2; next use in two iterations
 
-    __syncthreads();                       // s_excl / s_flags initialised
-    if (wave_bad && lane == 0) atomicOr(&s_flags, 1u);
-    if (lane == 0 && 64u * wave < nact) {
-        if (logC >= 9) {
-#pragma unroll
-            for (int t = 0; t < 8; ++t) s_maskw[((uint32_t)t << (logC - 9)) + wave] = mw[t];
-        } else {      // B = 2048: 16 groups per row, one wave
-#pragma unroll
-            for (int u = 0; u < 4; ++u) s_maskw[u] = mw[2 * u] | (mw[2 * u + 1] << 16);
-        }
-    }
-    if (M > 0 && active) {
-#pragma unroll
-        for (int q = 0; q < M; ++q)
-            *reinterpret_cast<uint2 *>(lds_low + ((size_t)q << logC) + 8u * tid) =
-                make_uint2(accP[q][0], accP[q][1]);
-    }
-    __syncthreads();
+        // the following block's rows start to travel while the previous block is stored
+        const uint32_t knext = s_k[slot ^ 1u];
+        if (knext != NO_BLOCK) load_block_rows(p, knext, tid, active, logC, padw, raw);
 
-    // ---- a5 (positions): exclusive popcount prefix over the block's mask words; every wave
-    // computes it for itself (a wave scan of at most 64 words) ---------------------------
-    const uint32_t nwords = B >> 9;
-    const uint32_t my_word = lane < nwords ? s_maskw[lane] : 0u;
-    const uint32_t my_pc = __popc(my_word);
-    const uint32_t my_incl = wave_incl_scan(my_pc, lane);
-    const uint32_t my_excl = my_incl - my_pc;
-    const uint32_t cnt = __shfl(my_incl, 63, 64);
-    const bool own_err = (s_flags & 1u) != 0;
-    const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
-    const uint32_t S = (fixed + 2u * A * cnt + 15u) & ~15u;
+        // ---- a7: stores of the previous block ----------------------------------------------
+        if (pend != NO_BLOCK)
+            store_block(pend, pend_cnt, pend_S, smem + (slot ^ 1u) * img_bytes, pend_err);
+        ENEC_TP(6);
+        __syncthreads();                                                     // barrier 3: other image free
+        ENEC_TP(7);
+        ENEC_TP_FLUSH;
 
-    // ---- a6: publish this block's size at once ---------------------------------------
-    const uint32_t gk = k >> 6, rk = k & 63u;
-    if (tid == 0) {
-        st_state(p.ws_block + k, ST_VALID | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
-        __hip_atomic_fetch_add(p.ws_group + gk, GS_ONE | (own_err ? GS_ERR : 0ull) | (uint64_t)(S >> 4),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-
-    // ---- a5: one record per masked group ------------------------------------------
-    if (A > 0) {
-        constexpr HHTable TH = HH<A>::table;
-        const uint32_t par = tid & 1u;
+        // this block becomes the pending one
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            // even lanes pack the group of row 2u, odd lanes the group of row 2u+1
-            const uint32_t own0 = par ? HI[2 * u + 1][0] : HI[2 * u][0];
-            const uint32_t own1 = par ? HI[2 * u + 1][1] : HI[2 * u][1];
-            const uint32_t snd0 = par ? HI[2 * u][0] : HI[2 * u + 1][0];
-            const uint32_t snd1 = par ? HI[2 * u][1] : HI[2 * u + 1][1];
-            const uint32_t rcv0 = swap_pair(snd0);
-            const uint32_t rcv1 = swap_pair(snd1);
-            uint32_t F[4];
-            F[0] = par ? rcv0 : own0;
-            F[1] = par ? rcv1 : own1;
-            F[2] = par ? own0 : rcv0;
-            F[3] = par ? own1 : rcv1;
-            const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
-            const uint32_t wv = __shfl(my_word, g >> 5, 64);
-            const uint32_t pre = __shfl(my_excl, g >> 5, 64);
-            const uint32_t bit = (wv >> (g & 31u)) & 1u;
-            if (active && bit) {
-                const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                // the group's 16 values are 2 columns of 8 rows: row r = bytes (2r, 2r+1)
-                uint32_t P[AP];
-#pragma unroll
-                for (int q = 0; q < AP; ++q) P[q] = 0;
-#pragma unroll
-                for (int f = 0; f < TH.count; ++f) {
-                    const int r = TH.row[f];
-                    const uint32_t s = shl_or_shr(F[r >> 1], TH.shift[f] - 16 * (r & 1));
-                    P[TH.plane[f]] |= s & (TH.dmask[f] * 0x0101u);
-                }
-                // normalized byte j = byte (j & 1) of P[j >> 1]; stream word i = nb[i] | nb[i + A] << 8
-                uint16_t *dst = reinterpret_cast<uint16_t *>(lds_high + 2u * A * rank);
-#pragma unroll
-                for (int i = 0; i < A; ++i) {
-                    const uint32_t lo = (P[i >> 1] >> (8 * (i & 1))) & 0xFFu;
-                    const uint32_t hi = (P[(i + A) >> 1] >> (8 * ((i + A) & 1))) & 0xFFu;
-                    dst[i] = (uint16_t)(lo | (hi << 8));
-                }
-            }
+        for (int t = 0; t < 8; ++t) { SMp[t][0] = SMc[t][0]; SMp[t][1] = SMc[t][1]; }
+        pend = k; pend_cnt = cnt; pend_S = S; pend_err = own_err; pend_have_own = cur_have_own; pend_own = cur_own;
+        slot ^= 1u;
+        k = knext;
+        if (k == NO_BLOCK && !p.lookahead) {           // without lookahead the next ticket is drawn only now
+            if (tid == 0) s_k[slot] = drawing ? decode_draw(atomicAdd(ctl + zero, 1u)) : NO_BLOCK;
+            __syncthreads();
+            k = s_k[slot];
+            if (k != NO_BLOCK) load_block_rows(p, k, tid, active, logC, padw, raw);
         }
     }
 
-    // ---- a6: sum of the sizes of all earlier blocks ------------------------------------
-    {
-        uint64_t part = 0;
-        uint32_t flags = 0;
-        for (uint32_t e = tid; e < gk + rk; e += blockDim.x) {
-            uint32_t spins = 0;
-            uint64_t v;
-            if (e < gk) {
-                while ((((v = ld_state(p.ws_group + e)) >> 48) & 0xFFu) != 64u) {
-                    if (++spins > SPIN_LIMIT) { flags |= 4u; break; }      // never hang
-                    __builtin_amdgcn_s_sleep(2);
-                }
-                if ((v >> 40) & 0xFFu) flags |= 2u;
-            } else {
-                const uint64_t *q = p.ws_block + ((uint64_t)gk << 6) + (e - gk);
-                while (!((v = ld_state(q)) & ST_VALID)) {
-                    if (++spins > SPIN_LIMIT) { flags |= 4u; break; }
-                    __builtin_amdgcn_s_sleep(2);
-                }
-                if (v & ST_ERR) flags |= 2u;
-            }
-            part += v & ST_VALUE;
+    // ---- drain: the last block of this workgroup ---------------------------------------------
+    if (pend != NO_BLOCK) {
+        if (wave == 0) {
+            const uint64_t off = block_start(pend, pend_have_own, pend_own);
+            if (lane == 0) { s_off = off; s_status = scan_flags; }
         }
-        part = wave_sum(part);
-        const uint64_t any = __builtin_amdgcn_ballot_w64(flags != 0);
-        if (any) atomicOr(&s_flags, flags);
-        if (lane == 0 && part) atomicAdd(&s_excl, (unsigned long long)part);
-    }
-    __syncthreads();
-
-    // ---- a7: stores -----------------------------------------------------------------
-    const uint64_t off = (uint64_t)s_excl << 4;
-    uint8_t *dst = p.out + p.payload_base + off;
-    if (active) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t)
-            *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SM[t][0], SM[t][1]);
-    }
-    if (tid < (B >> 11))
-        *reinterpret_cast<uint4 *>(dst + B + 16u * tid) = *reinterpret_cast<const uint4 *>(&s_maskw[4 * tid]);
-    if (M > 0) {
-        uint8_t *dlow = dst + B + (B >> 7);
-        const uint32_t T2 = (M * B) >> 4;                 // half of the plane's length
-        for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
-            const uint2 a = *reinterpret_cast<const uint2 *>(lds_low + 8u * v);
-            const uint2 c = *reinterpret_cast<const uint2 *>(lds_low + 8u * v + T2);
-            uint4 o;   // stream byte 2i = normalized byte i, stream byte 2i+1 = normalized byte i + T/2
-            o.x = byte_perm(c.x, a.x, 0x05010400u);
-            o.y = byte_perm(c.x, a.x, 0x07030602u);
-            o.z = byte_perm(c.y, a.y, 0x05010400u);
-            o.w = byte_perm(c.y, a.y, 0x07030602u);
-            *reinterpret_cast<uint4 *>(dlow + 16u * v) = o;
-        }
-    }
-    if (A > 0) {
-        uint8_t *dhigh = dst + fixed;
-        const uint32_t hbytes = 2u * A * cnt;             // even
-        for (uint32_t v = tid; 16u * v < hbytes; v += blockDim.x) {
-            uint4 o = *reinterpret_cast<const uint4 *>(lds_high + 16u * v);
-            uint32_t w[4] = {o.x, o.y, o.z, o.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {                 // zero the padding behind the last record
-                const uint32_t at = 16u * v + 4u * i;
-                if (at >= hbytes) w[i] = 0;
-                else if (at + 2 >= hbytes) w[i] &= 0xFFFFu;
-            }
-            *reinterpret_cast<uint4 *>(dhigh + 16u * v) = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-    }
-    if (tid == 0) {
-        uint64_t *table = reinterpret_cast<uint64_t *>(p.out + 64);
-        table[k] = off;
-        if (k == p.nb - 1u) {
-            const uint64_t end = off + S;
-            const uint32_t fl = s_flags;
-            const uint32_t status = (fl & 4u) ? 8u : ((fl & 3u) ? 6u : 0u);
-            const uint64_t total = status ? 0ull : p.payload_base + end;
-            table[p.nb] = end;
-            if (((uint64_t)(p.nb + 1u) & 1ull)) table[p.nb + 1u] = 0;   // pad up to the payload base
-            uint32_t *h = reinterpret_cast<uint32_t *>(p.out);
-            h[0] = 0x43454E45u;                              // "ENEC"
-            h[1] = 1u | (0u << 16) | (16u << 24);            // version, dtype bf16, L
-            h[2] = (uint32_t)p.n_elems; h[3] = (uint32_t)(p.n_elems >> 32);
-            h[4] = B; h[5] = p.nb;
-            h[6] = p.b | ((uint32_t)N << 8) | ((uint32_t)M << 16) | (8u << 24);
-            h[7] = status;
-            h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
-#pragma unroll
-            for (int i = 10; i < 16; ++i) h[i] = 0;
-            if (p.out_bytes) *p.out_bytes = total;
-        }
-    }
-
-    // ---- hand the workspace back zeroed: the last block of each group to finish reading
-    // clears the group's block words, the last group to finish clears the group words ----
-    if (wave == 0) {
-        uint32_t last = 0;
-        if (lane == 0) {
-            const uint32_t ng = (p.nb + 63u) >> 6;
-            const uint32_t gsize = (gk == ng - 1u) ? p.nb - (gk << 6) : 64u;
-            if (atomicAdd(p.ws_gdone + gk, 1u) == gsize - 1u) {
-                last = 1;
-                if (atomicAdd(p.ws_done, 1u) == ng - 1u) last = 2;
-            }
-        }
-        last = __shfl(last, 0, 64);
-        if (last) {
-            const uint32_t idx = (gk << 6) + lane;
-            if (idx < p.nb) p.ws_block[idx] = 0;
-        }
-        if (last == 2) {
-            const uint32_t ng = (p.nb + 63u) >> 6;
-            for (uint32_t i = lane; i < ng; i += 64) { p.ws_group[i] = 0; p.ws_gdone[i] = 0; }
-            if (lane == 0) *p.ws_done = 0;
-        }
+        __syncthreads();
+        store_block(pend, pend_cnt, pend_S, smem + (slot ^ 1u) * img_bytes, pend_err);
     }
 }
 

@@ -173,8 +173,10 @@ def test_workspace_is_reusable_and_results_are_deterministic(gpu, oracle):
         assert rc == 0 and nbytes == sb.size and np.array_equal(out[:nbytes], sb), f"run {i}"
         rc, out, nbytes, _ = gpu.compress(small, ps, 16384, src=src_s)
         assert rc == 0 and nbytes == ss.size and np.array_equal(out[:nbytes], ss), f"run {i}"
-    wsb = gpu.ws.cpu().numpy()          # everything but the histogram area is handed back zeroed
-    assert not wsb[:256].any() and not wsb[2304:].any()
+    # the ticket counter of every class has come back to the base the next call will read
+    ctl = gpu.ws.cpu().numpy()[:1024].view(np.uint32).reshape(8, 32)
+    assert (ctl[:, 0] == ctl[:, 1]).all()
+    assert len(set(ctl[:, 2].tolist())) == 1
 
 
 def test_back_to_back_calls_without_sync(gpu, oracle):

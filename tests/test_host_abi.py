@@ -43,7 +43,7 @@ def test_bounds_and_block_sizes_match_oracle(enec, oracle):
         for B in [2048, 4096, 8192, 16384, 32768]:
             assert enec.compress_bound(n, block_size=B) == oracle.compress_bound(n, B)
         assert enec.compress_bound(n) == oracle.compress_bound(n, oracle.default_block(n))
-        assert enec.workspace_bytes(n) >= 2304 + 8 * max(1, oracle.num_blocks(n, oracle.default_block(n)))
+        assert enec.workspace_bytes(n) >= 3072 + 8 * max(1, oracle.num_blocks(n, oracle.default_block(n)))
         assert enec.workspace_bytes(n) % 256 == 0
     assert enec.compress_bound(100, block_size=3000) == 0
     assert enec.compress_bound(100, dtype=1) == 0
