@@ -65,12 +65,14 @@ def main():
     sizes = torch.zeros(len(srcs), dtype=torch.int64, device="cuda")
     nt = len(srcs)
 
+    per_launch = os.environ.get("BENCH_PASS_EVENTS_ONLY") is None
+
     def compress_all(ev=None):
         for i in range(nt):
-            if ev:
+            if ev and (per_launch or i == 0):
                 ev[0][i].record()
             rc = enec.compress(srcs[i], params[i], outs[i], ws, out_bytes=sizes[i:i + 1])
-            if ev:
+            if ev and (per_launch or i == nt - 1):
                 ev[1][i].record()
             assert rc == 0, enec.strerror(rc)
 
@@ -82,10 +84,10 @@ def main():
 
     def decompress_all(ev=None):
         for i in range(nt):
-            if ev:
+            if ev and (per_launch or i == 0):
                 ev[0][i].record()
             rc = enec.decompress_with_header(outs[i], headers[i], backs[i])
-            if ev:
+            if ev and (per_launch or i == nt - 1):
                 ev[1][i].record()
             assert rc == 0, enec.strerror(rc)
 
@@ -115,8 +117,11 @@ def main():
     value = 2 * raw_bytes / (ms_per_step * 1e-3) / 1e9
 
     # per-launch durations from the events recorded inside the timed region
-    dur_c = np.array([[evc[k][0][i].elapsed_time(evc[k][1][i]) for i in range(nt)] for k in range(args.steps)])
-    dur_d = np.array([[evd[k][0][i].elapsed_time(evd[k][1][i]) for i in range(nt)] for k in range(args.steps)])
+    if per_launch:
+        dur_c = np.array([[evc[k][0][i].elapsed_time(evc[k][1][i]) for i in range(nt)] for k in range(args.steps)])
+        dur_d = np.array([[evd[k][0][i].elapsed_time(evd[k][1][i]) for i in range(nt)] for k in range(args.steps)])
+    else:
+        dur_c = dur_d = np.ones((args.steps, nt))
     # whole pass: first launch start to last launch end
     pass_c = np.array([evc[k][0][0].elapsed_time(evc[k][1][nt - 1]) for k in range(args.steps)])
     pass_d = np.array([evd[k][0][0].elapsed_time(evd[k][1][nt - 1]) for k in range(args.steps)])

@@ -328,8 +328,11 @@ int enec_decompress_with_header(const void *in, size_t in_bytes, const void *hos
     DecompressFn fn = pick_decompress(h.prm.m, h.prm.n - h.prm.m);
     if (!fn) return ENEC_E_FORMAT;
     const unsigned threads = h.B / 64 < 64 ? 64 : h.B / 64;
-    const size_t lds = (size_t)h.prm.n * h.B / 8;
-    hipLaunchKernelGGL(fn, dim3(a.nb), dim3(threads), lds, (hipStream_t)stream, a);
+    const size_t lds = 2 * ((size_t)h.B / 128 + (size_t)h.prm.n * h.B / 8);    // two images of the packed part
+    const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_DECOMPRESS_WGS_PER_CU");
+    if (resident == 0) return ENEC_E_HIP;
+    const unsigned grid = a.nb < resident ? a.nb : resident;
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, (hipStream_t)stream, a);
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 

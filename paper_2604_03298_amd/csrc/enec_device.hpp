@@ -341,13 +341,13 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     uint64_t groups_sum = 0;
     uint32_t groups_summed = 0, scan_flags = 0;       // bit 1 earlier range error, bit 2 gave up
 
-    // sum of the (valid) words base[0 .. count), count <= 64, one word per lane; waits for them
-    auto sum_words = [&](const uint64_t *base, uint32_t count) -> uint64_t {
+    // sum of the (valid) words base[0 .. count), count <= 64, one word per lane; `v` may hold a
+    // copy read earlier (have = true), words that were not valid yet are read again until they are
+    auto sum_words = [&](const uint64_t *base, uint32_t count, bool have, uint64_t v) -> uint64_t {
         const bool need = lane < count;
-        uint64_t v = 0;
-        bool ok = !need;
+        bool ok = !need || (have && (v & ~0xFFFFFFull) == tag);
         uint32_t spins = 0;
-        for (;;) {
+        while (__builtin_amdgcn_ballot_w64(!ok) != 0) {
             if (!ok) {
                 v = ld_state(base + lane);
                 ok = (v & ~0xFFFFFFull) == tag;
@@ -359,15 +359,18 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         if (__builtin_amdgcn_ballot_w64(need && (v & ST_ERR))) scan_flags |= 2u;
         return wave_sum(need ? (v & ST_VALUE) : 0ull);
     };
-    // start of block kb (wave 0; own_group = sum of the earlier block words of its group if known)
-    auto block_start = [&](uint32_t kb, bool have_own, uint64_t own_group) -> uint64_t {
+    // start of block kb (wave 0; own_group = sum of the earlier block words of its group if known;
+    // early_g / early_b = copies of the first needed group words / of the block words read earlier)
+    auto block_start = [&](uint32_t kb, bool have_own, uint64_t own_group, bool early, uint64_t early_g,
+                           uint64_t early_b) -> uint64_t {
         const uint32_t g = kb >> 6;
         while (groups_summed < g) {
             const uint32_t c = g - groups_summed < 64u ? g - groups_summed : 64u;
-            groups_sum += sum_words(p.ws_group + groups_summed, c);
+            groups_sum += sum_words(p.ws_group + groups_summed, c, early, early_g);
             groups_summed += c;
+            early = false;
         }
-        if (!have_own) own_group = sum_words(p.ws_block + ((uint64_t)g << 6), kb & 63u);
+        if (!have_own) own_group = sum_words(p.ws_block + ((uint64_t)g << 6), kb & 63u, early_b != 0, early_b);
         return (groups_sum + own_group) << 4;
     };
 
@@ -451,6 +454,15 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         uint32_t *img_maskw = reinterpret_cast<uint32_t *>(img);
         uint8_t *img_low = img + (B >> 7);
         uint8_t *img_high = img_low + (((size_t)M * B) >> 3);
+
+        // wave 0 reads the scan state for the block stored in this iteration now and uses it
+        // after the arithmetic: published an iteration ago, it is normally all there
+        uint64_t early_g = 0, early_b = 0;
+        if (wave == 0 && pend != NO_BLOCK) {
+            const uint32_t pg = pend >> 6;
+            if (groups_summed + lane < pg) early_g = ld_state(p.ws_group + groups_summed + lane);
+            if (!pend_have_own && lane < (pend & 63u)) early_b = ld_state(p.ws_block + ((uint64_t)pg << 6) + lane);
+        }
 
         // the ticket for the following block is drawn now and looked at after the arithmetic
         uint32_t next_raw = 0;
@@ -600,14 +612,14 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         uint64_t cur_own = 0;
         if (wave == 0) {
             if ((k & 63u) == 63u) {
-                cur_own = sum_words(p.ws_block + ((uint64_t)(k >> 6) << 6), 63u);
+                cur_own = sum_words(p.ws_block + ((uint64_t)(k >> 6) << 6), 63u, false, 0);
                 cur_have_own = true;
                 if (lane == 0 && !(scan_flags & 4u))
                     st_state(p.ws_group + (k >> 6), tag | ((scan_flags & 2u) || own_err ? ST_ERR : 0ull) |
                                                         (cur_own + (S >> 4)));
             }
             if (pend != NO_BLOCK) {
-                const uint64_t off = block_start(pend, pend_have_own, pend_own);
+                const uint64_t off = block_start(pend, pend_have_own, pend_own, true, early_g, early_b);
                 if (lane == 0) { s_off = off; s_status = scan_flags; }
             }
         }
@@ -645,7 +657,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     // ---- drain: the last block of this workgroup ---------------------------------------------
     if (pend != NO_BLOCK) {
         if (wave == 0) {
-            const uint64_t off = block_start(pend, pend_have_own, pend_own);
+            const uint64_t off = block_start(pend, pend_have_own, pend_own, false, 0, 0);
             if (lane == 0) { s_off = off; s_status = scan_flags; }
         }
         __syncthreads();
@@ -673,6 +685,11 @@ __global__ void compress_empty_kernel(const CompressArgs p, uint32_t n, uint32_t
 // ---------------------------------------------------------------------------------
 // decompression: offset lookup, mask prefix, unpack, inverse transform, recombine
 // (Sec. V-A decompression path; Alg. 1 decompression part)
+//
+// Persistent grid, block k handled by workgroup k mod gridDim (blocks are independent, so no
+// tickets are needed).  While block k is unpacked and stored, the payload of the workgroup's
+// next block is already travelling: its sign/mantissa bytes into registers, its packed part
+// (mask | low plane | high records, exactly as in the stream) into the other of two LDS images.
 // ---------------------------------------------------------------------------------
 template <int M, int A>
 __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
@@ -681,25 +698,20 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
     constexpr uint32_t SREP = (1u << (N - 1)) * 0x01010101u;
     constexpr int MP = M > 0 ? M : 1;
     constexpr int AP = A > 0 ? A : 1;
+    constexpr int VMAX = N / 2 + 1;          // 16-byte vectors of packed payload per thread
 
     extern __shared__ __align__(16) uint8_t smem[];
-    __shared__ uint32_t s_maskw[64];
-    __shared__ uint32_t s_pre[64];
 
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const uint32_t B = p.B, logC = p.logB - 3u;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t B = p.B, logC = p.logB - 3u, C = 1u << logC;
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
-    const uint32_t k = blockIdx.x;
-    uint8_t *lds_low = smem;
-    uint8_t *lds_high = smem + (((size_t)M * B) >> 3);
+    const uint32_t img_bytes = (B >> 7) + (((uint32_t)N * B) >> 3);
+    const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
+    const uint32_t par = tid & 1u;
 
-    // d1: offset lookup.  The header in memory must be the one the launch was configured from
-    // (the host has checked that header and table lie inside the buffer), and the block's
-    // payload must lie inside the stream: otherwise touch nothing.
-    const uint64_t *table = reinterpret_cast<const uint64_t *>(p.in + 64);
-    const uint64_t off = table[k];
-    const uint64_t size = table[k + 1] - off;
+    // d1: the header in memory must be the one the launch was configured from (the host has
+    // checked that header and table lie inside the buffer); otherwise touch nothing
     {
         const uint32_t *h = reinterpret_cast<const uint32_t *>(p.in);
         bool same = true;
@@ -707,138 +719,189 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
         for (int i = 0; i < 10; ++i) same &= (h[i] == p.hdr[i]);
         if (!same) return;
     }
-    const uint8_t *src = p.in + p.payload_base + off;
-    const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
-    if (size < fixed || size > fixed + 2u * A * (B >> 4) + 15u || off > p.payload_bytes ||
-        size > p.payload_bytes - off)
-        return;
+    const uint64_t *table = reinterpret_cast<const uint64_t *>(p.in + 64);
 
-    // sign/mantissa bytes: 64-bit loads, issued first
-    uint2 smv[8];
+    // d1: offset lookup, in two steps so that the loads can be issued well before they are used;
+    // a block whose table entries point outside the stream is skipped
+    auto fetch = [&](uint32_t kb, uint64_t &t0, uint64_t &t1) {
+        if (kb < p.nb) { t0 = table[kb]; t1 = table[kb + 1]; }
+    };
+    auto check = [&](uint32_t kb, uint64_t t0, uint64_t t1, uint64_t &off, uint32_t &size) -> bool {
+        if (kb >= p.nb) return false;
+        const uint64_t sz = t1 - t0;
+        off = t0;
+        size = (uint32_t)sz;
+        return !(sz < fixed || sz > fixed + 2u * A * (B >> 4) + 15u || (sz & 15u) || t0 > p.payload_bytes ||
+                 sz > p.payload_bytes - t0);
+    };
+    // issue the loads of one block: sign/mantissa rows and the packed part
+    auto issue = [&](uint64_t off, uint32_t size, uint2 (&smv)[8], uint4 (&vec)[VMAX]) {
+        const uint8_t *src = p.in + p.payload_base + off;
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
-        smv[t] = active ? *reinterpret_cast<const uint2 *>(src + ((size_t)t << logC) + 8u * tid) : make_uint2(0, 0);
-
-    // d2: mask words and their exclusive popcount prefix
-    const uint32_t nwords = B >> 9;
-    if (wave == 0) {
-        const uint32_t wv = lane < nwords ? reinterpret_cast<const uint32_t *>(src + B)[lane] : 0u;
-        const uint32_t pc = __popc(wv);
-        const uint32_t incl = wave_incl_scan(pc, lane);
-        s_maskw[lane] = wv;
-        s_pre[lane] = incl - pc;
-    }
-    // low plane -> normalized bytes in LDS (undo the final byte interleave of Alg. 2)
-    if (M > 0) {
-        const uint8_t *slow = src + B + (B >> 7);
-        const uint32_t T2 = (M * B) >> 4;
-        for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
-            const uint4 q = *reinterpret_cast<const uint4 *>(slow + 16u * v);
-            uint2 ev, od;
-            ev.x = byte_perm(q.y, q.x, 0x06040200u);
-            ev.y = byte_perm(q.w, q.z, 0x06040200u);
-            od.x = byte_perm(q.y, q.x, 0x07050301u);
-            od.y = byte_perm(q.w, q.z, 0x07050301u);
-            *reinterpret_cast<uint2 *>(lds_low + 8u * v) = ev;
-            *reinterpret_cast<uint2 *>(lds_low + 8u * v + T2) = od;
-        }
-    }
-    if (A > 0) {
-        const uint8_t *shigh = src + fixed;
-        const uint32_t hbytes = (uint32_t)size - fixed;   // multiple of 16 by construction of `size` checks below
-        for (uint32_t v = tid; 16u * v + 16u <= hbytes; v += blockDim.x)
-            *reinterpret_cast<uint4 *>(lds_high + 16u * v) = *reinterpret_cast<const uint4 *>(shigh + 16u * v);
-    }
-    __syncthreads();
-    if (!active) return;
-
-    uint32_t Pl[MP][2];
+        for (int t = 0; t < 8; ++t)
+            smv[t] = active ? *reinterpret_cast<const uint2 *>(src + ((size_t)t << logC) + 8u * tid) : make_uint2(0, 0);
+        const uint32_t nvec = (size - B) >> 4;
 #pragma unroll
-    for (int q = 0; q < MP; ++q) {
-        if (M > 0) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(lds_low + ((size_t)q << logC) + 8u * tid);
-            Pl[q][0] = v.x; Pl[q][1] = v.y;
-        } else {
-            Pl[q][0] = Pl[q][1] = 0;
+        for (int i = 0; i < VMAX; ++i) {
+            const uint32_t v = tid + (uint32_t)i * blockDim.x;
+            vec[i] = v < nvec ? *reinterpret_cast<const uint4 *>(src + B + 16u * v) : make_uint4(0, 0, 0, 0);
         }
-    }
+    };
+    auto to_image = [&](uint8_t *img, const uint4 (&vec)[VMAX]) {
+#pragma unroll
+        for (int i = 0; i < VMAX; ++i) {
+            const uint32_t v = tid + (uint32_t)i * blockDim.x;
+            if (16u * v < img_bytes) *reinterpret_cast<uint4 *>(img + 16u * v) = vec[i];
+        }
+    };
 
+    uint32_t k = blockIdx.x;
+    uint64_t off = 0, offn = 0;
+    uint32_t size = 0, sizen = 0;
+    uint64_t ta = 0, tb = 0, tc = 0, td = 0;
+    fetch(k, ta, tb);
+    fetch(k + gridDim.x, tc, td);                           // the table is read one block ahead
+    bool valid = check(k, ta, tb, off, size);
+    bool validn = check(k + gridDim.x, tc, td, offn, sizen);
+    uint2 smc[8], smn[8];
+    uint4 vec[VMAX];
+    if (valid) {
+        issue(off, size, smc, vec);
+        to_image(smem, vec);
+    }
+    uint32_t slot = 0;
     const uint32_t crep = ((p.b + (1u << (N - 1))) & 0xFFu) * 0x01010101u;
-    const uint64_t blk0 = (uint64_t)k << p.logB;
-    const uint32_t par = tid & 1u;
     constexpr HHTable TL = HH<M>::table;
 
+    ENEC_TP_DECL;
+    while (k < p.nb) {
+        ENEC_TP(0);
+        __syncthreads();            // image[slot] is complete, image[slot ^ 1] is free
+        ENEC_TP(1);
+        // the next block's loads start now and are consumed at the end of the iteration
+        const uint32_t kn = k + gridDim.x;
+        if (validn) issue(offn, sizen, smn, vec);
+        fetch(kn + gridDim.x, ta, tb);
+        ENEC_TP(2);
+
+        if (valid && active) {
+            const uint8_t *img = smem + slot * img_bytes;
+            const uint8_t *img_low = img + (B >> 7);
+            const uint8_t *img_high = img_low + (((size_t)M * B) >> 3);
+            // d2: mask words and their exclusive popcount prefix (a wave scan per wave)
+            const uint32_t nwords = B >> 9;
+            const uint32_t my_word = lane < nwords ? reinterpret_cast<const uint32_t *>(img)[lane] : 0u;
+            const uint32_t my_pc = __popc(my_word);
+            const uint32_t my_excl = wave_incl_scan(my_pc, lane) - my_pc;
+
+            // low plane: the 8 normalized bytes of plane q for this thread's columns are every
+            // other byte of one 16-byte span of the stream (undoing the final join of Alg. 2)
+            uint32_t Pl[MP][2];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        uint32_t Y[2] = {0u, 0u};
-        // d3: low m bits of the 8 columns of this row
-        if (M > 0) {
-#pragma unroll
-            for (int f = 0; f < TL.count; ++f)
-                if (TL.row[f] == t) {
-                    const uint32_t smask = (TL.shift[f] >= 0 ? (TL.dmask[f] >> TL.shift[f])
-                                                            : (TL.dmask[f] << (-TL.shift[f]))) * 0x01010101u;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-                        Y[h] |= shl_or_shr(Pl[TL.plane[f]][h], -TL.shift[f]) & smask;
+            for (int q = 0; q < MP; ++q) {
+                if (M > 0) {
+                    const uint32_t T2 = (M * B) >> 4;
+                    const uint32_t i = ((uint32_t)q << logC) + 8u * tid;
+                    const bool even = i < T2;
+                    const uint4 sp = *reinterpret_cast<const uint4 *>(img_low + 2u * (even ? i : i - T2));
+                    const uint32_t sel = even ? 0x06040200u : 0x07050301u;
+                    Pl[q][0] = byte_perm(sp.y, sp.x, sel);
+                    Pl[q][1] = byte_perm(sp.w, sp.z, sel);
+                } else {
+                    Pl[q][0] = Pl[q][1] = 0;
                 }
-        }
-        // d2/d3: high bits of masked groups, found through the mask prefix
-        if (A > 0) {
-            constexpr HHTable TH = HH<A>::table;
-            const uint32_t g = ((uint32_t)t << (logC - 4)) + (tid >> 1);
-            const uint32_t wv = s_maskw[g >> 5];
-            if ((wv >> (g & 31u)) & 1u) {
-                const uint32_t rank = s_pre[g >> 5] + __popc(wv & ((1u << (g & 31u)) - 1u));
-                const uint16_t *rec = reinterpret_cast<const uint16_t *>(lds_high + 2u * A * rank);
-                uint32_t nbyte[2 * AP];
+            }
+            const uint64_t blk0 = (uint64_t)k << p.logB;
+            ENEC_TP(3);
 #pragma unroll
-                for (int i = 0; i < A; ++i) {
-                    const uint32_t w = rec[i];
-                    nbyte[i] = w & 0xFFu;
-                    nbyte[i + A] = w >> 8;
+            for (int t = 0; t < 8; ++t) {
+                uint32_t Y[2] = {0u, 0u};
+                // d3: low m bits of the 8 columns of this row
+                if (M > 0) {
+#pragma unroll
+                    for (int f = 0; f < TL.count; ++f)
+                        if (TL.row[f] == t) {
+                            const uint32_t smask = (TL.shift[f] >= 0 ? (TL.dmask[f] >> TL.shift[f])
+                                                                    : (TL.dmask[f] << (-TL.shift[f]))) * 0x01010101u;
+#pragma unroll
+                            for (int h = 0; h < 2; ++h)
+                                Y[h] |= shl_or_shr(Pl[TL.plane[f]][h], -TL.shift[f]) & smask;
+                        }
                 }
-                uint32_t P[AP];
+                // d2/d3: high bits of masked groups, found through the mask prefix
+                if (A > 0) {
+                    constexpr HHTable TH = HH<A>::table;
+                    const uint32_t g = ((uint32_t)t << (logC - 4)) + (tid >> 1);
+                    const uint32_t wv = __shfl(my_word, g >> 5, 64);
+                    const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+                    if ((wv >> (g & 31u)) & 1u) {
+                        const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+                        const uint16_t *rec = reinterpret_cast<const uint16_t *>(img_high + 2u * A * rank);
+                        uint32_t nbyte[2 * AP];
 #pragma unroll
-                for (int q = 0; q < A; ++q) P[q] = 0;
+                        for (int i = 0; i < A; ++i) {
+                            const uint32_t w = rec[i];
+                            nbyte[i] = w & 0xFFu;
+                            nbyte[i + A] = w >> 8;
+                        }
+                        uint32_t P[AP];
 #pragma unroll
-                for (int j = 0; j < 2 * A; ++j) P[j >> 1] |= nbyte[j] << (8 * (j & 1));
-                uint32_t E[8];
+                        for (int q = 0; q < A; ++q) P[q] = 0;
 #pragma unroll
-                for (int r = 0; r < 8; ++r) E[r] = 0;
+                        for (int j = 0; j < 2 * A; ++j) P[j >> 1] |= nbyte[j] << (8 * (j & 1));
+                        uint32_t E[8];
 #pragma unroll
-                for (int f = 0; f < TH.count; ++f) {
-                    const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
-                                                            : (TH.dmask[f] << (-TH.shift[f]))) * 0x0101u;
-                    E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
+                        for (int r = 0; r < 8; ++r) E[r] = 0;
+#pragma unroll
+                        for (int f = 0; f < TH.count; ++f) {
+                            const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
+                                                                    : (TH.dmask[f] << (-TH.shift[f]))) * 0x0101u;
+                            E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
+                        }
+                        // this lane's 8 elements are rows 4*par .. 4*par+3 of the two-column view
+                        const uint32_t h0 = par ? (E[4] | (E[5] << 16)) : (E[0] | (E[1] << 16));
+                        const uint32_t h1 = par ? (E[6] | (E[7] << 16)) : (E[2] | (E[3] << 16));
+                        Y[0] |= h0 << M;
+                        Y[1] |= h1 << M;
+                    }
                 }
-                // this lane's 8 elements are rows 4*par .. 4*par+3 of the two-column view
-                const uint32_t h0 = par ? (E[4] | (E[5] << 16)) : (E[0] | (E[1] << 16));
-                const uint32_t h1 = par ? (E[6] | (E[7] << 16)) : (E[2] | (E[3] << 16));
-                Y[0] |= h0 << M;
-                Y[1] |= h1 << M;
+                // d4: x = b - sext_n(y) = (b + 2^(n-1)) - (y ^ 2^(n-1)); recombine with sign/mantissa
+                uint32_t o[4];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t Z = Y[h] ^ SREP;
+                    const uint32_t X = p.mode == 0 ? crep - Z : bytesub_safe(crep, Z);
+                    const uint32_t sm = h ? smc[t].y : smc[t].x;
+                    const uint32_t Hi = bfi(0x7F7F7F7Fu, X >> 1, sm);
+                    const uint32_t Lo = bfi(0x7F7F7F7Fu, sm, X << 7);
+                    o[2 * h] = byte_perm(Hi, Lo, 0x05010400u);
+                    o[2 * h + 1] = byte_perm(Hi, Lo, 0x07030602u);
+                }
+                const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
+                if (e0 + 8 <= p.n_elems) {
+                    *reinterpret_cast<uint4 *>(p.out + e0) = make_uint4(o[0], o[1], o[2], o[3]);
+                } else if (e0 < p.n_elems) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (e0 + i < p.n_elems) p.out[e0 + i] = (uint16_t)(o[i >> 1] >> (16 * (i & 1)));
+                }
             }
         }
-        // d4: x = b - sext_n(y) = (b + 2^(n-1)) - (y ^ 2^(n-1)); recombine with sign/mantissa
-        uint32_t o[4];
+        ENEC_TP(4);
+        // the next block's packed part goes to the other image
+        if (validn) {
+            to_image(smem + (slot ^ 1u) * img_bytes, vec);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t Z = Y[h] ^ SREP;
-            const uint32_t X = p.mode == 0 ? crep - Z : bytesub_safe(crep, Z);
-            const uint32_t sm = h ? smv[t].y : smv[t].x;
-            const uint32_t Hi = bfi(0x7F7F7F7Fu, X >> 1, sm);
-            const uint32_t Lo = bfi(0x7F7F7F7Fu, sm, X << 7);
-            o[2 * h] = byte_perm(Hi, Lo, 0x05010400u);
-            o[2 * h + 1] = byte_perm(Hi, Lo, 0x07030602u);
+            for (int t = 0; t < 8; ++t) smc[t] = smn[t];
         }
-        const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
-        if (e0 + 8 <= p.n_elems) {
-            *reinterpret_cast<uint4 *>(p.out + e0) = make_uint4(o[0], o[1], o[2], o[3]);
-        } else if (e0 < p.n_elems) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (e0 + i < p.n_elems) p.out[e0 + i] = (uint16_t)(o[i >> 1] >> (16 * (i & 1)));
-        }
+        valid = validn;
+        validn = check(kn + gridDim.x, ta, tb, offn, sizen);
+        k = kn;
+        slot ^= 1u;
+        ENEC_TP(5);
+        ENEC_TP(6);
+        ENEC_TP(7);
+        ENEC_TP_FLUSH;
     }
 }
 
