@@ -2,8 +2,10 @@
 """Benchmark of the ENEC codec hot path on one MI355X.
 
 Workload (default): the synthetic 7B-style decoder layer (nine bf16 tensors, 404.8 MB), resident
-in HBM.  One step = compress all nine tensors, then decompress all nine (18 kernel launches, every
-row of the hot path).  Throughput counts uncompressed bytes, as the paper does (Sec. VI-B).
+in HBM.  One step = compress all nine tensors, then decompress all nine (every row of the hot
+path).  Throughput counts uncompressed bytes, as the paper does (Sec. VI-B).
+The tensors of a pass go to the library's batch entry points, one call per (n, m) tuple, which
+is one kernel launch each.
 
 Prints ONE JSON line.  `value` is the whole-step throughput: uncompressed bytes through the codec
 (compress pass + decompress pass) per second.  `compress_GBps` / `decompress_GBps` are the two
@@ -58,38 +60,46 @@ def main():
     srcs = [torch.from_numpy(w.view(np.int16)).cuda() for _, w in host]
     n_el = [w.size for _, w in host]
     raw_bytes = 2 * sum(n_el)
-    ws = enec.new_workspace(max(n_el))
+    ws = enec.new_workspace(sum(n_el))
     params = [enec.tune(s, ws) for s in srcs]                      # library tuner, not timed
     outs = [torch.zeros(enec.compress_bound(n), dtype=torch.uint8, device="cuda") for n in n_el]
     backs = [torch.zeros_like(s) for s in srcs]
     sizes = torch.zeros(len(srcs), dtype=torch.int64, device="cuda")
     nt = len(srcs)
 
-    per_launch = os.environ.get("BENCH_PASS_EVENTS_ONLY") is None
+    # tensors that share (n, m) go into one library call (= one kernel launch)
+    groups = {}
+    for i in range(nt):
+        groups.setdefault((params[i][1], params[i][2]), []).append(i)
+    groups = list(groups.values())
+    ng = len(groups)
 
     def compress_all(ev=None):
-        for i in range(nt):
-            if ev and (per_launch or i == 0):
-                ev[0][i].record()
-            rc = enec.compress(srcs[i], params[i], outs[i], ws, out_bytes=sizes[i:i + 1])
-            if ev and (per_launch or i == nt - 1):
-                ev[1][i].record()
+        if ev:
+            ev[0].record()
+        for gi, g in enumerate(groups):
+            rc = enec.compress_batch([srcs[i] for i in g], [params[i] for i in g], [outs[i] for i in g], ws,
+                                     out_bytes=[sizes[i:i + 1] for i in g])
             assert rc == 0, enec.strerror(rc)
+            if ev:
+                ev[gi + 1].record()
 
     compress_all()
     torch.cuda.synchronize()
     stream_bytes = [int(v) for v in sizes.cpu()]
     assert all(v > 0 for v in stream_bytes)
     headers = [outs[i][:64].cpu().numpy().tobytes() for i in range(nt)]
+    ditems = [enec.make_decompress_items([outs[i] for i in g], [headers[i] for i in g], [backs[i] for i in g])
+              for g in groups]
 
     def decompress_all(ev=None):
-        for i in range(nt):
-            if ev and (per_launch or i == 0):
-                ev[0][i].record()
-            rc = enec.decompress_with_header(outs[i], headers[i], backs[i])
-            if ev and (per_launch or i == nt - 1):
-                ev[1][i].record()
+        if ev:
+            ev[0].record()
+        for gi, g in enumerate(groups):
+            rc = enec.decompress_batch(None, None, None, items=ditems[gi][0])
             assert rc == 0, enec.strerror(rc)
+            if ev:
+                ev[gi + 1].record()
 
     decompress_all()
     torch.cuda.synchronize()
@@ -97,7 +107,7 @@ def main():
         assert torch.equal(backs[i], srcs[i]), f"round trip of {names[i]} is not bit-exact"
 
     def new_events():
-        return [[torch.cuda.Event(enable_timing=True) for _ in range(nt)] for _ in range(2)]
+        return [torch.cuda.Event(enable_timing=True) for _ in range(ng + 1)]
 
     evc = [new_events() for _ in range(args.steps)]
     evd = [new_events() for _ in range(args.steps)]
@@ -116,31 +126,28 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = 2 * raw_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # per-launch durations from the events recorded inside the timed region
-    if per_launch:
-        dur_c = np.array([[evc[k][0][i].elapsed_time(evc[k][1][i]) for i in range(nt)] for k in range(args.steps)])
-        dur_d = np.array([[evd[k][0][i].elapsed_time(evd[k][1][i]) for i in range(nt)] for k in range(args.steps)])
-    else:
-        dur_c = dur_d = np.ones((args.steps, nt))
-    # whole pass: first launch start to last launch end
-    pass_c = np.array([evc[k][0][0].elapsed_time(evc[k][1][nt - 1]) for k in range(args.steps)])
-    pass_d = np.array([evd[k][0][0].elapsed_time(evd[k][1][nt - 1]) for k in range(args.steps)])
+    # per-launch durations from the events recorded inside the timed region (one launch per group)
+    dur_c = np.array([[evc[k][gi].elapsed_time(evc[k][gi + 1]) for gi in range(ng)] for k in range(args.steps)])
+    dur_d = np.array([[evd[k][gi].elapsed_time(evd[k][gi + 1]) for gi in range(ng)] for k in range(args.steps)])
+    pass_c = np.array([evc[k][0].elapsed_time(evc[k][ng]) for k in range(args.steps)])
+    pass_d = np.array([evd[k][0].elapsed_time(evd[k][ng]) for k in range(args.steps)])
     comp_gbps = raw_bytes / (np.median(pass_c) * 1e-3) / 1e9
     decomp_gbps = raw_bytes / (np.median(pass_d) * 1e-3) / 1e9
 
     # ---- roofline of the dominant kernel ------------------------------------------------
-    # algorithmic bytes of one launch = bf16 tensor (2 bytes/element) + its whole stream
-    # (sign/mantissa plane, mask, packed planes, offset table, header), read or written once
-    groups = {}
-    for i in range(nt):
-        m, a = params[i][2], params[i][1] - params[i][2]
+    # algorithmic bytes of one launch = for each of its tensors the bf16 data (2 bytes/element) plus
+    # the whole stream (sign/mantissa plane, mask, packed planes, offset table, header), each read
+    # or written once
+    kern = {}
+    for gi, g in enumerate(groups):
+        m, a = params[g[0]][2], params[g[0]][1] - params[g[0]][2]
+        moved = sum(2 * n_el[i] + stream_bytes[i] for i in g)
         for kind, dur in (("compress", dur_c), ("decompress", dur_d)):
-            g = groups.setdefault(f"enec::{kind}_kernel<{m},{a}>", dict(ms=0.0, bytes=0, launches=0))
-            g["ms"] += float(dur[:, i].sum())
-            g["bytes"] += (2 * n_el[i] + stream_bytes[i]) * args.steps
-            g["launches"] += args.steps
-    dom = max(groups, key=lambda k: groups[k]["ms"])
-    gd = groups[dom]
+            kern[f"enec::{kind}_kernel<{m},{a}>"] = dict(
+                ms=float(dur[:, gi].sum()), bytes=moved * args.steps, launches=args.steps,
+                tensors=[names[i] for i in g])
+    dom = max(kern, key=lambda k: kern[k]["ms"])
+    gd = kern[dom]
     achieved = gd["bytes"] / (gd["ms"] * 1e-3) / 1e9
     roofline = {
         "kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -151,8 +158,10 @@ def main():
     }
     per_kernel = {k: {"GBps_moved": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1),
                       "frac_of_hbm_peak": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                      "avg_launch_us": round(v["ms"] * 1e3 / v["launches"], 2), "launches": v["launches"]}
-                  for k, v in sorted(groups.items())}
+                      "avg_launch_us": round(v["ms"] * 1e3 / v["launches"], 2), "launches": v["launches"],
+                      "tensors_per_launch": len(v["tensors"])}
+                  for k, v in sorted(kern.items())}
+    moved_total = raw_bytes + sum(stream_bytes)
 
     # practical ceiling: the library's plain 128-bit copy on a buffer of the layer's size
     cp_src, cp_dst = srcs[4].view(torch.uint8), backs[4].view(torch.uint8)
@@ -195,6 +204,8 @@ def main():
         "config": {"workload": wl_name, "tensors": nt, "uncompressed_bytes": raw_bytes,
                    "block_size": 16384, "params": {names[i]: list(params[i]) for i in range(nt)}},
         "compress_GBps": round(comp_gbps, 1), "decompress_GBps": round(decomp_gbps, 1),
+        "compress_frac_of_hbm_peak": round(moved_total / (np.median(pass_c) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "decompress_frac_of_hbm_peak": round(moved_total / (np.median(pass_d) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "compression_ratio": round(ratio, 4),
         "compress_ms": round(float(np.median(pass_c)), 4), "decompress_ms": round(float(np.median(pass_d)), 4),
         "copy_kernel_GBps_moved": round(copy_gbps, 1),

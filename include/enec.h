@@ -83,13 +83,14 @@ uint32_t enec_default_block_size(size_t n_elems);
 size_t enec_compress_bound(size_t n_elems, int dtype, uint32_t block_size);
 
 /* Size in bytes of the DEVICE workspace enec_compress / enec_tune need for a tensor of n_elems
- * elements (inter-block scan state, completion counters, histogram).  A workspace sized for a larger
- * tensor serves smaller ones.  Returns 0 on invalid block_size. */
+ * elements (inter-block scan state, ticket counters, histogram), or for a batch of up to 16 tensors
+ * with n_elems elements in total.  A workspace sized for a larger tensor serves smaller ones.
+ * Returns 0 on invalid block_size. */
 size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size);
 
 /* Enqueues a fill kernel that zeroes `bytes` bytes of the DEVICE workspace.  Must run once after
- * the workspace is allocated; every later library call leaves the workspace zeroed again, so one
- * workspace can be reused by any number of calls that do not overlap in time.  16-byte aligned. */
+ * the workspace is allocated; after that one workspace serves any number of calls that do not
+ * overlap in time (the library keeps its counters and call tags in it).  16-byte aligned. */
 int enec_workspace_init(void *workspace, size_t bytes, void *stream);
 
 /* Compress n_elems bf16 values [Sec. V-A compression path; Sec. V-B; Sec. V-C; Fig. 4].
@@ -116,6 +117,25 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
                   const enec_params *params, void *out, size_t out_capacity,
                   uint64_t *out_bytes, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Compress several tensors with as few kernel launches as possible: tensors that share (m, n - m,
+ * block size) go into one launch, whose workgroups walk the data blocks of all of them, so that
+ * small tensors cost no launch of their own and the device never drains between tensors.
+ * Every field of an item means what the argument of the same name means for enec_compress
+ * (params == NULL tunes that tensor first, which makes the call synchronous).  The workspace
+ * must hold enec_workspace_bytes(sum of the items' n_elems, block size).  Items are independent:
+ * a range error in one is reported in that item's header only. */
+typedef struct {
+    const void *in;             /* DEVICE */
+    size_t n_elems;
+    uint32_t block_size;        /* 0 = default */
+    const enec_params *params;  /* HOST, or NULL */
+    void *out;                  /* DEVICE */
+    size_t out_capacity;
+    uint64_t *out_bytes;        /* device-accessible, or NULL */
+} enec_compress_item;
+int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
 /* Decompress [Sec. V-A decompression path; Alg. 1 decompression part].
  *   in        DEVICE, a stream written by enec_compress, 16-byte aligned
  *   in_bytes  size of the buffer behind `in`; ENEC_E_FORMAT if the header's total_bytes exceeds it.
@@ -131,6 +151,17 @@ int enec_decompress(const void *in, size_t in_bytes, void *out, size_t n_elems, 
  * the header in device memory and writes nothing if they differ. */
 int enec_decompress_with_header(const void *in, size_t in_bytes, const void *host_header, void *out,
                                 size_t n_elems, void *stream);
+
+/* Decompress several streams with one launch per (m, n - m, block size); fields as the arguments of
+ * enec_decompress_with_header.  Fully asynchronous. */
+typedef struct {
+    const void *in;             /* DEVICE */
+    size_t in_bytes;
+    const void *host_header;    /* HOST, 64 bytes */
+    void *out;                  /* DEVICE */
+    size_t n_elems;
+} enec_decompress_item;
+int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, void *stream);
 
 /* Parameter tuning [Sec. V-E phases 1-3]: exponent histogram on the device (one read of the
  * tensor), then the search for (b, n) by Eq. 1-3 and for m by Eq. 4 (L = 16) on the host.

@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
+#include <vector>
 
 namespace {
 
@@ -15,7 +16,6 @@ using namespace enec;
 // group words | block words (the last two sized by the call's block count)
 constexpr size_t WS_CTL = 0, WS_HIST = 1024, WS_STATE = WS_HIST + 256 * 8;
 inline size_t ws_groups(size_t nb) { return (nb + 63) / 64; }
-inline size_t ws_block_off(size_t nb) { return WS_STATE + 8 * ws_groups(nb); }
 constexpr size_t MAX_ELEMS = (size_t)1 << 34;      // keeps every offset below 2^36 bytes
 
 inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
@@ -159,9 +159,9 @@ size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size)
 {
     const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
     if (!block_ok(B)) return 0;
-    size_t nb = num_blocks(n_elems, B);
-    if (nb == 0) nb = 1;
-    return (ws_block_off(nb) + 8 * nb + 255) & ~(size_t)255;
+    // room for the scan words of up to MAX_BATCH tensors with n_elems elements in total
+    const size_t nb = num_blocks(n_elems, B) + MAX_BATCH;
+    return (WS_STATE + 8 * (ws_groups(nb) + MAX_BATCH + nb) + 255) & ~(size_t)255;
 }
 
 int enec_workspace_init(void *workspace, size_t bytes, void *stream)
@@ -239,60 +239,160 @@ int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params, ui
     return enec_tune_histogram(host_hist, params);
 }
 
+int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    if (dtype != ENEC_BF16) return ENEC_E_DTYPE;
+    if (!items || !workspace || !aligned16(workspace)) return ENEC_E_ARG;
+    hipStream_t s = (hipStream_t)stream;
+
+    // ---- every check that can be made on the host, before anything is enqueued -------------
+    struct Prepared { enec_params prm; uint32_t B; uint32_t nb; };
+    std::vector<Prepared> prep(n_items);
+    size_t state_words = 0;
+    for (size_t i = 0; i < n_items; ++i) {
+        const enec_compress_item &it = items[i];
+        if (!it.out || (!it.in && it.n_elems) || !aligned16(it.in) || !aligned16(it.out) ||
+            it.n_elems > MAX_ELEMS || ((uintptr_t)it.out_bytes & 7))
+            return ENEC_E_ARG;
+        const uint32_t B = it.block_size ? it.block_size : enec_default_block_size(it.n_elems);
+        if (!block_ok(B)) return ENEC_E_BLOCK;
+        prep[i].B = B;
+        prep[i].nb = (uint32_t)num_blocks(it.n_elems, B);
+        state_words += ws_groups(prep[i].nb) + prep[i].nb;
+    }
+    if (workspace_bytes < WS_STATE + 8 * state_words) return ENEC_E_CAPACITY;
+    for (size_t i = 0; i < n_items; ++i) {
+        const enec_compress_item &it = items[i];
+        if (it.params) {
+            prep[i].prm = *it.params;
+        } else {
+            int rc = enec_tune(it.in, it.n_elems, dtype, &prep[i].prm, nullptr, workspace, workspace_bytes, stream);
+            if (rc != ENEC_OK) return rc;
+        }
+        const enec_params &prm = prep[i].prm;
+        if (prm.n < 1 || prm.n > 8 || prm.m > prm.n || prm.L != 16) return ENEC_E_PARAMS;
+        if (it.out_capacity < enec_compress_bound(it.n_elems, dtype, prep[i].B)) return ENEC_E_CAPACITY;
+        if (it.out_bytes && !device_accessible(it.out_bytes)) return ENEC_E_ARG;
+    }
+
+    // ---- one launch per group of tensors that share (m, n - m, block size) ------------------
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    std::vector<char> done(n_items, 0);
+    for (size_t i = 0; i < n_items; ++i) {
+        if (done[i]) continue;
+        if (prep[i].nb == 0) {
+            compress_empty_kernel<<<1, 64, 0, s>>>(static_cast<uint8_t *>(items[i].out), items[i].out_bytes,
+                                                   prep[i].B, prep[i].prm.b, prep[i].prm.n, prep[i].prm.m);
+            done[i] = 1;
+            continue;
+        }
+        CompressArgs a;
+        a.ws_ctl = reinterpret_cast<uint32_t *>(ws + WS_CTL);
+        a.B = prep[i].B;
+        a.logB = ilog2(a.B);
+        a.n_items = 0;
+        a.total = 0;
+        size_t word = 0;      // scan words handed out to this launch (tags make reuse between launches safe)
+        for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
+            if (done[j] || prep[j].nb == 0 || prep[j].B != a.B || prep[j].prm.m != prep[i].prm.m ||
+                prep[j].prm.n != prep[i].prm.n)
+                continue;
+            CompressItem &c = a.item[a.n_items++];
+            c.in = static_cast<const uint16_t *>(items[j].in);
+            c.out = static_cast<uint8_t *>(items[j].out);
+            c.out_bytes = items[j].out_bytes;
+            c.ws_group = reinterpret_cast<uint64_t *>(ws + WS_STATE) + word;
+            word += ws_groups(prep[j].nb);
+            c.ws_block = reinterpret_cast<uint64_t *>(ws + WS_STATE) + word;
+            word += prep[j].nb;
+            c.n_elems = items[j].n_elems;
+            c.payload_base = payload_base(items[j].n_elems, a.B);
+            c.nb = prep[j].nb;
+            c.first = a.total;
+            c.b = prep[j].prm.b;
+            const unsigned cc = prep[j].prm.b + (1u << (prep[j].prm.n - 1));
+            const bool plain = cc <= 255 && cc >= (1u << prep[j].prm.n) - 1u;
+            c.mode = plain ? 0u : (prep[j].prm.n == 8 ? 1u : 2u);
+            a.total += c.nb;
+            done[j] = 1;
+        }
+        CompressFn fn = pick_compress(prep[i].prm.m, prep[i].prm.n - prep[i].prm.m);
+        if (!fn) return ENEC_E_PARAMS;
+        const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
+        const size_t lds = 2 * ((size_t)a.B / 128 + (size_t)prep[i].prm.n * a.B / 8);    // two images of the packed part
+        const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_COMPRESS_WGS_PER_CU");
+        if (resident == 0) return ENEC_E_HIP;
+        const unsigned grid = a.total < resident ? a.total : resident;
+        a.ncls = grid < 8 ? grid : 8;
+        a.lookahead = a.total >= 2 * grid ? 1u : 0u;
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
+    }
+    return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+}
+
 int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size,
                   const enec_params *params, void *out, size_t out_capacity, uint64_t *out_bytes,
                   void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (dtype != ENEC_BF16) return ENEC_E_DTYPE;
-    if (!out || !workspace || (!in && n_elems) || !aligned16(in) || !aligned16(out) ||
-        !aligned16(workspace) || n_elems > MAX_ELEMS || ((uintptr_t)out_bytes & 7))
-        return ENEC_E_ARG;
-    const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
-    if (!block_ok(B)) return ENEC_E_BLOCK;
-    if (workspace_bytes < enec_workspace_bytes(n_elems, B)) return ENEC_E_CAPACITY;
-    enec_params prm;
-    if (params) {
-        prm = *params;
-    } else {
-        int rc = enec_tune(in, n_elems, dtype, &prm, nullptr, workspace, workspace_bytes, stream);
+    enec_compress_item it;
+    it.in = in; it.n_elems = n_elems; it.block_size = block_size; it.params = params;
+    it.out = out; it.out_capacity = out_capacity; it.out_bytes = out_bytes;
+    return enec_compress_batch(&it, 1, dtype, workspace, workspace_bytes, stream);
+}
+
+int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, void *stream)
+{
+    if (!items) return ENEC_E_ARG;
+    std::vector<Header> hdr(n_items);
+    for (size_t i = 0; i < n_items; ++i) {
+        const enec_decompress_item &it = items[i];
+        if (!it.in || !it.host_header || (!it.out && it.n_elems) || !aligned16(it.in) || !aligned16(it.out))
+            return ENEC_E_ARG;
+        Header &h = hdr[i];
+        int rc = parse_header(it.host_header, &h);
         if (rc != ENEC_OK) return rc;
+        if (h.dtype != ENEC_BF16) return ENEC_E_DTYPE;
+        if (h.status != ENEC_OK || h.n_elems != it.n_elems || !block_ok(h.B) || it.n_elems > MAX_ELEMS ||
+            h.nb != num_blocks(it.n_elems, h.B) || h.prm.n < 1 || h.prm.n > 8 || h.prm.m > h.prm.n ||
+            h.total < payload_base(it.n_elems, h.B) || h.total > it.in_bytes)
+            return ENEC_E_FORMAT;
     }
-    if (prm.n < 1 || prm.n > 8 || prm.m > prm.n || prm.L != 16) return ENEC_E_PARAMS;
-    if (out_capacity < enec_compress_bound(n_elems, dtype, B)) return ENEC_E_CAPACITY;
-    if (out_bytes && !device_accessible(out_bytes)) return ENEC_E_ARG;
-
-    uint8_t *ws = static_cast<uint8_t *>(workspace);
-    CompressArgs a;
-    a.in = static_cast<const uint16_t *>(in);
-    a.out = static_cast<uint8_t *>(out);
-    a.n_elems = n_elems;
-    a.payload_base = payload_base(n_elems, B);
-    a.nb = (uint32_t)num_blocks(n_elems, B);
-    a.ws_group = reinterpret_cast<uint64_t *>(ws + WS_STATE);
-    a.ws_block = reinterpret_cast<uint64_t *>(ws + ws_block_off(a.nb));
-    a.ws_ctl = reinterpret_cast<uint32_t *>(ws + WS_CTL);
-    a.out_bytes = out_bytes;
-    a.B = B;
-    a.logB = ilog2(B);
-    a.b = prm.b;
-    const unsigned c = prm.b + (1u << (prm.n - 1));
-    const bool plain = c <= 255 && c >= (1u << prm.n) - 1u;
-    a.mode = plain ? 0u : (prm.n == 8 ? 1u : 2u);
-
-    hipStream_t s = (hipStream_t)stream;
-    if (a.nb == 0) {
-        compress_empty_kernel<<<1, 64, 0, s>>>(a, prm.n, prm.m);
-    } else {
-        CompressFn fn = pick_compress(prm.m, prm.n - prm.m);
-        if (!fn) return ENEC_E_PARAMS;
-        const unsigned threads = B / 64 < 64 ? 64 : B / 64;
-        const size_t lds = 2 * ((size_t)B / 128 + (size_t)prm.n * B / 8);    // two images of the packed part
-        const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_COMPRESS_WGS_PER_CU");
+    std::vector<char> done(n_items, 0);
+    for (size_t i = 0; i < n_items; ++i) {
+        if (done[i]) continue;
+        if (hdr[i].nb == 0) { done[i] = 1; continue; }
+        DecompressArgs a;
+        a.B = hdr[i].B;
+        a.logB = ilog2(a.B);
+        a.n_items = 0;
+        a.total = 0;
+        for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
+            const Header &h = hdr[j];
+            if (done[j] || h.nb == 0 || h.B != a.B || h.prm.m != hdr[i].prm.m || h.prm.n != hdr[i].prm.n) continue;
+            DecompressItem &c = a.item[a.n_items++];
+            c.in = static_cast<const uint8_t *>(items[j].in);
+            c.out = static_cast<uint16_t *>(items[j].out);
+            c.n_elems = items[j].n_elems;
+            c.payload_base = payload_base(items[j].n_elems, h.B);
+            c.payload_bytes = h.total - c.payload_base;
+            c.nb = h.nb;
+            c.first = a.total;
+            c.b = h.prm.b;
+            const unsigned cc = h.prm.b + (1u << (h.prm.n - 1));
+            c.mode = (cc <= 255 && cc >= (1u << h.prm.n) - 1u) ? 0u : 1u;
+            std::memcpy(c.hdr, items[j].host_header, sizeof c.hdr);
+            a.total += c.nb;
+            done[j] = 1;
+        }
+        DecompressFn fn = pick_decompress(hdr[i].prm.m, hdr[i].prm.n - hdr[i].prm.m);
+        if (!fn) return ENEC_E_FORMAT;
+        const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
+        const size_t lds = 2 * ((size_t)a.B / 128 + (size_t)hdr[i].prm.n * a.B / 8);    // two images of the packed part
+        const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_DECOMPRESS_WGS_PER_CU");
         if (resident == 0) return ENEC_E_HIP;
-        const unsigned grid = a.nb < resident ? a.nb : resident;
-        a.ncls = grid < 8 ? grid : 8;
-        a.lookahead = a.nb >= 2 * grid ? 1u : 0u;
-        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
+        const unsigned grid = a.total < resident ? a.total : resident;
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, (hipStream_t)stream, a);
     }
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
@@ -300,40 +400,9 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
 int enec_decompress_with_header(const void *in, size_t in_bytes, const void *host_header, void *out,
                                 size_t n_elems, void *stream)
 {
-    if (!in || !host_header || (!out && n_elems) || !aligned16(in) || !aligned16(out)) return ENEC_E_ARG;
-    Header h;
-    int rc = parse_header(host_header, &h);
-    if (rc != ENEC_OK) return rc;
-    if (h.dtype != ENEC_BF16) return ENEC_E_DTYPE;
-    if (h.status != ENEC_OK || h.n_elems != n_elems || !block_ok(h.B) || n_elems > MAX_ELEMS ||
-        h.nb != num_blocks(n_elems, h.B) || h.prm.n < 1 || h.prm.n > 8 || h.prm.m > h.prm.n ||
-        h.total < payload_base(n_elems, h.B) || h.total > in_bytes)
-        return ENEC_E_FORMAT;
-    if (h.nb == 0) return ENEC_OK;
-
-    DecompressArgs a;
-    a.in = static_cast<const uint8_t *>(in);
-    a.out = static_cast<uint16_t *>(out);
-    a.n_elems = n_elems;
-    a.payload_base = payload_base(n_elems, h.B);
-    a.payload_bytes = h.total - a.payload_base;
-    a.B = h.B;
-    a.logB = ilog2(h.B);
-    a.nb = h.nb;
-    a.b = h.prm.b;
-    const unsigned c = h.prm.b + (1u << (h.prm.n - 1));
-    a.mode = (c <= 255 && c >= (1u << h.prm.n) - 1u) ? 0u : 1u;
-    std::memcpy(a.hdr, host_header, sizeof a.hdr);
-
-    DecompressFn fn = pick_decompress(h.prm.m, h.prm.n - h.prm.m);
-    if (!fn) return ENEC_E_FORMAT;
-    const unsigned threads = h.B / 64 < 64 ? 64 : h.B / 64;
-    const size_t lds = 2 * ((size_t)h.B / 128 + (size_t)h.prm.n * h.B / 8);    // two images of the packed part
-    const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_DECOMPRESS_WGS_PER_CU");
-    if (resident == 0) return ENEC_E_HIP;
-    const unsigned grid = a.nb < resident ? a.nb : resident;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, (hipStream_t)stream, a);
-    return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+    enec_decompress_item it;
+    it.in = in; it.in_bytes = in_bytes; it.host_header = host_header; it.out = out; it.n_elems = n_elems;
+    return enec_decompress_batch(&it, 1, stream);
 }
 
 int enec_decompress(const void *in, size_t in_bytes, void *out, size_t n_elems, void *stream)

@@ -208,38 +208,58 @@ __device__ __forceinline__ void spin_pause(uint32_t spins)
     else __builtin_amdgcn_s_sleep(64);
 }
 
-struct CompressArgs {
+// One launch handles up to MAX_BATCH tensors that share (m, n - m, block size): their data blocks
+// form one global sequence (tensor after tensor), item[i].first is the global index of tensor i's
+// first block.
+constexpr int MAX_BATCH = 16;
+
+struct CompressItem {
     const uint16_t *in;
     uint8_t *out;
-    uint64_t n_elems;
-    uint64_t payload_base;
+    uint64_t *out_bytes;    // device-accessible or null
     uint64_t *ws_block;     // nb block words
     uint64_t *ws_group;     // ceil(nb / 64) group words
-    uint32_t *ws_ctl;       // WS_CLASSES control records
-    uint64_t *out_bytes;    // device-accessible or null
-    uint32_t B, logB, nb;
+    uint64_t n_elems;
+    uint64_t payload_base;
+    uint32_t nb, first;
     uint32_t b, mode;       // mode 0: window clear of 0 and 255; 1: n = 8; 2: window touches an end
-    uint32_t ncls;          // number of block classes = min(8, gridDim.x)
-    uint32_t lookahead;     // draw the next ticket while working on the current block
 };
 
-struct DecompressArgs {
+struct CompressArgs {
+    uint32_t *ws_ctl;       // WS_CLASSES control records
+    uint32_t B, logB;
+    uint32_t total;         // data blocks of all items
+    uint32_t ncls;          // number of block classes = min(8, gridDim.x)
+    uint32_t lookahead;     // draw the next ticket while working on the current block
+    uint32_t n_items;
+    CompressItem item[MAX_BATCH];
+};
+
+struct DecompressItem {
     const uint8_t *in;
     uint16_t *out;
     uint64_t n_elems;
     uint64_t payload_base;
     uint64_t payload_bytes; // total_bytes - payload_base
-    uint32_t B, logB, nb;
+    uint32_t nb, first;
     uint32_t b, mode;       // mode 0: plain byte subtract is exact; 1: borrow-safe subtract
     uint32_t hdr[10];       // first 40 bytes of the expected header
 };
 
+struct DecompressArgs {
+    uint32_t B, logB;
+    uint32_t total;
+    uint32_t n_items;
+    DecompressItem item[MAX_BATCH];
+};
+
 // a1: 128-bit loads of the 8 rows of data block k (pad elements beyond the tensor's end)
-__device__ __forceinline__ void load_block_rows(const CompressArgs &p, uint32_t k, uint32_t tid, bool active,
-                                                uint32_t logC, uint32_t padw, uint4 (&raw)[8])
+__device__ __forceinline__ void load_block_rows(const CompressItem &p, uint32_t B, uint32_t logB, uint32_t k,
+                                                uint32_t tid, bool active, uint32_t logC, uint4 (&raw)[8])
 {
-    const uint64_t blk0 = (uint64_t)k << p.logB;
-    if (blk0 + p.B <= p.n_elems) {               // whole block inside the tensor: no per-row tests
+    const uint64_t blk0 = (uint64_t)k << logB;
+    const uint32_t padw = (p.b << 7) * 0x00010001u;   // a pad element has exponent b: y = 0, sm = 0
+    if (blk0 + B <= p.n_elems) {               // whole block inside the tensor: no per-row tests
 #pragma unroll
         for (int t = 0; t < 8; ++t)
             raw[t] = active ? *reinterpret_cast<const uint4 *>(p.in + blk0 + ((uint64_t)t << logC) + 8u * tid)
@@ -292,13 +312,12 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
     const uint32_t img_bytes = (B >> 7) + (((uint32_t)N * B) >> 3);
-    const uint32_t padw = (p.b << 7) * 0x00010001u;   // a pad element has exponent b: y = 0, sm = 0
     const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
 
     // ---- control record of this workgroup's class (thread 0) ---------------------------
     const uint32_t home = blockIdx.x % p.ncls;
     uint32_t *ctl = p.ws_ctl + WS_STRIDE * home;
-    const uint32_t class_blocks = home < p.nb ? (p.nb - home + p.ncls - 1u) / p.ncls : 0u;
+    const uint32_t class_blocks = home < p.total ? (p.total - home + p.ncls - 1u) / p.ncls : 0u;
     const uint32_t class_wgs = (gridDim.x - home + p.ncls - 1u) / p.ncls;
     uint32_t ticket_base = 0, zero = 0;
     uint64_t tag0 = 0;
@@ -326,24 +345,30 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         s_status = 0;
     }
     __syncthreads();
-    uint32_t k = s_k[0];
+    uint32_t k = __builtin_amdgcn_readfirstlane(s_k[0]);     // global block index
     const uint64_t tag = (uint64_t)s_tag << 24;
     uint32_t slot = 0;
+    // tensor that global block kg belongs to, searching upwards from item c
+    auto item_of = [&](uint32_t kg, uint32_t c) -> uint32_t {
+        while (c + 1u < p.n_items && kg >= p.item[c + 1u].first) ++c;
+        return c;
+    };
+    uint32_t ci = 0;                                         // item of the current block
     uint4 raw[8];
-    if (k != NO_BLOCK) load_block_rows(p, k, tid, active, logC, padw, raw);
-
-    const uint32_t crep = ((p.b + (1u << (N - 1))) & 0xFFu) * 0x01010101u;
-    const uint32_t xlo = p.b + 1u > (1u << (N - 1)) ? p.b + 1u - (1u << (N - 1)) : 0u;
-    const uint32_t xhi = p.b + (1u << (N - 1)) < 255u ? p.b + (1u << (N - 1)) : 255u;
+    if (k != NO_BLOCK) {
+        ci = item_of(k, 0);
+        load_block_rows(p.item[ci], B, p.logB, k - p.item[ci].first, tid, active, logC, raw);
+    }
     constexpr HHTable TL = HH<M>::table;
 
-    // wave 0 carries the scan: sum of the group words [0, groups_summed) and errors seen so far
+    // wave 0 carries the scan of one tensor: sum of its group words [0, groups_summed) and what
+    // went wrong so far (bit 1 range error in an earlier block, bit 2 gave up waiting)
     uint64_t groups_sum = 0;
-    uint32_t groups_summed = 0, scan_flags = 0;       // bit 1 earlier range error, bit 2 gave up
+    uint32_t groups_summed = 0, scan_flags = 0, scan_item = NO_BLOCK;
 
     // sum of the (valid) words base[0 .. count), count <= 64, one word per lane; `v` may hold a
     // copy read earlier (have = true), words that were not valid yet are read again until they are
-    auto sum_words = [&](const uint64_t *base, uint32_t count, bool have, uint64_t v) -> uint64_t {
+    auto sum_words = [&](const uint64_t *base, uint32_t count, bool have, uint64_t v, uint32_t &flags) -> uint64_t {
         const bool need = lane < count;
         bool ok = !need || (have && (v & ~0xFFFFFFull) == tag);
         uint32_t spins = 0;
@@ -353,37 +378,39 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                 ok = (v & ~0xFFFFFFull) == tag;
             }
             if (__builtin_amdgcn_ballot_w64(!ok) == 0) break;
-            if (++spins > SPIN_LIMIT) { scan_flags |= 4u; v = 0; break; }      // never hang
+            if (++spins > SPIN_LIMIT) { flags |= 4u; v = 0; break; }           // never hang
             spin_pause(spins);
         }
-        if (__builtin_amdgcn_ballot_w64(need && (v & ST_ERR))) scan_flags |= 2u;
+        if (__builtin_amdgcn_ballot_w64(need && (v & ST_ERR))) flags |= 2u;
         return wave_sum(need ? (v & ST_VALUE) : 0ull);
     };
     // start of block kb (wave 0; own_group = sum of the earlier block words of its group if known;
     // early_g / early_b = copies of the first needed group words / of the block words read earlier)
-    auto block_start = [&](uint32_t kb, bool have_own, uint64_t own_group, bool early, uint64_t early_g,
-                           uint64_t early_b) -> uint64_t {
+    auto block_start = [&](const CompressItem &it, uint32_t kb, bool have_own, uint64_t own_group, bool early,
+                           uint64_t early_g, uint64_t early_b) -> uint64_t {
         const uint32_t g = kb >> 6;
         while (groups_summed < g) {
             const uint32_t c = g - groups_summed < 64u ? g - groups_summed : 64u;
-            groups_sum += sum_words(p.ws_group + groups_summed, c, early, early_g);
+            groups_sum += sum_words(it.ws_group + groups_summed, c, early, early_g, scan_flags);
             groups_summed += c;
             early = false;
         }
-        if (!have_own) own_group = sum_words(p.ws_block + ((uint64_t)g << 6), kb & 63u, early_b != 0, early_b);
+        if (!have_own)
+            own_group = sum_words(it.ws_block + ((uint64_t)g << 6), kb & 63u, early_b != 0, early_b, scan_flags);
         return (groups_sum + own_group) << 4;
     };
 
     // the block waiting to be stored
-    uint32_t pend = NO_BLOCK, pend_cnt = 0, pend_S = 0, pend_err = 0;
+    uint32_t pend = NO_BLOCK, pend_item = 0, pend_cnt = 0, pend_S = 0, pend_err = 0;   // pend: index inside its tensor
     bool pend_have_own = false;
     uint64_t pend_own = 0;
     uint32_t SMp[8][2];
 
     // stores block `kb` whose packed part sits in image `img` and whose sign/mantissa bytes sit in SMp
-    auto store_block = [&](uint32_t kb, uint32_t cnt, uint32_t S, const uint8_t *img, uint32_t err_own) {
+    auto store_block = [&](const CompressItem &it, uint32_t kb, uint32_t cnt, uint32_t S, const uint8_t *img,
+                           uint32_t err_own) {
         const uint64_t off = s_off;
-        uint8_t *dst = p.out + p.payload_base + off;
+        uint8_t *dst = it.out + it.payload_base + off;
         if (active) {
 #pragma unroll
             for (int t = 0; t < 8; ++t)
@@ -423,26 +450,26 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             }
         }
         if (tid == 0) {
-            uint64_t *table = reinterpret_cast<uint64_t *>(p.out + 64);
+            uint64_t *table = reinterpret_cast<uint64_t *>(it.out + 64);
             table[kb] = off;
-            if (kb == p.nb - 1u) {
+            if (kb == it.nb - 1u) {
                 const uint64_t end = off + S;
                 const uint32_t fl = s_status | err_own;
                 const uint32_t status = (fl & 4u) ? 8u : ((fl & 3u) ? 6u : 0u);
-                const uint64_t total = status ? 0ull : p.payload_base + end;
-                table[p.nb] = end;
-                if (((uint64_t)(p.nb + 1u) & 1ull)) table[p.nb + 1u] = 0;   // pad up to the payload base
-                uint32_t *h = reinterpret_cast<uint32_t *>(p.out);
+                const uint64_t total = status ? 0ull : it.payload_base + end;
+                table[it.nb] = end;
+                if (((uint64_t)(it.nb + 1u) & 1ull)) table[it.nb + 1u] = 0;   // pad up to the payload base
+                uint32_t *h = reinterpret_cast<uint32_t *>(it.out);
                 h[0] = 0x43454E45u;                              // "ENEC"
                 h[1] = 1u | (0u << 16) | (16u << 24);            // version, dtype bf16, L
-                h[2] = (uint32_t)p.n_elems; h[3] = (uint32_t)(p.n_elems >> 32);
-                h[4] = B; h[5] = p.nb;
-                h[6] = p.b | ((uint32_t)N << 8) | ((uint32_t)M << 16) | (8u << 24);
+                h[2] = (uint32_t)it.n_elems; h[3] = (uint32_t)(it.n_elems >> 32);
+                h[4] = B; h[5] = it.nb;
+                h[6] = it.b | ((uint32_t)N << 8) | ((uint32_t)M << 16) | (8u << 24);
                 h[7] = status;
                 h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
 #pragma unroll
                 for (int i = 10; i < 16; ++i) h[i] = 0;
-                if (p.out_bytes) *p.out_bytes = total;
+                if (it.out_bytes) *it.out_bytes = total;
             }
         }
     };
@@ -457,11 +484,19 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 
         // wave 0 reads the scan state for the block stored in this iteration now and uses it
         // after the arithmetic: published an iteration ago, it is normally all there
+        const CompressItem &it = p.item[ci];
+        const uint32_t kl = k - it.first;                    // index of the block inside its tensor
+        const uint32_t crep = ((it.b + (1u << (N - 1))) & 0xFFu) * 0x01010101u;
+        const uint32_t xlo = it.b + 1u > (1u << (N - 1)) ? it.b + 1u - (1u << (N - 1)) : 0u;
+        const uint32_t xhi = it.b + (1u << (N - 1)) < 255u ? it.b + (1u << (N - 1)) : 255u;
+        const uint32_t mode = it.mode;
         uint64_t early_g = 0, early_b = 0;
         if (wave == 0 && pend != NO_BLOCK) {
+            if (scan_item != pend_item) { scan_item = pend_item; groups_sum = 0; groups_summed = 0; scan_flags = 0; }
+            const CompressItem &pit = p.item[pend_item];
             const uint32_t pg = pend >> 6;
-            if (groups_summed + lane < pg) early_g = ld_state(p.ws_group + groups_summed + lane);
-            if (!pend_have_own && lane < (pend & 63u)) early_b = ld_state(p.ws_block + ((uint64_t)pg << 6) + lane);
+            if (groups_summed + lane < pg) early_g = ld_state(pit.ws_group + groups_summed + lane);
+            if (!pend_have_own && lane < (pend & 63u)) early_b = ld_state(pit.ws_block + ((uint64_t)pg << 6) + lane);
         }
 
         // the ticket for the following block is drawn now and looked at after the arithmetic
@@ -489,12 +524,12 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                 const uint32_t X = bfi(0xFEFEFEFEu, Hb << 1, Lb >> 7);
                 // a2 transform: z = (b + 2^(n-1) - x) mod 256 per byte, y = z with the sign bit flipped
                 uint32_t Z;
-                if (p.mode == 0) {
+                if (mode == 0) {
                     Z = crep - X;
                     if (N < 8) err_acc |= Z;
                 } else {
                     Z = bytesub_safe(crep, X);
-                    if (p.mode == 2) {
+                    if (mode == 2) {
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const uint32_t xb = (X >> (8 * i)) & 0xFFu;
@@ -522,7 +557,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             gor |= swap_pair(gor);
             mw[t] = compact_even_bits(__builtin_amdgcn_ballot_w64(gor != 0));
         }
-        if (N < 8 && p.mode == 0) bad = (err_acc & ~NMASK) != 0;
+        if (N < 8 && mode == 0) bad = (err_acc & ~NMASK) != 0;
         if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(&s_err[slot], 1u);
         ENEC_TP(1);
 
@@ -557,7 +592,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         const uint32_t S = (fixed + 2u * A * cnt + 15u) & ~15u;
 
         // ---- a6: publish this block's size at once -----------------------------------
-        if (tid == 0) st_state(p.ws_block + k, tag | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
+        if (tid == 0) st_state(it.ws_block + kl, tag | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
 
         // ---- a5: one record per masked group ------------------------------------------
         if (A > 0) {
@@ -611,15 +646,16 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         bool cur_have_own = false;
         uint64_t cur_own = 0;
         if (wave == 0) {
-            if ((k & 63u) == 63u) {
-                cur_own = sum_words(p.ws_block + ((uint64_t)(k >> 6) << 6), 63u, false, 0);
-                cur_have_own = true;
-                if (lane == 0 && !(scan_flags & 4u))
-                    st_state(p.ws_group + (k >> 6), tag | ((scan_flags & 2u) || own_err ? ST_ERR : 0ull) |
-                                                        (cur_own + (S >> 4)));
+            if ((kl & 63u) == 63u) {
+                uint32_t gf = 0;
+                cur_own = sum_words(it.ws_block + ((uint64_t)(kl >> 6) << 6), 63u, false, 0, gf);
+                cur_have_own = !(gf & 4u);
+                if (lane == 0 && cur_have_own)
+                    st_state(it.ws_group + (kl >> 6), tag | ((gf & 2u) || own_err ? ST_ERR : 0ull) |
+                                                          (cur_own + (S >> 4)));
             }
             if (pend != NO_BLOCK) {
-                const uint64_t off = block_start(pend, pend_have_own, pend_own, true, early_g, early_b);
+                const uint64_t off = block_start(p.item[pend_item], pend, pend_have_own, pend_own, true, early_g, early_b);
                 if (lane == 0) { s_off = off; s_status = scan_flags; }
             }
         }
@@ -629,12 +665,16 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         if (tid == 0) s_err[slot] = 0;          // read by everybody before barrier 2; next use in two iterations
 
         // the following block's rows start to travel while the previous block is stored
-        const uint32_t knext = s_k[slot ^ 1u];
-        if (knext != NO_BLOCK) load_block_rows(p, knext, tid, active, logC, padw, raw);
+        const uint32_t knext = __builtin_amdgcn_readfirstlane(s_k[slot ^ 1u]);
+        uint32_t cnext = ci;
+        if (knext != NO_BLOCK) {
+            cnext = item_of(knext, ci);
+            load_block_rows(p.item[cnext], B, p.logB, knext - p.item[cnext].first, tid, active, logC, raw);
+        }
 
         // ---- a7: stores of the previous block ----------------------------------------------
         if (pend != NO_BLOCK)
-            store_block(pend, pend_cnt, pend_S, smem + (slot ^ 1u) * img_bytes, pend_err);
+            store_block(p.item[pend_item], pend, pend_cnt, pend_S, smem + (slot ^ 1u) * img_bytes, pend_err);
         ENEC_TP(6);
         __syncthreads();                                                     // barrier 3: other image free
         ENEC_TP(7);
@@ -643,43 +683,49 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         // this block becomes the pending one
 #pragma unroll
         for (int t = 0; t < 8; ++t) { SMp[t][0] = SMc[t][0]; SMp[t][1] = SMc[t][1]; }
-        pend = k; pend_cnt = cnt; pend_S = S; pend_err = own_err; pend_have_own = cur_have_own; pend_own = cur_own;
+        pend = kl; pend_item = ci; pend_cnt = cnt; pend_S = S; pend_err = own_err;
+        pend_have_own = cur_have_own; pend_own = cur_own;
         slot ^= 1u;
         k = knext;
+        ci = cnext;
         if (k == NO_BLOCK && !p.lookahead) {           // without lookahead the next ticket is drawn only now
             if (tid == 0) s_k[slot] = drawing ? decode_draw(atomicAdd(ctl + zero, 1u)) : NO_BLOCK;
             __syncthreads();
-            k = s_k[slot];
-            if (k != NO_BLOCK) load_block_rows(p, k, tid, active, logC, padw, raw);
+            k = __builtin_amdgcn_readfirstlane(s_k[slot]);
+            if (k != NO_BLOCK) {
+                ci = item_of(k, ci);
+                load_block_rows(p.item[ci], B, p.logB, k - p.item[ci].first, tid, active, logC, raw);
+            }
         }
     }
 
     // ---- drain: the last block of this workgroup ---------------------------------------------
     if (pend != NO_BLOCK) {
         if (wave == 0) {
-            const uint64_t off = block_start(pend, pend_have_own, pend_own, false, 0, 0);
+            if (scan_item != pend_item) { scan_item = pend_item; groups_sum = 0; groups_summed = 0; scan_flags = 0; }
+            const uint64_t off = block_start(p.item[pend_item], pend, pend_have_own, pend_own, false, 0, 0);
             if (lane == 0) { s_off = off; s_status = scan_flags; }
         }
         __syncthreads();
-        store_block(pend, pend_cnt, pend_S, smem + (slot ^ 1u) * img_bytes, pend_err);
+        store_block(p.item[pend_item], pend, pend_cnt, pend_S, smem + (slot ^ 1u) * img_bytes, pend_err);
     }
 }
 
 // Header-only stream for an empty tensor.
-__global__ void compress_empty_kernel(const CompressArgs p, uint32_t n, uint32_t m)
+__global__ void compress_empty_kernel(uint8_t *out, uint64_t *out_bytes, uint32_t B, uint32_t b, uint32_t n, uint32_t m)
 {
     if (threadIdx.x != 0) return;
-    uint32_t *h = reinterpret_cast<uint32_t *>(p.out);
+    uint32_t *h = reinterpret_cast<uint32_t *>(out);
     h[0] = 0x43454E45u;
     h[1] = 1u | (16u << 24);
     h[2] = h[3] = 0;
-    h[4] = p.B; h[5] = 0;
-    h[6] = p.b | (n << 8) | (m << 16) | (8u << 24);
+    h[4] = B; h[5] = 0;
+    h[6] = b | (n << 8) | (m << 16) | (8u << 24);
     h[7] = 0;
     h[8] = 80; h[9] = 0;
     for (int i = 10; i < 16; ++i) h[i] = 0;
     h[16] = h[17] = h[18] = h[19] = 0;      // table[0] = 0 and the pad to 80 bytes
-    if (p.out_bytes) *p.out_bytes = 80;
+    if (out_bytes) *out_bytes = 80;
 }
 
 // ---------------------------------------------------------------------------------
@@ -710,33 +756,47 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
     const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
     const uint32_t par = tid & 1u;
 
-    // d1: the header in memory must be the one the launch was configured from (the host has
-    // checked that header and table lie inside the buffer); otherwise touch nothing
-    {
-        const uint32_t *h = reinterpret_cast<const uint32_t *>(p.in);
-        bool same = true;
-#pragma unroll
-        for (int i = 0; i < 10; ++i) same &= (h[i] == p.hdr[i]);
-        if (!same) return;
-    }
-    const uint64_t *table = reinterpret_cast<const uint64_t *>(p.in + 64);
-
-    // d1: offset lookup, in two steps so that the loads can be issued well before they are used;
-    // a block whose table entries point outside the stream is skipped
-    auto fetch = [&](uint32_t kb, uint64_t &t0, uint64_t &t1) {
-        if (kb < p.nb) { t0 = table[kb]; t1 = table[kb + 1]; }
+    // tensor that global block kg belongs to, searching upwards from item c
+    auto item_of = [&](uint32_t kg, uint32_t c) -> uint32_t {
+        while (c + 1u < p.n_items && kg >= p.item[c + 1u].first) ++c;
+        return c;
     };
-    auto check = [&](uint32_t kb, uint64_t t0, uint64_t t1, uint64_t &off, uint32_t &size) -> bool {
-        if (kb >= p.nb) return false;
+    // d1: the header in memory must be the one the launch was configured from (the host has
+    // checked that header and table lie inside the buffer); otherwise the tensor is not touched
+    uint32_t hdr_ok = 0, hdr_seen = 0;                       // one bit per item
+    auto header_matches = [&](uint32_t c) -> bool {
+        if (!((hdr_seen >> c) & 1u)) {
+            const uint32_t *h = reinterpret_cast<const uint32_t *>(p.item[c].in);
+            bool same = true;
+#pragma unroll
+            for (int i = 0; i < 10; ++i) same &= (h[i] == p.item[c].hdr[i]);
+            hdr_seen |= 1u << c;
+            if (same) hdr_ok |= 1u << c;
+        }
+        return (hdr_ok >> c) & 1u;
+    };
+    // d1: offset lookup, in two steps so that the loads can be issued well before they are used;
+    // a block whose table entries point outside the stream is skipped.  kg = global block index.
+    auto fetch = [&](uint32_t kg, uint32_t c, uint64_t &t0, uint64_t &t1) {
+        if (kg < p.total) {
+            const uint64_t *table = reinterpret_cast<const uint64_t *>(p.item[c].in + 64);
+            const uint32_t kb = kg - p.item[c].first;
+            t0 = table[kb];
+            t1 = table[kb + 1];
+        }
+    };
+    auto check = [&](uint32_t kg, uint32_t c, uint64_t t0, uint64_t t1, uint64_t &off, uint32_t &size) -> bool {
+        if (kg >= p.total) return false;
         const uint64_t sz = t1 - t0;
         off = t0;
         size = (uint32_t)sz;
-        return !(sz < fixed || sz > fixed + 2u * A * (B >> 4) + 15u || (sz & 15u) || t0 > p.payload_bytes ||
-                 sz > p.payload_bytes - t0);
+        return header_matches(c) &&
+               !(sz < fixed || sz > fixed + 2u * A * (B >> 4) + 15u || (sz & 15u) || t0 > p.item[c].payload_bytes ||
+                 sz > p.item[c].payload_bytes - t0);
     };
     // issue the loads of one block: sign/mantissa rows and the packed part
-    auto issue = [&](uint64_t off, uint32_t size, uint2 (&smv)[8], uint4 (&vec)[VMAX]) {
-        const uint8_t *src = p.in + p.payload_base + off;
+    auto issue = [&](uint32_t c, uint64_t off, uint32_t size, uint2 (&smv)[8], uint4 (&vec)[VMAX]) {
+        const uint8_t *src = p.item[c].in + p.item[c].payload_base + off;
 #pragma unroll
         for (int t = 0; t < 8; ++t)
             smv[t] = active ? *reinterpret_cast<const uint2 *>(src + ((size_t)t << logC) + 8u * tid) : make_uint2(0, 0);
@@ -755,33 +815,38 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
         }
     };
 
-    uint32_t k = blockIdx.x;
+    uint32_t k = blockIdx.x;                                // global block index
+    if (k >= p.total) return;
+    uint32_t ci = item_of(k, 0);
+    uint32_t cn = item_of(k + gridDim.x, ci);               // item of the next block (if there is one)
     uint64_t off = 0, offn = 0;
     uint32_t size = 0, sizen = 0;
     uint64_t ta = 0, tb = 0, tc = 0, td = 0;
-    fetch(k, ta, tb);
-    fetch(k + gridDim.x, tc, td);                           // the table is read one block ahead
-    bool valid = check(k, ta, tb, off, size);
-    bool validn = check(k + gridDim.x, tc, td, offn, sizen);
+    fetch(k, ci, ta, tb);
+    fetch(k + gridDim.x, cn, tc, td);                       // the table is read one block ahead
+    bool valid = check(k, ci, ta, tb, off, size);
+    bool validn = check(k + gridDim.x, cn, tc, td, offn, sizen);
     uint2 smc[8], smn[8];
     uint4 vec[VMAX];
     if (valid) {
-        issue(off, size, smc, vec);
+        issue(ci, off, size, smc, vec);
         to_image(smem, vec);
     }
     uint32_t slot = 0;
-    const uint32_t crep = ((p.b + (1u << (N - 1))) & 0xFFu) * 0x01010101u;
     constexpr HHTable TL = HH<M>::table;
 
     ENEC_TP_DECL;
-    while (k < p.nb) {
+    while (k < p.total) {
         ENEC_TP(0);
         __syncthreads();            // image[slot] is complete, image[slot ^ 1] is free
         ENEC_TP(1);
         // the next block's loads start now and are consumed at the end of the iteration
         const uint32_t kn = k + gridDim.x;
-        if (validn) issue(offn, sizen, smn, vec);
-        fetch(kn + gridDim.x, ta, tb);
+        if (validn) issue(cn, offn, sizen, smn, vec);
+        const uint32_t c2 = item_of(kn + gridDim.x, cn);
+        fetch(kn + gridDim.x, c2, ta, tb);
+        const DecompressItem &it = p.item[ci];
+        const uint32_t crep = ((it.b + (1u << (N - 1))) & 0xFFu) * 0x01010101u;
         ENEC_TP(2);
 
         if (valid && active) {
@@ -811,7 +876,7 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
                     Pl[q][0] = Pl[q][1] = 0;
                 }
             }
-            const uint64_t blk0 = (uint64_t)k << p.logB;
+            const uint64_t blk0 = (uint64_t)(k - it.first) << p.logB;
             ENEC_TP(3);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
@@ -870,7 +935,7 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     const uint32_t Z = Y[h] ^ SREP;
-                    const uint32_t X = p.mode == 0 ? crep - Z : bytesub_safe(crep, Z);
+                    const uint32_t X = it.mode == 0 ? crep - Z : bytesub_safe(crep, Z);
                     const uint32_t sm = h ? smc[t].y : smc[t].x;
                     const uint32_t Hi = bfi(0x7F7F7F7Fu, X >> 1, sm);
                     const uint32_t Lo = bfi(0x7F7F7F7Fu, sm, X << 7);
@@ -878,12 +943,12 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
                     o[2 * h + 1] = byte_perm(Hi, Lo, 0x07030602u);
                 }
                 const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
-                if (e0 + 8 <= p.n_elems) {
-                    *reinterpret_cast<uint4 *>(p.out + e0) = make_uint4(o[0], o[1], o[2], o[3]);
-                } else if (e0 < p.n_elems) {
+                if (e0 + 8 <= it.n_elems) {
+                    *reinterpret_cast<uint4 *>(it.out + e0) = make_uint4(o[0], o[1], o[2], o[3]);
+                } else if (e0 < it.n_elems) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i)
-                        if (e0 + i < p.n_elems) p.out[e0 + i] = (uint16_t)(o[i >> 1] >> (16 * (i & 1)));
+                        if (e0 + i < it.n_elems) it.out[e0 + i] = (uint16_t)(o[i >> 1] >> (16 * (i & 1)));
                 }
             }
         }
@@ -895,8 +960,10 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
             for (int t = 0; t < 8; ++t) smc[t] = smn[t];
         }
         valid = validn;
-        validn = check(kn + gridDim.x, ta, tb, offn, sizen);
+        validn = check(kn + gridDim.x, c2, ta, tb, offn, sizen);
         k = kn;
+        ci = cn;
+        cn = c2;
         slot ^= 1u;
         ENEC_TP(5);
         ENEC_TP(6);

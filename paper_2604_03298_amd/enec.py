@@ -22,7 +22,7 @@ EXPORTS = [
     "enec_version", "enec_strerror", "enec_default_block_size", "enec_compress_bound",
     "enec_workspace_bytes", "enec_workspace_init", "enec_compress", "enec_decompress",
     "enec_decompress_with_header", "enec_tune", "enec_tune_histogram", "enec_stream_info",
-    "enec_copy",
+    "enec_copy", "enec_compress_batch", "enec_decompress_batch",
 ]
 
 
@@ -31,6 +31,17 @@ class Params(C.Structure):
 
     def astuple(self):
         return (self.b, self.n, self.m, self.L)
+
+
+class CompressItem(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("n_elems", C.c_size_t), ("block_size", C.c_uint32),
+                ("params", C.POINTER(Params)), ("out", C.c_void_p), ("out_capacity", C.c_size_t),
+                ("out_bytes", C.c_void_p)]
+
+
+class DecompressItem(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("in_bytes", C.c_size_t), ("host_header", C.c_void_p),
+                ("out", C.c_void_p), ("n_elems", C.c_size_t)]
 
 
 class EnecError(RuntimeError):
@@ -79,6 +90,10 @@ def lib():
                                        C.POINTER(C.c_int), C.POINTER(u32)]
         L.enec_copy.restype = C.c_int
         L.enec_copy.argtypes = [vp, vp, sz, vp]
+        L.enec_compress_batch.restype = C.c_int
+        L.enec_compress_batch.argtypes = [C.POINTER(CompressItem), sz, C.c_int, vp, sz, vp]
+        L.enec_decompress_batch.restype = C.c_int
+        L.enec_decompress_batch.argtypes = [C.POINTER(DecompressItem), sz, vp]
         _lib = L
     return _lib
 
@@ -183,6 +198,47 @@ def decompress_with_header(stream_buf, host_header, out, n_elems: int | None = N
     return int(lib().enec_decompress_with_header(
         C.c_void_p(stream_buf.data_ptr()), stream_buf.numel() * stream_buf.element_size(),
         hdr.ctypes.data, C.c_void_p(out.data_ptr()), n, _stream_handle(stream)))
+
+
+def compress_batch(srcs, params, outs, workspace, block_sizes=None, out_bytes=None, stream=None) -> int:
+    """Enqueues enec_compress_batch.  srcs / outs: lists of device tensors; params: list of
+    (b, n, m, L) or None per tensor; out_bytes: None or a list of one-u64 device-accessible tensors."""
+    n = len(srcs)
+    keep = [_params(p) if p is not None else None for p in params]
+    items = (CompressItem * n)()
+    for i in range(n):
+        items[i].src = srcs[i].data_ptr()
+        items[i].n_elems = srcs[i].numel()
+        items[i].block_size = block_sizes[i] if block_sizes else 0
+        items[i].params = C.pointer(keep[i]) if keep[i] is not None else None
+        items[i].out = outs[i].data_ptr()
+        items[i].out_capacity = outs[i].numel() * outs[i].element_size()
+        items[i].out_bytes = out_bytes[i].data_ptr() if out_bytes is not None else None
+    return int(lib().enec_compress_batch(items, n, BF16, C.c_void_p(workspace.data_ptr()),
+                                         workspace.numel() * workspace.element_size(),
+                                         _stream_handle(stream)))
+
+
+def make_decompress_items(stream_bufs, host_headers, outs):
+    """Builds the item array for decompress_batch once (it can be reused for repeated calls).
+    Returns (items, keepalive)."""
+    n = len(stream_bufs)
+    hdrs = [np.frombuffer(bytes(h[:HEADER_BYTES]), dtype=np.uint8).copy() for h in host_headers]
+    items = (DecompressItem * n)()
+    for i in range(n):
+        items[i].src = stream_bufs[i].data_ptr()
+        items[i].in_bytes = stream_bufs[i].numel() * stream_bufs[i].element_size()
+        items[i].host_header = hdrs[i].ctypes.data
+        items[i].out = outs[i].data_ptr()
+        items[i].n_elems = outs[i].numel()
+    return items, hdrs
+
+
+def decompress_batch(stream_bufs, host_headers, outs, stream=None, items=None) -> int:
+    keep = None
+    if items is None:
+        items, keep = make_decompress_items(stream_bufs, host_headers, outs)
+    return int(lib().enec_decompress_batch(items, len(items), _stream_handle(stream)))
 
 
 def tune(src, workspace, stream=None, want_histogram: bool = False):

@@ -203,6 +203,61 @@ def test_back_to_back_calls_without_sync(gpu, oracle):
         assert np.array_equal(backs[i].cpu().numpy().view(np.uint16)[:t.size], t)
 
 
+def test_batch_entry_points(gpu, oracle):
+    torch, enec = gpu.torch, gpu.enec
+    rng = np.random.default_rng(123)
+    # tensors of several shapes and parameter tuples, empty and single-block ones included
+    tensors = [W.gaussian(16384 * 70 + 9, 0.02, 301), W.norm_vector(4096, 27), W.gaussian(16384 * 3, 0.02, 302),
+               W.gaussian(40000, 0.3, 303), np.zeros(0, np.uint16), W.norm_vector(4096, 28),
+               in_window_tensor(rng, 128, 8, 16384 * 5 + 1, m=4), W.gaussian(16384 * 33 + 100, 0.02, 304),
+               np.zeros(50000, np.uint16), W.gaussian(2049, 0.02, 305)]
+    params = [oracle.tune(t) for t in tensors]
+    params[6] = (128, 8, 4, 16)
+    srcs = [gpu.to_dev(t) for t in tensors]
+    outs = [torch.full((enec.compress_bound(t.size),), 0x5A, dtype=torch.uint8, device="cuda") for t in tensors]
+    sizes = [torch.zeros(1, dtype=torch.int64, device="cuda") for _ in tensors]
+    total = sum(t.size for t in tensors)
+    ws = enec.new_workspace(total)
+    class Shim:          # compress_batch takes numel() from the tensor: empty tensors are padded on the device
+        def __init__(self, t, n): self.t, self.n = t, n
+        def data_ptr(self): return self.t.data_ptr()
+        def numel(self): return self.n
+    shims = [Shim(srcs[i], tensors[i].size) for i in range(len(tensors))]
+    for rep in range(3):
+        assert enec.compress_batch(shims, params, outs, ws, out_bytes=sizes) == 0
+        torch.cuda.synchronize()
+        for i, t in enumerate(tensors):
+            s_o = oracle.compress(t, params[i], oracle.default_block(t.size))[1]
+            assert int(sizes[i]) == s_o.size, (rep, i)
+            assert np.array_equal(outs[i].cpu().numpy()[:s_o.size], s_o), (rep, i)
+    backs = [torch.full((max(t.size, 8),), 0x1111, dtype=torch.int16, device="cuda") for t in tensors]
+    hdrs = [outs[i][:64].cpu().numpy().tobytes() for i in range(len(tensors))]
+    bshims = [Shim(backs[i], tensors[i].size) for i in range(len(tensors))]
+    assert enec.decompress_batch(outs, hdrs, bshims) == 0
+    torch.cuda.synchronize()
+    for i, t in enumerate(tensors):
+        assert np.array_equal(backs[i].cpu().numpy().view(np.uint16)[:t.size], t), i
+    # one item with a range error does not disturb the others
+    bad_params = list(params)
+    bad_params[2] = (122, 3, 1, 16)
+    assert enec.compress_batch(shims, bad_params, outs, ws, out_bytes=sizes) == 0
+    torch.cuda.synchronize()
+    assert int(sizes[2]) == 0 and enec.stream_info(outs[2][:64].cpu().numpy())["status"] == enec.E_RANGE
+    for i in (0, 3, 7):
+        s_o = oracle.compress(tensors[i], params[i], oracle.default_block(tensors[i].size))[1]
+        assert np.array_equal(outs[i].cpu().numpy()[:s_o.size], s_o), i
+    # more than 16 tensors of one kind: several launches
+    many = [W.gaussian(16384 + 7 * j, 0.02, 400 + j) for j in range(20)]
+    msrc = [gpu.to_dev(t) for t in many]
+    mout = [torch.zeros(enec.compress_bound(t.size), dtype=torch.uint8, device="cuda") for t in many]
+    msz = [torch.zeros(1, dtype=torch.int64, device="cuda") for _ in many]
+    assert enec.compress_batch(msrc, [(122, 6, 3, 16)] * 20, mout, ws, out_bytes=msz) == 0
+    torch.cuda.synchronize()
+    for j, t in enumerate(many):
+        s_o = oracle.compress(t, (122, 6, 3, 16), 16384)[1]
+        assert int(msz[j]) == s_o.size and np.array_equal(mout[j].cpu().numpy()[:s_o.size], s_o), j
+
+
 def test_decompress_variants_and_header_mismatch(gpu, oracle):
     w = W.gaussian(5 * 16384 + 3, 0.02, 99)
     p = oracle.tune(w)
