@@ -24,10 +24,13 @@ if ROOT not in sys.path:
 METRIC = "decompress & compress GB/s (uncompressed bf16) + compression ratio, 1 MI355X"
 HBM_PEAK_GBPS = 8000.0
 
-# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE, scaled by what the same counters read for enec_copy of known size); filled in from
-# the summaries under profiles/.  None = not measured yet.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch measured with rocprofv3 --pmc on this workload (FETCH_SIZE and WRITE_SIZE in
+# two runs, each scaled by what the same counter reads for enec_copy of known size); the figures
+# and the commands are in profiles/codec_kernels_config2_hbm_traffic.md.  They apply to the default
+# workload only; another workload reports null.
+MEASURED_TRAFFIC_BYTES = {
+    "config2": {"enec::compress_kernel<4,2>": 770882001, "enec::decompress_kernel<4,2>": 713747717},
+}
 
 
 def main():
@@ -154,7 +157,7 @@ def main():
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "avg_launch_us": round(gd["ms"] * 1e3 / gd["launches"], 2),
         "algorithmic_bytes_per_launch": gd["bytes"] // gd["launches"],
-        "traffic": MEASURED_TRAFFIC_BYTES.get(dom),
+        "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dom),
     }
     per_kernel = {k: {"GBps_moved": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1),
                       "frac_of_hbm_peak": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
@@ -181,7 +184,7 @@ def main():
         from oracle import enec_oracle
         done_bytes, t_cpu, i = 0, 0.0, 0
         order = sorted(range(nt), key=lambda j: -n_el[j])
-        while t_cpu < 10.0 and i < 3 * nt:
+        while t_cpu < 12.0 and i < 40 * nt:
             j = order[i % nt]
             w = host[j][1]
             B = enec_oracle.default_block(w.size)
