@@ -203,6 +203,48 @@ def test_back_to_back_calls_without_sync(gpu, oracle):
         assert np.array_equal(backs[i].cpu().numpy().view(np.uint16)[:t.size], t)
 
 
+def test_random_shapes_and_parameters(gpu, oracle):
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        B = int(rng.choice([2048, 4096, 8192, 16384, 32768]))
+        size = int(rng.integers(1, 12 * B))
+        n = int(rng.integers(1, 9))
+        m = int(rng.integers(0, n + 1))
+        half = 1 << (n - 1)
+        b = int(rng.integers(0, 256)) if n == 8 else int(rng.integers(max(0, half - 1), 256 - half + 1))
+        if case % 5 == 0:                        # windows that touch the ends of the exponent range
+            b = int(rng.choice([0, 1, 254, 255]))
+        w = in_window_tensor(rng, b, n, size, quiet_frac=float(rng.random()), m=m)
+        check_both_ways(gpu, oracle, w, (b, n, m, 16), B, f"case {case}: B={B} size={size} b={b} n={n} m={m}")
+
+
+def test_config3_full_size(gpu, oracle):
+    w, cat = W.config3()
+    check_both_ways(gpu, oracle, w, oracle.tune(w), 16384, "config3 mix, 64M elements")
+
+
+def test_two_streams_two_workspaces(gpu, oracle):
+    torch, enec = gpu.torch, gpu.enec
+    tensors = [W.gaussian(16384 * 200 + 3, 0.02, 700), W.gaussian(16384 * 150 + 11, 0.01, 701)]
+    params = [oracle.tune(t) for t in tensors]
+    refs = [oracle.compress(t, p, 16384)[1] for t, p in zip(tensors, params)]
+    srcs = [gpu.to_dev(t) for t in tensors]
+    outs = [torch.zeros(enec.compress_bound(t.size), dtype=torch.uint8, device="cuda") for t in tensors]
+    backs = [torch.zeros(t.size, dtype=torch.int16, device="cuda") for t in tensors]
+    wss = [enec.new_workspace(t.size) for t in tensors]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for i in range(2):
+            assert enec.compress(srcs[i], params[i], outs[i], wss[i], stream=streams[i]) == 0
+        for i in range(2):
+            assert enec.decompress_with_header(outs[i], refs[i][:64].tobytes(), backs[i], stream=streams[i]) == 0
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert np.array_equal(outs[i].cpu().numpy()[:refs[i].size], refs[i]), (rep, i)
+            assert np.array_equal(backs[i].cpu().numpy().view(np.uint16), tensors[i]), (rep, i)
+
+
 def test_batch_entry_points(gpu, oracle):
     torch, enec = gpu.torch, gpu.enec
     rng = np.random.default_rng(123)
