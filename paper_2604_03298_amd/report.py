@@ -1,0 +1,178 @@
+"""Runs the codec on all five synthetic configurations on one MI355X and prints one JSON line per
+configuration (throughput on uncompressed bytes, ratio, fraction of the 8 TB/s HBM peak in bytes
+moved).  `python -m paper_2604_03298_amd.report [--configs 1,2,3a,3b,4,5]`.
+
+Tensors of configurations 1-3 come from the seeded numpy generators of `workloads.py` (the ones the
+parity tests use); configurations 4 and 5 (15 GB / 4.8 GB of bf16) are drawn on the GPU with a
+seeded torch generator, same shapes and standard deviations.  Every run checks on the device that
+decompress(compress(x)) == x bit for bit.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import time
+
+import numpy as np
+
+HBM_PEAK = 8000.0
+
+
+def _events(torch, n):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def run_group(torch, enec, name, srcs, reps=5):
+    """Tune, compress (batched), decompress (batched), verify; returns a dict of results."""
+    n_el = [s.numel() for s in srcs]
+    raw = 2 * sum(n_el)
+    ws = enec.new_workspace(sum(n_el))
+    params = [enec.tune(s, ws) for s in srcs]
+    outs = [torch.empty(enec.compress_bound(n), dtype=torch.uint8, device="cuda") for n in n_el]
+    sizes = torch.zeros(len(srcs), dtype=torch.int64, device="cuda")
+    szl = [sizes[i:i + 1] for i in range(len(srcs))]
+    chunks = [list(range(i, min(i + 16, len(srcs)))) for i in range(0, len(srcs), 16)]
+
+    def comp():
+        for c in chunks:
+            rc = enec.compress_batch([srcs[i] for i in c], [params[i] for i in c], [outs[i] for i in c], ws,
+                                     out_bytes=[szl[i] for i in c])
+            assert rc == 0, enec.strerror(rc)
+
+    comp()
+    torch.cuda.synchronize()
+    stream_bytes = [int(v) for v in sizes.cpu()]
+    assert all(v > 0 for v in stream_bytes), "range error"
+    hdrs = [outs[i][:64].cpu().numpy().tobytes() for i in range(len(srcs))]
+    backs = [torch.empty_like(s) for s in srcs]
+    items = [enec.make_decompress_items([outs[i] for i in c], [hdrs[i] for i in c], [backs[i] for i in c])
+             for c in chunks]
+
+    def decomp():
+        for it in items:
+            rc = enec.decompress_batch(None, None, None, items=it[0])
+            assert rc == 0, enec.strerror(rc)
+
+    decomp()
+    torch.cuda.synchronize()
+    assert all(torch.equal(b, s) for b, s in zip(backs, srcs)), "round trip is not bit-exact"
+    tc, td = [], []
+    for _ in range(reps):
+        e = _events(torch, 3)
+        e[0].record(); comp(); e[1].record(); decomp(); e[2].record()
+        torch.cuda.synchronize()
+        tc.append(e[0].elapsed_time(e[1])); td.append(e[1].elapsed_time(e[2]))
+    tc, td = float(np.median(tc)), float(np.median(td))
+    moved = raw + sum(stream_bytes)
+    return {
+        "config": name, "tensors": len(srcs), "uncompressed_bytes": raw, "compression_ratio": round(raw / sum(stream_bytes), 4),
+        "params": sorted({tuple(p) for p in params}),
+        "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
+        "compress_GBps": round(raw / tc / 1e6, 1), "decompress_GBps": round(raw / td / 1e6, 1),
+        "compress_frac_of_hbm_peak": round(moved / tc / 1e6 / HBM_PEAK, 4),
+        "decompress_frac_of_hbm_peak": round(moved / td / 1e6 / HBM_PEAK, 4),
+        "roundtrip_bit_exact": True,
+    }, (outs, stream_bytes, hdrs, backs)
+
+
+def gpu_gaussian(torch, rows, cols, std, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    x = torch.empty(rows * cols, dtype=torch.bfloat16, device="cuda")
+    step = 1 << 25      # float64 draws: float32 samplers emit exact zeros, which would force n = 8
+    for s in range(0, x.numel(), step):
+        e = min(x.numel(), s + step)
+        x[s:e] = (torch.randn(e - s, generator=g, device="cuda", dtype=torch.float64) * std).to(torch.bfloat16)
+    return x.view(torch.int16)
+
+
+def offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs):
+    """Configuration 5: compressed streams in pinned host memory; per tensor copy the stream over PCIe
+    on one HIP stream and decompress it on another, overlapped with the next copy; compared with
+    copying the uncompressed bf16."""
+    host_c = [torch.empty(b, dtype=torch.uint8).pin_memory() for b in stream_bytes]
+    for h, o, b in zip(host_c, outs, stream_bytes):
+        h.copy_(o[:b])
+    host_raw = [torch.empty(s.numel(), dtype=torch.int16).pin_memory() for s in srcs]
+    for h, s in zip(host_raw, srcs):
+        h.copy_(s)
+    torch.cuda.synchronize()
+    copy_s, comp_s = torch.cuda.Stream(), torch.cuda.Stream()
+    dev_c = [torch.empty(max(stream_bytes), dtype=torch.uint8, device="cuda") for _ in range(2)]
+    n = len(srcs)
+
+    def pipelined():
+        ready = [torch.cuda.Event() for _ in range(n)]
+        freed = [torch.cuda.Event() for _ in range(n)]
+        for i in range(n):
+            buf = dev_c[i % 2]
+            with torch.cuda.stream(copy_s):
+                if i >= 2:
+                    copy_s.wait_event(freed[i - 2])
+                buf[:stream_bytes[i]].copy_(host_c[i], non_blocking=True)
+                ready[i].record(copy_s)
+            comp_s.wait_event(ready[i])
+            rc = enec.decompress_with_header(buf, hdrs[i], backs[i], stream=comp_s)
+            assert rc == 0
+            freed[i].record(comp_s)
+        comp_s.synchronize()
+
+    def plain():
+        with torch.cuda.stream(copy_s):
+            for i in range(n):
+                backs[i].copy_(host_raw[i], non_blocking=True)
+        copy_s.synchronize()
+
+    res = {}
+    for name, fn in (("compressed_copy_plus_decompress", pipelined), ("uncompressed_copy", plain)):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(3):
+            t0 = time.perf_counter(); fn(); torch.cuda.synchronize(); ts.append(time.perf_counter() - t0)
+        res[name + "_ms"] = round(1e3 * float(np.median(ts)), 3)
+    assert all(torch.equal(b, s) for b, s in zip(backs, srcs))
+    raw = 2 * sum(s.numel() for s in srcs)
+    res["effective_weights_GBps_compressed"] = round(raw / res["compressed_copy_plus_decompress_ms"] / 1e6, 1)
+    res["effective_weights_GBps_uncompressed"] = round(raw / res["uncompressed_copy_ms"] / 1e6, 1)
+    res["speedup"] = round(res["uncompressed_copy_ms"] / res["compressed_copy_plus_decompress_ms"], 3)
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--configs", default="1,2,3a,3b,4,5")
+    args = ap.parse_args()
+    want = args.configs.split(",")
+    import torch
+    from . import enec, workloads as W
+    assert torch.cuda.is_available()
+    enec.lib()
+
+    def dev(a):
+        return torch.from_numpy(a.view(np.int16)).cuda()
+
+    if "1" in want:
+        print(json.dumps(run_group(torch, enec, "1: 1024x4096 N(0,0.02^2)", [dev(W.config1())], reps=20)[0]), flush=True)
+    if "2" in want:
+        print(json.dumps(run_group(torch, enec, "2: 7B-style decoder layer", [dev(w) for _, w in W.config2()], reps=20)[0]), flush=True)
+    if "3a" in want:
+        print(json.dumps(run_group(torch, enec, "3a: edge-case mix, one tensor", [dev(W.config3()[0])], reps=10)[0]), flush=True)
+    if "3b" in want:
+        for c, t in enumerate(W.config3_by_category()):
+            name = ["zero blocks", "constant blocks", "Student-t blocks", "random 16-bit patterns"][c]
+            print(json.dumps(run_group(torch, enec, f"3b: {name}", [dev(t)], reps=10)[0]), flush=True)
+    if "4" in want:
+        srcs = [gpu_gaussian(torch, 8192, 28672, W.config4_std(i), 4000 + i) for i in range(32)]
+        print(json.dumps(run_group(torch, enec, "4: 32 tensors 8192x28672", srcs, reps=3)[0]), flush=True)
+        del srcs
+        torch.cuda.empty_cache()
+    if "5" in want:
+        srcs = [gpu_gaussian(torch, r, c, 0.015, seed) for r, c, seed in W.config5_spec()]
+        res, (outs, stream_bytes, hdrs, backs) = run_group(torch, enec, "5: 8 layers 8192x8192 + 8192x28672 (HBM resident)", srcs, reps=3)
+        res["offload"] = offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs)
+        print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()
