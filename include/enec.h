@@ -90,7 +90,10 @@ size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size);
 
 /* Enqueues a fill kernel that zeroes `bytes` bytes of the DEVICE workspace.  Must run once after
  * the workspace is allocated; after that one workspace serves any number of calls that do not
- * overlap in time (the library keeps its counters and call tags in it).  16-byte aligned. */
+ * overlap in time (the library keeps its counters and call tags in it).  16-byte aligned.
+ * Pass the same workspace_bytes with a workspace on every call: the library places its state by
+ * that size.  After a size change, or after a process died in the middle of a call, initialise
+ * the workspace again. */
 int enec_workspace_init(void *workspace, size_t bytes, void *stream);
 
 /* Compress n_elems bf16 values [Sec. V-A compression path; Sec. V-B; Sec. V-C; Fig. 4].

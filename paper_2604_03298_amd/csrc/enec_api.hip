@@ -16,6 +16,11 @@ using namespace enec;
 // group words | block words (the last two sized by the call's block count)
 constexpr size_t WS_CTL = 0, WS_HIST = 1024, WS_STATE = WS_HIST + 256 * 8;
 inline size_t ws_groups(size_t nb) { return (nb + 63) / 64; }
+// The state words behind WS_STATE: first the group accumulators, which every call leaves zero, in
+// a region whose length depends only on the size of the workspace (1/33 of the words), then the
+// tagged group and block words, handed out anew by every launch.
+inline size_t ws_state_words(size_t workspace_bytes) { return workspace_bytes < WS_STATE ? 0 : (workspace_bytes - WS_STATE) / 8; }
+inline size_t ws_acc_words(size_t workspace_bytes) { return ws_state_words(workspace_bytes) / 33; }
 constexpr size_t MAX_ELEMS = (size_t)1 << 34;      // keeps every offset below 2^36 bytes
 
 inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
@@ -161,7 +166,9 @@ size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size)
     if (!block_ok(B)) return 0;
     // room for the scan words of up to MAX_BATCH tensors with n_elems elements in total
     const size_t nb = num_blocks(n_elems, B) + MAX_BATCH;
-    return (WS_STATE + 8 * (ws_groups(nb) + MAX_BATCH + nb) + 255) & ~(size_t)255;
+    const size_t groups = ws_groups(nb) + MAX_BATCH;
+    const size_t by_acc = 33 * groups, by_words = (33 * (groups + nb) + 31) / 32;
+    return (WS_STATE + 8 * ((by_acc > by_words ? by_acc : by_words) + 33) + 255) & ~(size_t)255;
 }
 
 int enec_workspace_init(void *workspace, size_t bytes, void *stream)
@@ -249,7 +256,7 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
     // ---- every check that can be made on the host, before anything is enqueued -------------
     struct Prepared { enec_params prm; uint32_t B; uint32_t nb; };
     std::vector<Prepared> prep(n_items);
-    size_t state_words = 0;
+    size_t state_words = 0, groups = 0;
     for (size_t i = 0; i < n_items; ++i) {
         const enec_compress_item &it = items[i];
         if (!it.out || (!it.in && it.n_elems) || !aligned16(it.in) || !aligned16(it.out) ||
@@ -260,8 +267,10 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         prep[i].B = B;
         prep[i].nb = (uint32_t)num_blocks(it.n_elems, B);
         state_words += ws_groups(prep[i].nb) + prep[i].nb;
+        groups += ws_groups(prep[i].nb);
     }
-    if (workspace_bytes < WS_STATE + 8 * state_words) return ENEC_E_CAPACITY;
+    const size_t acc_words = ws_acc_words(workspace_bytes);
+    if (groups > acc_words || acc_words + state_words > ws_state_words(workspace_bytes)) return ENEC_E_CAPACITY;
     for (size_t i = 0; i < n_items; ++i) {
         const enec_compress_item &it = items[i];
         if (it.params) {
@@ -293,7 +302,7 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         a.logB = ilog2(a.B);
         a.n_items = 0;
         a.total = 0;
-        size_t word = 0;      // scan words handed out to this launch (tags make reuse between launches safe)
+        size_t word = acc_words, acc = 0;   // scan words handed out to this launch (tags make reuse between launches safe)
         for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
             if (done[j] || prep[j].nb == 0 || prep[j].B != a.B || prep[j].prm.m != prep[i].prm.m ||
                 prep[j].prm.n != prep[i].prm.n)
@@ -302,6 +311,8 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
             c.in = static_cast<const uint16_t *>(items[j].in);
             c.out = static_cast<uint8_t *>(items[j].out);
             c.out_bytes = items[j].out_bytes;
+            c.ws_acc = reinterpret_cast<uint64_t *>(ws + WS_STATE) + acc;
+            acc += ws_groups(prep[j].nb);
             c.ws_group = reinterpret_cast<uint64_t *>(ws + WS_STATE) + word;
             word += ws_groups(prep[j].nb);
             c.ws_block = reinterpret_cast<uint64_t *>(ws + WS_STATE) + word;

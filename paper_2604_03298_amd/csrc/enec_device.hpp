@@ -157,13 +157,19 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
 // ---------------------------------------------------------------------------------
 // Inter-block scan (Fig. 4: prefix sums of per-block compressed sizes) and work distribution.
 //
-// Scan state.  Every word is self-contained: [63:24] tag of the call that wrote it, [23] range
-// error, [22:0] a size in units of 16 bytes.  Relaxed device-scope loads and stores are enough,
-// no fence is needed, and nothing has to be cleared between calls: a word whose tag is not the
+// Scan state.  Block and group words are self-contained: [63:24] tag of the call that wrote it,
+// [23] range error, [22:0] a size in units of 16 bytes.  Relaxed device-scope loads and stores
+// are enough, no fence is needed, and they are never cleared: a word whose tag is not the
 // current call's tag is simply "not published yet".
 //   block word k   size of data block k, stored as soon as the block's mask is known
-//   group word g   sum of the sizes of blocks 64g .. 64g+63, stored by the workgroup that owns
-//                  block 64g+63 once the other 63 block words of the group are there
+//   group word g   sum of the sizes of blocks 64g .. 64g+63
+//   accumulator g  [63:48] blocks counted, [47:32] of them with a range error, [31:0] sum of
+//                  their sizes; zero between calls.  Every block adds itself with one atomic; the
+//                  workgroup whose addition completes the group stores the group word and zeroes
+//                  the accumulator.  So a group word appears as soon as its last block is known
+//                  and no workgroup ever waits for blocks of its own generation (an owner that
+//                  polled its 63 neighbours turned the loop latency-bound as soon as the blocks
+//                  took equal time and the workgroups ran in lockstep).
 // The start of block k is the sum of the group words below k/64 plus the block words of the
 // earlier blocks of its own group: few words, read by one wave.
 //
@@ -219,6 +225,7 @@ struct CompressItem {
     uint64_t *out_bytes;    // device-accessible or null
     uint64_t *ws_block;     // nb block words
     uint64_t *ws_group;     // ceil(nb / 64) group words
+    uint64_t *ws_acc;       // ceil(nb / 64) group accumulators, zero between calls
     uint64_t n_elems;
     uint64_t payload_base;
     uint32_t nb, first;
@@ -311,6 +318,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     const uint32_t B = p.B, logC = p.logB - 3u;
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
+    const uint32_t acc_tid = blockDim.x > 64u ? 64u : 0u;   // the lane that talks to the group accumulators
     const uint32_t img_bytes = (B >> 7) + (((uint32_t)N * B) >> 3);
     const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
 
@@ -384,10 +392,9 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         if (__builtin_amdgcn_ballot_w64(need && (v & ST_ERR))) flags |= 2u;
         return wave_sum(need ? (v & ST_VALUE) : 0ull);
     };
-    // start of block kb (wave 0; own_group = sum of the earlier block words of its group if known;
-    // early_g / early_b = copies of the first needed group words / of the block words read earlier)
-    auto block_start = [&](const CompressItem &it, uint32_t kb, bool have_own, uint64_t own_group, bool early,
-                           uint64_t early_g, uint64_t early_b) -> uint64_t {
+    // start of block kb (wave 0; early_g / early_b = copies of the first needed group words / of
+    // the earlier block words of its group, read ahead of time)
+    auto block_start = [&](const CompressItem &it, uint32_t kb, bool early, uint64_t early_g, uint64_t early_b) -> uint64_t {
         const uint32_t g = kb >> 6;
         while (groups_summed < g) {
             const uint32_t c = g - groups_summed < 64u ? g - groups_summed : 64u;
@@ -395,15 +402,12 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             groups_summed += c;
             early = false;
         }
-        if (!have_own)
-            own_group = sum_words(it.ws_block + ((uint64_t)g << 6), kb & 63u, early_b != 0, early_b, scan_flags);
+        const uint64_t own_group = sum_words(it.ws_block + ((uint64_t)g << 6), kb & 63u, early_b != 0, early_b, scan_flags);
         return (groups_sum + own_group) << 4;
     };
 
     // the block waiting to be stored
     uint32_t pend = NO_BLOCK, pend_item = 0, pend_cnt = 0, pend_S = 0, pend_err = 0;   // pend: index inside its tensor
-    bool pend_have_own = false;
-    uint64_t pend_own = 0;
     uint32_t SMp[8][2];
 
     // stores block `kb` whose packed part sits in image `img` and whose sign/mantissa bytes sit in SMp
@@ -496,7 +500,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             const CompressItem &pit = p.item[pend_item];
             const uint32_t pg = pend >> 6;
             if (groups_summed + lane < pg) early_g = ld_state(pit.ws_group + groups_summed + lane);
-            if (!pend_have_own && lane < (pend & 63u)) early_b = ld_state(pit.ws_block + ((uint64_t)pg << 6) + lane);
+            if (lane < (pend & 63u)) early_b = ld_state(pit.ws_block + ((uint64_t)pg << 6) + lane);
         }
 
         // the ticket for the following block is drawn now and looked at after the arithmetic
@@ -591,8 +595,14 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         const uint32_t own_err = s_err[slot] & 1u;
         const uint32_t S = (fixed + 2u * A * cnt + 15u) & ~15u;
 
-        // ---- a6: publish this block's size at once -----------------------------------
+        // ---- a6: publish this block's size at once, and add it to its group's accumulator
+        // [blocks:16 | blocks with a range error:16 | sum of sizes:32]; what the addition returns
+        // is looked at after barrier 2, when it has had time to travel ---------------------
         if (tid == 0) st_state(it.ws_block + kl, tag | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
+        uint64_t acc_old = 0;
+        if (tid == acc_tid)
+            acc_old = __hip_atomic_fetch_add(it.ws_acc + (kl >> 6), (1ull << 48) | ((uint64_t)own_err << 32) | (uint64_t)(S >> 4),
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         // ---- a5: one record per masked group ------------------------------------------
         if (A > 0) {
@@ -641,28 +651,28 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         }
         ENEC_TP(3);
 
-        // ---- a6 (wave 0): the owner of the last block of a group adds the group up; then the
-        // start of the block stored in this iteration ------------------------------------
-        bool cur_have_own = false;
-        uint64_t cur_own = 0;
-        if (wave == 0) {
-            if ((kl & 63u) == 63u) {
-                uint32_t gf = 0;
-                cur_own = sum_words(it.ws_block + ((uint64_t)(kl >> 6) << 6), 63u, false, 0, gf);
-                cur_have_own = !(gf & 4u);
-                if (lane == 0 && cur_have_own)
-                    st_state(it.ws_group + (kl >> 6), tag | ((gf & 2u) || own_err ? ST_ERR : 0ull) |
-                                                          (cur_own + (S >> 4)));
-            }
-            if (pend != NO_BLOCK) {
-                const uint64_t off = block_start(p.item[pend_item], pend, pend_have_own, pend_own, true, early_g, early_b);
-                if (lane == 0) { s_off = off; s_status = scan_flags; }
-            }
+        // ---- a6 (wave 0): the start of the block stored in this iteration -----------------
+        if (wave == 0 && pend != NO_BLOCK) {
+            const uint64_t off = block_start(p.item[pend_item], pend, true, early_g, early_b);
+            if (lane == 0) { s_off = off; s_status = scan_flags; }
         }
         ENEC_TP(4);
         __syncthreads();                                                     // barrier 2
         ENEC_TP(5);
         if (tid == 0) s_err[slot] = 0;          // read by everybody before barrier 2; next use in two iterations
+
+        // ---- a6: whoever completes a group publishes its word and clears the accumulator for
+        // the next call; nobody ever waits for blocks of its own generation ------------------
+        if (tid == acc_tid) {
+            const uint32_t g = kl >> 6;
+            const uint32_t members = it.nb - (g << 6) < 64u ? it.nb - (g << 6) : 64u;
+            if ((uint32_t)(acc_old >> 48) == members - 1u) {
+                const uint64_t sum = (acc_old & 0xFFFFFFFFull) + (S >> 4);
+                const bool any_err = ((acc_old >> 32) & 0xFFFFull) != 0 || own_err;
+                st_state(it.ws_group + g, tag | (any_err ? ST_ERR : 0ull) | sum);
+                st_state(it.ws_acc + g, 0ull);
+            }
+        }
 
         // the following block's rows start to travel while the previous block is stored
         const uint32_t knext = __builtin_amdgcn_readfirstlane(s_k[slot ^ 1u]);
@@ -684,7 +694,6 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 #pragma unroll
         for (int t = 0; t < 8; ++t) { SMp[t][0] = SMc[t][0]; SMp[t][1] = SMc[t][1]; }
         pend = kl; pend_item = ci; pend_cnt = cnt; pend_S = S; pend_err = own_err;
-        pend_have_own = cur_have_own; pend_own = cur_own;
         slot ^= 1u;
         k = knext;
         ci = cnext;
@@ -703,7 +712,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     if (pend != NO_BLOCK) {
         if (wave == 0) {
             if (scan_item != pend_item) { scan_item = pend_item; groups_sum = 0; groups_summed = 0; scan_flags = 0; }
-            const uint64_t off = block_start(p.item[pend_item], pend, pend_have_own, pend_own, false, 0, 0);
+            const uint64_t off = block_start(p.item[pend_item], pend, false, 0, 0);
             if (lane == 0) { s_off = off; s_status = scan_flags; }
         }
         __syncthreads();
@@ -752,6 +761,7 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
     const uint32_t B = p.B, logC = p.logB - 3u, C = 1u << logC;
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
+    const uint32_t acc_tid = blockDim.x > 64u ? 64u : 0u;   // the lane that talks to the group accumulators
     const uint32_t img_bytes = (B >> 7) + (((uint32_t)N * B) >> 3);
     const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
     const uint32_t par = tid & 1u;
