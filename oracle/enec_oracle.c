@@ -1,5 +1,5 @@
 /*
- * ENEC lossless bf16 weight codec -- CPU ORACLE.
+ * ENEC lossless weight codec (bf16, fp16, fp32) -- CPU ORACLE.
  *
  * THIS FILE IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
  * single-threaded scalar C implementation of the codec exactly as the paper
@@ -16,7 +16,11 @@
  *
  * What is computed, with the passages followed:
  *   split      bf16 -> 8-bit exponent x, and sign+7-bit mantissa kept raw
- *              (Sec. IV-B, Alg. 1 "Split"; Sec. V-A step 1)
+ *              (Sec. IV-B, Alg. 1 "Split"; Sec. V-A step 1); fp16 (5-bit
+ *              exponent) and fp32 (8-bit exponent) are split the same way
+ *              (Alg. 1 input line; Sec. VI-B: mantissas are never coded), the
+ *              mantissa bits beyond the first seven are kept raw as well, see
+ *              orc_compress_dt for where they go
  *   transform  y = (b - x) mod 2^n               (Sec. V-C; Sec. V-E Eq. 2)
  *   group test OR of the L=16 values of a group; group is "anomalous"
  *              (mask bit 1, stored with n bits) iff OR >= 2^m, else stored
@@ -184,6 +188,22 @@ unsigned orc_inverse_transform(unsigned y, unsigned b, unsigned n)
     return (unsigned)(((int)b - s) & 0xFF);
 }
 
+/* The same two for an exponent field of E bits (8 for bf16 and fp32, 5 for
+ * fp16): at n = E the map is a bijection of all E-bit exponents. */
+int orc_in_range_e(unsigned x, unsigned b, unsigned n, unsigned E)
+{
+    int d = (int)b - (int)x;
+    if (n >= E) return 1;
+    return d >= -(1 << (n - 1)) && d <= (1 << (n - 1)) - 1;
+}
+
+unsigned orc_inverse_transform_e(unsigned y, unsigned b, unsigned n, unsigned E)
+{
+    int s = (int)y;
+    if (y >= (1u << (n - 1))) s -= (1 << n);
+    return (unsigned)(((int)b - s) & ((1 << E) - 1));
+}
+
 /* ------------------------------------------------------------------ */
 /* Sec. V-E: parameter tuning.                                         */
 /* ------------------------------------------------------------------ */
@@ -198,26 +218,78 @@ static unsigned bitlen(unsigned v)
 /* Eq. 1 with its edge cases made explicit: floor(log2 v)+1 = bitlen(v) and
  * ceil(log2 v) = bitlen(v-1) wherever Eq. 1 is defined; bitlen(0)=0 covers
  * b = l and b = h; n is capped at the 8 bits an exponent has. */
-unsigned orc_width_for(unsigned b, unsigned l, unsigned h)
+unsigned orc_width_for_e(unsigned b, unsigned l, unsigned h, unsigned E)
 {
     unsigned pos = bitlen(b - l);
     unsigned neg = (h > b) ? bitlen(h - b - 1) : 0;
     unsigned n = (pos > neg ? pos : neg) + 1;
-    return n > 8 ? 8 : n;
+    return n > E ? E : n;
+}
+
+unsigned orc_width_for(unsigned b, unsigned l, unsigned h) { return orc_width_for_e(b, l, h, 8); }
+
+/* Element formats.  dtype 0 = bf16 (1|8|7), 1 = fp16 (1|5|10), 2 = fp32 (1|8|23). */
+enum { ORC_BF16 = 0, ORC_FP16 = 1, ORC_FP32 = 2 };
+
+static int dtype_ok(int dtype) { return dtype == ORC_BF16 || dtype == ORC_FP16 || dtype == ORC_FP32; }
+unsigned orc_exp_bits(int dtype) { return dtype == ORC_FP16 ? 5u : 8u; }
+unsigned orc_elem_bytes(int dtype) { return dtype == ORC_FP32 ? 4u : 2u; }
+
+/* Element e of a tensor as an unsigned integer (little-endian words in memory). */
+static uint32_t load_elem(const void *in, size_t e, int dtype)
+{
+    if (dtype == ORC_FP32) return ((const uint32_t *)in)[e];
+    return ((const uint16_t *)in)[e];
+}
+
+/* Split (Alg. 1 "Split"): exponent field, the raw byte sign<<7 | first seven
+ * mantissa bits, and the mantissa bits that are left over (none for bf16,
+ * 3 for fp16, 16 for fp32). */
+static void split_elem(uint32_t w, int dtype, unsigned *x, unsigned *sm, unsigned *rest)
+{
+    if (dtype == ORC_FP32) {
+        *x = (w >> 23) & 0xFFu;
+        *sm = ((w >> 24) & 0x80u) | ((w >> 16) & 0x7Fu);
+        *rest = w & 0xFFFFu;
+    } else if (dtype == ORC_FP16) {
+        *x = (w >> 10) & 0x1Fu;
+        *sm = ((w >> 8) & 0x80u) | ((w >> 3) & 0x7Fu);
+        *rest = w & 0x7u;
+    } else {
+        *x = (w >> 7) & 0xFFu;
+        *sm = ((w >> 8) & 0x80u) | (w & 0x7Fu);
+        *rest = 0;
+    }
+}
+
+static uint32_t join_elem(unsigned x, unsigned sm, unsigned rest, int dtype)
+{
+    if (dtype == ORC_FP32) return ((uint32_t)(sm & 0x80u) << 24) | ((uint32_t)x << 23) | ((uint32_t)(sm & 0x7Fu) << 16) | rest;
+    if (dtype == ORC_FP16) return ((sm & 0x80u) << 8) | (x << 10) | ((sm & 0x7Fu) << 3) | rest;
+    return ((sm & 0x80u) << 8) | (x << 7) | (sm & 0x7Fu);
+}
+
+void orc_histogram_dt(const void *w, size_t n_elems, int dtype, uint64_t hist[256])
+{
+    size_t i;
+    memset(hist, 0, 256 * sizeof(uint64_t));
+    for (i = 0; i < n_elems; i++) {
+        unsigned x, sm, rest;
+        split_elem(load_elem(w, i, dtype), dtype, &x, &sm, &rest);
+        hist[x]++;
+    }
 }
 
 void orc_histogram(const uint16_t *w, size_t n_elems, uint64_t hist[256])
 {
-    size_t i;
-    memset(hist, 0, 256 * sizeof(uint64_t));
-    for (i = 0; i < n_elems; i++) hist[(w[i] >> 7) & 0xFF]++;
+    orc_histogram_dt(w, n_elems, ORC_BF16, hist);
 }
 
 /* Phases 2 and 3 on a given histogram.  out_D receives the integer cost
  * sum_x c[x]*y (Eq. 3 times N), out_bexp the value of Eq. 4 at the optimum.
  * Ties: smaller D wins, then smaller n, then smaller b; for m the smaller m.
  * L is fixed to 16.  An empty histogram gives (0, 1, 0). */
-void orc_tune_hist(const uint64_t hist[256], uint8_t params[4], uint64_t *out_D, double *out_bexp)
+void orc_tune_hist_e(const uint64_t hist[256], unsigned E, uint8_t params[4], uint64_t *out_D, double *out_bexp)
 {
     unsigned l = 256, h = 0, x, b, best_b = 0, best_n = 1, m, best_m = 0;
     uint64_t total = 0, best_D = 0;
@@ -233,7 +305,7 @@ void orc_tune_hist(const uint64_t hist[256], uint8_t params[4], uint64_t *out_D,
         return;
     }
     for (b = l; b <= h; b++) {
-        unsigned n = orc_width_for(b, l, h);
+        unsigned n = orc_width_for_e(b, l, h, E);
         uint64_t D = 0;
         for (x = l; x <= h; x++) D += hist[x] * (uint64_t)orc_transform(x, b, n);
         if (!have || D < best_D || (D == best_D && n < best_n)) {
@@ -257,11 +329,23 @@ void orc_tune_hist(const uint64_t hist[256], uint8_t params[4], uint64_t *out_D,
     if (out_bexp) *out_bexp = best_bexp;
 }
 
+void orc_tune_hist(const uint64_t hist[256], uint8_t params[4], uint64_t *out_D, double *out_bexp)
+{
+    orc_tune_hist_e(hist, 8, params, out_D, out_bexp);
+}
+
 void orc_tune(const uint16_t *w, size_t n_elems, uint8_t params[4], uint64_t *out_D, double *out_bexp)
 {
     uint64_t hist[256];
     orc_histogram(w, n_elems, hist);
     orc_tune_hist(hist, params, out_D, out_bexp);
+}
+
+void orc_tune_dt(const void *w, size_t n_elems, int dtype, uint8_t params[4], uint64_t *out_D, double *out_bexp)
+{
+    uint64_t hist[256];
+    orc_histogram_dt(w, n_elems, dtype, hist);
+    orc_tune_hist_e(hist, orc_exp_bits(dtype), params, out_D, out_bexp);
 }
 
 /* ------------------------------------------------------------------ */
@@ -288,18 +372,33 @@ uint32_t orc_default_block(size_t n_elems)
 
 size_t orc_num_blocks(size_t n_elems, uint32_t B) { return (n_elems + B - 1) / B; }
 
-size_t orc_payload_base(size_t n_elems, uint32_t B)
+/* End of header + offset table, rounded up to 16. */
+size_t orc_table_end(size_t n_elems, uint32_t B)
 {
     return align16(ORC_HEADER + 8u * (orc_num_blocks(n_elems, B) + 1u));
 }
 
-/* Worst case: every group anomalous with n = 8, m = 0 or any split of 8. */
-size_t orc_compress_bound(size_t n_elems, uint32_t B)
+/* Where the block payloads start.  An fp32 stream keeps the low 16 mantissa
+ * bits of all elements between the table and the payloads. */
+size_t orc_payload_base_dt(size_t n_elems, uint32_t B, int dtype)
+{
+    size_t base = orc_table_end(n_elems, B);
+    if (dtype == ORC_FP32) base += align16(2u * n_elems);
+    return base;
+}
+
+size_t orc_payload_base(size_t n_elems, uint32_t B) { return orc_payload_base_dt(n_elems, B, ORC_BF16); }
+
+/* Worst case: every group anomalous with n = 8 (bf16, fp32: B raw bytes + B
+ * bytes of planes) or n = 5 (fp16: B raw bytes + (5+3)B/8 bytes of planes). */
+size_t orc_compress_bound_dt(size_t n_elems, uint32_t B, int dtype)
 {
     size_t nb = orc_num_blocks(n_elems, B);
     size_t per_block = align16((size_t)B + B / 128u + (size_t)B);
-    return orc_payload_base(n_elems, B) + nb * per_block;
+    return orc_payload_base_dt(n_elems, B, dtype) + nb * per_block;
 }
+
+size_t orc_compress_bound(size_t n_elems, uint32_t B) { return orc_compress_bound_dt(n_elems, B, ORC_BF16); }
 
 static void put_u16(uint8_t *p, uint16_t v) { p[0] = (uint8_t)v; p[1] = (uint8_t)(v >> 8); }
 static void put_u32(uint8_t *p, uint32_t v) { int i; for (i = 0; i < 4; i++) p[i] = (uint8_t)(v >> (8 * i)); }
@@ -308,64 +407,88 @@ static uint16_t get_u16(const uint8_t *p) { return (uint16_t)(p[0] | (p[1] << 8)
 static uint32_t get_u32(const uint8_t *p) { uint32_t v = 0; int i; for (i = 3; i >= 0; i--) v = (v << 8) | p[i]; return v; }
 static uint64_t get_u64(const uint8_t *p) { uint64_t v = 0; int i; for (i = 7; i >= 0; i--) v = (v << 8) | p[i]; return v; }
 
-static void write_header(uint8_t *out, size_t n_elems, uint32_t B, size_t nb,
+static void write_header(uint8_t *out, size_t n_elems, int dtype, uint32_t B, size_t nb,
                          const uint8_t params[4], uint32_t status, uint64_t total)
 {
     memset(out, 0, ORC_HEADER);
     out[0] = 'E'; out[1] = 'N'; out[2] = 'E'; out[3] = 'C';
     put_u16(out + 4, 1);
-    out[6] = 0;                       /* dtype 0 = bf16 */
+    out[6] = (uint8_t)dtype;
     out[7] = ORC_L;
     put_u64(out + 8, (uint64_t)n_elems);
     put_u32(out + 16, B);
     put_u32(out + 20, (uint32_t)nb);
-    out[24] = params[0]; out[25] = params[1]; out[26] = params[2]; out[27] = 8; /* exponent bits */
+    out[24] = params[0]; out[25] = params[1]; out[26] = params[2];
+    out[27] = (uint8_t)orc_exp_bits(dtype);
     put_u32(out + 28, status);
     put_u64(out + 32, total);
 }
 
-/* Compresses n_elems bf16 values (as little-endian u16) with data-block size B
- * and parameters (b, n, m, L=16).
+/* Compresses n_elems values of the given dtype (little-endian words) with
+ * data-block size B and parameters (b, n, m, L=16); n is at most the width of
+ * the dtype's exponent field.
  *
  * Per data block (Sec. V-A, V-B; stream layout after the Fig. 4 caption):
- *   payload = sign/mantissa bytes of the B elements, element order
+ *   payload = raw bytes (sign<<7 | first seven mantissa bits) of the B elements,
+ *             element order
  *           | group bit mask, B/128 bytes, group g = bit (g mod 8), LSB first,
  *             of byte (g div 8); 1 = anomalous
- *           | Alg. 2 over the low m bits of all B values            (m*B/8 bytes)
+ *           | Alg. 2 over the low plane of all B values
+ *               bf16, fp32: the low m bits of y                     (m*B/8 bytes)
+ *               fp16: the low m bits of y with the element's last three
+ *                     mantissa bits on top, (y mod 2^m) | (w & 7) << m
+ *                                                                   ((m+3)*B/8 bytes)
  *           | for each anomalous group in group order, Alg. 2 over the
  *             high n-m bits of its 16 values                        (2(n-m) bytes each)
  *           | zeros up to a multiple of 16
- * The last block is completed with elements that encode as y = 0 and a zero
- * sign/mantissa byte.  Groups are runs of 16 consecutive elements.
+ * The last block is completed with elements that encode as y = 0 and zero raw
+ * bits.  Groups are runs of 16 consecutive elements.
  * Stream = 64-byte header | (nb+1) u64 block offsets (exclusive prefix sums
- * of payload sizes, last = sum) | zeros to a multiple of 16 | payloads.
+ * of payload sizes, last = sum) | zeros to a multiple of 16
+ *        | fp32 only: the low 16 bits of every element, element order, little
+ *          endian, then zeros to a multiple of 16
+ *        | payloads.
+ * The paper codes exponents only and leaves the storage of the remaining
+ * mantissa bits open (Sec. VI-B "we avoid compressing the mantissa"): fp16's
+ * three bits ride in the low plane because 11 raw bits are no whole number of
+ * bytes and m + 3 <= 8 always fits Alg. 2; fp32's two bytes per element sit at
+ * a position that does not depend on any compressed size.
  *
  * A value outside the representable window gives ORC_E_RANGE: the header is
  * still written, with status = ORC_E_RANGE and total_bytes = 0, *out_bytes = 0.
  */
-int orc_compress(const uint16_t *in, size_t n_elems, uint32_t B, const uint8_t params[4],
-                 uint8_t *out, size_t capacity, size_t *out_bytes)
+int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const uint8_t params[4],
+                    uint8_t *out, size_t capacity, size_t *out_bytes)
 {
-    unsigned b, n, m, a;
-    size_t nb, base, k, off = 0, G;
+    unsigned b, n, m, a, E, lowbits;
+    size_t nb, base, k, off = 0, G, e;
     uint8_t *sm, *maskbytes;
-    uint16_t *y, *tmp;
+    uint16_t *y, *rest, *tmp;
     int range_error = 0;
 
     if (!out || !out_bytes || !params || (!in && n_elems)) return ORC_E_ARG;
+    if (!dtype_ok(dtype)) return ORC_E_DTYPE;
     if (!block_ok(B)) return ORC_E_BLOCK;
+    E = orc_exp_bits(dtype);
     b = params[0]; n = params[1]; m = params[2];
-    if (n < 1 || n > 8 || m > n || params[3] != ORC_L) return ORC_E_PARAMS;
-    if (capacity < orc_compress_bound(n_elems, B)) return ORC_E_CAPACITY;
+    if (n < 1 || n > E || m > n || b >= (1u << E) || params[3] != ORC_L) return ORC_E_PARAMS;
+    if (capacity < orc_compress_bound_dt(n_elems, B, dtype)) return ORC_E_CAPACITY;
     a = n - m;
+    lowbits = m + (dtype == ORC_FP16 ? 3u : 0u);
     nb = orc_num_blocks(n_elems, B);
-    base = orc_payload_base(n_elems, B);
+    base = orc_payload_base_dt(n_elems, B, dtype);
     G = B / ORC_L;
     memset(out, 0, base);
+
+    if (dtype == ORC_FP32) {
+        uint8_t *t = out + orc_table_end(n_elems, B);
+        for (e = 0; e < n_elems; e++) put_u16(t + 2 * e, (uint16_t)(load_elem(in, e, dtype) & 0xFFFFu));
+    }
 
     sm = (uint8_t *)malloc(B);
     maskbytes = (uint8_t *)malloc(G / 8 ? G / 8 : 1);
     y = (uint16_t *)malloc(B * sizeof(uint16_t));
+    rest = (uint16_t *)malloc(B * sizeof(uint16_t));
     tmp = (uint16_t *)malloc(B * sizeof(uint16_t));
 
     for (k = 0; k < nb; k++) {
@@ -373,15 +496,17 @@ int orc_compress(const uint16_t *in, size_t n_elems, uint32_t B, const uint8_t p
         size_t pos = 0, i, g;
         /* split + transform */
         for (i = 0; i < B; i++) {
-            size_t e = k * (size_t)B + i;
+            e = k * (size_t)B + i;
             if (e < n_elems) {
-                unsigned w = in[e];
-                unsigned x = (w >> 7) & 0xFFu;
-                sm[i] = (uint8_t)(((w >> 8) & 0x80u) | (w & 0x7Fu));
-                if (!orc_in_range(x, b, n)) range_error = 1;
+                unsigned x, s, r;
+                split_elem(load_elem(in, e, dtype), dtype, &x, &s, &r);
+                sm[i] = (uint8_t)s;
+                rest[i] = (uint16_t)r;
+                if (!orc_in_range_e(x, b, n, E)) range_error = 1;
                 y[i] = (uint16_t)orc_transform(x, b, n);
             } else {
                 sm[i] = 0;
+                rest[i] = 0;
                 y[i] = 0;
             }
         }
@@ -395,9 +520,13 @@ int orc_compress(const uint16_t *in, size_t n_elems, uint32_t B, const uint8_t p
         memcpy(p + pos, sm, B); pos += B;
         memcpy(p + pos, maskbytes, G / 8); pos += G / 8;
         /* low plane */
-        if (m > 0) {
-            for (i = 0; i < B; i++) tmp[i] = (uint16_t)(y[i] & ((1u << m) - 1u));
-            pos += orc_hh_pack(tmp, B, (int)m, p + pos);
+        if (lowbits > 0) {
+            for (i = 0; i < B; i++) {
+                unsigned v = y[i] & ((1u << m) - 1u);
+                if (dtype == ORC_FP16) v |= (unsigned)rest[i] << m;
+                tmp[i] = (uint16_t)v;
+            }
+            pos += orc_hh_pack(tmp, B, (int)lowbits, p + pos);
         }
         /* high plane: one record per anomalous group */
         for (g = 0; g < G; g++) {
@@ -411,57 +540,78 @@ int orc_compress(const uint16_t *in, size_t n_elems, uint32_t B, const uint8_t p
         off += pos;
     }
     put_u64(out + ORC_HEADER + 8 * nb, (uint64_t)off);
-    free(sm); free(maskbytes); free(y); free(tmp);
+    free(sm); free(maskbytes); free(y); free(rest); free(tmp);
 
     if (range_error) {
-        write_header(out, n_elems, B, nb, params, ORC_E_RANGE, 0);
+        write_header(out, n_elems, dtype, B, nb, params, ORC_E_RANGE, 0);
         *out_bytes = 0;
         return ORC_E_RANGE;
     }
-    write_header(out, n_elems, B, nb, params, ORC_OK, (uint64_t)(base + off));
+    write_header(out, n_elems, dtype, B, nb, params, ORC_OK, (uint64_t)(base + off));
     *out_bytes = base + off;
     return ORC_OK;
 }
 
-/* Reads the fixed header.  Any field may be NULL. */
-int orc_stream_info(const uint8_t *hdr, uint8_t params[4], uint64_t *n_elems, uint32_t *B,
-                    uint64_t *total, uint32_t *status)
+int orc_compress(const uint16_t *in, size_t n_elems, uint32_t B, const uint8_t params[4],
+                 uint8_t *out, size_t capacity, size_t *out_bytes)
+{
+    return orc_compress_dt(in, n_elems, ORC_BF16, B, params, out, capacity, out_bytes);
+}
+
+/* Reads the fixed header.  Any output may be NULL. */
+int orc_stream_info_dt(const uint8_t *hdr, uint8_t params[4], uint64_t *n_elems, uint32_t *B,
+                       uint64_t *total, uint32_t *status, int *dtype)
 {
     if (!hdr) return ORC_E_ARG;
     if (hdr[0] != 'E' || hdr[1] != 'N' || hdr[2] != 'E' || hdr[3] != 'C') return ORC_E_FORMAT;
     if (get_u16(hdr + 4) != 1) return ORC_E_FORMAT;
-    if (hdr[6] != 0) return ORC_E_DTYPE;
-    if (hdr[7] != ORC_L || hdr[27] != 8) return ORC_E_FORMAT;
+    if (!dtype_ok(hdr[6])) return ORC_E_DTYPE;
+    if (hdr[7] != ORC_L || hdr[27] != orc_exp_bits(hdr[6])) return ORC_E_FORMAT;
     if (params) { params[0] = hdr[24]; params[1] = hdr[25]; params[2] = hdr[26]; params[3] = hdr[7]; }
     if (n_elems) *n_elems = get_u64(hdr + 8);
     if (B) *B = get_u32(hdr + 16);
     if (total) *total = get_u64(hdr + 32);
     if (status) *status = get_u32(hdr + 28);
+    if (dtype) *dtype = hdr[6];
     return ORC_OK;
 }
 
-/* Decompresses a stream made by orc_compress into n_elems u16 values. */
-int orc_decompress(const uint8_t *in, size_t in_bytes, uint16_t *out, size_t n_elems)
+/* The bf16-only form: any other dtype in the header is ORC_E_DTYPE. */
+int orc_stream_info(const uint8_t *hdr, uint8_t params[4], uint64_t *n_elems, uint32_t *B,
+                    uint64_t *total, uint32_t *status)
+{
+    int dtype = 0, rc = orc_stream_info_dt(hdr, params, n_elems, B, total, status, &dtype);
+    if (rc == ORC_OK && dtype != ORC_BF16) return ORC_E_DTYPE;
+    return rc;
+}
+
+/* Decompresses a stream made by orc_compress_dt into n_elems values of the
+ * dtype its header names (u16 or u32 words). */
+int orc_decompress_dt(const uint8_t *in, size_t in_bytes, void *out, size_t n_elems)
 {
     uint8_t params[4];
     uint64_t hdr_n, total;
     uint32_t B, status;
-    unsigned b, n, m, a;
+    unsigned b, n, m, a, E, lowbits;
     size_t nb, base, k, G;
     uint16_t *low, *high, *prefix;
-    int rc;
+    const uint8_t *tail16;
+    int rc, dtype;
 
     if (!in || (!out && n_elems) || in_bytes < ORC_HEADER) return ORC_E_ARG;
-    rc = orc_stream_info(in, params, &hdr_n, &B, &total, &status);
+    rc = orc_stream_info_dt(in, params, &hdr_n, &B, &total, &status, &dtype);
     if (rc != ORC_OK) return rc;
     if (status != ORC_OK || hdr_n != (uint64_t)n_elems || !block_ok(B)) return ORC_E_FORMAT;
+    E = orc_exp_bits(dtype);
     b = params[0]; n = params[1]; m = params[2];
-    if (n < 1 || n > 8 || m > n) return ORC_E_FORMAT;
+    if (n < 1 || n > E || m > n) return ORC_E_FORMAT;
     a = n - m;
+    lowbits = m + (dtype == ORC_FP16 ? 3u : 0u);
     nb = orc_num_blocks(n_elems, B);
-    base = orc_payload_base(n_elems, B);
+    base = orc_payload_base_dt(n_elems, B, dtype);
     if (get_u32(in + 20) != (uint32_t)nb || total > in_bytes || total < base) return ORC_E_FORMAT;
     G = B / ORC_L;
+    tail16 = in + orc_table_end(n_elems, B);
 
     low = (uint16_t *)malloc(B * sizeof(uint16_t));
     high = (uint16_t *)malloc(ORC_L * sizeof(uint16_t));
@@ -473,29 +623,44 @@ int orc_decompress(const uint8_t *in, size_t in_bytes, uint16_t *out, size_t n_e
         const uint8_t *sm = p;
         const uint8_t *maskbytes = p + B;
         const uint8_t *lowplane = maskbytes + G / 8;
-        const uint8_t *highplane = lowplane + (size_t)m * B / 8;
+        const uint8_t *highplane = lowplane + (size_t)lowbits * B / 8;
         size_t i, g;
         /* mask bits -> {0,1} integers -> exclusive prefix sum = record index */
         prefix[0] = 0;
         for (g = 0; g < G; g++)
             prefix[g + 1] = (uint16_t)(prefix[g] + ((maskbytes[g / 8] >> (g % 8)) & 1u));
-        if (m > 0) orc_hh_unpack(lowplane, B, (int)m, low);
+        if (lowbits > 0) orc_hh_unpack(lowplane, B, (int)lowbits, low);
         else for (i = 0; i < B; i++) low[i] = 0;
         for (g = 0; g < G; g++) {
             int anomalous = (maskbytes[g / 8] >> (g % 8)) & 1u;
             if (anomalous) orc_hh_unpack(highplane + (size_t)2 * a * prefix[g], ORC_L, (int)a, high);
             for (i = 0; i < ORC_L; i++) {
                 size_t e = k * (size_t)B + g * ORC_L + i;
-                unsigned yv, x, s;
+                unsigned yv, x, s, r = 0;
+                uint32_t w;
                 if (e >= n_elems) break;
-                yv = low[g * ORC_L + i];
+                yv = low[g * ORC_L + i] & ((1u << m) - 1u);
+                if (dtype == ORC_FP16) r = low[g * ORC_L + i] >> m;
+                if (dtype == ORC_FP32) r = get_u16(tail16 + 2 * e);
                 if (anomalous) yv |= (unsigned)high[i] << m;
-                x = orc_inverse_transform(yv, b, n);
+                x = orc_inverse_transform_e(yv, b, n, E);
                 s = sm[g * ORC_L + i];
-                out[e] = (uint16_t)(((s & 0x80u) << 8) | (x << 7) | (s & 0x7Fu));
+                w = join_elem(x, s, r, dtype);
+                if (dtype == ORC_FP32) ((uint32_t *)out)[e] = w;
+                else ((uint16_t *)out)[e] = (uint16_t)w;
             }
         }
     }
     free(low); free(high); free(prefix);
     return ORC_OK;
+}
+
+/* The bf16-only form. */
+int orc_decompress(const uint8_t *in, size_t in_bytes, uint16_t *out, size_t n_elems)
+{
+    if (in && in_bytes >= ORC_HEADER && in[6] != ORC_BF16 && in[0] == 'E') {
+        int rc = orc_stream_info(in, NULL, NULL, NULL, NULL, NULL);
+        if (rc != ORC_OK) return rc;
+    }
+    return orc_decompress_dt(in, in_bytes, out, n_elems);
 }

@@ -19,6 +19,7 @@ _SRC = os.path.join(_HERE, "enec_oracle.c")
 _LIB = os.path.join(_HERE, "libenec_oracle.so")
 
 OK, E_ARG, E_DTYPE, E_BLOCK, E_PARAMS, E_CAPACITY, E_RANGE, E_FORMAT = range(8)
+BF16, FP16, FP32 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -72,6 +73,32 @@ def lib():
                                       C.POINTER(C.c_uint32)]
         L.orc_decompress.restype = C.c_int
         L.orc_decompress.argtypes = [u8p, C.c_size_t, u16p, C.c_size_t]
+        L.orc_in_range_e.restype = C.c_int
+        L.orc_in_range_e.argtypes = [C.c_uint] * 4
+        L.orc_inverse_transform_e.restype = C.c_uint
+        L.orc_inverse_transform_e.argtypes = [C.c_uint] * 4
+        L.orc_width_for_e.restype = C.c_uint
+        L.orc_width_for_e.argtypes = [C.c_uint] * 4
+        L.orc_exp_bits.restype = C.c_uint
+        L.orc_exp_bits.argtypes = [C.c_int]
+        L.orc_histogram_dt.restype = None
+        L.orc_histogram_dt.argtypes = [C.c_void_p, C.c_size_t, C.c_int, u64p]
+        L.orc_tune_hist_e.restype = None
+        L.orc_tune_hist_e.argtypes = [u64p, C.c_uint, u8p, u64p, C.POINTER(C.c_double)]
+        L.orc_table_end.restype = C.c_size_t
+        L.orc_table_end.argtypes = [C.c_size_t, C.c_uint32]
+        L.orc_payload_base_dt.restype = C.c_size_t
+        L.orc_payload_base_dt.argtypes = [C.c_size_t, C.c_uint32, C.c_int]
+        L.orc_compress_bound_dt.restype = C.c_size_t
+        L.orc_compress_bound_dt.argtypes = [C.c_size_t, C.c_uint32, C.c_int]
+        L.orc_compress_dt.restype = C.c_int
+        L.orc_compress_dt.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_uint32, u8p, u8p, C.c_size_t,
+                                      C.POINTER(C.c_size_t)]
+        L.orc_stream_info_dt.restype = C.c_int
+        L.orc_stream_info_dt.argtypes = [u8p, u8p, u64p, C.POINTER(C.c_uint32), u64p,
+                                         C.POINTER(C.c_uint32), C.POINTER(C.c_int)]
+        L.orc_decompress_dt.restype = C.c_int
+        L.orc_decompress_dt.argtypes = [u8p, C.c_size_t, C.c_void_p, C.c_size_t]
         _lib = L
     return _lib
 
@@ -83,6 +110,14 @@ def _p(arr, ctype):
 def _u16(w) -> np.ndarray:
     w = np.ascontiguousarray(w)
     assert w.dtype == np.uint16, "bf16 values are passed as their uint16 bit patterns"
+    return w.reshape(-1)
+
+
+def _words(w, dtype: int) -> np.ndarray:
+    """Elements as their bit patterns: uint16 for bf16 / fp16, uint32 for fp32."""
+    w = np.ascontiguousarray(w)
+    want = np.uint32 if dtype == FP32 else np.uint16
+    assert w.dtype == want, f"dtype {dtype} takes {want.__name__} bit patterns"
     return w.reshape(-1)
 
 
@@ -116,26 +151,42 @@ def width_for(b: int, l: int, h: int) -> int:
     return int(lib().orc_width_for(b, l, h))
 
 
-def histogram(w) -> np.ndarray:
-    w = _u16(w)
+def exp_bits(dtype: int) -> int:
+    return int(lib().orc_exp_bits(dtype))
+
+
+def in_range_e(x: int, b: int, n: int, E: int) -> bool:
+    return bool(lib().orc_in_range_e(x, b, n, E))
+
+
+def inverse_transform_e(y: int, b: int, n: int, E: int) -> int:
+    return int(lib().orc_inverse_transform_e(y, b, n, E))
+
+
+def width_for_e(b: int, l: int, h: int, E: int) -> int:
+    return int(lib().orc_width_for_e(b, l, h, E))
+
+
+def histogram(w, dtype: int = BF16) -> np.ndarray:
+    w = _words(w, dtype)
     hist = np.zeros(256, dtype=np.uint64)
-    lib().orc_histogram(_p(w, C.c_uint16), w.size, _p(hist, C.c_uint64))
+    lib().orc_histogram_dt(w.ctypes.data, w.size, dtype, _p(hist, C.c_uint64))
     return hist
 
 
-def tune_hist(hist):
-    """-> ((b, n, m, L), D_integer, B_exp)"""
+def tune_hist(hist, E: int = 8):
+    """-> ((b, n, m, L), D_integer, B_exp); E = width of the exponent field"""
     hist = np.ascontiguousarray(hist, dtype=np.uint64)
     params = np.zeros(4, dtype=np.uint8)
     D = C.c_uint64(0)
     bexp = C.c_double(0)
-    lib().orc_tune_hist(_p(hist, C.c_uint64), _p(params, C.c_uint8), C.byref(D), C.byref(bexp))
+    lib().orc_tune_hist_e(_p(hist, C.c_uint64), E, _p(params, C.c_uint8), C.byref(D), C.byref(bexp))
     return tuple(int(v) for v in params), int(D.value), float(bexp.value)
 
 
-def tune(w):
-    """-> (b, n, m, L) for a tensor of bf16 bit patterns."""
-    return tune_hist(histogram(w))[0]
+def tune(w, dtype: int = BF16):
+    """-> (b, n, m, L) for a tensor of bit patterns."""
+    return tune_hist(histogram(w, dtype), exp_bits(dtype))[0]
 
 
 def default_block(n_elems: int) -> int:
@@ -146,27 +197,31 @@ def num_blocks(n_elems: int, B: int) -> int:
     return int(lib().orc_num_blocks(n_elems, B))
 
 
-def payload_base(n_elems: int, B: int) -> int:
-    return int(lib().orc_payload_base(n_elems, B))
+def table_end(n_elems: int, B: int) -> int:
+    return int(lib().orc_table_end(n_elems, B))
 
 
-def compress_bound(n_elems: int, B: int) -> int:
-    return int(lib().orc_compress_bound(n_elems, B))
+def payload_base(n_elems: int, B: int, dtype: int = BF16) -> int:
+    return int(lib().orc_payload_base_dt(n_elems, B, dtype))
 
 
-def compress(w, params, B: int = 16384, capacity: int | None = None):
-    """-> (status, stream bytes as uint8 array).  On E_RANGE the array holds header+table only."""
-    w = _u16(w)
-    cap = compress_bound(w.size, B) if capacity is None else capacity
+def compress_bound(n_elems: int, B: int, dtype: int = BF16) -> int:
+    return int(lib().orc_compress_bound_dt(n_elems, B, dtype))
+
+
+def compress(w, params, B: int = 16384, capacity: int | None = None, dtype: int = BF16):
+    """-> (status, stream bytes as uint8 array).  On E_RANGE the array holds everything before the payloads."""
+    w = _words(w, dtype)
+    cap = compress_bound(w.size, B, dtype) if capacity is None else capacity
     out = np.zeros(max(cap, 1), dtype=np.uint8)
     prm = np.asarray(params, dtype=np.uint8)
     nbytes = C.c_size_t(0)
-    rc = lib().orc_compress(_p(w, C.c_uint16), w.size, B, _p(prm, C.c_uint8), _p(out, C.c_uint8),
-                            cap, C.byref(nbytes))
+    rc = lib().orc_compress_dt(w.ctypes.data, w.size, dtype, B, _p(prm, C.c_uint8), _p(out, C.c_uint8),
+                               cap, C.byref(nbytes))
     if rc == OK:
         return rc, out[:nbytes.value].copy()
     if rc == E_RANGE:
-        return rc, out[:payload_base(w.size, B)].copy()
+        return rc, out[:payload_base(w.size, B, dtype)].copy()
     return rc, None
 
 
@@ -177,15 +232,18 @@ def stream_info(stream) -> dict:
     B = C.c_uint32(0)
     total = C.c_uint64(0)
     status = C.c_uint32(0)
-    rc = lib().orc_stream_info(_p(s, C.c_uint8), _p(params, C.c_uint8), C.byref(n), C.byref(B),
-                               C.byref(total), C.byref(status))
+    dt = C.c_int(0)
+    rc = lib().orc_stream_info_dt(_p(s, C.c_uint8), _p(params, C.c_uint8), C.byref(n), C.byref(B),
+                                  C.byref(total), C.byref(status), C.byref(dt))
     return dict(rc=rc, params=tuple(int(v) for v in params), n_elems=int(n.value),
-                block_size=int(B.value), total_bytes=int(total.value), status=int(status.value))
+                block_size=int(B.value), total_bytes=int(total.value), status=int(status.value),
+                dtype=int(dt.value))
 
 
 def decompress(stream, n_elems: int):
-    """-> (status, uint16 array)"""
+    """-> (status, array of bit patterns: uint32 if the header says fp32, else uint16)"""
     s = np.ascontiguousarray(stream, dtype=np.uint8)
-    out = np.zeros(n_elems, dtype=np.uint16)
-    rc = lib().orc_decompress(_p(s, C.c_uint8), s.size, _p(out, C.c_uint16), n_elems)
+    fp32 = s.size > 6 and int(s[6]) == FP32
+    out = np.zeros(n_elems, dtype=np.uint32 if fp32 else np.uint16)
+    rc = lib().orc_decompress_dt(_p(s, C.c_uint8), s.size, out.ctypes.data, n_elems)
     return rc, out

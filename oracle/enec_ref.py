@@ -12,7 +12,9 @@ vectorised forms, so that the two can check each other:
   * the group test uses the definition "largest bit width in the group > m"
     instead of the bitwise OR the paper substitutes for it (Sec. V-B);
   * record positions come from a running count of mask bits (Alg. 1,
-    decompression part).
+    decompression part);
+  * elements are taken apart by the IEEE field widths (sign, exponent, mantissa)
+    with divisions and remainders, not by per-format shift constants.
 
 Everything works on Python integers; use it for blocks of 128-2048 elements.
 """
@@ -87,22 +89,41 @@ def transform(x, b, n):
     return (b - x) % (1 << n)          # Python's % is already non-negative
 
 
-def in_range(x, b, n):
-    return n >= 8 or -(1 << (n - 1)) <= b - x <= (1 << (n - 1)) - 1
+def in_range(x, b, n, E=8):
+    return n >= E or -(1 << (n - 1)) <= b - x <= (1 << (n - 1)) - 1
 
 
-def inverse_transform(y, b, n):
+def inverse_transform(y, b, n, E=8):
     s = y - (1 << n) if y >= (1 << (n - 1)) else y
-    return (b - s) % 256
+    return (b - s) % (1 << E)
 
 
-def width_for(b, l, h):
+def width_for(b, l, h, E=8):
     pos = (b - l).bit_length()
     neg = (h - b - 1).bit_length() if h > b else 0
-    return min(8, max(pos, neg) + 1)
+    return min(E, max(pos, neg) + 1)
 
 
-def tune_hist(hist):
+# dtype code -> (exponent bits, mantissa bits); the sign is the top bit
+FIELDS = {0: (8, 7), 1: (5, 10), 2: (8, 23)}
+
+
+def take_apart(w, dtype):
+    """-> (exponent, raw byte sign*128 + first seven mantissa bits, left-over mantissa bits)"""
+    E, M = FIELDS[dtype]
+    mant = w % (1 << M)
+    expo = (w // (1 << M)) % (1 << E)
+    sign = w // (1 << (M + E))
+    return expo, sign * 128 + mant // (1 << (M - 7)), mant % (1 << (M - 7))
+
+
+def put_together(expo, raw, rest, dtype):
+    E, M = FIELDS[dtype]
+    mant = (raw % 128) * (1 << (M - 7)) + rest
+    return ((raw // 128) * (1 << E) + expo) * (1 << M) + mant
+
+
+def tune_hist(hist, E=8):
     """Phases 2-3 of Sec. V-E on a 256-bin histogram -> ((b, n, m, L), D, B_exp)."""
     occupied = [x for x in range(256) if hist[x]]
     if not occupied:
@@ -111,7 +132,7 @@ def tune_hist(hist):
     total = sum(int(hist[x]) for x in occupied)
     best = None
     for b in range(l, h + 1):
-        n = width_for(b, l, h)
+        n = width_for(b, l, h, E)
         D = sum(int(hist[x]) * transform(x, b, n) for x in occupied)
         key = (D, n, b)
         if best is None or key < best:
@@ -131,11 +152,11 @@ def tune_hist(hist):
     return (b, n, best_m[1], L), D, best_m[0]
 
 
-def tune(words):
+def tune(words, dtype=0):
     hist = [0] * 256
     for w in words:
-        hist[(int(w) >> 7) & 0xFF] += 1
-    return tune_hist(hist)[0]
+        hist[take_apart(int(w), dtype)[0]] += 1
+    return tune_hist(hist, FIELDS[dtype][0])[0]
 
 
 # --------------------------------------------------------------------------
@@ -145,10 +166,12 @@ def _align16(v):
     return (v + 15) & ~15
 
 
-def compress(words, params, B):
-    """-> (range_ok, bytes)"""
+def compress(words, params, B, dtype=0):
+    """-> (range_ok, bytes).  fp16: the three left-over mantissa bits sit on top of the low
+    m bits in the low plane; fp32: the sixteen left-over bits of all elements follow the table."""
     b, n, m, Lp = params
-    assert Lp == L and 1 <= n <= 8 and 0 <= m <= n
+    E = FIELDS[dtype][0]
+    assert Lp == L and 1 <= n <= E and 0 <= m <= n
     a = n - m
     words = [int(w) for w in words]
     N = len(words)
@@ -158,31 +181,40 @@ def compress(words, params, B):
     for k in range(nb):
         blk = list(words[k * B:(k + 1) * B])
         real = len(blk)
-        sm = [((w >> 8) & 0x80) | (w & 0x7F) for w in blk] + [0] * (B - real)
-        xs = [(w >> 7) & 0xFF for w in blk]
-        ok = ok and all(in_range(x, b, n) for x in xs)
+        parts = [take_apart(w, dtype) for w in blk]
+        sm = [p[1] for p in parts] + [0] * (B - real)
+        rest = [p[2] for p in parts] + [0] * (B - real)
+        xs = [p[0] for p in parts]
+        ok = ok and all(in_range(x, b, n, E) for x in xs)
         y = [transform(x, b, n) for x in xs] + [0] * (B - real)
         anomalous = [max(v.bit_length() for v in y[g * L:(g + 1) * L]) > m for g in range(G)]
         mask = bytearray(G // 8)
         for g, flag in enumerate(anomalous):
             if flag:
                 mask[g // 8] |= 1 << (g % 8)
-        low = hh_pack([v & ((1 << m) - 1) for v in y], m) if m else b""
+        if dtype == 1:
+            low = hh_pack([v % (1 << m) + r * (1 << m) for v, r in zip(y, rest)], m + 3)
+        else:
+            low = hh_pack([v & ((1 << m) - 1) for v in y], m) if m else b""
         high = b"".join(hh_pack([v >> m for v in y[g * L:(g + 1) * L]], a)
                         for g in range(G) if anomalous[g])
         p = bytes(sm) + bytes(mask) + low + high
         p += bytes(_align16(len(p)) - len(p))
         payloads.append(p)
         offsets.append(offsets[-1] + len(p))
-    base = _align16(HEADER + 8 * (nb + 1))
+    tail = b""
+    if dtype == 2:
+        tail = b"".join(struct.pack("<H", take_apart(w, dtype)[2]) for w in words)
+        tail += bytes(_align16(len(tail)) - len(tail))
+    base = _align16(HEADER + 8 * (nb + 1)) + len(tail)
     total = base + offsets[-1]
     status = 0 if ok else 6
-    hdr = struct.pack("<4sHBBQIIBBBBIQ", b"ENEC", 1, 0, L, N, B, nb, b, n, m, 8, status,
+    hdr = struct.pack("<4sHBBQIIBBBBIQ", b"ENEC", 1, dtype, L, N, B, nb, b, n, m, E, status,
                       total if ok else 0)
     hdr += bytes(HEADER - len(hdr))
     table = b"".join(struct.pack("<Q", o) for o in offsets)
     head = hdr + table
-    head += bytes(base - len(head))
+    head += bytes(_align16(len(head)) - len(head)) + tail
     return ok, head + b"".join(payloads)
 
 
@@ -190,20 +222,22 @@ def decompress(stream, N):
     stream = bytes(stream)
     magic, ver, dtype, Lp, n_elems, B, nb, b, n, m, ebits, status, total = struct.unpack_from(
         "<4sHBBQIIBBBBIQ", stream, 0)
-    assert magic == b"ENEC" and ver == 1 and dtype == 0 and Lp == L and ebits == 8
+    assert magic == b"ENEC" and ver == 1 and dtype in FIELDS and Lp == L and ebits == FIELDS[dtype][0]
     assert n_elems == N and status == 0
     a = n - m
     G = B // L
-    base = _align16(HEADER + 8 * (nb + 1))
+    tail_at = _align16(HEADER + 8 * (nb + 1))
+    base = tail_at + (_align16(2 * N) if dtype == 2 else 0)
+    lowbits = m + (3 if dtype == 1 else 0)
     out = []
     for k in range(nb):
         off = struct.unpack_from("<Q", stream, HEADER + 8 * k)[0]
         p = stream[base + off:]
         sm = p[:B]
         mask = p[B:B + G // 8]
-        lowplane = p[B + G // 8:B + G // 8 + m * B // 8]
-        highplane = p[B + G // 8 + m * B // 8:]
-        low = hh_unpack(lowplane, B, m) if m else [0] * B
+        lowplane = p[B + G // 8:B + G // 8 + lowbits * B // 8]
+        highplane = p[B + G // 8 + lowbits * B // 8:]
+        low = hh_unpack(lowplane, B, lowbits) if lowbits else [0] * B
         seen = 0                                   # running count of mask bits
         for g in range(G):
             bit = (mask[g // 8] >> (g % 8)) & 1
@@ -213,8 +247,10 @@ def decompress(stream, N):
                 e = k * B + g * L + i
                 if e >= N:
                     break
-                y = low[g * L + i] | (high[i] << m)
-                x = inverse_transform(y, b, n)
-                s = sm[g * L + i]
-                out.append(((s & 0x80) << 8) | (x << 7) | (s & 0x7F))
+                y = low[g * L + i] % (1 << m) + (high[i] << m)
+                rest = low[g * L + i] >> m if dtype == 1 else 0
+                if dtype == 2:
+                    rest = struct.unpack_from("<H", stream, tail_at + 2 * e)[0]
+                x = inverse_transform(y, b, n, ebits)
+                out.append(put_together(x, sm[g * L + i], rest, dtype))
     return out
