@@ -1,5 +1,5 @@
 /*
- * libenec -- ENEC lossless codec for bf16 model weights on AMD MI355X (gfx950).
+ * libenec -- ENEC lossless codec for bf16 / fp16 / fp32 model weights on AMD MI355X (gfx950).
  *
  * C ABI.  Every entry point takes plain pointers and sizes; the doc of each argument
  * says whether it is a HOST or a DEVICE pointer.  The library allocates no device
@@ -10,6 +10,7 @@
  *
  * The codec (paper sections in brackets):
  *   bf16 word -> exponent x (8 bit) and a raw sign+mantissa byte       [Sec. IV-B; Sec. V-A step 1]
+ *   fp16 / fp32 are split the same way, only exponents are coded        [Alg. 1 input; Sec. VI-B]
  *   y = (b - x) mod 2^n, the branch-free integer transformation        [Sec. V-C; Eq. 2]
  *   per group of L = 16 consecutive elements: OR of the y; the group is
  *   stored with m bits per element if OR < 2^m, else with n bits       [Sec. V-B]
@@ -22,23 +23,27 @@
  *   parameters (b, n, m, L) from the exponent histogram                 [Sec. V-E, Eq. 1-4]
  *
  * Stream format, version 1 (all integers little-endian):
- *   0   "ENEC"                 4   u16 version = 1      6  u8 dtype (0 = bf16)   7  u8 L (= 16)
+ *   0   "ENEC"                 4   u16 version = 1      6  u8 dtype (enec_dtype) 7  u8 L (= 16)
  *   8   u64 n_elems            16  u32 block_size B     20 u32 n_blocks nb = ceil(n_elems / B)
- *   24  u8 b   25 u8 n   26 u8 m   27 u8 exponent bits (= 8)
+ *   24  u8 b   25 u8 n   26 u8 m   27 u8 exponent bits (8; fp16: 5)
  *   28  u32 status (ENEC_OK or ENEC_E_RANGE)            32 u64 total_bytes (0 if status != OK)
  *   40..63 zero
  *   64  (nb + 1) x u64: offset of each data block's payload relative to the payload base,
  *       i.e. the exclusive prefix sums of payload sizes; entry nb is their total
- *   zero bytes up to payload base = align16(64 + 8 (nb + 1))
+ *   zero bytes up to align16(64 + 8 (nb + 1)) = payload base for bf16 and fp16
+ *   fp32 only: the lower 16 bits of every element, element order, then zero bytes up to a
+ *       multiple of 16; the payload base follows.  (The upper 16 bits of an fp32 element are a
+ *       bf16 word and are coded as such.)
  *   per data block, at payload base + offset[k] (always 16-byte aligned):
- *       B bytes            sign<<7 | mantissa of every element, element order
+ *       B bytes            sign<<7 | first seven mantissa bits of every element, element order
  *       B/128 bytes        group mask: group g is bit (g mod 8), LSB first, of byte (g div 8);
  *                          1 = stored with n bits
- *       m*B/8 bytes        Alg. 2 over (y mod 2^m) of all B elements
+ *       m*B/8 bytes        Alg. 2 over (y mod 2^m) of all B elements; fp16: (m+3)*B/8 bytes, Alg. 2
+ *                          over (y mod 2^m) | (last three mantissa bits) << m
  *       2(n-m) bytes per masked group, in group order: Alg. 2 over (y >> m) of its 16 elements
  *       zero bytes up to a multiple of 16
- *   The last data block is completed with elements that encode as y = 0 and a zero
- *   sign/mantissa byte.
+ *   The last data block is completed with elements that encode as y = 0 and zero sign and
+ *   mantissa bits.
  */
 #ifndef ENEC_H
 #define ENEC_H
@@ -53,16 +58,18 @@ extern "C" {
 typedef enum {
     ENEC_OK = 0,
     ENEC_E_ARG = 1,       /* null / misaligned pointer, size out of range */
-    ENEC_E_DTYPE = 2,     /* only ENEC_BF16 is implemented */
+    ENEC_E_DTYPE = 2,     /* not one of enec_dtype */
     ENEC_E_BLOCK = 3,     /* block_size not a power of two in [2048, 32768] */
-    ENEC_E_PARAMS = 4,    /* need 1 <= n <= 8, 0 <= m <= n, L == 16 */
+    ENEC_E_PARAMS = 4,    /* need 1 <= n <= E, 0 <= m <= n, b < 2^E, L == 16 (E = exponent bits: 8, fp16: 5) */
     ENEC_E_CAPACITY = 5,  /* out_capacity < enec_compress_bound() or workspace too small */
-    ENEC_E_RANGE = 6,     /* an exponent lies outside [b - 2^(n-1) + 1, b + 2^(n-1)] while n < 8 */
+    ENEC_E_RANGE = 6,     /* an exponent lies outside [b - 2^(n-1) + 1, b + 2^(n-1)] while n < E */
     ENEC_E_FORMAT = 7,    /* not an ENEC stream, or header does not match the call */
     ENEC_E_HIP = 8        /* a HIP runtime call failed */
 } enec_status;
 
-typedef enum { ENEC_BF16 = 0 } enec_dtype;
+/* Element formats [Alg. 1 input line; Table VI]: sign | exponent | mantissa = 1|8|7, 1|5|10, 1|8|23.
+ * Tensors are arrays of little-endian 16-bit (bf16, fp16) or 32-bit (fp32) words. */
+typedef enum { ENEC_BF16 = 0, ENEC_FP16 = 1, ENEC_FP32 = 2 } enec_dtype;
 
 /* Codec parameters [Sec. V-E; Table VI]: mapping centre b, stored width n, threshold width m,
  * group length L (must be 16). */
@@ -96,9 +103,9 @@ size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size);
  * the workspace again. */
 int enec_workspace_init(void *workspace, size_t bytes, void *stream);
 
-/* Compress n_elems bf16 values [Sec. V-A compression path; Sec. V-B; Sec. V-C; Fig. 4].
- *   in            DEVICE, n_elems * 2 bytes, 16-byte aligned, read only
- *   dtype         ENEC_BF16
+/* Compress n_elems values [Sec. V-A compression path; Sec. V-B; Sec. V-C; Fig. 4].
+ *   in            DEVICE, n_elems * 2 bytes (fp32: * 4), 16-byte aligned, read only
+ *   dtype         an enec_dtype
  *   block_size    data-block size B in elements: power of two in [2048, 32768], 0 = default
  *   params        HOST, read before return.  NULL = tune on the device first (this makes the call
  *                 synchronous: it waits for the histogram, see enec_tune)
@@ -143,7 +150,7 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
  *   in        DEVICE, a stream written by enec_compress, 16-byte aligned
  *   in_bytes  size of the buffer behind `in`; ENEC_E_FORMAT if the header's total_bytes exceeds it.
  *             The kernel never reads past the header's total_bytes.
- *   out       DEVICE, n_elems * 2 bytes, 16-byte aligned
+ *   out       DEVICE, n_elems * 2 bytes (4 if the header's dtype is fp32), 16-byte aligned
  *   n_elems   must equal the header's n_elems
  * This variant copies the 64-byte header to the host first (one small synchronous copy on
  * `stream`), validates it (ENEC_E_FORMAT / ENEC_E_DTYPE), then enqueues one kernel. */
@@ -155,7 +162,7 @@ int enec_decompress(const void *in, size_t in_bytes, void *out, size_t n_elems, 
 int enec_decompress_with_header(const void *in, size_t in_bytes, const void *host_header, void *out,
                                 size_t n_elems, void *stream);
 
-/* Decompress several streams with one launch per (m, n - m, block size); fields as the arguments of
+/* Decompress several streams with one launch per (dtype, m, n - m, block size); fields as the arguments of
  * enec_decompress_with_header.  Fully asynchronous. */
 typedef struct {
     const void *in;             /* DEVICE */
@@ -168,7 +175,7 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
 
 /* Parameter tuning [Sec. V-E phases 1-3]: exponent histogram on the device (one read of the
  * tensor), then the search for (b, n) by Eq. 1-3 and for m by Eq. 4 (L = 16) on the host.
- *   in         DEVICE, n_elems * 2 bytes, 16-byte aligned
+ *   in         DEVICE, n_elems * 2 bytes (fp32: * 4), 16-byte aligned
  *   params     HOST, written before return
  *   histogram  NULL, or HOST array of 256 u64 that receives the exponent counts
  *   workspace  DEVICE, as for enec_compress (workspace_bytes: its size)
@@ -176,8 +183,9 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
 int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params,
               uint64_t *histogram, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Host-only search of Sec. V-E phases 2-3 on a given 256-bin exponent histogram (HOST). */
-int enec_tune_histogram(const uint64_t *histogram, enec_params *params);
+/* Host-only search of Sec. V-E phases 2-3 on a given 256-bin exponent histogram (HOST); dtype
+ * fixes the cap of Eq. 1's width (the exponent field: 8 bits, fp16: 5). */
+int enec_tune_histogram(const uint64_t *histogram, int dtype, enec_params *params);
 
 /* Parse a HOST copy of a stream's first 64 bytes.  Any output pointer may be NULL.
  * Returns ENEC_E_FORMAT if it is not a version-1 ENEC header. */

@@ -1,26 +1,58 @@
-"""Builds libenec.so (HIP, gfx950) in-tree with hipcc.  `python -m paper_2604_03298_amd.build`."""
+"""Builds libenec.so (HIP, gfx950) in-tree with hipcc.  `python -m paper_2604_03298_amd.build`.
+
+The host code (csrc/enec_api.hip) and the six kernel tables (csrc/enec_kernels.hip, once per element
+format and direction) are compiled side by side into _build/*.o and linked into libenec.so.
+"""
 from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libenec.so")
-SOURCES = [os.path.join(HERE, "csrc", "enec_api.hip")]
-HEADERS = [os.path.join(HERE, "csrc", "enec_device.hpp"), os.path.join(ROOT, "include", "enec.h")]
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+SOURCES = [os.path.join(CSRC, "enec_api.hip"), os.path.join(CSRC, "enec_kernels.hip")]
+HEADERS = [os.path.join(CSRC, "enec_device.hpp"), os.path.join(CSRC, "enec_kernels.hpp"),
+           os.path.join(ROOT, "include", "enec.h")]
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-ffp-contract=off",
+         "-fPIC", "-I", os.path.join(ROOT, "include")]
+
+
+def _units():
+    units = [("enec_api.o", [SOURCES[0]])]
+    for dt in (0, 1, 2):
+        for direction in (0, 1):
+            units.append((f"enec_kernels_dt{dt}_dir{direction}.o", [f"-DENEC_DT={dt}", f"-DENEC_DIR={direction}", SOURCES[1]]))
+    return units
 
 
 def build(verbose: bool = False) -> str:
     """Compiles every HIP source for gfx950 (cross-compiles without a GPU) and returns the path."""
-    cmd = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-ffp-contract=off",
-           "-fPIC", "-shared", "-I", os.path.join(ROOT, "include"), "-o", LIB] + SOURCES
+    os.makedirs(OBJ, exist_ok=True)
+
+    def compile_one(unit):
+        name, args = unit
+        cmd = ["hipcc"] + FLAGS + ["-c", "-o", os.path.join(OBJ, name)] + args
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+        return os.path.join(OBJ, name)
+
+    workers = max(1, min(7, os.cpu_count() or 1))
+    with ThreadPoolExecutor(workers) as pool:
+        objects = list(pool.map(compile_one, _units()))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB] + objects
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+        raise RuntimeError("hipcc (link) failed:\n" + res.stdout + res.stderr)
     return LIB
 
 

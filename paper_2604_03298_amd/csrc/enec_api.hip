@@ -1,12 +1,47 @@
 // Host side of libenec: argument checks, kernel dispatch, the parameter search.
 // See include/enec.h for the contract of every entry point.
 #include "enec.h"
-#include "enec_device.hpp"
+#include "enec_kernels.hpp"
 
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
+
+namespace enec {
+
+// kernels that exist once: the header-only stream of an empty tensor, zero fill, plain copy
+__global__ void compress_empty_kernel(uint8_t *out, uint64_t *out_bytes, uint32_t B, uint32_t b, uint32_t n, uint32_t m,
+                                      uint32_t dtype)
+{
+    if (threadIdx.x != 0) return;
+    uint32_t *h = reinterpret_cast<uint32_t *>(out);
+    h[0] = 0x43454E45u;
+    h[1] = 1u | (dtype << 16) | (16u << 24);
+    h[2] = h[3] = 0;
+    h[4] = B; h[5] = 0;
+    h[6] = b | (n << 8) | (m << 16) | (exponent_bits((int)dtype) << 24);
+    h[7] = 0;
+    h[8] = 80; h[9] = 0;
+    for (int i = 10; i < 16; ++i) h[i] = 0;
+    h[16] = h[17] = h[18] = h[19] = 0;      // table[0] = 0 and the pad to 80 bytes
+    if (out_bytes) *out_bytes = 80;
+}
+
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint4 *p, uint64_t nvec)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t v = (uint64_t)blockIdx.x * 256u + threadIdx.x; v < nvec; v += stride)
+        p[v] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ void __launch_bounds__(256) copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, uint64_t nvec)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t v = (uint64_t)blockIdx.x * 256u + threadIdx.x; v < nvec; v += stride) dst[v] = src[v];
+}
+
+}  // namespace enec
 
 namespace {
 
@@ -27,35 +62,41 @@ inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
 inline bool block_ok(uint32_t B) { return B >= 2048 && B <= 32768 && (B & (B - 1)) == 0; }
 inline uint32_t ilog2(uint32_t v) { uint32_t r = 0; while ((1u << r) < v) ++r; return r; }
 inline size_t num_blocks(size_t n, uint32_t B) { return (n + B - 1) / B; }
-inline size_t payload_base(size_t n, uint32_t B) { return align16(ENEC_HEADER_BYTES + 8 * (num_blocks(n, B) + 1)); }
+inline bool dtype_ok(int dtype) { return dtype == ENEC_BF16 || dtype == ENEC_FP16 || dtype == ENEC_FP32; }
+inline unsigned exp_bits(int dtype) { return dtype == ENEC_FP16 ? 5u : 8u; }
+inline size_t elem_bytes(int dtype) { return dtype == ENEC_FP32 ? 4 : 2; }
+// end of header + offset table; an fp32 stream keeps the lower halves of its elements from here on
+inline size_t table_end(size_t n, uint32_t B) { return align16(ENEC_HEADER_BYTES + 8 * (num_blocks(n, B) + 1)); }
+inline size_t payload_base(size_t n, uint32_t B, int dtype)
+{
+    return table_end(n, B) + (dtype == ENEC_FP32 ? align16(2 * n) : 0);
+}
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
-using CompressFn = void (*)(const CompressArgs);
-using DecompressFn = void (*)(const DecompressArgs);
+inline CompressFn pick_compress(int m, int a, int dtype)
+{
+    if (dtype == ENEC_FP16) return pick_compress_fp16(m, a);
+    if (dtype == ENEC_FP32) return pick_compress_fp32(m, a);
+    return pick_compress_bf16(m, a);
+}
+inline DecompressFn pick_decompress(int m, int a, int dtype)
+{
+    if (dtype == ENEC_FP16) return pick_decompress_fp16(m, a);
+    if (dtype == ENEC_FP32) return pick_decompress_fp32(m, a);
+    return pick_decompress_bf16(m, a);
+}
 
-template <int M, int A> constexpr CompressFn cfn() { return &compress_kernel<M, A>; }
-template <int M, int A> constexpr DecompressFn dfn() { return &decompress_kernel<M, A>; }
-
-// every (m, a = n - m) with 1 <= m + a <= 8
-template <int M, int A> struct Pick {
-    static CompressFn c(int m, int a)
-    {
-        if (m == M && a == A) return cfn<M, A>();
-        if constexpr (A < 8 - M) return Pick<M, A + 1>::c(m, a);
-        else if constexpr (M < 8) return Pick<M + 1, 0>::c(m, a);
-        else return nullptr;
-    }
-    static DecompressFn d(int m, int a)
-    {
-        if (m == M && a == A) return dfn<M, A>();
-        if constexpr (A < 8 - M) return Pick<M, A + 1>::d(m, a);
-        else if constexpr (M < 8) return Pick<M + 1, 0>::d(m, a);
-        else return nullptr;
-    }
-};
-
-inline CompressFn pick_compress(int m, int a) { return Pick<0, 1>::c(m, a); }
-inline DecompressFn pick_decompress(int m, int a) { return Pick<0, 1>::d(m, a); }
+// how the kernels subtract exponents in byte lanes: 0 = plain subtract (no byte can borrow for
+// an exponent inside the window), 1 = borrow-safe subtract, the window is the whole exponent
+// range, 2 = borrow-safe subtract plus an explicit window test (the window of an 8-bit exponent
+// touches 0 or 255, where a plain subtract could wrap back into the window)
+inline unsigned subtract_mode(unsigned b, unsigned n, int dtype)
+{
+    if (n == exp_bits(dtype)) return 1u;
+    if (dtype == ENEC_FP16) return 0u;           // 5-bit exponents in byte lanes cannot wrap
+    const unsigned cc = b + (1u << (n - 1));
+    return (cc <= 255 && cc >= (1u << n) - 1u) ? 0u : 2u;
+}
 
 bool device_accessible(const void *p)
 {
@@ -112,8 +153,10 @@ int parse_header(const void *host_header, Header *h)
     const uint8_t *p = static_cast<const uint8_t *>(host_header);
     if (std::memcmp(p, "ENEC", 4) != 0) return ENEC_E_FORMAT;
     uint16_t ver; std::memcpy(&ver, p + 4, 2);
-    if (ver != 1 || p[7] != 16 || p[27] != 8) return ENEC_E_FORMAT;
+    if (ver != 1 || p[7] != 16) return ENEC_E_FORMAT;
     h->dtype = p[6];
+    if (!dtype_ok(h->dtype)) return ENEC_E_DTYPE;
+    if (p[27] != exp_bits(h->dtype)) return ENEC_E_FORMAT;
     std::memcpy(&h->n_elems, p + 8, 8);
     std::memcpy(&h->B, p + 16, 4);
     std::memcpy(&h->nb, p + 20, 4);
@@ -134,9 +177,9 @@ const char *enec_strerror(int status)
     switch (status) {
     case ENEC_OK: return "ok";
     case ENEC_E_ARG: return "invalid argument (null or misaligned pointer, size out of range)";
-    case ENEC_E_DTYPE: return "unsupported dtype (only bf16)";
+    case ENEC_E_DTYPE: return "unsupported dtype (bf16, fp16 and fp32 are supported)";
     case ENEC_E_BLOCK: return "block_size must be a power of two in [2048, 32768]";
-    case ENEC_E_PARAMS: return "invalid parameters (need 1 <= n <= 8, 0 <= m <= n, L == 16)";
+    case ENEC_E_PARAMS: return "invalid parameters (need 1 <= n <= exponent width, 0 <= m <= n, b inside the exponent range, L == 16)";
     case ENEC_E_CAPACITY: return "output capacity or workspace too small";
     case ENEC_E_RANGE: return "an exponent lies outside the window of (b, n)";
     case ENEC_E_FORMAT: return "not an ENEC stream or header mismatch";
@@ -154,10 +197,11 @@ uint32_t enec_default_block_size(size_t n_elems)
 
 size_t enec_compress_bound(size_t n_elems, int dtype, uint32_t block_size)
 {
-    if (dtype != ENEC_BF16) return 0;
+    if (!dtype_ok(dtype)) return 0;
     const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
     if (!block_ok(B)) return 0;
-    return payload_base(n_elems, B) + num_blocks(n_elems, B) * align16((size_t)B + B / 128 + B);
+    // worst case: every group anomalous at full exponent width (fp16: (5 + 3) plane bits)
+    return payload_base(n_elems, B, dtype) + num_blocks(n_elems, B) * align16((size_t)B + B / 128 + B);
 }
 
 size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size)
@@ -181,9 +225,11 @@ int enec_workspace_init(void *workspace, size_t bytes, void *stream)
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 
-int enec_tune_histogram(const uint64_t *hist, enec_params *params)
+int enec_tune_histogram(const uint64_t *hist, int dtype, enec_params *params)
 {
+    if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
     if (!hist || !params) return ENEC_E_ARG;
+    const unsigned nmax = exp_bits(dtype);
     // Sec. V-E phase 1: occupied range [l, h] and the element count
     int l = -1, h = -1;
     uint64_t total = 0;
@@ -197,7 +243,7 @@ int enec_tune_histogram(const uint64_t *hist, enec_params *params)
         unsigned below = bit_length((unsigned)(b - l));
         unsigned above = h > b ? bit_length((unsigned)(h - b - 1)) : 0;
         unsigned n = (below > above ? below : above) + 1;
-        if (n > 8) n = 8;
+        if (n > nmax) n = nmax;
         const unsigned wrap = (1u << n) - 1u;
         uint64_t D = 0;
         for (int x = l; x <= h; ++x) D += hist[x] * (uint64_t)(((unsigned)(b - x)) & wrap);
@@ -223,7 +269,7 @@ int enec_tune_histogram(const uint64_t *hist, enec_params *params)
 int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params, uint64_t *histogram,
               void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (dtype != ENEC_BF16) return ENEC_E_DTYPE;
+    if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
     if (workspace_bytes < WS_STATE) return ENEC_E_CAPACITY;
     if (!params || !workspace || (!in && n_elems) || !aligned16(in) || !aligned16(workspace) ||
         n_elems > MAX_ELEMS)
@@ -234,22 +280,24 @@ int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params, ui
     if (n_elems) {
         auto *dhist = reinterpret_cast<unsigned long long *>(static_cast<uint8_t *>(workspace) + WS_HIST);
         fill_zero_kernel<<<1, 256, 0, s>>>(reinterpret_cast<uint4 *>(dhist), 256 * 8 / 16);
-        const uint64_t nvec = n_elems / 8;
+        const uint64_t nvec = n_elems * elem_bytes(dtype) / 16;
         uint64_t want = (nvec + 255) / 256;
         const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
-        histogram_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t *>(in), n_elems, dhist);
+        if (dtype == ENEC_FP32) histogram_kernel<DT_FP32><<<grid, 256, 0, s>>>(in, n_elems, dhist);
+        else if (dtype == ENEC_FP16) histogram_kernel<DT_FP16><<<grid, 256, 0, s>>>(in, n_elems, dhist);
+        else histogram_kernel<DT_BF16><<<grid, 256, 0, s>>>(in, n_elems, dhist);
         if (hipMemcpyAsync(host_hist, dhist, sizeof host_hist, hipMemcpyDeviceToHost, s) != hipSuccess ||
             hipStreamSynchronize(s) != hipSuccess)
             return ENEC_E_HIP;
     }
     if (histogram) std::memcpy(histogram, host_hist, sizeof host_hist);
-    return enec_tune_histogram(host_hist, params);
+    return enec_tune_histogram(host_hist, dtype, params);
 }
 
 int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
                         size_t workspace_bytes, void *stream)
 {
-    if (dtype != ENEC_BF16) return ENEC_E_DTYPE;
+    if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
     if (!items || !workspace || !aligned16(workspace)) return ENEC_E_ARG;
     hipStream_t s = (hipStream_t)stream;
 
@@ -280,7 +328,8 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
             if (rc != ENEC_OK) return rc;
         }
         const enec_params &prm = prep[i].prm;
-        if (prm.n < 1 || prm.n > 8 || prm.m > prm.n || prm.L != 16) return ENEC_E_PARAMS;
+        if (prm.n < 1 || prm.n > exp_bits(dtype) || prm.m > prm.n || prm.b >= (1u << exp_bits(dtype)) || prm.L != 16)
+            return ENEC_E_PARAMS;
         if (it.out_capacity < enec_compress_bound(it.n_elems, dtype, prep[i].B)) return ENEC_E_CAPACITY;
         if (it.out_bytes && !device_accessible(it.out_bytes)) return ENEC_E_ARG;
     }
@@ -292,7 +341,8 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         if (done[i]) continue;
         if (prep[i].nb == 0) {
             compress_empty_kernel<<<1, 64, 0, s>>>(static_cast<uint8_t *>(items[i].out), items[i].out_bytes,
-                                                   prep[i].B, prep[i].prm.b, prep[i].prm.n, prep[i].prm.m);
+                                                   prep[i].B, prep[i].prm.b, prep[i].prm.n, prep[i].prm.m,
+                                                   (uint32_t)dtype);
             done[i] = 1;
             continue;
         }
@@ -318,20 +368,20 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
             c.ws_block = reinterpret_cast<uint64_t *>(ws + WS_STATE) + word;
             word += prep[j].nb;
             c.n_elems = items[j].n_elems;
-            c.payload_base = payload_base(items[j].n_elems, a.B);
+            c.payload_base = payload_base(items[j].n_elems, a.B, dtype);
+            c.tail_base = table_end(items[j].n_elems, a.B);
             c.nb = prep[j].nb;
             c.first = a.total;
             c.b = prep[j].prm.b;
-            const unsigned cc = prep[j].prm.b + (1u << (prep[j].prm.n - 1));
-            const bool plain = cc <= 255 && cc >= (1u << prep[j].prm.n) - 1u;
-            c.mode = plain ? 0u : (prep[j].prm.n == 8 ? 1u : 2u);
+            c.mode = subtract_mode(prep[j].prm.b, prep[j].prm.n, dtype);
             a.total += c.nb;
             done[j] = 1;
         }
-        CompressFn fn = pick_compress(prep[i].prm.m, prep[i].prm.n - prep[i].prm.m);
+        CompressFn fn = pick_compress(prep[i].prm.m, prep[i].prm.n - prep[i].prm.m, dtype);
         if (!fn) return ENEC_E_PARAMS;
         const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
-        const size_t lds = 2 * ((size_t)a.B / 128 + (size_t)prep[i].prm.n * a.B / 8);    // two images of the packed part
+        const size_t plane_bits = prep[i].prm.n + (dtype == ENEC_FP16 ? 3 : 0);
+        const size_t lds = 2 * ((size_t)a.B / 128 + plane_bits * a.B / 8);               // two images of the packed part
         const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_COMPRESS_WGS_PER_CU");
         if (resident == 0) return ENEC_E_HIP;
         const unsigned grid = a.total < resident ? a.total : resident;
@@ -363,10 +413,10 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
         Header &h = hdr[i];
         int rc = parse_header(it.host_header, &h);
         if (rc != ENEC_OK) return rc;
-        if (h.dtype != ENEC_BF16) return ENEC_E_DTYPE;
         if (h.status != ENEC_OK || h.n_elems != it.n_elems || !block_ok(h.B) || it.n_elems > MAX_ELEMS ||
-            h.nb != num_blocks(it.n_elems, h.B) || h.prm.n < 1 || h.prm.n > 8 || h.prm.m > h.prm.n ||
-            h.total < payload_base(it.n_elems, h.B) || h.total > it.in_bytes)
+            h.nb != num_blocks(it.n_elems, h.B) || h.prm.n < 1 || h.prm.n > exp_bits(h.dtype) || h.prm.m > h.prm.n ||
+            h.prm.b >= (1u << exp_bits(h.dtype)) ||
+            h.total < payload_base(it.n_elems, h.B, h.dtype) || h.total > it.in_bytes)
             return ENEC_E_FORMAT;
     }
     std::vector<char> done(n_items, 0);
@@ -380,26 +430,29 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
         a.total = 0;
         for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
             const Header &h = hdr[j];
-            if (done[j] || h.nb == 0 || h.B != a.B || h.prm.m != hdr[i].prm.m || h.prm.n != hdr[i].prm.n) continue;
+            if (done[j] || h.nb == 0 || h.B != a.B || h.prm.m != hdr[i].prm.m || h.prm.n != hdr[i].prm.n ||
+                h.dtype != hdr[i].dtype)
+                continue;
             DecompressItem &c = a.item[a.n_items++];
             c.in = static_cast<const uint8_t *>(items[j].in);
             c.out = static_cast<uint16_t *>(items[j].out);
             c.n_elems = items[j].n_elems;
-            c.payload_base = payload_base(items[j].n_elems, h.B);
+            c.payload_base = payload_base(items[j].n_elems, h.B, h.dtype);
             c.payload_bytes = h.total - c.payload_base;
+            c.tail_base = table_end(items[j].n_elems, h.B);
             c.nb = h.nb;
             c.first = a.total;
             c.b = h.prm.b;
-            const unsigned cc = h.prm.b + (1u << (h.prm.n - 1));
-            c.mode = (cc <= 255 && cc >= (1u << h.prm.n) - 1u) ? 0u : 1u;
+            c.mode = subtract_mode(h.prm.b, h.prm.n, h.dtype) == 0 ? 0u : 1u;
             std::memcpy(c.hdr, items[j].host_header, sizeof c.hdr);
             a.total += c.nb;
             done[j] = 1;
         }
-        DecompressFn fn = pick_decompress(hdr[i].prm.m, hdr[i].prm.n - hdr[i].prm.m);
+        DecompressFn fn = pick_decompress(hdr[i].prm.m, hdr[i].prm.n - hdr[i].prm.m, hdr[i].dtype);
         if (!fn) return ENEC_E_FORMAT;
         const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
-        const size_t lds = 2 * ((size_t)a.B / 128 + (size_t)hdr[i].prm.n * a.B / 8);    // two images of the packed part
+        const size_t plane_bits = hdr[i].prm.n + (hdr[i].dtype == ENEC_FP16 ? 3 : 0);
+        const size_t lds = 2 * ((size_t)a.B / 128 + plane_bits * a.B / 8);              // two images of the packed part
         const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_DECOMPRESS_WGS_PER_CU");
         if (resident == 0) return ENEC_E_HIP;
         const unsigned grid = a.total < resident ? a.total : resident;

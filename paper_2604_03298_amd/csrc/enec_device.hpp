@@ -1,4 +1,4 @@
-// Device code of libenec: the ENEC bf16 codec on CDNA4 (gfx950), wave64.
+// Device code of libenec: the ENEC codec (bf16, fp16, fp32 tensors) on CDNA4 (gfx950), wave64.
 //
 // Thread mapping (both directions).  A data block of B elements is seen as 8 rows of
 // C = B/8 columns: element c + t*C is row t, column c.  Alg. 2 (hierarchical halving
@@ -11,6 +11,16 @@
 //   * owns half of a group of 16 consecutive elements per row; the two halves sit in
 //     adjacent lanes and are combined with one DPP operation.
 // A workgroup has B/64 threads (256 for the default B = 16384) and handles one block.
+//
+// Element formats (template parameter DT).  Only the exponent field is coded (Sec. VI-B);
+// every format is first split into an exponent byte X and the raw byte sign<<7 | first seven
+// mantissa bits, after which the three formats share all code:
+//   DT_BF16  1|8|7   nothing is left over
+//   DT_FP16  1|5|10  the last three mantissa bits ride on top of the m low bits of y in the low
+//                    plane, which is therefore m + 3 bits wide
+//   DT_FP32  1|8|23  the upper half of an element is a bf16 word; the lower halves are copied
+//                    to a region between the offset table and the payloads, at positions that
+//                    do not depend on any compressed size
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -28,6 +38,10 @@
 #endif
 
 namespace enec {
+
+constexpr int DT_BF16 = 0, DT_FP16 = 1, DT_FP32 = 2;
+constexpr int low_plane_bits(int m, int dt) { return m + (dt == DT_FP16 ? 3 : 0); }
+constexpr uint32_t exponent_bits(int dt) { return dt == DT_FP16 ? 5u : 8u; }
 
 // ---------------------------------------------------------------------------------
 // Compile-time bit map of Alg. 2 for one column (8 values of W bits -> W bytes).
@@ -229,8 +243,9 @@ struct CompressItem {
     uint64_t *ws_acc;       // ceil(nb / 64) group accumulators, zero between calls
     uint64_t n_elems;
     uint64_t payload_base;
+    uint64_t tail_base;     // fp32: where the lower halves of the elements go
     uint32_t nb, first;
-    uint32_t b, mode;       // mode 0: window clear of 0 and 255; 1: n = 8; 2: window touches an end
+    uint32_t b, mode;       // mode 0: window clear of 0 and 255; 1: n = exponent width; 2: window touches an end
 };
 
 struct CompressArgs {
@@ -249,6 +264,7 @@ struct DecompressItem {
     uint64_t n_elems;
     uint64_t payload_base;
     uint64_t payload_bytes; // total_bytes - payload_base
+    uint64_t tail_base;     // fp32: where the lower halves of the elements are
     uint32_t nb, first;
     uint32_t b, mode;       // mode 0: plain byte subtract is exact; 1: borrow-safe subtract
     uint32_t hdr[10];       // first 40 bytes of the expected header
@@ -261,33 +277,62 @@ struct DecompressArgs {
     DecompressItem item[MAX_BATCH];
 };
 
-// a1: 128-bit loads of the 8 rows of data block k (pad elements beyond the tensor's end)
+// a1: 128-bit loads of the 8 rows of data block k (pad elements beyond the tensor's end); a
+// thread's 8 elements of a row are one vector (16-bit formats) or two (fp32)
+template <int DT>
 __device__ __forceinline__ void load_block_rows(const CompressItem &p, uint32_t B, uint32_t logB, uint32_t k,
-                                                uint32_t tid, bool active, uint32_t logC, uint4 (&raw)[8])
+                                                uint32_t tid, bool active, uint32_t logC,
+                                                uint4 (&raw)[DT == DT_FP32 ? 16 : 8])
 {
     const uint64_t blk0 = (uint64_t)k << logB;
-    const uint32_t padw = (p.b << 7) * 0x00010001u;   // a pad element has exponent b: y = 0, sm = 0
-    if (blk0 + B <= p.n_elems) {               // whole block inside the tensor: no per-row tests
+    // a pad element has exponent b and nothing else: y = 0, raw byte 0, no left-over bits
+    const uint32_t padw = DT == DT_FP32 ? (p.b << 23) : (p.b << (DT == DT_FP16 ? 10 : 7)) * 0x00010001u;
+    if constexpr (DT == DT_FP32) {
+        const uint32_t *in = reinterpret_cast<const uint32_t *>(p.in);
+        if (blk0 + B <= p.n_elems) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
-            raw[t] = active ? *reinterpret_cast<const uint4 *>(p.in + blk0 + ((uint64_t)t << logC) + 8u * tid)
-                            : make_uint4(padw, padw, padw, padw);
-        return;
-    }
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
-        uint32_t d[4] = {padw, padw, padw, padw};
-        if (active && e0 < p.n_elems) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (e0 + i < p.n_elems) {
-                    const uint32_t v = p.in[e0 + i];
-                    d[i >> 1] = (i & 1) ? ((d[i >> 1] & 0x0000FFFFu) | (v << 16))
-                                        : ((d[i >> 1] & 0xFFFF0000u) | v);
-                }
+            for (int t = 0; t < 8; ++t) {
+                const uint4 *src = reinterpret_cast<const uint4 *>(in + blk0 + ((uint64_t)t << logC) + 8u * tid);
+                raw[2 * t] = active ? src[0] : make_uint4(padw, padw, padw, padw);
+                raw[2 * t + 1] = active ? src[1] : make_uint4(padw, padw, padw, padw);
+            }
+            return;
         }
-        raw[t] = make_uint4(d[0], d[1], d[2], d[3]);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
+            uint32_t d[8] = {padw, padw, padw, padw, padw, padw, padw, padw};
+            if (active && e0 < p.n_elems) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (e0 + i < p.n_elems) d[i] = in[e0 + i];
+            }
+            raw[2 * t] = make_uint4(d[0], d[1], d[2], d[3]);
+            raw[2 * t + 1] = make_uint4(d[4], d[5], d[6], d[7]);
+        }
+    } else {
+        if (blk0 + B <= p.n_elems) {               // whole block inside the tensor: no per-row tests
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                raw[t] = active ? *reinterpret_cast<const uint4 *>(p.in + blk0 + ((uint64_t)t << logC) + 8u * tid)
+                                : make_uint4(padw, padw, padw, padw);
+            return;
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
+            uint32_t d[4] = {padw, padw, padw, padw};
+            if (active && e0 < p.n_elems) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (e0 + i < p.n_elems) {
+                        const uint32_t v = p.in[e0 + i];
+                        d[i >> 1] = (i & 1) ? ((d[i >> 1] & 0x0000FFFFu) | (v << 16))
+                                            : ((d[i >> 1] & 0xFFFF0000u) | v);
+                    }
+            }
+            raw[t] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
     }
 }
 
@@ -295,16 +340,18 @@ __device__ __forceinline__ void load_block_rows(const CompressItem &p, uint32_t 
 // compression: split, transform, group test, packing, inter-block scan, store
 // (Sec. V-A compression path; Sec. V-B; Sec. V-C; Fig. 4)
 // ---------------------------------------------------------------------------------
-template <int M, int A>
+template <int M, int A, int DT>
 __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(const CompressArgs p)
 {
     constexpr int N = M + A;
+    constexpr int LM = low_plane_bits(M, DT);            // width of the low plane
     constexpr uint32_t NMASK = ((1u << N) - 1u) * 0x01010101u;
     constexpr uint32_t LMASK = ((1u << M) - 1u) * 0x01010101u;
     constexpr uint32_t AMASK = ((1u << A) - 1u) * 0x01010101u;
     constexpr uint32_t SREP = (1u << (N - 1)) * 0x01010101u;
-    constexpr int MP = M > 0 ? M : 1;
+    constexpr int MP = LM > 0 ? LM : 1;
     constexpr int AP = A > 0 ? A : 1;
+    constexpr int RW = DT == DT_FP32 ? 16 : 8;           // 128-bit vectors of one block per thread
 
     // two LDS images of the packed part of a payload: mask | low plane (as normalized bytes,
     // interleaved on the way out) | high records
@@ -320,8 +367,8 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
     const uint32_t acc_tid = blockDim.x > 64u ? 64u : 0u;   // the lane that talks to the group accumulators
-    const uint32_t img_bytes = (B >> 7) + (((uint32_t)N * B) >> 3);
-    const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
+    const uint32_t img_bytes = (B >> 7) + (((uint32_t)(LM + A) * B) >> 3);
+    const uint32_t fixed = B + (B >> 7) + ((LM * B) >> 3);
 
     // ---- control record of this workgroup's class (thread 0) ---------------------------
     const uint32_t home = blockIdx.x % p.ncls;
@@ -358,8 +405,8 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         return c;
     };
     uint32_t ci = item_of(k, 0);                             // item of the current block
-    uint4 raw[8];
-    load_block_rows(p.item[ci], B, p.logB, k - p.item[ci].first, tid, active, logC, raw);
+    uint4 raw[RW];
+    load_block_rows<DT>(p.item[ci], B, p.logB, k - p.item[ci].first, tid, active, logC, raw);
     if (tid == 0) {
         // the record must have been read before this workgroup's first draw can be counted
         zero = ticket_base ^ (uint32_t)tag0;
@@ -370,7 +417,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     }
     __syncthreads();
     const uint64_t tag = (uint64_t)s_tag << 24;
-    constexpr HHTable TL = HH<M>::table;
+    constexpr HHTable TL = HH<MP>::table;
 
     // wave 0 carries the scan of one tensor: sum of its group words [0, groups_summed) and what
     // went wrong so far (bit 1 range error in an earlier block, bit 2 gave up waiting)
@@ -425,10 +472,10 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         }
         if (tid < (B >> 11))
             *reinterpret_cast<uint4 *>(dst + B + 16u * tid) = *reinterpret_cast<const uint4 *>(img + 16u * tid);
-        if (M > 0) {
+        if (LM > 0) {
             const uint8_t *ilow = img + (B >> 7);
             uint8_t *dlow = dst + B + (B >> 7);
-            const uint32_t T2 = (M * B) >> 4;                 // half of the plane's length
+            const uint32_t T2 = (LM * B) >> 4;                // half of the plane's length
             for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
                 const uint2 a = *reinterpret_cast<const uint2 *>(ilow + 8u * v);
                 const uint2 c = *reinterpret_cast<const uint2 *>(ilow + 8u * v + T2);
@@ -441,7 +488,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             }
         }
         if (A > 0) {
-            const uint8_t *ihigh = img + (B >> 7) + ((M * B) >> 3);
+            const uint8_t *ihigh = img + (B >> 7) + ((LM * B) >> 3);
             uint8_t *dhigh = dst + fixed;
             const uint32_t hbytes = 2u * A * cnt;             // even
             for (uint32_t v = tid; 16u * v < hbytes; v += blockDim.x) {
@@ -468,10 +515,10 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                 if (((uint64_t)(it.nb + 1u) & 1ull)) table[it.nb + 1u] = 0;   // pad up to the payload base
                 uint32_t *h = reinterpret_cast<uint32_t *>(it.out);
                 h[0] = 0x43454E45u;                              // "ENEC"
-                h[1] = 1u | (0u << 16) | (16u << 24);            // version, dtype bf16, L
+                h[1] = 1u | ((uint32_t)DT << 16) | (16u << 24);  // version, dtype, L
                 h[2] = (uint32_t)it.n_elems; h[3] = (uint32_t)(it.n_elems >> 32);
                 h[4] = B; h[5] = it.nb;
-                h[6] = it.b | ((uint32_t)N << 8) | ((uint32_t)M << 16) | (8u << 24);
+                h[6] = it.b | ((uint32_t)N << 8) | ((uint32_t)M << 16) | (exponent_bits(DT) << 24);
                 h[7] = status;
                 h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
 #pragma unroll
@@ -487,7 +534,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         uint8_t *img = smem + slot * img_bytes;
         uint32_t *img_maskw = reinterpret_cast<uint32_t *>(img);
         uint8_t *img_low = img + (B >> 7);
-        uint8_t *img_high = img_low + (((size_t)M * B) >> 3);
+        uint8_t *img_high = img_low + (((size_t)LM * B) >> 3);
 
         // wave 0 reads the scan state for the block stored in this iteration now and uses it
         // after the arithmetic: published an iteration ago, it is normally all there
@@ -517,18 +564,40 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 #pragma unroll
         for (int q = 0; q < MP; ++q) accP[q][0] = accP[q][1] = 0;
 
+        const uint64_t row0 = ((uint64_t)kl << p.logB) + 8u * tid;   // this thread's first element of row 0
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             uint32_t gor = 0;
+            uint4 r16;                           // the row's eight 16-bit words
+            if constexpr (DT == DT_FP32) {
+                // upper halves go on as bf16 words, lower halves leave at once
+                const uint4 u = raw[2 * t], v = raw[2 * t + 1];
+                r16 = make_uint4(byte_perm(u.y, u.x, 0x07060302u), byte_perm(u.w, u.z, 0x07060302u),
+                                 byte_perm(v.y, v.x, 0x07060302u), byte_perm(v.w, v.z, 0x07060302u));
+                const uint64_t e0 = row0 + ((uint64_t)t << logC);
+                if (active && e0 < it.n_elems)   // elements past the end are pads with zero lower halves
+                    *reinterpret_cast<uint4 *>(it.out + it.tail_base + 2u * e0) =
+                        make_uint4(byte_perm(u.y, u.x, 0x05040100u), byte_perm(u.w, u.z, 0x05040100u),
+                                   byte_perm(v.y, v.x, 0x05040100u), byte_perm(v.w, v.z, 0x05040100u));
+            } else {
+                r16 = raw[t];
+            }
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const uint32_t d0 = h ? raw[t].z : raw[t].x;
-                const uint32_t d1 = h ? raw[t].w : raw[t].y;
-                // a1 split: low / high bytes of four bf16 words
+                const uint32_t d0 = h ? r16.z : r16.x;
+                const uint32_t d1 = h ? r16.w : r16.y;
+                // a1 split: low / high bytes of four 16-bit words
                 const uint32_t Lb = byte_perm(d1, d0, 0x06040200u);
                 const uint32_t Hb = byte_perm(d1, d0, 0x07050301u);
-                SMc[t][h] = bfi(0x7F7F7F7Fu, Lb, Hb);
-                const uint32_t X = bfi(0xFEFEFEFEu, Hb << 1, Lb >> 7);
+                uint32_t X, T3 = 0;
+                if constexpr (DT == DT_FP16) {
+                    SMc[t][h] = (Hb & 0x80808080u) | ((Hb & 0x03030303u) << 5) | ((Lb >> 3) & 0x1F1F1F1Fu);
+                    X = (Hb >> 2) & 0x1F1F1F1Fu;
+                    T3 = Lb & 0x07070707u;
+                } else {
+                    SMc[t][h] = bfi(0x7F7F7F7Fu, Lb, Hb);
+                    X = bfi(0xFEFEFEFEu, Hb << 1, Lb >> 7);
+                }
                 // a2 transform: z = (b + 2^(n-1) - x) mod 256 per byte, y = z with the sign bit flipped
                 uint32_t Z;
                 if (mode == 0) {
@@ -550,8 +619,8 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                 const uint32_t hi = A > 0 ? ((Y >> M) & AMASK) : 0u;
                 HI[t][h] = hi;
                 gor |= hi;
-                if (M > 0) {
-                    const uint32_t low = Y & LMASK;
+                if (LM > 0) {
+                    const uint32_t low = (Y & LMASK) | (T3 << M);
 #pragma unroll
                     for (int f = 0; f < TL.count; ++f)
                         if (TL.row[f] == t) {
@@ -577,9 +646,9 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                 for (int u = 0; u < 4; ++u) img_maskw[u] = mw[2 * u] | (mw[2 * u + 1] << 16);
             }
         }
-        if (M > 0 && active) {
+        if (LM > 0 && active) {
 #pragma unroll
-            for (int q = 0; q < M; ++q)
+            for (int q = 0; q < LM; ++q)
                 *reinterpret_cast<uint2 *>(img_low + ((size_t)q << logC) + 8u * tid) =
                     make_uint2(accP[q][0], accP[q][1]);
         }
@@ -682,7 +751,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         uint32_t cnext = ci;
         if (knext != NO_BLOCK) {
             cnext = item_of(knext, ci);
-            load_block_rows(p.item[cnext], B, p.logB, knext - p.item[cnext].first, tid, active, logC, raw);
+            load_block_rows<DT>(p.item[cnext], B, p.logB, knext - p.item[cnext].first, tid, active, logC, raw);
         }
 
         // ---- a7: stores of the previous block ----------------------------------------------
@@ -706,7 +775,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             k = __builtin_amdgcn_readfirstlane(s_k[slot]);
             if (k != NO_BLOCK) {
                 ci = item_of(k, ci);
-                load_block_rows(p.item[ci], B, p.logB, k - p.item[ci].first, tid, active, logC, raw);
+                load_block_rows<DT>(p.item[ci], B, p.logB, k - p.item[ci].first, tid, active, logC, raw);
             }
         }
     }
@@ -723,23 +792,6 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     }
 }
 
-// Header-only stream for an empty tensor.
-__global__ void compress_empty_kernel(uint8_t *out, uint64_t *out_bytes, uint32_t B, uint32_t b, uint32_t n, uint32_t m)
-{
-    if (threadIdx.x != 0) return;
-    uint32_t *h = reinterpret_cast<uint32_t *>(out);
-    h[0] = 0x43454E45u;
-    h[1] = 1u | (16u << 24);
-    h[2] = h[3] = 0;
-    h[4] = B; h[5] = 0;
-    h[6] = b | (n << 8) | (m << 16) | (8u << 24);
-    h[7] = 0;
-    h[8] = 80; h[9] = 0;
-    for (int i = 10; i < 16; ++i) h[i] = 0;
-    h[16] = h[17] = h[18] = h[19] = 0;      // table[0] = 0 and the pad to 80 bytes
-    if (out_bytes) *out_bytes = 80;
-}
-
 // ---------------------------------------------------------------------------------
 // decompression: offset lookup, mask prefix, unpack, inverse transform, recombine
 // (Sec. V-A decompression path; Alg. 1 decompression part)
@@ -749,14 +801,16 @@ __global__ void compress_empty_kernel(uint8_t *out, uint64_t *out_bytes, uint32_
 // next block is already travelling: its sign/mantissa bytes into registers, its packed part
 // (mask | low plane | high records, exactly as in the stream) into the other of two LDS images.
 // ---------------------------------------------------------------------------------
-template <int M, int A>
+template <int M, int A, int DT>
 __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
 {
     constexpr int N = M + A;
+    constexpr int LM = low_plane_bits(M, DT);            // width of the low plane
     constexpr uint32_t SREP = (1u << (N - 1)) * 0x01010101u;
-    constexpr int MP = M > 0 ? M : 1;
+    constexpr uint32_t LMASK = ((1u << M) - 1u) * 0x01010101u;
+    constexpr int MP = LM > 0 ? LM : 1;
     constexpr int AP = A > 0 ? A : 1;
-    constexpr int VMAX = N / 2 + 1;          // 16-byte vectors of packed payload per thread
+    constexpr int VMAX = (LM + A) / 2 + 1;   // 16-byte vectors of packed payload per thread
 
     extern __shared__ __align__(16) uint8_t smem[];
 
@@ -764,9 +818,8 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
     const uint32_t B = p.B, logC = p.logB - 3u, C = 1u << logC;
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
-    const uint32_t acc_tid = blockDim.x > 64u ? 64u : 0u;   // the lane that talks to the group accumulators
-    const uint32_t img_bytes = (B >> 7) + (((uint32_t)N * B) >> 3);
-    const uint32_t fixed = B + (B >> 7) + ((M * B) >> 3);
+    const uint32_t img_bytes = (B >> 7) + (((uint32_t)(LM + A) * B) >> 3);
+    const uint32_t fixed = B + (B >> 7) + ((LM * B) >> 3);
     const uint32_t par = tid & 1u;
 
     // tensor that global block kg belongs to, searching upwards from item c
@@ -846,7 +899,7 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
         to_image(smem, vec);
     }
     uint32_t slot = 0;
-    constexpr HHTable TL = HH<M>::table;
+    constexpr HHTable TL = HH<MP>::table;
 
     ENEC_TP_DECL;
     while (k < p.total) {
@@ -865,7 +918,18 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
         if (valid && active) {
             const uint8_t *img = smem + slot * img_bytes;
             const uint8_t *img_low = img + (B >> 7);
-            const uint8_t *img_high = img_low + (((size_t)M * B) >> 3);
+            const uint8_t *img_high = img_low + (((size_t)LM * B) >> 3);
+            const uint64_t blk0 = (uint64_t)(k - it.first) << p.logB;
+            // fp32: the lower halves of this thread's elements, straight from the stream
+            uint4 tl[DT == DT_FP32 ? 8 : 1];
+            if constexpr (DT == DT_FP32) {
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
+                    tl[t] = e0 < it.n_elems ? *reinterpret_cast<const uint4 *>(it.in + it.tail_base + 2u * e0)
+                                            : make_uint4(0, 0, 0, 0);
+                }
+            }
             // d2: mask words and their exclusive popcount prefix (a wave scan per wave)
             const uint32_t nwords = B >> 9;
             const uint32_t my_word = lane < nwords ? reinterpret_cast<const uint32_t *>(img)[lane] : 0u;
@@ -877,8 +941,8 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
             uint32_t Pl[MP][2];
 #pragma unroll
             for (int q = 0; q < MP; ++q) {
-                if (M > 0) {
-                    const uint32_t T2 = (M * B) >> 4;
+                if (LM > 0) {
+                    const uint32_t T2 = (LM * B) >> 4;
                     const uint32_t i = ((uint32_t)q << logC) + 8u * tid;
                     const bool even = i < T2;
                     const uint4 sp = *reinterpret_cast<const uint4 *>(img_low + 2u * (even ? i : i - T2));
@@ -889,13 +953,13 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
                     Pl[q][0] = Pl[q][1] = 0;
                 }
             }
-            const uint64_t blk0 = (uint64_t)(k - it.first) << p.logB;
             ENEC_TP(3);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                uint32_t Y[2] = {0u, 0u};
-                // d3: low m bits of the 8 columns of this row
-                if (M > 0) {
+                uint32_t Y[2] = {0u, 0u}, T3[2] = {0u, 0u};
+                // d3: low-plane values of the 8 columns of this row: the low m bits of y (fp16:
+                // with the last three mantissa bits on top)
+                if (LM > 0) {
 #pragma unroll
                     for (int f = 0; f < TL.count; ++f)
                         if (TL.row[f] == t) {
@@ -905,6 +969,13 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
                             for (int h = 0; h < 2; ++h)
                                 Y[h] |= shl_or_shr(Pl[TL.plane[f]][h], -TL.shift[f]) & smask;
                         }
+                    if constexpr (DT == DT_FP16) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            T3[h] = (Y[h] >> M) & 0x07070707u;
+                            Y[h] &= LMASK;
+                        }
+                    }
                 }
                 // d2/d3: high bits of masked groups, found through the mask prefix
                 if (A > 0) {
@@ -950,13 +1021,37 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
                     const uint32_t Z = Y[h] ^ SREP;
                     const uint32_t X = it.mode == 0 ? crep - Z : bytesub_safe(crep, Z);
                     const uint32_t sm = h ? smc[t].y : smc[t].x;
-                    const uint32_t Hi = bfi(0x7F7F7F7Fu, X >> 1, sm);
-                    const uint32_t Lo = bfi(0x7F7F7F7Fu, sm, X << 7);
+                    uint32_t Hi, Lo;         // high / low bytes of four 16-bit words
+                    if constexpr (DT == DT_FP16) {
+                        Hi = (sm & 0x80808080u) | ((X & 0x1F1F1F1Fu) << 2) | ((sm >> 5) & 0x03030303u);
+                        Lo = ((sm & 0x1F1F1F1Fu) << 3) | T3[h];
+                    } else {
+                        Hi = bfi(0x7F7F7F7Fu, X >> 1, sm);
+                        Lo = bfi(0x7F7F7F7Fu, sm, X << 7);
+                    }
                     o[2 * h] = byte_perm(Hi, Lo, 0x05010400u);
                     o[2 * h + 1] = byte_perm(Hi, Lo, 0x07030602u);
                 }
                 const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
-                if (e0 + 8 <= it.n_elems) {
+                if constexpr (DT == DT_FP32) {
+                    // element = lower half | bf16 word << 16
+                    const uint32_t lo[4] = {tl[t].x, tl[t].y, tl[t].z, tl[t].w};
+                    uint32_t w[8];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        w[2 * i] = byte_perm(o[i], lo[i], 0x05040100u);
+                        w[2 * i + 1] = byte_perm(o[i], lo[i], 0x07060302u);
+                    }
+                    uint32_t *out32 = reinterpret_cast<uint32_t *>(it.out);
+                    if (e0 + 8 <= it.n_elems) {
+                        *reinterpret_cast<uint4 *>(out32 + e0) = make_uint4(w[0], w[1], w[2], w[3]);
+                        *reinterpret_cast<uint4 *>(out32 + e0 + 4) = make_uint4(w[4], w[5], w[6], w[7]);
+                    } else if (e0 < it.n_elems) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (e0 + i < it.n_elems) out32[e0 + i] = w[i];
+                    }
+                } else if (e0 + 8 <= it.n_elems) {
                     *reinterpret_cast<uint4 *>(it.out + e0) = make_uint4(o[0], o[1], o[2], o[3]);
                 } else if (e0 < it.n_elems) {
 #pragma unroll
@@ -986,47 +1081,48 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
 }
 
 // ---------------------------------------------------------------------------------
-// exponent histogram (Sec. V-E phase 1), zero fill, plain copy
+// exponent histogram (Sec. V-E phase 1)
 // ---------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) histogram_kernel(const uint16_t *in, uint64_t n_elems,
-                                                        unsigned long long *hist)
+template <int DT>
+__global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_t n_elems, unsigned long long *hist)
 {
     __shared__ uint32_t s_h[4][256];
     const uint32_t tid = threadIdx.x;
     for (uint32_t i = tid; i < 1024; i += 256) (&s_h[0][0])[i] = 0;
     __syncthreads();
     uint32_t *mine = s_h[tid >> 6];
-    const uint64_t nvec = n_elems >> 3;
+    constexpr uint32_t PER_VEC = DT == DT_FP32 ? 4u : 8u;        // elements in 16 bytes
+    const uint64_t nvec = n_elems / PER_VEC;
     const uint64_t stride = (uint64_t)gridDim.x * 256u;
     // a wave's LDS counters cannot overflow: each thread adds at most 8 per iteration and the
     // launch keeps iterations * 64 * 8 below 2^32
     for (uint64_t v = (uint64_t)blockIdx.x * 256u + tid; v < nvec; v += stride) {
-        const uint4 q = reinterpret_cast<const uint4 *>(in)[v];
+        const uint4 q = reinterpret_cast<const uint4 *>(in_)[v];
         const uint32_t d[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            atomicAdd(&mine[(d[i] >> 7) & 0xFFu], 1u);
-            atomicAdd(&mine[(d[i] >> 23) & 0xFFu], 1u);
+            if constexpr (DT == DT_FP32) {
+                atomicAdd(&mine[(d[i] >> 23) & 0xFFu], 1u);
+            } else if constexpr (DT == DT_FP16) {
+                atomicAdd(&mine[(d[i] >> 10) & 0x1Fu], 1u);
+                atomicAdd(&mine[(d[i] >> 26) & 0x1Fu], 1u);
+            } else {
+                atomicAdd(&mine[(d[i] >> 7) & 0xFFu], 1u);
+                atomicAdd(&mine[(d[i] >> 23) & 0xFFu], 1u);
+            }
         }
     }
-    if (blockIdx.x == 0 && tid < (uint32_t)(n_elems & 7u))
-        atomicAdd(&mine[(in[(nvec << 3) + tid] >> 7) & 0xFFu], 1u);
+    if (blockIdx.x == 0 && tid < (uint32_t)(n_elems % PER_VEC)) {
+        const uint64_t e = nvec * PER_VEC + tid;
+        uint32_t x;
+        if constexpr (DT == DT_FP32) x = (reinterpret_cast<const uint32_t *>(in_)[e] >> 23) & 0xFFu;
+        else if constexpr (DT == DT_FP16) x = (reinterpret_cast<const uint16_t *>(in_)[e] >> 10) & 0x1Fu;
+        else x = (reinterpret_cast<const uint16_t *>(in_)[e] >> 7) & 0xFFu;
+        atomicAdd(&mine[x], 1u);
+    }
     __syncthreads();
     const uint32_t c = s_h[0][tid] + s_h[1][tid] + s_h[2][tid] + s_h[3][tid];
     if (c) atomicAdd(&hist[tid], (unsigned long long)c);
-}
-
-__global__ void __launch_bounds__(256) fill_zero_kernel(uint4 *p, uint64_t nvec)
-{
-    const uint64_t stride = (uint64_t)gridDim.x * 256u;
-    for (uint64_t v = (uint64_t)blockIdx.x * 256u + threadIdx.x; v < nvec; v += stride)
-        p[v] = make_uint4(0, 0, 0, 0);
-}
-
-__global__ void __launch_bounds__(256) copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, uint64_t nvec)
-{
-    const uint64_t stride = (uint64_t)gridDim.x * 256u;
-    for (uint64_t v = (uint64_t)blockIdx.x * 256u + threadIdx.x; v < nvec; v += stride) dst[v] = src[v];
 }
 
 }  // namespace enec

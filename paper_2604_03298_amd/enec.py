@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libenec.so")
 
 OK, E_ARG, E_DTYPE, E_BLOCK, E_PARAMS, E_CAPACITY, E_RANGE, E_FORMAT, E_HIP = range(9)
-BF16 = 0
+BF16, FP16, FP32 = 0, 1, 2
 HEADER_BYTES = 64
 
 EXPORTS = [
@@ -84,7 +84,7 @@ def lib():
         L.enec_tune.restype = C.c_int
         L.enec_tune.argtypes = [vp, sz, C.c_int, C.POINTER(Params), u64p, vp, sz, vp]
         L.enec_tune_histogram.restype = C.c_int
-        L.enec_tune_histogram.argtypes = [u64p, C.POINTER(Params)]
+        L.enec_tune_histogram.argtypes = [u64p, C.c_int, C.POINTER(Params)]
         L.enec_stream_info.restype = C.c_int
         L.enec_stream_info.argtypes = [vp, C.POINTER(Params), u64p, C.POINTER(u32), u64p,
                                        C.POINTER(C.c_int), C.POINTER(u32)]
@@ -113,6 +113,17 @@ def _params(p) -> Params:
     return p if isinstance(p, Params) else Params(*[int(v) for v in p])
 
 
+def dtype_of(t, dtype=None) -> int:
+    """The library's dtype code for a torch tensor: float16 -> FP16, 4-byte elements -> FP32,
+    any other 2-byte element (bfloat16, or int16 / uint16 bit patterns) -> BF16, unless given."""
+    if dtype is not None:
+        return int(dtype)
+    import torch
+    if getattr(t, "dtype", None) == torch.float16:
+        return FP16
+    return FP32 if hasattr(t, "element_size") and t.element_size() == 4 else BF16
+
+
 # ---- host-only entry points -------------------------------------------------------
 def version() -> int:
     return int(lib().enec_version())
@@ -134,11 +145,11 @@ def workspace_bytes(n_elems: int, block_size: int = 0) -> int:
     return int(lib().enec_workspace_bytes(n_elems, block_size))
 
 
-def tune_histogram(hist) -> tuple:
+def tune_histogram(hist, dtype: int = BF16) -> tuple:
     h = np.ascontiguousarray(hist, dtype=np.uint64)
     assert h.size == 256
     p = Params()
-    _check(lib().enec_tune_histogram(h.ctypes.data_as(C.POINTER(C.c_uint64)), C.byref(p)),
+    _check(lib().enec_tune_histogram(h.ctypes.data_as(C.POINTER(C.c_uint64)), dtype, C.byref(p)),
            "enec_tune_histogram")
     return p.astuple()
 
@@ -170,17 +181,18 @@ def new_workspace(n_elems: int, block_size: int = 0, device="cuda", stream=None)
 
 
 def compress(src, params, out, workspace, block_size: int = 0, out_bytes=None, stream=None,
-             n_elems: int | None = None) -> int:
-    """Enqueues enec_compress.  src: device tensor of 2-byte elements; params: (b, n, m, L) or
-    None (tune first); out: device uint8 tensor of >= compress_bound bytes; out_bytes: None or a
-    device / pinned-host tensor with room for one u64.  Returns the status code (range errors
-    are reported through the stream header, not here)."""
+             n_elems: int | None = None, dtype: int | None = None) -> int:
+    """Enqueues enec_compress.  src: device tensor of 2- or 4-byte elements (dtype: see dtype_of);
+    params: (b, n, m, L) or None (tune first); out: device uint8 tensor of >= compress_bound bytes;
+    out_bytes: None or a device / pinned-host tensor with room for one u64.  Returns the status
+    code (range errors are reported through the stream header, not here)."""
     n = src.numel() if n_elems is None else n_elems
-    assert src.element_size() == 2
+    dt = dtype_of(src, dtype)
+    assert src.element_size() == (4 if dt == FP32 else 2)
     pp = C.byref(_params(params)) if params is not None else None
     ob = C.c_void_p(out_bytes.data_ptr()) if out_bytes is not None else None
     return int(lib().enec_compress(
-        C.c_void_p(src.data_ptr()), n, BF16, block_size, pp, C.c_void_p(out.data_ptr()),
+        C.c_void_p(src.data_ptr()), n, dt, block_size, pp, C.c_void_p(out.data_ptr()),
         out.numel() * out.element_size(), ob, C.c_void_p(workspace.data_ptr()),
         workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 
@@ -200,10 +212,13 @@ def decompress_with_header(stream_buf, host_header, out, n_elems: int | None = N
         hdr.ctypes.data, C.c_void_p(out.data_ptr()), n, _stream_handle(stream)))
 
 
-def compress_batch(srcs, params, outs, workspace, block_sizes=None, out_bytes=None, stream=None) -> int:
-    """Enqueues enec_compress_batch.  srcs / outs: lists of device tensors; params: list of
-    (b, n, m, L) or None per tensor; out_bytes: None or a list of one-u64 device-accessible tensors."""
+def compress_batch(srcs, params, outs, workspace, block_sizes=None, out_bytes=None, stream=None,
+                   dtype: int | None = None) -> int:
+    """Enqueues enec_compress_batch.  srcs / outs: lists of device tensors (one element format for
+    all, see dtype_of); params: list of (b, n, m, L) or None per tensor; out_bytes: None or a list
+    of one-u64 device-accessible tensors."""
     n = len(srcs)
+    dt = dtype_of(srcs[0], dtype) if n else BF16
     keep = [_params(p) if p is not None else None for p in params]
     items = (CompressItem * n)()
     for i in range(n):
@@ -214,7 +229,7 @@ def compress_batch(srcs, params, outs, workspace, block_sizes=None, out_bytes=No
         items[i].out = outs[i].data_ptr()
         items[i].out_capacity = outs[i].numel() * outs[i].element_size()
         items[i].out_bytes = out_bytes[i].data_ptr() if out_bytes is not None else None
-    return int(lib().enec_compress_batch(items, n, BF16, C.c_void_p(workspace.data_ptr()),
+    return int(lib().enec_compress_batch(items, n, dt, C.c_void_p(workspace.data_ptr()),
                                          workspace.numel() * workspace.element_size(),
                                          _stream_handle(stream)))
 
@@ -241,11 +256,11 @@ def decompress_batch(stream_bufs, host_headers, outs, stream=None, items=None) -
     return int(lib().enec_decompress_batch(items, len(items), _stream_handle(stream)))
 
 
-def tune(src, workspace, stream=None, want_histogram: bool = False):
+def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int | None = None):
     """-> (b, n, m, L) [, histogram]; synchronous."""
     p = Params()
     hist = np.zeros(256, dtype=np.uint64)
-    _check(lib().enec_tune(C.c_void_p(src.data_ptr()), src.numel(), BF16, C.byref(p),
+    _check(lib().enec_tune(C.c_void_p(src.data_ptr()), src.numel(), dtype_of(src, dtype), C.byref(p),
                            hist.ctypes.data_as(C.POINTER(C.c_uint64)),
                            C.c_void_p(workspace.data_ptr()),
                            workspace.numel() * workspace.element_size(), _stream_handle(stream)),

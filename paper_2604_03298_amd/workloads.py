@@ -1,9 +1,9 @@
-"""Seeded synthetic bf16 weight tensors for the tests and the benchmark.
+"""Seeded synthetic weight tensors (bf16; fp16 and fp32 variants) for the tests and the benchmark.
 
 This module only makes inputs.  It holds none of the codec's arithmetic and is
 the one module that both the CPU oracle's tests and the GPU path's tests use, so
-that both sides always see the same bytes.  All tensors are returned as numpy
-uint16 arrays holding bf16 bit patterns.
+that both sides always see the same bytes.  Tensors are returned as numpy arrays of
+bit patterns: uint16 for bf16 and fp16, uint32 for fp32.
 
 The tensors stand in for the HuggingFace checkpoints the paper measures on
 (Table II), which are not available offline: shapes follow 7B-70B decoder layers,
@@ -34,6 +34,16 @@ def gaussian(n_elems: int, std: float, seed: int) -> np.ndarray:
         e = min(n_elems, s + step)
         out[s:e] = f32_to_bf16_bits((std * g.standard_normal(e - s)).astype(np.float32))
     return out
+
+
+def gaussian_fp16(n_elems: int, std: float, seed: int) -> np.ndarray:
+    """i.i.d. N(0, std^2) drawn in float64, rounded to IEEE half; uint16 bit patterns."""
+    return (std * _rng(seed).standard_normal(n_elems)).astype(np.float16).view(np.uint16)
+
+
+def gaussian_fp32(n_elems: int, std: float, seed: int) -> np.ndarray:
+    """i.i.d. N(0, std^2) drawn in float64, rounded to float32; uint32 bit patterns."""
+    return (std * _rng(seed).standard_normal(n_elems)).astype(np.float32).view(np.uint32)
 
 
 def config1(seed: int = 1, rows: int = 1024, cols: int = 4096) -> np.ndarray:

@@ -45,8 +45,11 @@ def test_bounds_and_block_sizes_match_oracle(enec, oracle):
         assert enec.compress_bound(n) == oracle.compress_bound(n, oracle.default_block(n))
         assert enec.workspace_bytes(n) >= 3072 + 8 * max(1, oracle.num_blocks(n, oracle.default_block(n)))
         assert enec.workspace_bytes(n) % 256 == 0
+        for dt in (1, 2):                     # fp16, fp32
+            for B in [2048, 16384]:
+                assert enec.compress_bound(n, dtype=dt, block_size=B) == oracle.compress_bound(n, B, dt)
     assert enec.compress_bound(100, block_size=3000) == 0
-    assert enec.compress_bound(100, dtype=1) == 0
+    assert enec.compress_bound(100, dtype=3) == 0
     assert enec.workspace_bytes(100, block_size=1000) == 0
 
 
@@ -66,6 +69,15 @@ def test_host_tuner_matches_oracle(enec, oracle, ref):
         assert enec.tune_histogram(h) == oracle.tune_hist(h)[0]
     for h in hists[:20]:
         assert enec.tune_histogram(h) == ref.tune_hist([int(v) for v in h])[0]
+    # fp16: 32 exponent values, Eq. 1's width capped at 5
+    for _ in range(200):
+        h = np.zeros(256, np.uint64)
+        lo = int(rng.integers(0, 31)); width = int(rng.integers(1, 33 - lo))
+        idx = rng.integers(lo, lo + width, size=int(rng.integers(1, 12)))
+        h[idx] = rng.integers(1, 1 << int(rng.integers(1, 40)), size=idx.size).astype(np.uint64)
+        assert enec.tune_histogram(h, dtype=1) == oracle.tune_hist(h, 5)[0]
+    with pytest.raises(Exception):
+        enec.tune_histogram(hists[0], dtype=7)
 
 
 def test_stream_info_parses_oracle_headers(enec, oracle):
@@ -90,7 +102,7 @@ def test_null_and_misaligned_arguments_are_rejected_on_the_host(enec):
     assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(p), None, 1 << 20, None, fake, 1 << 20, None) == enec.E_ARG
     assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(p), fake, 1 << 20, None, None, 1 << 20, None) == enec.E_ARG
     assert L.enec_compress(odd, 10, 0, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_ARG
-    assert L.enec_compress(fake, 10, 1, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_DTYPE
+    assert L.enec_compress(fake, 10, 5, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_DTYPE
     assert L.enec_compress(fake, 10, 0, 1000, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_BLOCK
     assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(p), fake, 10, None, fake, 1 << 20, None) == enec.E_CAPACITY
     assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 16, None) == enec.E_CAPACITY
@@ -106,7 +118,11 @@ def test_null_and_misaligned_arguments_are_rejected_on_the_host(enec):
     assert L.enec_workspace_init(None, 16, None) == enec.E_ARG
     assert L.enec_workspace_init(fake, 17, None) == enec.E_ARG
     assert L.enec_copy(fake, odd, 16, None) == enec.E_ARG
-    assert L.enec_tune_histogram(None, ctypes.byref(p)) == enec.E_ARG
+    assert L.enec_tune_histogram(None, 0, ctypes.byref(p)) == enec.E_ARG
+    for dt, bad in ((1, (10, 6, 2, 16)), (1, (40, 4, 2, 16)), (2, (122, 9, 3, 16))):
+        q = enec.Params(*bad)
+        assert L.enec_compress(fake, 10, dt, 0, ctypes.byref(q), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_PARAMS
+    assert L.enec_compress(fake, 10, 3, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_DTYPE
     assert L.enec_stream_info(None, None, None, None, None, None, None) == enec.E_ARG
 
 
