@@ -29,7 +29,7 @@
 // Three waves per SIMD for the compression kernel: the register budget (168) that lets three
 // workgroups of 256 threads share a CU.
 #ifndef ENEC_COMPRESS_OCCUPANCY
-#define ENEC_COMPRESS_OCCUPANCY __attribute__((amdgpu_waves_per_eu(3, 3)))
+#define ENEC_COMPRESS_OCCUPANCY __attribute__((amdgpu_waves_per_eu(DT == 2 ? 2 : 3, DT == 2 ? 2 : 3)))
 #endif
 #ifndef ENEC_TP
 #define ENEC_TP_DECL
@@ -243,9 +243,9 @@ struct CompressItem {
     uint64_t *ws_acc;       // ceil(nb / 64) group accumulators, zero between calls
     uint64_t n_elems;
     uint64_t payload_base;
-    uint64_t tail_base;     // fp32: where the lower halves of the elements go
     uint32_t nb, first;
     uint32_t b, mode;       // mode 0: window clear of 0 and 255; 1: n = exponent width; 2: window touches an end
+    uint64_t tail_base;     // fp32: where the lower halves of the elements go
 };
 
 struct CompressArgs {

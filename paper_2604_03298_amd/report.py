@@ -1,6 +1,7 @@
 """Runs the codec on all five synthetic configurations on one MI355X and prints one JSON line per
 configuration (throughput on uncompressed bytes, ratio, fraction of the 8 TB/s HBM peak in bytes
-moved).  `python -m paper_2604_03298_amd.report [--configs 1,2,3a,3b,4,5]`.
+moved).  `python -m paper_2604_03298_amd.report [--configs 1,2,3a,3b,4,5,fp16,fp32]`.
+The last two are the seven matrix shapes of configuration 2 as fp16 / fp32 tensors, N(0, 0.02^2).
 
 Tensors of configurations 1-3 come from the seeded numpy generators of `workloads.py` (the ones the
 parity tests use); configurations 4 and 5 (15 GB / 4.8 GB of bf16) are drawn on the GPU with a
@@ -22,13 +23,13 @@ def _events(torch, n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
-def run_group(torch, enec, name, srcs, reps=5):
+def run_group(torch, enec, name, srcs, reps=5, dtype=0):
     """Tune, compress (batched), decompress (batched), verify; returns a dict of results."""
     n_el = [s.numel() for s in srcs]
-    raw = 2 * sum(n_el)
+    raw = srcs[0].element_size() * sum(n_el)
     ws = enec.new_workspace(sum(n_el))
-    params = [enec.tune(s, ws) for s in srcs]
-    outs = [torch.empty(enec.compress_bound(n), dtype=torch.uint8, device="cuda") for n in n_el]
+    params = [enec.tune(s, ws, dtype=dtype) for s in srcs]
+    outs = [torch.empty(enec.compress_bound(n, dtype=dtype), dtype=torch.uint8, device="cuda") for n in n_el]
     sizes = torch.zeros(len(srcs), dtype=torch.int64, device="cuda")
     szl = [sizes[i:i + 1] for i in range(len(srcs))]
     chunks = [list(range(i, min(i + 16, len(srcs)))) for i in range(0, len(srcs), 16)]
@@ -36,7 +37,7 @@ def run_group(torch, enec, name, srcs, reps=5):
     def comp():
         for c in chunks:
             rc = enec.compress_batch([srcs[i] for i in c], [params[i] for i in c], [outs[i] for i in c], ws,
-                                     out_bytes=[szl[i] for i in c])
+                                     out_bytes=[szl[i] for i in c], dtype=dtype)
             assert rc == 0, enec.strerror(rc)
 
     comp()
@@ -75,15 +76,17 @@ def run_group(torch, enec, name, srcs, reps=5):
     }, (outs, stream_bytes, hdrs, backs)
 
 
-def gpu_gaussian(torch, rows, cols, std, seed):
+def gpu_gaussian(torch, rows, cols, std, seed, dtype=None):
+    """N(0, std^2) drawn on the GPU, as bit patterns: int16 for bf16 (default) and float16, int32 for float32."""
+    dtype = torch.bfloat16 if dtype is None else dtype
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
-    x = torch.empty(rows * cols, dtype=torch.bfloat16, device="cuda")
+    x = torch.empty(rows * cols, dtype=dtype, device="cuda")
     step = 1 << 25      # float64 draws: float32 samplers emit exact zeros, which would force n = 8
     for s in range(0, x.numel(), step):
         e = min(x.numel(), s + step)
-        x[s:e] = (torch.randn(e - s, generator=g, device="cuda", dtype=torch.float64) * std).to(torch.bfloat16)
-    return x.view(torch.int16)
+        x[s:e] = (torch.randn(e - s, generator=g, device="cuda", dtype=torch.float64) * std).to(dtype)
+    return x.view(torch.int32 if dtype == torch.float32 else torch.int16)
 
 
 def offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs):
@@ -172,6 +175,16 @@ def main():
         res, (outs, stream_bytes, hdrs, backs) = run_group(torch, enec, "5: 8 layers 8192x8192 + 8192x28672 (HBM resident)", srcs, reps=3)
         res["offload"] = offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs)
         print(json.dumps(res), flush=True)
+        del srcs, outs, backs
+        torch.cuda.empty_cache()
+    for key, tdt, code in (("fp16", torch.float16, enec.FP16), ("fp32", torch.float32, enec.FP32)):
+        if key in want:
+            shapes = [(r, c) for name, r, c, _ in W.config2_spec() if r > 1 and c > 1]
+            srcs = [gpu_gaussian(torch, r, c, 0.02, 6000 + i, tdt) for i, (r, c) in enumerate(shapes)]
+            print(json.dumps(run_group(torch, enec, f"{key}: the seven matrices of configuration 2 as {key}, N(0,0.02^2)",
+                                       srcs, reps=20, dtype=code)[0]), flush=True)
+            del srcs
+            torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":
