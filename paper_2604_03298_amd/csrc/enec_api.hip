@@ -50,12 +50,12 @@ using namespace enec;
 // workspace: [0, 1024) control records of the block classes | [1024, 3072) histogram |
 // group words | block words (the last two sized by the call's block count)
 constexpr size_t WS_CTL = 0, WS_HIST = 1024, WS_STATE = WS_HIST + 256 * 8;
-inline size_t ws_groups(size_t nb) { return (nb + 63) / 64; }
+inline size_t ws_groups(size_t nb) { return (nb + GROUP - 1) / GROUP; }
 // The state words behind WS_STATE: first the group accumulators, which every call leaves zero, in
-// a region whose length depends only on the size of the workspace (1/33 of the words), then the
+// a region whose length depends only on the size of the workspace (1/9 of the words), then the
 // tagged group and block words, handed out anew by every launch.
 inline size_t ws_state_words(size_t workspace_bytes) { return workspace_bytes < WS_STATE ? 0 : (workspace_bytes - WS_STATE) / 8; }
-inline size_t ws_acc_words(size_t workspace_bytes) { return ws_state_words(workspace_bytes) / 33; }
+inline size_t ws_acc_words(size_t workspace_bytes) { return ws_state_words(workspace_bytes) / 9; }
 constexpr size_t MAX_ELEMS = (size_t)1 << 34;      // keeps every offset below 2^36 bytes
 
 inline size_t align16(size_t v) { return (v + 15) & ~(size_t)15; }
@@ -211,8 +211,8 @@ size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size)
     // room for the scan words of up to MAX_BATCH tensors with n_elems elements in total
     const size_t nb = num_blocks(n_elems, B) + MAX_BATCH;
     const size_t groups = ws_groups(nb) + MAX_BATCH;
-    const size_t by_acc = 33 * groups, by_words = (33 * (groups + nb) + 31) / 32;
-    return (WS_STATE + 8 * ((by_acc > by_words ? by_acc : by_words) + 33) + 255) & ~(size_t)255;
+    const size_t by_acc = 9 * groups, by_words = (9 * (groups + nb) + 7) / 8;
+    return (WS_STATE + 8 * ((by_acc > by_words ? by_acc : by_words) + 9) + 255) & ~(size_t)255;
 }
 
 int enec_workspace_init(void *workspace, size_t bytes, void *stream)

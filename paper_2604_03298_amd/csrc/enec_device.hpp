@@ -176,7 +176,7 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
 // are enough, no fence is needed, and they are never cleared: a word whose tag is not the
 // current call's tag is simply "not published yet".
 //   block word k   size of data block k, stored as soon as the block's mask is known
-//   group word g   sum of the sizes of blocks 64g .. 64g+63
+//   group word g   sum of the sizes of the GROUP blocks of group g
 //   accumulator g  [63:48] blocks counted, [47:32] of them with a range error, [31:0] sum of
 //                  their sizes; zero between calls.  Every block adds itself with one atomic; the
 //                  workgroup whose addition completes the group stores the group word and zeroes
@@ -184,7 +184,7 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
 //                  and no workgroup ever waits for blocks of its own generation (an owner that
 //                  polled its 63 neighbours turned the loop latency-bound as soon as the blocks
 //                  took equal time and the workgroups ran in lockstep).
-// The start of block k is the sum of the group words below k/64 plus the block words of the
+// The start of block k is the sum of the group words below its group plus the block words of the
 // earlier blocks of its own group: few words, read by one wave.
 //
 // Work distribution.  The grid is persistent (at most as many workgroups as the device holds at
@@ -213,6 +213,9 @@ constexpr uint32_t SPIN_LIMIT = 1u << 20;
 constexpr uint32_t NO_BLOCK = 0xFFFFFFFFu;
 constexpr uint32_t WS_STRIDE = 32;            // control records sit 128 bytes apart
 constexpr uint32_t WS_CLASSES = 8;
+// blocks per scan group: with G blocks a start costs G - 1 block words plus (blocks in flight) / G
+// group words, and G additions meet on one accumulator at about 12 ns each
+constexpr uint32_t GROUP_LOG = 3, GROUP = 1u << GROUP_LOG;
 
 __device__ __forceinline__ uint64_t ld_state(const uint64_t *p)
 {
@@ -239,8 +242,8 @@ struct CompressItem {
     uint8_t *out;
     uint64_t *out_bytes;    // device-accessible or null
     uint64_t *ws_block;     // nb block words
-    uint64_t *ws_group;     // ceil(nb / 64) group words
-    uint64_t *ws_acc;       // ceil(nb / 64) group accumulators, zero between calls
+    uint64_t *ws_group;     // ceil(nb / GROUP) group words
+    uint64_t *ws_acc;       // ceil(nb / GROUP) group accumulators, zero between calls
     uint64_t n_elems;
     uint64_t payload_base;
     uint32_t nb, first;
@@ -445,14 +448,14 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     // start of block kb (wave 0; early_g / early_b = copies of the first needed group words / of
     // the earlier block words of its group, read ahead of time)
     auto block_start = [&](const CompressItem &it, uint32_t kb, bool early, uint64_t early_g, uint64_t early_b) -> uint64_t {
-        const uint32_t g = kb >> 6;
+        const uint32_t g = kb >> GROUP_LOG;
         while (groups_summed < g) {
             const uint32_t c = g - groups_summed < 64u ? g - groups_summed : 64u;
             groups_sum += sum_words(it.ws_group + groups_summed, c, early, early_g, scan_flags);
             groups_summed += c;
             early = false;
         }
-        const uint64_t own_group = sum_words(it.ws_block + ((uint64_t)g << 6), kb & 63u, early_b != 0, early_b, scan_flags);
+        const uint64_t own_group = sum_words(it.ws_block + ((uint64_t)g << GROUP_LOG), kb & (GROUP - 1u), early_b != 0, early_b, scan_flags);
         return (groups_sum + own_group) << 4;
     };
 
@@ -548,9 +551,9 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         if (wave == 0 && pend != NO_BLOCK) {
             if (scan_item != pend_item) { scan_item = pend_item; groups_sum = 0; groups_summed = 0; scan_flags = 0; }
             const CompressItem &pit = p.item[pend_item];
-            const uint32_t pg = pend >> 6;
+            const uint32_t pg = pend >> GROUP_LOG;
             if (groups_summed + lane < pg) early_g = ld_state(pit.ws_group + groups_summed + lane);
-            if (lane < (pend & 63u)) early_b = ld_state(pit.ws_block + ((uint64_t)pg << 6) + lane);
+            if (lane < (pend & (GROUP - 1u))) early_b = ld_state(pit.ws_block + ((uint64_t)pg << GROUP_LOG) + lane);
         }
 
         // the ticket for the following block is drawn now and looked at after the arithmetic
@@ -673,7 +676,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         if (tid == 0) st_state(it.ws_block + kl, tag | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
         uint64_t acc_old = 0;
         if (tid == acc_tid)
-            acc_old = __hip_atomic_fetch_add(it.ws_acc + (kl >> 6), (1ull << 48) | ((uint64_t)own_err << 32) | (uint64_t)(S >> 4),
+            acc_old = __hip_atomic_fetch_add(it.ws_acc + (kl >> GROUP_LOG), (1ull << 48) | ((uint64_t)own_err << 32) | (uint64_t)(S >> 4),
                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         // ---- a5: one record per masked group ------------------------------------------
@@ -736,8 +739,8 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         // ---- a6: whoever completes a group publishes its word and clears the accumulator for
         // the next call; nobody ever waits for blocks of its own generation ------------------
         if (tid == acc_tid) {
-            const uint32_t g = kl >> 6;
-            const uint32_t members = it.nb - (g << 6) < 64u ? it.nb - (g << 6) : 64u;
+            const uint32_t g = kl >> GROUP_LOG;
+            const uint32_t members = it.nb - (g << GROUP_LOG) < GROUP ? it.nb - (g << GROUP_LOG) : GROUP;
             if ((uint32_t)(acc_old >> 48) == members - 1u) {
                 const uint64_t sum = (acc_old & 0xFFFFFFFFull) + (S >> 4);
                 const bool any_err = ((acc_old >> 32) & 0xFFFFull) != 0 || own_err;

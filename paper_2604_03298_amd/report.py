@@ -144,7 +144,7 @@ def offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--configs", default="1,2,3a,3b,4,5")
+    ap.add_argument("--configs", default="1,2,3a,3b,4,5,fp16,fp32")
     args = ap.parse_args()
     want = args.configs.split(",")
     import torch
