@@ -386,7 +386,10 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         if (resident == 0) return ENEC_E_HIP;
         const unsigned grid = a.total < resident ? a.total : resident;
         a.ncls = grid < 8 ? grid : 8;
-        a.lookahead = a.total >= 2 * grid ? 1u : 0u;
+        // The next ticket is drawn while the current block is worked on if the draw cannot take work
+        // away from a workgroup that has not started yet: enough blocks for two rounds, or none
+        // beyond the first round (then every draw only closes the books of its class).
+        a.lookahead = (a.total >= 2 * grid || a.total == grid) ? 1u : 0u;
         hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
     }
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;

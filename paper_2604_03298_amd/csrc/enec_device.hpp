@@ -674,9 +674,12 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         // [blocks:16 | blocks with a range error:16 | sum of sizes:32]; what the addition returns
         // is looked at after barrier 2, when it has had time to travel ---------------------
         if (tid == 0) st_state(it.ws_block + kl, tag | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
+        // (a group of one block, e.g. a tensor of one block, is complete with its only member)
+        const uint32_t grp = kl >> GROUP_LOG;
+        const uint32_t members = it.nb - (grp << GROUP_LOG) < GROUP ? it.nb - (grp << GROUP_LOG) : GROUP;
         uint64_t acc_old = 0;
-        if (tid == acc_tid)
-            acc_old = __hip_atomic_fetch_add(it.ws_acc + (kl >> GROUP_LOG), (1ull << 48) | ((uint64_t)own_err << 32) | (uint64_t)(S >> 4),
+        if (tid == acc_tid && members > 1u)
+            acc_old = __hip_atomic_fetch_add(it.ws_acc + grp, (1ull << 48) | ((uint64_t)own_err << 32) | (uint64_t)(S >> 4),
                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         // ---- a5: one record per masked group ------------------------------------------
@@ -739,13 +742,11 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         // ---- a6: whoever completes a group publishes its word and clears the accumulator for
         // the next call; nobody ever waits for blocks of its own generation ------------------
         if (tid == acc_tid) {
-            const uint32_t g = kl >> GROUP_LOG;
-            const uint32_t members = it.nb - (g << GROUP_LOG) < GROUP ? it.nb - (g << GROUP_LOG) : GROUP;
             if ((uint32_t)(acc_old >> 48) == members - 1u) {
                 const uint64_t sum = (acc_old & 0xFFFFFFFFull) + (S >> 4);
                 const bool any_err = ((acc_old >> 32) & 0xFFFFull) != 0 || own_err;
-                st_state(it.ws_group + g, tag | (any_err ? ST_ERR : 0ull) | sum);
-                st_state(it.ws_acc + g, 0ull);
+                st_state(it.ws_group + grp, tag | (any_err ? ST_ERR : 0ull) | sum);
+                if (members > 1u) st_state(it.ws_acc + grp, 0ull);
             }
         }
 
