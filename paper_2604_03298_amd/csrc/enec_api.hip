@@ -390,6 +390,11 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         // away from a workgroup that has not started yet: enough blocks for two rounds, or none
         // beyond the first round (then every draw only closes the books of its class).
         a.lookahead = (a.total >= 2 * grid || a.total == grid) ? 1u : 0u;
+        a.spin_limit = SPIN_LIMIT;
+        if (const char *e = std::getenv("ENEC_SPIN_LIMIT")) {       // test aid: make a scan that cannot progress give up early
+            const long v = std::atol(e);
+            if (v > 0 && v < (long)SPIN_LIMIT) a.spin_limit = (uint32_t)v;
+        }
         hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
     }
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;

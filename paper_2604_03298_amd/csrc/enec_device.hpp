@@ -209,7 +209,7 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
 // ---------------------------------------------------------------------------------
 constexpr uint64_t ST_ERR = 1ull << 23;
 constexpr uint64_t ST_VALUE = (1ull << 23) - 1;
-constexpr uint32_t SPIN_LIMIT = 1u << 20;
+constexpr uint32_t SPIN_LIMIT = 1u << 20;      // default of CompressArgs::spin_limit: seconds, far beyond any real wait
 constexpr uint32_t NO_BLOCK = 0xFFFFFFFFu;
 constexpr uint32_t WS_STRIDE = 32;            // control records sit 128 bytes apart
 constexpr uint32_t WS_CLASSES = 8;
@@ -258,6 +258,7 @@ struct CompressArgs {
     uint32_t ncls;          // number of block classes = min(8, gridDim.x)
     uint32_t lookahead;     // draw the next ticket while working on the current block
     uint32_t n_items;
+    uint32_t spin_limit;    // polls of the scan state after which a workgroup gives up (status ENEC_E_HIP)
     CompressItem item[MAX_BATCH];
 };
 
@@ -439,7 +440,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                 ok = (v & ~0xFFFFFFull) == tag;
             }
             if (__builtin_amdgcn_ballot_w64(!ok) == 0) break;
-            if (++spins > SPIN_LIMIT) { flags |= 4u; v = 0; break; }           // never hang
+            if (++spins > p.spin_limit) { flags |= 4u; v = 0; break; }         // never hang
             spin_pause(spins);
         }
         if (__builtin_amdgcn_ballot_w64(need && (v & ST_ERR))) flags |= 2u;

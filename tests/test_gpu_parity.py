@@ -174,9 +174,39 @@ def test_workspace_is_reusable_and_results_are_deterministic(gpu, oracle):
         rc, out, nbytes, _ = gpu.compress(small, ps, 16384, src=src_s)
         assert rc == 0 and nbytes == ss.size and np.array_equal(out[:nbytes], ss), f"run {i}"
     # the ticket counter of every class has come back to the base the next call will read
-    ctl = gpu.ws.cpu().numpy()[:1024].view(np.uint32).reshape(8, 32)
+    ws_host = gpu.ws.cpu().numpy()
+    ctl = ws_host[:1024].view(np.uint32).reshape(8, 32)
     assert (ctl[:, 0] == ctl[:, 1]).all()
     assert len(set(ctl[:, 2].tolist())) == 1
+    # every group accumulator (the first ninth of the state words) is back to zero
+    words = ws_host[3072:3072 + (ws_host.size - 3072) // 8 * 8].view(np.uint64)
+    assert (words[:words.size // 9] == 0).all()
+
+
+def test_dirty_workspace_ends_in_a_status_not_in_a_hang(gpu, oracle, monkeypatch):
+    """A workspace left dirty (a process died in the middle of a call) must not hang the scan: the
+    waits are bounded and the stream header then says ENEC_E_HIP.  The bound is shortened through
+    the library's test aid so that the kernel gives up after microseconds."""
+    torch, enec = gpu.torch, gpu.enec
+    w = W.gaussian(40 * 16384, 0.02, 83)
+    p = oracle.tune(w)
+    src = gpu.to_dev(w)
+    ws = enec.new_workspace(w.size)
+    words = ws[3072:3072 + (ws.numel() - 3072) // 8 * 8].view(torch.int64)
+    words[:words.numel() // 9] = 100 << 48            # accumulators claim 100 blocks too many: no group ever completes
+    out = torch.zeros(enec.compress_bound(w.size), dtype=torch.uint8, device="cuda")
+    size = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    monkeypatch.setenv("ENEC_SPIN_LIMIT", "200")
+    assert enec.compress(src, p, out, ws, out_bytes=size) == 0
+    torch.cuda.synchronize()
+    monkeypatch.delenv("ENEC_SPIN_LIMIT")
+    info = enec.stream_info(out[:64].cpu().numpy())
+    assert info["status"] == enec.E_HIP and info["total_bytes"] == 0 and int(size.item()) == 0
+    enec.workspace_init(ws)                              # the documented way out
+    assert enec.compress(src, p, out, ws, out_bytes=size) == 0
+    torch.cuda.synchronize()
+    s_o = oracle.compress(w, p, 16384)[1]
+    assert int(size.item()) == s_o.size and np.array_equal(out[:s_o.size].cpu().numpy(), s_o)
 
 
 def test_back_to_back_calls_without_sync(gpu, oracle):
