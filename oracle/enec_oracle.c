@@ -57,7 +57,11 @@ enum {
     ORC_E_FORMAT = 7
 };
 
-#define ORC_L 16u          /* group length, Sec. VI-D "Group Length" / Table VI */
+#define ORC_L 16u          /* default group length, Sec. VI-D "Group Length" / Table VI */
+
+/* Group lengths the container accepts: Eq. 4 searches L jointly with m; the paper's hardware
+ * forces L >= 16 and L = 16 always wins there (Sec. V-E phase 3, Sec. VI-D). */
+static int group_ok(unsigned L) { return L == 8u || L == 16u || L == 32u; }
 #define ORC_HEADER 64u
 
 /* ------------------------------------------------------------------ */
@@ -334,6 +338,43 @@ void orc_tune_hist(const uint64_t hist[256], uint8_t params[4], uint64_t *out_D,
     orc_tune_hist_e(hist, 8, params, out_D, out_bexp);
 }
 
+/* Phase 3 as Eq. 4 states it, with the group length searched jointly with m over the lengths
+ * whose bits are set in `lengths` (8 | 16 | 32): B_exp(m, L) = 1/L + n + (m - n) p(m)^L, the power
+ * by repeated squaring.  (b, n) come from phase 2 as above.  Ties: smaller m, then smaller L. */
+void orc_tune_hist_groups(const uint64_t hist[256], unsigned E, unsigned lengths, uint8_t params[4],
+                          uint64_t *out_D, double *out_bexp)
+{
+    unsigned l = 256, h = 0, x, m, L, best_m = 0, best_L = 0, b, n;
+    uint64_t total = 0;
+    double best = 0.0;
+    int have = 0;
+    orc_tune_hist_e(hist, E, params, out_D, NULL);
+    b = params[0]; n = params[1];
+    for (x = 0; x < 256; x++)
+        if (hist[x]) { if (x < l) l = x; h = x; total += hist[x]; }
+    for (m = 0; m <= n; m++) {
+        uint64_t cnt = 0;
+        double p, pw;
+        if (total) {
+            for (x = l; x <= h; x++)
+                if (orc_transform(x, b, n) < (1u << m)) cnt += hist[x];
+            p = (double)cnt / (double)total;
+        } else {
+            p = 1.0;
+        }
+        pw = p * p; pw = pw * pw; pw = pw * pw;          /* p^8 */
+        for (L = 8; L <= 32; L *= 2) {
+            if (lengths & L) {
+                double bexp = (1.0 / (double)L + (double)n) + ((double)m - (double)n) * pw;
+                if (!have || bexp < best) { have = 1; best = bexp; best_m = m; best_L = L; }
+            }
+            pw = pw * pw;                                /* p^16, p^32 */
+        }
+    }
+    if (have) { params[2] = (uint8_t)best_m; params[3] = (uint8_t)best_L; }
+    if (out_bexp) *out_bexp = best;
+}
+
 void orc_tune(const uint16_t *w, size_t n_elems, uint8_t params[4], uint64_t *out_D, double *out_bexp)
 {
     uint64_t hist[256];
@@ -389,12 +430,13 @@ size_t orc_payload_base_dt(size_t n_elems, uint32_t B, int dtype)
 
 size_t orc_payload_base(size_t n_elems, uint32_t B) { return orc_payload_base_dt(n_elems, B, ORC_BF16); }
 
-/* Worst case: every group anomalous with n = 8 (bf16, fp32: B raw bytes + B
- * bytes of planes) or n = 5 (fp16: B raw bytes + (5+3)B/8 bytes of planes). */
+/* Worst case for any group length: every group anomalous with n = 8 (bf16, fp32:
+ * B raw bytes + B bytes of planes) or n = 5 (fp16: B raw bytes + (5+3)B/8
+ * bytes of planes), and the longest mask (L = 8: B/64 bytes). */
 size_t orc_compress_bound_dt(size_t n_elems, uint32_t B, int dtype)
 {
     size_t nb = orc_num_blocks(n_elems, B);
-    size_t per_block = align16((size_t)B + B / 128u + (size_t)B);
+    size_t per_block = align16((size_t)B + B / 64u + (size_t)B);
     return orc_payload_base_dt(n_elems, B, dtype) + nb * per_block;
 }
 
@@ -414,7 +456,7 @@ static void write_header(uint8_t *out, size_t n_elems, int dtype, uint32_t B, si
     out[0] = 'E'; out[1] = 'N'; out[2] = 'E'; out[3] = 'C';
     put_u16(out + 4, 1);
     out[6] = (uint8_t)dtype;
-    out[7] = ORC_L;
+    out[7] = params[3];
     put_u64(out + 8, (uint64_t)n_elems);
     put_u32(out + 16, B);
     put_u32(out + 20, (uint32_t)nb);
@@ -425,13 +467,13 @@ static void write_header(uint8_t *out, size_t n_elems, int dtype, uint32_t B, si
 }
 
 /* Compresses n_elems values of the given dtype (little-endian words) with
- * data-block size B and parameters (b, n, m, L=16); n is at most the width of
- * the dtype's exponent field.
+ * data-block size B and parameters (b, n, m, L), L one of 8, 16, 32 with
+ * B >= 8 L; n is at most the width of the dtype's exponent field.
  *
  * Per data block (Sec. V-A, V-B; stream layout after the Fig. 4 caption):
  *   payload = raw bytes (sign<<7 | first seven mantissa bits) of the B elements,
  *             element order
- *           | group bit mask, B/128 bytes, group g = bit (g mod 8), LSB first,
+ *           | group bit mask, B/(8L) bytes, group g = bit (g mod 8), LSB first,
  *             of byte (g div 8); 1 = anomalous
  *           | Alg. 2 over the low plane of all B values
  *               bf16, fp32: the low m bits of y                     (m*B/8 bytes)
@@ -439,10 +481,12 @@ static void write_header(uint8_t *out, size_t n_elems, int dtype, uint32_t B, si
  *                     mantissa bits on top, (y mod 2^m) | (w & 7) << m
  *                                                                   ((m+3)*B/8 bytes)
  *           | for each anomalous group in group order, Alg. 2 over the
- *             high n-m bits of its 16 values                        (2(n-m) bytes each)
+ *             high n-m bits of its L values; the zero byte Alg. 2 appends to an
+ *             odd byte count (only L = 8 with odd n-m) is not stored
+ *                                                                   ((n-m)L/8 bytes each)
  *           | zeros up to a multiple of 16
  * The last block is completed with elements that encode as y = 0 and zero raw
- * bits.  Groups are runs of 16 consecutive elements.
+ * bits.  Groups are runs of L consecutive elements.
  * Stream = 64-byte header | (nb+1) u64 block offsets (exclusive prefix sums
  * of payload sizes, last = sum) | zeros to a multiple of 16
  *        | fp32 only: the low 16 bits of every element, element order, little
@@ -460,9 +504,9 @@ static void write_header(uint8_t *out, size_t n_elems, int dtype, uint32_t B, si
 int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const uint8_t params[4],
                     uint8_t *out, size_t capacity, size_t *out_bytes)
 {
-    unsigned b, n, m, a, E, lowbits;
-    size_t nb, base, k, off = 0, G, e;
-    uint8_t *sm, *maskbytes;
+    unsigned b, n, m, a, E, lowbits, L;
+    size_t nb, base, k, off = 0, G, e, rb;
+    uint8_t *sm, *maskbytes, rec[80];
     uint16_t *y, *rest, *tmp;
     int range_error = 0;
 
@@ -470,14 +514,15 @@ int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const
     if (!dtype_ok(dtype)) return ORC_E_DTYPE;
     if (!block_ok(B)) return ORC_E_BLOCK;
     E = orc_exp_bits(dtype);
-    b = params[0]; n = params[1]; m = params[2];
-    if (n < 1 || n > E || m > n || b >= (1u << E) || params[3] != ORC_L) return ORC_E_PARAMS;
+    b = params[0]; n = params[1]; m = params[2]; L = params[3];
+    if (n < 1 || n > E || m > n || b >= (1u << E) || !group_ok(L) || B < 8u * L) return ORC_E_PARAMS;
     if (capacity < orc_compress_bound_dt(n_elems, B, dtype)) return ORC_E_CAPACITY;
     a = n - m;
+    rb = (size_t)a * L / 8u;                 /* bytes of one high record */
     lowbits = m + (dtype == ORC_FP16 ? 3u : 0u);
     nb = orc_num_blocks(n_elems, B);
     base = orc_payload_base_dt(n_elems, B, dtype);
-    G = B / ORC_L;
+    G = B / L;
     memset(out, 0, base);
 
     if (dtype == ORC_FP32) {
@@ -514,7 +559,7 @@ int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const
         memset(maskbytes, 0, G / 8 ? G / 8 : 1);
         for (g = 0; g < G; g++) {
             unsigned o = 0;
-            for (i = 0; i < ORC_L; i++) o |= y[g * ORC_L + i];
+            for (i = 0; i < L; i++) o |= y[g * L + i];
             if (o >= (1u << m)) maskbytes[g / 8] |= (uint8_t)(1u << (g % 8));
         }
         memcpy(p + pos, sm, B); pos += B;
@@ -531,8 +576,10 @@ int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const
         /* high plane: one record per anomalous group */
         for (g = 0; g < G; g++) {
             if (maskbytes[g / 8] & (1u << (g % 8))) {
-                for (i = 0; i < ORC_L; i++) tmp[i] = (uint16_t)(y[g * ORC_L + i] >> m);
-                pos += orc_hh_pack(tmp, ORC_L, (int)a, p + pos);
+                for (i = 0; i < L; i++) tmp[i] = (uint16_t)(y[g * L + i] >> m);
+                orc_hh_pack(tmp, L, (int)a, rec);
+                memcpy(p + pos, rec, rb);
+                pos += rb;
             }
         }
         while (pos % 16) p[pos++] = 0;
@@ -566,7 +613,7 @@ int orc_stream_info_dt(const uint8_t *hdr, uint8_t params[4], uint64_t *n_elems,
     if (hdr[0] != 'E' || hdr[1] != 'N' || hdr[2] != 'E' || hdr[3] != 'C') return ORC_E_FORMAT;
     if (get_u16(hdr + 4) != 1) return ORC_E_FORMAT;
     if (!dtype_ok(hdr[6])) return ORC_E_DTYPE;
-    if (hdr[7] != ORC_L || hdr[27] != orc_exp_bits(hdr[6])) return ORC_E_FORMAT;
+    if (!group_ok(hdr[7]) || hdr[27] != orc_exp_bits(hdr[6])) return ORC_E_FORMAT;
     if (params) { params[0] = hdr[24]; params[1] = hdr[25]; params[2] = hdr[26]; params[3] = hdr[7]; }
     if (n_elems) *n_elems = get_u64(hdr + 8);
     if (B) *B = get_u32(hdr + 16);
@@ -592,9 +639,10 @@ int orc_decompress_dt(const uint8_t *in, size_t in_bytes, void *out, size_t n_el
     uint8_t params[4];
     uint64_t hdr_n, total;
     uint32_t B, status;
-    unsigned b, n, m, a, E, lowbits;
-    size_t nb, base, k, G;
+    unsigned b, n, m, a, E, lowbits, L;
+    size_t nb, base, k, G, rb;
     uint16_t *low, *high, *prefix;
+    uint8_t rec[80];
     const uint8_t *tail16;
     int rc, dtype;
 
@@ -603,18 +651,19 @@ int orc_decompress_dt(const uint8_t *in, size_t in_bytes, void *out, size_t n_el
     if (rc != ORC_OK) return rc;
     if (status != ORC_OK || hdr_n != (uint64_t)n_elems || !block_ok(B)) return ORC_E_FORMAT;
     E = orc_exp_bits(dtype);
-    b = params[0]; n = params[1]; m = params[2];
-    if (n < 1 || n > E || m > n) return ORC_E_FORMAT;
+    b = params[0]; n = params[1]; m = params[2]; L = params[3];
+    if (n < 1 || n > E || m > n || B < 8u * L) return ORC_E_FORMAT;
     a = n - m;
+    rb = (size_t)a * L / 8u;
     lowbits = m + (dtype == ORC_FP16 ? 3u : 0u);
     nb = orc_num_blocks(n_elems, B);
     base = orc_payload_base_dt(n_elems, B, dtype);
     if (get_u32(in + 20) != (uint32_t)nb || total > in_bytes || total < base) return ORC_E_FORMAT;
-    G = B / ORC_L;
+    G = B / L;
     tail16 = in + orc_table_end(n_elems, B);
 
     low = (uint16_t *)malloc(B * sizeof(uint16_t));
-    high = (uint16_t *)malloc(ORC_L * sizeof(uint16_t));
+    high = (uint16_t *)malloc(L * sizeof(uint16_t));
     prefix = (uint16_t *)malloc((G + 1) * sizeof(uint16_t));
 
     for (k = 0; k < nb; k++) {
@@ -633,18 +682,22 @@ int orc_decompress_dt(const uint8_t *in, size_t in_bytes, void *out, size_t n_el
         else for (i = 0; i < B; i++) low[i] = 0;
         for (g = 0; g < G; g++) {
             int anomalous = (maskbytes[g / 8] >> (g % 8)) & 1u;
-            if (anomalous) orc_hh_unpack(highplane + (size_t)2 * a * prefix[g], ORC_L, (int)a, high);
-            for (i = 0; i < ORC_L; i++) {
-                size_t e = k * (size_t)B + g * ORC_L + i;
+            if (anomalous) {
+                memset(rec, 0, sizeof rec);             /* the pad byte Alg. 2 expects after an odd count */
+                memcpy(rec, highplane + rb * prefix[g], rb);
+                orc_hh_unpack(rec, L, (int)a, high);
+            }
+            for (i = 0; i < L; i++) {
+                size_t e = k * (size_t)B + g * L + i;
                 unsigned yv, x, s, r = 0;
                 uint32_t w;
                 if (e >= n_elems) break;
-                yv = low[g * ORC_L + i] & ((1u << m) - 1u);
-                if (dtype == ORC_FP16) r = low[g * ORC_L + i] >> m;
+                yv = low[g * L + i] & ((1u << m) - 1u);
+                if (dtype == ORC_FP16) r = low[g * L + i] >> m;
                 if (dtype == ORC_FP32) r = get_u16(tail16 + 2 * e);
                 if (anomalous) yv |= (unsigned)high[i] << m;
                 x = orc_inverse_transform_e(yv, b, n, E);
-                s = sm[g * ORC_L + i];
+                s = sm[g * L + i];
                 w = join_elem(x, s, r, dtype);
                 if (dtype == ORC_FP32) ((uint32_t *)out)[e] = w;
                 else ((uint16_t *)out)[e] = (uint16_t)w;

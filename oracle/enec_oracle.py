@@ -85,6 +85,8 @@ def lib():
         L.orc_histogram_dt.argtypes = [C.c_void_p, C.c_size_t, C.c_int, u64p]
         L.orc_tune_hist_e.restype = None
         L.orc_tune_hist_e.argtypes = [u64p, C.c_uint, u8p, u64p, C.POINTER(C.c_double)]
+        L.orc_tune_hist_groups.restype = None
+        L.orc_tune_hist_groups.argtypes = [u64p, C.c_uint, C.c_uint, u8p, u64p, C.POINTER(C.c_double)]
         L.orc_table_end.restype = C.c_size_t
         L.orc_table_end.argtypes = [C.c_size_t, C.c_uint32]
         L.orc_payload_base_dt.restype = C.c_size_t
@@ -184,9 +186,24 @@ def tune_hist(hist, E: int = 8):
     return tuple(int(v) for v in params), int(D.value), float(bexp.value)
 
 
-def tune(w, dtype: int = BF16):
-    """-> (b, n, m, L) for a tensor of bit patterns."""
-    return tune_hist(histogram(w, dtype), exp_bits(dtype))[0]
+def tune_hist_groups(hist, E: int = 8, lengths=(8, 16, 32)):
+    """Eq. 4 with the group length searched jointly with m -> ((b, n, m, L), D_integer, B_exp)"""
+    hist = np.ascontiguousarray(hist, dtype=np.uint64)
+    params = np.zeros(4, dtype=np.uint8)
+    D = C.c_uint64(0)
+    bexp = C.c_double(0)
+    mask = 0
+    for v in lengths:
+        mask |= int(v)
+    lib().orc_tune_hist_groups(_p(hist, C.c_uint64), E, mask, _p(params, C.c_uint8), C.byref(D), C.byref(bexp))
+    return tuple(int(v) for v in params), int(D.value), float(bexp.value)
+
+
+def tune(w, dtype: int = BF16, lengths=None):
+    """-> (b, n, m, L) for a tensor of bit patterns; L = 16 unless a set of group lengths is given."""
+    if lengths is None:
+        return tune_hist(histogram(w, dtype), exp_bits(dtype))[0]
+    return tune_hist_groups(histogram(w, dtype), exp_bits(dtype), lengths)[0]
 
 
 def default_block(n_elems: int) -> int:

@@ -23,7 +23,7 @@ from __future__ import annotations
 import struct
 from functools import lru_cache
 
-L = 16
+L = 16              # default group length
 HEADER = 64
 
 
@@ -152,6 +152,24 @@ def tune_hist(hist, E=8):
     return (b, n, best_m[1], L), D, best_m[0]
 
 
+def tune_hist_groups(hist, E=8, lengths=(8, 16, 32)):
+    """Eq. 4 over m and the group length together; ties: smaller m, then smaller length."""
+    (b, n, _, _), D, _ = tune_hist(hist, E)
+    occupied = [x for x in range(256) if hist[x]]
+    total = sum(int(hist[x]) for x in occupied)
+    best = None
+    for m in range(0, n + 1):
+        p = sum(int(hist[x]) for x in occupied if transform(x, b, n) < (1 << m)) / total if total else 1.0
+        for Lg in sorted(lengths):
+            q = p
+            for _ in range(Lg.bit_length() - 1):       # p^Lg by squarings
+                q = q * q
+            bexp = (1.0 / Lg + float(n)) + (float(m) - float(n)) * q
+            if best is None or bexp < best[0]:
+                best = (bexp, m, Lg)
+    return (b, n, best[1], best[2]), D, best[0]
+
+
 def tune(words, dtype=0):
     hist = [0] * 256
     for w in words:
@@ -169,10 +187,11 @@ def _align16(v):
 def compress(words, params, B, dtype=0):
     """-> (range_ok, bytes).  fp16: the three left-over mantissa bits sit on top of the low
     m bits in the low plane; fp32: the sixteen left-over bits of all elements follow the table."""
-    b, n, m, Lp = params
+    b, n, m, L = params
     E = FIELDS[dtype][0]
-    assert Lp == L and 1 <= n <= E and 0 <= m <= n
+    assert L in (8, 16, 32) and B >= 8 * L and 1 <= n <= E and 0 <= m <= n
     a = n - m
+    rb = a * L // 8                      # a record without the pad byte Alg. 2 adds to an odd count
     words = [int(w) for w in words]
     N = len(words)
     nb = (N + B - 1) // B
@@ -196,7 +215,7 @@ def compress(words, params, B, dtype=0):
             low = hh_pack([v % (1 << m) + r * (1 << m) for v, r in zip(y, rest)], m + 3)
         else:
             low = hh_pack([v & ((1 << m) - 1) for v in y], m) if m else b""
-        high = b"".join(hh_pack([v >> m for v in y[g * L:(g + 1) * L]], a)
+        high = b"".join(hh_pack([v >> m for v in y[g * L:(g + 1) * L]], a)[:rb]
                         for g in range(G) if anomalous[g])
         p = bytes(sm) + bytes(mask) + low + high
         p += bytes(_align16(len(p)) - len(p))
@@ -220,11 +239,12 @@ def compress(words, params, B, dtype=0):
 
 def decompress(stream, N):
     stream = bytes(stream)
-    magic, ver, dtype, Lp, n_elems, B, nb, b, n, m, ebits, status, total = struct.unpack_from(
+    magic, ver, dtype, L, n_elems, B, nb, b, n, m, ebits, status, total = struct.unpack_from(
         "<4sHBBQIIBBBBIQ", stream, 0)
-    assert magic == b"ENEC" and ver == 1 and dtype in FIELDS and Lp == L and ebits == FIELDS[dtype][0]
+    assert magic == b"ENEC" and ver == 1 and dtype in FIELDS and L in (8, 16, 32) and ebits == FIELDS[dtype][0]
     assert n_elems == N and status == 0
     a = n - m
+    rb = a * L // 8
     G = B // L
     tail_at = _align16(HEADER + 8 * (nb + 1))
     base = tail_at + (_align16(2 * N) if dtype == 2 else 0)
@@ -241,7 +261,7 @@ def decompress(stream, N):
         seen = 0                                   # running count of mask bits
         for g in range(G):
             bit = (mask[g // 8] >> (g % 8)) & 1
-            high = hh_unpack(highplane[2 * a * seen:2 * a * (seen + 1)], L, a) if bit else [0] * L
+            high = hh_unpack(highplane[rb * seen:rb * (seen + 1)] + b"\0", L, a) if bit else [0] * L
             seen += bit
             for i in range(L):
                 e = k * B + g * L + i

@@ -200,8 +200,9 @@ size_t enec_compress_bound(size_t n_elems, int dtype, uint32_t block_size)
     if (!dtype_ok(dtype)) return 0;
     const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
     if (!block_ok(B)) return 0;
-    // worst case: every group anomalous at full exponent width (fp16: (5 + 3) plane bits)
-    return payload_base(n_elems, B, dtype) + num_blocks(n_elems, B) * align16((size_t)B + B / 128 + B);
+    // worst case for any group length: every group anomalous at full exponent width (fp16: (5 + 3)
+    // plane bits) and the longest mask (L = 8)
+    return payload_base(n_elems, B, dtype) + num_blocks(n_elems, B) * align16((size_t)B + B / 64 + B);
 }
 
 size_t enec_workspace_bytes(size_t n_elems, uint32_t block_size)

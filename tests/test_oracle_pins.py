@@ -316,7 +316,10 @@ def test_closed_form_sizes(oracle):
         assert rc == 0 and s.size == oracle.payload_base(w.size, B) + 4 * (B + B // 128 + B)
         rc, d = oracle.decompress(s, w.size)
         assert rc == 0 and (d == w).all()
-    assert s.size == oracle.compress_bound(w.size, B)
+    # the bound holds for every group length Eq. 4 may choose and is met by the shortest one (longest mask)
+    assert s.size < oracle.compress_bound(w.size, B)
+    rc, s = oracle.compress(w, (127, 8, 3, 8), B)
+    assert rc == 0 and s.size == oracle.payload_base(w.size, B) + 4 * (B + B // 64 + B) == oracle.compress_bound(w.size, B)
 
 
 def test_bits_per_element_accounting_matches_paper(oracle):
@@ -441,7 +444,7 @@ def test_error_paths(oracle):
     assert oracle.compress(w, (122, 6, 3, 16), 3000)[0] == oracle.E_BLOCK
     assert oracle.compress(w, (122, 9, 3, 16), 2048)[0] == oracle.E_PARAMS
     assert oracle.compress(w, (122, 6, 7, 16), 2048)[0] == oracle.E_PARAMS
-    assert oracle.compress(w, (122, 6, 3, 8), 2048)[0] == oracle.E_PARAMS
+    assert oracle.compress(w, (122, 6, 3, 12), 2048)[0] == oracle.E_PARAMS      # group lengths are 8, 16, 32
     assert oracle.compress(w, (122, 6, 3, 16), 2048, capacity=1000)[0] == oracle.E_CAPACITY
     # window [b-2^(n-1)+1, b+2^(n-1)] = [119, 126] does not hold these exponents
     rc, s = oracle.compress(w, (122, 3, 1, 16), 2048)
