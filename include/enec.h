@@ -12,7 +12,7 @@
  *   bf16 word -> exponent x (8 bit) and a raw sign+mantissa byte       [Sec. IV-B; Sec. V-A step 1]
  *   fp16 / fp32 are split the same way, only exponents are coded        [Alg. 1 input; Sec. VI-B]
  *   y = (b - x) mod 2^n, the branch-free integer transformation        [Sec. V-C; Eq. 2]
- *   per group of L = 16 consecutive elements: OR of the y; the group is
+ *   per group of L consecutive elements (16 in the paper): OR of the y; the group is
  *   stored with m bits per element if OR < 2^m, else with n bits       [Sec. V-B]
  *   fixed-length fields are packed with hierarchical halving
  *   bit-packing with byte normalisation                                 [Sec. V-B, Alg. 2]
@@ -23,7 +23,7 @@
  *   parameters (b, n, m, L) from the exponent histogram                 [Sec. V-E, Eq. 1-4]
  *
  * Stream format, version 1 (all integers little-endian):
- *   0   "ENEC"                 4   u16 version = 1      6  u8 dtype (enec_dtype) 7  u8 L (= 16)
+ *   0   "ENEC"                 4   u16 version = 1      6  u8 dtype (enec_dtype) 7  u8 L (8, 16, 32)
  *   8   u64 n_elems            16  u32 block_size B     20 u32 n_blocks nb = ceil(n_elems / B)
  *   24  u8 b   25 u8 n   26 u8 m   27 u8 exponent bits (8; fp16: 5)
  *   28  u32 status (ENEC_OK or ENEC_E_RANGE)            32 u64 total_bytes (0 if status != OK)
@@ -36,11 +36,12 @@
  *       bf16 word and are coded as such.)
  *   per data block, at payload base + offset[k] (always 16-byte aligned):
  *       B bytes            sign<<7 | first seven mantissa bits of every element, element order
- *       B/128 bytes        group mask: group g is bit (g mod 8), LSB first, of byte (g div 8);
- *                          1 = stored with n bits
+ *       B/(8L) bytes       group mask: group g (elements gL .. gL+L-1) is bit (g mod 8), LSB first,
+ *                          of byte (g div 8); 1 = stored with n bits
  *       m*B/8 bytes        Alg. 2 over (y mod 2^m) of all B elements; fp16: (m+3)*B/8 bytes, Alg. 2
  *                          over (y mod 2^m) | (last three mantissa bits) << m
- *       2(n-m) bytes per masked group, in group order: Alg. 2 over (y >> m) of its 16 elements
+ *       (n-m)L/8 bytes per masked group, in group order: Alg. 2 over (y >> m) of its L elements
+ *                          (without the zero byte Alg. 2 appends to an odd byte count)
  *       zero bytes up to a multiple of 16
  *   The last data block is completed with elements that encode as y = 0 and zero sign and
  *   mantissa bits.
@@ -60,7 +61,8 @@ typedef enum {
     ENEC_E_ARG = 1,       /* null / misaligned pointer, size out of range */
     ENEC_E_DTYPE = 2,     /* not one of enec_dtype */
     ENEC_E_BLOCK = 3,     /* block_size not a power of two in [2048, 32768] */
-    ENEC_E_PARAMS = 4,    /* need 1 <= n <= E, 0 <= m <= n, b < 2^E, L == 16 (E = exponent bits: 8, fp16: 5) */
+    ENEC_E_PARAMS = 4,    /* need 1 <= n <= E, 0 <= m <= n, b < 2^E (E = exponent bits: 8, fp16: 5), L in {8, 16, 32}
+                             with 128 L <= block_size <= 2048 L */
     ENEC_E_CAPACITY = 5,  /* out_capacity < enec_compress_bound() or workspace too small */
     ENEC_E_RANGE = 6,     /* an exponent lies outside [b - 2^(n-1) + 1, b + 2^(n-1)] while n < E */
     ENEC_E_FORMAT = 7,    /* not an ENEC stream, or header does not match the call */
@@ -72,7 +74,7 @@ typedef enum {
 typedef enum { ENEC_BF16 = 0, ENEC_FP16 = 1, ENEC_FP32 = 2 } enec_dtype;
 
 /* Codec parameters [Sec. V-E; Table VI]: mapping centre b, stored width n, threshold width m,
- * group length L (must be 16). */
+ * group length L (8, 16 or 32; the tuners return 16 unless asked otherwise). */
 typedef struct { uint8_t b, n, m, L; } enec_params;
 
 #define ENEC_HEADER_BYTES 64u
@@ -186,6 +188,13 @@ int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params,
 /* Host-only search of Sec. V-E phases 2-3 on a given 256-bin exponent histogram (HOST); dtype
  * fixes the cap of Eq. 1's width (the exponent field: 8 bits, fp16: 5). */
 int enec_tune_histogram(const uint64_t *histogram, int dtype, enec_params *params);
+
+/* The same search with the group length L chosen together with m, as Eq. 4 states it [Sec. V-E phase 3]:
+ * group_lengths is the OR of the candidate lengths (8, 16, 32).  The paper's hardware forces L >= 16 and
+ * finds 16 optimal throughout [Sec. VI-D], which is what enec_tune and enec_tune_histogram return;
+ * without that rule shorter groups often win.  A tuple with L = 32 needs block_size >= 4096, one with
+ * L = 8 block_size <= 16384 (ENEC_E_PARAMS from enec_compress otherwise). */
+int enec_tune_histogram_groups(const uint64_t *histogram, int dtype, uint32_t group_lengths, enec_params *params);
 
 /* Parse a HOST copy of a stream's first 64 bytes.  Any output pointer may be NULL.
  * Returns ENEC_E_FORMAT if it is not a version-1 ENEC header. */

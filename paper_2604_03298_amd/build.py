@@ -1,7 +1,7 @@
 """Builds libenec.so (HIP, gfx950) in-tree with hipcc.  `python -m paper_2604_03298_amd.build`.
 
-The host code (csrc/enec_api.hip) and the six kernel tables (csrc/enec_kernels.hip, once per element
-format and direction) are compiled side by side into _build/*.o and linked into libenec.so.
+The host code (csrc/enec_api.hip) and the 18 kernel tables (csrc/enec_kernels.hip, once per element
+format, group length and direction) are compiled side by side into _build/*.o and linked into libenec.so.
 """
 from __future__ import annotations
 
@@ -24,9 +24,11 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950",
 
 def _units():
     units = [("enec_api.o", [SOURCES[0]])]
-    for dt in (0, 1, 2):
-        for direction in (0, 1):
-            units.append((f"enec_kernels_dt{dt}_dir{direction}.o", [f"-DENEC_DT={dt}", f"-DENEC_DIR={direction}", SOURCES[1]]))
+    for lpg in (2, 1, 4):           # lanes per group: group lengths 16, 8, 32
+        for dt in (0, 2, 1):
+            for direction in (0, 1):
+                units.append((f"enec_kernels_dt{dt}_lpg{lpg}_dir{direction}.o",
+                              [f"-DENEC_DT={dt}", f"-DENEC_LPG={lpg}", f"-DENEC_DIR={direction}", SOURCES[1]]))
     return units
 
 
@@ -44,7 +46,7 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
         return os.path.join(OBJ, name)
 
-    workers = max(1, min(7, os.cpu_count() or 1))
+    workers = max(1, min(8, os.cpu_count() or 1))
     with ThreadPoolExecutor(workers) as pool:
         objects = list(pool.map(compile_one, _units()))
     cmd = ["hipcc", "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB] + objects

@@ -12,12 +12,12 @@ namespace enec {
 
 // kernels that exist once: the header-only stream of an empty tensor, zero fill, plain copy
 __global__ void compress_empty_kernel(uint8_t *out, uint64_t *out_bytes, uint32_t B, uint32_t b, uint32_t n, uint32_t m,
-                                      uint32_t dtype)
+                                      uint32_t dtype, uint32_t L)
 {
     if (threadIdx.x != 0) return;
     uint32_t *h = reinterpret_cast<uint32_t *>(out);
     h[0] = 0x43454E45u;
-    h[1] = 1u | (dtype << 16) | (16u << 24);
+    h[1] = 1u | (dtype << 16) | (L << 24);
     h[2] = h[3] = 0;
     h[4] = B; h[5] = 0;
     h[6] = b | (n << 8) | (m << 16) | (exponent_bits((int)dtype) << 24);
@@ -73,18 +73,28 @@ inline size_t payload_base(size_t n, uint32_t B, int dtype)
 }
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
-inline CompressFn pick_compress(int m, int a, int dtype)
+inline bool group_ok(unsigned L) { return L == 8 || L == 16 || L == 32; }
+
+inline CompressFn pick_compress(int m, int a, int dtype, unsigned L)
 {
-    if (dtype == ENEC_FP16) return pick_compress_fp16(m, a);
-    if (dtype == ENEC_FP32) return pick_compress_fp32(m, a);
-    return pick_compress_bf16(m, a);
+#define ENEC_ROW(dt) (L == 8 ? pick_compress_##dt##_lpg1(m, a) : L == 16 ? pick_compress_##dt##_lpg2(m, a) : pick_compress_##dt##_lpg4(m, a))
+    if (dtype == ENEC_FP16) return ENEC_ROW(dt1);
+    if (dtype == ENEC_FP32) return ENEC_ROW(dt2);
+    return ENEC_ROW(dt0);
+#undef ENEC_ROW
 }
-inline DecompressFn pick_decompress(int m, int a, int dtype)
+inline DecompressFn pick_decompress(int m, int a, int dtype, unsigned L)
 {
-    if (dtype == ENEC_FP16) return pick_decompress_fp16(m, a);
-    if (dtype == ENEC_FP32) return pick_decompress_fp32(m, a);
-    return pick_decompress_bf16(m, a);
+#define ENEC_ROW(dt) (L == 8 ? pick_decompress_##dt##_lpg1(m, a) : L == 16 ? pick_decompress_##dt##_lpg2(m, a) : pick_decompress_##dt##_lpg4(m, a))
+    if (dtype == ENEC_FP16) return ENEC_ROW(dt1);
+    if (dtype == ENEC_FP32) return ENEC_ROW(dt2);
+    return ENEC_ROW(dt0);
+#undef ENEC_ROW
 }
+
+// A group length needs whole 16-byte vectors of mask per block (B >= 128 L) and at most 64 mask
+// words per block (the kernels scan them with one wave: B / L <= 2048).
+inline bool group_fits_block(unsigned L, uint32_t B) { return B >= 128u * L && B / L <= 2048u; }
 
 // how the kernels subtract exponents in byte lanes: 0 = plain subtract (no byte can borrow for
 // an exponent inside the window), 1 = borrow-safe subtract, the window is the whole exponent
@@ -153,7 +163,7 @@ int parse_header(const void *host_header, Header *h)
     const uint8_t *p = static_cast<const uint8_t *>(host_header);
     if (std::memcmp(p, "ENEC", 4) != 0) return ENEC_E_FORMAT;
     uint16_t ver; std::memcpy(&ver, p + 4, 2);
-    if (ver != 1 || p[7] != 16) return ENEC_E_FORMAT;
+    if (ver != 1 || !group_ok(p[7])) return ENEC_E_FORMAT;
     h->dtype = p[6];
     if (!dtype_ok(h->dtype)) return ENEC_E_DTYPE;
     if (p[27] != exp_bits(h->dtype)) return ENEC_E_FORMAT;
@@ -267,6 +277,42 @@ int enec_tune_histogram(const uint64_t *hist, int dtype, enec_params *params)
     return ENEC_OK;
 }
 
+int enec_tune_histogram_groups(const uint64_t *hist, int dtype, uint32_t group_lengths, enec_params *params)
+{
+    if (!(group_lengths & (8u | 16u | 32u)) || (group_lengths & ~(8u | 16u | 32u))) return ENEC_E_PARAMS;
+    int rc = enec_tune_histogram(hist, dtype, params);            // (b, n) of phase 2
+    if (rc != ENEC_OK) return rc;
+    int l = -1, h = -1;
+    uint64_t total = 0;
+    for (int x = 0; x < 256; ++x)
+        if (hist[x]) { if (l < 0) l = x; h = x; total += hist[x]; }
+    // phase 3 as Eq. 4 states it: m and L together; p^L by squarings; ties to the smaller m, then the smaller L
+    const unsigned n = params->n, b = params->b, wrap = (1u << n) - 1u;
+    double bestE = 0.0;
+    unsigned bestM = 0, bestL = 0;
+    bool have = false;
+    for (unsigned m = 0; m <= n; ++m) {
+        double pm = 1.0;
+        if (total) {
+            uint64_t cnt = 0;
+            for (int x = l; x <= h; ++x)
+                if (((b - (unsigned)x) & wrap) < (1u << m)) cnt += hist[x];
+            pm = (double)cnt / (double)total;
+        }
+        double pw = pm * pm; pw = pw * pw; pw = pw * pw;               // p^8
+        for (unsigned L = 8; L <= 32; L *= 2) {
+            if (group_lengths & L) {
+                const double e = (1.0 / (double)L + (double)n) + ((double)m - (double)n) * pw;
+                if (!have || e < bestE) { have = true; bestE = e; bestM = m; bestL = L; }
+            }
+            pw = pw * pw;                                              // p^16, p^32
+        }
+    }
+    params->m = (uint8_t)bestM;
+    params->L = (uint8_t)bestL;
+    return ENEC_OK;
+}
+
 int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params, uint64_t *histogram,
               void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -329,7 +375,8 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
             if (rc != ENEC_OK) return rc;
         }
         const enec_params &prm = prep[i].prm;
-        if (prm.n < 1 || prm.n > exp_bits(dtype) || prm.m > prm.n || prm.b >= (1u << exp_bits(dtype)) || prm.L != 16)
+        if (prm.n < 1 || prm.n > exp_bits(dtype) || prm.m > prm.n || prm.b >= (1u << exp_bits(dtype)) ||
+            !group_ok(prm.L) || !group_fits_block(prm.L, prep[i].B))
             return ENEC_E_PARAMS;
         if (it.out_capacity < enec_compress_bound(it.n_elems, dtype, prep[i].B)) return ENEC_E_CAPACITY;
         if (it.out_bytes && !device_accessible(it.out_bytes)) return ENEC_E_ARG;
@@ -343,7 +390,7 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         if (prep[i].nb == 0) {
             compress_empty_kernel<<<1, 64, 0, s>>>(static_cast<uint8_t *>(items[i].out), items[i].out_bytes,
                                                    prep[i].B, prep[i].prm.b, prep[i].prm.n, prep[i].prm.m,
-                                                   (uint32_t)dtype);
+                                                   (uint32_t)dtype, prep[i].prm.L);
             done[i] = 1;
             continue;
         }
@@ -356,7 +403,7 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         size_t word = acc_words, acc = 0;   // scan words handed out to this launch (tags make reuse between launches safe)
         for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
             if (done[j] || prep[j].nb == 0 || prep[j].B != a.B || prep[j].prm.m != prep[i].prm.m ||
-                prep[j].prm.n != prep[i].prm.n)
+                prep[j].prm.n != prep[i].prm.n || prep[j].prm.L != prep[i].prm.L)
                 continue;
             CompressItem &c = a.item[a.n_items++];
             c.in = static_cast<const uint16_t *>(items[j].in);
@@ -378,11 +425,11 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
             a.total += c.nb;
             done[j] = 1;
         }
-        CompressFn fn = pick_compress(prep[i].prm.m, prep[i].prm.n - prep[i].prm.m, dtype);
+        CompressFn fn = pick_compress(prep[i].prm.m, prep[i].prm.n - prep[i].prm.m, dtype, prep[i].prm.L);
         if (!fn) return ENEC_E_PARAMS;
         const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
         const size_t plane_bits = prep[i].prm.n + (dtype == ENEC_FP16 ? 3 : 0);
-        const size_t lds = 2 * ((size_t)a.B / 128 + plane_bits * a.B / 8);               // two images of the packed part
+        const size_t lds = 2 * ((size_t)a.B / (8 * prep[i].prm.L) + plane_bits * a.B / 8);   // two images of the packed part
         const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_COMPRESS_WGS_PER_CU");
         if (resident == 0) return ENEC_E_HIP;
         const unsigned grid = a.total < resident ? a.total : resident;
@@ -424,7 +471,7 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
         if (rc != ENEC_OK) return rc;
         if (h.status != ENEC_OK || h.n_elems != it.n_elems || !block_ok(h.B) || it.n_elems > MAX_ELEMS ||
             h.nb != num_blocks(it.n_elems, h.B) || h.prm.n < 1 || h.prm.n > exp_bits(h.dtype) || h.prm.m > h.prm.n ||
-            h.prm.b >= (1u << exp_bits(h.dtype)) ||
+            h.prm.b >= (1u << exp_bits(h.dtype)) || !group_fits_block(h.prm.L, h.B) ||
             h.total < payload_base(it.n_elems, h.B, h.dtype) || h.total > it.in_bytes)
             return ENEC_E_FORMAT;
     }
@@ -440,7 +487,7 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
         for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
             const Header &h = hdr[j];
             if (done[j] || h.nb == 0 || h.B != a.B || h.prm.m != hdr[i].prm.m || h.prm.n != hdr[i].prm.n ||
-                h.dtype != hdr[i].dtype)
+                h.dtype != hdr[i].dtype || h.prm.L != hdr[i].prm.L)
                 continue;
             DecompressItem &c = a.item[a.n_items++];
             c.in = static_cast<const uint8_t *>(items[j].in);
@@ -457,11 +504,11 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
             a.total += c.nb;
             done[j] = 1;
         }
-        DecompressFn fn = pick_decompress(hdr[i].prm.m, hdr[i].prm.n - hdr[i].prm.m, hdr[i].dtype);
+        DecompressFn fn = pick_decompress(hdr[i].prm.m, hdr[i].prm.n - hdr[i].prm.m, hdr[i].dtype, hdr[i].prm.L);
         if (!fn) return ENEC_E_FORMAT;
         const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
         const size_t plane_bits = hdr[i].prm.n + (hdr[i].dtype == ENEC_FP16 ? 3 : 0);
-        const size_t lds = 2 * ((size_t)a.B / 128 + plane_bits * a.B / 8);              // two images of the packed part
+        const size_t lds = 2 * ((size_t)a.B / (8 * hdr[i].prm.L) + plane_bits * a.B / 8);   // two images of the packed part
         const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_DECOMPRESS_WGS_PER_CU");
         if (resident == 0) return ENEC_E_HIP;
         const unsigned grid = a.total < resident ? a.total : resident;

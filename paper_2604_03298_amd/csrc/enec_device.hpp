@@ -9,7 +9,8 @@
 //   * packs its 8 columns in registers with byte-lane SIMD-within-a-register
 //     arithmetic (4 columns per 32-bit register),
 //   * owns half of a group of 16 consecutive elements per row; the two halves sit in
-//     adjacent lanes and are combined with one DPP operation.
+//     adjacent lanes and are combined with one DPP operation.  (Template parameter LPG =
+//     lanes per group: 1, 2 or 4 for group lengths 8, 16, 32; Eq. 4 searches the length.)
 // A workgroup has B/64 threads (256 for the default B = 16384) and handles one block.
 //
 // Element formats (template parameter DT).  Only the exponent field is coded (Sec. VI-B);
@@ -145,6 +146,25 @@ __device__ __forceinline__ uint32_t compact_even_bits(uint64_t x)
     x = (x | (x >> 8)) & 0x0000FFFF0000FFFFull;
     x = (x | (x >> 16)) & 0x00000000FFFFFFFFull;
     return (uint32_t)x;
+}
+
+// keep every fourth bit of x, packed into 16 bits
+__device__ __forceinline__ uint32_t compact_fourth_bits(uint64_t x)
+{
+    x &= 0x1111111111111111ull;
+    x = (x | (x >> 3)) & 0x0303030303030303ull;
+    x = (x | (x >> 6)) & 0x000F000F000F000Full;
+    x = (x | (x >> 12)) & 0x000000FF000000FFull;
+    x = (x | (x >> 24)) & 0x000000000000FFFFull;
+    return (uint32_t)x;
+}
+
+// OR over the four lanes of a quad, two DPP moves
+__device__ __forceinline__ uint32_t quad_or(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false);
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, false);
+    return v;
 }
 
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane)
@@ -344,10 +364,12 @@ __device__ __forceinline__ void load_block_rows(const CompressItem &p, uint32_t 
 // compression: split, transform, group test, packing, inter-block scan, store
 // (Sec. V-A compression path; Sec. V-B; Sec. V-C; Fig. 4)
 // ---------------------------------------------------------------------------------
-template <int M, int A, int DT>
+template <int M, int A, int DT, int LPG>
 __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(const CompressArgs p)
 {
     constexpr int N = M + A;
+    constexpr int LOG_LPG = LPG == 4 ? 2 : LPG - 1;
+    constexpr uint32_t RB = A * LPG;                     // bytes of one high record: (n - m) L / 8
     constexpr int LM = low_plane_bits(M, DT);            // width of the low plane
     constexpr uint32_t NMASK = ((1u << N) - 1u) * 0x01010101u;
     constexpr uint32_t LMASK = ((1u << M) - 1u) * 0x01010101u;
@@ -371,8 +393,9 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
     const uint32_t acc_tid = blockDim.x > 64u ? 64u : 0u;   // the lane that talks to the group accumulators
-    const uint32_t img_bytes = (B >> 7) + (((uint32_t)(LM + A) * B) >> 3);
-    const uint32_t fixed = B + (B >> 7) + ((LM * B) >> 3);
+    const uint32_t mask_bytes = (B >> 6) >> LOG_LPG;                  // B / (8 L)
+    const uint32_t img_bytes = mask_bytes + (((uint32_t)(LM + A) * B) >> 3);
+    const uint32_t fixed = B + mask_bytes + ((LM * B) >> 3);
 
     // ---- control record of this workgroup's class (thread 0) ---------------------------
     const uint32_t home = blockIdx.x % p.ncls;
@@ -474,11 +497,11 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             for (int t = 0; t < 8; ++t)
                 *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SMp[t][0], SMp[t][1]);
         }
-        if (tid < (B >> 11))
-            *reinterpret_cast<uint4 *>(dst + B + 16u * tid) = *reinterpret_cast<const uint4 *>(img + 16u * tid);
+        for (uint32_t v = tid; v < (mask_bytes >> 4); v += blockDim.x)
+            *reinterpret_cast<uint4 *>(dst + B + 16u * v) = *reinterpret_cast<const uint4 *>(img + 16u * v);
         if (LM > 0) {
-            const uint8_t *ilow = img + (B >> 7);
-            uint8_t *dlow = dst + B + (B >> 7);
+            const uint8_t *ilow = img + mask_bytes;
+            uint8_t *dlow = dst + B + mask_bytes;
             const uint32_t T2 = (LM * B) >> 4;                // half of the plane's length
             for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
                 const uint2 a = *reinterpret_cast<const uint2 *>(ilow + 8u * v);
@@ -492,9 +515,9 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             }
         }
         if (A > 0) {
-            const uint8_t *ihigh = img + (B >> 7) + ((LM * B) >> 3);
+            const uint8_t *ihigh = img + mask_bytes + ((LM * B) >> 3);
             uint8_t *dhigh = dst + fixed;
-            const uint32_t hbytes = 2u * A * cnt;             // even
+            const uint32_t hbytes = RB * cnt;
             for (uint32_t v = tid; 16u * v < hbytes; v += blockDim.x) {
                 uint4 o = *reinterpret_cast<const uint4 *>(ihigh + 16u * v);
                 uint32_t w[4] = {o.x, o.y, o.z, o.w};
@@ -502,7 +525,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                 for (int i = 0; i < 4; ++i) {                 // zero the padding behind the last record
                     const uint32_t at = 16u * v + 4u * i;
                     if (at >= hbytes) w[i] = 0;
-                    else if (at + 2 >= hbytes) w[i] &= 0xFFFFu;
+                    else if (at + 4u > hbytes) w[i] &= (1u << (8u * (hbytes - at))) - 1u;
                 }
                 *reinterpret_cast<uint4 *>(dhigh + 16u * v) = make_uint4(w[0], w[1], w[2], w[3]);
             }
@@ -519,7 +542,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                 if (((uint64_t)(it.nb + 1u) & 1ull)) table[it.nb + 1u] = 0;   // pad up to the payload base
                 uint32_t *h = reinterpret_cast<uint32_t *>(it.out);
                 h[0] = 0x43454E45u;                              // "ENEC"
-                h[1] = 1u | ((uint32_t)DT << 16) | (16u << 24);  // version, dtype, L
+                h[1] = 1u | ((uint32_t)DT << 16) | ((8u * LPG) << 24);   // version, dtype, L
                 h[2] = (uint32_t)it.n_elems; h[3] = (uint32_t)(it.n_elems >> 32);
                 h[4] = B; h[5] = it.nb;
                 h[6] = it.b | ((uint32_t)N << 8) | ((uint32_t)M << 16) | (exponent_bits(DT) << 24);
@@ -537,7 +560,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         ENEC_TP(0);
         uint8_t *img = smem + slot * img_bytes;
         uint32_t *img_maskw = reinterpret_cast<uint32_t *>(img);
-        uint8_t *img_low = img + (B >> 7);
+        uint8_t *img_low = img + mask_bytes;
         uint8_t *img_high = img_low + (((size_t)LM * B) >> 3);
 
         // wave 0 reads the scan state for the block stored in this iteration now and uses it
@@ -562,7 +585,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         const bool draw_now = tid == 0 && p.lookahead && drawing;
         if (draw_now) next_raw = atomicAdd(ctl + zero, 1u);
 
-        uint32_t SMc[8][2], HI[8][2], accP[MP][2], mw[8];
+        uint32_t SMc[8][2], HI[8][2], accP[MP][2], mw[8], mw_hi[LPG == 1 ? 8 : 1];
         uint32_t err_acc = 0;
         bool bad = false;
 #pragma unroll
@@ -634,20 +657,44 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                         }
                 }
             }
-            gor |= swap_pair(gor);
-            mw[t] = compact_even_bits(__builtin_amdgcn_ballot_w64(gor != 0));
+            // a3: OR over the lanes that share a group, one mask bit per group
+            if constexpr (LPG == 2) gor |= swap_pair(gor);
+            if constexpr (LPG == 4) gor = quad_or(gor);
+            const uint64_t flagged = __builtin_amdgcn_ballot_w64(gor != 0);
+            if constexpr (LPG == 1) { mw[t] = (uint32_t)flagged; mw_hi[t] = (uint32_t)(flagged >> 32); }
+            else if constexpr (LPG == 2) mw[t] = compact_even_bits(flagged);
+            else mw[t] = compact_fourth_bits(flagged);
         }
         if (N < 8 && mode == 0) bad = (err_acc & ~NMASK) != 0;
         if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(&s_err[slot], 1u);
         ENEC_TP(1);
 
+        // a wave holds 64 / LPG mask bits of every row (nact / LPG when the block has 2048 elements
+        // and the only wave is half empty); group order = row-major
         if (lane == 0 && 64u * wave < nact) {
-            if (logC >= 9) {
+            if constexpr (LPG == 1) {
+                if (logC >= 9) {
 #pragma unroll
-                for (int t = 0; t < 8; ++t) img_maskw[((uint32_t)t << (logC - 9)) + wave] = mw[t];
-            } else {      // B = 2048: 16 groups per row, one wave
+                    for (int t = 0; t < 8; ++t) {
+                        img_maskw[((uint32_t)t << (logC - 8)) + 2u * wave] = mw[t];
+                        img_maskw[((uint32_t)t << (logC - 8)) + 2u * wave + 1u] = mw_hi[t];
+                    }
+                } else {  // B = 2048: 32 groups per row
 #pragma unroll
-                for (int u = 0; u < 4; ++u) img_maskw[u] = mw[2 * u] | (mw[2 * u + 1] << 16);
+                    for (int t = 0; t < 8; ++t) img_maskw[t] = mw[t];
+                }
+            } else if constexpr (LPG == 2) {
+                if (logC >= 9) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) img_maskw[((uint32_t)t << (logC - 9)) + wave] = mw[t];
+                } else {  // B = 2048: 16 groups per row, one wave
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) img_maskw[u] = mw[2 * u] | (mw[2 * u + 1] << 16);
+                }
+            } else {      // 16 bits per wave and row (B >= 4096)
+                uint16_t *img_mask16 = reinterpret_cast<uint16_t *>(img);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) img_mask16[((uint32_t)t << (logC - 9)) + wave] = (uint16_t)mw[t];
             }
         }
         if (LM > 0 && active) {
@@ -662,14 +709,14 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 
         // ---- a5 (positions): exclusive popcount prefix over the block's mask words; every wave
         // computes it for itself (a wave scan of at most 64 words) -----------------------
-        const uint32_t nwords = B >> 9;
+        const uint32_t nwords = (B >> 8) >> LOG_LPG;          // 32-bit words of the mask (at most 64)
         const uint32_t my_word = lane < nwords ? img_maskw[lane] : 0u;
         const uint32_t my_pc = __popc(my_word);
         const uint32_t my_incl = wave_incl_scan(my_pc, lane);
         const uint32_t my_excl = my_incl - my_pc;
         const uint32_t cnt = __shfl(my_incl, 63, 64);
         const uint32_t own_err = s_err[slot] & 1u;
-        const uint32_t S = (fixed + 2u * A * cnt + 15u) & ~15u;
+        const uint32_t S = (fixed + RB * cnt + 15u) & ~15u;
 
         // ---- a6: publish this block's size at once, and add it to its group's accumulator
         // [blocks:16 | blocks with a range error:16 | sum of sizes:32]; what the addition returns
@@ -686,44 +733,108 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         // ---- a5: one record per masked group ------------------------------------------
         if (A > 0) {
             constexpr HHTable TH = HH<A>::table;
-            const uint32_t par = tid & 1u;
+            if constexpr (LPG == 1) {
+                // a group is this lane's 8 elements of a row: Alg. 2 with N = 8 is the column map itself,
+                // its A normalized bytes are joined (byte i with byte i + ceil(A/2)), the pad byte is dropped
+                constexpr int HALF = (A + 1) / 2;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                // even lanes pack the group of row 2u, odd lanes the group of row 2u+1
-                const uint32_t own0 = par ? HI[2 * u + 1][0] : HI[2 * u][0];
-                const uint32_t own1 = par ? HI[2 * u + 1][1] : HI[2 * u][1];
-                const uint32_t snd0 = par ? HI[2 * u][0] : HI[2 * u + 1][0];
-                const uint32_t snd1 = par ? HI[2 * u][1] : HI[2 * u + 1][1];
-                const uint32_t rcv0 = swap_pair(snd0);
-                const uint32_t rcv1 = swap_pair(snd1);
-                uint32_t F[4];
-                F[0] = par ? rcv0 : own0;
-                F[1] = par ? rcv1 : own1;
-                F[2] = par ? own0 : rcv0;
-                F[3] = par ? own1 : rcv1;
-                const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
-                const uint32_t wv = __shfl(my_word, g >> 5, 64);
-                const uint32_t pre = __shfl(my_excl, g >> 5, 64);
-                const uint32_t bit = (wv >> (g & 31u)) & 1u;
-                if (active && bit) {
-                    const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                    // the group's 16 values are 2 columns of 8 rows: row r = bytes (2r, 2r+1)
-                    uint32_t P[AP];
+                for (int t = 0; t < 8; ++t) {
+                    const uint32_t g = ((uint32_t)t << (logC - 3)) + tid;
+                    const uint32_t wv = __shfl(my_word, g >> 5, 64);
+                    const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+                    if (active && ((wv >> (g & 31u)) & 1u)) {
+                        const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+                        uint32_t P[AP + 1];
 #pragma unroll
-                    for (int q = 0; q < AP; ++q) P[q] = 0;
+                        for (int q = 0; q <= AP; ++q) P[q] = 0;
 #pragma unroll
-                    for (int f = 0; f < TH.count; ++f) {
-                        const int r = TH.row[f];
-                        const uint32_t s = shl_or_shr(F[r >> 1], TH.shift[f] - 16 * (r & 1));
-                        P[TH.plane[f]] |= s & (TH.dmask[f] * 0x0101u);
+                        for (int f = 0; f < TH.count; ++f) {
+                            const int r = TH.row[f];
+                            const uint32_t v = (HI[t][r >> 2] >> (8 * (r & 3))) & 0xFFu;
+                            P[TH.plane[f]] |= shl_or_shr(v, TH.shift[f]) & TH.dmask[f];
+                        }
+                        uint8_t *dst = img_high + RB * rank;
+#pragma unroll
+                        for (int j = 0; j < A; ++j) dst[j] = (uint8_t)P[(j & 1) ? (j >> 1) + HALF : (j >> 1)];
                     }
-                    // normalized byte j = byte (j & 1) of P[j >> 1]; stream word i = nb[i] | nb[i + A] << 8
-                    uint16_t *dst = reinterpret_cast<uint16_t *>(img_high + 2u * A * rank);
+                }
+            } else if constexpr (LPG == 2) {
+                const uint32_t par = tid & 1u;
 #pragma unroll
-                    for (int i = 0; i < A; ++i) {
-                        const uint32_t lo = (P[i >> 1] >> (8 * (i & 1))) & 0xFFu;
-                        const uint32_t hi = (P[(i + A) >> 1] >> (8 * ((i + A) & 1))) & 0xFFu;
-                        dst[i] = (uint16_t)(lo | (hi << 8));
+                for (int u = 0; u < 4; ++u) {
+                    // even lanes pack the group of row 2u, odd lanes the group of row 2u+1
+                    const uint32_t own0 = par ? HI[2 * u + 1][0] : HI[2 * u][0];
+                    const uint32_t own1 = par ? HI[2 * u + 1][1] : HI[2 * u][1];
+                    const uint32_t snd0 = par ? HI[2 * u][0] : HI[2 * u + 1][0];
+                    const uint32_t snd1 = par ? HI[2 * u][1] : HI[2 * u + 1][1];
+                    const uint32_t rcv0 = swap_pair(snd0);
+                    const uint32_t rcv1 = swap_pair(snd1);
+                    uint32_t F[4];
+                    F[0] = par ? rcv0 : own0;
+                    F[1] = par ? rcv1 : own1;
+                    F[2] = par ? own0 : rcv0;
+                    F[3] = par ? own1 : rcv1;
+                    const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
+                    const uint32_t wv = __shfl(my_word, g >> 5, 64);
+                    const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+                    const uint32_t bit = (wv >> (g & 31u)) & 1u;
+                    if (active && bit) {
+                        const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+                        // the group's 16 values are 2 columns of 8 rows: row r = bytes (2r, 2r+1)
+                        uint32_t P[AP];
+#pragma unroll
+                        for (int q = 0; q < AP; ++q) P[q] = 0;
+#pragma unroll
+                        for (int f = 0; f < TH.count; ++f) {
+                            const int r = TH.row[f];
+                            const uint32_t s = shl_or_shr(F[r >> 1], TH.shift[f] - 16 * (r & 1));
+                            P[TH.plane[f]] |= s & (TH.dmask[f] * 0x0101u);
+                        }
+                        // normalized byte j = byte (j & 1) of P[j >> 1]; stream word i = nb[i] | nb[i + A] << 8
+                        uint16_t *dst = reinterpret_cast<uint16_t *>(img_high + 2u * A * rank);
+#pragma unroll
+                        for (int i = 0; i < A; ++i) {
+                            const uint32_t lo = (P[i >> 1] >> (8 * (i & 1))) & 0xFFu;
+                            const uint32_t hi = (P[(i + A) >> 1] >> (8 * ((i + A) & 1))) & 0xFFu;
+                            dst[i] = (uint16_t)(lo | (hi << 8));
+                        }
+                    }
+                }
+            } else {
+                // a group is the 32 elements of a quad: seen as 8 rows of 4 columns (element i = row i / 4,
+                // column i % 4) Alg. 2's folds again stay inside a column; lane j holds rows 2j and 2j+1
+                const uint32_t j = tid & 3u;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const uint32_t g = ((uint32_t)t << (logC - 5)) + (tid >> 2);
+                    const uint32_t wv = __shfl(my_word, g >> 5, 64);
+                    const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+                    if (active && ((wv >> (g & 31u)) & 1u)) {
+                        const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+                        uint32_t P[AP];
+#pragma unroll
+                        for (int q = 0; q < AP; ++q) P[q] = 0;
+#pragma unroll
+                        for (int f = 0; f < TH.count; ++f) {
+                            const int r = TH.row[f];
+                            const uint32_t c = shl_or_shr(HI[t][r & 1], TH.shift[f]) & (TH.dmask[f] * 0x01010101u);
+                            P[TH.plane[f]] |= ((uint32_t)(r >> 1) == j) ? c : 0u;
+                        }
+#pragma unroll
+                        for (int q = 0; q < A; ++q) P[q] = quad_or(P[q]);
+                        if (j == 0) {
+                            // normalized byte 4q + c = byte c of P[q]; stream word i = nb[i] | nb[i + 2A] << 8
+                            uint32_t *dst = reinterpret_cast<uint32_t *>(img_high + RB * rank);
+#pragma unroll
+                            for (int k = 0; k < A; ++k) {
+                                const int i0 = 2 * k, i1 = 2 * k + 1, h0 = i0 + 2 * A, h1 = i1 + 2 * A;
+                                const uint32_t b0 = (P[i0 >> 2] >> (8 * (i0 & 3))) & 0xFFu;
+                                const uint32_t b1 = (P[h0 >> 2] >> (8 * (h0 & 3))) & 0xFFu;
+                                const uint32_t b2 = (P[i1 >> 2] >> (8 * (i1 & 3))) & 0xFFu;
+                                const uint32_t b3 = (P[h1 >> 2] >> (8 * (h1 & 3))) & 0xFFu;
+                                dst[k] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+                            }
+                        }
                     }
                 }
             }
@@ -806,10 +917,12 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 // next block is already travelling: its sign/mantissa bytes into registers, its packed part
 // (mask | low plane | high records, exactly as in the stream) into the other of two LDS images.
 // ---------------------------------------------------------------------------------
-template <int M, int A, int DT>
+template <int M, int A, int DT, int LPG>
 __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
 {
     constexpr int N = M + A;
+    constexpr int LOG_LPG = LPG == 4 ? 2 : LPG - 1;
+    constexpr uint32_t RB = A * LPG;                     // bytes of one high record: (n - m) L / 8
     constexpr int LM = low_plane_bits(M, DT);            // width of the low plane
     constexpr uint32_t SREP = (1u << (N - 1)) * 0x01010101u;
     constexpr uint32_t LMASK = ((1u << M) - 1u) * 0x01010101u;
@@ -823,9 +936,9 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
     const uint32_t B = p.B, logC = p.logB - 3u, C = 1u << logC;
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
-    const uint32_t img_bytes = (B >> 7) + (((uint32_t)(LM + A) * B) >> 3);
-    const uint32_t fixed = B + (B >> 7) + ((LM * B) >> 3);
-    const uint32_t par = tid & 1u;
+    const uint32_t mask_bytes = (B >> 6) >> LOG_LPG;                  // B / (8 L)
+    const uint32_t img_bytes = mask_bytes + (((uint32_t)(LM + A) * B) >> 3);
+    const uint32_t fixed = B + mask_bytes + ((LM * B) >> 3);
 
     // tensor that global block kg belongs to, searching upwards from item c
     auto item_of = [&](uint32_t kg, uint32_t c) -> uint32_t {
@@ -862,7 +975,7 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
         off = t0;
         size = (uint32_t)sz;
         return header_matches(c) &&
-               !(sz < fixed || sz > fixed + 2u * A * (B >> 4) + 15u || (sz & 15u) || t0 > p.item[c].payload_bytes ||
+               !(sz < fixed || sz > fixed + RB * ((B >> 3) >> LOG_LPG) + 15u || (sz & 15u) || t0 > p.item[c].payload_bytes ||
                  sz > p.item[c].payload_bytes - t0);
     };
     // issue the loads of one block: sign/mantissa rows and the packed part
@@ -922,7 +1035,7 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
 
         if (valid && active) {
             const uint8_t *img = smem + slot * img_bytes;
-            const uint8_t *img_low = img + (B >> 7);
+            const uint8_t *img_low = img + mask_bytes;
             const uint8_t *img_high = img_low + (((size_t)LM * B) >> 3);
             const uint64_t blk0 = (uint64_t)(k - it.first) << p.logB;
             // fp32: the lower halves of this thread's elements, straight from the stream
@@ -936,7 +1049,7 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
                 }
             }
             // d2: mask words and their exclusive popcount prefix (a wave scan per wave)
-            const uint32_t nwords = B >> 9;
+            const uint32_t nwords = (B >> 8) >> LOG_LPG;
             const uint32_t my_word = lane < nwords ? reinterpret_cast<const uint32_t *>(img)[lane] : 0u;
             const uint32_t my_pc = __popc(my_word);
             const uint32_t my_excl = wave_incl_scan(my_pc, lane) - my_pc;
@@ -985,38 +1098,93 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
                 // d2/d3: high bits of masked groups, found through the mask prefix
                 if (A > 0) {
                     constexpr HHTable TH = HH<A>::table;
-                    const uint32_t g = ((uint32_t)t << (logC - 4)) + (tid >> 1);
+                    const uint32_t g = ((uint32_t)t << (logC - 3 - LOG_LPG)) + (tid >> LOG_LPG);
                     const uint32_t wv = __shfl(my_word, g >> 5, 64);
                     const uint32_t pre = __shfl(my_excl, g >> 5, 64);
                     if ((wv >> (g & 31u)) & 1u) {
                         const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                        const uint16_t *rec = reinterpret_cast<const uint16_t *>(img_high + 2u * A * rank);
-                        uint32_t nbyte[2 * AP];
+                        const uint8_t *rec8 = img_high + RB * rank;
+                        if constexpr (LPG == 1) {
+                            // this lane's 8 elements are the group: stream byte j is normalized byte j/2
+                            // (even j) or j/2 + ceil(A/2) (odd j), the dropped pad byte is zero
+                            constexpr int HALF = (A + 1) / 2;
+                            uint32_t P[AP + 1];
 #pragma unroll
-                        for (int i = 0; i < A; ++i) {
-                            const uint32_t w = rec[i];
-                            nbyte[i] = w & 0xFFu;
-                            nbyte[i + A] = w >> 8;
+                            for (int q = 0; q <= AP; ++q) P[q] = 0;
+#pragma unroll
+                            for (int j = 0; j < A; ++j) P[(j & 1) ? (j >> 1) + HALF : (j >> 1)] = rec8[j];
+                            uint32_t h[2] = {0u, 0u};
+#pragma unroll
+                            for (int f = 0; f < TH.count; ++f) {
+                                const int r = TH.row[f];
+                                const uint32_t smask = TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
+                                                                        : (TH.dmask[f] << (-TH.shift[f]));
+                                h[r >> 2] |= (shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask) << (8 * (r & 3));
+                            }
+                            Y[0] |= h[0] << M;
+                            Y[1] |= h[1] << M;
+                        } else if constexpr (LPG == 2) {
+                            const uint32_t par = tid & 1u;
+                            const uint16_t *rec = reinterpret_cast<const uint16_t *>(rec8);
+                            uint32_t nbyte[2 * AP];
+#pragma unroll
+                            for (int i = 0; i < A; ++i) {
+                                const uint32_t w = rec[i];
+                                nbyte[i] = w & 0xFFu;
+                                nbyte[i + A] = w >> 8;
+                            }
+                            uint32_t P[AP];
+#pragma unroll
+                            for (int q = 0; q < A; ++q) P[q] = 0;
+#pragma unroll
+                            for (int j = 0; j < 2 * A; ++j) P[j >> 1] |= nbyte[j] << (8 * (j & 1));
+                            uint32_t E[8];
+#pragma unroll
+                            for (int r = 0; r < 8; ++r) E[r] = 0;
+#pragma unroll
+                            for (int f = 0; f < TH.count; ++f) {
+                                const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
+                                                                        : (TH.dmask[f] << (-TH.shift[f]))) * 0x0101u;
+                                E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
+                            }
+                            // this lane's 8 elements are rows 4*par .. 4*par+3 of the two-column view
+                            const uint32_t h0 = par ? (E[4] | (E[5] << 16)) : (E[0] | (E[1] << 16));
+                            const uint32_t h1 = par ? (E[6] | (E[7] << 16)) : (E[2] | (E[3] << 16));
+                            Y[0] |= h0 << M;
+                            Y[1] |= h1 << M;
+                        } else {
+                            // the quad's group as 8 rows of 4 columns: stream word i = normalized byte i |
+                            // normalized byte i + 2A << 8, normalized byte 4q + c = byte c of plane q
+                            const uint32_t *rec = reinterpret_cast<const uint32_t *>(rec8);
+                            uint32_t nbyte[4 * AP];
+#pragma unroll
+                            for (int k = 0; k < A; ++k) {
+                                const uint32_t w = rec[k];
+                                nbyte[2 * k] = w & 0xFFu;
+                                nbyte[2 * k + 2 * A] = (w >> 8) & 0xFFu;
+                                nbyte[2 * k + 1] = (w >> 16) & 0xFFu;
+                                nbyte[2 * k + 1 + 2 * A] = w >> 24;
+                            }
+                            uint32_t P[AP];
+#pragma unroll
+                            for (int q = 0; q < A; ++q)
+                                P[q] = nbyte[4 * q] | (nbyte[4 * q + 1] << 8) | (nbyte[4 * q + 2] << 16) | (nbyte[4 * q + 3] << 24);
+                            uint32_t E[8];
+#pragma unroll
+                            for (int r = 0; r < 8; ++r) E[r] = 0;
+#pragma unroll
+                            for (int f = 0; f < TH.count; ++f) {
+                                const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
+                                                                        : (TH.dmask[f] << (-TH.shift[f]))) * 0x01010101u;
+                                E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
+                            }
+                            // lane j of the quad holds rows 2j and 2j+1
+                            const uint32_t j = tid & 3u;
+                            const uint32_t h0 = j == 0 ? E[0] : (j == 1 ? E[2] : (j == 2 ? E[4] : E[6]));
+                            const uint32_t h1 = j == 0 ? E[1] : (j == 1 ? E[3] : (j == 2 ? E[5] : E[7]));
+                            Y[0] |= h0 << M;
+                            Y[1] |= h1 << M;
                         }
-                        uint32_t P[AP];
-#pragma unroll
-                        for (int q = 0; q < A; ++q) P[q] = 0;
-#pragma unroll
-                        for (int j = 0; j < 2 * A; ++j) P[j >> 1] |= nbyte[j] << (8 * (j & 1));
-                        uint32_t E[8];
-#pragma unroll
-                        for (int r = 0; r < 8; ++r) E[r] = 0;
-#pragma unroll
-                        for (int f = 0; f < TH.count; ++f) {
-                            const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
-                                                                    : (TH.dmask[f] << (-TH.shift[f]))) * 0x0101u;
-                            E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
-                        }
-                        // this lane's 8 elements are rows 4*par .. 4*par+3 of the two-column view
-                        const uint32_t h0 = par ? (E[4] | (E[5] << 16)) : (E[0] | (E[1] << 16));
-                        const uint32_t h1 = par ? (E[6] | (E[7] << 16)) : (E[2] | (E[3] << 16));
-                        Y[0] |= h0 << M;
-                        Y[1] |= h1 << M;
                     }
                 }
                 // d4: x = b - sext_n(y) = (b + 2^(n-1)) - (y ^ 2^(n-1)); recombine with sign/mantissa

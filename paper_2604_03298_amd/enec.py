@@ -22,7 +22,7 @@ EXPORTS = [
     "enec_version", "enec_strerror", "enec_default_block_size", "enec_compress_bound",
     "enec_workspace_bytes", "enec_workspace_init", "enec_compress", "enec_decompress",
     "enec_decompress_with_header", "enec_tune", "enec_tune_histogram", "enec_stream_info",
-    "enec_copy", "enec_compress_batch", "enec_decompress_batch",
+    "enec_copy", "enec_compress_batch", "enec_decompress_batch", "enec_tune_histogram_groups",
 ]
 
 
@@ -85,6 +85,8 @@ def lib():
         L.enec_tune.argtypes = [vp, sz, C.c_int, C.POINTER(Params), u64p, vp, sz, vp]
         L.enec_tune_histogram.restype = C.c_int
         L.enec_tune_histogram.argtypes = [u64p, C.c_int, C.POINTER(Params)]
+        L.enec_tune_histogram_groups.restype = C.c_int
+        L.enec_tune_histogram_groups.argtypes = [u64p, C.c_int, u32, C.POINTER(Params)]
         L.enec_stream_info.restype = C.c_int
         L.enec_stream_info.argtypes = [vp, C.POINTER(Params), u64p, C.POINTER(u32), u64p,
                                        C.POINTER(C.c_int), C.POINTER(u32)]
@@ -145,12 +147,20 @@ def workspace_bytes(n_elems: int, block_size: int = 0) -> int:
     return int(lib().enec_workspace_bytes(n_elems, block_size))
 
 
-def tune_histogram(hist, dtype: int = BF16) -> tuple:
+def tune_histogram(hist, dtype: int = BF16, lengths=None) -> tuple:
+    """(b, n, m, L) from a 256-bin exponent histogram; L = 16 unless candidate group lengths are given."""
     h = np.ascontiguousarray(hist, dtype=np.uint64)
     assert h.size == 256
     p = Params()
-    _check(lib().enec_tune_histogram(h.ctypes.data_as(C.POINTER(C.c_uint64)), dtype, C.byref(p)),
-           "enec_tune_histogram")
+    if lengths is None:
+        _check(lib().enec_tune_histogram(h.ctypes.data_as(C.POINTER(C.c_uint64)), dtype, C.byref(p)),
+               "enec_tune_histogram")
+    else:
+        mask = 0
+        for v in lengths:
+            mask |= int(v)
+        _check(lib().enec_tune_histogram_groups(h.ctypes.data_as(C.POINTER(C.c_uint64)), dtype, mask, C.byref(p)),
+               "enec_tune_histogram_groups")
     return p.astuple()
 
 
@@ -256,16 +266,19 @@ def decompress_batch(stream_bufs, host_headers, outs, stream=None, items=None) -
     return int(lib().enec_decompress_batch(items, len(items), _stream_handle(stream)))
 
 
-def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int | None = None):
-    """-> (b, n, m, L) [, histogram]; synchronous."""
+def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int | None = None, lengths=None):
+    """-> (b, n, m, L) [, histogram]; synchronous.  lengths: candidate group lengths for Eq. 4's joint
+    search of (m, L), e.g. (8, 16, 32); None keeps the paper's L = 16."""
     p = Params()
     hist = np.zeros(256, dtype=np.uint64)
-    _check(lib().enec_tune(C.c_void_p(src.data_ptr()), src.numel(), dtype_of(src, dtype), C.byref(p),
+    dt = dtype_of(src, dtype)
+    _check(lib().enec_tune(C.c_void_p(src.data_ptr()), src.numel(), dt, C.byref(p),
                            hist.ctypes.data_as(C.POINTER(C.c_uint64)),
                            C.c_void_p(workspace.data_ptr()),
                            workspace.numel() * workspace.element_size(), _stream_handle(stream)),
            "enec_tune")
-    return (p.astuple(), hist) if want_histogram else p.astuple()
+    prm = p.astuple() if lengths is None else tune_histogram(hist, dt, lengths)
+    return (prm, hist) if want_histogram else prm
 
 
 def copy(dst, src, nbytes: int | None = None, stream=None) -> int:

@@ -7,7 +7,7 @@ from paper_2604_03298_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 BF16, FP16, FP32 = 0, 1, 2
-WORD = {FP16: np.uint16, FP32: np.uint32}
+WORD = {BF16: np.uint16, FP16: np.uint16, FP32: np.uint32}
 
 
 @pytest.fixture(scope="module")

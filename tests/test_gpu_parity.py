@@ -377,7 +377,7 @@ def test_host_argument_errors_on_device_pointers(gpu):
     assert enec.compress(src, (122, 6, 3, 16), out[:1000], gpu.ws) == enec.E_CAPACITY
     assert enec.compress(src, (122, 6, 3, 16), out, gpu.ws, block_size=3000) == enec.E_BLOCK
     assert enec.compress(src, (122, 9, 3, 16), out, gpu.ws) == enec.E_PARAMS
-    assert enec.compress(src, (122, 6, 3, 8), out, gpu.ws) == enec.E_PARAMS
+    assert enec.compress(src, (122, 6, 3, 12), out, gpu.ws) == enec.E_PARAMS
     assert enec.compress(src[1:], (122, 6, 3, 16), out, gpu.ws, n_elems=100) == enec.E_ARG   # misaligned
     pageable = torch.zeros(1, dtype=torch.int64)
     assert enec.compress(src, (122, 6, 3, 16), out, gpu.ws, out_bytes=pageable) == enec.E_ARG

@@ -78,6 +78,12 @@ def test_host_tuner_matches_oracle(enec, oracle, ref):
         assert enec.tune_histogram(h, dtype=1) == oracle.tune_hist(h, 5)[0]
     with pytest.raises(Exception):
         enec.tune_histogram(hists[0], dtype=7)
+    # Eq. 4 with the group length searched together with m
+    for h in hists[:60]:
+        for lengths in ((8, 16, 32), (16,), (8,), (16, 32)):
+            assert enec.tune_histogram(h, lengths=lengths) == oracle.tune_hist_groups(h, 8, lengths)[0]
+    with pytest.raises(Exception):
+        enec.tune_histogram(hists[0], lengths=(4,))
 
 
 def test_stream_info_parses_oracle_headers(enec, oracle):
@@ -119,7 +125,7 @@ def test_null_and_misaligned_arguments_are_rejected_on_the_host(enec):
     assert L.enec_workspace_init(fake, 17, None) == enec.E_ARG
     assert L.enec_copy(fake, odd, 16, None) == enec.E_ARG
     assert L.enec_tune_histogram(None, 0, ctypes.byref(p)) == enec.E_ARG
-    for dt, bad in ((1, (10, 6, 2, 16)), (1, (40, 4, 2, 16)), (2, (122, 9, 3, 16))):
+    for dt, bad in ((1, (10, 6, 2, 16)), (1, (40, 4, 2, 16)), (2, (122, 9, 3, 16)), (0, (122, 6, 3, 12)), (0, (122, 6, 3, 64))):
         q = enec.Params(*bad)
         assert L.enec_compress(fake, 10, dt, 0, ctypes.byref(q), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_PARAMS
     assert L.enec_compress(fake, 10, 3, 0, ctypes.byref(p), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_DTYPE
