@@ -1,7 +1,8 @@
 """Runs the codec on all five synthetic configurations on one MI355X and prints one JSON line per
 configuration (throughput on uncompressed bytes, ratio, fraction of the 8 TB/s HBM peak in bytes
-moved).  `python -m paper_2604_03298_amd.report [--configs 1,2,3a,3b,4,5,fp16,fp32]`.
-The last two are the seven matrix shapes of configuration 2 as fp16 / fp32 tensors, N(0, 0.02^2).
+moved).  `python -m paper_2604_03298_amd.report [--configs 1,2,2j,3a,3b,4,5,fp16,fp32]`.
+2j is configuration 2 tuned with the group length searched together with m (Eq. 4); the last two are the
+seven matrix shapes of configuration 2 as fp16 / fp32 tensors, N(0, 0.02^2).
 
 Tensors of configurations 1-3 come from the seeded numpy generators of `workloads.py` (the ones the
 parity tests use); configurations 4 and 5 (15 GB / 4.8 GB of bf16) are drawn on the GPU with a
@@ -23,12 +24,12 @@ def _events(torch, n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
-def run_group(torch, enec, name, srcs, reps=5, dtype=0):
+def run_group(torch, enec, name, srcs, reps=5, dtype=0, lengths=None):
     """Tune, compress (batched), decompress (batched), verify; returns a dict of results."""
     n_el = [s.numel() for s in srcs]
     raw = srcs[0].element_size() * sum(n_el)
     ws = enec.new_workspace(sum(n_el))
-    params = [enec.tune(s, ws, dtype=dtype) for s in srcs]
+    params = [enec.tune(s, ws, dtype=dtype, lengths=lengths) for s in srcs]
     outs = [torch.empty(enec.compress_bound(n, dtype=dtype), dtype=torch.uint8, device="cuda") for n in n_el]
     sizes = torch.zeros(len(srcs), dtype=torch.int64, device="cuda")
     szl = [sizes[i:i + 1] for i in range(len(srcs))]
@@ -144,7 +145,7 @@ def offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--configs", default="1,2,3a,3b,4,5,fp16,fp32")
+    ap.add_argument("--configs", default="1,2,2j,3a,3b,4,5,fp16,fp32")
     args = ap.parse_args()
     want = args.configs.split(",")
     import torch
@@ -159,6 +160,9 @@ def main():
         print(json.dumps(run_group(torch, enec, "1: 1024x4096 N(0,0.02^2)", [dev(W.config1())], reps=20)[0]), flush=True)
     if "2" in want:
         print(json.dumps(run_group(torch, enec, "2: 7B-style decoder layer", [dev(w) for _, w in W.config2()], reps=20)[0]), flush=True)
+    if "2j" in want:      # the same layer with Eq. 4's joint search of (m, L) instead of the paper's L = 16
+        print(json.dumps(run_group(torch, enec, "2j: 7B-style decoder layer, group length searched with m",
+                                   [dev(w) for _, w in W.config2()], reps=20, lengths=(8, 16, 32))[0]), flush=True)
     if "3a" in want:
         print(json.dumps(run_group(torch, enec, "3a: edge-case mix, one tensor", [dev(W.config3()[0])], reps=10)[0]), flush=True)
     if "3b" in want:
