@@ -11,7 +11,7 @@ GOLDEN = os.path.join(ROOT, "tests", "golden")
 
 
 def pytest_configure(config):
-    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with gpurun)")
+    config.addinivalue_line("markers", "gpu: needs a real MI355X")
 
 
 def golden_lines(name):
