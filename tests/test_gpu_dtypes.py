@@ -222,3 +222,38 @@ def test_decompress_without_host_header_and_wrong_size(gpu, oracle):
     out = gpu.torch.zeros(w.size, dtype=gpu.torch.int32, device="cuda")
     assert gpu.enec.decompress(buf, out, n_elems=w.size - 1) == gpu.enec.E_FORMAT
     assert gpu.enec.decompress(buf[:s.size - 16], out, n_elems=w.size) == gpu.enec.E_FORMAT
+
+
+def test_fp32_tensor_beyond_4_gib(gpu, oracle):
+    """1.3e9 fp32 elements (5.2 GB): the region of lower halves alone exceeds 2^31 bytes, offsets exceed 2^32."""
+    torch, enec = gpu.torch, gpu.enec
+    from paper_2604_03298_amd.report import gpu_gaussian
+    src = gpu_gaussian(torch, 45000, 28672 + 231, 0.02, 4343, torch.float32)
+    n = src.numel()
+    assert 4 * n > (1 << 32)
+    ws = enec.new_workspace(n)
+    prm = enec.tune(src, ws, dtype=FP32)
+    out = torch.empty(enec.compress_bound(n, dtype=FP32), dtype=torch.uint8, device="cuda")
+    size = torch.zeros(1, dtype=torch.int64, device="cuda")
+    assert enec.compress(src, prm, out, ws, out_bytes=size, dtype=FP32) == 0
+    torch.cuda.synchronize()
+    back = torch.empty_like(src)
+    assert enec.decompress_with_header(out, out[:64].cpu().numpy().tobytes(), back) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(back, src)
+    del back
+    B = 16384
+    nb = (n + B - 1) // B
+    te, base = oracle.table_end(n, B), oracle.payload_base(n, B, FP32)
+    assert int(size.item()) > base
+    table = out[64:64 + 8 * (nb + 1)].cpu().numpy().view("<u8")
+    for k0 in (0, nb // 2, nb - 2):
+        cnt = min(2, nb - k0)
+        w = src[k0 * B:min(n, (k0 + cnt) * B)].cpu().numpy().view(np.uint32)
+        rc, s = oracle.compress(w, prm, B, dtype=FP32)
+        assert rc == 0
+        ob = oracle.payload_base(w.size, B, FP32)
+        got = out[base + int(table[k0]):base + int(table[k0 + cnt])].cpu().numpy()
+        assert np.array_equal(got, s[ob:]), k0
+        tail = out[te + 2 * k0 * B:te + 2 * (k0 * B + w.size)].cpu().numpy()
+        assert np.array_equal(tail.view("<u2"), (w & 0xFFFF).astype(np.uint16)), k0

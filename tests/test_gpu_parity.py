@@ -390,3 +390,41 @@ def test_full_size_layer_and_large_tensor(gpu, oracle):
     # one tensor of the large-layer stream (8192 x 28672)
     w = W.config4_tensor(0)
     check_both_ways(gpu, oracle, w, oracle.tune(w), 16384, "config4[0]")
+
+
+def test_tensor_beyond_4_gib_sampled_against_the_oracle(gpu, oracle):
+    """2.6e9 elements (5.2 GB of bf16): element and byte offsets beyond 32 bits.  The round trip is compared
+    on the device; blocks sampled along the tensor are recompressed by the oracle one group of blocks at a
+    time, and their payloads must be the bytes the library wrote at the offsets its table gives."""
+    torch, enec = gpu.torch, gpu.enec
+    from paper_2604_03298_amd.report import gpu_gaussian
+    rows, cols = 90000, 28672 + 231          # not a multiple of the block size: ragged tail
+    src = gpu_gaussian(torch, rows, cols, 0.02, 4242)
+    n = src.numel()
+    assert 2 * n > (1 << 32)
+    ws = enec.new_workspace(n)
+    prm = enec.tune(src, ws)
+    out = torch.empty(enec.compress_bound(n), dtype=torch.uint8, device="cuda")
+    size = torch.zeros(1, dtype=torch.int64, device="cuda")
+    assert enec.compress(src, prm, out, ws, out_bytes=size) == 0
+    torch.cuda.synchronize()
+    total = int(size.item())
+    assert 0 < total < 2 * n
+    back = torch.empty_like(src)
+    assert enec.decompress_with_header(out, out[:64].cpu().numpy().tobytes(), back) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(back, src)
+    del back
+    B = 16384
+    nb = (n + B - 1) // B
+    base = oracle.payload_base(n, B)
+    table = out[64:64 + 8 * (nb + 1)].cpu().numpy().view("<u8")
+    assert table[0] == 0 and int(table[nb]) + base == total and (np.diff(table.astype(np.int64)) > 0).all()
+    for k0 in (0, 1234, nb // 2, (1 << 32) // (2 * B) + 5, nb - 3):           # incl. the blocks around byte 2^32 and the tail
+        cnt = min(3, nb - k0)
+        w = src[k0 * B:min(n, (k0 + cnt) * B)].cpu().numpy().view(np.uint16)
+        rc, s = oracle.compress(w, prm, B)
+        assert rc == 0
+        ob = oracle.payload_base(w.size, B)
+        got = out[base + int(table[k0]):base + int(table[k0 + cnt])].cpu().numpy()
+        assert got.size == s.size - ob and np.array_equal(got, s[ob:]), k0
