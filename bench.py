@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config2", choices=["config1", "config2"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the brief fp16 / fp32 / joint-search measurements")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -199,6 +200,25 @@ def main():
                "sample": f"{i} tensors of the same layer, largest first, compress + decompress each, "
                          f"{done_bytes / 2e6:.0f} MB of bf16, {t_cpu:.1f} s of CPU time"}
 
+    # ---- the other element formats and the joint (m, L) search, measured briefly beside the headline -----
+    # (same seven matrix shapes, N(0, 0.02^2) drawn on the GPU; bf16 with Eq. 4's group-length search)
+    extra = None
+    if args.workload == "config2" and not args.no_extra:
+        try:
+            from paper_2604_03298_amd import report
+            shapes = [(r, c) for _, r, c, _ in workloads.config2_spec() if r > 1]
+            extra = {}
+            for key, tdt, code, lengths in (("fp16", torch.float16, enec.FP16, None), ("fp32", torch.float32, enec.FP32, None),
+                                            ("bf16_joint_m_L", torch.bfloat16, enec.BF16, (8, 16, 32))):
+                t = [report.gpu_gaussian(torch, r, c, 0.02, 6000 + i, tdt) for i, (r, c) in enumerate(shapes)]
+                res = report.run_group(torch, enec, key, t, reps=5, dtype=code, lengths=lengths)[0]
+                extra[key] = {k: res[k] for k in ("params", "compression_ratio", "compress_GBps", "decompress_GBps",
+                                                  "compress_frac_of_hbm_peak", "decompress_frac_of_hbm_peak")}
+                del t
+                torch.cuda.empty_cache()
+        except Exception as exc:          # the headline line must not depend on this
+            extra = {"error": repr(exc)}
+
     ratio = raw_bytes / sum(stream_bytes)
     line = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -212,7 +232,7 @@ def main():
         "compression_ratio": round(ratio, 4),
         "compress_ms": round(float(np.median(pass_c)), 4), "decompress_ms": round(float(np.median(pass_d)), 4),
         "copy_kernel_GBps_moved": round(copy_gbps, 1),
-        "roofline": roofline, "kernels": per_kernel, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": per_kernel, "cpu_baseline": cpu, "other_formats": extra,
     }
     print(json.dumps(line))
 
