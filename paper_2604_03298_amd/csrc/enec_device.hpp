@@ -734,9 +734,33 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         if (A > 0) {
             constexpr HHTable TH = HH<A>::table;
             if constexpr (LPG == 1) {
-                // a group is this lane's 8 elements of a row: Alg. 2 with N = 8 is the column map itself,
-                // its A normalized bytes are joined (byte i with byte i + ceil(A/2)), the pad byte is dropped
+                // A group is this lane's 8 elements of a row, and Alg. 2 with N = 8 is the column map
+                // itself.  The lane's 8 x 8 bytes (row = group, byte = element) are transposed, so that
+                // one register holds the same element of four groups and the eight groups are packed at
+                // once in byte lanes; A normalized bytes per group are then joined (byte i with byte
+                // i + ceil(A/2)), the pad byte of an odd count is dropped.
                 constexpr int HALF = (A + 1) / 2;
+                uint32_t T[8][2];                 // T[element][k]: groups 4k .. 4k+3
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t r0 = HI[4 * k][h], r1 = HI[4 * k + 1][h], r2 = HI[4 * k + 2][h], r3 = HI[4 * k + 3][h];
+                        const uint32_t lo01 = byte_perm(r1, r0, 0x05010400u), hi01 = byte_perm(r1, r0, 0x07030602u);
+                        const uint32_t lo23 = byte_perm(r3, r2, 0x05010400u), hi23 = byte_perm(r3, r2, 0x07030602u);
+                        T[4 * h][k] = byte_perm(lo23, lo01, 0x05040100u);
+                        T[4 * h + 1][k] = byte_perm(lo23, lo01, 0x07060302u);
+                        T[4 * h + 2][k] = byte_perm(hi23, hi01, 0x05040100u);
+                        T[4 * h + 3][k] = byte_perm(hi23, hi01, 0x07060302u);
+                    }
+                uint32_t P[AP + 1][2];            // normalized byte q of groups 4k .. 4k+3 (P[A] = the pad)
+#pragma unroll
+                for (int q = 0; q <= AP; ++q) P[q][0] = P[q][1] = 0;
+#pragma unroll
+                for (int f = 0; f < TH.count; ++f)
+#pragma unroll
+                    for (int k = 0; k < 2; ++k)
+                        P[TH.plane[f]][k] |= shl_or_shr(T[TH.row[f]][k], TH.shift[f]) & (TH.dmask[f] * 0x01010101u);
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
                     const uint32_t g = ((uint32_t)t << (logC - 3)) + tid;
@@ -744,18 +768,10 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                     const uint32_t pre = __shfl(my_excl, g >> 5, 64);
                     if (active && ((wv >> (g & 31u)) & 1u)) {
                         const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                        uint32_t P[AP + 1];
-#pragma unroll
-                        for (int q = 0; q <= AP; ++q) P[q] = 0;
-#pragma unroll
-                        for (int f = 0; f < TH.count; ++f) {
-                            const int r = TH.row[f];
-                            const uint32_t v = (HI[t][r >> 2] >> (8 * (r & 3))) & 0xFFu;
-                            P[TH.plane[f]] |= shl_or_shr(v, TH.shift[f]) & TH.dmask[f];
-                        }
                         uint8_t *dst = img_high + RB * rank;
 #pragma unroll
-                        for (int j = 0; j < A; ++j) dst[j] = (uint8_t)P[(j & 1) ? (j >> 1) + HALF : (j >> 1)];
+                        for (int j = 0; j < A; ++j)
+                            dst[j] = (uint8_t)(P[(j & 1) ? (j >> 1) + HALF : (j >> 1)][t >> 2] >> (8 * (t & 3)));
                     }
                 }
             } else if constexpr (LPG == 2) {
