@@ -58,13 +58,15 @@ def run_group(torch, enec, name, srcs, reps=5, dtype=0, lengths=None):
     decomp()
     torch.cuda.synchronize()
     assert all(torch.equal(b, s) for b, s in zip(backs, srcs)), "round trip is not bit-exact"
-    tc, td = [], []
-    for _ in range(reps):
-        e = _events(torch, 3)
+    # all repetitions are queued back to back (no host synchronisation in between, which would add the
+    # latency of a launch into an idle GPU to every pass); events bracket each pass on the stream
+    evs = [_events(torch, 3) for _ in range(reps)]
+    comp(); decomp()
+    for e in evs:
         e[0].record(); comp(); e[1].record(); decomp(); e[2].record()
-        torch.cuda.synchronize()
-        tc.append(e[0].elapsed_time(e[1])); td.append(e[1].elapsed_time(e[2]))
-    tc, td = float(np.median(tc)), float(np.median(td))
+    torch.cuda.synchronize()
+    tc = float(np.median([e[0].elapsed_time(e[1]) for e in evs]))
+    td = float(np.median([e[1].elapsed_time(e[2]) for e in evs]))
     moved = raw + sum(stream_bytes)
     return {
         "config": name, "tensors": len(srcs), "uncompressed_bytes": raw, "compression_ratio": round(raw / sum(stream_bytes), 4),
