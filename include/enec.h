@@ -66,7 +66,7 @@ typedef enum {
     ENEC_E_CAPACITY = 5,  /* out_capacity < enec_compress_bound() or workspace too small */
     ENEC_E_RANGE = 6,     /* an exponent lies outside [b - 2^(n-1) + 1, b + 2^(n-1)] while n < E */
     ENEC_E_FORMAT = 7,    /* not an ENEC stream, or header does not match the call */
-    ENEC_E_HIP = 8        /* a HIP runtime call failed */
+    ENEC_E_HIP = 8        /* a HIP runtime call failed; as a header status: the scan gave up on a corrupt workspace */
 } enec_status;
 
 /* Element formats [Alg. 1 input line; Table VI]: sign | exponent | mantissa = 1|8|7, 1|5|10, 1|8|23.
@@ -124,13 +124,14 @@ int enec_workspace_init(void *workspace, size_t bytes, void *stream);
  * One kernel launch.  The stream written is a pure function of (input bytes, params, block_size).
  * Errors detectable on the host return at once with nothing enqueued.  The data-dependent
  * ENEC_E_RANGE is found by the kernel: header.status = ENEC_E_RANGE, header.total_bytes = 0,
- * *out_bytes = 0, payload undefined. */
+ * *out_bytes = 0, payload undefined.  The same holds for header.status = ENEC_E_HIP, which the kernel
+ * writes instead of waiting for ever if the workspace was not in the state the last call left it in. */
 int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size,
                   const enec_params *params, void *out, size_t out_capacity,
                   uint64_t *out_bytes, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Compress several tensors with as few kernel launches as possible: tensors that share (m, n - m,
- * block size) go into one launch, whose workgroups walk the data blocks of all of them, so that
+/* Compress several tensors with as few kernel launches as possible: tensors that share (m, n - m, L,
+ * block size) go into one launch (up to 16 tensors each), whose workgroups walk the data blocks of all of them, so that
  * small tensors cost no launch of their own and the device never drains between tensors.
  * Every field of an item means what the argument of the same name means for enec_compress
  * (params == NULL tunes that tensor first, which makes the call synchronous).  The workspace
