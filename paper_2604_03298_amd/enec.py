@@ -266,9 +266,11 @@ def decompress_batch(stream_bufs, host_headers, outs, stream=None, items=None) -
     return int(lib().enec_decompress_batch(items, len(items), _stream_handle(stream)))
 
 
-def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int | None = None, lengths=None):
+def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int | None = None, lengths=None,
+         block_size: int = 0):
     """-> (b, n, m, L) [, histogram]; synchronous.  lengths: candidate group lengths for Eq. 4's joint
-    search of (m, L), e.g. (8, 16, 32); None keeps the paper's L = 16."""
+    search of (m, L), e.g. (8, 16, 32); None keeps the paper's L = 16.  Lengths that the block size the
+    tensor will be compressed with does not admit (128 L <= block size <= 2048 L) are left out."""
     p = Params()
     hist = np.zeros(256, dtype=np.uint64)
     dt = dtype_of(src, dtype)
@@ -277,6 +279,9 @@ def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int |
                            C.c_void_p(workspace.data_ptr()),
                            workspace.numel() * workspace.element_size(), _stream_handle(stream)),
            "enec_tune")
+    if lengths is not None:
+        B = block_size or default_block_size(src.numel())
+        lengths = [v for v in lengths if 128 * v <= B <= 2048 * v] or [16]
     prm = p.astuple() if lengths is None else tune_histogram(hist, dt, lengths)
     return (prm, hist) if want_histogram else prm
 

@@ -73,6 +73,16 @@ def test_joint_tuner_and_ratio_gain(gpu, oracle):
     assert s8.size < s16.size
 
 
+def test_joint_tuner_respects_the_block_size(gpu, oracle):
+    """A tensor shorter than 4096 elements is compressed with blocks of 2048, which do not admit L = 32."""
+    w = np.full(3000, 0x3F80, np.uint16)                 # a constant tensor: Eq. 4 prefers the longest group
+    src = gpu.to_dev(w, BF16)
+    assert oracle.tune(w, lengths=(8, 16, 32))[3] == 32
+    prm = gpu.enec.tune(src, gpu.ws, lengths=(8, 16, 32))
+    assert prm[3] == 16 and prm == oracle.tune(w, lengths=(8, 16))
+    check_both_ways(gpu, oracle, w, prm, BF16, 0, "short constant tensor")
+
+
 def test_invalid_combinations_are_refused(gpu):
     torch, enec = gpu.torch, gpu.enec
     src = torch.zeros(1 << 16, dtype=torch.int16, device="cuda")
