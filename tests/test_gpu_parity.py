@@ -352,6 +352,48 @@ def test_decompress_variants_and_header_mismatch(gpu, oracle):
                                        n_elems=w.size) == enec.E_FORMAT
 
 
+def test_damaged_offset_table_skips_blocks_and_stays_in_bounds(gpu, oracle):
+    """Offsets come from the stream: entries that point outside it, go backwards, are misaligned or imply an
+    impossible size make the kernel leave that block's output alone; the other blocks are exact and nothing
+    outside the output tensor is written."""
+    torch, enec = gpu.torch, gpu.enec
+    B = 16384
+    w = W.gaussian(12 * B + 1000, 0.02, 98)
+    s = oracle.compress(w, oracle.tune(w), B)[1]
+    nb = 13
+    table = s[64:64 + 8 * (nb + 1)].view("<u8").copy()
+    damaged = {}
+    for k, how in ((2, "huge"), (5, "backwards"), (8, "misaligned"), (10, "too_long")):
+        t = table.copy()
+        if how == "huge":
+            t[k] = np.uint64(1) << np.uint64(40)
+        elif how == "backwards":
+            t[k + 1] = t[k] - np.uint64(16)
+        elif how == "misaligned":
+            t[k] += np.uint64(8)
+        else:
+            t[k + 1] = t[k] + np.uint64(4 * B)
+        damaged[how] = (k, t)
+    for how, (k, t) in damaged.items():
+        bad = s.copy()
+        bad[64:64 + 8 * (nb + 1)] = t.view(np.uint8)
+        buf = torch.from_numpy(bad).cuda()
+        out = torch.full((w.size + 64,), 0x5A5A, dtype=torch.int16, device="cuda")
+        assert enec.decompress_with_header(buf, bad[:64].tobytes(), out, n_elems=w.size) == 0
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().view(np.uint16)
+        assert (got[w.size:] == 0x5A5A).all(), how
+        # entry k starts block k and ends block k - 1; entry k + 1 ends block k and starts block k + 1
+        touched = {k, k - 1} if how in ("huge", "misaligned") else {k, k + 1}
+        for blk in range(nb):
+            seg = slice(blk * B, min(w.size, (blk + 1) * B))
+            if blk in touched:
+                assert (got[seg] == 0x5A5A).all() or np.array_equal(got[seg], w[seg]), (how, blk)
+            else:
+                assert np.array_equal(got[seg], w[seg]), (how, blk)
+        assert any((got[blk * B:min(w.size, (blk + 1) * B)] == 0x5A5A).all() for blk in touched), how
+
+
 def test_tuner_matches_oracle(gpu, oracle):
     cases = [W.config1(), W.gaussian(100003, 0.003, 5), np.zeros(70000, np.uint16),
              np.full(33333, 0x3D12, np.uint16), W.config3(n_blocks=64)[0],
