@@ -201,9 +201,9 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
 //                  their sizes; zero between calls.  Every block adds itself with one atomic; the
 //                  workgroup whose addition completes the group stores the group word and zeroes
 //                  the accumulator.  So a group word appears as soon as its last block is known
-//                  and no workgroup ever waits for blocks of its own generation (an owner that
-//                  polled its 63 neighbours turned the loop latency-bound as soon as the blocks
-//                  took equal time and the workgroups ran in lockstep).
+//                  and no workgroup ever waits for blocks of its own generation (a designated
+//                  owner polling the other blocks of its group turned the loop latency-bound as
+//                  soon as the blocks took equal time and the workgroups ran in lockstep).
 // The start of block k is the sum of the group words below its group plus the block words of the
 // earlier blocks of its own group: few words, read by one wave.
 //
