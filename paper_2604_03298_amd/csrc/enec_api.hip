@@ -434,10 +434,9 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         if (resident == 0) return ENEC_E_HIP;
         const unsigned grid = a.total < resident ? a.total : resident;
         a.ncls = grid < 8 ? grid : 8;
-        // The next ticket is drawn while the current block is worked on if the draw cannot take work
-        // away from a workgroup that has not started yet: enough blocks for two rounds, or none
-        // beyond the first round (then every draw only closes the books of its class).
-        a.lookahead = (a.total >= 2 * grid || a.total == grid) ? 1u : 0u;
+        // The next ticket is drawn while the current block is worked on only if there are blocks for
+        // two rounds: with fewer, an early workgroup would take the block of one that starts a moment later.
+        a.lookahead = a.total >= 2 * grid ? 1u : 0u;
         a.spin_limit = SPIN_LIMIT;
         if (const char *e = std::getenv("ENEC_SPIN_LIMIT")) {       // test aid: make a scan that cannot progress give up early
             const long v = std::atol(e);

@@ -221,11 +221,10 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
 // succeed at the first attempt and nobody spins on hot cache lines in the steady state.
 //
 // Control record of class c (WS_STRIDE words apart): [0] ticket counter, never reset; [1] value
-// of the counter when the current call started; [2..3] tag of the last finished call.  The first
-// block of each of the W workgroups of a class is implied (no draw), so a class with L >= W
-// blocks sees exactly L draws per call (L - W blocks and one draw beyond the end per workgroup):
-// the workgroup that receives draw number L - 1 knows that nobody will touch the record again in
-// this call and writes the next call's base and tag.
+// of the counter when the current call started; [2..3] tag of the last finished call.  A class
+// with L blocks and W workgroups sees exactly L + W draws per call (every workgroup draws until
+// its first draw beyond L), so the workgroup that receives draw number L + W - 1 knows that
+// nobody will touch the record again in this call and writes the next call's base and tag.
 // ---------------------------------------------------------------------------------
 constexpr uint64_t ST_ERR = 1ull << 23;
 constexpr uint64_t ST_VALUE = (1ull << 23) - 1;
@@ -405,44 +404,48 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     uint32_t ticket_base = 0, zero = 0;
     uint64_t tag0 = 0;
     bool drawing = true;
-    // The first block of a workgroup needs no draw: workgroup w starts with block w, which is
-    // ticket w / ncls of its class, so its rows are requested before the control record has even
-    // arrived.  Draw number d of a call (d = 0, 1, ...) is ticket class_wgs + d; the last draw of
-    // the class hands the record over to the next call.
+    // decode a draw; the last draw of the class hands the record over to the next call
     auto decode_draw = [&](uint32_t raw) -> uint32_t {
-        const uint32_t d = raw - ticket_base;
-        if (d == class_blocks - 1u) {
+        const uint32_t t = raw - ticket_base;
+        if (t == class_blocks + class_wgs - 1u) {
             ctl[1] = raw + 1u;
             for (uint32_t c = home; c < WS_CLASSES; c += p.ncls)
                 *reinterpret_cast<uint64_t *>(p.ws_ctl + WS_STRIDE * c + 2) = tag0;
         }
-        const uint32_t t = d + class_wgs;
         if (t >= class_blocks) { drawing = false; return NO_BLOCK; }
         return t * p.ncls + home;
     };
-    if (tid == 0) {
-        ticket_base = ctl[1];
-        tag0 = *reinterpret_cast<const uint64_t *>(ctl + 2) + 1u;
-    }
-    uint32_t k = blockIdx.x;                                 // global block index (the grid never exceeds the blocks)
     uint32_t slot = 0;
     // tensor that global block kg belongs to, searching upwards from item c
     auto item_of = [&](uint32_t kg, uint32_t c) -> uint32_t {
         while (c + 1u < p.n_items && kg >= p.item[c + 1u].first) ++c;
         return c;
     };
-    uint32_t ci = item_of(k, 0);                             // item of the current block
+    // Every block is drawn, also the first one: a workgroup that is dispatched late (the device may
+    // be shared with other kernels) must not own a block that running workgroups wait for.  When all
+    // workgroups start together, workgroup w draws block w, so its rows are requested on that guess
+    // while the control record and the draw are still travelling.
+    const uint32_t guess = blockIdx.x;                       // the grid never exceeds the number of blocks
+    uint32_t ci = item_of(guess, 0);
     uint4 raw[RW];
-    load_block_rows<DT>(p.item[ci], B, p.logB, k - p.item[ci].first, tid, active, logC, raw);
+    load_block_rows<DT>(p.item[ci], B, p.logB, guess - p.item[ci].first, tid, active, logC, raw);
     if (tid == 0) {
+        ticket_base = ctl[1];
+        tag0 = *reinterpret_cast<const uint64_t *>(ctl + 2) + 1u;
         // the record must have been read before this workgroup's first draw can be counted
         zero = ticket_base ^ (uint32_t)tag0;
         asm volatile("v_and_b32 %0, 0, %0" : "+v"(zero));
+        s_k[0] = decode_draw(atomicAdd(ctl + zero, 1u));
         s_tag = tag0;
         s_err[0] = s_err[1] = 0;
         s_status = 0;
     }
     __syncthreads();
+    uint32_t k = __builtin_amdgcn_readfirstlane(s_k[0]);     // global block index
+    if (k != guess && k != NO_BLOCK) {                       // the guess was wrong: ask again
+        ci = item_of(k, 0);
+        load_block_rows<DT>(p.item[ci], B, p.logB, k - p.item[ci].first, tid, active, logC, raw);
+    }
     const uint64_t tag = (uint64_t)s_tag << 24;
     constexpr HHTable TL = HH<MP>::table;
 
