@@ -275,6 +275,32 @@ def test_two_streams_two_workspaces(gpu, oracle):
             assert np.array_equal(backs[i].cpu().numpy().view(np.uint16), tensors[i]), (rep, i)
 
 
+def test_two_full_grids_at_once(gpu, oracle, monkeypatch):
+    """Two compressions whose persistent grids each fill the device run on two streams: the device cannot hold
+    both grids, workgroups of either kernel start late.  Every block is drawn from a ticket counter, so a late
+    workgroup never owns a block that running ones wait for.  (The wait bound is lowered so that a regression
+    would end in a header status within milliseconds instead of seconds.)"""
+    torch, enec = gpu.torch, gpu.enec
+    monkeypatch.setenv("ENEC_SPIN_LIMIT", "20000")
+    tensors = [W.gaussian(16384 * 1500 + 3, 0.02, 710), W.gaussian(16384 * 1300 + 11, 0.01, 711)]
+    params = [oracle.tune(t) for t in tensors]
+    refs = [oracle.compress(t, p, 16384)[1] for t, p in zip(tensors, params)]
+    srcs = [gpu.to_dev(t) for t in tensors]
+    outs = [torch.zeros(enec.compress_bound(t.size), dtype=torch.uint8, device="cuda") for t in tensors]
+    wss = [enec.new_workspace(t.size) for t in tensors]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for _ in range(3):                       # several launches per stream keep both queues busy
+            for i in range(2):
+                assert enec.compress(srcs[i], params[i], outs[i], wss[i], stream=streams[i]) == 0
+        torch.cuda.synchronize()
+        for i in range(2):
+            got = outs[i][:refs[i].size].cpu().numpy()
+            assert enec.stream_info(got[:64])["status"] == 0, (rep, i)
+            assert np.array_equal(got, refs[i]), (rep, i)
+
+
 def test_batch_entry_points(gpu, oracle):
     torch, enec = gpu.torch, gpu.enec
     rng = np.random.default_rng(123)
