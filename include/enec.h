@@ -186,6 +186,25 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
 int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params,
               uint64_t *histogram, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The tuner on a sample [Sec. V-E phase 1 counts exponents; a sample keeps the counting cheap]: only
+ * the elements whose index e has (e / 4096) % every == 0 are counted, i.e. every `every`-th chunk
+ * of 4096 elements, the first one included; every = 1 is enec_tune.  An exponent that the sample
+ * misses can fall outside the window of the tuple found: enec_compress then reports ENEC_E_RANGE in
+ * the header.  ENEC_E_ARG if every == 0; otherwise as enec_tune. */
+int enec_tune_sampled(const void *in, size_t n_elems, int dtype, uint32_t every, enec_params *params,
+                      uint64_t *histogram, void *workspace, size_t workspace_bytes, void *stream);
+
+/* enec_tune_sampled, then enec_compress with the tuple found; if the kernel reports ENEC_E_RANGE the
+ * tensor is compressed once more with n widened to the exponent field's width, for which the
+ * transform is a bijection and no exponent is out of range [Sec. V-C]; b, m and L stay.
+ *   params_used  HOST, may be NULL: the tuple of the stream that `out` holds on return
+ * Other arguments as for enec_compress.  Synchronous (the header's status is read back after each
+ * pass).  Returns ENEC_OK, or what enec_tune_sampled / enec_compress return, or the header's status
+ * if it is neither ENEC_OK nor ENEC_E_RANGE. */
+int enec_compress_sampled(const void *in, size_t n_elems, int dtype, uint32_t block_size, uint32_t every,
+                          enec_params *params_used, void *out, size_t out_capacity, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
 /* Host-only search of Sec. V-E phases 2-3 on a given 256-bin exponent histogram (HOST); dtype
  * fixes the cap of Eq. 1's width (the exponent field: 8 bits, fp16: 5). */
 int enec_tune_histogram(const uint64_t *histogram, int dtype, enec_params *params);

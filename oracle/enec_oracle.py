@@ -206,6 +206,29 @@ def tune(w, dtype: int = BF16, lengths=None):
     return tune_hist_groups(histogram(w, dtype), exp_bits(dtype), lengths)[0]
 
 
+SAMPLE_CHUNK = 4096
+
+
+def sample(w, every: int, dtype: int = BF16) -> np.ndarray:
+    """The elements a sampled tuner looks at: index e with (e // 4096) % every == 0, in order."""
+    w = _words(w, dtype)
+    e = np.arange(w.size, dtype=np.int64)
+    return w[(e // SAMPLE_CHUNK) % every == 0]
+
+
+def compress_sampled(w, every: int, B: int = 16384, dtype: int = BF16):
+    """Sec. V-E on the sample, then the codec; if an exponent the sample missed is out of range, once more
+    with n = width of the exponent field, where the transform is a bijection (Sec. V-C).
+    -> (tuple used, status, stream)"""
+    w = _words(w, dtype)
+    prm = tune(sample(w, every, dtype), dtype)
+    rc, s = compress(w, prm, B, dtype=dtype)
+    if rc == E_RANGE:
+        prm = (prm[0], exp_bits(dtype), prm[2], prm[3])
+        rc, s = compress(w, prm, B, dtype=dtype)
+    return prm, rc, s
+
+
 def default_block(n_elems: int) -> int:
     return int(lib().orc_default_block(n_elems))
 

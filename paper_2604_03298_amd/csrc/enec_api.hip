@@ -313,13 +313,13 @@ int enec_tune_histogram_groups(const uint64_t *hist, int dtype, uint32_t group_l
     return ENEC_OK;
 }
 
-int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params, uint64_t *histogram,
-              void *workspace, size_t workspace_bytes, void *stream)
+int enec_tune_sampled(const void *in, size_t n_elems, int dtype, uint32_t every, enec_params *params,
+                      uint64_t *histogram, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
     if (workspace_bytes < WS_STATE) return ENEC_E_CAPACITY;
     if (!params || !workspace || (!in && n_elems) || !aligned16(in) || !aligned16(workspace) ||
-        n_elems > MAX_ELEMS)
+        n_elems > MAX_ELEMS || every == 0)
         return ENEC_E_ARG;
     hipStream_t s = (hipStream_t)stream;
     uint64_t host_hist[256];
@@ -328,17 +328,50 @@ int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params, ui
         auto *dhist = reinterpret_cast<unsigned long long *>(static_cast<uint8_t *>(workspace) + WS_HIST);
         fill_zero_kernel<<<1, 256, 0, s>>>(reinterpret_cast<uint4 *>(dhist), 256 * 8 / 16);
         const uint64_t nvec = n_elems * elem_bytes(dtype) / 16;
-        uint64_t want = (nvec + 255) / 256;
+        uint64_t want = (nvec / every + 255) / 256;
         const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
-        if (dtype == ENEC_FP32) histogram_kernel<DT_FP32><<<grid, 256, 0, s>>>(in, n_elems, dhist);
-        else if (dtype == ENEC_FP16) histogram_kernel<DT_FP16><<<grid, 256, 0, s>>>(in, n_elems, dhist);
-        else histogram_kernel<DT_BF16><<<grid, 256, 0, s>>>(in, n_elems, dhist);
+        if (dtype == ENEC_FP32) histogram_kernel<DT_FP32><<<grid, 256, 0, s>>>(in, n_elems, dhist, every);
+        else if (dtype == ENEC_FP16) histogram_kernel<DT_FP16><<<grid, 256, 0, s>>>(in, n_elems, dhist, every);
+        else histogram_kernel<DT_BF16><<<grid, 256, 0, s>>>(in, n_elems, dhist, every);
         if (hipMemcpyAsync(host_hist, dhist, sizeof host_hist, hipMemcpyDeviceToHost, s) != hipSuccess ||
             hipStreamSynchronize(s) != hipSuccess)
             return ENEC_E_HIP;
     }
     if (histogram) std::memcpy(histogram, host_hist, sizeof host_hist);
     return enec_tune_histogram(host_hist, dtype, params);
+}
+
+int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params, uint64_t *histogram,
+              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return enec_tune_sampled(in, n_elems, dtype, 1, params, histogram, workspace, workspace_bytes, stream);
+}
+
+int enec_compress_sampled(const void *in, size_t n_elems, int dtype, uint32_t block_size, uint32_t every,
+                          enec_params *params_used, void *out, size_t out_capacity, void *workspace,
+                          size_t workspace_bytes, void *stream)
+{
+    enec_params prm;
+    int rc = enec_tune_sampled(in, n_elems, dtype, every, &prm, nullptr, workspace, workspace_bytes, stream);
+    if (rc != ENEC_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        rc = enec_compress(in, n_elems, dtype, block_size, &prm, out, out_capacity, nullptr, workspace,
+                           workspace_bytes, stream);
+        if (rc != ENEC_OK) return rc;
+        uint8_t head[ENEC_HEADER_BYTES];
+        if (hipMemcpyAsync(head, out, sizeof head, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            return ENEC_E_HIP;
+        uint32_t status = 0;
+        rc = enec_stream_info(head, nullptr, nullptr, nullptr, nullptr, nullptr, &status);
+        if (rc != ENEC_OK) return rc;
+        if (params_used) *params_used = prm;
+        if (status != (uint32_t)ENEC_E_RANGE) return (int)status;
+        // an exponent outside the sample's window: the full width makes the map a bijection [Sec. V-C]
+        prm.n = (uint8_t)exp_bits(dtype);
+    }
+    return ENEC_E_RANGE;   // not reached: the full width has no range error
 }
 
 int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,

@@ -1273,10 +1273,13 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
 }
 
 // ---------------------------------------------------------------------------------
-// exponent histogram (Sec. V-E phase 1)
+// exponent histogram (Sec. V-E phase 1), of the whole tensor (every = 1) or of a sample of it
 // ---------------------------------------------------------------------------------
+constexpr uint32_t SAMPLE_CHUNK = 4096;     // elements; the sample is taken in whole chunks
+
 template <int DT>
-__global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_t n_elems, unsigned long long *hist)
+__global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_t n_elems, unsigned long long *hist,
+                                                        uint32_t every)
 {
     __shared__ uint32_t s_h[4][256];
     const uint32_t tid = threadIdx.x;
@@ -1288,7 +1291,13 @@ __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_
     const uint64_t stride = (uint64_t)gridDim.x * 256u;
     // a wave's LDS counters cannot overflow: each thread adds at most 8 per iteration and the
     // launch keeps iterations * 64 * 8 below 2^32
-    for (uint64_t v = (uint64_t)blockIdx.x * 256u + tid; v < nvec; v += stride) {
+    // the sample: chunks of SAMPLE_CHUNK elements whose number is a multiple of `every`
+    constexpr uint32_t LOG_VPC = DT == DT_FP32 ? 10u : 9u;      // 16-byte vectors in a chunk
+    const uint64_t chunks = (nvec + (1u << LOG_VPC) - 1u) >> LOG_VPC;
+    const uint64_t picked = ((chunks + every - 1u) / every) << LOG_VPC;
+    for (uint64_t sv = (uint64_t)blockIdx.x * 256u + tid; sv < picked; sv += stride) {
+        const uint64_t v = (((sv >> LOG_VPC) * every) << LOG_VPC) + (sv & ((1u << LOG_VPC) - 1u));
+        if (v >= nvec) continue;
         const uint4 q = reinterpret_cast<const uint4 *>(in_)[v];
         const uint32_t d[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
@@ -1304,7 +1313,7 @@ __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_
             }
         }
     }
-    if (blockIdx.x == 0 && tid < (uint32_t)(n_elems % PER_VEC)) {
+    if (blockIdx.x == 0 && tid < (uint32_t)(n_elems % PER_VEC) && ((nvec * PER_VEC) / SAMPLE_CHUNK) % every == 0) {
         const uint64_t e = nvec * PER_VEC + tid;
         uint32_t x;
         if constexpr (DT == DT_FP32) x = (reinterpret_cast<const uint32_t *>(in_)[e] >> 23) & 0xFFu;

@@ -23,6 +23,7 @@ EXPORTS = [
     "enec_workspace_bytes", "enec_workspace_init", "enec_compress", "enec_decompress",
     "enec_decompress_with_header", "enec_tune", "enec_tune_histogram", "enec_stream_info",
     "enec_copy", "enec_compress_batch", "enec_decompress_batch", "enec_tune_histogram_groups",
+    "enec_tune_sampled", "enec_compress_sampled",
 ]
 
 
@@ -83,6 +84,11 @@ def lib():
         L.enec_decompress_with_header.argtypes = [vp, sz, vp, vp, sz, vp]
         L.enec_tune.restype = C.c_int
         L.enec_tune.argtypes = [vp, sz, C.c_int, C.POINTER(Params), u64p, vp, sz, vp]
+        L.enec_tune_sampled.restype = C.c_int
+        L.enec_tune_sampled.argtypes = [vp, sz, C.c_int, C.c_uint32, C.POINTER(Params), u64p, vp, sz, vp]
+        L.enec_compress_sampled.restype = C.c_int
+        L.enec_compress_sampled.argtypes = [vp, sz, C.c_int, C.c_uint32, C.c_uint32, C.POINTER(Params), vp, sz,
+                                            vp, sz, vp]
         L.enec_tune_histogram.restype = C.c_int
         L.enec_tune_histogram.argtypes = [u64p, C.c_int, C.POINTER(Params)]
         L.enec_tune_histogram_groups.restype = C.c_int
@@ -284,6 +290,30 @@ def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int |
         lengths = [v for v in lengths if 128 * v <= B <= 2048 * v] or [16]
     prm = p.astuple() if lengths is None else tune_histogram(hist, dt, lengths)
     return (prm, hist) if want_histogram else prm
+
+
+def tune_sampled(src, every: int, workspace, stream=None, dtype: int | None = None, want_histogram: bool = False):
+    """(b, n, m, 16) from the exponents of every `every`-th chunk of 4096 elements; synchronous."""
+    p = Params()
+    hist = np.zeros(256, dtype=np.uint64)
+    _check(lib().enec_tune_sampled(C.c_void_p(src.data_ptr()), src.numel(), dtype_of(src, dtype), every,
+                                   C.byref(p), hist.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                   C.c_void_p(workspace.data_ptr()),
+                                   workspace.numel() * workspace.element_size(), _stream_handle(stream)),
+           "enec_tune_sampled")
+    return (p.astuple(), hist) if want_histogram else p.astuple()
+
+
+def compress_sampled(src, every: int, out, workspace, block_size: int = 0, stream=None,
+                     dtype: int | None = None):
+    """Tunes on a sample, compresses, and compresses again with the full exponent width if the sample
+    missed an exponent.  Synchronous.  -> (status, tuple of the stream in `out`)."""
+    p = Params()
+    rc = int(lib().enec_compress_sampled(
+        C.c_void_p(src.data_ptr()), src.numel(), dtype_of(src, dtype), block_size, every, C.byref(p),
+        C.c_void_p(out.data_ptr()), out.numel() * out.element_size(), C.c_void_p(workspace.data_ptr()),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+    return rc, p.astuple()
 
 
 def copy(dst, src, nbytes: int | None = None, stream=None) -> int:

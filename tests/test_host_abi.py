@@ -125,6 +125,7 @@ def test_null_and_misaligned_arguments_are_rejected_on_the_host(enec):
     assert L.enec_workspace_init(fake, 17, None) == enec.E_ARG
     assert L.enec_copy(fake, odd, 16, None) == enec.E_ARG
     assert L.enec_tune_histogram(None, 0, ctypes.byref(p)) == enec.E_ARG
+    assert L.enec_tune_sampled(fake, 10, 0, 0, ctypes.byref(p), None, fake, 1 << 20, None) == enec.E_ARG
     for dt, bad in ((1, (10, 6, 2, 16)), (1, (40, 4, 2, 16)), (2, (122, 9, 3, 16)), (0, (122, 6, 3, 12)), (0, (122, 6, 3, 64))):
         q = enec.Params(*bad)
         assert L.enec_compress(fake, 10, dt, 0, ctypes.byref(q), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_PARAMS
