@@ -430,6 +430,19 @@ size_t orc_payload_base_dt(size_t n_elems, uint32_t B, int dtype)
 
 size_t orc_payload_base(size_t n_elems, uint32_t B) { return orc_payload_base_dt(n_elems, B, ORC_BF16); }
 
+/* A stream with one tuple per data block keeps them, four bytes each (b, n, m, 0),
+ * block order, zeros to a multiple of 16, right behind the offset table; the fp32
+ * region and the payloads follow. */
+size_t orc_tuple_table_bytes(size_t n_elems, uint32_t B)
+{
+    return align16(4u * orc_num_blocks(n_elems, B));
+}
+
+size_t orc_payload_base_pb(size_t n_elems, uint32_t B, int dtype)
+{
+    return orc_payload_base_dt(n_elems, B, dtype) + orc_tuple_table_bytes(n_elems, B);
+}
+
 /* Worst case for any group length: every group anomalous with n = 8 (bf16, fp32:
  * B raw bytes + B bytes of planes) or n = 5 (fp16: B raw bytes + (5+3)B/8
  * bytes of planes), and the longest mask (L = 8: B/64 bytes). */
@@ -441,6 +454,11 @@ size_t orc_compress_bound_dt(size_t n_elems, uint32_t B, int dtype)
 }
 
 size_t orc_compress_bound(size_t n_elems, uint32_t B) { return orc_compress_bound_dt(n_elems, B, ORC_BF16); }
+
+size_t orc_compress_bound_pb(size_t n_elems, uint32_t B, int dtype)
+{
+    return orc_compress_bound_dt(n_elems, B, dtype) + orc_tuple_table_bytes(n_elems, B);
+}
 
 static void put_u16(uint8_t *p, uint16_t v) { p[0] = (uint8_t)v; p[1] = (uint8_t)(v >> 8); }
 static void put_u32(uint8_t *p, uint32_t v) { int i; for (i = 0; i < 4; i++) p[i] = (uint8_t)(v >> (8 * i)); }
@@ -501,12 +519,12 @@ static void write_header(uint8_t *out, size_t n_elems, int dtype, uint32_t B, si
  * A value outside the representable window gives ORC_E_RANGE: the header is
  * still written, with status = ORC_E_RANGE and total_bytes = 0, *out_bytes = 0.
  */
-int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const uint8_t params[4],
-                    uint8_t *out, size_t capacity, size_t *out_bytes)
+static int compress_core(const void *in, size_t n_elems, int dtype, uint32_t B, const uint8_t params[4],
+                         int per_block, uint8_t *out, size_t capacity, size_t *out_bytes)
 {
     unsigned b, n, m, a, E, lowbits, L;
     size_t nb, base, k, off = 0, G, e, rb;
-    uint8_t *sm, *maskbytes, rec[80];
+    uint8_t *sm, *maskbytes, rec[80], *tuples = NULL;
     uint16_t *y, *rest, *tmp;
     int range_error = 0;
 
@@ -515,17 +533,21 @@ int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const
     if (!block_ok(B)) return ORC_E_BLOCK;
     E = orc_exp_bits(dtype);
     b = params[0]; n = params[1]; m = params[2]; L = params[3];
-    if (n < 1 || n > E || m > n || b >= (1u << E) || !group_ok(L) || B < 8u * L) return ORC_E_PARAMS;
-    if (capacity < orc_compress_bound_dt(n_elems, B, dtype)) return ORC_E_CAPACITY;
-    a = n - m;
-    rb = (size_t)a * L / 8u;                 /* bytes of one high record */
-    lowbits = m + (dtype == ORC_FP16 ? 3u : 0u);
+    if (!group_ok(L) || B < 8u * L) return ORC_E_PARAMS;
+    if (!per_block && (n < 1 || n > E || m > n || b >= (1u << E))) return ORC_E_PARAMS;
+    if (capacity < (per_block ? orc_compress_bound_pb(n_elems, B, dtype) : orc_compress_bound_dt(n_elems, B, dtype)))
+        return ORC_E_CAPACITY;
     nb = orc_num_blocks(n_elems, B);
-    base = orc_payload_base_dt(n_elems, B, dtype);
+    base = per_block ? orc_payload_base_pb(n_elems, B, dtype) : orc_payload_base_dt(n_elems, B, dtype);
     G = B / L;
     memset(out, 0, base);
+    if (per_block) tuples = out + orc_table_end(n_elems, B);
+    if (dtype == ORC_FP32 && per_block) {
+        uint8_t *t = out + orc_table_end(n_elems, B) + orc_tuple_table_bytes(n_elems, B);
+        for (e = 0; e < n_elems; e++) put_u16(t + 2 * e, (uint16_t)(load_elem(in, e, dtype) & 0xFFFFu));
+    }
 
-    if (dtype == ORC_FP32) {
+    if (dtype == ORC_FP32 && !per_block) {
         uint8_t *t = out + orc_table_end(n_elems, B);
         for (e = 0; e < n_elems; e++) put_u16(t + 2 * e, (uint16_t)(load_elem(in, e, dtype) & 0xFFFFu));
     }
@@ -539,6 +561,20 @@ int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const
     for (k = 0; k < nb; k++) {
         uint8_t *p = out + base + off;
         size_t pos = 0, i, g;
+        if (per_block) {
+            /* Sec. V-E on the exponents of this block's own elements */
+            uint8_t t[4];
+            size_t first = k * (size_t)B, count = n_elems - first < B ? n_elems - first : B;
+            uint64_t hist[256];
+            const uint8_t *src = (const uint8_t *)in + first * orc_elem_bytes(dtype);
+            orc_histogram_dt(src, count, dtype, hist);
+            orc_tune_hist_e(hist, E, t, NULL, NULL);
+            b = t[0]; n = t[1]; m = t[2];
+            tuples[4 * k] = t[0]; tuples[4 * k + 1] = t[1]; tuples[4 * k + 2] = t[2];
+        }
+        a = n - m;
+        rb = (size_t)a * L / 8u;                 /* bytes of one high record */
+        lowbits = m + (dtype == ORC_FP16 ? 3u : 0u);
         /* split + transform */
         for (i = 0; i < B; i++) {
             e = k * (size_t)B + i;
@@ -595,8 +631,28 @@ int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const
         return ORC_E_RANGE;
     }
     write_header(out, n_elems, dtype, B, nb, params, ORC_OK, (uint64_t)(base + off));
+    if (per_block) out[40] = 1;
     *out_bytes = base + off;
     return ORC_OK;
+}
+
+int orc_compress_dt(const void *in, size_t n_elems, int dtype, uint32_t B, const uint8_t params[4],
+                    uint8_t *out, size_t capacity, size_t *out_bytes)
+{
+    return compress_core(in, n_elems, dtype, B, params, 0, out, capacity, out_bytes);
+}
+
+/* One tuple per data block: block k is coded with the (b, n, m) that Sec. V-E's
+ * search returns for the exponents of its own elements (the pad elements of the
+ * last block are not counted), so no exponent is ever out of range.  Header:
+ * byte 40 = 1, and (b, n, m) = (0, 0, 0); n = 0 occurs in no other stream.
+ * The tuples sit behind the offset table (see orc_tuple_table_bytes). */
+int orc_compress_pb(const void *in, size_t n_elems, int dtype, uint32_t B, unsigned L,
+                    uint8_t *out, size_t capacity, size_t *out_bytes)
+{
+    uint8_t params[4] = {0, 0, 0, 0};
+    params[3] = (uint8_t)L;
+    return compress_core(in, n_elems, dtype, B, params, 1, out, capacity, out_bytes);
 }
 
 int orc_compress(const uint16_t *in, size_t n_elems, uint32_t B, const uint8_t params[4],
@@ -623,6 +679,9 @@ int orc_stream_info_dt(const uint8_t *hdr, uint8_t params[4], uint64_t *n_elems,
     return ORC_OK;
 }
 
+/* 1 if the stream carries one tuple per data block, 0 if one tuple for all. */
+int orc_stream_per_block(const uint8_t *hdr) { return hdr && hdr[40] == 1; }
+
 /* The bf16-only form: any other dtype in the header is ORC_E_DTYPE. */
 int orc_stream_info(const uint8_t *hdr, uint8_t params[4], uint64_t *n_elems, uint32_t *B,
                     uint64_t *total, uint32_t *status)
@@ -643,24 +702,28 @@ int orc_decompress_dt(const uint8_t *in, size_t in_bytes, void *out, size_t n_el
     size_t nb, base, k, G, rb;
     uint16_t *low, *high, *prefix;
     uint8_t rec[80];
-    const uint8_t *tail16;
-    int rc, dtype;
+    const uint8_t *tail16, *tuples;
+    int rc, dtype, per_block;
 
     if (!in || (!out && n_elems) || in_bytes < ORC_HEADER) return ORC_E_ARG;
     rc = orc_stream_info_dt(in, params, &hdr_n, &B, &total, &status, &dtype);
     if (rc != ORC_OK) return rc;
     if (status != ORC_OK || hdr_n != (uint64_t)n_elems || !block_ok(B)) return ORC_E_FORMAT;
     E = orc_exp_bits(dtype);
+    per_block = orc_stream_per_block(in);
     b = params[0]; n = params[1]; m = params[2]; L = params[3];
-    if (n < 1 || n > E || m > n || B < 8u * L) return ORC_E_FORMAT;
-    a = n - m;
-    rb = (size_t)a * L / 8u;
-    lowbits = m + (dtype == ORC_FP16 ? 3u : 0u);
+    if (B < 8u * L) return ORC_E_FORMAT;
+    if (!per_block && (n < 1 || n > E || m > n)) return ORC_E_FORMAT;
     nb = orc_num_blocks(n_elems, B);
-    base = orc_payload_base_dt(n_elems, B, dtype);
+    base = per_block ? orc_payload_base_pb(n_elems, B, dtype) : orc_payload_base_dt(n_elems, B, dtype);
     if (get_u32(in + 20) != (uint32_t)nb || total > in_bytes || total < base) return ORC_E_FORMAT;
     G = B / L;
-    tail16 = in + orc_table_end(n_elems, B);
+    tuples = in + orc_table_end(n_elems, B);
+    tail16 = tuples + (per_block ? orc_tuple_table_bytes(n_elems, B) : 0);
+    if (per_block)
+        for (k = 0; k < nb; k++)
+            if (tuples[4 * k + 1] < 1 || tuples[4 * k + 1] > E || tuples[4 * k + 2] > tuples[4 * k + 1])
+                return ORC_E_FORMAT;
 
     low = (uint16_t *)malloc(B * sizeof(uint16_t));
     high = (uint16_t *)malloc(L * sizeof(uint16_t));
@@ -672,8 +735,13 @@ int orc_decompress_dt(const uint8_t *in, size_t in_bytes, void *out, size_t n_el
         const uint8_t *sm = p;
         const uint8_t *maskbytes = p + B;
         const uint8_t *lowplane = maskbytes + G / 8;
-        const uint8_t *highplane = lowplane + (size_t)lowbits * B / 8;
+        const uint8_t *highplane;
         size_t i, g;
+        if (per_block) { b = tuples[4 * k]; n = tuples[4 * k + 1]; m = tuples[4 * k + 2]; }
+        a = n - m;
+        rb = (size_t)a * L / 8u;
+        lowbits = m + (dtype == ORC_FP16 ? 3u : 0u);
+        highplane = lowplane + (size_t)lowbits * B / 8;
         /* mask bits -> {0,1} integers -> exclusive prefix sum = record index */
         prefix[0] = 0;
         for (g = 0; g < G; g++)

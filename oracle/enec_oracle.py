@@ -101,6 +101,17 @@ def lib():
                                          C.POINTER(C.c_uint32), C.POINTER(C.c_int)]
         L.orc_decompress_dt.restype = C.c_int
         L.orc_decompress_dt.argtypes = [u8p, C.c_size_t, C.c_void_p, C.c_size_t]
+        L.orc_tuple_table_bytes.restype = C.c_size_t
+        L.orc_tuple_table_bytes.argtypes = [C.c_size_t, C.c_uint32]
+        L.orc_payload_base_pb.restype = C.c_size_t
+        L.orc_payload_base_pb.argtypes = [C.c_size_t, C.c_uint32, C.c_int]
+        L.orc_compress_bound_pb.restype = C.c_size_t
+        L.orc_compress_bound_pb.argtypes = [C.c_size_t, C.c_uint32, C.c_int]
+        L.orc_compress_pb.restype = C.c_int
+        L.orc_compress_pb.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_uint32, C.c_uint, u8p, C.c_size_t,
+                                      C.POINTER(C.c_size_t)]
+        L.orc_stream_per_block.restype = C.c_int
+        L.orc_stream_per_block.argtypes = [u8p]
         _lib = L
     return _lib
 
@@ -265,6 +276,34 @@ def compress(w, params, B: int = 16384, capacity: int | None = None, dtype: int 
     return rc, None
 
 
+def payload_base_pb(n_elems: int, B: int, dtype: int = BF16) -> int:
+    return int(lib().orc_payload_base_pb(n_elems, B, dtype))
+
+
+def compress_bound_pb(n_elems: int, B: int, dtype: int = BF16) -> int:
+    return int(lib().orc_compress_bound_pb(n_elems, B, dtype))
+
+
+def compress_per_block(w, B: int = 16384, dtype: int = BF16, L: int = 16):
+    """One tuned (b, n, m) per data block -> (status, stream bytes as uint8 array)."""
+    w = _words(w, dtype)
+    cap = compress_bound_pb(w.size, B, dtype)
+    out = np.zeros(max(cap, 1), dtype=np.uint8)
+    nbytes = C.c_size_t(0)
+    rc = lib().orc_compress_pb(w.ctypes.data, w.size, dtype, B, L, _p(out, C.c_uint8), cap, C.byref(nbytes))
+    return rc, (out[:nbytes.value].copy() if rc == OK else None)
+
+
+def block_tuples(stream) -> list:
+    """The (b, n, m) of every data block of a stream that carries one tuple per block."""
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    info = stream_info(s)
+    assert info["per_block"]
+    nb = num_blocks(info["n_elems"], info["block_size"])
+    at = table_end(info["n_elems"], info["block_size"])
+    return [tuple(int(v) for v in s[at + 4 * k:at + 4 * k + 3]) for k in range(nb)]
+
+
 def stream_info(stream) -> dict:
     s = np.ascontiguousarray(stream, dtype=np.uint8)
     params = np.zeros(4, dtype=np.uint8)
@@ -277,7 +316,7 @@ def stream_info(stream) -> dict:
                                   C.byref(total), C.byref(status), C.byref(dt))
     return dict(rc=rc, params=tuple(int(v) for v in params), n_elems=int(n.value),
                 block_size=int(B.value), total_bytes=int(total.value), status=int(status.value),
-                dtype=int(dt.value))
+                dtype=int(dt.value), per_block=bool(s.size > 40 and lib().orc_stream_per_block(_p(s, C.c_uint8))))
 
 
 def decompress(stream, n_elems: int):

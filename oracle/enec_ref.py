@@ -184,23 +184,31 @@ def _align16(v):
     return (v + 15) & ~15
 
 
-def compress(words, params, B, dtype=0):
+def compress(words, params, B, dtype=0, per_block=False):
     """-> (range_ok, bytes).  fp16: the three left-over mantissa bits sit on top of the low
-    m bits in the low plane; fp32: the sixteen left-over bits of all elements follow the table."""
+    m bits in the low plane; fp32: the sixteen left-over bits of all elements follow the table.
+    per_block: params = (0, 0, 0, L) and every block is coded with the tuple tuned on its own
+    exponents; the tuples follow the offset table, four bytes each."""
     b, n, m, L = params
     E = FIELDS[dtype][0]
-    assert L in (8, 16, 32) and B >= 8 * L and 1 <= n <= E and 0 <= m <= n
-    a = n - m
-    rb = a * L // 8                      # a record without the pad byte Alg. 2 adds to an odd count
+    assert L in (8, 16, 32) and B >= 8 * L and (per_block or (1 <= n <= E and 0 <= m <= n))
     words = [int(w) for w in words]
     N = len(words)
     nb = (N + B - 1) // B
     G = B // L
-    payloads, offsets, ok = [], [0], True
+    payloads, offsets, ok, tuples = [], [0], True, b""
     for k in range(nb):
         blk = list(words[k * B:(k + 1) * B])
         real = len(blk)
         parts = [take_apart(w, dtype) for w in blk]
+        if per_block:
+            hist = [0] * 256
+            for part in parts:
+                hist[part[0]] += 1
+            b, n, m, _ = tune_hist(hist, E)[0]
+            tuples += bytes([b, n, m, 0])
+        a = n - m
+        rb = a * L // 8                  # a record without the pad byte Alg. 2 adds to an odd count
         sm = [p[1] for p in parts] + [0] * (B - real)
         rest = [p[2] for p in parts] + [0] * (B - real)
         xs = [p[0] for p in parts]
@@ -225,15 +233,18 @@ def compress(words, params, B, dtype=0):
     if dtype == 2:
         tail = b"".join(struct.pack("<H", take_apart(w, dtype)[2]) for w in words)
         tail += bytes(_align16(len(tail)) - len(tail))
-    base = _align16(HEADER + 8 * (nb + 1)) + len(tail)
+    tuples += bytes(_align16(len(tuples)) - len(tuples))
+    base = _align16(HEADER + 8 * (nb + 1)) + len(tuples) + len(tail)
     total = base + offsets[-1]
     status = 0 if ok else 6
-    hdr = struct.pack("<4sHBBQIIBBBBIQ", b"ENEC", 1, dtype, L, N, B, nb, b, n, m, E, status,
-                      total if ok else 0)
+    if per_block:
+        b = n = m = 0
+    hdr = struct.pack("<4sHBBQIIBBBBIQB", b"ENEC", 1, dtype, L, N, B, nb, b, n, m, E, status,
+                      total if ok else 0, 1 if per_block else 0)
     hdr += bytes(HEADER - len(hdr))
     table = b"".join(struct.pack("<Q", o) for o in offsets)
     head = hdr + table
-    head += bytes(_align16(len(head)) - len(head)) + tail
+    head += bytes(_align16(len(head)) - len(head)) + tuples + tail
     return ok, head + b"".join(payloads)
 
 
@@ -243,14 +254,18 @@ def decompress(stream, N):
         "<4sHBBQIIBBBBIQ", stream, 0)
     assert magic == b"ENEC" and ver == 1 and dtype in FIELDS and L in (8, 16, 32) and ebits == FIELDS[dtype][0]
     assert n_elems == N and status == 0
-    a = n - m
-    rb = a * L // 8
+    per_block = stream[40] == 1
     G = B // L
-    tail_at = _align16(HEADER + 8 * (nb + 1))
+    tuples_at = _align16(HEADER + 8 * (nb + 1))
+    tail_at = tuples_at + (_align16(4 * nb) if per_block else 0)
     base = tail_at + (_align16(2 * N) if dtype == 2 else 0)
-    lowbits = m + (3 if dtype == 1 else 0)
     out = []
     for k in range(nb):
+        if per_block:
+            b, n, m = stream[tuples_at + 4 * k:tuples_at + 4 * k + 3]
+        a = n - m
+        rb = a * L // 8
+        lowbits = m + (3 if dtype == 1 else 0)
         off = struct.unpack_from("<Q", stream, HEADER + 8 * k)[0]
         p = stream[base + off:]
         sm = p[:B]

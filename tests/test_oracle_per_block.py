@@ -1,0 +1,142 @@
+"""Pins of the oracle's streams with one tuple per data block (CPU only).
+
+The paper tunes one tuple per tensor (Sec. V-E) and finds that tensors differ (Table VI); a tuple per data
+block applies the same search to each block's own exponents.  Pinned without trusting the new code path:
+a stream worked by hand, the reduction of every block's payload to the (pinned) one-tuple codec applied to
+that block alone, the pure-Python twin, round trips, the size accounting.
+"""
+import struct
+
+import numpy as np
+import pytest
+
+from conftest import golden_lines
+from paper_2604_03298_amd import workloads as W
+
+BF16, FP16, FP32 = 0, 1, 2
+
+
+def test_two_blocks_worked_by_hand(oracle, ref):
+    g = dict(ln.split(None, 1) for ln in golden_lines("two_blocks_per_block_tuples_handworked.txt"))
+    w = np.full(256, 0x3D00, np.uint16)
+    w[:128] = 0x3C00
+    w[128 + 5], w[128 + 40] = 0x3E80, 0xBC05
+    rc, s = oracle.compress_per_block(w, 128)
+    assert rc == oracle.OK and s.size == int(g["stream_bytes"])
+    base = int(g["payload_base"])
+    assert oracle.payload_base_pb(256, 128) == base
+    assert list(struct.unpack_from("<3Q", s.tobytes(), 64)) == [int(v) for v in g["offset_table"].split()]
+    assert [int(v) for v in s[24:28]] == [int(v) for v in g["header_b_n_m_expbits"].split()]
+    assert int(s[40]) == int(g["header_byte_40"]) and (s[41:64] == 0).all()
+    assert s[96:112].tobytes() == bytes(int(h, 16) for h in g["tuple_table"].split())
+    assert struct.unpack_from("<Q", s.tobytes(), 32)[0] == 400
+    p0, p1 = s[base:base + 144], s[base + 144:]
+    assert (p0 == 0).all()
+    sm = np.zeros(128, np.uint8)
+    for tok in g["block1_sm_nonzero"].split():
+        i, v = tok.split(":")
+        sm[int(i)] = int(v, 16)
+    assert (p1[:128] == sm).all()
+    assert int(p1[128]) == int(g["block1_mask_byte"], 16)
+    assert p1[129:141].tobytes() == bytes(int(h, 16) for h in g["block1_high_records"].split())
+    assert (p1[141:] == 0).all()
+    assert oracle.block_tuples(s) == [(120, 1, 0), (122, 3, 0)]
+    info = oracle.stream_info(s)
+    assert info["per_block"] and info["params"] == (0, 0, 0, 16)
+    rc, d = oracle.decompress(s, 256)
+    assert rc == oracle.OK and (d == w).all()
+    ok, s2 = ref.compress(w, (0, 0, 0, 16), 128, per_block=True)
+    assert ok and s2 == s.tobytes()
+    assert ref.decompress(s.tobytes(), 256) == [int(v) for v in w]
+
+
+def _mixed(n_blocks, B, seed):
+    """Blocks of four kinds in a seeded order: zeros, one repeated value, heavy-tailed, uniform bits."""
+    rng = np.random.default_rng(seed)
+    out = np.empty(n_blocks * B, np.uint16)
+    for k in range(n_blocks):
+        kind = int(rng.integers(0, 4))
+        blk = out[k * B:(k + 1) * B]
+        if kind == 0:
+            blk[:] = 0
+        elif kind == 1:
+            blk[:] = W.gaussian(1, 0.02, seed + k)[0]
+        elif kind == 2:
+            blk[:] = W.gaussian(B, 0.02 * (1 + k % 5), seed + k)
+        else:
+            blk[:] = rng.integers(0, 65536, B)
+    return out
+
+
+@pytest.mark.parametrize("dtype", [BF16, FP16, FP32])
+@pytest.mark.parametrize("L", [8, 16, 32])
+def test_every_payload_is_the_one_tuple_codec_on_that_block(oracle, dtype, L):
+    B = 256
+    if dtype == BF16:
+        w = _mixed(9, B, 5)[:9 * B - 37]
+    elif dtype == FP16:
+        w = np.concatenate([W.gaussian_fp16(B * 3, 0.5, 1), np.zeros(B, np.uint16), W.gaussian_fp16(B * 2 - 11, 1e-3, 2)])
+    else:
+        w = np.concatenate([W.gaussian_fp32(B * 2, 0.02, 3), np.full(B, 0x3F800000, np.uint32), W.gaussian_fp32(B + 5, 30.0, 4)])
+    rc, s = oracle.compress_per_block(w, B, dtype, L)
+    assert rc == oracle.OK
+    nb = (w.size + B - 1) // B
+    tuples = oracle.block_tuples(s)
+    base = oracle.payload_base_pb(w.size, B, dtype)
+    assert base == oracle.payload_base(w.size, B, dtype) + ((4 * nb + 15) // 16) * 16
+    offs = struct.unpack_from(f"<{nb + 1}Q", s.tobytes(), 64)
+    assert s.size == base + offs[-1]
+    for k in range(nb):
+        blk = w[k * B:(k + 1) * B]
+        b, n, m = tuples[k]
+        assert (b, n, m, 16) == oracle.tune(blk, dtype)                 # the tensor tuner on the block alone
+        rc1, one = oracle.compress(blk, (b, n, m, L), B, dtype=dtype)   # one-block stream of the pinned codec
+        assert rc1 == oracle.OK
+        pb1 = oracle.payload_base(blk.size, B, dtype)
+        assert s[base + offs[k]:base + offs[k + 1]].tobytes() == one[pb1:].tobytes(), k
+    if dtype == FP32:       # the lower halves sit between the tuple table and the payloads
+        at = oracle.table_end(w.size, B) + ((4 * nb + 15) // 16) * 16
+        assert (s[at:at + 2 * w.size].view(np.uint16) == (w & 0xFFFF).astype(np.uint16)).all()
+    rc, d = oracle.decompress(s, w.size)
+    assert rc == oracle.OK and (d == w).all()
+
+
+@pytest.mark.parametrize("dtype,L", [(BF16, 16), (BF16, 8), (FP16, 16), (FP32, 32)])
+def test_twin_agrees_and_round_trips(oracle, ref, dtype, L):
+    B = 256
+    rng = np.random.default_rng(17 + dtype)
+    if dtype == FP32:
+        w = np.concatenate([W.gaussian_fp32(B + 9, 0.02, 1), rng.integers(0, 2**32, B, dtype=np.uint64).astype(np.uint32)])
+    elif dtype == FP16:
+        w = np.concatenate([W.gaussian_fp16(B, 0.02, 1), rng.integers(0, 65536, B + 3).astype(np.uint16)])
+    else:
+        w = _mixed(4, B, 9)[:4 * B - 100]
+    rc, s = oracle.compress_per_block(w, B, dtype, L)
+    ok, s2 = ref.compress(w, (0, 0, 0, L), B, dtype, per_block=True)
+    assert rc == oracle.OK and ok and s.tobytes() == s2
+    assert ref.decompress(s2, w.size) == [int(v) for v in w]
+
+
+def test_mixed_tensor_compresses_like_its_parts(oracle):
+    """A tensor of blocks of different kinds: one tuple for all cannot adapt, a tuple per block does."""
+    B = 2048
+    w = _mixed(24, B, 3)
+    rc, whole = oracle.compress(w, oracle.tune(w), B)
+    rc2, per = oracle.compress_per_block(w, B)
+    assert rc == oracle.OK and rc2 == oracle.OK
+    parts = sum(oracle.compress(w[k * B:(k + 1) * B], oracle.tune(w[k * B:(k + 1) * B]), B)[1].size
+                - oracle.payload_base(B, B) for k in range(24))
+    assert per.size == oracle.payload_base_pb(w.size, B) + parts
+    assert per.size < 0.85 * whole.size
+    assert oracle.decompress(per, w.size)[1].tobytes() == w.tobytes()
+
+
+def test_empty_and_bound(oracle):
+    rc, s = oracle.compress_per_block(np.zeros(0, np.uint16), 2048)
+    assert rc == oracle.OK and s.size == 80 and s[40] == 1
+    assert oracle.decompress(s, 0)[0] == oracle.OK
+    rng = np.random.default_rng(1)
+    w = rng.integers(0, 65536, 2048 * 3 + 1).astype(np.uint16)
+    rc, s = oracle.compress_per_block(w, 2048, BF16, 8)
+    assert rc == oracle.OK and s.size <= oracle.compress_bound_pb(w.size, 2048)
+    assert oracle.compress_bound_pb(w.size, 2048) == oracle.compress_bound(w.size, 2048) + 16
