@@ -205,6 +205,24 @@ int enec_compress_sampled(const void *in, size_t n_elems, int dtype, uint32_t bl
                           enec_params *params_used, void *out, size_t out_capacity, void *workspace,
                           size_t workspace_bytes, void *stream);
 
+/* One tuple per data block.  The paper tunes one (b, n, m) per tensor [Sec. V-E] and reports that
+ * tensors differ [Table VI]; here the same search (Eq. 1-4, L = 16) runs inside the compress kernel
+ * on the exponents of each data block's own elements, and the block is coded with what it finds, so
+ * no exponent is ever out of range and a tensor whose blocks differ in kind or scale is coded as
+ * well as its parts would be.  Stream layout: as described at the top, with
+ *   header byte 40 = 1, header (b, n, m) = (0, 0, 0) (n = 0 occurs in no other stream),
+ *   the tuples, 4 bytes per block (b, n, m, 0), zero-padded to a multiple of 16, between the offset
+ *   table and the fp32 region / the payloads.
+ * enec_decompress, enec_decompress_with_header and enec_decompress_batch read such streams as any
+ * other (a launch of its own per stream).  Arguments as for enec_compress, without params;
+ * out_capacity >= enec_compress_bound_per_block(n_elems, dtype, block_size) (0 for an invalid dtype
+ * or block size).  The workspace is used as by enec_compress and must not be shared with a call
+ * that is still running.  Asynchronous. */
+size_t enec_compress_bound_per_block(size_t n_elems, int dtype, uint32_t block_size);
+int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t block_size, void *out,
+                            size_t out_capacity, uint64_t *out_bytes, void *workspace, size_t workspace_bytes,
+                            void *stream);
+
 /* Host-only search of Sec. V-E phases 2-3 on a given 256-bin exponent histogram (HOST); dtype
  * fixes the cap of Eq. 1's width (the exponent field: 8 bits, fp16: 5). */
 int enec_tune_histogram(const uint64_t *histogram, int dtype, enec_params *params);

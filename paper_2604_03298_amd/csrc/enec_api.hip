@@ -17,13 +17,14 @@ __global__ void compress_empty_kernel(uint8_t *out, uint64_t *out_bytes, uint32_
     if (threadIdx.x != 0) return;
     uint32_t *h = reinterpret_cast<uint32_t *>(out);
     h[0] = 0x43454E45u;
-    h[1] = 1u | (dtype << 16) | (L << 24);
+    h[1] = 1u | (dtype << 16) | ((L & 0xFFu) << 24);
     h[2] = h[3] = 0;
     h[4] = B; h[5] = 0;
     h[6] = b | (n << 8) | (m << 16) | (exponent_bits((int)dtype) << 24);
     h[7] = 0;
     h[8] = 80; h[9] = 0;
-    for (int i = 10; i < 16; ++i) h[i] = 0;
+    h[10] = L >> 8;                           // 1 = a stream with one tuple per data block
+    for (int i = 11; i < 16; ++i) h[i] = 0;
     h[16] = h[17] = h[18] = h[19] = 0;      // table[0] = 0 and the pad to 80 bytes
     if (out_bytes) *out_bytes = 80;
 }
@@ -72,6 +73,8 @@ inline size_t payload_base(size_t n, uint32_t B, int dtype)
     return table_end(n, B) + (dtype == ENEC_FP32 ? align16(2 * n) : 0);
 }
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+// a stream with one tuple per data block keeps them (4 bytes each) right behind the offset table
+inline size_t tuple_table_bytes(size_t n, uint32_t B) { return align16(4 * num_blocks(n, B)); }
 
 inline bool group_ok(unsigned L) { return L == 8 || L == 16 || L == 32; }
 
@@ -156,6 +159,7 @@ struct Header {
     uint64_t n_elems, total;
     uint32_t B, nb, status;
     int dtype;
+    bool per_block;          // one tuple per data block (header byte 40)
 };
 
 int parse_header(const void *host_header, Header *h)
@@ -173,6 +177,8 @@ int parse_header(const void *host_header, Header *h)
     h->prm.b = p[24]; h->prm.n = p[25]; h->prm.m = p[26]; h->prm.L = p[7];
     std::memcpy(&h->status, p + 28, 4);
     std::memcpy(&h->total, p + 32, 8);
+    if (p[40] > 1) return ENEC_E_FORMAT;
+    h->per_block = p[40] == 1;
     return ENEC_OK;
 }
 
@@ -490,6 +496,67 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
     return enec_compress_batch(&it, 1, dtype, workspace, workspace_bytes, stream);
 }
 
+size_t enec_compress_bound_per_block(size_t n_elems, int dtype, uint32_t block_size)
+{
+    const size_t bound = enec_compress_bound(n_elems, dtype, block_size);
+    if (!bound) return 0;
+    const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
+    return bound + tuple_table_bytes(n_elems, B);
+}
+
+int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t block_size, void *out,
+                            size_t out_capacity, uint64_t *out_bytes, void *workspace, size_t workspace_bytes,
+                            void *stream)
+{
+    if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
+    if (!out || !workspace || (!in && n_elems) || !aligned16(in) || !aligned16(out) || !aligned16(workspace) ||
+        n_elems > MAX_ELEMS)
+        return ENEC_E_ARG;
+    const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
+    if (!block_ok(B)) return ENEC_E_BLOCK;
+    if (out_capacity < enec_compress_bound_per_block(n_elems, dtype, B)) return ENEC_E_CAPACITY;
+    if (out_bytes && !device_accessible(out_bytes)) return ENEC_E_ARG;
+    const size_t nb = num_blocks(n_elems, B);
+    hipStream_t s = (hipStream_t)stream;
+    if (nb == 0) {
+        compress_empty_kernel<<<1, 64, 0, s>>>(static_cast<uint8_t *>(out), out_bytes, B, 0, 0, 0, (uint32_t)dtype,
+                                               16u | 0x100u);
+        return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+    }
+    // look-back words (and the ticket in front of them) behind the accumulators, cleared for this call
+    size_t first = ws_acc_words(workspace_bytes);
+    first += first & 1;                                   // 16-byte aligned for the fill kernel
+    const size_t words = ws_state_words(workspace_bytes);
+    const size_t need = 2 + nb + (nb & 1);
+    if (words < first + need) return ENEC_E_CAPACITY;
+    uint64_t *base = reinterpret_cast<uint64_t *>(static_cast<uint8_t *>(workspace) + WS_STATE) + first;
+    const uint64_t nvec = need / 2;
+    const unsigned fill_grid = (unsigned)((nvec + 255) / 256 < 1024 ? (nvec + 255) / 256 : 1024);
+    fill_zero_kernel<<<fill_grid, 256, 0, s>>>(reinterpret_cast<uint4 *>(base), nvec);
+    PbCompressArgs a;
+    a.in = in;
+    a.out = static_cast<uint8_t *>(out);
+    a.out_bytes = reinterpret_cast<unsigned long long *>(out_bytes);
+    a.ticket = reinterpret_cast<uint32_t *>(base);
+    a.words = base + 2;
+    a.n_elems = n_elems;
+    a.tuples_at = table_end(n_elems, B);
+    a.tail_base = a.tuples_at + tuple_table_bytes(n_elems, B);
+    a.payload_base = payload_base(n_elems, B, dtype) + tuple_table_bytes(n_elems, B);
+    a.nb = (uint32_t)nb; a.B = B; a.logB = ilog2(B);
+    a.spin_limit = SPIN_LIMIT;
+    if (const char *e = std::getenv("ENEC_SPIN_LIMIT")) {
+        const long v = std::atol(e);
+        if (v > 0 && v < (long)SPIN_LIMIT) a.spin_limit = (uint32_t)v;
+    }
+    PbCompressFn fn = pick_compress_per_block(dtype);
+    if (!fn) return ENEC_E_DTYPE;
+    const unsigned threads = B / 64 < 64 ? 64 : B / 64;
+    const size_t lds = (size_t)B / 128 + (size_t)B;       // mask | low plane | high records: at most 8 plane bits together
+    hipLaunchKernelGGL(fn, dim3((unsigned)nb), dim3(threads), lds, s, a);
+    return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+}
+
 int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, void *stream)
 {
     if (!items) return ENEC_E_ARG;
@@ -502,15 +569,41 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
         int rc = parse_header(it.host_header, &h);
         if (rc != ENEC_OK) return rc;
         if (h.status != ENEC_OK || h.n_elems != it.n_elems || !block_ok(h.B) || it.n_elems > MAX_ELEMS ||
-            h.nb != num_blocks(it.n_elems, h.B) || h.prm.n < 1 || h.prm.n > exp_bits(h.dtype) || h.prm.m > h.prm.n ||
-            h.prm.b >= (1u << exp_bits(h.dtype)) || !group_fits_block(h.prm.L, h.B) ||
-            h.total < payload_base(it.n_elems, h.B, h.dtype) || h.total > it.in_bytes)
+            h.nb != num_blocks(it.n_elems, h.B) || !group_fits_block(h.prm.L, h.B) || h.total > it.in_bytes)
             return ENEC_E_FORMAT;
+        if (h.per_block) {
+            if (h.prm.L != 16 || h.prm.n != 0 || h.prm.m != 0 || h.prm.b != 0 ||
+                h.total < payload_base(it.n_elems, h.B, h.dtype) + tuple_table_bytes(it.n_elems, h.B))
+                return ENEC_E_FORMAT;
+        } else if (h.prm.n < 1 || h.prm.n > exp_bits(h.dtype) || h.prm.m > h.prm.n ||
+                   h.prm.b >= (1u << exp_bits(h.dtype)) || h.total < payload_base(it.n_elems, h.B, h.dtype)) {
+            return ENEC_E_FORMAT;
+        }
     }
     std::vector<char> done(n_items, 0);
     for (size_t i = 0; i < n_items; ++i) {
         if (done[i]) continue;
         if (hdr[i].nb == 0) { done[i] = 1; continue; }
+        if (hdr[i].per_block) {                      // its tuples are in the stream: a launch of its own
+            const Header &h = hdr[i];
+            PbDecompressArgs a;
+            a.in = static_cast<const uint8_t *>(items[i].in);
+            a.out = items[i].out;
+            a.n_elems = items[i].n_elems;
+            a.tuples_at = table_end(a.n_elems, h.B);
+            a.tail_base = a.tuples_at + tuple_table_bytes(a.n_elems, h.B);
+            a.payload_base = payload_base(a.n_elems, h.B, h.dtype) + tuple_table_bytes(a.n_elems, h.B);
+            a.payload_bytes = h.total - a.payload_base;
+            a.nb = h.nb; a.B = h.B; a.logB = ilog2(h.B);
+            std::memcpy(a.hdr, items[i].host_header, sizeof a.hdr);
+            PbDecompressFn fn = pick_decompress_per_block(h.dtype);
+            if (!fn) return ENEC_E_FORMAT;
+            const unsigned threads = h.B / 64 < 64 ? 64 : h.B / 64;
+            const size_t lds = (size_t)h.B / 128 + h.B + 16;     // the packed part of the widest block
+            hipLaunchKernelGGL(fn, dim3(h.nb), dim3(threads), lds, (hipStream_t)stream, a);
+            done[i] = 1;
+            continue;
+        }
         DecompressArgs a;
         a.B = hdr[i].B;
         a.logB = ilog2(a.B);
@@ -518,7 +611,7 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
         a.total = 0;
         for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
             const Header &h = hdr[j];
-            if (done[j] || h.nb == 0 || h.B != a.B || h.prm.m != hdr[i].prm.m || h.prm.n != hdr[i].prm.n ||
+            if (done[j] || h.nb == 0 || h.per_block || h.B != a.B || h.prm.m != hdr[i].prm.m || h.prm.n != hdr[i].prm.n ||
                 h.dtype != hdr[i].dtype || h.prm.L != hdr[i].prm.L)
                 continue;
             DecompressItem &c = a.item[a.n_items++];

@@ -23,4 +23,33 @@ ENEC_TABLES(dt1)
 ENEC_TABLES(dt2)
 #undef ENEC_TABLES
 
+// Streams with one tuple per data block (enec_per_block.hpp, compiled in enec_per_block.hip): the
+// widths are run-time values there, one kernel per element format and direction.
+struct PbCompressArgs {
+    const void *in;
+    uint8_t *out;
+    unsigned long long *out_bytes;
+    uint64_t *words;            // nb look-back words, zero at launch
+    uint32_t *ticket;           // zero at launch
+    uint64_t n_elems;
+    uint64_t tuples_at;         // byte offset of the tuple table in the stream
+    uint64_t tail_base;         // fp32: where the lower halves go
+    uint64_t payload_base;
+    uint32_t nb, B, logB, spin_limit;
+};
+
+struct PbDecompressArgs {
+    const uint8_t *in;
+    void *out;
+    uint64_t n_elems;
+    uint64_t tuples_at, tail_base, payload_base, payload_bytes;
+    uint32_t nb, B, logB;
+    uint32_t hdr[11];           // the header the launch was configured from
+};
+
+using PbCompressFn = void (*)(const PbCompressArgs);
+using PbDecompressFn = void (*)(const PbDecompressArgs);
+PbCompressFn pick_compress_per_block(int dtype);
+PbDecompressFn pick_decompress_per_block(int dtype);
+
 }  // namespace enec

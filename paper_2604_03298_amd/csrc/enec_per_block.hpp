@@ -1,0 +1,638 @@
+// ENEC streams with one (b, n, m) per data block: the search of Sec. V-E (Eq. 1-4) runs inside the
+// compress kernel on the exponents of each block's own elements, so a tensor whose blocks differ
+// (zeros, constants, weights of several scales, noise) is coded block by block with the tuple
+// that fits.  Group length 16.  One workgroup per data block, one pass over the tensor:
+//   ticket -> rows -> split -> LDS histogram -> (b, n) by Eq. 1-3 -> m by Eq. 4 -> transform ->
+//   group test -> packing (Alg. 2, widths chosen at run time from the template instances) ->
+//   size -> look-back over the earlier blocks' sizes -> stores.
+// The widths are run-time values here, so the packers are reached through a switch; the kernels
+// of enec_device.hpp, which know their widths at compile time, stay the fast path for one tuple
+// per tensor.
+#pragma once
+#include "enec_kernels.hpp"
+
+namespace enec {
+
+// look-back word of a block: zero = nothing yet
+constexpr uint64_t PB_PREFIX = 1ull << 63;     // [60:0] = end of this block's payload (inclusive prefix), / 16
+constexpr uint64_t PB_SIZE = 1ull << 62;       // [60:0] = size of this block's payload, / 16
+constexpr uint64_t PB_GAVE_UP = 1ull << 61;    // somebody before (or this block) stopped waiting
+constexpr uint64_t PB_VALUE = (1ull << 61) - 1;
+
+// Alg. 2 over the low plane, one column (this thread's 8 rows) at a time: LOW[t][h] holds the
+// plane values of row t in byte lanes; normalized byte q of the thread's 8 columns goes to the image
+template <int LM>
+__device__ __forceinline__ void pb_pack_low(const uint32_t (&LOW)[8][2], uint8_t *img_low, uint32_t logC, uint32_t tid)
+{
+    constexpr HHTable TL = HH<LM>::table;
+    uint32_t acc[LM][2];
+#pragma unroll
+    for (int q = 0; q < LM; ++q) acc[q][0] = acc[q][1] = 0;
+#pragma unroll
+    for (int f = 0; f < TL.count; ++f)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t s = shl_or_shr(LOW[TL.row[f]][h], TL.shift[f]);
+            if (!TL.clean[f]) s &= TL.dmask[f] * 0x01010101u;
+            acc[TL.plane[f]][h] |= s;
+        }
+#pragma unroll
+    for (int q = 0; q < LM; ++q)
+        *reinterpret_cast<uint2 *>(img_low + ((size_t)q << logC) + 8u * tid) = make_uint2(acc[q][0], acc[q][1]);
+}
+
+// the inverse: plane values of the thread's 8 rows from the stream's low plane (already joined
+// pairwise by Alg. 2's last step: stream byte 2i = normalized byte i, 2i+1 = normalized byte i + T/2)
+template <int LM>
+__device__ __forceinline__ void pb_unpack_low(const uint8_t *img_low, uint32_t B, uint32_t logC, uint32_t tid,
+                                              uint32_t (&LOW)[8][2])
+{
+    constexpr HHTable TL = HH<LM>::table;
+    uint32_t Pl[LM][2];
+    const uint32_t T2 = (LM * B) >> 4;
+#pragma unroll
+    for (int q = 0; q < LM; ++q) {
+        const uint32_t i = ((uint32_t)q << logC) + 8u * tid;
+        const bool even = i < T2;
+        const uint4 sp = *reinterpret_cast<const uint4 *>(img_low + 2u * (even ? i : i - T2));
+        const uint32_t sel = even ? 0x06040200u : 0x07050301u;
+        Pl[q][0] = byte_perm(sp.y, sp.x, sel);
+        Pl[q][1] = byte_perm(sp.w, sp.z, sel);
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) LOW[t][0] = LOW[t][1] = 0;
+#pragma unroll
+    for (int f = 0; f < TL.count; ++f) {
+        const uint32_t smask = (TL.shift[f] >= 0 ? (TL.dmask[f] >> TL.shift[f]) : (TL.dmask[f] << (-TL.shift[f]))) * 0x01010101u;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) LOW[TL.row[f]][h] |= shl_or_shr(Pl[TL.plane[f]][h], -TL.shift[f]) & smask;
+    }
+}
+
+// Alg. 2 with N = 16 over the high parts of every masked group: a group is the 16 elements of two
+// neighbouring lanes in one row, seen as 8 rows of 2 columns; even lanes pack the group of row 2u,
+// odd lanes that of row 2u + 1.  rank = position of the record among the block's records.
+template <int A>
+__device__ __forceinline__ void pb_pack_records(const uint32_t (&HI)[8][2], uint32_t my_word, uint32_t my_excl,
+                                                uint8_t *img_high, uint32_t logC, uint32_t tid, bool active)
+{
+    constexpr HHTable TH = HH<A>::table;
+    const uint32_t par = tid & 1u;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const uint32_t own0 = par ? HI[2 * u + 1][0] : HI[2 * u][0];
+        const uint32_t own1 = par ? HI[2 * u + 1][1] : HI[2 * u][1];
+        const uint32_t snd0 = par ? HI[2 * u][0] : HI[2 * u + 1][0];
+        const uint32_t snd1 = par ? HI[2 * u][1] : HI[2 * u + 1][1];
+        const uint32_t rcv0 = swap_pair(snd0);
+        const uint32_t rcv1 = swap_pair(snd1);
+        uint32_t F[4];
+        F[0] = par ? rcv0 : own0;
+        F[1] = par ? rcv1 : own1;
+        F[2] = par ? own0 : rcv0;
+        F[3] = par ? own1 : rcv1;
+        const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
+        const uint32_t wv = __shfl(my_word, g >> 5, 64);
+        const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+        if (active && ((wv >> (g & 31u)) & 1u)) {
+            const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+            uint32_t P[A];
+#pragma unroll
+            for (int q = 0; q < A; ++q) P[q] = 0;
+#pragma unroll
+            for (int f = 0; f < TH.count; ++f) {
+                const int r = TH.row[f];
+                const uint32_t s = shl_or_shr(F[r >> 1], TH.shift[f] - 16 * (r & 1));
+                P[TH.plane[f]] |= s & (TH.dmask[f] * 0x0101u);
+            }
+            // normalized byte j = byte (j & 1) of P[j >> 1]; stream word i = nb[i] | nb[i + A] << 8
+            uint16_t *dst = reinterpret_cast<uint16_t *>(img_high + 2u * A * rank);
+#pragma unroll
+            for (int i = 0; i < A; ++i) {
+                const uint32_t lo = (P[i >> 1] >> (8 * (i & 1))) & 0xFFu;
+                const uint32_t hi = (P[(i + A) >> 1] >> (8 * ((i + A) & 1))) & 0xFFu;
+                dst[i] = (uint16_t)(lo | (hi << 8));
+            }
+        }
+    }
+}
+
+// the inverse for this thread's 8 rows: HI[t][h] = high parts (zero for groups without a record)
+template <int A>
+__device__ __forceinline__ void pb_unpack_records(const uint8_t *img_high, uint32_t my_word, uint32_t my_excl,
+                                                  uint32_t logC, uint32_t tid, uint32_t (&HI)[8][2])
+{
+    constexpr HHTable TH = HH<A>::table;
+    const uint32_t par = tid & 1u;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        HI[t][0] = HI[t][1] = 0;
+        const uint32_t g = ((uint32_t)t << (logC - 4)) + (tid >> 1);
+        const uint32_t wv = __shfl(my_word, g >> 5, 64);
+        const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+        if ((wv >> (g & 31u)) & 1u) {
+            const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+            const uint16_t *rec = reinterpret_cast<const uint16_t *>(img_high + 2u * A * rank);
+            uint32_t nbyte[2 * A];
+#pragma unroll
+            for (int i = 0; i < A; ++i) {
+                const uint32_t w = rec[i];
+                nbyte[i] = w & 0xFFu;
+                nbyte[i + A] = w >> 8;
+            }
+            uint32_t P[A];
+#pragma unroll
+            for (int q = 0; q < A; ++q) P[q] = 0;
+#pragma unroll
+            for (int j = 0; j < 2 * A; ++j) P[j >> 1] |= nbyte[j] << (8 * (j & 1));
+            uint32_t E[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) E[r] = 0;
+#pragma unroll
+            for (int f = 0; f < TH.count; ++f) {
+                const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f]) : (TH.dmask[f] << (-TH.shift[f]))) * 0x0101u;
+                E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
+            }
+            // this lane's 8 elements are rows 4 par .. 4 par + 3 of the two-column view
+            HI[t][0] = par ? (E[4] | (E[5] << 16)) : (E[0] | (E[1] << 16));
+            HI[t][1] = par ? (E[6] | (E[7] << 16)) : (E[2] | (E[3] << 16));
+        }
+    }
+}
+
+// Eq. 1: bits needed for the window [l, h] around b, capped by the exponent field
+__device__ __forceinline__ uint32_t pb_width_for(uint32_t b, uint32_t l, uint32_t h, uint32_t E)
+{
+    const uint32_t pos = 32u - __clz(b - l);                          // bit length, 0 for 0
+    const uint32_t neg = h > b ? 32u - __clz(h - b - 1u) : 0u;
+    const uint32_t w = (pos > neg ? pos : neg) + 1u;
+    return w < E ? w : E;
+}
+
+template <int DT>
+__global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompressArgs p)
+{
+    constexpr uint32_t E = exponent_bits(DT);
+    constexpr int RW = DT == DT_FP32 ? 16 : 8;
+
+    extern __shared__ __align__(16) uint8_t smem[];      // mask | low plane (normalized bytes) | high records
+    __shared__ uint32_t s_hist[256];
+    __shared__ unsigned long long s_best;                // Eq. 3 cost << 16 | n << 8 | b of the best candidate
+    __shared__ double s_bexp[9];
+    __shared__ uint32_t s_k, s_lo, s_hi, s_m, s_flags;
+    __shared__ unsigned long long s_off;
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t B = p.B, logC = p.logB - 3u;
+    const uint32_t nact = B >> 6;
+    const bool active = tid < nact;
+    const uint32_t mask_bytes = B >> 7;
+
+    if (tid == 0) {
+        s_k = atomicAdd(p.ticket, 1u);                   // blocks are taken in the order workgroups start
+        s_best = ~0ull;
+        s_lo = 255u;
+        s_hi = 0u;
+        s_flags = 0u;
+    }
+    for (uint32_t i = tid; i < 256u; i += blockDim.x) s_hist[i] = 0;
+    __syncthreads();
+    const uint32_t k = s_k;
+    if (k >= p.nb) return;                               // (the grid has exactly nb workgroups)
+    const uint64_t blk0 = (uint64_t)k << p.logB;
+    const uint32_t real = p.n_elems - blk0 < B ? (uint32_t)(p.n_elems - blk0) : B;   // elements that are not pads
+
+    // ---- a1: rows, split into exponent bytes X, raw bytes SM (and fp16's three left-over bits) ----
+    uint32_t X[8][2], SM[8][2], T3[DT == DT_FP16 ? 8 : 1][2];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint32_t at = ((uint32_t)t << logC) + 8u * tid;         // first element of the thread in this row
+        uint4 r16 = make_uint4(0, 0, 0, 0);
+        if (active && at < real) {
+            if constexpr (DT == DT_FP32) {
+                const uint32_t *in = reinterpret_cast<const uint32_t *>(p.in) + blk0 + at;
+                uint4 u, v;
+                if (at + 8u <= real) {
+                    u = *reinterpret_cast<const uint4 *>(in);
+                    v = *reinterpret_cast<const uint4 *>(in + 4);
+                } else {
+                    uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (at + i < real) d[i] = in[i];
+                    u = make_uint4(d[0], d[1], d[2], d[3]);
+                    v = make_uint4(d[4], d[5], d[6], d[7]);
+                }
+                r16 = make_uint4(byte_perm(u.y, u.x, 0x07060302u), byte_perm(u.w, u.z, 0x07060302u),
+                                 byte_perm(v.y, v.x, 0x07060302u), byte_perm(v.w, v.z, 0x07060302u));
+                // the lower halves leave at once (pads have zero lower halves; the region is padded to 16 bytes)
+                *reinterpret_cast<uint4 *>(p.out + p.tail_base + 2u * (blk0 + at)) =
+                    make_uint4(byte_perm(u.y, u.x, 0x05040100u), byte_perm(u.w, u.z, 0x05040100u),
+                               byte_perm(v.y, v.x, 0x05040100u), byte_perm(v.w, v.z, 0x05040100u));
+            } else {
+                const uint16_t *in = reinterpret_cast<const uint16_t *>(p.in) + blk0 + at;
+                if (at + 8u <= real) {
+                    r16 = *reinterpret_cast<const uint4 *>(in);
+                } else {
+                    uint32_t d[4] = {0, 0, 0, 0};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (at + i < real) d[i >> 1] |= (uint32_t)in[i] << (16 * (i & 1));
+                    r16 = make_uint4(d[0], d[1], d[2], d[3]);
+                }
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t d0 = h ? r16.z : r16.x;
+            const uint32_t d1 = h ? r16.w : r16.y;
+            const uint32_t Lb = byte_perm(d1, d0, 0x06040200u);
+            const uint32_t Hb = byte_perm(d1, d0, 0x07050301u);
+            if constexpr (DT == DT_FP16) {
+                SM[t][h] = (Hb & 0x80808080u) | ((Hb & 0x03030303u) << 5) | ((Lb >> 3) & 0x1F1F1F1Fu);
+                X[t][h] = (Hb >> 2) & 0x1F1F1F1Fu;
+                T3[t][h] = Lb & 0x07070707u;
+            } else {
+                SM[t][h] = bfi(0x7F7F7F7Fu, Lb, Hb);
+                X[t][h] = bfi(0xFEFEFEFEu, Hb << 1, Lb >> 7);
+            }
+            // ---- Sec. V-E phase 1: exponent counts of the block's own elements ----
+            if (active) {
+                const uint32_t e = at + 4u * h;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (e + i < real) atomicAdd(&s_hist[(X[t][h] >> (8 * i)) & 0xFFu], 1u);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: lowest and highest exponent, then every b in between with Eq. 1's n and Eq. 3's cost ----
+    for (uint32_t x = tid; x < 256u; x += blockDim.x)
+        if (s_hist[x]) {
+            atomicMin(&s_lo, x);
+            atomicMax(&s_hi, x);
+        }
+    __syncthreads();
+    const uint32_t xl = s_lo, xh = s_hi;
+    for (uint32_t b = xl + tid; b <= xh; b += blockDim.x) {
+        const uint32_t n = pb_width_for(b, xl, xh, E);
+        const uint32_t nmask = (1u << n) - 1u;
+        uint32_t D = 0;                                   // at most 2^15 elements * 255
+        for (uint32_t x = xl; x <= xh; ++x) D += s_hist[x] * ((b - x) & nmask);
+        atomicMin(&s_best, ((unsigned long long)D << 16) | (n << 8) | b);     // ties: smaller n, then smaller b
+    }
+    __syncthreads();
+    const uint32_t b = (uint32_t)s_best & 0xFFu, n = ((uint32_t)s_best >> 8) & 0xFFu;
+    // ---- phase 3: Eq. 4 for every m, in IEEE double, p^16 by four squarings ----
+    if (tid <= n) {
+        const uint32_t nmask = (1u << n) - 1u;
+        uint32_t cnt = 0;
+        for (uint32_t x = xl; x <= xh; ++x)
+            if (((b - x) & nmask) < (1u << tid)) cnt += s_hist[x];
+        const double q = (double)cnt / (double)real;
+        const double q2 = q * q, q4 = q2 * q2, q8 = q4 * q4, q16 = q8 * q8;
+        s_bexp[tid] = (1.0 / 16.0 + (double)n) + ((double)tid - (double)n) * q16;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t best_m = 0;
+        double best = s_bexp[0];
+        for (uint32_t m = 1; m <= n; ++m)
+            if (s_bexp[m] < best) { best = s_bexp[m]; best_m = m; }          // ties: smaller m
+        s_m = best_m;
+    }
+    __syncthreads();
+    const uint32_t m = s_m, a = n - m;
+    const uint32_t lm = m + (DT == DT_FP16 ? 3u : 0u);
+
+    uint8_t *img = smem;
+    uint32_t *img_maskw = reinterpret_cast<uint32_t *>(img);
+    uint8_t *img_low = img + mask_bytes;
+    uint8_t *img_high = img_low + ((lm * B) >> 3);
+    const uint32_t fixed = B + mask_bytes + ((lm * B) >> 3);
+
+    // ---- a2 transform, a3 group test, a4 low plane ----
+    const uint32_t crep = ((b + (1u << (n - 1))) & 0xFFu) * 0x01010101u;
+    const uint32_t brep = b * 0x01010101u;
+    const uint32_t srep = (1u << (n - 1)) * 0x01010101u;
+    const uint32_t nrep = ((1u << n) - 1u) * 0x01010101u;
+    const uint32_t lrep = ((1u << m) - 1u) * 0x01010101u;
+    const uint32_t arep = ((1u << a) - 1u) * 0x01010101u;
+    uint32_t HI[8][2], LOW[8][2], mw[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        uint32_t gor = 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // pads behave like exponent b: y = 0
+            const int32_t left = (int32_t)real - (int32_t)(((uint32_t)t << logC) + 8u * tid + 4u * h);
+            const uint32_t padm = !active || left <= 0 ? 0xFFFFFFFFu : (left >= 4 ? 0u : 0xFFFFFFFFu << (8 * left));
+            const uint32_t x = bfi(padm, brep, X[t][h]);
+            const uint32_t Y = (bytesub_safe(crep, x) ^ srep) & nrep;
+            HI[t][h] = (Y >> m) & arep;
+            gor |= HI[t][h];
+            if constexpr (DT == DT_FP16) LOW[t][h] = (Y & lrep) | (T3[t][h] << m);
+            else LOW[t][h] = Y & lrep;
+        }
+        gor |= swap_pair(gor);
+        mw[t] = compact_even_bits(__builtin_amdgcn_ballot_w64(gor != 0));
+    }
+    if (lane == 0 && 64u * wave < nact) {
+        if (logC >= 9) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) img_maskw[((uint32_t)t << (logC - 9)) + wave] = mw[t];
+        } else {  // B = 2048: 16 groups per row, one wave
+#pragma unroll
+            for (int u = 0; u < 4; ++u) img_maskw[u] = mw[2 * u] | (mw[2 * u + 1] << 16);
+        }
+    }
+    if (active) {
+        switch (lm) {
+        case 1: pb_pack_low<1>(LOW, img_low, logC, tid); break;
+        case 2: pb_pack_low<2>(LOW, img_low, logC, tid); break;
+        case 3: pb_pack_low<3>(LOW, img_low, logC, tid); break;
+        case 4: pb_pack_low<4>(LOW, img_low, logC, tid); break;
+        case 5: pb_pack_low<5>(LOW, img_low, logC, tid); break;
+        case 6: pb_pack_low<6>(LOW, img_low, logC, tid); break;
+        case 7: pb_pack_low<7>(LOW, img_low, logC, tid); break;
+        case 8: pb_pack_low<8>(LOW, img_low, logC, tid); break;
+        default: break;
+        }
+    }
+    __syncthreads();
+
+    // ---- a5 positions: exclusive popcount prefix over the mask words (a wave scan per wave) ----
+    const uint32_t nwords = B >> 9;
+    const uint32_t my_word = lane < nwords ? img_maskw[lane] : 0u;
+    const uint32_t my_pc = __popc(my_word);
+    const uint32_t my_incl = wave_incl_scan(my_pc, lane);
+    const uint32_t my_excl = my_incl - my_pc;
+    const uint32_t cnt = __shfl(my_incl, 63, 64);
+    const uint32_t S = (fixed + 2u * a * cnt + 15u) & ~15u;
+    // ---- a6: the size is known: publish it before anything else ----
+    if (tid == 0) st_state(p.words + k, PB_SIZE | (uint64_t)(S >> 4));
+
+    switch (a) {
+    case 1: pb_pack_records<1>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 2: pb_pack_records<2>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 3: pb_pack_records<3>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 4: pb_pack_records<4>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 5: pb_pack_records<5>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 6: pb_pack_records<6>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 7: pb_pack_records<7>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 8: pb_pack_records<8>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    default: break;
+    }
+
+    // ---- a6 (wave 0): look back over the earlier blocks, 64 at a time, until one of them carries
+    // its inclusive prefix.  Block j's workgroup started before this one (tickets), and it publishes
+    // its size before it waits for anything, so every wait ends; the spin limit is a safety net. ----
+    if (wave == 0) {
+        uint64_t sum = 0;
+        uint32_t flags = 0;
+        int64_t top = (int64_t)k - 1;                    // highest block of the current window
+        while (top >= 0) {
+            const int64_t j = top - (int64_t)lane;
+            uint64_t v = 0;
+            uint32_t spins = 0;
+            bool ok = j < 0;
+            uint64_t stop = 0;                           // lanes at or above the first prefix word
+            for (;;) {
+                if (!ok) {
+                    v = ld_state(p.words + j);
+                    ok = v != 0;
+                }
+                stop = __builtin_amdgcn_ballot_w64(j >= 0 && (v & PB_PREFIX));
+                // everything up to the nearest prefix word (or the whole window) must be there
+                const uint64_t need = stop ? ((stop & (~stop + 1ull)) << 1) - 1ull : ~0ull;
+                if ((__builtin_amdgcn_ballot_w64(!ok) & need) == 0) break;
+                if (++spins > p.spin_limit) { flags |= 4u; break; }
+                spin_pause(spins);
+            }
+            if (flags & 4u) break;
+            const uint32_t first = stop ? (uint32_t)__builtin_ctzll(stop) : 64u;
+            const bool use = j >= 0 && lane <= first;
+            if (__builtin_amdgcn_ballot_w64(use && (v & PB_GAVE_UP))) flags |= 4u;
+            sum += wave_sum(use ? (v & PB_VALUE) : 0ull);
+            if (stop) break;
+            top -= 64;
+        }
+        if (lane == 0) {
+            s_off = sum << 4;
+            s_flags = flags;
+            st_state(p.words + k, PB_PREFIX | ((flags & 4u) ? PB_GAVE_UP : 0ull) | (sum + (S >> 4)));
+        }
+    }
+    __syncthreads();
+
+    // ---- a7: stores ----
+    const uint64_t off = s_off;
+    uint8_t *dst = p.out + p.payload_base + off;
+    if (active) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            // pads have zero raw bytes already (their words were loaded as zero)
+            *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SM[t][0], SM[t][1]);
+        }
+    }
+    for (uint32_t v = tid; v < (mask_bytes >> 4); v += blockDim.x)
+        *reinterpret_cast<uint4 *>(dst + B + 16u * v) = *reinterpret_cast<const uint4 *>(img + 16u * v);
+    if (lm > 0) {
+        uint8_t *dlow = dst + B + mask_bytes;
+        const uint32_t T2 = (lm * B) >> 4;               // half of the plane's length
+        for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
+            const uint2 lo = *reinterpret_cast<const uint2 *>(img_low + 8u * v);
+            const uint2 hi = *reinterpret_cast<const uint2 *>(img_low + 8u * v + T2);
+            uint4 o;   // stream byte 2i = normalized byte i, stream byte 2i+1 = normalized byte i + T/2
+            o.x = byte_perm(hi.x, lo.x, 0x05010400u);
+            o.y = byte_perm(hi.x, lo.x, 0x07030602u);
+            o.z = byte_perm(hi.y, lo.y, 0x05010400u);
+            o.w = byte_perm(hi.y, lo.y, 0x07030602u);
+            *reinterpret_cast<uint4 *>(dlow + 16u * v) = o;
+        }
+    }
+    if (a > 0) {
+        uint8_t *dhigh = dst + fixed;
+        const uint32_t hbytes = 2u * a * cnt;
+        for (uint32_t v = tid; 16u * v < hbytes; v += blockDim.x) {
+            const uint4 o = *reinterpret_cast<const uint4 *>(img_high + 16u * v);
+            uint32_t w[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {                // zero the padding behind the last record
+                const uint32_t at = 16u * v + 4u * i;
+                if (at >= hbytes) w[i] = 0;
+                else if (at + 4u > hbytes) w[i] &= (1u << (8u * (hbytes - at))) - 1u;
+            }
+            *reinterpret_cast<uint4 *>(dhigh + 16u * v) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+    if (tid == 0) {
+        uint64_t *table = reinterpret_cast<uint64_t *>(p.out + 64);
+        table[k] = off;
+        *reinterpret_cast<uint32_t *>(p.out + p.tuples_at + 4u * k) = b | (n << 8) | (m << 16);
+        if (k == p.nb - 1u) {
+            const uint64_t end = off + S;
+            const uint32_t status = (s_flags & 4u) ? 8u : 0u;
+            const uint64_t total = status ? 0ull : p.payload_base + end;
+            table[p.nb] = end;
+            if (((uint64_t)(p.nb + 1u) & 1ull)) table[p.nb + 1u] = 0;          // pad up to the tuple table
+            for (uint32_t i = p.nb; i < ((p.nb + 3u) & ~3u); ++i)              // pad behind the tuple table
+                *reinterpret_cast<uint32_t *>(p.out + p.tuples_at + 4u * i) = 0;
+            uint32_t *h = reinterpret_cast<uint32_t *>(p.out);
+            h[0] = 0x43454E45u;                                                // "ENEC"
+            h[1] = 1u | ((uint32_t)DT << 16) | (16u << 24);                    // version, dtype, L
+            h[2] = (uint32_t)p.n_elems; h[3] = (uint32_t)(p.n_elems >> 32);
+            h[4] = B; h[5] = p.nb;
+            h[6] = E << 24;                                                    // (b, n, m) = 0: see the tuple table
+            h[7] = status;
+            h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
+            h[10] = 1u;                                                        // one tuple per block
+#pragma unroll
+            for (int i = 11; i < 16; ++i) h[i] = 0;
+            if (p.out_bytes) *p.out_bytes = total;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// decompression of such a stream: one workgroup per data block; tuple and offsets come from the
+// stream, every size is checked against the tuple before anything is read or written
+// ---------------------------------------------------------------------------------
+template <int DT>
+__global__ void __launch_bounds__(512) decompress_per_block_kernel(const PbDecompressArgs p)
+{
+    constexpr uint32_t E = exponent_bits(DT);
+    extern __shared__ __align__(16) uint8_t smem[];      // the packed part as it is in the stream
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t B = p.B, logC = p.logB - 3u;
+    const uint32_t nact = B >> 6;
+    const bool active = tid < nact;
+    const uint32_t mask_bytes = B >> 7;
+    const uint32_t k = blockIdx.x;
+    if (k >= p.nb) return;
+
+    // d1: header as configured, tuple, offsets
+    const uint32_t *hd = reinterpret_cast<const uint32_t *>(p.in);
+    bool same = true;
+#pragma unroll
+    for (int i = 0; i < 11; ++i) same &= (hd[i] == p.hdr[i]);
+    const uint32_t tup = *reinterpret_cast<const uint32_t *>(p.in + p.tuples_at + 4u * k);
+    const uint32_t b = tup & 0xFFu, n = (tup >> 8) & 0xFFu, m = (tup >> 16) & 0xFFu;
+    const uint64_t *table = reinterpret_cast<const uint64_t *>(p.in + 64);
+    const uint64_t t0 = table[k], t1 = table[k + 1];
+    if (!same || n < 1u || n > E || m > n || b >= (1u << E)) return;
+    const uint32_t a = n - m, lm = m + (DT == DT_FP16 ? 3u : 0u);
+    const uint32_t fixed = B + mask_bytes + ((lm * B) >> 3);
+    const uint64_t sz = t1 - t0;
+    if (sz < fixed || sz > fixed + 2u * a * (B >> 4) + 15u || ((sz | t0) & 15u) || t0 > p.payload_bytes || sz > p.payload_bytes - t0)
+        return;                                          // a damaged table entry: the block is skipped
+    const uint8_t *src = p.in + p.payload_base + t0;
+    const uint32_t nvec = ((uint32_t)sz - B) >> 4;
+    for (uint32_t v = tid; v < nvec; v += blockDim.x)
+        *reinterpret_cast<uint4 *>(smem + 16u * v) = *reinterpret_cast<const uint4 *>(src + B + 16u * v);
+    uint2 smv[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        smv[t] = active ? *reinterpret_cast<const uint2 *>(src + ((size_t)t << logC) + 8u * tid) : make_uint2(0, 0);
+    __syncthreads();
+    if (!active) return;
+
+    const uint8_t *img_low = smem + mask_bytes;
+    const uint8_t *img_high = img_low + ((lm * B) >> 3);
+    const uint32_t nwords = B >> 9;
+    const uint32_t my_word = lane < nwords ? reinterpret_cast<const uint32_t *>(smem)[lane] : 0u;
+    const uint32_t my_pc = __popc(my_word);
+    const uint32_t my_excl = wave_incl_scan(my_pc, lane) - my_pc;
+
+    uint32_t LOW[8][2], HI[8][2];
+    switch (lm) {
+    case 1: pb_unpack_low<1>(img_low, B, logC, tid, LOW); break;
+    case 2: pb_unpack_low<2>(img_low, B, logC, tid, LOW); break;
+    case 3: pb_unpack_low<3>(img_low, B, logC, tid, LOW); break;
+    case 4: pb_unpack_low<4>(img_low, B, logC, tid, LOW); break;
+    case 5: pb_unpack_low<5>(img_low, B, logC, tid, LOW); break;
+    case 6: pb_unpack_low<6>(img_low, B, logC, tid, LOW); break;
+    case 7: pb_unpack_low<7>(img_low, B, logC, tid, LOW); break;
+    case 8: pb_unpack_low<8>(img_low, B, logC, tid, LOW); break;
+    default:
+#pragma unroll
+        for (int t = 0; t < 8; ++t) LOW[t][0] = LOW[t][1] = 0;
+        break;
+    }
+    switch (a) {
+    case 1: pb_unpack_records<1>(img_high, my_word, my_excl, logC, tid, HI); break;
+    case 2: pb_unpack_records<2>(img_high, my_word, my_excl, logC, tid, HI); break;
+    case 3: pb_unpack_records<3>(img_high, my_word, my_excl, logC, tid, HI); break;
+    case 4: pb_unpack_records<4>(img_high, my_word, my_excl, logC, tid, HI); break;
+    case 5: pb_unpack_records<5>(img_high, my_word, my_excl, logC, tid, HI); break;
+    case 6: pb_unpack_records<6>(img_high, my_word, my_excl, logC, tid, HI); break;
+    case 7: pb_unpack_records<7>(img_high, my_word, my_excl, logC, tid, HI); break;
+    case 8: pb_unpack_records<8>(img_high, my_word, my_excl, logC, tid, HI); break;
+    default:
+#pragma unroll
+        for (int t = 0; t < 8; ++t) HI[t][0] = HI[t][1] = 0;
+        break;
+    }
+
+    const uint32_t crep = ((b + (1u << (n - 1))) & 0xFFu) * 0x01010101u;
+    const uint32_t srep = (1u << (n - 1)) * 0x01010101u;
+    const uint32_t lrep = ((1u << m) - 1u) * 0x01010101u;
+    const uint32_t erep = ((1u << E) - 1u) * 0x01010101u;
+    const uint64_t blk0 = (uint64_t)k << p.logB;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint64_t e0 = blk0 + ((uint64_t)t << logC) + 8u * tid;
+        uint32_t o[4];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t Y = (LOW[t][h] & lrep) | (HI[t][h] << m);
+            // d4: x = b - sext_n(y) = (b + 2^(n-1)) - (y ^ 2^(n-1)), modulo the exponent field
+            const uint32_t Xv = bytesub_safe(crep, Y ^ srep) & erep;
+            const uint32_t sm = h ? smv[t].y : smv[t].x;
+            uint32_t Hi, Lo;
+            if constexpr (DT == DT_FP16) {
+                const uint32_t T3 = (LOW[t][h] >> m) & 0x07070707u;
+                Hi = (sm & 0x80808080u) | (Xv << 2) | ((sm >> 5) & 0x03030303u);
+                Lo = ((sm & 0x1F1F1F1Fu) << 3) | T3;
+            } else {
+                Hi = bfi(0x7F7F7F7Fu, Xv >> 1, sm);
+                Lo = bfi(0x7F7F7F7Fu, sm, Xv << 7);
+            }
+            o[2 * h] = byte_perm(Hi, Lo, 0x05010400u);
+            o[2 * h + 1] = byte_perm(Hi, Lo, 0x07030602u);
+        }
+        if constexpr (DT == DT_FP32) {
+            if (e0 < p.n_elems) {
+                const uint4 tl = *reinterpret_cast<const uint4 *>(p.in + p.tail_base + 2u * e0);   // region padded to 16 bytes
+                const uint32_t lo[4] = {tl.x, tl.y, tl.z, tl.w};
+                uint32_t w[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    w[2 * i] = byte_perm(o[i], lo[i], 0x05040100u);
+                    w[2 * i + 1] = byte_perm(o[i], lo[i], 0x07060302u);
+                }
+                uint32_t *out32 = reinterpret_cast<uint32_t *>(p.out);
+                if (e0 + 8 <= p.n_elems) {
+                    *reinterpret_cast<uint4 *>(out32 + e0) = make_uint4(w[0], w[1], w[2], w[3]);
+                    *reinterpret_cast<uint4 *>(out32 + e0 + 4) = make_uint4(w[4], w[5], w[6], w[7]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (e0 + i < p.n_elems) out32[e0 + i] = w[i];
+                }
+            }
+        } else {
+            uint16_t *out16 = reinterpret_cast<uint16_t *>(p.out);
+            if (e0 + 8 <= p.n_elems) {
+                *reinterpret_cast<uint4 *>(out16 + e0) = make_uint4(o[0], o[1], o[2], o[3]);
+            } else if (e0 < p.n_elems) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (e0 + i < p.n_elems) out16[e0 + i] = (uint16_t)(o[i >> 1] >> (16 * (i & 1)));
+            }
+        }
+    }
+}
+
+}  // namespace enec

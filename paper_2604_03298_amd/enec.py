@@ -23,7 +23,7 @@ EXPORTS = [
     "enec_workspace_bytes", "enec_workspace_init", "enec_compress", "enec_decompress",
     "enec_decompress_with_header", "enec_tune", "enec_tune_histogram", "enec_stream_info",
     "enec_copy", "enec_compress_batch", "enec_decompress_batch", "enec_tune_histogram_groups",
-    "enec_tune_sampled", "enec_compress_sampled",
+    "enec_tune_sampled", "enec_compress_sampled", "enec_compress_bound_per_block", "enec_compress_per_block",
 ]
 
 
@@ -84,6 +84,10 @@ def lib():
         L.enec_decompress_with_header.argtypes = [vp, sz, vp, vp, sz, vp]
         L.enec_tune.restype = C.c_int
         L.enec_tune.argtypes = [vp, sz, C.c_int, C.POINTER(Params), u64p, vp, sz, vp]
+        L.enec_compress_bound_per_block.restype = sz
+        L.enec_compress_bound_per_block.argtypes = [sz, C.c_int, C.c_uint32]
+        L.enec_compress_per_block.restype = C.c_int
+        L.enec_compress_per_block.argtypes = [vp, sz, C.c_int, C.c_uint32, vp, sz, vp, vp, sz, vp]
         L.enec_tune_sampled.restype = C.c_int
         L.enec_tune_sampled.argtypes = [vp, sz, C.c_int, C.c_uint32, C.POINTER(Params), u64p, vp, sz, vp]
         L.enec_compress_sampled.restype = C.c_int
@@ -209,6 +213,23 @@ def compress(src, params, out, workspace, block_size: int = 0, out_bytes=None, s
     ob = C.c_void_p(out_bytes.data_ptr()) if out_bytes is not None else None
     return int(lib().enec_compress(
         C.c_void_p(src.data_ptr()), n, dt, block_size, pp, C.c_void_p(out.data_ptr()),
+        out.numel() * out.element_size(), ob, C.c_void_p(workspace.data_ptr()),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+def compress_bound_per_block(n_elems: int, dtype: int = BF16, block_size: int = 0) -> int:
+    return int(lib().enec_compress_bound_per_block(n_elems, dtype, block_size))
+
+
+def compress_per_block(src, out, workspace, block_size: int = 0, out_bytes=None, stream=None,
+                       n_elems: int | None = None, dtype: int | None = None) -> int:
+    """Enqueues enec_compress_per_block: every data block is coded with the tuple tuned on its own
+    exponents.  out: device uint8 tensor of >= compress_bound_per_block bytes."""
+    n = src.numel() if n_elems is None else n_elems
+    dt = dtype_of(src, dtype)
+    ob = C.c_void_p(out_bytes.data_ptr()) if out_bytes is not None else None
+    return int(lib().enec_compress_per_block(
+        C.c_void_p(src.data_ptr()), n, dt, block_size, C.c_void_p(out.data_ptr()),
         out.numel() * out.element_size(), ob, C.c_void_p(workspace.data_ptr()),
         workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 

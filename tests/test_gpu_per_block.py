@@ -1,0 +1,175 @@
+"""GPU parity for streams with one tuple per data block: libenec (through its C ABI) against the CPU oracle,
+byte for byte in both directions; every decision (b, n by Eq. 1-3 in integers, m by Eq. 4 in IEEE double)
+is taken by the kernel and by the oracle in the same precision, so the tuples must be identical."""
+import numpy as np
+import pytest
+
+from paper_2604_03298_amd import workloads as W
+from test_gpu_dtypes import gpu, BF16, FP16, FP32, WORD  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def _compress(gpu, w, dtype, B=0):
+    torch, enec = gpu.torch, gpu.enec
+    src = gpu.to_dev(w, dtype)
+    cap = enec.compress_bound_per_block(w.size, dtype=dtype, block_size=B)
+    out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    gpu.size_pinned.fill_(-1)
+    rc = enec.compress_per_block(src, out, gpu.ws, block_size=B, out_bytes=gpu.size_pinned, n_elems=w.size, dtype=dtype)
+    torch.cuda.synchronize()
+    return rc, out.cpu().numpy(), int(gpu.size_pinned.item()), cap
+
+
+def _check(gpu, oracle, w, dtype, B=0, label=""):
+    Bo = B if B else oracle.default_block(w.size)
+    rc_o, s_o = oracle.compress_per_block(w, Bo, dtype)
+    assert rc_o == oracle.OK, label
+    rc, out, nbytes, cap = _compress(gpu, w, dtype, B)
+    assert rc == 0, label
+    assert nbytes == s_o.size, f"{label}: size {nbytes} vs oracle {s_o.size}"
+    bad = np.nonzero(out[:nbytes] != s_o)[0]
+    assert bad.size == 0, f"{label}: stream differs from the oracle's, first at byte {bad[:4]}"
+    assert (out[cap:] == 0xA5).all(), f"{label}: wrote past the bound"
+    for with_header in (True, False):
+        rc, d, rest = gpu.decompress(s_o, w.size, dtype, with_header)
+        assert rc == 0 and np.array_equal(d, w), f"{label}: GPU decompress(oracle stream) != input"
+        assert (rest == (0x5A5A5A5A if dtype == FP32 else 0x5A5A)).all(), f"{label}: wrote past the tensor"
+    return s_o
+
+
+def _mixed16(n_blocks, B, seed, dtype=BF16):
+    rng = np.random.default_rng(seed)
+    out = np.empty(n_blocks * B, np.uint16)
+    gen = W.gaussian if dtype == BF16 else W.gaussian_fp16
+    for k in range(n_blocks):
+        kind = int(rng.integers(0, 5))
+        blk = out[k * B:(k + 1) * B]
+        if kind == 0:
+            blk[:] = 0
+        elif kind == 1:
+            blk[:] = gen(1, 0.02, seed + k)[0]
+        elif kind == 2:
+            blk[:] = gen(B, 0.02 * 2.0 ** (k % 7 - 3), seed + k)
+        elif kind == 3:
+            blk[:] = rng.integers(0, 65536, B)
+        else:       # a quiet block with a few outliers
+            blk[:] = gen(B, 0.01, seed + k)
+            blk[rng.integers(0, B, 5)] = rng.integers(0, 65536, 5)
+    return out
+
+
+@pytest.mark.parametrize("B", [2048, 4096, 16384, 32768])
+def test_bf16_mixed_blocks(gpu, oracle, B):
+    w = _mixed16(19, B, 100 + B)
+    _check(gpu, oracle, w, BF16, B, f"B={B}")
+    _check(gpu, oracle, w[:w.size - B // 2 - 3], BF16, B, f"B={B} ragged")
+    _check(gpu, oracle, w[:B + 1], BF16, B, f"B={B} one element in the last block")
+
+
+def test_config3_blocks_and_ratio(gpu, oracle):
+    w, cat = W.config3(n_blocks=256)
+    s = _check(gpu, oracle, w, BF16, 16384, "config 3a, 256 blocks")
+    tuples = oracle.block_tuples(s)
+    assert all(tuples[k] == (0, 1, 0) for k in range(256) if cat[k] == 0)
+    assert all(tuples[k][1] == 1 for k in range(256) if cat[k] == 1)
+    assert all(tuples[k][1] == 8 for k in range(256) if cat[k] == 3)
+    one = oracle.compress(w, oracle.tune(w), 16384)[1]
+    assert s.size < 0.85 * one.size          # one tuple for the tensor cannot adapt to the mix
+
+
+def test_fp16_and_fp32(gpu, oracle):
+    for B in (2048, 16384):
+        w = _mixed16(9, B, 7 + B, FP16)
+        _check(gpu, oracle, w, FP16, B, f"fp16 B={B}")
+        _check(gpu, oracle, w[:w.size - 1234], FP16, B, f"fp16 B={B} ragged")
+        parts = [W.gaussian_fp32(B * 2, 0.02, 1), np.zeros(B, np.uint32), W.gaussian_fp32(B, 300.0, 2),
+                 np.random.default_rng(B).integers(0, 2**32, B, dtype=np.uint64).astype(np.uint32),
+                 W.gaussian_fp32(B * 2 - 77, 1e-4, 3)]
+        _check(gpu, oracle, np.concatenate(parts), FP32, B, f"fp32 B={B}")
+
+
+def test_degenerate_tensors(gpu, oracle):
+    for dt in (BF16, FP16, FP32):
+        word = WORD[dt]
+        _check(gpu, oracle, np.zeros(0, word), dt, 0, "empty")
+        _check(gpu, oracle, np.array([0x3C01], word), dt, 0, "one element")
+        _check(gpu, oracle, np.zeros(5000, word), dt, 0, "zeros")
+        top = 0xFFFFFFFF if dt == FP32 else 0xFFFF
+        _check(gpu, oracle, np.full(4097, top, word), dt, 2048, "all ones")
+    rng = np.random.default_rng(5)
+    _check(gpu, oracle, rng.integers(0, 65536, 16384 * 3 + 5).astype(np.uint16), BF16, 0, "noise")
+    # exponents 0 and 255 in one block: the window is the whole range
+    w = W.gaussian(16384, 0.02, 6)
+    w[3], w[9000] = 0x0001, 0x7F80
+    _check(gpu, oracle, w, BF16, 0, "extremes")
+
+
+def test_oracle_reads_the_gpu_stream_and_many_blocks(gpu, oracle):
+    """More blocks than the device holds workgroups at once: the look-back crosses many windows."""
+    w = _mixed16(3000, 2048, 77)
+    s = _check(gpu, oracle, w, BF16, 2048, "3000 blocks")
+    rc, d = oracle.decompress(s, w.size)
+    assert rc == oracle.OK and np.array_equal(d, w)
+
+
+def test_workspace_shared_with_the_one_tuple_path(gpu, oracle):
+    """Both kinds of call use the same workspace one after the other."""
+    w = _mixed16(40, 4096, 9)
+    prm = oracle.tune(w)
+    for _ in range(2):
+        _check(gpu, oracle, w, BF16, 4096, "per block")
+        rc, out, nbytes, cap = gpu.compress(w, prm, BF16, 4096)
+        assert rc == 0 and np.array_equal(out[:nbytes], oracle.compress(w, prm, 4096)[1])
+
+
+def test_batch_decompress_mixes_both_kinds(gpu, oracle):
+    torch, enec = gpu.torch, gpu.enec
+    ws = [_mixed16(5, 2048, 1), W.gaussian(30000, 0.02, 2), _mixed16(3, 16384, 3), W.gaussian(2048 * 4, 0.02, 4)]
+    streams = [oracle.compress_per_block(ws[0], 2048)[1], oracle.compress(ws[1], oracle.tune(ws[1]), 16384)[1],
+               oracle.compress_per_block(ws[2], 16384)[1], oracle.compress(ws[3], oracle.tune(ws[3]), 2048)[1]]
+    bufs = [torch.from_numpy(s).cuda() for s in streams]
+    outs = [torch.full((w.size,), 0x5A5A, dtype=torch.int16, device="cuda") for w in ws]
+    assert enec.decompress_batch(bufs, [s[:64].tobytes() for s in streams], outs) == 0
+    torch.cuda.synchronize()
+    for w, o in zip(ws, outs):
+        assert np.array_equal(o.cpu().numpy().view(np.uint16), w)
+
+
+def test_damaged_tuples_and_offsets_skip_blocks(gpu, oracle):
+    """A tuple or table entry that cannot be right makes the kernel leave that block alone."""
+    B = 2048
+    w = _mixed16(8, B, 21)
+    s = oracle.compress_per_block(w, B)[1]
+    at = oracle.table_end(w.size, B)
+    for what in ("n zero", "m above n", "n above 8", "offset"):
+        bad = s.copy()
+        k = 3
+        if what == "n zero":
+            bad[at + 4 * k + 1] = 0
+        elif what == "m above n":
+            bad[at + 4 * k + 2] = bad[at + 4 * k + 1] + 1
+        elif what == "n above 8":
+            bad[at + 4 * k + 1] = 9
+        else:
+            bad[64 + 8 * k:64 + 8 * k + 8] = np.frombuffer(np.uint64(1 << 40).tobytes(), np.uint8)
+        rc, d, rest = gpu.decompress(bad, w.size, BF16)
+        assert rc == 0 and (rest == 0x5A5A).all()
+        touched = {k, k - 1} if what == "offset" else {k}
+        for j in range(8):
+            blk = d[j * B:(j + 1) * B]
+            if j in touched:
+                assert (blk == 0x5A5A).all(), (what, j)
+            else:
+                assert np.array_equal(blk, w[j * B:(j + 1) * B]), (what, j)
+
+
+def test_host_checks(gpu):
+    torch, enec = gpu.torch, gpu.enec
+    src = torch.zeros(4096, dtype=torch.int16, device="cuda")
+    out = torch.zeros(enec.compress_bound_per_block(4096), dtype=torch.uint8, device="cuda")
+    assert enec.compress_per_block(src, out[:100], gpu.ws) == enec.E_CAPACITY
+    assert enec.compress_per_block(src, out, gpu.ws, block_size=3000) == enec.E_BLOCK
+    assert enec.compress_per_block(src, out, gpu.ws, dtype=7) == enec.E_DTYPE
+    assert enec.compress_per_block(src, out, gpu.ws[:3072]) == enec.E_CAPACITY
+    assert enec.compress_bound_per_block(4096, BF16, 2048) == enec.compress_bound(4096, BF16, 2048) + 16

@@ -48,6 +48,7 @@ def test_bounds_and_block_sizes_match_oracle(enec, oracle):
         for dt in (1, 2):                     # fp16, fp32
             for B in [2048, 16384]:
                 assert enec.compress_bound(n, dtype=dt, block_size=B) == oracle.compress_bound(n, B, dt)
+                assert enec.compress_bound_per_block(n, dtype=dt, block_size=B) == oracle.compress_bound_pb(n, B, dt)
     assert enec.compress_bound(100, block_size=3000) == 0
     assert enec.compress_bound(100, dtype=3) == 0
     assert enec.workspace_bytes(100, block_size=1000) == 0
