@@ -527,7 +527,8 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
     size_t first = ws_acc_words(workspace_bytes);
     first += first & 1;                                   // 16-byte aligned for the fill kernel
     const size_t words = ws_state_words(workspace_bytes);
-    const size_t need = 2 + nb + (nb & 1);
+    const size_t counters = 2;                            // the ticket, in 8-byte words
+    const size_t need = counters + nb + (nb & 1);
     if (words < first + need) return ENEC_E_CAPACITY;
     uint64_t *base = reinterpret_cast<uint64_t *>(static_cast<uint8_t *>(workspace) + WS_STATE) + first;
     const uint64_t nvec = need / 2;
@@ -538,7 +539,7 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
     a.out = static_cast<uint8_t *>(out);
     a.out_bytes = reinterpret_cast<unsigned long long *>(out_bytes);
     a.ticket = reinterpret_cast<uint32_t *>(base);
-    a.words = base + 2;
+    a.words = base + counters;
     a.n_elems = n_elems;
     a.tuples_at = table_end(n_elems, B);
     a.tail_base = a.tuples_at + tuple_table_bytes(n_elems, B);
@@ -552,8 +553,14 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
     PbCompressFn fn = pick_compress_per_block(dtype);
     if (!fn) return ENEC_E_DTYPE;
     const unsigned threads = B / 64 < 64 ? 64 : B / 64;
-    const size_t lds = (size_t)B / 128 + (size_t)B;       // mask | low plane | high records: at most 8 plane bits together
-    hipLaunchKernelGGL(fn, dim3((unsigned)nb), dim3(threads), lds, s, a);
+    // mask | low plane | high records (at most 8 plane bits together); before that the histogram copies
+    const size_t image = (size_t)B / 128 + (size_t)B, hist = (size_t)PB_HIST_COPIES * PB_HIST_STRIDE * 4;
+    const size_t lds = image > hist ? image : hist;
+    const unsigned grid = (unsigned)nb;
+#ifdef ENEC_PB_TIMING
+    a.dbg = reinterpret_cast<unsigned long long *>(static_cast<uint8_t *>(workspace) + WS_HIST);
+#endif
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 

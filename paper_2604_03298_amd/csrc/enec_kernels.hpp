@@ -25,6 +25,9 @@ ENEC_TABLES(dt2)
 
 // Streams with one tuple per data block (enec_per_block.hpp, compiled in enec_per_block.hip): the
 // widths are run-time values there, one kernel per element format and direction.
+// LDS copies of the block histogram in the compress kernel, and their distance in words
+constexpr uint32_t PB_HIST_COPIES = 16, PB_HIST_STRIDE = 257;   // words; 16 * 257 * 4 bytes of LDS
+
 struct PbCompressArgs {
     const void *in;
     uint8_t *out;
@@ -36,6 +39,9 @@ struct PbCompressArgs {
     uint64_t tail_base;         // fp32: where the lower halves go
     uint64_t payload_base;
     uint32_t nb, B, logB, spin_limit;
+#ifdef ENEC_PB_TIMING
+    unsigned long long *dbg;    // eight counters of 10 ns ticks per phase (development aid)
+#endif
 };
 
 struct PbDecompressArgs {

@@ -11,6 +11,14 @@
 #pragma once
 #include "enec_kernels.hpp"
 
+#ifdef ENEC_PB_TIMING
+#define PB_T(i) do { if (tid == 0) { const unsigned long long now_ = wall_clock64(); atomicAdd(p.dbg + (i), now_ - t_last_); t_last_ = now_; } } while (0)
+#define PB_T_DECL unsigned long long t_last_ = wall_clock64()
+#else
+#define PB_T(i)
+#define PB_T_DECL
+#endif
+
 namespace enec {
 
 // look-back word of a block: zero = nothing yet
@@ -18,6 +26,7 @@ constexpr uint64_t PB_PREFIX = 1ull << 63;     // [60:0] = end of this block's p
 constexpr uint64_t PB_SIZE = 1ull << 62;       // [60:0] = size of this block's payload, / 16
 constexpr uint64_t PB_GAVE_UP = 1ull << 61;    // somebody before (or this block) stopped waiting
 constexpr uint64_t PB_VALUE = (1ull << 61) - 1;
+constexpr int PB_WINDOW = 256;                  // blocks one look-back step covers (4 words per lane)
 
 // Alg. 2 over the low plane, one column (this thread's 8 rows) at a time: LOW[t][h] holds the
 // plane values of row t in byte lanes; normalized byte q of the thread's 8 columns goes to the image
@@ -169,6 +178,54 @@ __device__ __forceinline__ uint32_t pb_width_for(uint32_t b, uint32_t l, uint32_
     return w < E ? w : E;
 }
 
+// a1: the 8 rows of data block k as 128-bit vectors (a thread's 8 elements of a row are one vector,
+// two for fp32); elements beyond the tensor's end read as zero words
+template <int DT>
+__device__ __forceinline__ void pb_load_rows(const PbCompressArgs &p, uint32_t k, uint32_t tid, bool active,
+                                             uint32_t logC, uint4 (&raw)[DT == DT_FP32 ? 16 : 8])
+{
+    const uint64_t blk0 = (uint64_t)k << p.logB;
+    const uint32_t real = p.n_elems - blk0 < p.B ? (uint32_t)(p.n_elems - blk0) : p.B;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint32_t at = ((uint32_t)t << logC) + 8u * tid;         // first element of the thread in this row
+        if constexpr (DT == DT_FP32) {
+            uint4 u = make_uint4(0, 0, 0, 0), v = make_uint4(0, 0, 0, 0);
+            if (active && at < real) {
+                const uint32_t *in = reinterpret_cast<const uint32_t *>(p.in) + blk0 + at;
+                if (at + 8u <= real) {
+                    u = *reinterpret_cast<const uint4 *>(in);
+                    v = *reinterpret_cast<const uint4 *>(in + 4);
+                } else {
+                    uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (at + i < real) d[i] = in[i];
+                    u = make_uint4(d[0], d[1], d[2], d[3]);
+                    v = make_uint4(d[4], d[5], d[6], d[7]);
+                }
+            }
+            raw[2 * t] = u;
+            raw[2 * t + 1] = v;
+        } else {
+            uint4 r = make_uint4(0, 0, 0, 0);
+            if (active && at < real) {
+                const uint16_t *in = reinterpret_cast<const uint16_t *>(p.in) + blk0 + at;
+                if (at + 8u <= real) {
+                    r = *reinterpret_cast<const uint4 *>(in);
+                } else {
+                    uint32_t d[4] = {0, 0, 0, 0};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (at + i < real) d[i >> 1] |= (uint32_t)in[i] << (16 * (i & 1));
+                    r = make_uint4(d[0], d[1], d[2], d[3]);
+                }
+            }
+            raw[t] = r;
+        }
+    }
+}
+
 template <int DT>
 __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompressArgs p)
 {
@@ -188,17 +245,35 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
     const bool active = tid < nact;
     const uint32_t mask_bytes = B >> 7;
 
+    // One workgroup per data block.  Blocks are taken in the order in which workgroups start (a ticket),
+    // not by blockIdx: a workgroup then only ever waits for blocks whose workgroups are already
+    // running, and those publish their size before they wait for anything, so the look-back cannot
+    // deadlock, whatever part of the grid is resident.  (A persistent loop over blocks was tried: the
+    // compiler then keeps the constants of all sixteen packer instances in registers, about 250
+    // VGPRs, and the kernel is slower.)
+    PB_T_DECL;
     if (tid == 0) {
-        s_k = atomicAdd(p.ticket, 1u);                   // blocks are taken in the order workgroups start
+        s_k = atomicAdd(p.ticket, 1u);
         s_best = ~0ull;
         s_lo = 255u;
         s_hi = 0u;
         s_flags = 0u;
     }
-    for (uint32_t i = tid; i < 256u; i += blockDim.x) s_hist[i] = 0;
     __syncthreads();
     const uint32_t k = s_k;
     if (k >= p.nb) return;                               // (the grid has exactly nb workgroups)
+    PB_T(0);
+    uint4 raw[RW];
+    pb_load_rows<DT>(p, k, tid, active, logC, raw);
+    // Phase 1 counts into PB_HIST_COPIES copies of the histogram (lane i uses copy i mod 16), so that
+    // lanes with equal exponents, the normal case, do not queue up on one LDS word; the copies are
+    // PB_HIST_STRIDE words apart, which spreads one bin of all copies over the banks.  They share
+    // the dynamic LDS with the payload image, which is written only after the search.
+    uint32_t *hcopy = reinterpret_cast<uint32_t *>(smem);
+    for (uint32_t i = tid; i < PB_HIST_COPIES * PB_HIST_STRIDE / 4u; i += blockDim.x)
+        reinterpret_cast<uint4 *>(hcopy)[i] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+    uint32_t *mine = hcopy + (lane & (PB_HIST_COPIES - 1u)) * PB_HIST_STRIDE;
     const uint64_t blk0 = (uint64_t)k << p.logB;
     const uint32_t real = p.n_elems - blk0 < B ? (uint32_t)(p.n_elems - blk0) : B;   // elements that are not pads
 
@@ -207,40 +282,18 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const uint32_t at = ((uint32_t)t << logC) + 8u * tid;         // first element of the thread in this row
-        uint4 r16 = make_uint4(0, 0, 0, 0);
-        if (active && at < real) {
-            if constexpr (DT == DT_FP32) {
-                const uint32_t *in = reinterpret_cast<const uint32_t *>(p.in) + blk0 + at;
-                uint4 u, v;
-                if (at + 8u <= real) {
-                    u = *reinterpret_cast<const uint4 *>(in);
-                    v = *reinterpret_cast<const uint4 *>(in + 4);
-                } else {
-                    uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        if (at + i < real) d[i] = in[i];
-                    u = make_uint4(d[0], d[1], d[2], d[3]);
-                    v = make_uint4(d[4], d[5], d[6], d[7]);
-                }
-                r16 = make_uint4(byte_perm(u.y, u.x, 0x07060302u), byte_perm(u.w, u.z, 0x07060302u),
-                                 byte_perm(v.y, v.x, 0x07060302u), byte_perm(v.w, v.z, 0x07060302u));
-                // the lower halves leave at once (pads have zero lower halves; the region is padded to 16 bytes)
+        uint4 r16;
+        if constexpr (DT == DT_FP32) {
+            const uint4 u = raw[2 * t], v = raw[2 * t + 1];
+            r16 = make_uint4(byte_perm(u.y, u.x, 0x07060302u), byte_perm(u.w, u.z, 0x07060302u),
+                             byte_perm(v.y, v.x, 0x07060302u), byte_perm(v.w, v.z, 0x07060302u));
+            // the lower halves leave at once (pads have zero lower halves; the region is padded to 16 bytes)
+            if (active && at < real)
                 *reinterpret_cast<uint4 *>(p.out + p.tail_base + 2u * (blk0 + at)) =
                     make_uint4(byte_perm(u.y, u.x, 0x05040100u), byte_perm(u.w, u.z, 0x05040100u),
                                byte_perm(v.y, v.x, 0x05040100u), byte_perm(v.w, v.z, 0x05040100u));
-            } else {
-                const uint16_t *in = reinterpret_cast<const uint16_t *>(p.in) + blk0 + at;
-                if (at + 8u <= real) {
-                    r16 = *reinterpret_cast<const uint4 *>(in);
-                } else {
-                    uint32_t d[4] = {0, 0, 0, 0};
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        if (at + i < real) d[i >> 1] |= (uint32_t)in[i] << (16 * (i & 1));
-                    r16 = make_uint4(d[0], d[1], d[2], d[3]);
-                }
-            }
+        } else {
+            r16 = raw[t];
         }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -261,24 +314,31 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
                 const uint32_t e = at + 4u * h;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    if (e + i < real) atomicAdd(&s_hist[(X[t][h] >> (8 * i)) & 0xFFu], 1u);
+                    if (e + i < real) atomicAdd(&mine[(X[t][h] >> (8 * i)) & 0xFFu], 1u);
             }
         }
     }
     __syncthreads();
+    PB_T(1);
 
     // ---- phase 2: lowest and highest exponent, then every b in between with Eq. 1's n and Eq. 3's cost ----
-    for (uint32_t x = tid; x < 256u; x += blockDim.x)
-        if (s_hist[x]) {
+    for (uint32_t x = tid; x < 256u; x += blockDim.x) {
+        uint32_t c = 0;
+#pragma unroll 8
+        for (uint32_t i = 0; i < PB_HIST_COPIES; ++i) c += hcopy[i * PB_HIST_STRIDE + x];
+        s_hist[x] = c;
+        if (c) {
             atomicMin(&s_lo, x);
             atomicMax(&s_hi, x);
         }
+    }
     __syncthreads();
     const uint32_t xl = s_lo, xh = s_hi;
     for (uint32_t b = xl + tid; b <= xh; b += blockDim.x) {
         const uint32_t n = pb_width_for(b, xl, xh, E);
         const uint32_t nmask = (1u << n) - 1u;
         uint32_t D = 0;                                   // at most 2^15 elements * 255
+#pragma unroll 8
         for (uint32_t x = xl; x <= xh; ++x) D += s_hist[x] * ((b - x) & nmask);
         atomicMin(&s_best, ((unsigned long long)D << 16) | (n << 8) | b);     // ties: smaller n, then smaller b
     }
@@ -288,6 +348,7 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
     if (tid <= n) {
         const uint32_t nmask = (1u << n) - 1u;
         uint32_t cnt = 0;
+#pragma unroll 8
         for (uint32_t x = xl; x <= xh; ++x)
             if (((b - x) & nmask) < (1u << tid)) cnt += s_hist[x];
         const double q = (double)cnt / (double)real;
@@ -303,6 +364,7 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
         s_m = best_m;
     }
     __syncthreads();
+    PB_T(2);
     const uint32_t m = s_m, a = n - m;
     const uint32_t lm = m + (DT == DT_FP16 ? 3u : 0u);
 
@@ -361,6 +423,7 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
         }
     }
     __syncthreads();
+    PB_T(3);
 
     // ---- a5 positions: exclusive popcount prefix over the mask words (a wave scan per wave) ----
     const uint32_t nwords = B >> 9;
@@ -385,38 +448,59 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
     default: break;
     }
 
-    // ---- a6 (wave 0): look back over the earlier blocks, 64 at a time, until one of them carries
-    // its inclusive prefix.  Block j's workgroup started before this one (tickets), and it publishes
-    // its size before it waits for anything, so every wait ends; the spin limit is a safety net. ----
+    PB_T(4);
+    // ---- a6 (wave 0): look back over the earlier blocks, PB_WINDOW at a time (lane i reads blocks
+    // top - i, top - 64 - i, ...), until one of them carries its inclusive prefix.  A lower block is held
+    // by a workgroup that publishes its size before it waits for anything (see above), so every wait
+    // ends; the spin limit is a safety net. ----
     if (wave == 0) {
         uint64_t sum = 0;
         uint32_t flags = 0;
         int64_t top = (int64_t)k - 1;                    // highest block of the current window
         while (top >= 0) {
-            const int64_t j = top - (int64_t)lane;
-            uint64_t v = 0;
-            uint32_t spins = 0;
-            bool ok = j < 0;
-            uint64_t stop = 0;                           // lanes at or above the first prefix word
+            uint64_t v[PB_WINDOW / 64];
+            bool ok[PB_WINDOW / 64];
+#pragma unroll
+            for (int w = 0; w < PB_WINDOW / 64; ++w) { v[w] = 0; ok[w] = top - 64 * w - (int64_t)lane < 0; }
+            uint32_t spins = 0, first_w = PB_WINDOW / 64, first_lane = 64;
             for (;;) {
-                if (!ok) {
-                    v = ld_state(p.words + j);
-                    ok = v != 0;
+#pragma unroll
+                for (int w = 0; w < PB_WINDOW / 64; ++w)
+                    if (!ok[w]) v[w] = ld_state(p.words + (top - 64 * w - (int64_t)lane));
+                // the nearest block with a prefix; everything above it must be there
+                bool missing = false;
+                first_w = PB_WINDOW / 64;
+                first_lane = 64;
+#pragma unroll
+                for (int w = 0; w < PB_WINDOW / 64; ++w) {
+                    if (!ok[w]) ok[w] = v[w] != 0;
+                    if (first_w == PB_WINDOW / 64) {
+                        const uint64_t stop = __builtin_amdgcn_ballot_w64((v[w] & PB_PREFIX) != 0);
+                        const uint64_t need = stop ? ((stop & (~stop + 1ull)) << 1) - 1ull : ~0ull;
+                        if (__builtin_amdgcn_ballot_w64(!ok[w]) & need) missing = true;
+                        if (stop) { first_w = w; first_lane = (uint32_t)__builtin_ctzll(stop); }
+                    }
                 }
-                stop = __builtin_amdgcn_ballot_w64(j >= 0 && (v & PB_PREFIX));
-                // everything up to the nearest prefix word (or the whole window) must be there
-                const uint64_t need = stop ? ((stop & (~stop + 1ull)) << 1) - 1ull : ~0ull;
-                if ((__builtin_amdgcn_ballot_w64(!ok) & need) == 0) break;
+                if (!missing) break;
                 if (++spins > p.spin_limit) { flags |= 4u; break; }
                 spin_pause(spins);
             }
+#ifdef ENEC_PB_TIMING
+            if (lane == 0) { atomicAdd(p.dbg + 8, (unsigned long long)spins); atomicAdd(p.dbg + 9, 1ull); }
+#endif
             if (flags & 4u) break;
-            const uint32_t first = stop ? (uint32_t)__builtin_ctzll(stop) : 64u;
-            const bool use = j >= 0 && lane <= first;
-            if (__builtin_amdgcn_ballot_w64(use && (v & PB_GAVE_UP))) flags |= 4u;
-            sum += wave_sum(use ? (v & PB_VALUE) : 0ull);
-            if (stop) break;
-            top -= 64;
+            uint64_t part = 0;
+            bool gave_up = false;
+#pragma unroll
+            for (int w = 0; w < PB_WINDOW / 64; ++w) {
+                const bool use = top - 64 * w - (int64_t)lane >= 0 &&
+                                 ((uint32_t)w < first_w || ((uint32_t)w == first_w && lane <= first_lane));
+                if (use) { part += v[w] & PB_VALUE; gave_up |= (v[w] & PB_GAVE_UP) != 0; }
+            }
+            if (__builtin_amdgcn_ballot_w64(gave_up)) flags |= 4u;
+            sum += wave_sum(part);
+            if (first_w != PB_WINDOW / 64) break;
+            top -= PB_WINDOW;
         }
         if (lane == 0) {
             s_off = sum << 4;
@@ -425,6 +509,7 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
         }
     }
     __syncthreads();
+    PB_T(5);
 
     // ---- a7: stores ----
     const uint64_t off = s_off;
@@ -493,6 +578,7 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
             if (p.out_bytes) *p.out_bytes = total;
         }
     }
+    PB_T(6);
 }
 
 // ---------------------------------------------------------------------------------

@@ -79,6 +79,53 @@ def run_group(torch, enec, name, srcs, reps=5, dtype=0, lengths=None):
     }, (outs, stream_bytes, hdrs, backs)
 
 
+def run_per_block(torch, enec, name, srcs, reps=5, dtype=0):
+    """The same measurement for streams with one tuple per data block (one launch per tensor)."""
+    n_el = [s.numel() for s in srcs]
+    raw = srcs[0].element_size() * sum(n_el)
+    ws = enec.new_workspace(max(n_el))
+    outs = [torch.empty(enec.compress_bound_per_block(n, dtype=dtype), dtype=torch.uint8, device="cuda") for n in n_el]
+    sizes = torch.zeros(len(srcs), dtype=torch.int64, device="cuda")
+
+    def comp():
+        for i, s in enumerate(srcs):
+            rc = enec.compress_per_block(s, outs[i], ws, out_bytes=sizes[i:i + 1], dtype=dtype)
+            assert rc == 0, enec.strerror(rc)
+
+    comp()
+    torch.cuda.synchronize()
+    stream_bytes = [int(v) for v in sizes.cpu()]
+    assert all(v > 0 for v in stream_bytes)
+    hdrs = [o[:64].cpu().numpy().tobytes() for o in outs]
+    backs = [torch.empty_like(s) for s in srcs]
+    items = enec.make_decompress_items(outs, hdrs, backs)
+
+    def decomp():
+        rc = enec.decompress_batch(None, None, None, items=items[0])
+        assert rc == 0, enec.strerror(rc)
+
+    decomp()
+    torch.cuda.synchronize()
+    assert all(torch.equal(b, s) for b, s in zip(backs, srcs)), "round trip is not bit-exact"
+    evs = [_events(torch, 3) for _ in range(reps)]
+    comp(); decomp()
+    for e in evs:
+        e[0].record(); comp(); e[1].record(); decomp(); e[2].record()
+    torch.cuda.synchronize()
+    tc = float(np.median([e[0].elapsed_time(e[1]) for e in evs]))
+    td = float(np.median([e[1].elapsed_time(e[2]) for e in evs]))
+    moved = raw + sum(stream_bytes)
+    return {
+        "config": name, "tensors": len(srcs), "uncompressed_bytes": raw, "compression_ratio": round(raw / sum(stream_bytes), 4),
+        "params": "one tuple per data block",
+        "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
+        "compress_GBps": round(raw / tc / 1e6, 1), "decompress_GBps": round(raw / td / 1e6, 1),
+        "compress_frac_of_hbm_peak": round(moved / tc / 1e6 / HBM_PEAK, 4),
+        "decompress_frac_of_hbm_peak": round(moved / td / 1e6 / HBM_PEAK, 4),
+        "roundtrip_bit_exact": True,
+    }
+
+
 def gpu_gaussian(torch, rows, cols, std, seed, dtype=None):
     """N(0, std^2) drawn on the GPU, as bit patterns: int16 for bf16 (default) and float16, int32 for float32."""
     dtype = torch.bfloat16 if dtype is None else dtype
@@ -147,7 +194,7 @@ def offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--configs", default="1,2,2j,3a,3b,4,5,fp16,fp32")
+    ap.add_argument("--configs", default="1,2,2j,2p,3a,3p,3b,4,5,fp16,fp32")
     args = ap.parse_args()
     want = args.configs.split(",")
     import torch
@@ -167,6 +214,12 @@ def main():
                                    [dev(w) for _, w in W.config2()], reps=20, lengths=(8, 16, 32))[0]), flush=True)
     if "3a" in want:
         print(json.dumps(run_group(torch, enec, "3a: edge-case mix, one tensor", [dev(W.config3()[0])], reps=10)[0]), flush=True)
+    if "3p" in want:      # the same tensor with one tuple per data block
+        print(json.dumps(run_per_block(torch, enec, "3p: edge-case mix, one tensor, one tuple per data block",
+                                       [dev(W.config3()[0])], reps=10)), flush=True)
+    if "2p" in want:
+        print(json.dumps(run_per_block(torch, enec, "2p: 7B-style decoder layer, one tuple per data block",
+                                       [dev(w) for _, w in W.config2()], reps=20)), flush=True)
     if "3b" in want:
         for c, t in enumerate(W.config3_by_category()):
             name = ["zero blocks", "constant blocks", "Student-t blocks", "random 16-bit patterns"][c]
