@@ -56,3 +56,46 @@ def test_compress_and_decompress_replay_from_a_graph(oracle):
             assert int(sizes[i]) == want[i].size, (replay, i)
             assert np.array_equal(outs[i][:want[i].size].cpu().numpy(), want[i]), (replay, i)
             assert np.array_equal(backs[i].cpu().numpy().view(np.uint16), t), (replay, i)
+
+
+def test_one_tuple_per_block_replays_from_a_graph(oracle):
+    """The per-block call clears its look-back words with a fill kernel (no memset), so it can be captured too."""
+    import torch
+    from paper_2604_03298_amd import enec
+    enec.lib()
+    rng = np.random.default_rng(5)
+    t = np.concatenate([W.gaussian(7 * 16384, 0.02, 1), np.zeros(16384, np.uint16),
+                        rng.integers(0, 65536, 16384).astype(np.uint16), W.gaussian(3 * 16384 + 55, 0.2, 2)])
+    want = oracle.compress_per_block(t, 16384)[1]
+    src = torch.from_numpy(t.view(np.int16)).cuda()
+    out = torch.zeros(enec.compress_bound_per_block(t.size), dtype=torch.uint8, device="cuda")
+    back = torch.zeros_like(src)
+    size = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ws = enec.new_workspace(t.size)
+    hdr = want[:64].tobytes()
+
+    def step():
+        assert enec.compress_per_block(src, out, ws, out_bytes=size) == 0
+        assert enec.decompress_with_header(out, hdr, back) == 0
+
+    step()
+    torch.cuda.synchronize()
+    assert int(size) == want.size and np.array_equal(out[:want.size].cpu().numpy(), want)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        step()
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for replay in range(4):
+        out.zero_(); back.zero_(); size.zero_()
+        if replay % 2:
+            step()
+            out.zero_(); back.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(size) == want.size, replay
+        assert np.array_equal(out[:want.size].cpu().numpy(), want), replay
+        assert np.array_equal(back.cpu().numpy().view(np.uint16), t), replay

@@ -173,3 +173,15 @@ def test_host_checks(gpu):
     assert enec.compress_per_block(src, out, gpu.ws, dtype=7) == enec.E_DTYPE
     assert enec.compress_per_block(src, out, gpu.ws[:3072]) == enec.E_CAPACITY
     assert enec.compress_bound_per_block(4096, BF16, 2048) == enec.compress_bound(4096, BF16, 2048) + 16
+
+
+def test_configuration_3_at_full_size(gpu, oracle):
+    """All 4096 data blocks of the edge-case mix (134 MB), the launch the report times: the whole stream against the oracle's."""
+    w, cat = W.config3()
+    rc_o, s_o = oracle.compress_per_block(w, 16384)
+    assert rc_o == oracle.OK
+    rc, out, nbytes, cap = _compress(gpu, w, BF16, 16384)
+    assert rc == 0 and nbytes == s_o.size
+    assert np.array_equal(out[:nbytes], s_o)
+    rc, d, rest = gpu.decompress(s_o, w.size, BF16)
+    assert rc == 0 and np.array_equal(d, w)
