@@ -185,3 +185,40 @@ def test_configuration_3_at_full_size(gpu, oracle):
     assert np.array_equal(out[:nbytes], s_o)
     rc, d, rest = gpu.decompress(s_o, w.size, BF16)
     assert rc == 0 and np.array_equal(d, w)
+
+
+def test_repeated_and_back_to_back_calls_give_the_same_bytes(gpu, oracle):
+    """The look-back must not depend on timing: the same stream 60 times, calls queued without synchronisation,
+    two tensors alternating on one workspace."""
+    torch, enec = gpu.torch, gpu.enec
+    ws_a, ws_b = _mixed16(300, 2048, 31), _mixed16(37, 16384, 32)
+    want = [oracle.compress_per_block(w, B)[1] for w, B in ((ws_a, 2048), (ws_b, 16384))]
+    srcs = [gpu.to_dev(w, BF16) for w in (ws_a, ws_b)]
+    outs = [[torch.zeros(enec.compress_bound_per_block(w.size, block_size=B) + 64, dtype=torch.uint8, device="cuda")
+             for _ in range(30)] for w, B in ((ws_a, 2048), (ws_b, 16384))]
+    for rep in range(30):
+        assert enec.compress_per_block(srcs[0], outs[0][rep], gpu.ws, block_size=2048) == 0
+        assert enec.compress_per_block(srcs[1], outs[1][rep], gpu.ws, block_size=16384) == 0
+    torch.cuda.synchronize()
+    for t in range(2):
+        for rep in range(30):
+            got = outs[t][rep].cpu().numpy()
+            assert np.array_equal(got[:want[t].size], want[t]), (t, rep)
+
+
+def test_two_streams_two_workspaces(gpu, oracle):
+    torch, enec = gpu.torch, gpu.enec
+    w1, w2 = _mixed16(64, 16384, 41), _mixed16(64, 16384, 42)
+    want = [oracle.compress_per_block(w, 16384)[1] for w in (w1, w2)]
+    srcs = [gpu.to_dev(w, BF16) for w in (w1, w2)]
+    outs = [torch.zeros(enec.compress_bound_per_block(w.size), dtype=torch.uint8, device="cuda") for w in (w1, w2)]
+    wss = [enec.new_workspace(w.size) for w in (w1, w2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for i in range(2):
+            with torch.cuda.stream(streams[i]):
+                assert enec.compress_per_block(srcs[i], outs[i], wss[i], stream=streams[i]) == 0
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert np.array_equal(outs[i].cpu().numpy()[:want[i].size], want[i]), i
