@@ -28,9 +28,13 @@
 
 // Phase-timestamp hook for bench experiments; expands to nothing in the library.
 // Three waves per SIMD for the compression kernel: the register budget (168) that lets three
-// workgroups of 256 threads share a CU.
+// workgroups of 256 threads share a CU.  The fp32 instances (twice the row registers) and the
+// instances for group lengths 8 and 32 (larger record packers) spill at that budget and run
+// faster with two (measured: L = 8 layer 0.25 -> 0.21 ms, L = 32 on 2 x 90 MB 0.133 -> 0.102 ms;
+// L = 16 is faster with three, 0.082 against 0.091 ms).
 #ifndef ENEC_COMPRESS_OCCUPANCY
-#define ENEC_COMPRESS_OCCUPANCY __attribute__((amdgpu_waves_per_eu(DT == 2 ? 2 : 3, DT == 2 ? 2 : 3)))
+#define ENEC_COMPRESS_WAVES ((DT == 2 || LPG != 2) ? 2 : 3)
+#define ENEC_COMPRESS_OCCUPANCY __attribute__((amdgpu_waves_per_eu(ENEC_COMPRESS_WAVES, ENEC_COMPRESS_WAVES)))
 #endif
 #ifndef ENEC_TP
 #define ENEC_TP_DECL
