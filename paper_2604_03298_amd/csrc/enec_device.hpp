@@ -492,9 +492,11 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 
     // the block waiting to be stored
     uint32_t pend = NO_BLOCK, pend_item = 0, pend_cnt = 0, pend_S = 0, pend_err = 0;   // pend: index inside its tensor
-    uint32_t SMp[8][2];
+    // its sign/mantissa bytes wait in LDS behind the two images, every thread's own 64 bytes (in
+    // registers they were what the compiler spilled)
+    uint8_t *sm_wait = smem + 2u * img_bytes;
 
-    // stores block `kb` whose packed part sits in image `img` and whose sign/mantissa bytes sit in SMp
+    // stores block `kb` whose packed part sits in image `img` and whose sign/mantissa bytes sit in sm_wait
     auto store_block = [&](const CompressItem &it, uint32_t kb, uint32_t cnt, uint32_t S, const uint8_t *img,
                            uint32_t err_own) {
         const uint64_t off = s_off;
@@ -502,7 +504,8 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         if (active) {
 #pragma unroll
             for (int t = 0; t < 8; ++t)
-                *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SMp[t][0], SMp[t][1]);
+                *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) =
+                    *reinterpret_cast<const uint2 *>(sm_wait + ((size_t)t << logC) + 8u * tid);
         }
         for (uint32_t v = tid; v < (mask_bytes >> 4); v += blockDim.x)
             *reinterpret_cast<uint4 *>(dst + B + 16u * v) = *reinterpret_cast<const uint4 *>(img + 16u * v);
@@ -903,7 +906,9 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 
         // this block becomes the pending one
 #pragma unroll
-        for (int t = 0; t < 8; ++t) { SMp[t][0] = SMc[t][0]; SMp[t][1] = SMc[t][1]; }
+        for (int t = 0; t < 8; ++t)
+            if (active)
+                *reinterpret_cast<uint2 *>(sm_wait + ((size_t)t << logC) + 8u * tid) = make_uint2(SMc[t][0], SMc[t][1]);
         pend = kl; pend_item = ci; pend_cnt = cnt; pend_S = S; pend_err = own_err;
         slot ^= 1u;
         k = knext;
