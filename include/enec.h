@@ -215,13 +215,15 @@ int enec_compress_sampled(const void *in, size_t n_elems, int dtype, uint32_t bl
  *   table and the fp32 region / the payloads.
  * enec_decompress, enec_decompress_with_header and enec_decompress_batch read such streams as any
  * other (a launch of its own per stream).  Arguments as for enec_compress, without params;
+ * group_length = 8, 16, 32 or 0 (= 16) is the group length the blocks are coded with (ENEC_E_PARAMS if
+ * the block size does not admit it; the search itself evaluates Eq. 4 with L = 16, as enec_tune does);
  * out_capacity >= enec_compress_bound_per_block(n_elems, dtype, block_size) (0 for an invalid dtype
  * or block size).  The workspace is used as by enec_compress and must not be shared with a call
  * that is still running.  Asynchronous. */
 size_t enec_compress_bound_per_block(size_t n_elems, int dtype, uint32_t block_size);
-int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t block_size, void *out,
-                            size_t out_capacity, uint64_t *out_bytes, void *workspace, size_t workspace_bytes,
-                            void *stream);
+int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t block_size, uint32_t group_length,
+                            void *out, size_t out_capacity, uint64_t *out_bytes, void *workspace,
+                            size_t workspace_bytes, void *stream);
 
 /* Host-only search of Sec. V-E phases 2-3 on a given 256-bin exponent histogram (HOST); dtype
  * fixes the cap of Eq. 1's width (the exponent field: 8 bits, fp16: 5). */

@@ -505,9 +505,9 @@ size_t enec_compress_bound_per_block(size_t n_elems, int dtype, uint32_t block_s
     return bound + tuple_table_bytes(n_elems, B);
 }
 
-int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t block_size, void *out,
-                            size_t out_capacity, uint64_t *out_bytes, void *workspace, size_t workspace_bytes,
-                            void *stream)
+int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t block_size, uint32_t group_length,
+                            void *out, size_t out_capacity, uint64_t *out_bytes, void *workspace,
+                            size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
     if (!out || !workspace || (!in && n_elems) || !aligned16(in) || !aligned16(out) || !aligned16(workspace) ||
@@ -515,13 +515,15 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
         return ENEC_E_ARG;
     const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
     if (!block_ok(B)) return ENEC_E_BLOCK;
+    const unsigned L = group_length ? group_length : 16u;
+    if (!group_ok(L) || !group_fits_block(L, B)) return ENEC_E_PARAMS;
     if (out_capacity < enec_compress_bound_per_block(n_elems, dtype, B)) return ENEC_E_CAPACITY;
     if (out_bytes && !device_accessible(out_bytes)) return ENEC_E_ARG;
     const size_t nb = num_blocks(n_elems, B);
     hipStream_t s = (hipStream_t)stream;
     if (nb == 0) {
         compress_empty_kernel<<<1, 64, 0, s>>>(static_cast<uint8_t *>(out), out_bytes, B, 0, 0, 0, (uint32_t)dtype,
-                                               16u | 0x100u);
+                                               L | 0x100u);
         return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
     }
     // look-back words (and the ticket in front of them) behind the accumulators, cleared for this call
@@ -551,11 +553,11 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
         const long v = std::atol(e);
         if (v > 0 && v < (long)SPIN_LIMIT) a.spin_limit = (uint32_t)v;
     }
-    PbCompressFn fn = pick_compress_per_block(dtype);
+    PbCompressFn fn = pick_compress_per_block(dtype, L);
     if (!fn) return ENEC_E_DTYPE;
     const unsigned threads = B / 64 < 64 ? 64 : B / 64;
     // mask | low plane | high records (at most 8 plane bits together); before that the histogram copies
-    const size_t image = (size_t)B / 128 + (size_t)B, hist = (size_t)PB_HIST_COPIES * PB_HIST_STRIDE * 4;
+    const size_t image = (size_t)B / (8 * L) + (size_t)B, hist = (size_t)PB_HIST_COPIES * PB_HIST_STRIDE * 4;
     const size_t lds = image > hist ? image : hist;
     const unsigned grid = (unsigned)nb;
 #ifdef ENEC_PB_TIMING
@@ -580,7 +582,7 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
             h.nb != num_blocks(it.n_elems, h.B) || !group_fits_block(h.prm.L, h.B) || h.total > it.in_bytes)
             return ENEC_E_FORMAT;
         if (h.per_block) {
-            if (h.prm.L != 16 || h.prm.n != 0 || h.prm.m != 0 || h.prm.b != 0 ||
+            if (h.prm.n != 0 || h.prm.m != 0 || h.prm.b != 0 ||
                 h.total < payload_base(it.n_elems, h.B, h.dtype) + tuple_table_bytes(it.n_elems, h.B))
                 return ENEC_E_FORMAT;
         } else if (h.prm.n < 1 || h.prm.n > exp_bits(h.dtype) || h.prm.m > h.prm.n ||
@@ -604,10 +606,10 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
             a.payload_bytes = h.total - a.payload_base;
             a.nb = h.nb; a.B = h.B; a.logB = ilog2(h.B);
             std::memcpy(a.hdr, items[i].host_header, sizeof a.hdr);
-            PbDecompressFn fn = pick_decompress_per_block(h.dtype);
+            PbDecompressFn fn = pick_decompress_per_block(h.dtype, h.prm.L);
             if (!fn) return ENEC_E_FORMAT;
             const unsigned threads = h.B / 64 < 64 ? 64 : h.B / 64;
-            const size_t lds = (size_t)h.B / 128 + h.B + 16;     // the packed part of the widest block
+            const size_t lds = (size_t)h.B / (8 * h.prm.L) + h.B + 16;     // the packed part of the widest block
             hipLaunchKernelGGL(fn, dim3(h.nb), dim3(threads), lds, (hipStream_t)stream, a);
             done[i] = 1;
             continue;

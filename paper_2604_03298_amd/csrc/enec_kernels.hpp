@@ -24,7 +24,7 @@ ENEC_TABLES(dt2)
 #undef ENEC_TABLES
 
 // Streams with one tuple per data block (enec_per_block.hpp, compiled in enec_per_block.hip): the
-// widths are run-time values there, one kernel per element format and direction.
+// widths are run-time values there, one kernel per element format, group length and direction.
 // LDS copies of the block histogram in the compress kernel, and their distance in words
 constexpr uint32_t PB_HIST_COPIES = 16, PB_HIST_STRIDE = 257;   // words; 16 * 257 * 4 bytes of LDS
 
@@ -55,7 +55,7 @@ struct PbDecompressArgs {
 
 using PbCompressFn = void (*)(const PbCompressArgs);
 using PbDecompressFn = void (*)(const PbDecompressArgs);
-PbCompressFn pick_compress_per_block(int dtype);
-PbDecompressFn pick_decompress_per_block(int dtype);
+PbCompressFn pick_compress_per_block(int dtype, unsigned L);
+PbDecompressFn pick_decompress_per_block(int dtype, unsigned L);
 
 }  // namespace enec

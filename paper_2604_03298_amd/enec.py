@@ -87,7 +87,7 @@ def lib():
         L.enec_compress_bound_per_block.restype = sz
         L.enec_compress_bound_per_block.argtypes = [sz, C.c_int, C.c_uint32]
         L.enec_compress_per_block.restype = C.c_int
-        L.enec_compress_per_block.argtypes = [vp, sz, C.c_int, C.c_uint32, vp, sz, vp, vp, sz, vp]
+        L.enec_compress_per_block.argtypes = [vp, sz, C.c_int, C.c_uint32, C.c_uint32, vp, sz, vp, vp, sz, vp]
         L.enec_tune_sampled.restype = C.c_int
         L.enec_tune_sampled.argtypes = [vp, sz, C.c_int, C.c_uint32, C.POINTER(Params), u64p, vp, sz, vp]
         L.enec_compress_sampled.restype = C.c_int
@@ -222,14 +222,14 @@ def compress_bound_per_block(n_elems: int, dtype: int = BF16, block_size: int = 
 
 
 def compress_per_block(src, out, workspace, block_size: int = 0, out_bytes=None, stream=None,
-                       n_elems: int | None = None, dtype: int | None = None) -> int:
+                       n_elems: int | None = None, dtype: int | None = None, group_length: int = 0) -> int:
     """Enqueues enec_compress_per_block: every data block is coded with the tuple tuned on its own
     exponents.  out: device uint8 tensor of >= compress_bound_per_block bytes."""
     n = src.numel() if n_elems is None else n_elems
     dt = dtype_of(src, dtype)
     ob = C.c_void_p(out_bytes.data_ptr()) if out_bytes is not None else None
     return int(lib().enec_compress_per_block(
-        C.c_void_p(src.data_ptr()), n, dt, block_size, C.c_void_p(out.data_ptr()),
+        C.c_void_p(src.data_ptr()), n, dt, block_size, group_length, C.c_void_p(out.data_ptr()),
         out.numel() * out.element_size(), ob, C.c_void_p(workspace.data_ptr()),
         workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 

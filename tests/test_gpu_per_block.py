@@ -10,22 +10,23 @@ from test_gpu_dtypes import gpu, BF16, FP16, FP32, WORD  # noqa: F401  (fixture)
 pytestmark = pytest.mark.gpu
 
 
-def _compress(gpu, w, dtype, B=0):
+def _compress(gpu, w, dtype, B=0, L=0):
     torch, enec = gpu.torch, gpu.enec
     src = gpu.to_dev(w, dtype)
     cap = enec.compress_bound_per_block(w.size, dtype=dtype, block_size=B)
     out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device="cuda")
     gpu.size_pinned.fill_(-1)
-    rc = enec.compress_per_block(src, out, gpu.ws, block_size=B, out_bytes=gpu.size_pinned, n_elems=w.size, dtype=dtype)
+    rc = enec.compress_per_block(src, out, gpu.ws, block_size=B, out_bytes=gpu.size_pinned, n_elems=w.size, dtype=dtype,
+                                 group_length=L)
     torch.cuda.synchronize()
     return rc, out.cpu().numpy(), int(gpu.size_pinned.item()), cap
 
 
-def _check(gpu, oracle, w, dtype, B=0, label=""):
+def _check(gpu, oracle, w, dtype, B=0, label="", L=0):
     Bo = B if B else oracle.default_block(w.size)
-    rc_o, s_o = oracle.compress_per_block(w, Bo, dtype)
+    rc_o, s_o = oracle.compress_per_block(w, Bo, dtype, L if L else 16)
     assert rc_o == oracle.OK, label
-    rc, out, nbytes, cap = _compress(gpu, w, dtype, B)
+    rc, out, nbytes, cap = _compress(gpu, w, dtype, B, L)
     assert rc == 0, label
     assert nbytes == s_o.size, f"{label}: size {nbytes} vs oracle {s_o.size}"
     bad = np.nonzero(out[:nbytes] != s_o)[0]
@@ -222,3 +223,21 @@ def test_two_streams_two_workspaces(gpu, oracle):
     torch.cuda.synchronize()
     for i in range(2):
         assert np.array_equal(outs[i].cpu().numpy()[:want[i].size], want[i]), i
+
+
+@pytest.mark.parametrize("L", [8, 32])
+def test_group_lengths_8_and_32(gpu, oracle, L):
+    """Blocks coded with groups of 8 or 32 elements (the search is the same, the records differ)."""
+    for B in ((2048, 16384) if L == 8 else (4096, 16384, 32768)):
+        w = _mixed16(11, B, 500 + B + L)
+        _check(gpu, oracle, w, BF16, B, f"L={L} B={B}", L)
+        _check(gpu, oracle, w[:w.size - B // 3 - 1], BF16, B, f"L={L} B={B} ragged", L)
+    w = _mixed16(7, 16384, 77 + L, FP16)
+    _check(gpu, oracle, w, FP16, 16384, f"fp16 L={L}", L)
+    parts = [W.gaussian_fp32(16384 * 2, 0.02, 1), np.zeros(16384, np.uint32), W.gaussian_fp32(16384 + 99, 300.0, 2)]
+    _check(gpu, oracle, np.concatenate(parts), FP32, 16384, f"fp32 L={L}", L)
+    torch, enec = gpu.torch, gpu.enec
+    src = torch.zeros(4096, dtype=torch.int16, device="cuda")
+    out = torch.zeros(enec.compress_bound_per_block(4096), dtype=torch.uint8, device="cuda")
+    assert enec.compress_per_block(src, out, gpu.ws, block_size=2048, group_length=32) == enec.E_PARAMS
+    assert enec.compress_per_block(src, out, gpu.ws, block_size=2048, group_length=12) == enec.E_PARAMS
