@@ -469,7 +469,8 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
         const size_t plane_bits = prep[i].prm.n + (dtype == ENEC_FP16 ? 3 : 0);
         // two images of the packed part, and the sign/mantissa bytes of the block that waits to be stored
-        const size_t lds = 2 * ((size_t)a.B / (8 * prep[i].prm.L) + plane_bits * a.B / 8) + a.B;
+        const size_t lds = 2 * ((size_t)a.B / (8 * prep[i].prm.L) + plane_bits * a.B / 8) +
+                           (compress_sm_in_lds(dtype, prep[i].prm.L == 8 ? 1 : prep[i].prm.L == 16 ? 2 : 4) ? a.B : 0);
         const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_COMPRESS_WGS_PER_CU");
         if (resident == 0) return ENEC_E_HIP;
         const unsigned grid = a.total < resident ? a.total : resident;

@@ -33,7 +33,7 @@
 // faster with two (measured: L = 8 layer 0.25 -> 0.21 ms, L = 32 on 2 x 90 MB 0.133 -> 0.102 ms;
 // L = 16 is faster with three, 0.082 against 0.091 ms).
 #ifndef ENEC_COMPRESS_OCCUPANCY
-#define ENEC_COMPRESS_WAVES ((DT == 2 || LPG != 2) ? 2 : 3)
+#define ENEC_COMPRESS_WAVES (compress_sm_in_lds(DT, LPG) ? 3 : 2)
 #define ENEC_COMPRESS_OCCUPANCY __attribute__((amdgpu_waves_per_eu(ENEC_COMPRESS_WAVES, ENEC_COMPRESS_WAVES)))
 #endif
 #ifndef ENEC_TP
@@ -47,6 +47,9 @@ namespace enec {
 constexpr int DT_BF16 = 0, DT_FP16 = 1, DT_FP32 = 2;
 constexpr int low_plane_bits(int m, int dt) { return m + (dt == DT_FP16 ? 3 : 0); }
 constexpr uint32_t exponent_bits(int dt) { return dt == DT_FP16 ? 5u : 8u; }
+// the compress instances that run three waves per SIMD (16-bit formats with group length 16) and
+// therefore park the waiting block's sign/mantissa bytes in LDS; the others get two waves
+constexpr bool compress_sm_in_lds(int dt, int lpg) { return dt != DT_FP32 && lpg == 2; }
 
 // ---------------------------------------------------------------------------------
 // Compile-time bit map of Alg. 2 for one column (8 values of W bits -> W bytes).
@@ -493,8 +496,11 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     // the block waiting to be stored
     uint32_t pend = NO_BLOCK, pend_item = 0, pend_cnt = 0, pend_S = 0, pend_err = 0;   // pend: index inside its tensor
     // its sign/mantissa bytes wait in LDS behind the two images, every thread's own 64 bytes (in
-    // registers they were what the compiler spilled)
+    // registers they were what the compiler spilled); the instances built for two waves per SIMD have
+    // the registers and keep them there
+    constexpr bool SM_IN_LDS = compress_sm_in_lds(DT, LPG);
     uint8_t *sm_wait = smem + 2u * img_bytes;
+    uint32_t SMp[SM_IN_LDS ? 1 : 8][2];
 
     // stores block `kb` whose packed part sits in image `img` and whose sign/mantissa bytes sit in sm_wait
     auto store_block = [&](const CompressItem &it, uint32_t kb, uint32_t cnt, uint32_t S, const uint8_t *img,
@@ -504,8 +510,11 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         if (active) {
 #pragma unroll
             for (int t = 0; t < 8; ++t)
-                *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) =
-                    *reinterpret_cast<const uint2 *>(sm_wait + ((size_t)t << logC) + 8u * tid);
+                if constexpr (SM_IN_LDS)
+                    *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) =
+                        *reinterpret_cast<const uint2 *>(sm_wait + ((size_t)t << logC) + 8u * tid);
+                else
+                    *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SMp[t][0], SMp[t][1]);
         }
         for (uint32_t v = tid; v < (mask_bytes >> 4); v += blockDim.x)
             *reinterpret_cast<uint4 *>(dst + B + 16u * v) = *reinterpret_cast<const uint4 *>(img + 16u * v);
@@ -906,9 +915,15 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 
         // this block becomes the pending one
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
-            if (active)
-                *reinterpret_cast<uint2 *>(sm_wait + ((size_t)t << logC) + 8u * tid) = make_uint2(SMc[t][0], SMc[t][1]);
+        for (int t = 0; t < 8; ++t) {
+            if constexpr (SM_IN_LDS) {
+                if (active)
+                    *reinterpret_cast<uint2 *>(sm_wait + ((size_t)t << logC) + 8u * tid) = make_uint2(SMc[t][0], SMc[t][1]);
+            } else {
+                SMp[t][0] = SMc[t][0];
+                SMp[t][1] = SMc[t][1];
+            }
+        }
         pend = kl; pend_item = ci; pend_cnt = cnt; pend_S = S; pend_err = own_err;
         slot ^= 1u;
         k = knext;
