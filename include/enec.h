@@ -27,10 +27,13 @@
  *   8   u64 n_elems            16  u32 block_size B     20 u32 n_blocks nb = ceil(n_elems / B)
  *   24  u8 b   25 u8 n   26 u8 m   27 u8 exponent bits (8; fp16: 5)
  *   28  u32 status (ENEC_OK or ENEC_E_RANGE)            32 u64 total_bytes (0 if status != OK)
- *   40..63 zero
+ *   40  u8 tuple mode: 0 = (b, n, m) above hold for every data block; 1 = one tuple per data block
+ *       (then bytes 24..26 are zero and the tuples follow the offset table, see enec_compress_per_block)
+ *   41..63 zero
  *   64  (nb + 1) x u64: offset of each data block's payload relative to the payload base,
  *       i.e. the exclusive prefix sums of payload sizes; entry nb is their total
  *   zero bytes up to align16(64 + 8 (nb + 1)) = payload base for bf16 and fp16
+ *   tuple mode 1 only: nb x 4 bytes (b, n, m, 0), then zero bytes up to a multiple of 16
  *   fp32 only: the lower 16 bits of every element, element order, then zero bytes up to a
  *       multiple of 16; the payload base follows.  (The upper 16 bits of an fp32 element are a
  *       bf16 word and are coded as such.)
