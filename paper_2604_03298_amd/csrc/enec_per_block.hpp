@@ -382,27 +382,29 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
     // compiler then keeps the constants of all sixteen packer instances in registers, about 250
     // VGPRs, and the kernel is slower.)
     PB_T_DECL;
+    uint32_t ticket = 0;
     if (tid == 0) {
-        s_k = atomicAdd(p.ticket, 1u);
+        ticket = atomicAdd(p.ticket, 1u);
         s_best = ~0ull;
         s_lo = 255u;
         s_hi = 0u;
         s_flags = 0u;
     }
+    // Phase 1 counts into PB_HIST_COPIES copies of the histogram (lane i uses copy i mod 16), so that
+    // lanes with equal exponents, the normal case, do not queue up on one LDS word; the copies are
+    // PB_HIST_STRIDE words apart, which spreads one bin of all copies over the banks.  They share
+    // the dynamic LDS with the payload image, which is written only after the search.  They are
+    // cleared while the ticket travels.
+    uint32_t *hcopy = reinterpret_cast<uint32_t *>(smem);
+    for (uint32_t i = tid; i < PB_HIST_COPIES * PB_HIST_STRIDE / 4u; i += blockDim.x)
+        reinterpret_cast<uint4 *>(hcopy)[i] = make_uint4(0, 0, 0, 0);
+    if (tid == 0) s_k = ticket;
     __syncthreads();
     const uint32_t k = s_k;
     if (k >= p.nb) return;                               // (the grid has exactly nb workgroups)
     PB_T(0);
     uint4 raw[RW];
     pb_load_rows<DT>(p, k, tid, active, logC, raw);
-    // Phase 1 counts into PB_HIST_COPIES copies of the histogram (lane i uses copy i mod 16), so that
-    // lanes with equal exponents, the normal case, do not queue up on one LDS word; the copies are
-    // PB_HIST_STRIDE words apart, which spreads one bin of all copies over the banks.  They share
-    // the dynamic LDS with the payload image, which is written only after the search.
-    uint32_t *hcopy = reinterpret_cast<uint32_t *>(smem);
-    for (uint32_t i = tid; i < PB_HIST_COPIES * PB_HIST_STRIDE / 4u; i += blockDim.x)
-        reinterpret_cast<uint4 *>(hcopy)[i] = make_uint4(0, 0, 0, 0);
-    __syncthreads();
     uint32_t *mine = hcopy + (lane & (PB_HIST_COPIES - 1u)) * PB_HIST_STRIDE;
     const uint64_t blk0 = (uint64_t)k << p.logB;
     const uint32_t real = p.n_elems - blk0 < B ? (uint32_t)(p.n_elems - blk0) : B;   // elements that are not pads
