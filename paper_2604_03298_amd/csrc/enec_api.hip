@@ -556,15 +556,35 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
     }
     PbCompressFn fn = pick_compress_per_block(dtype, L);
     if (!fn) return ENEC_E_DTYPE;
-    const unsigned threads = B / 64 < 64 ? 64 : B / 64;
-    // mask | low plane | high records (at most 8 plane bits together); before that the histogram copies
+    const unsigned part_threads = B / 64 < 64 ? 64 : B / 64;
+    // per part: mask | low plane | high records (at most 8 plane bits together); before that the histogram copies
     const size_t image = (size_t)B / (8 * L) + (size_t)B, hist = (size_t)PB_HIST_COPIES * PB_HIST_STRIDE * 4;
-    const size_t lds = image > hist ? image : hist;
-    const unsigned grid = (unsigned)nb;
-#ifdef ENEC_PB_TIMING
-    a.dbg = reinterpret_cast<unsigned long long *>(static_cast<uint8_t *>(workspace) + WS_HIST);
-#endif
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
+    const size_t part_lds = (image > hist ? image : hist) + 15 & ~(size_t)15;
+    // several blocks per workgroup (one ticket for all of them) when there are enough blocks; the few
+    // blocks left over get a launch with one block per workgroup
+    unsigned per_wg = 1024 / part_threads < (unsigned)PB_MAX_PARTS ? 1024 / part_threads : (unsigned)PB_MAX_PARTS;
+    if (const char *e = std::getenv("ENEC_PER_BLOCK_PARTS")) {        // tuning aid
+        const unsigned v = (unsigned)std::atoi(e);
+        if (v >= 1 && v <= per_wg) per_wg = v;
+    }
+    if (nb < 64 * (size_t)per_wg) per_wg = 1;
+    if (per_wg * part_lds > 65536 &&
+        hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(per_wg * part_lds)) != hipSuccess) {
+        (void)hipGetLastError();
+        per_wg = 1;
+    }
+    a.log_sub = ilog2(part_threads);
+    a.part_lds = (uint32_t)part_lds;
+    const size_t main_wgs = nb / per_wg, rest = nb - main_wgs * per_wg;
+    a.first_block = 0;
+    a.per_wg = per_wg;
+    hipLaunchKernelGGL(fn, dim3((unsigned)main_wgs), dim3(part_threads * per_wg), per_wg * part_lds, s, a);
+    if (rest) {
+        a.first_block = (uint32_t)(main_wgs * per_wg);
+        a.per_wg = 1;
+        a.ticket = reinterpret_cast<uint32_t *>(base) + 1;      // a counter of its own, cleared with the first
+        hipLaunchKernelGGL(fn, dim3((unsigned)rest), dim3(part_threads), part_lds, s, a);
+    }
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 

@@ -28,6 +28,8 @@ ENEC_TABLES(dt2)
 // LDS copies of the block histogram in the compress kernel, and their distance in words
 constexpr uint32_t PB_HIST_COPIES = 16, PB_HIST_STRIDE = 257;   // words; 16 * 257 * 4 bytes of LDS
 
+constexpr int PB_MAX_PARTS = 4;                 // data blocks a workgroup of the compress kernel works on at once
+
 struct PbCompressArgs {
     const void *in;
     uint8_t *out;
@@ -39,6 +41,9 @@ struct PbCompressArgs {
     uint64_t tail_base;         // fp32: where the lower halves go
     uint64_t payload_base;
     uint32_t nb, B, logB, spin_limit;
+    uint32_t first_block;       // this launch codes blocks first_block .. first_block + gridDim * per_wg - 1
+    uint32_t per_wg;            // data blocks per workgroup (parts), log_sub = log2 of the threads of a part
+    uint32_t log_sub, part_lds; // part_lds = bytes of dynamic LDS per part
 #ifdef ENEC_PB_TIMING
     unsigned long long *dbg;    // eight counters of 10 ns ticks per phase (development aid)
 #endif

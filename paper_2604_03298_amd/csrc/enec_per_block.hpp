@@ -356,35 +356,47 @@ __device__ __forceinline__ void pb_load_rows(const PbCompressArgs &p, uint32_t k
 }
 
 template <int DT, int LPG>
-__global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompressArgs p)
+__global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompressArgs p)
 {
     constexpr uint32_t E = exponent_bits(DT);
     constexpr int RW = DT == DT_FP32 ? 16 : 8;
     constexpr int LOG_LPG = LPG == 4 ? 2 : LPG - 1;
 
-    extern __shared__ __align__(16) uint8_t smem[];      // mask | low plane (normalized bytes) | high records
-    __shared__ uint32_t s_hist[256];
-    __shared__ unsigned long long s_best;                // Eq. 3 cost << 16 | n << 8 | b of the best candidate
-    __shared__ double s_bexp[9];
-    __shared__ uint32_t s_k, s_lo, s_hi, s_m, s_flags;
-    __shared__ unsigned long long s_off;
+    // A workgroup works on p.per_wg consecutive data blocks at once, one per group of 2^p.log_sub threads
+    // ("part"): the parts run the same code side by side, share the barriers and nothing else.  One ticket
+    // then stands for per_wg blocks (one returning atomic on one address sustains about 28 draws per
+    // microsecond on this machine: with a ticket per block that rate bounded the kernel).  From here on
+    // tid, wave, the shared variables and the dynamic LDS are those of the thread's own part.
+    extern __shared__ __align__(16) uint8_t smem_all[];  // per part: mask | low plane (normalized bytes) | high records
+    __shared__ uint32_t s_hist_all[PB_MAX_PARTS][256];
+    __shared__ unsigned long long s_best_all[PB_MAX_PARTS];   // Eq. 3 cost << 16 | n << 8 | b of the best candidate
+    __shared__ double s_bexp_all[PB_MAX_PARTS][9];
+    __shared__ uint32_t s_ticket, s_lo_all[PB_MAX_PARTS], s_hi_all[PB_MAX_PARTS], s_m_all[PB_MAX_PARTS], s_flags_all[PB_MAX_PARTS];
+    __shared__ unsigned long long s_off_all[PB_MAX_PARTS];
 
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t part = threadIdx.x >> p.log_sub, part_threads = 1u << p.log_sub;
+    const uint32_t tid = threadIdx.x & (part_threads - 1u), lane = tid & 63u, wave = tid >> 6;
+    uint8_t *smem = smem_all + part * p.part_lds;
+    uint32_t *s_hist = s_hist_all[part];
+    unsigned long long &s_best = s_best_all[part];
+    double *s_bexp = s_bexp_all[part];
+    uint32_t &s_lo = s_lo_all[part], &s_hi = s_hi_all[part], &s_m = s_m_all[part], &s_flags = s_flags_all[part];
+    unsigned long long &s_off = s_off_all[part];
     const uint32_t B = p.B, logC = p.logB - 3u;
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
     const uint32_t mask_bytes = (B >> 6) >> LOG_LPG;                  // B / (8 L)
 
-    // One workgroup per data block.  Blocks are taken in the order in which workgroups start (a ticket),
-    // not by blockIdx: a workgroup then only ever waits for blocks whose workgroups are already
-    // running, and those publish their size before they wait for anything, so the look-back cannot
-    // deadlock, whatever part of the grid is resident.  (A persistent loop over blocks was tried: the
-    // compiler then keeps the constants of all sixteen packer instances in registers, about 250
-    // VGPRs, and the kernel is slower.)
+    // Blocks are taken in the order in which workgroups start (a ticket), not by blockIdx: a part then
+    // only ever waits for blocks whose workgroups are already running (or for the lower parts of its
+    // own workgroup, which run beside it), and those publish their size before they wait for anything,
+    // so the look-back cannot deadlock, whatever part of the grid is resident.  (A persistent loop over
+    // blocks was tried: the compiler then keeps the constants of all sixteen packer instances in
+    // registers, about 250 VGPRs, and the kernel is slower.)
     PB_T_DECL;
     uint32_t ticket = 0;
+    if (threadIdx.x == 0) ticket = atomicAdd(p.ticket, 1u);
     if (tid == 0) {
-        ticket = atomicAdd(p.ticket, 1u);
         s_best = ~0ull;
         s_lo = 255u;
         s_hi = 0u;
@@ -396,12 +408,12 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
     // the dynamic LDS with the payload image, which is written only after the search.  They are
     // cleared while the ticket travels.
     uint32_t *hcopy = reinterpret_cast<uint32_t *>(smem);
-    for (uint32_t i = tid; i < PB_HIST_COPIES * PB_HIST_STRIDE / 4u; i += blockDim.x)
+    for (uint32_t i = tid; i < PB_HIST_COPIES * PB_HIST_STRIDE / 4u; i += part_threads)
         reinterpret_cast<uint4 *>(hcopy)[i] = make_uint4(0, 0, 0, 0);
-    if (tid == 0) s_k = ticket;
+    if (threadIdx.x == 0) s_ticket = ticket;
     __syncthreads();
-    const uint32_t k = s_k;
-    if (k >= p.nb) return;                               // (the grid has exactly nb workgroups)
+    if (p.first_block + (s_ticket + 1u) * p.per_wg > p.nb) return;     // (never: the grid is sized to fit)
+    const uint32_t k = p.first_block + s_ticket * p.per_wg + part;
     PB_T(0);
     uint4 raw[RW];
     pb_load_rows<DT>(p, k, tid, active, logC, raw);
@@ -454,7 +466,7 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
     PB_T(1);
 
     // ---- phase 2: lowest and highest exponent, then every b in between with Eq. 1's n and Eq. 3's cost ----
-    for (uint32_t x = tid; x < 256u; x += blockDim.x) {
+    for (uint32_t x = tid; x < 256u; x += part_threads) {
         uint32_t c = 0;
 #pragma unroll 8
         for (uint32_t i = 0; i < PB_HIST_COPIES; ++i) c += hcopy[i * PB_HIST_STRIDE + x];
@@ -466,7 +478,7 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
     }
     __syncthreads();
     const uint32_t xl = s_lo, xh = s_hi;
-    for (uint32_t b = xl + tid; b <= xh; b += blockDim.x) {
+    for (uint32_t b = xl + tid; b <= xh; b += part_threads) {
         const uint32_t n = pb_width_for(b, xl, xh, E);
         const uint32_t nmask = (1u << n) - 1u;
         uint32_t D = 0;                                   // at most 2^15 elements * 255
@@ -676,12 +688,12 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
             *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SM[t][0], SM[t][1]);
         }
     }
-    for (uint32_t v = tid; v < (mask_bytes >> 4); v += blockDim.x)
+    for (uint32_t v = tid; v < (mask_bytes >> 4); v += part_threads)
         *reinterpret_cast<uint4 *>(dst + B + 16u * v) = *reinterpret_cast<const uint4 *>(img + 16u * v);
     if (lm > 0) {
         uint8_t *dlow = dst + B + mask_bytes;
         const uint32_t T2 = (lm * B) >> 4;               // half of the plane's length
-        for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
+        for (uint32_t v = tid; v < (T2 >> 3); v += part_threads) {
             const uint2 lo = *reinterpret_cast<const uint2 *>(img_low + 8u * v);
             const uint2 hi = *reinterpret_cast<const uint2 *>(img_low + 8u * v + T2);
             uint4 o;   // stream byte 2i = normalized byte i, stream byte 2i+1 = normalized byte i + T/2
@@ -695,7 +707,7 @@ __global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompres
     if (a > 0) {
         uint8_t *dhigh = dst + fixed;
         const uint32_t hbytes = (uint32_t)LPG * a * cnt;
-        for (uint32_t v = tid; 16u * v < hbytes; v += blockDim.x) {
+        for (uint32_t v = tid; 16u * v < hbytes; v += part_threads) {
             const uint4 o = *reinterpret_cast<const uint4 *>(img_high + 16u * v);
             uint32_t w[4] = {o.x, o.y, o.z, o.w};
 #pragma unroll
