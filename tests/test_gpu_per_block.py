@@ -241,3 +241,48 @@ def test_group_lengths_8_and_32(gpu, oracle, L):
     out = torch.zeros(enec.compress_bound_per_block(4096), dtype=torch.uint8, device="cuda")
     assert enec.compress_per_block(src, out, gpu.ws, block_size=2048, group_length=32) == enec.E_PARAMS
     assert enec.compress_per_block(src, out, gpu.ws, block_size=2048, group_length=12) == enec.E_PARAMS
+
+
+def test_tensor_beyond_4_gib_sampled_against_the_oracle(gpu, oracle):
+    """2.6e9 elements (5.2 GB of bf16), 158 000 data blocks with one tuple each: element and byte offsets beyond
+    32 bits, a look-back over many windows.  The round trip is compared on the device; blocks sampled along the
+    tensor are recompressed by the oracle, tuples and payloads must be what the library wrote."""
+    torch, enec = gpu.torch, gpu.enec
+    from paper_2604_03298_amd.report import gpu_gaussian
+    rows, cols = 90000, 28672 + 231          # not a multiple of the block size: ragged tail
+    src = gpu_gaussian(torch, rows, cols, 0.02, 4343)
+    n = src.numel()
+    assert 2 * n > (1 << 32)
+    B = 16384
+    nb = (n + B - 1) // B
+    src[5 * B:6 * B] = 0                      # a block of zeros and a block of noise among the weights
+    src[(nb // 2) * B:(nb // 2 + 1) * B] = torch.randint(-32768, 32767, (B,), dtype=torch.int16, device="cuda",
+                                                         generator=torch.Generator(device="cuda").manual_seed(1))
+    ws = enec.new_workspace(n)
+    out = torch.empty(enec.compress_bound_per_block(n), dtype=torch.uint8, device="cuda")
+    size = torch.zeros(1, dtype=torch.int64, device="cuda")
+    assert enec.compress_per_block(src, out, ws, out_bytes=size) == 0
+    torch.cuda.synchronize()
+    total = int(size.item())
+    assert 0 < total < 2 * n
+    back = torch.empty_like(src)
+    assert enec.decompress_with_header(out, out[:64].cpu().numpy().tobytes(), back) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(back, src)
+    del back
+    base = oracle.payload_base_pb(n, B)
+    at = oracle.table_end(n, B)
+    table = out[64:64 + 8 * (nb + 1)].cpu().numpy().view("<u8")
+    tuples = out[at:at + 4 * nb].cpu().numpy().reshape(nb, 4)
+    assert table[0] == 0 and int(table[nb]) + base == total and (np.diff(table.astype(np.int64)) > 0).all()
+    assert (tuples[:, 3] == 0).all()
+    for k in (0, 5, 1234, nb // 2, (1 << 32) // (2 * B) + 5, nb - 2, nb - 1):      # incl. byte 2^32 and the ragged tail
+        w = src[k * B:min(n, (k + 1) * B)].cpu().numpy().view(np.uint16)
+        b, n_, m, _ = oracle.tune(w)
+        assert tuple(int(v) for v in tuples[k, :3]) == (b, n_, m), k
+        rc, s = oracle.compress(w, (b, n_, m, 16), B)
+        assert rc == 0
+        ob = oracle.payload_base(w.size, B)
+        got = out[base + int(table[k]):base + int(table[k + 1])].cpu().numpy()
+        assert got.size == s.size - ob and np.array_equal(got, s[ob:]), k
+    assert tuple(int(v) for v in tuples[5, :3]) == (0, 1, 0)
