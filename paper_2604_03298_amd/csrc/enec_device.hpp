@@ -1305,16 +1305,21 @@ template <int DT>
 __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_t n_elems, unsigned long long *hist,
                                                         uint32_t every)
 {
-    __shared__ uint32_t s_h[4][256];
+    // sixteen copies of the histogram, lane i of every wave counts into copy i mod 16: lanes with equal
+    // exponents, the normal case, would otherwise queue up on one LDS word; the copies are 257 words
+    // apart, which puts the same bin of all copies into different banks.  (More copies do not help:
+    // the LDS atomic unit itself, at one to two lanes per clock and CU, is what bounds this kernel.)
+    constexpr uint32_t COPIES = 16, STRIDE = 257;
+    __shared__ uint32_t s_h[COPIES * STRIDE];
     const uint32_t tid = threadIdx.x;
-    for (uint32_t i = tid; i < 1024; i += 256) (&s_h[0][0])[i] = 0;
+    for (uint32_t i = tid; i < COPIES * STRIDE; i += 256) s_h[i] = 0;
     __syncthreads();
-    uint32_t *mine = s_h[tid >> 6];
+    uint32_t *mine = s_h + (tid & (COPIES - 1u)) * STRIDE;
     constexpr uint32_t PER_VEC = DT == DT_FP32 ? 4u : 8u;        // elements in 16 bytes
     const uint64_t nvec = n_elems / PER_VEC;
     const uint64_t stride = (uint64_t)gridDim.x * 256u;
-    // a wave's LDS counters cannot overflow: each thread adds at most 8 per iteration and the
-    // launch keeps iterations * 64 * 8 below 2^32
+    // the LDS counters cannot overflow: each thread adds at most 8 per iteration and the
+    // launch keeps iterations * 256 * 8 below 2^32
     // the sample: chunks of SAMPLE_CHUNK elements whose number is a multiple of `every`
     constexpr uint32_t LOG_VPC = DT == DT_FP32 ? 10u : 9u;      // 16-byte vectors in a chunk
     const uint64_t chunks = (nvec + (1u << LOG_VPC) - 1u) >> LOG_VPC;
@@ -1346,7 +1351,9 @@ __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_
         atomicAdd(&mine[x], 1u);
     }
     __syncthreads();
-    const uint32_t c = s_h[0][tid] + s_h[1][tid] + s_h[2][tid] + s_h[3][tid];
+    uint32_t c = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < COPIES; ++i) c += s_h[i * STRIDE + tid];
     if (c) atomicAdd(&hist[tid], (unsigned long long)c);
 }
 
