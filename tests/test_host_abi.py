@@ -142,3 +142,12 @@ def test_product_does_not_import_the_oracle():
                 src = open(os.path.join(dirpath, f)).read()
                 for needle in ("import oracle", "from oracle", "enec_oracle", "enec_ref", "orc_"):
                     assert needle not in src, (f, needle)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: `bench.py --gpus N` with N > 1 exits with a message, before anything touches a GPU."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr or "one GPU" in res.stderr.lower()
