@@ -182,7 +182,8 @@ def stream_info(header) -> dict:
     rc = lib().enec_stream_info(buf.ctypes.data, C.byref(p), C.byref(n), C.byref(B), C.byref(total),
                                 C.byref(dtype), C.byref(status))
     return dict(rc=rc, params=p.astuple(), n_elems=int(n.value), block_size=int(B.value),
-                total_bytes=int(total.value), dtype=int(dtype.value), status=int(status.value))
+                total_bytes=int(total.value), dtype=int(dtype.value), status=int(status.value),
+                per_block=bool(rc == OK and buf[40] == 1))      # header byte 40: one tuple per data block
 
 
 # ---- device entry points (torch tensors carry the pointers) ------------------------

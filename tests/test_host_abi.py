@@ -151,3 +151,21 @@ def test_bench_refuses_more_than_one_gpu():
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert res.returncode != 0
     assert "ONE GPU" in res.stderr or "one GPU" in res.stderr.lower()
+
+
+def test_stream_info_reads_oracle_headers(oracle):
+    """The library's header parser against headers the oracle wrote: one tuple per tensor, one per data block, a bad byte 40."""
+    import numpy as np
+    from paper_2604_03298_amd import enec, workloads as W
+    w = W.gaussian(5000, 0.02, 3)
+    prm = oracle.tune(w)
+    one = oracle.compress(w, prm, 2048)[1]
+    info = enec.stream_info(one[:64])
+    assert info["rc"] == 0 and info["params"] == prm and not info["per_block"]
+    assert info["n_elems"] == 5000 and info["block_size"] == 2048 and info["total_bytes"] == one.size and info["status"] == 0
+    per = oracle.compress_per_block(w, 2048, 0, 8)[1]
+    info = enec.stream_info(per[:64])
+    assert info["rc"] == 0 and info["per_block"] and info["params"] == (0, 0, 0, 8) and info["total_bytes"] == per.size
+    bad = per[:64].copy()
+    bad[40] = 2
+    assert enec.stream_info(bad)["rc"] == enec.E_FORMAT
