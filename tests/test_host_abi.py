@@ -93,7 +93,7 @@ def test_stream_info_parses_oracle_headers(enec, oracle):
     rc, s = oracle.compress(w, p, 16384)
     info = enec.stream_info(s[:64])
     assert info == dict(rc=0, params=p, n_elems=w.size, block_size=16384, total_bytes=s.size,
-                        dtype=0, status=0)
+                        dtype=0, status=0, per_block=False)
     bad = s[:64].copy(); bad[1] = 0
     assert enec.stream_info(bad)["rc"] == enec.E_FORMAT
     bad = s[:64].copy(); bad[4] = 2
