@@ -286,3 +286,22 @@ def test_tensor_beyond_4_gib_sampled_against_the_oracle(gpu, oracle):
         got = out[base + int(table[k]):base + int(table[k + 1])].cpu().numpy()
         assert got.size == s.size - ob and np.array_equal(got, s[ob:]), k
     assert tuple(int(v) for v in tuples[5, :3]) == (0, 1, 0)
+
+
+@pytest.mark.parametrize("L", [8, 16, 32])
+def test_four_blocks_per_workgroup_all_formats(gpu, oracle, L):
+    """Enough data blocks (>= 256) for the launch in which a workgroup works on four blocks side by side, plus a few left
+    over for the second launch; every element format and group length."""
+    B = 16384
+    w = _mixed16(261, B, 900 + L)
+    _check(gpu, oracle, w[:w.size - 77], BF16, B, f"bf16 L={L}", L)
+    h = _mixed16(258, B, 950 + L, FP16)
+    _check(gpu, oracle, h, FP16, B, f"fp16 L={L}", L)
+    f = np.concatenate([W.gaussian_fp32(200 * B, 0.02, 1), np.zeros(B, np.uint32), W.gaussian_fp32(58 * B + 5, 3.0, 2)])
+    _check(gpu, oracle, f, FP32, B, f"fp32 L={L}", L)
+
+
+def test_two_blocks_per_workgroup_at_the_largest_block_size(gpu, oracle):
+    w = _mixed16(131, 32768, 77)
+    _check(gpu, oracle, w, BF16, 32768, "B=32768, 131 blocks")
+    _check(gpu, oracle, w, BF16, 32768, "B=32768, 131 blocks, L=32", 32)
