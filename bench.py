@@ -76,6 +76,11 @@ def main():
         got = [fn(s) for s in srcs]
         tune_info[key] = {"ms_for_the_layer": round((time.perf_counter() - tt) * 1e3, 3),
                           "same_tuples_as_all_exponents": got == params}
+    torch.cuda.synchronize()
+    tt = time.perf_counter()
+    got = enec.tune_batch(srcs, ws)                                  # one wait for the stream instead of nine
+    tune_info["all_exponents_batched"] = {"ms_for_the_layer": round((time.perf_counter() - tt) * 1e3, 3),
+                                          "same_tuples_as_all_exponents": got == params}
     outs = [torch.zeros(enec.compress_bound(n), dtype=torch.uint8, device="cuda") for n in n_el]
     backs = [torch.zeros_like(s) for s in srcs]
     sizes = torch.zeros(len(srcs), dtype=torch.int64, device="cuda")

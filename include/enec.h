@@ -189,6 +189,21 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
 int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params,
               uint64_t *histogram, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Many tensors at once: the histograms of up to sixteen tensors are counted into sixteen slots of the
+ * workspace, copied back together, and the stream is waited for once per sixteen tensors (tuning a
+ * layer's tensors one by one spends most of its time in those waits).
+ *   items       HOST array; in = DEVICE, 16-byte aligned
+ *   every       1 = all exponents, k = every k-th chunk of 4096 elements (see enec_tune_sampled)
+ *   params      HOST array of n_items tuples, written before return
+ *   histograms  NULL, or HOST array of n_items * 256 u64
+ * enec_compress and enec_compress_batch tune the tensors they are given without a tuple this way. */
+typedef struct {
+    const void *in;
+    size_t n_elems;
+} enec_tune_item;
+int enec_tune_batch(const enec_tune_item *items, size_t n_items, int dtype, uint32_t every, enec_params *params,
+                    uint64_t *histograms, void *workspace, size_t workspace_bytes, void *stream);
+
 /* The tuner on a sample [Sec. V-E phase 1 counts exponents; a sample keeps the counting cheap]: only
  * the elements whose index e has (e / 4096) % every == 0 are counted, i.e. every `every`-th chunk
  * of 4096 elements, the first one included; every = 1 is enec_tune.  An exponent that the sample

@@ -48,9 +48,9 @@ namespace {
 
 using namespace enec;
 
-// workspace: [0, 1024) control records of the block classes | [1024, 3072) histogram |
+// workspace: [0, 1024) control records of the block classes | [1024, 33792) sixteen histograms |
 // group words | block words (the last two sized by the call's block count)
-constexpr size_t WS_CTL = 0, WS_HIST = 1024, WS_STATE = WS_HIST + 256 * 8;
+constexpr size_t WS_CTL = 0, WS_HIST = 1024, WS_HIST_SLOTS = MAX_BATCH, WS_STATE = WS_HIST + WS_HIST_SLOTS * 256 * 8;
 inline size_t ws_groups(size_t nb) { return (nb + GROUP - 1) / GROUP; }
 // The state words behind WS_STATE: first the group accumulators, which every call leaves zero, in
 // a region whose length depends only on the size of the workspace (1/9 of the words), then the
@@ -319,32 +319,55 @@ int enec_tune_histogram_groups(const uint64_t *hist, int dtype, uint32_t group_l
     return ENEC_OK;
 }
 
-int enec_tune_sampled(const void *in, size_t n_elems, int dtype, uint32_t every, enec_params *params,
-                      uint64_t *histogram, void *workspace, size_t workspace_bytes, void *stream)
+int enec_tune_batch(const enec_tune_item *items, size_t n_items, int dtype, uint32_t every, enec_params *params,
+                    uint64_t *histograms, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
     if (workspace_bytes < WS_STATE) return ENEC_E_CAPACITY;
-    if (!params || !workspace || (!in && n_elems) || !aligned16(in) || !aligned16(workspace) ||
-        n_elems > MAX_ELEMS || every == 0)
-        return ENEC_E_ARG;
+    if ((!items && n_items) || (!params && n_items) || !workspace || !aligned16(workspace) || every == 0) return ENEC_E_ARG;
+    for (size_t i = 0; i < n_items; ++i)
+        if ((!items[i].in && items[i].n_elems) || !aligned16(items[i].in) || items[i].n_elems > MAX_ELEMS) return ENEC_E_ARG;
     hipStream_t s = (hipStream_t)stream;
-    uint64_t host_hist[256];
-    std::memset(host_hist, 0, sizeof host_hist);
-    if (n_elems) {
-        auto *dhist = reinterpret_cast<unsigned long long *>(static_cast<uint8_t *>(workspace) + WS_HIST);
-        fill_zero_kernel<<<1, 256, 0, s>>>(reinterpret_cast<uint4 *>(dhist), 256 * 8 / 16);
-        const uint64_t nvec = n_elems * elem_bytes(dtype) / 16;
-        uint64_t want = (nvec / every + 255) / 256;
-        const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
-        if (dtype == ENEC_FP32) histogram_kernel<DT_FP32><<<grid, 256, 0, s>>>(in, n_elems, dhist, every);
-        else if (dtype == ENEC_FP16) histogram_kernel<DT_FP16><<<grid, 256, 0, s>>>(in, n_elems, dhist, every);
-        else histogram_kernel<DT_BF16><<<grid, 256, 0, s>>>(in, n_elems, dhist, every);
-        if (hipMemcpyAsync(host_hist, dhist, sizeof host_hist, hipMemcpyDeviceToHost, s) != hipSuccess ||
-            hipStreamSynchronize(s) != hipSuccess)
+    auto *dhist = reinterpret_cast<unsigned long long *>(static_cast<uint8_t *>(workspace) + WS_HIST);
+    std::vector<uint64_t> host(WS_HIST_SLOTS * 256);
+    // sixteen tensors at a time: their histograms are counted into sixteen slots, copied back together,
+    // and the stream is waited for once
+    for (size_t first = 0; first < n_items; first += WS_HIST_SLOTS) {
+        const size_t count = n_items - first < WS_HIST_SLOTS ? n_items - first : WS_HIST_SLOTS;
+        fill_zero_kernel<<<(unsigned)count, 256, 0, s>>>(reinterpret_cast<uint4 *>(dhist), count * 256 * 8 / 16);
+        for (size_t j = 0; j < count; ++j) {
+            const enec_tune_item &it = items[first + j];
+            if (it.n_elems == 0) continue;
+            const uint64_t nvec = it.n_elems * elem_bytes(dtype) / 16;
+            uint64_t want = (nvec / every + 255) / 256;
+            const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+            unsigned long long *slot = dhist + 256 * j;
+            if (dtype == ENEC_FP32) histogram_kernel<DT_FP32><<<grid, 256, 0, s>>>(it.in, it.n_elems, slot, every);
+            else if (dtype == ENEC_FP16) histogram_kernel<DT_FP16><<<grid, 256, 0, s>>>(it.in, it.n_elems, slot, every);
+            else histogram_kernel<DT_BF16><<<grid, 256, 0, s>>>(it.in, it.n_elems, slot, every);
+        }
+        if (hipMemcpyAsync(host.data(), dhist, count * 256 * 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess) {
+            (void)hipGetLastError();
             return ENEC_E_HIP;
+        }
+        for (size_t j = 0; j < count; ++j) {
+            int rc = enec_tune_histogram(host.data() + 256 * j, dtype, &params[first + j]);
+            if (rc != ENEC_OK) return rc;
+            if (histograms) std::memcpy(histograms + 256 * (first + j), host.data() + 256 * j, 256 * 8);
+        }
     }
-    if (histogram) std::memcpy(histogram, host_hist, sizeof host_hist);
-    return enec_tune_histogram(host_hist, dtype, params);
+    return ENEC_OK;
+}
+
+int enec_tune_sampled(const void *in, size_t n_elems, int dtype, uint32_t every, enec_params *params,
+                      uint64_t *histogram, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!params) return ENEC_E_ARG;
+    enec_tune_item it;
+    it.in = in;
+    it.n_elems = n_elems;
+    return enec_tune_batch(&it, 1, dtype, every, params, histogram, workspace, workspace_bytes, stream);
 }
 
 int enec_tune(const void *in, size_t n_elems, int dtype, enec_params *params, uint64_t *histogram,
@@ -405,14 +428,27 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
     }
     const size_t acc_words = ws_acc_words(workspace_bytes);
     if (groups > acc_words || acc_words + state_words > ws_state_words(workspace_bytes)) return ENEC_E_CAPACITY;
+    {   // tensors without a tuple are tuned first, together (one wait for the stream per sixteen of them)
+        std::vector<enec_tune_item> todo;
+        std::vector<size_t> who;
+        for (size_t i = 0; i < n_items; ++i)
+            if (!items[i].params) {
+                enec_tune_item t;
+                t.in = items[i].in;
+                t.n_elems = items[i].n_elems;
+                todo.push_back(t);
+                who.push_back(i);
+            }
+        if (!todo.empty()) {
+            std::vector<enec_params> found(todo.size());
+            int rc = enec_tune_batch(todo.data(), todo.size(), dtype, 1, found.data(), nullptr, workspace, workspace_bytes, stream);
+            if (rc != ENEC_OK) return rc;
+            for (size_t j = 0; j < who.size(); ++j) prep[who[j]].prm = found[j];
+        }
+    }
     for (size_t i = 0; i < n_items; ++i) {
         const enec_compress_item &it = items[i];
-        if (it.params) {
-            prep[i].prm = *it.params;
-        } else {
-            int rc = enec_tune(it.in, it.n_elems, dtype, &prep[i].prm, nullptr, workspace, workspace_bytes, stream);
-            if (rc != ENEC_OK) return rc;
-        }
+        if (it.params) prep[i].prm = *it.params;
         const enec_params &prm = prep[i].prm;
         if (prm.n < 1 || prm.n > exp_bits(dtype) || prm.m > prm.n || prm.b >= (1u << exp_bits(dtype)) ||
             !group_ok(prm.L) || !group_fits_block(prm.L, prep[i].B))

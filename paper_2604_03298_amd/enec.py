@@ -24,7 +24,12 @@ EXPORTS = [
     "enec_decompress_with_header", "enec_tune", "enec_tune_histogram", "enec_stream_info",
     "enec_copy", "enec_compress_batch", "enec_decompress_batch", "enec_tune_histogram_groups",
     "enec_tune_sampled", "enec_compress_sampled", "enec_compress_bound_per_block", "enec_compress_per_block",
+    "enec_tune_batch",
 ]
+
+
+class TuneItem(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("n_elems", C.c_size_t)]
 
 
 class Params(C.Structure):
@@ -88,6 +93,8 @@ def lib():
         L.enec_compress_bound_per_block.argtypes = [sz, C.c_int, C.c_uint32]
         L.enec_compress_per_block.restype = C.c_int
         L.enec_compress_per_block.argtypes = [vp, sz, C.c_int, C.c_uint32, C.c_uint32, vp, sz, vp, vp, sz, vp]
+        L.enec_tune_batch.restype = C.c_int
+        L.enec_tune_batch.argtypes = [C.POINTER(TuneItem), sz, C.c_int, C.c_uint32, C.POINTER(Params), u64p, vp, sz, vp]
         L.enec_tune_sampled.restype = C.c_int
         L.enec_tune_sampled.argtypes = [vp, sz, C.c_int, C.c_uint32, C.POINTER(Params), u64p, vp, sz, vp]
         L.enec_compress_sampled.restype = C.c_int
@@ -312,6 +319,23 @@ def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int |
         lengths = [v for v in lengths if 128 * v <= B <= 2048 * v] or [16]
     prm = p.astuple() if lengths is None else tune_histogram(hist, dt, lengths)
     return (prm, hist) if want_histogram else prm
+
+
+def tune_batch(srcs, workspace, every: int = 1, stream=None, dtype: int | None = None, want_histograms: bool = False):
+    """[(b, n, m, 16), ...] for a list of device tensors of one element format; one wait per sixteen tensors."""
+    n = len(srcs)
+    items = (TuneItem * n)()
+    for i, s in enumerate(srcs):
+        items[i].src = s.data_ptr()
+        items[i].n_elems = s.numel()
+    out = (Params * n)()
+    hist = np.zeros((n, 256), dtype=np.uint64)
+    dt = dtype_of(srcs[0], dtype) if n else BF16
+    _check(lib().enec_tune_batch(items, n, dt, every, out, hist.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                 C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                 _stream_handle(stream)), "enec_tune_batch")
+    prm = [out[i].astuple() for i in range(n)]
+    return (prm, hist) if want_histograms else prm
 
 
 def tune_sampled(src, every: int, workspace, stream=None, dtype: int | None = None, want_histogram: bool = False):

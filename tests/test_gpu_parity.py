@@ -11,6 +11,9 @@ from paper_2604_03298_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 
+STATE_AT = 1024 + 16 * 2048     # workspace: control records, sixteen histogram slots, then the scan state
+
+
 
 @pytest.fixture(scope="module")
 def gpu():
@@ -179,7 +182,7 @@ def test_workspace_is_reusable_and_results_are_deterministic(gpu, oracle):
     assert (ctl[:, 0] == ctl[:, 1]).all()
     assert len(set(ctl[:, 2].tolist())) == 1
     # every group accumulator (the first ninth of the state words) is back to zero
-    words = ws_host[3072:3072 + (ws_host.size - 3072) // 8 * 8].view(np.uint64)
+    words = ws_host[STATE_AT:STATE_AT + (ws_host.size - STATE_AT) // 8 * 8].view(np.uint64)
     assert (words[:words.size // 9] == 0).all()
 
 
@@ -192,7 +195,7 @@ def test_dirty_workspace_ends_in_a_status_not_in_a_hang(gpu, oracle, monkeypatch
     p = oracle.tune(w)
     src = gpu.to_dev(w)
     ws = enec.new_workspace(w.size)
-    words = ws[3072:3072 + (ws.numel() - 3072) // 8 * 8].view(torch.int64)
+    words = ws[STATE_AT:STATE_AT + (ws.numel() - STATE_AT) // 8 * 8].view(torch.int64)
     words[:words.numel() // 9] = 100 << 48            # accumulators claim 100 blocks too many: no group ever completes
     out = torch.zeros(enec.compress_bound(w.size), dtype=torch.uint8, device="cuda")
     size = torch.full((1,), -1, dtype=torch.int64, device="cuda")

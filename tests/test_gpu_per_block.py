@@ -172,7 +172,7 @@ def test_host_checks(gpu):
     assert enec.compress_per_block(src, out[:100], gpu.ws) == enec.E_CAPACITY
     assert enec.compress_per_block(src, out, gpu.ws, block_size=3000) == enec.E_BLOCK
     assert enec.compress_per_block(src, out, gpu.ws, dtype=7) == enec.E_DTYPE
-    assert enec.compress_per_block(src, out, gpu.ws[:3072]) == enec.E_CAPACITY
+    assert enec.compress_per_block(src, out, gpu.ws[:1024 + 16 * 2048]) == enec.E_CAPACITY
     assert enec.compress_bound_per_block(4096, BF16, 2048) == enec.compress_bound(4096, BF16, 2048) + 16
 
 

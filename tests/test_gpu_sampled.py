@@ -62,3 +62,29 @@ def test_every_zero_is_an_argument_error(gpu):
     rc = gpu.enec.lib().enec_tune_sampled(C.c_void_p(src.data_ptr()), 4096, 0, 0, C.byref(p), None,
                                           C.c_void_p(gpu.ws.data_ptr()), gpu.ws.numel(), None)
     assert rc == gpu.enec.E_ARG
+
+
+def test_batched_tuner_matches_the_oracle(gpu, oracle):
+    """Twenty tensors (two rounds of sixteen slots), one empty: histograms and tuples against the oracle's, for all
+    exponents and for a sample; enec_compress_batch tunes the tensors it gets without a tuple the same way."""
+    torch, enec = gpu.torch, gpu.enec
+    ws = [W.gaussian(4096 * (3 + 2 * i) + 17 * i, 0.005 * (1 + i % 5), 100 + i) for i in range(19)]
+    ws.insert(7, np.zeros(0, np.uint16))
+    srcs = [gpu.to_dev(w, BF16)[:w.size] for w in ws]
+    for every in (1, 3):
+        prm, hist = enec.tune_batch(srcs, gpu.ws, every=every, want_histograms=True)
+        for i, w in enumerate(ws):
+            picked = oracle.sample(w, every)
+            assert np.array_equal(hist[i], oracle.histogram(picked)), (every, i)
+            assert prm[i] == oracle.tune(picked), (every, i)
+    f = [W.gaussian_fp32(5000 + 4096 * i, 0.02, i) for i in range(3)]
+    prm = enec.tune_batch([gpu.to_dev(w, FP32) for w in f], gpu.ws, dtype=FP32)
+    assert prm == [oracle.tune(w, FP32) for w in f]
+    some = [w for w in ws if w.size][:5]
+    dev = [gpu.to_dev(w, BF16) for w in some]
+    outs = [torch.zeros(enec.compress_bound(w.size), dtype=torch.uint8, device="cuda") for w in some]
+    assert enec.compress_batch(dev, [None] * len(some), outs, gpu.ws) == 0
+    torch.cuda.synchronize()
+    for w, o in zip(some, outs):
+        want = oracle.compress(w, oracle.tune(w), oracle.default_block(w.size))[1]
+        assert np.array_equal(o.cpu().numpy()[:want.size], want)
