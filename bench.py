@@ -220,12 +220,12 @@ def main():
     extra = None
     if args.workload == "config2" and not args.no_extra:
         try:
-            from paper_2604_03298_amd import report
+            import report
             shapes = [(r, c) for _, r, c, _ in workloads.config2_spec() if r > 1]
             extra = {}
             for key, tdt, code, lengths in (("fp16", torch.float16, enec.FP16, None), ("fp32", torch.float32, enec.FP32, None),
                                             ("bf16_joint_m_L", torch.bfloat16, enec.BF16, (8, 16, 32))):
-                t = [report.gpu_gaussian(torch, r, c, 0.02, 6000 + i, tdt) for i, (r, c) in enumerate(shapes)]
+                t = [workloads.gpu_gaussian(torch, r, c, 0.02, 6000 + i, tdt) for i, (r, c) in enumerate(shapes)]
                 res = report.run_group(torch, enec, key, t, reps=5, dtype=code, lengths=lengths)[0]
                 extra[key] = {k: res[k] for k in ("params", "compression_ratio", "compress_GBps", "decompress_GBps",
                                                   "compress_frac_of_hbm_peak", "decompress_frac_of_hbm_peak")}

@@ -179,6 +179,54 @@ typedef struct {
 } enec_decompress_item;
 int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, void *stream);
 
+/* Decompression pipelines [Sec. VI, "End-to-End Inference Configurations": weights are decompressed layer
+ * by layer, the decompression of layer k+1 overlapping the forward pass of layer k; Sec. VI, "End-to-End
+ * Inference Speedup": what is saved is the transfer of weights from the CPU].  A pipeline is a HOST object that orders
+ * work on the caller's HIP streams with events; it owns no device memory and launches only what
+ * enec_decompress_batch launches.  Layers are decoded into `n_slots` sets of output buffers that the caller
+ * owns (two = double buffering): slot s holds layer k while the consumer computes with it and is handed to
+ * layer k + n_slots afterwards.
+ *   enec_pipeline_prefetch            on the decompression stream: wait until the consumer has released
+ *                                     the slot, then decompress `items` (DEVICE streams, as for
+ *                                     enec_decompress_batch) into the slot's buffers
+ *   enec_pipeline_prefetch_from_host  the same for streams held in pinned HOST memory (hipHostMalloc): each
+ *                                     stream is copied into one half of the DEVICE staging buffer on the
+ *                                     copy stream and decoded out of it on the decompression stream, so that
+ *                                     the copy of stream i + 1 overlaps the decoding of stream i.  The header
+ *                                     is read from the host copy.  ENEC_E_CAPACITY if a stream is larger than
+ *                                     half the staging buffer.
+ *   enec_pipeline_acquire             the consumer's stream waits until the slot's prefetch has finished
+ *   enec_pipeline_release             marks, on the consumer's stream, the point after which the slot's
+ *                                     buffers may be overwritten
+ * All four return at once (nothing waits on the host).  Calls on one pipeline must come from one host
+ * thread at a time.  Streams are hipStream_t handles and stay the caller's; keep them at the default
+ * priority.  Items (also the host headers they point to) are read before the call returns.
+ *   n_slots            1..64
+ *   decompress_stream  where the decompression kernels run (a side stream, so that they overlap the consumer)
+ *   copy_stream        NULL, or a third stream for the host-to-device copies (needed for ..._from_host)
+ *   staging            NULL, or DEVICE, 16-byte aligned, staging_bytes bytes, used in two halves
+ *   trace              non-zero: record timing events around every copy and every decompression;
+ *                      enec_pipeline_trace then waits for them and returns, per step in call order, four
+ *                      times in milliseconds since the first event: copy start, copy end, decompression
+ *                      start, decompression end (-1 for the copy of a step that had none), and forgets them
+ * enec_pipeline_destroy frees the host object and its events; work already enqueued is not affected. */
+typedef struct enec_pipeline enec_pipeline;
+typedef struct {
+    const void *host_stream;    /* HOST, pinned: a whole ENEC stream */
+    size_t stream_bytes;
+    void *out;                  /* DEVICE, 16-byte aligned */
+    size_t n_elems;
+} enec_offload_item;
+int enec_pipeline_create(enec_pipeline **pipeline, uint32_t n_slots, void *decompress_stream, void *copy_stream,
+                         void *staging, size_t staging_bytes, int trace);
+void enec_pipeline_destroy(enec_pipeline *pipeline);
+int enec_pipeline_prefetch(enec_pipeline *pipeline, uint32_t slot, const enec_decompress_item *items, size_t n_items);
+int enec_pipeline_prefetch_from_host(enec_pipeline *pipeline, uint32_t slot, const enec_offload_item *items,
+                                     size_t n_items);
+int enec_pipeline_acquire(enec_pipeline *pipeline, uint32_t slot, void *consumer_stream);
+int enec_pipeline_release(enec_pipeline *pipeline, uint32_t slot, void *consumer_stream);
+int enec_pipeline_trace(enec_pipeline *pipeline, float *ms, size_t max_steps, size_t *n_steps);
+
 /* Parameter tuning [Sec. V-E phases 1-3]: exponent histogram on the device (one read of the
  * tensor), then the search for (b, n) by Eq. 1-3 and for m by Eq. 4 (L = 16) on the host.
  *   in         DEVICE, n_elems * 2 bytes (fp32: * 4), 16-byte aligned

@@ -1,6 +1,6 @@
 """Builds libenec.so (HIP, gfx950) in-tree with hipcc.  `python -m paper_2604_03298_amd.build`.
 
-The host code (csrc/enec_api.hip), the kernels for streams with one tuple per data block
+The host code (csrc/enec_api.hip, csrc/enec_pipeline.hip), the kernels for streams with one tuple per data block
 (csrc/enec_per_block.hip) and the 18 kernel tables (csrc/enec_kernels.hip, once per element format, group
 length and direction) are compiled side by side into _build/*.o and linked into libenec.so.
 """
@@ -16,7 +16,7 @@ LIB = os.path.join(HERE, "libenec.so")
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 SOURCES = [os.path.join(CSRC, "enec_api.hip"), os.path.join(CSRC, "enec_kernels.hip"),
-           os.path.join(CSRC, "enec_per_block.hip")]
+           os.path.join(CSRC, "enec_per_block.hip"), os.path.join(CSRC, "enec_pipeline.hip")]
 HEADERS = [os.path.join(CSRC, "enec_device.hpp"), os.path.join(CSRC, "enec_kernels.hpp"),
            os.path.join(CSRC, "enec_per_block.hpp"),
            os.path.join(ROOT, "include", "enec.h")]
@@ -26,7 +26,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950",
 
 
 def _units():
-    units = [("enec_api.o", [SOURCES[0]]), ("enec_per_block.o", [SOURCES[2]])]
+    units = [("enec_api.o", [SOURCES[0]]), ("enec_per_block.o", [SOURCES[2]]), ("enec_pipeline.o", [SOURCES[3]])]
     for lpg in (2, 1, 4):           # lanes per group: group lengths 16, 8, 32
         for dt in (0, 2, 1):
             for direction in (0, 1):

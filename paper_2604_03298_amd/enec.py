@@ -24,7 +24,9 @@ EXPORTS = [
     "enec_decompress_with_header", "enec_tune", "enec_tune_histogram", "enec_stream_info",
     "enec_copy", "enec_compress_batch", "enec_decompress_batch", "enec_tune_histogram_groups",
     "enec_tune_sampled", "enec_compress_sampled", "enec_compress_bound_per_block", "enec_compress_per_block",
-    "enec_tune_batch",
+    "enec_tune_batch", "enec_pipeline_create", "enec_pipeline_destroy",
+    "enec_pipeline_prefetch", "enec_pipeline_prefetch_from_host", "enec_pipeline_acquire", "enec_pipeline_release",
+    "enec_pipeline_trace",
 ]
 
 
@@ -48,6 +50,11 @@ class CompressItem(C.Structure):
 class DecompressItem(C.Structure):
     _fields_ = [("src", C.c_void_p), ("in_bytes", C.c_size_t), ("host_header", C.c_void_p),
                 ("out", C.c_void_p), ("n_elems", C.c_size_t)]
+
+
+class OffloadItem(C.Structure):
+    _fields_ = [("host_stream", C.c_void_p), ("stream_bytes", C.c_size_t), ("out", C.c_void_p),
+                ("n_elems", C.c_size_t)]
 
 
 class EnecError(RuntimeError):
@@ -113,6 +120,20 @@ def lib():
         L.enec_compress_batch.argtypes = [C.POINTER(CompressItem), sz, C.c_int, vp, sz, vp]
         L.enec_decompress_batch.restype = C.c_int
         L.enec_decompress_batch.argtypes = [C.POINTER(DecompressItem), sz, vp]
+        L.enec_pipeline_create.restype = C.c_int
+        L.enec_pipeline_create.argtypes = [C.POINTER(vp), u32, vp, vp, vp, sz, C.c_int]
+        L.enec_pipeline_destroy.restype = None
+        L.enec_pipeline_destroy.argtypes = [vp]
+        L.enec_pipeline_prefetch.restype = C.c_int
+        L.enec_pipeline_prefetch.argtypes = [vp, u32, C.POINTER(DecompressItem), sz]
+        L.enec_pipeline_prefetch_from_host.restype = C.c_int
+        L.enec_pipeline_prefetch_from_host.argtypes = [vp, u32, C.POINTER(OffloadItem), sz]
+        L.enec_pipeline_acquire.restype = C.c_int
+        L.enec_pipeline_acquire.argtypes = [vp, u32, vp]
+        L.enec_pipeline_release.restype = C.c_int
+        L.enec_pipeline_release.argtypes = [vp, u32, vp]
+        L.enec_pipeline_trace.restype = C.c_int
+        L.enec_pipeline_trace.argtypes = [vp, C.POINTER(C.c_float), sz, C.POINTER(sz)]
         _lib = L
     return _lib
 
@@ -366,3 +387,56 @@ def copy(dst, src, nbytes: int | None = None, stream=None) -> int:
     nb = src.numel() * src.element_size() if nbytes is None else nbytes
     return int(lib().enec_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nb,
                                _stream_handle(stream)))
+
+
+class Pipeline:
+    """Handle of an enec_pipeline (include/enec.h): layer-wise decompression on a side stream, ordered
+    against the consumer's stream with events; optionally fed from pinned host memory through a staging
+    buffer.  Marshals arguments only."""
+
+    def __init__(self, n_slots: int, decompress_stream, copy_stream=None, staging=None, trace: bool = False):
+        self._h = C.c_void_p()
+        self._keep = (decompress_stream, copy_stream, staging)
+        _check(lib().enec_pipeline_create(
+            C.byref(self._h), n_slots, C.c_void_p(decompress_stream.cuda_stream),
+            C.c_void_p(copy_stream.cuda_stream) if copy_stream is not None else None,
+            C.c_void_p(staging.data_ptr()) if staging is not None else None,
+            staging.numel() * staging.element_size() if staging is not None else 0, int(trace)),
+            "enec_pipeline_create")
+
+    def close(self):
+        if self._h:
+            lib().enec_pipeline_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+    def prefetch(self, slot: int, items) -> int:
+        """items: the array make_decompress_items returns (device streams)."""
+        return int(lib().enec_pipeline_prefetch(self._h, slot, items, len(items)))
+
+    def prefetch_from_host(self, slot: int, host_streams, outs) -> int:
+        """host_streams: pinned uint8 tensors, each one whole stream; outs: device tensors."""
+        n = len(host_streams)
+        items = (OffloadItem * n)()
+        for i in range(n):
+            items[i].host_stream = host_streams[i].data_ptr()
+            items[i].stream_bytes = host_streams[i].numel()
+            items[i].out = outs[i].data_ptr()
+            items[i].n_elems = outs[i].numel()
+        return int(lib().enec_pipeline_prefetch_from_host(self._h, slot, items, n))
+
+    def acquire(self, slot: int, consumer_stream=None) -> int:
+        return int(lib().enec_pipeline_acquire(self._h, slot, _stream_handle(consumer_stream)))
+
+    def release(self, slot: int, consumer_stream=None) -> int:
+        return int(lib().enec_pipeline_release(self._h, slot, _stream_handle(consumer_stream)))
+
+    def trace(self, max_steps: int = 4096):
+        """Waits for the recorded steps; -> array (steps, 4) of milliseconds: copy start, copy end,
+        decompression start, decompression end (-1 where a step had no copy)."""
+        ms = np.zeros((max_steps, 4), dtype=np.float32)
+        n = C.c_size_t(0)
+        _check(lib().enec_pipeline_trace(self._h, ms.ctypes.data_as(C.POINTER(C.c_float)), max_steps, C.byref(n)),
+               "enec_pipeline_trace")
+        return ms[:min(int(n.value), max_steps)].copy()

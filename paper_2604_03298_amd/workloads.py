@@ -139,3 +139,29 @@ def config5_spec(n_layers: int = 8, hidden: int = 8192, ffn: int = 28672):
         spec.append((hidden, hidden, 500 + 2 * i))
         spec.append((hidden, ffn, 501 + 2 * i))
     return spec
+
+
+def gpu_gaussian(torch, rows, cols, std, seed, dtype=None):
+    """N(0, std^2) drawn on the GPU, as bit patterns: int16 for bf16 (default) and float16, int32 for float32."""
+    dtype = torch.bfloat16 if dtype is None else dtype
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    x = torch.empty(rows * cols, dtype=dtype, device="cuda")
+    step = 1 << 25      # float64 draws: float32 samplers emit exact zeros, which would force n = 8
+    for s in range(0, x.numel(), step):
+        e = min(x.numel(), s + step)
+        x[s:e] = (torch.randn(e - s, generator=g, device="cuda", dtype=torch.float64) * std).to(dtype)
+    return x.view(torch.int32 if dtype == torch.float32 else torch.int16)
+
+
+def config4_device(torch, index: int, rows: int = 8192, cols: int = 28672):
+    """Tensor `index` (0..31) of the large-layer stream drawn on the GPU (15 GB of numpy normals take
+    minutes): N(0, config4_std(index)^2), seed 4000 + index.  The host sees the same bytes through a
+    device-to-host copy."""
+    return gpu_gaussian(torch, rows, cols, config4_std(index), 4000 + index)
+
+
+def config5_device(torch, index: int, spec=None):
+    """Tensor `index` (0..15) of the offload scenario drawn on the GPU: N(0, 0.015^2), seeds of config5_spec."""
+    rows, cols, seed = (spec or config5_spec())[index]
+    return gpu_gaussian(torch, rows, cols, 0.015, seed)

@@ -1,6 +1,6 @@
 """Runs the codec on all five synthetic configurations on one MI355X and prints one JSON line per
 configuration (throughput on uncompressed bytes, ratio, fraction of the 8 TB/s HBM peak in bytes
-moved).  `python -m paper_2604_03298_amd.report [--configs 1,2,2j,3a,3b,4,5,fp16,fp32]`.
+moved).  `python report.py [--configs 1,2,2j,3a,3b,4,5,fp16,fp32]`.
 2j is configuration 2 tuned with the group length searched together with m (Eq. 4); the last two are the
 seven matrix shapes of configuration 2 as fp16 / fp32 tensors, N(0, 0.02^2).
 
@@ -126,19 +126,6 @@ def run_per_block(torch, enec, name, srcs, reps=5, dtype=0):
     }
 
 
-def gpu_gaussian(torch, rows, cols, std, seed, dtype=None):
-    """N(0, std^2) drawn on the GPU, as bit patterns: int16 for bf16 (default) and float16, int32 for float32."""
-    dtype = torch.bfloat16 if dtype is None else dtype
-    g = torch.Generator(device="cuda")
-    g.manual_seed(seed)
-    x = torch.empty(rows * cols, dtype=dtype, device="cuda")
-    step = 1 << 25      # float64 draws: float32 samplers emit exact zeros, which would force n = 8
-    for s in range(0, x.numel(), step):
-        e = min(x.numel(), s + step)
-        x[s:e] = (torch.randn(e - s, generator=g, device="cuda", dtype=torch.float64) * std).to(dtype)
-    return x.view(torch.int32 if dtype == torch.float32 else torch.int16)
-
-
 def offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs):
     """Configuration 5: compressed streams in pinned host memory; per tensor copy the stream over PCIe
     on one HIP stream and decompress it on another, overlapped with the next copy; compared with
@@ -198,7 +185,7 @@ def main():
     args = ap.parse_args()
     want = args.configs.split(",")
     import torch
-    from . import enec, workloads as W
+    from paper_2604_03298_amd import enec, workloads as W
     assert torch.cuda.is_available()
     enec.lib()
 
@@ -225,12 +212,12 @@ def main():
             name = ["zero blocks", "constant blocks", "Student-t blocks", "random 16-bit patterns"][c]
             print(json.dumps(run_group(torch, enec, f"3b: {name}", [dev(t)], reps=10)[0]), flush=True)
     if "4" in want:
-        srcs = [gpu_gaussian(torch, 8192, 28672, W.config4_std(i), 4000 + i) for i in range(32)]
+        srcs = [W.config4_device(torch, i) for i in range(32)]
         print(json.dumps(run_group(torch, enec, "4: 32 tensors 8192x28672", srcs, reps=3)[0]), flush=True)
         del srcs
         torch.cuda.empty_cache()
     if "5" in want:
-        srcs = [gpu_gaussian(torch, r, c, 0.015, seed) for r, c, seed in W.config5_spec()]
+        srcs = [W.config5_device(torch, i) for i in range(16)]
         res, (outs, stream_bytes, hdrs, backs) = run_group(torch, enec, "5: 8 layers 8192x8192 + 8192x28672 (HBM resident)", srcs, reps=3)
         res["offload"] = offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs)
         print(json.dumps(res), flush=True)
@@ -239,7 +226,7 @@ def main():
     for key, tdt, code in (("fp16", torch.float16, enec.FP16), ("fp32", torch.float32, enec.FP32)):
         if key in want:
             shapes = [(r, c) for name, r, c, _ in W.config2_spec() if r > 1 and c > 1]
-            srcs = [gpu_gaussian(torch, r, c, 0.02, 6000 + i, tdt) for i, (r, c) in enumerate(shapes)]
+            srcs = [W.gpu_gaussian(torch, r, c, 0.02, 6000 + i, tdt) for i, (r, c) in enumerate(shapes)]
             print(json.dumps(run_group(torch, enec, f"{key}: the seven matrices of configuration 2 as {key}, N(0,0.02^2)",
                                        srcs, reps=20, dtype=code)[0]), flush=True)
             del srcs

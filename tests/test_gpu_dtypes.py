@@ -227,7 +227,7 @@ def test_decompress_without_host_header_and_wrong_size(gpu, oracle):
 def test_fp32_tensor_beyond_4_gib(gpu, oracle):
     """1.3e9 fp32 elements (5.2 GB): the region of lower halves alone exceeds 2^31 bytes, offsets exceed 2^32."""
     torch, enec = gpu.torch, gpu.enec
-    from paper_2604_03298_amd.report import gpu_gaussian
+    from paper_2604_03298_amd.workloads import gpu_gaussian
     src = gpu_gaussian(torch, 45000, 28672 + 231, 0.02, 4343, torch.float32)
     n = src.numel()
     assert 4 * n > (1 << 32)

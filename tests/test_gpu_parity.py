@@ -468,7 +468,7 @@ def test_tensor_beyond_4_gib_sampled_against_the_oracle(gpu, oracle):
     on the device; blocks sampled along the tensor are recompressed by the oracle one group of blocks at a
     time, and their payloads must be the bytes the library wrote at the offsets its table gives."""
     torch, enec = gpu.torch, gpu.enec
-    from paper_2604_03298_amd.report import gpu_gaussian
+    from paper_2604_03298_amd.workloads import gpu_gaussian
     rows, cols = 90000, 28672 + 231          # not a multiple of the block size: ragged tail
     src = gpu_gaussian(torch, rows, cols, 0.02, 4242)
     n = src.numel()

@@ -248,7 +248,7 @@ def test_tensor_beyond_4_gib_sampled_against_the_oracle(gpu, oracle):
     32 bits, a look-back over many windows.  The round trip is compared on the device; blocks sampled along the
     tensor are recompressed by the oracle, tuples and payloads must be what the library wrote."""
     torch, enec = gpu.torch, gpu.enec
-    from paper_2604_03298_amd.report import gpu_gaussian
+    from paper_2604_03298_amd.workloads import gpu_gaussian
     rows, cols = 90000, 28672 + 231          # not a multiple of the block size: ragged tail
     src = gpu_gaussian(torch, rows, cols, 0.02, 4343)
     n = src.numel()
