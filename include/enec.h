@@ -133,6 +133,23 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
                   const enec_params *params, void *out, size_t out_capacity,
                   uint64_t *out_bytes, void *workspace, size_t workspace_bytes, void *stream);
 
+/* enec_compress for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scan state, ticket
+ * counters and call tags live in an array of ENEC_STATIC_SCRATCH_BYTES bytes inside the library's code
+ * object, one per GPU, held until the process ends; the call allocates nothing, on the device or through
+ * any library.  Arguments as for enec_compress, without the workspace; params must not be NULL
+ * (ENEC_E_ARG: tuning would wait for the stream).  ENEC_E_CAPACITY if the tensor needs more scan state
+ * than the array holds, i.e. if enec_workspace_bytes(n_elems, block_size) > ENEC_STATIC_SCRATCH_BYTES
+ * (at the default block size about 1.6e9 elements fit, at block size 2048 about 2.0e8).  The first
+ * call on a GPU enqueues a fill kernel on `stream` that zeroes the array; after that the array keeps
+ * the state the last call left, as a workspace does.  All calls on one GPU share that GPU's array:
+ * calls that overlap in time on one GPU (two streams, two host threads) race and must be serialised by
+ * the caller.  The stream written is the one enec_compress writes. */
+#define ENEC_STATIC_SCRATCH_BYTES (1u << 20)
+int enec_compress_static(const void *in, size_t n_elems, int dtype, uint32_t block_size,
+                         const enec_params *params, void *out, size_t out_capacity, uint64_t *out_bytes,
+                         void *stream);
+
 /* Compress several tensors with as few kernel launches as possible: tensors that share (m, n - m, L,
  * block size) go into one launch (up to 16 tensors each), whose workgroups walk the data blocks of all of them, so that
  * small tensors cost no launch of their own and the device never drains between tensors.

@@ -534,6 +534,57 @@ int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size
     return enec_compress_batch(&it, 1, dtype, workspace, workspace_bytes, stream);
 }
 
+// ---- enec_compress for callers that cannot allocate: the workspace is the library's own array ----
+}  // extern "C"
+
+namespace {
+
+// Scan state, ticket counters and call tags of enec_compress_static: one array per GPU, held until the
+// process ends.  In host code the array's name stands for the symbol, not for device memory; the
+// address on a device comes from hipGetSymbolAddress with that device current, once per device.
+static __device__ __align__(256) uint8_t scratch[ENEC_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+void *scratch_ptr[MAX_DEVICES];       // per device: the array's address there, null until its first call
+std::mutex scratch_mu;
+
+// address of `scratch` on the current device; the first call on a device looks it up and enqueues
+// the fill kernel that brings the array into the state enec_workspace_init leaves a workspace in
+int static_scratch(hipStream_t s, void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) { (void)hipGetLastError(); return ENEC_E_HIP; }
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return ENEC_E_HIP; }
+        const int rc = enec_workspace_init(ptr, ENEC_STATIC_SCRATCH_BYTES, s);
+        if (rc != ENEC_OK) return rc;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return ENEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int enec_compress_static(const void *in, size_t n_elems, int dtype, uint32_t block_size, const enec_params *params,
+                         void *out, size_t out_capacity, uint64_t *out_bytes, void *stream)
+{
+    if (!params) return ENEC_E_ARG;                       // tuning waits for the stream: not for these callers
+    if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
+    const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
+    if (!block_ok(B)) return ENEC_E_BLOCK;
+    if (n_elems > MAX_ELEMS) return ENEC_E_ARG;
+    if (enec_workspace_bytes(n_elems, B) > ENEC_STATIC_SCRATCH_BYTES) return ENEC_E_CAPACITY;
+    void *ws = nullptr;
+    const int rc = static_scratch((hipStream_t)stream, &ws);
+    if (rc != ENEC_OK) return rc;
+    return enec_compress(in, n_elems, dtype, B, params, out, out_capacity, out_bytes, ws, ENEC_STATIC_SCRATCH_BYTES, stream);
+}
+
 size_t enec_compress_bound_per_block(size_t n_elems, int dtype, uint32_t block_size)
 {
     const size_t bound = enec_compress_bound(n_elems, dtype, block_size);

@@ -24,7 +24,7 @@ EXPORTS = [
     "enec_decompress_with_header", "enec_tune", "enec_tune_histogram", "enec_stream_info",
     "enec_copy", "enec_compress_batch", "enec_decompress_batch", "enec_tune_histogram_groups",
     "enec_tune_sampled", "enec_compress_sampled", "enec_compress_bound_per_block", "enec_compress_per_block",
-    "enec_tune_batch", "enec_pipeline_create", "enec_pipeline_destroy",
+    "enec_tune_batch", "enec_compress_static", "enec_pipeline_create", "enec_pipeline_destroy",
     "enec_pipeline_prefetch", "enec_pipeline_prefetch_from_host", "enec_pipeline_acquire", "enec_pipeline_release",
     "enec_pipeline_trace",
 ]
@@ -90,6 +90,8 @@ def lib():
         L.enec_workspace_init.argtypes = [vp, sz, vp]
         L.enec_compress.restype = C.c_int
         L.enec_compress.argtypes = [vp, sz, C.c_int, u32, C.POINTER(Params), vp, sz, vp, vp, sz, vp]
+        L.enec_compress_static.restype = C.c_int
+        L.enec_compress_static.argtypes = [vp, sz, C.c_int, u32, C.POINTER(Params), vp, sz, vp, vp]
         L.enec_decompress.restype = C.c_int
         L.enec_decompress.argtypes = [vp, sz, vp, sz, vp]
         L.enec_decompress_with_header.restype = C.c_int
@@ -244,6 +246,22 @@ def compress(src, params, out, workspace, block_size: int = 0, out_bytes=None, s
         C.c_void_p(src.data_ptr()), n, dt, block_size, pp, C.c_void_p(out.data_ptr()),
         out.numel() * out.element_size(), ob, C.c_void_p(workspace.data_ptr()),
         workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+STATIC_SCRATCH_BYTES = 1 << 20
+
+
+def compress_static(src, params, out, block_size: int = 0, out_bytes=None, stream=None,
+                    n_elems: int | None = None, dtype: int | None = None) -> int:
+    """Enqueues enec_compress_static: enec_compress on the library's own scratch array (no workspace,
+    no allocation); params must be given."""
+    n = src.numel() if n_elems is None else n_elems
+    dt = dtype_of(src, dtype)
+    pp = C.byref(_params(params)) if params is not None else None
+    ob = C.c_void_p(out_bytes.data_ptr()) if out_bytes is not None else None
+    return int(lib().enec_compress_static(
+        C.c_void_p(src.data_ptr()), n, dt, block_size, pp, C.c_void_p(out.data_ptr()),
+        out.numel() * out.element_size(), ob, _stream_handle(stream)))
 
 
 def compress_bound_per_block(n_elems: int, dtype: int = BF16, block_size: int = 0) -> int:
