@@ -126,59 +126,6 @@ def run_per_block(torch, enec, name, srcs, reps=5, dtype=0):
     }
 
 
-def offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs):
-    """Configuration 5: compressed streams in pinned host memory; per tensor copy the stream over PCIe
-    on one HIP stream and decompress it on another, overlapped with the next copy; compared with
-    copying the uncompressed bf16."""
-    host_c = [torch.empty(b, dtype=torch.uint8).pin_memory() for b in stream_bytes]
-    for h, o, b in zip(host_c, outs, stream_bytes):
-        h.copy_(o[:b])
-    host_raw = [torch.empty(s.numel(), dtype=torch.int16).pin_memory() for s in srcs]
-    for h, s in zip(host_raw, srcs):
-        h.copy_(s)
-    torch.cuda.synchronize()
-    copy_s, comp_s = torch.cuda.Stream(), torch.cuda.Stream()
-    dev_c = [torch.empty(max(stream_bytes), dtype=torch.uint8, device="cuda") for _ in range(2)]
-    n = len(srcs)
-
-    def pipelined():
-        ready = [torch.cuda.Event() for _ in range(n)]
-        freed = [torch.cuda.Event() for _ in range(n)]
-        for i in range(n):
-            buf = dev_c[i % 2]
-            with torch.cuda.stream(copy_s):
-                if i >= 2:
-                    copy_s.wait_event(freed[i - 2])
-                buf[:stream_bytes[i]].copy_(host_c[i], non_blocking=True)
-                ready[i].record(copy_s)
-            comp_s.wait_event(ready[i])
-            rc = enec.decompress_with_header(buf, hdrs[i], backs[i], stream=comp_s)
-            assert rc == 0
-            freed[i].record(comp_s)
-        comp_s.synchronize()
-
-    def plain():
-        with torch.cuda.stream(copy_s):
-            for i in range(n):
-                backs[i].copy_(host_raw[i], non_blocking=True)
-        copy_s.synchronize()
-
-    res = {}
-    for name, fn in (("compressed_copy_plus_decompress", pipelined), ("uncompressed_copy", plain)):
-        fn()
-        torch.cuda.synchronize()
-        ts = []
-        for _ in range(3):
-            t0 = time.perf_counter(); fn(); torch.cuda.synchronize(); ts.append(time.perf_counter() - t0)
-        res[name + "_ms"] = round(1e3 * float(np.median(ts)), 3)
-    assert all(torch.equal(b, s) for b, s in zip(backs, srcs))
-    raw = 2 * sum(s.numel() for s in srcs)
-    res["effective_weights_GBps_compressed"] = round(raw / res["compressed_copy_plus_decompress_ms"] / 1e6, 1)
-    res["effective_weights_GBps_uncompressed"] = round(raw / res["uncompressed_copy_ms"] / 1e6, 1)
-    res["speedup"] = round(res["uncompressed_copy_ms"] / res["compressed_copy_plus_decompress_ms"], 3)
-    return res
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="1,2,2j,2p,3a,3p,3b,4,5,fp16,fp32")
@@ -219,7 +166,8 @@ def main():
     if "5" in want:
         srcs = [W.config5_device(torch, i) for i in range(16)]
         res, (outs, stream_bytes, hdrs, backs) = run_group(torch, enec, "5: 8 layers 8192x8192 + 8192x28672 (HBM resident)", srcs, reps=3)
-        res["offload"] = offload(torch, enec, srcs, outs, stream_bytes, hdrs, backs)
+        import bench
+        res["offload"] = bench.offload_scenario(torch, np, enec, srcs, [o[:b] for o, b in zip(outs, stream_bytes)])
         print(json.dumps(res), flush=True)
         del srcs, outs, backs
         torch.cuda.empty_cache()
