@@ -69,7 +69,8 @@ typedef enum {
     ENEC_E_CAPACITY = 5,  /* out_capacity < enec_compress_bound() or workspace too small */
     ENEC_E_RANGE = 6,     /* an exponent lies outside [b - 2^(n-1) + 1, b + 2^(n-1)] while n < E */
     ENEC_E_FORMAT = 7,    /* not an ENEC stream, or header does not match the call */
-    ENEC_E_HIP = 8        /* a HIP runtime call failed; as a header status: the scan gave up on a corrupt workspace */
+    ENEC_E_HIP = 8        /* a HIP runtime call failed; as a header status: the scan gave up on a corrupt workspace
+                             (every stream of that launch then carries it) */
 } enec_status;
 
 /* Element formats [Alg. 1 input line; Table VI]: sign | exponent | mantissa = 1|8|7, 1|5|10, 1|8|23.
@@ -169,6 +170,17 @@ typedef struct {
 int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
                         size_t workspace_bytes, void *stream);
 
+/* The same with a second HIP stream of the caller's to spread the launches over [Sec. V-A: the blocks
+ * of the work at hand are dealt to all cores]: a layer's tiny tensors (norm vectors, biases: one data
+ * block each) have tuples of their own and therefore a launch of their own, which costs about ten
+ * microseconds in front of or behind the launch of the large tensors.  Here such launches are enqueued on
+ * aux_stream, forked from and joined back into `stream` with events, so that they run beside the large
+ * launch; in `stream`'s order everything is complete when the next operation on `stream` starts.
+ * aux_stream must differ from stream (ENEC_E_ARG) and stay at the default priority.  Without tiny tensors
+ * the call is enec_compress_batch. */
+int enec_compress_batch_overlapped(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
+                                   size_t workspace_bytes, void *stream, void *aux_stream);
+
 /* Decompress [Sec. V-A decompression path; Alg. 1 decompression part].
  *   in        DEVICE, a stream written by enec_compress, 16-byte aligned
  *   in_bytes  size of the buffer behind `in`; ENEC_E_FORMAT if the header's total_bytes exceeds it.
@@ -181,9 +193,15 @@ int enec_decompress(const void *in, size_t in_bytes, void *out, size_t n_elems, 
 
 /* Same, fully asynchronous: `host_header` is a HOST copy of the stream's first 64 bytes that the
  * caller already holds (kept from compression, or read from a file).  The kernel compares it with
- * the header in device memory and writes nothing if they differ. */
+ * the header in device memory and writes nothing if they differ.
+ *   status   NULL, or a DEVICE-ACCESSIBLE pointer (device or pinned host memory, 4-byte aligned) to a
+ *            word the caller has set to 0: the kernel stores ENEC_E_FORMAT there if it leaves any data
+ *            block undecoded (header in memory differs from host_header, or an offset-table entry is
+ *            misaligned, out of order, outside the stream or implies an impossible size).  The blocks it
+ *            does decode are exact; a skipped block's part of `out` is not written.  Valid once the
+ *            stream has been synchronised.  With NULL such blocks are skipped silently. */
 int enec_decompress_with_header(const void *in, size_t in_bytes, const void *host_header, void *out,
-                                size_t n_elems, void *stream);
+                                size_t n_elems, uint32_t *status, void *stream);
 
 /* Decompress several streams with one launch per (dtype, m, n - m, block size); fields as the arguments of
  * enec_decompress_with_header.  Fully asynchronous. */
@@ -193,8 +211,14 @@ typedef struct {
     const void *host_header;    /* HOST, 64 bytes */
     void *out;                  /* DEVICE */
     size_t n_elems;
+    uint32_t *status;           /* device-accessible word set to 0 by the caller, or NULL */
 } enec_decompress_item;
 int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, void *stream);
+
+/* The same with launches for tensors of one data block on aux_stream, beside the large launches; see
+ * enec_compress_batch_overlapped. */
+int enec_decompress_batch_overlapped(const enec_decompress_item *items, size_t n_items, void *stream,
+                                     void *aux_stream);
 
 /* Decompression pipelines [Sec. VI, "End-to-End Inference Configurations": weights are decompressed layer
  * by layer, the decompression of layer k+1 overlapping the forward pass of layer k; Sec. VI, "End-to-End
@@ -233,6 +257,7 @@ typedef struct {
     size_t stream_bytes;
     void *out;                  /* DEVICE, 16-byte aligned */
     size_t n_elems;
+    uint32_t *status;           /* as in enec_decompress_item, or NULL */
 } enec_offload_item;
 int enec_pipeline_create(enec_pipeline **pipeline, uint32_t n_slots, void *decompress_stream, void *copy_stream,
                          void *staging, size_t staging_bytes, int trace);
@@ -315,9 +340,13 @@ int enec_tune_histogram(const uint64_t *histogram, int dtype, enec_params *param
 /* The same search with the group length L chosen together with m, as Eq. 4 states it [Sec. V-E phase 3]:
  * group_lengths is the OR of the candidate lengths (8, 16, 32).  The paper's hardware forces L >= 16 and
  * finds 16 optimal throughout [Sec. VI-D], which is what enec_tune and enec_tune_histogram return;
- * without that rule shorter groups often win.  A tuple with L = 32 needs block_size >= 4096, one with
- * L = 8 block_size <= 16384 (ENEC_E_PARAMS from enec_compress otherwise). */
-int enec_tune_histogram_groups(const uint64_t *histogram, int dtype, uint32_t group_lengths, enec_params *params);
+ * without that rule shorter groups often win.  block_size (0 = 16384) is the data-block size the tensor
+ * will be compressed with: a length it does not admit (128 L <= block_size <= 2048 L, i.e. L = 32 needs
+ * block_size >= 4096 and L = 8 block_size <= 16384) is left out of the search, and 16, which every block
+ * size admits, stands in if none is left.  ENEC_E_PARAMS if group_lengths names no or other lengths,
+ * ENEC_E_BLOCK for an invalid block size. */
+int enec_tune_histogram_groups(const uint64_t *histogram, int dtype, uint32_t group_lengths, uint32_t block_size,
+                               enec_params *params);
 
 /* Parse a HOST copy of a stream's first 64 bytes.  Any output pointer may be NULL.
  * Returns ENEC_E_FORMAT if it is not a version-1 ENEC header. */

@@ -1,5 +1,8 @@
 """Builds libenec.so (HIP, gfx950) in-tree with hipcc.  `python -m paper_2604_03298_amd.build`.
 
+libenec_test.so is the same library with ENEC_TEST_HOOKS defined for the host code: there the environment
+variable ENEC_SPIN_LIMIT lowers the bound of the scan's waits, which the tests of that bound need.
+
 The host code (csrc/enec_api.hip, csrc/enec_pipeline.hip), the kernels for streams with one tuple per data block
 (csrc/enec_per_block.hip) and the 18 kernel tables (csrc/enec_kernels.hip, once per element format, group
 length and direction) are compiled side by side into _build/*.o and linked into libenec.so.
@@ -13,6 +16,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libenec.so")
+TEST_LIB = os.path.join(HERE, "libenec_test.so")      # the same library with ENEC_TEST_HOOKS (tests of the bounded waits)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 SOURCES = [os.path.join(CSRC, "enec_api.hip"), os.path.join(CSRC, "enec_kernels.hip"),
@@ -26,7 +30,8 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950",
 
 
 def _units():
-    units = [("enec_api.o", [SOURCES[0]]), ("enec_per_block.o", [SOURCES[2]]), ("enec_pipeline.o", [SOURCES[3]])]
+    units = [("enec_api.o", [SOURCES[0]]), ("enec_api_test.o", ["-DENEC_TEST_HOOKS", SOURCES[0]]),
+             ("enec_per_block.o", [SOURCES[2]]), ("enec_pipeline.o", [SOURCES[3]])]
     for lpg in (2, 1, 4):           # lanes per group: group lengths 16, 8, 32
         for dt in (0, 2, 1):
             for direction in (0, 1):
@@ -52,12 +57,14 @@ def build(verbose: bool = False) -> str:
     workers = max(1, min(8, os.cpu_count() or 1))
     with ThreadPoolExecutor(workers) as pool:
         objects = list(pool.map(compile_one, _units()))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB] + objects
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc (link) failed:\n" + res.stdout + res.stderr)
+    api, api_test = os.path.join(OBJ, "enec_api.o"), os.path.join(OBJ, "enec_api_test.o")
+    for lib, skip in ((LIB, api_test), (TEST_LIB, api)):
+        cmd = ["hipcc", "--offload-arch=gfx950", "-fPIC", "-shared", "-o", lib] + [o for o in objects if o != skip]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc (link) failed:\n" + res.stdout + res.stderr)
     return LIB
 
 

@@ -5,7 +5,9 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <mutex>
+#include <tuple>
 #include <vector>
 
 namespace enec {
@@ -122,20 +124,20 @@ bool device_accessible(const void *p)
            attr.type == hipMemoryTypeManaged;
 }
 
-// Number of workgroups of `fn` the current device holds at once (cached per kernel and shape).
-// The environment variable named by `env_cap` caps the per-CU figure (a tuning aid).
-unsigned resident_workgroups(const void *fn, unsigned threads, size_t lds, const char *env_cap)
+// Number of workgroups of `fn` the current device holds at once.  The figure depends only on the
+// kernel, its launch shape and the device, so it is looked up once per such combination and kept (a
+// map under a mutex: there are several hundred kernel instances); a call whose combination is known
+// makes no HIP call here, which also keeps it usable under stream capture once warmed up.
+unsigned resident_workgroups(const void *fn, unsigned threads, size_t lds)
 {
-    struct Entry { const void *fn; unsigned threads; size_t lds; int dev; unsigned value; };
-    static Entry cache[256];
-    static int used = 0;
+    static std::map<std::tuple<const void *, unsigned, size_t, int>, unsigned> cache;
     static std::mutex mu;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     std::lock_guard<std::mutex> lock(mu);
-    for (int i = 0; i < used; ++i)
-        if (cache[i].fn == fn && cache[i].threads == threads && cache[i].lds == lds && cache[i].dev == dev)
-            return cache[i].value;
+    const auto key = std::make_tuple(fn, threads, lds, dev);
+    const auto hit = cache.find(key);
+    if (hit != cache.end()) return hit->second;
     if (lds > 65536 &&
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return 0;
@@ -143,16 +145,131 @@ unsigned resident_workgroups(const void *fn, unsigned threads, size_t lds, const
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, (int)threads, lds) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || per_cu < 1 || cus < 1)
         return 0;
-    if (const char *e = std::getenv(env_cap)) {
-        const int cap = std::atoi(e);
-        if (cap >= 1 && cap < per_cu) per_cu = cap;
-    }
     const unsigned value = (unsigned)per_cu * (unsigned)cus;
-    if (used < 256) cache[used++] = Entry{fn, threads, lds, dev, value};
+    cache.emplace(key, value);
     return value;
 }
 
+// A persistent grid for `total` blocks on a device that holds `resident` workgroups: the blocks take
+// ceil(total / resident) rounds whatever the grid, so the grid is shrunk until every round is full.
+// (With the largest grid the last round keeps a few workgroups busy and the rest of the device idle
+// for a whole block's latency.)
+unsigned balanced_grid(unsigned total, unsigned resident)
+{
+    if (total <= resident) return total;
+    const unsigned rounds = (total + resident - 1) / resident;
+    return (total + rounds - 1) / rounds;
+}
+
+// polls after which a waiting workgroup gives up; builds with ENEC_TEST_HOOKS (the test library) let
+// the environment lower it so that a test can watch a scan give up without waiting for seconds
+uint32_t spin_limit()
+{
+#ifdef ENEC_TEST_HOOKS
+    if (const char *e = std::getenv("ENEC_SPIN_LIMIT")) {
+        const long v = std::atol(e);
+        if (v > 0 && v < (long)SPIN_LIMIT) return (uint32_t)v;
+    }
+#endif
+    return SPIN_LIMIT;
+}
+
+// fork / join of an auxiliary stream around a batch call: work enqueued on `aux` between fork() and
+// join() runs beside what the call enqueues on `main` and is complete, in `main`'s order, after join()
+struct AuxFork {
+    hipStream_t main, aux;
+    bool forked = false;
+    AuxFork(hipStream_t m, hipStream_t a) : main(m), aux(a) {}
+    bool fork()
+    {
+        if (forked) return true;
+        hipEvent_t e = nullptr;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return false;
+        const bool good = hipEventRecord(e, main) == hipSuccess && hipStreamWaitEvent(aux, e, 0) == hipSuccess;
+        (void)hipEventDestroy(e);          // released by the runtime once the recorded work has passed it
+        forked = good;
+        return good;
+    }
+    bool join()
+    {
+        if (!forked) return true;
+        hipEvent_t e = nullptr;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return false;
+        const bool good = hipEventRecord(e, aux) == hipSuccess && hipStreamWaitEvent(main, e, 0) == hipSuccess;
+        (void)hipEventDestroy(e);
+        forked = false;
+        return good;
+    }
+};
+
 unsigned bit_length(unsigned v) { unsigned r = 0; for (; v; v >>= 1) ++r; return r; }
+
+// ---- Sec. V-E phases 1-3 on a 256-bin exponent histogram -------------------------------------
+struct Search {
+    unsigned lo, hi;            // occupied exponent range [l, h] (phase 1)
+    uint64_t total;             // number of elements
+    unsigned b, n;              // mapping centre and stored width (phase 2)
+    unsigned m, L;              // threshold width and group length (phase 3)
+    uint64_t at_most[9];        // at_most[w] = elements whose y fits in w bits, w = 0 .. n
+};
+
+// Phase 2: every centre b of [l, h] with the width Eq. 1 gives it (capped at the exponent field) is
+// priced by Eq. 3 in exact integers, sum of count * y with y from Eq. 2; the cheapest wins, then the
+// narrower, then the smaller centre.  Afterwards the elements are counted by the bit length of their y,
+// which is all phase 3 needs.  False for an empty histogram.
+bool centre_and_width(const uint64_t *hist, unsigned nmax, Search &r)
+{
+    r.lo = 256; r.hi = 0; r.total = 0;
+    for (unsigned x = 0; x < 256; ++x) {
+        if (!hist[x]) continue;
+        if (r.lo == 256) r.lo = x;
+        r.hi = x;
+        r.total += hist[x];
+    }
+    if (r.total == 0) return false;
+    auto key_of = [&](unsigned b) {
+        const unsigned need_below = bit_length(b - r.lo);                       // y = b - x, largest for x = l
+        const unsigned need_above = r.hi > b ? bit_length(r.hi - b - 1u) : 0u;  // y = 2^n - (x - b)
+        unsigned n = (need_below > need_above ? need_below : need_above) + 1u;
+        if (n > nmax) n = nmax;
+        uint64_t cost = 0;
+        for (unsigned x = r.lo; x <= r.hi; ++x) cost += hist[x] * (uint64_t)((b - x) & ((1u << n) - 1u));
+        return std::make_tuple(cost, n, b);
+    };
+    auto best = key_of(r.lo);
+    for (unsigned b = r.lo + 1; b <= r.hi; ++b) {
+        const auto k = key_of(b);
+        if (k < best) best = k;                   // lexicographic: cost, then width, then centre
+    }
+    r.n = std::get<1>(best);
+    r.b = std::get<2>(best);
+    uint64_t by_length[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    for (unsigned x = r.lo; x <= r.hi; ++x) by_length[bit_length((r.b - x) & ((1u << r.n) - 1u))] += hist[x];
+    uint64_t run = 0;
+    for (unsigned w = 0; w <= r.n; ++w) { run += by_length[w]; r.at_most[w] = run; }
+    return true;
+}
+
+// Phase 3, Eq. 4: expected exponent bits per element 1/L + n + (m - n) p(m)^L over m in [0, n] and the
+// candidate group lengths (OR of 8, 16, 32), p(m) = share of elements with y < 2^m.  Evaluated in IEEE
+// double, p^L by log2 L squarings, as (1/L + n) + (m - n) p^L; the smallest wins, then the smaller m,
+// then the smaller L.  (The build keeps the compiler from fusing the multiply and the add.)
+void threshold_and_length(Search &r, uint32_t lengths)
+{
+    bool have = false;
+    double least = 0.0;
+    for (unsigned L = 8, squarings = 3; L <= 32; L *= 2, ++squarings) {
+        if (!(lengths & L)) continue;
+        for (unsigned m = 0; m <= r.n; ++m) {
+            double q = (double)r.at_most[m] / (double)r.total;
+            for (unsigned i = 0; i < squarings; ++i) q = q * q;
+            const double bits = (1.0 / (double)L + (double)r.n) + ((double)m - (double)r.n) * q;
+            if (!have || bits < least || (bits == least && (m < r.m || (m == r.m && L < r.L)))) {
+                have = true; least = bits; r.m = m; r.L = L;
+            }
+        }
+    }
+}
 
 struct Header {
     enec_params prm;
@@ -195,11 +312,11 @@ const char *enec_strerror(int status)
     case ENEC_E_ARG: return "invalid argument (null or misaligned pointer, size out of range)";
     case ENEC_E_DTYPE: return "unsupported dtype (bf16, fp16 and fp32 are supported)";
     case ENEC_E_BLOCK: return "block_size must be a power of two in [2048, 32768]";
-    case ENEC_E_PARAMS: return "invalid parameters (need 1 <= n <= exponent width, 0 <= m <= n, b inside the exponent range, L == 16)";
+    case ENEC_E_PARAMS: return "invalid parameters (need 1 <= n <= exponent width, 0 <= m <= n, b inside the exponent range, L in {8, 16, 32} with 128 L <= block_size <= 2048 L)";
     case ENEC_E_CAPACITY: return "output capacity or workspace too small";
     case ENEC_E_RANGE: return "an exponent lies outside the window of (b, n)";
     case ENEC_E_FORMAT: return "not an ENEC stream or header mismatch";
-    case ENEC_E_HIP: return "HIP runtime error";
+    case ENEC_E_HIP: return "HIP runtime error (as a stream's status: the inter-block scan gave up on a workspace that was not in the state the last call left it in)";
     default: return "unknown status";
     }
 }
@@ -244,78 +361,29 @@ int enec_workspace_init(void *workspace, size_t bytes, void *stream)
 
 int enec_tune_histogram(const uint64_t *hist, int dtype, enec_params *params)
 {
-    if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
-    if (!hist || !params) return ENEC_E_ARG;
-    const unsigned nmax = exp_bits(dtype);
-    // Sec. V-E phase 1: occupied range [l, h] and the element count
-    int l = -1, h = -1;
-    uint64_t total = 0;
-    for (int x = 0; x < 256; ++x)
-        if (hist[x]) { if (l < 0) l = x; h = x; total += hist[x]; }
-    if (total == 0) { *params = enec_params{0, 1, 0, 16}; return ENEC_OK; }
-    // phase 2: every centre b in [l, h]; width from Eq. 1, cost from Eq. 2-3 in exact integers
-    uint64_t bestD = ~0ull;
-    unsigned bestN = 0, bestB = 0;
-    for (int b = l; b <= h; ++b) {
-        unsigned below = bit_length((unsigned)(b - l));
-        unsigned above = h > b ? bit_length((unsigned)(h - b - 1)) : 0;
-        unsigned n = (below > above ? below : above) + 1;
-        if (n > nmax) n = nmax;
-        const unsigned wrap = (1u << n) - 1u;
-        uint64_t D = 0;
-        for (int x = l; x <= h; ++x) D += hist[x] * (uint64_t)(((unsigned)(b - x)) & wrap);
-        if (D < bestD || (D == bestD && n < bestN)) { bestD = D; bestN = n; bestB = (unsigned)b; }
-    }
-    // phase 3: threshold m by Eq. 4 with L = 16 (p^16 by four squarings), ties to the smaller m
-    const unsigned wrap = (1u << bestN) - 1u;
-    double bestE = 0.0;
-    unsigned bestM = 0;
-    for (unsigned m = 0; m <= bestN; ++m) {
-        uint64_t cnt = 0;
-        for (int x = l; x <= h; ++x)
-            if (((bestB - (unsigned)x) & wrap) < (1u << m)) cnt += hist[x];
-        const double pm = (double)cnt / (double)total;
-        const double p2 = pm * pm, p4 = p2 * p2, p8 = p4 * p4, p16 = p8 * p8;
-        const double e = (1.0 / 16.0 + (double)bestN) + ((double)m - (double)bestN) * p16;
-        if (m == 0 || e < bestE) { bestE = e; bestM = m; }
-    }
-    *params = enec_params{(uint8_t)bestB, (uint8_t)bestN, (uint8_t)bestM, 16};
-    return ENEC_OK;
+    return enec_tune_histogram_groups(hist, dtype, 16u, 0u, params);
 }
 
-int enec_tune_histogram_groups(const uint64_t *hist, int dtype, uint32_t group_lengths, enec_params *params)
+int enec_tune_histogram_groups(const uint64_t *hist, int dtype, uint32_t group_lengths, uint32_t block_size,
+                               enec_params *params)
 {
+    if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
+    if (!hist || !params) return ENEC_E_ARG;
     if (!(group_lengths & (8u | 16u | 32u)) || (group_lengths & ~(8u | 16u | 32u))) return ENEC_E_PARAMS;
-    int rc = enec_tune_histogram(hist, dtype, params);            // (b, n) of phase 2
-    if (rc != ENEC_OK) return rc;
-    int l = -1, h = -1;
-    uint64_t total = 0;
-    for (int x = 0; x < 256; ++x)
-        if (hist[x]) { if (l < 0) l = x; h = x; total += hist[x]; }
-    // phase 3 as Eq. 4 states it: m and L together; p^L by squarings; ties to the smaller m, then the smaller L
-    const unsigned n = params->n, b = params->b, wrap = (1u << n) - 1u;
-    double bestE = 0.0;
-    unsigned bestM = 0, bestL = 0;
-    bool have = false;
-    for (unsigned m = 0; m <= n; ++m) {
-        double pm = 1.0;
-        if (total) {
-            uint64_t cnt = 0;
-            for (int x = l; x <= h; ++x)
-                if (((b - (unsigned)x) & wrap) < (1u << m)) cnt += hist[x];
-            pm = (double)cnt / (double)total;
-        }
-        double pw = pm * pm; pw = pw * pw; pw = pw * pw;               // p^8
-        for (unsigned L = 8; L <= 32; L *= 2) {
-            if (group_lengths & L) {
-                const double e = (1.0 / (double)L + (double)n) + ((double)m - (double)n) * pw;
-                if (!have || e < bestE) { have = true; bestE = e; bestM = m; bestL = L; }
-            }
-            pw = pw * pw;                                              // p^16, p^32
-        }
+    const uint32_t B = block_size ? block_size : ENEC_DEFAULT_BLOCK;
+    if (!block_ok(B)) return ENEC_E_BLOCK;
+    // only lengths the block size admits are candidates; 16 fits every block size and stands in if none is left
+    uint32_t lengths = 0;
+    for (unsigned L = 8; L <= 32; L *= 2)
+        if ((group_lengths & L) && group_fits_block(L, B)) lengths |= L;
+    if (!lengths) lengths = 16u;
+    Search r;
+    if (!centre_and_width(hist, exp_bits(dtype), r)) {          // no elements at all: (b, n) = (0, 1) and p = 1
+        r.b = 0; r.n = 1; r.total = 1;
+        r.at_most[0] = r.at_most[1] = 1;
     }
-    params->m = (uint8_t)bestM;
-    params->L = (uint8_t)bestL;
+    threshold_and_length(r, lengths);
+    *params = enec_params{(uint8_t)r.b, (uint8_t)r.n, (uint8_t)r.m, (uint8_t)r.L};
     return ENEC_OK;
 }
 
@@ -403,12 +471,16 @@ int enec_compress_sampled(const void *in, size_t n_elems, int dtype, uint32_t bl
     return ENEC_E_RANGE;   // not reached: the full width has no range error
 }
 
-int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
-                        size_t workspace_bytes, void *stream)
+}  // extern "C"
+
+namespace {
+
+// enec_compress_batch and enec_compress_batch_overlapped (aux != nullptr)
+int compress_batch(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
+                   size_t workspace_bytes, hipStream_t s, hipStream_t aux)
 {
     if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
     if (!items || !workspace || !aligned16(workspace)) return ENEC_E_ARG;
-    hipStream_t s = (hipStream_t)stream;
 
     // ---- every check that can be made on the host, before anything is enqueued -------------
     struct Prepared { enec_params prm; uint32_t B; uint32_t nb; };
@@ -441,7 +513,7 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
             }
         if (!todo.empty()) {
             std::vector<enec_params> found(todo.size());
-            int rc = enec_tune_batch(todo.data(), todo.size(), dtype, 1, found.data(), nullptr, workspace, workspace_bytes, stream);
+            int rc = enec_tune_batch(todo.data(), todo.size(), dtype, 1, found.data(), nullptr, workspace, workspace_bytes, s);
             if (rc != ENEC_OK) return rc;
             for (size_t j = 0; j < who.size(); ++j) prep[who[j]].prm = found[j];
         }
@@ -457,71 +529,98 @@ int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dty
         if (it.out_bytes && !device_accessible(it.out_bytes)) return ENEC_E_ARG;
     }
 
-    // ---- one launch per group of tensors that share (m, n - m, block size) ------------------
+    // ---- one launch per group of tensors that share (m, n - m, L, block size) ----------------
+    // Tensors of one data block need no scan state and no tickets; they get launches of their own
+    // (workgroup w codes tensor w), which go to the auxiliary stream, if there is one, and run beside
+    // the launches of the large tensors instead of in front of them.
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     std::vector<char> done(n_items, 0);
-    for (size_t i = 0; i < n_items; ++i) {
-        if (done[i]) continue;
-        if (prep[i].nb == 0) {
-            compress_empty_kernel<<<1, 64, 0, s>>>(static_cast<uint8_t *>(items[i].out), items[i].out_bytes,
-                                                   prep[i].B, prep[i].prm.b, prep[i].prm.n, prep[i].prm.m,
-                                                   (uint32_t)dtype, prep[i].prm.L);
-            done[i] = 1;
-            continue;
-        }
-        CompressArgs a;
-        a.ws_ctl = reinterpret_cast<uint32_t *>(ws + WS_CTL);
-        a.B = prep[i].B;
-        a.logB = ilog2(a.B);
-        a.n_items = 0;
-        a.total = 0;
-        size_t word = acc_words, acc = 0;   // scan words handed out to this launch (tags make reuse between launches safe)
-        for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
-            if (done[j] || prep[j].nb == 0 || prep[j].B != a.B || prep[j].prm.m != prep[i].prm.m ||
-                prep[j].prm.n != prep[i].prm.n || prep[j].prm.L != prep[i].prm.L)
+    AuxFork fork(s, aux);
+    for (int single = 1; single >= 0; --single) {
+        for (size_t i = 0; i < n_items; ++i) {
+            if (done[i]) continue;
+            if (prep[i].nb == 0) {
+                compress_empty_kernel<<<1, 64, 0, s>>>(static_cast<uint8_t *>(items[i].out), items[i].out_bytes,
+                                                       prep[i].B, prep[i].prm.b, prep[i].prm.n, prep[i].prm.m,
+                                                       (uint32_t)dtype, prep[i].prm.L);
+                done[i] = 1;
                 continue;
-            CompressItem &c = a.item[a.n_items++];
-            c.in = static_cast<const uint16_t *>(items[j].in);
-            c.out = static_cast<uint8_t *>(items[j].out);
-            c.out_bytes = items[j].out_bytes;
-            c.ws_acc = reinterpret_cast<uint64_t *>(ws + WS_STATE) + acc;
-            acc += ws_groups(prep[j].nb);
-            c.ws_group = reinterpret_cast<uint64_t *>(ws + WS_STATE) + word;
-            word += ws_groups(prep[j].nb);
-            c.ws_block = reinterpret_cast<uint64_t *>(ws + WS_STATE) + word;
-            word += prep[j].nb;
-            c.n_elems = items[j].n_elems;
-            c.payload_base = payload_base(items[j].n_elems, a.B, dtype);
-            c.tail_base = table_end(items[j].n_elems, a.B);
-            c.nb = prep[j].nb;
-            c.first = a.total;
-            c.b = prep[j].prm.b;
-            c.mode = subtract_mode(prep[j].prm.b, prep[j].prm.n, dtype);
-            a.total += c.nb;
-            done[j] = 1;
+            }
+            if (single && prep[i].nb != 1) continue;
+            CompressArgs a;
+            a.ws_ctl = single ? nullptr : reinterpret_cast<uint32_t *>(ws + WS_CTL);
+            a.B = prep[i].B;
+            a.logB = ilog2(a.B);
+            a.n_items = 0;
+            a.total = 0;
+            size_t word = acc_words, acc = 0;   // scan words handed out to this launch (tags make reuse between launches safe)
+            for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
+                if (done[j] || prep[j].nb == 0 || (single && prep[j].nb != 1) || prep[j].B != a.B ||
+                    prep[j].prm.m != prep[i].prm.m || prep[j].prm.n != prep[i].prm.n || prep[j].prm.L != prep[i].prm.L)
+                    continue;
+                CompressItem &c = a.item[a.n_items++];
+                c.in = static_cast<const uint16_t *>(items[j].in);
+                c.out = static_cast<uint8_t *>(items[j].out);
+                c.out_bytes = items[j].out_bytes;
+                c.ws_acc = reinterpret_cast<uint64_t *>(ws + WS_STATE) + acc;
+                acc += ws_groups(prep[j].nb);
+                c.ws_group = reinterpret_cast<uint64_t *>(ws + WS_STATE) + word;
+                word += ws_groups(prep[j].nb);
+                c.ws_block = reinterpret_cast<uint64_t *>(ws + WS_STATE) + word;
+                word += prep[j].nb;
+                c.n_elems = items[j].n_elems;
+                c.payload_base = payload_base(items[j].n_elems, a.B, dtype);
+                c.tail_base = table_end(items[j].n_elems, a.B);
+                c.nb = prep[j].nb;
+                c.first = a.total;
+                c.b = prep[j].prm.b;
+                c.mode = subtract_mode(prep[j].prm.b, prep[j].prm.n, dtype);
+                a.total += c.nb;
+                done[j] = 1;
+            }
+            CompressFn fn = pick_compress(prep[i].prm.m, prep[i].prm.n - prep[i].prm.m, dtype, prep[i].prm.L);
+            if (!fn) return ENEC_E_PARAMS;
+            const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
+            const size_t plane_bits = prep[i].prm.n + (dtype == ENEC_FP16 ? 3 : 0);
+            // two images of the packed part, and the sign/mantissa bytes of the block that waits to be stored
+            const size_t lds = 2 * ((size_t)a.B / (8 * prep[i].prm.L) + plane_bits * a.B / 8) +
+                               (compress_sm_in_lds(dtype, prep[i].prm.L == 8 ? 1 : prep[i].prm.L == 16 ? 2 : 4) ? a.B : 0);
+            const unsigned resident = resident_workgroups((const void *)fn, threads, lds);
+            if (resident == 0) return ENEC_E_HIP;
+            const unsigned grid = balanced_grid(a.total, resident);
+            a.ncls = grid < 8 ? grid : 8;
+            a.oneshot = grid == a.total ? 1u : 0u;
+            // The next ticket is drawn while the current block is worked on only if there are blocks for
+            // two rounds: with fewer, an early workgroup would take the block of one that starts a moment later.
+            a.lookahead = a.total >= 2 * grid ? 1u : 0u;
+            a.spin_limit = spin_limit();
+            hipStream_t where = s;
+            if (single && aux) {
+                if (!fork.fork()) { (void)hipGetLastError(); return ENEC_E_HIP; }
+                where = aux;
+            }
+            hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, where, a);
         }
-        CompressFn fn = pick_compress(prep[i].prm.m, prep[i].prm.n - prep[i].prm.m, dtype, prep[i].prm.L);
-        if (!fn) return ENEC_E_PARAMS;
-        const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
-        const size_t plane_bits = prep[i].prm.n + (dtype == ENEC_FP16 ? 3 : 0);
-        // two images of the packed part, and the sign/mantissa bytes of the block that waits to be stored
-        const size_t lds = 2 * ((size_t)a.B / (8 * prep[i].prm.L) + plane_bits * a.B / 8) +
-                           (compress_sm_in_lds(dtype, prep[i].prm.L == 8 ? 1 : prep[i].prm.L == 16 ? 2 : 4) ? a.B : 0);
-        const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_COMPRESS_WGS_PER_CU");
-        if (resident == 0) return ENEC_E_HIP;
-        const unsigned grid = a.total < resident ? a.total : resident;
-        a.ncls = grid < 8 ? grid : 8;
-        // The next ticket is drawn while the current block is worked on only if there are blocks for
-        // two rounds: with fewer, an early workgroup would take the block of one that starts a moment later.
-        a.lookahead = a.total >= 2 * grid ? 1u : 0u;
-        a.spin_limit = SPIN_LIMIT;
-        if (const char *e = std::getenv("ENEC_SPIN_LIMIT")) {       // test aid: make a scan that cannot progress give up early
-            const long v = std::atol(e);
-            if (v > 0 && v < (long)SPIN_LIMIT) a.spin_limit = (uint32_t)v;
-        }
-        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
     }
+    if (!fork.join()) { (void)hipGetLastError(); return ENEC_E_HIP; }
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    return compress_batch(items, n_items, dtype, workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+}
+
+int enec_compress_batch_overlapped(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
+                                   size_t workspace_bytes, void *stream, void *aux_stream)
+{
+    if (!aux_stream || aux_stream == stream) return ENEC_E_ARG;
+    return compress_batch(items, n_items, dtype, workspace, workspace_bytes, (hipStream_t)stream, (hipStream_t)aux_stream);
 }
 
 int enec_compress(const void *in, size_t n_elems, int dtype, uint32_t block_size,
@@ -636,11 +735,7 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
     a.tail_base = a.tuples_at + tuple_table_bytes(n_elems, B);
     a.payload_base = payload_base(n_elems, B, dtype) + tuple_table_bytes(n_elems, B);
     a.nb = (uint32_t)nb; a.B = B; a.logB = ilog2(B);
-    a.spin_limit = SPIN_LIMIT;
-    if (const char *e = std::getenv("ENEC_SPIN_LIMIT")) {
-        const long v = std::atol(e);
-        if (v > 0 && v < (long)SPIN_LIMIT) a.spin_limit = (uint32_t)v;
-    }
+    a.spin_limit = spin_limit();
     PbCompressFn fn = pick_compress_per_block(dtype, L);
     if (!fn) return ENEC_E_DTYPE;
     const unsigned part_threads = B / 64 < 64 ? 64 : B / 64;
@@ -650,10 +745,6 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
     // several blocks per workgroup (one ticket for all of them) when there are enough blocks; the few
     // blocks left over get a launch with one block per workgroup
     unsigned per_wg = 1024 / part_threads < (unsigned)PB_MAX_PARTS ? 1024 / part_threads : (unsigned)PB_MAX_PARTS;
-    if (const char *e = std::getenv("ENEC_PER_BLOCK_PARTS")) {        // tuning aid
-        const unsigned v = (unsigned)std::atoi(e);
-        if (v >= 1 && v <= per_wg) per_wg = v;
-    }
     if (nb < 64 * (size_t)per_wg) per_wg = 1;
     if (per_wg * part_lds > 65536 &&
         hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(per_wg * part_lds)) != hipSuccess) {
@@ -675,14 +766,21 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 
-int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, void *stream)
+}  // extern "C"
+
+namespace {
+
+// enec_decompress_batch and enec_decompress_batch_overlapped (aux != nullptr)
+int decompress_batch(const enec_decompress_item *items, size_t n_items, hipStream_t s, hipStream_t aux)
 {
     if (!items) return ENEC_E_ARG;
     std::vector<Header> hdr(n_items);
     for (size_t i = 0; i < n_items; ++i) {
         const enec_decompress_item &it = items[i];
-        if (!it.in || !it.host_header || (!it.out && it.n_elems) || !aligned16(it.in) || !aligned16(it.out))
+        if (!it.in || !it.host_header || (!it.out && it.n_elems) || !aligned16(it.in) || !aligned16(it.out) ||
+            ((uintptr_t)it.status & 3))
             return ENEC_E_ARG;
+        if (it.status && !device_accessible(it.status)) return ENEC_E_ARG;
         Header &h = hdr[i];
         int rc = parse_header(it.host_header, &h);
         if (rc != ENEC_OK) return rc;
@@ -699,72 +797,101 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
         }
     }
     std::vector<char> done(n_items, 0);
-    for (size_t i = 0; i < n_items; ++i) {
-        if (done[i]) continue;
-        if (hdr[i].nb == 0) { done[i] = 1; continue; }
-        if (hdr[i].per_block) {                      // its tuples are in the stream: a launch of its own
-            const Header &h = hdr[i];
-            PbDecompressArgs a;
-            a.in = static_cast<const uint8_t *>(items[i].in);
-            a.out = items[i].out;
-            a.n_elems = items[i].n_elems;
-            a.tuples_at = table_end(a.n_elems, h.B);
-            a.tail_base = a.tuples_at + tuple_table_bytes(a.n_elems, h.B);
-            a.payload_base = payload_base(a.n_elems, h.B, h.dtype) + tuple_table_bytes(a.n_elems, h.B);
-            a.payload_bytes = h.total - a.payload_base;
-            a.nb = h.nb; a.B = h.B; a.logB = ilog2(h.B);
-            std::memcpy(a.hdr, items[i].host_header, sizeof a.hdr);
-            PbDecompressFn fn = pick_decompress_per_block(h.dtype, h.prm.L);
-            if (!fn) return ENEC_E_FORMAT;
-            const unsigned threads = h.B / 64 < 64 ? 64 : h.B / 64;
-            const size_t lds = (size_t)h.B / (8 * h.prm.L) + h.B + 16;     // the packed part of the widest block
-            hipLaunchKernelGGL(fn, dim3(h.nb), dim3(threads), lds, (hipStream_t)stream, a);
-            done[i] = 1;
-            continue;
-        }
-        DecompressArgs a;
-        a.B = hdr[i].B;
-        a.logB = ilog2(a.B);
-        a.n_items = 0;
-        a.total = 0;
-        for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
-            const Header &h = hdr[j];
-            if (done[j] || h.nb == 0 || h.per_block || h.B != a.B || h.prm.m != hdr[i].prm.m || h.prm.n != hdr[i].prm.n ||
-                h.dtype != hdr[i].dtype || h.prm.L != hdr[i].prm.L)
+    AuxFork fork(s, aux);
+    // launches whose tensors all have one data block go to the auxiliary stream, if there is one, and
+    // run beside the launches of the large tensors
+    for (int single = 1; single >= 0; --single) {
+        for (size_t i = 0; i < n_items; ++i) {
+            if (done[i]) continue;
+            if (hdr[i].nb == 0) { done[i] = 1; continue; }
+            if (single && (hdr[i].nb != 1 || hdr[i].per_block)) continue;
+            if (hdr[i].per_block) {                      // its tuples are in the stream: a launch of its own
+                const Header &h = hdr[i];
+                PbDecompressArgs a;
+                a.in = static_cast<const uint8_t *>(items[i].in);
+                a.out = items[i].out;
+                a.n_elems = items[i].n_elems;
+                a.tuples_at = table_end(a.n_elems, h.B);
+                a.tail_base = a.tuples_at + tuple_table_bytes(a.n_elems, h.B);
+                a.payload_base = payload_base(a.n_elems, h.B, h.dtype) + tuple_table_bytes(a.n_elems, h.B);
+                a.payload_bytes = h.total - a.payload_base;
+                a.nb = h.nb; a.B = h.B; a.logB = ilog2(h.B);
+                a.status = items[i].status;
+                std::memcpy(a.hdr, items[i].host_header, sizeof a.hdr);
+                PbDecompressFn fn = pick_decompress_per_block(h.dtype, h.prm.L);
+                if (!fn) return ENEC_E_FORMAT;
+                const unsigned threads = h.B / 64 < 64 ? 64 : h.B / 64;
+                const size_t lds = (size_t)h.B / (8 * h.prm.L) + h.B + 16;     // the packed part of the widest block
+                hipLaunchKernelGGL(fn, dim3(h.nb), dim3(threads), lds, s, a);
+                done[i] = 1;
                 continue;
-            DecompressItem &c = a.item[a.n_items++];
-            c.in = static_cast<const uint8_t *>(items[j].in);
-            c.out = static_cast<uint16_t *>(items[j].out);
-            c.n_elems = items[j].n_elems;
-            c.payload_base = payload_base(items[j].n_elems, h.B, h.dtype);
-            c.payload_bytes = h.total - c.payload_base;
-            c.tail_base = table_end(items[j].n_elems, h.B);
-            c.nb = h.nb;
-            c.first = a.total;
-            c.b = h.prm.b;
-            c.mode = subtract_mode(h.prm.b, h.prm.n, h.dtype) == 0 ? 0u : 1u;
-            std::memcpy(c.hdr, items[j].host_header, sizeof c.hdr);
-            a.total += c.nb;
-            done[j] = 1;
+            }
+            DecompressArgs a;
+            a.B = hdr[i].B;
+            a.logB = ilog2(a.B);
+            a.n_items = 0;
+            a.total = 0;
+            for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
+                const Header &h = hdr[j];
+                if (done[j] || h.nb == 0 || h.per_block || (single && h.nb != 1) || h.B != a.B || h.prm.m != hdr[i].prm.m ||
+                    h.prm.n != hdr[i].prm.n || h.dtype != hdr[i].dtype || h.prm.L != hdr[i].prm.L)
+                    continue;
+                DecompressItem &c = a.item[a.n_items++];
+                c.in = static_cast<const uint8_t *>(items[j].in);
+                c.out = static_cast<uint16_t *>(items[j].out);
+                c.n_elems = items[j].n_elems;
+                c.payload_base = payload_base(items[j].n_elems, h.B, h.dtype);
+                c.payload_bytes = h.total - c.payload_base;
+                c.tail_base = table_end(items[j].n_elems, h.B);
+                c.nb = h.nb;
+                c.first = a.total;
+                c.b = h.prm.b;
+                c.mode = subtract_mode(h.prm.b, h.prm.n, h.dtype) == 0 ? 0u : 1u;
+                c.status = items[j].status;
+                std::memcpy(c.hdr, items[j].host_header, sizeof c.hdr);
+                a.total += c.nb;
+                done[j] = 1;
+            }
+            DecompressFn fn = pick_decompress(hdr[i].prm.m, hdr[i].prm.n - hdr[i].prm.m, hdr[i].dtype, hdr[i].prm.L);
+            if (!fn) return ENEC_E_FORMAT;
+            const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
+            const size_t plane_bits = hdr[i].prm.n + (hdr[i].dtype == ENEC_FP16 ? 3 : 0);
+            const size_t lds = 2 * ((size_t)a.B / (8 * hdr[i].prm.L) + plane_bits * a.B / 8);   // two images of the packed part
+            const unsigned resident = resident_workgroups((const void *)fn, threads, lds);
+            if (resident == 0) return ENEC_E_HIP;
+            hipStream_t where = s;
+            if (single && aux) {
+                if (!fork.fork()) { (void)hipGetLastError(); return ENEC_E_HIP; }
+                where = aux;
+            }
+            hipLaunchKernelGGL(fn, dim3(balanced_grid(a.total, resident)), dim3(threads), lds, where, a);
         }
-        DecompressFn fn = pick_decompress(hdr[i].prm.m, hdr[i].prm.n - hdr[i].prm.m, hdr[i].dtype, hdr[i].prm.L);
-        if (!fn) return ENEC_E_FORMAT;
-        const unsigned threads = a.B / 64 < 64 ? 64 : a.B / 64;
-        const size_t plane_bits = hdr[i].prm.n + (hdr[i].dtype == ENEC_FP16 ? 3 : 0);
-        const size_t lds = 2 * ((size_t)a.B / (8 * hdr[i].prm.L) + plane_bits * a.B / 8);   // two images of the packed part
-        const unsigned resident = resident_workgroups((const void *)fn, threads, lds, "ENEC_DECOMPRESS_WGS_PER_CU");
-        if (resident == 0) return ENEC_E_HIP;
-        const unsigned grid = a.total < resident ? a.total : resident;
-        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, (hipStream_t)stream, a);
     }
+    if (!fork.join()) { (void)hipGetLastError(); return ENEC_E_HIP; }
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 
+}  // namespace
+
+extern "C" {
+
+int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, void *stream)
+{
+    return decompress_batch(items, n_items, (hipStream_t)stream, nullptr);
+}
+
+int enec_decompress_batch_overlapped(const enec_decompress_item *items, size_t n_items, void *stream, void *aux_stream)
+{
+    if (!aux_stream || aux_stream == stream) return ENEC_E_ARG;
+    return decompress_batch(items, n_items, (hipStream_t)stream, (hipStream_t)aux_stream);
+}
+
 int enec_decompress_with_header(const void *in, size_t in_bytes, const void *host_header, void *out,
-                                size_t n_elems, void *stream)
+                                size_t n_elems, uint32_t *status, void *stream)
 {
     enec_decompress_item it;
     it.in = in; it.in_bytes = in_bytes; it.host_header = host_header; it.out = out; it.n_elems = n_elems;
+    it.status = status;
     return enec_decompress_batch(&it, 1, stream);
 }
 
@@ -779,7 +906,7 @@ int enec_decompress(const void *in, size_t in_bytes, void *out, size_t n_elems, 
         (void)hipGetLastError();
         return ENEC_E_HIP;
     }
-    return enec_decompress_with_header(in, in_bytes, hdr, out, n_elems, stream);
+    return enec_decompress_with_header(in, in_bytes, hdr, out, n_elems, nullptr, stream);
 }
 
 int enec_stream_info(const void *host_header, enec_params *params, uint64_t *n_elems,

@@ -56,6 +56,7 @@ struct PbDecompressArgs {
     uint64_t tuples_at, tail_base, payload_base, payload_bytes;
     uint32_t nb, B, logB;
     uint32_t hdr[11];           // the header the launch was configured from
+    uint32_t *status;           // device-accessible or null: set to 7 (format error) when a block is left undecoded
 };
 
 using PbCompressFn = void (*)(const PbCompressArgs);

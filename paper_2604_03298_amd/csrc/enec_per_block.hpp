@@ -775,12 +775,16 @@ __global__ void __launch_bounds__(512) decompress_per_block_kernel(const PbDecom
     const uint32_t b = tup & 0xFFu, n = (tup >> 8) & 0xFFu, m = (tup >> 16) & 0xFFu;
     const uint64_t *table = reinterpret_cast<const uint64_t *>(p.in + 64);
     const uint64_t t0 = table[k], t1 = table[k + 1];
-    if (!same || n < 1u || n > E || m > n || b >= (1u << E)) return;
+    // a block that is skipped (damaged header, tuple or table entry) leaves its part of the output
+    // untouched: the caller is told through the status word
     const uint32_t a = n - m, lm = m + (DT == DT_FP16 ? 3u : 0u);
     const uint32_t fixed = B + mask_bytes + ((lm * B) >> 3);
     const uint64_t sz = t1 - t0;
-    if (sz < fixed || sz > fixed + (uint32_t)LPG * a * ((B >> 3) >> LOG_LPG) + 15u || ((sz | t0) & 15u) || t0 > p.payload_bytes || sz > p.payload_bytes - t0)
-        return;                                          // a damaged table entry: the block is skipped
+    if (!same || n < 1u || n > E || m > n || b >= (1u << E) ||
+        sz < fixed || sz > fixed + (uint32_t)LPG * a * ((B >> 3) >> LOG_LPG) + 15u || ((sz | t0) & 15u) || t0 > p.payload_bytes || sz > p.payload_bytes - t0) {
+        if (tid == 0 && p.status) *p.status = 7u;
+        return;
+    }
     const uint8_t *src = p.in + p.payload_base + t0;
     const uint32_t nvec = ((uint32_t)sz - B) >> 4;
     for (uint32_t v = tid; v < nvec; v += blockDim.x)

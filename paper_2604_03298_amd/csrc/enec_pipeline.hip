@@ -152,6 +152,7 @@ int enec_pipeline_prefetch_from_host(enec_pipeline *p, uint32_t slot, const enec
         d.host_header = items[i].host_stream;           // the stream's first 64 bytes, read here on the host
         d.out = items[i].out;
         d.n_elems = items[i].n_elems;
+        d.status = items[i].status;
         const int rc = enec_decompress_batch(&d, 1, p->dec);
         if (p->trace && !mark(p, p->dec)) return ENEC_E_HIP;
         // also after a refused stream: the half is free again as far as this pipeline is concerned

@@ -26,7 +26,7 @@ EXPORTS = [
     "enec_tune_sampled", "enec_compress_sampled", "enec_compress_bound_per_block", "enec_compress_per_block",
     "enec_tune_batch", "enec_compress_static", "enec_pipeline_create", "enec_pipeline_destroy",
     "enec_pipeline_prefetch", "enec_pipeline_prefetch_from_host", "enec_pipeline_acquire", "enec_pipeline_release",
-    "enec_pipeline_trace",
+    "enec_pipeline_trace", "enec_compress_batch_overlapped", "enec_decompress_batch_overlapped",
 ]
 
 
@@ -49,12 +49,12 @@ class CompressItem(C.Structure):
 
 class DecompressItem(C.Structure):
     _fields_ = [("src", C.c_void_p), ("in_bytes", C.c_size_t), ("host_header", C.c_void_p),
-                ("out", C.c_void_p), ("n_elems", C.c_size_t)]
+                ("out", C.c_void_p), ("n_elems", C.c_size_t), ("status", C.c_void_p)]
 
 
 class OffloadItem(C.Structure):
     _fields_ = [("host_stream", C.c_void_p), ("stream_bytes", C.c_size_t), ("out", C.c_void_p),
-                ("n_elems", C.c_size_t)]
+                ("n_elems", C.c_size_t), ("status", C.c_void_p)]
 
 
 class EnecError(RuntimeError):
@@ -95,7 +95,7 @@ def lib():
         L.enec_decompress.restype = C.c_int
         L.enec_decompress.argtypes = [vp, sz, vp, sz, vp]
         L.enec_decompress_with_header.restype = C.c_int
-        L.enec_decompress_with_header.argtypes = [vp, sz, vp, vp, sz, vp]
+        L.enec_decompress_with_header.argtypes = [vp, sz, vp, vp, sz, vp, vp]
         L.enec_tune.restype = C.c_int
         L.enec_tune.argtypes = [vp, sz, C.c_int, C.POINTER(Params), u64p, vp, sz, vp]
         L.enec_compress_bound_per_block.restype = sz
@@ -112,7 +112,7 @@ def lib():
         L.enec_tune_histogram.restype = C.c_int
         L.enec_tune_histogram.argtypes = [u64p, C.c_int, C.POINTER(Params)]
         L.enec_tune_histogram_groups.restype = C.c_int
-        L.enec_tune_histogram_groups.argtypes = [u64p, C.c_int, u32, C.POINTER(Params)]
+        L.enec_tune_histogram_groups.argtypes = [u64p, C.c_int, u32, u32, C.POINTER(Params)]
         L.enec_stream_info.restype = C.c_int
         L.enec_stream_info.argtypes = [vp, C.POINTER(Params), u64p, C.POINTER(u32), u64p,
                                        C.POINTER(C.c_int), C.POINTER(u32)]
@@ -122,6 +122,10 @@ def lib():
         L.enec_compress_batch.argtypes = [C.POINTER(CompressItem), sz, C.c_int, vp, sz, vp]
         L.enec_decompress_batch.restype = C.c_int
         L.enec_decompress_batch.argtypes = [C.POINTER(DecompressItem), sz, vp]
+        L.enec_compress_batch_overlapped.restype = C.c_int
+        L.enec_compress_batch_overlapped.argtypes = [C.POINTER(CompressItem), sz, C.c_int, vp, sz, vp, vp]
+        L.enec_decompress_batch_overlapped.restype = C.c_int
+        L.enec_decompress_batch_overlapped.argtypes = [C.POINTER(DecompressItem), sz, vp, vp]
         L.enec_pipeline_create.restype = C.c_int
         L.enec_pipeline_create.argtypes = [C.POINTER(vp), u32, vp, vp, vp, sz, C.c_int]
         L.enec_pipeline_destroy.restype = None
@@ -187,8 +191,9 @@ def workspace_bytes(n_elems: int, block_size: int = 0) -> int:
     return int(lib().enec_workspace_bytes(n_elems, block_size))
 
 
-def tune_histogram(hist, dtype: int = BF16, lengths=None) -> tuple:
-    """(b, n, m, L) from a 256-bin exponent histogram; L = 16 unless candidate group lengths are given."""
+def tune_histogram(hist, dtype: int = BF16, lengths=None, block_size: int = 0) -> tuple:
+    """(b, n, m, L) from a 256-bin exponent histogram; L = 16 unless candidate group lengths are given (the
+    library leaves out those that block_size, 0 = 16384, does not admit)."""
     h = np.ascontiguousarray(hist, dtype=np.uint64)
     assert h.size == 256
     p = Params()
@@ -199,7 +204,8 @@ def tune_histogram(hist, dtype: int = BF16, lengths=None) -> tuple:
         mask = 0
         for v in lengths:
             mask |= int(v)
-        _check(lib().enec_tune_histogram_groups(h.ctypes.data_as(C.POINTER(C.c_uint64)), dtype, mask, C.byref(p)),
+        _check(lib().enec_tune_histogram_groups(h.ctypes.data_as(C.POINTER(C.c_uint64)), dtype, mask, block_size,
+                                                C.byref(p)),
                "enec_tune_histogram_groups")
     return p.astuple()
 
@@ -288,19 +294,22 @@ def decompress(stream_buf, out, n_elems: int | None = None, stream=None) -> int:
                                      C.c_void_p(out.data_ptr()), n, _stream_handle(stream)))
 
 
-def decompress_with_header(stream_buf, host_header, out, n_elems: int | None = None, stream=None) -> int:
+def decompress_with_header(stream_buf, host_header, out, n_elems: int | None = None, stream=None, status=None) -> int:
+    """status: None, or a device / pinned-host int32 tensor holding 0; the kernel stores E_FORMAT there if it
+    leaves a data block undecoded."""
     n = out.numel() if n_elems is None else n_elems
     hdr = np.frombuffer(bytes(host_header[:HEADER_BYTES]), dtype=np.uint8).copy()
     return int(lib().enec_decompress_with_header(
         C.c_void_p(stream_buf.data_ptr()), stream_buf.numel() * stream_buf.element_size(),
-        hdr.ctypes.data, C.c_void_p(out.data_ptr()), n, _stream_handle(stream)))
+        hdr.ctypes.data, C.c_void_p(out.data_ptr()), n,
+        C.c_void_p(status.data_ptr()) if status is not None else None, _stream_handle(stream)))
 
 
 def compress_batch(srcs, params, outs, workspace, block_sizes=None, out_bytes=None, stream=None,
-                   dtype: int | None = None) -> int:
-    """Enqueues enec_compress_batch.  srcs / outs: lists of device tensors (one element format for
-    all, see dtype_of); params: list of (b, n, m, L) or None per tensor; out_bytes: None or a list
-    of one-u64 device-accessible tensors."""
+                   dtype: int | None = None, aux_stream=None) -> int:
+    """Enqueues enec_compress_batch (with aux_stream: enec_compress_batch_overlapped).  srcs / outs: lists of
+    device tensors (one element format for all, see dtype_of); params: list of (b, n, m, L) or None per
+    tensor; out_bytes: None or a list of one-u64 device-accessible tensors."""
     n = len(srcs)
     dt = dtype_of(srcs[0], dtype) if n else BF16
     keep = [_params(p) if p is not None else None for p in params]
@@ -313,14 +322,18 @@ def compress_batch(srcs, params, outs, workspace, block_sizes=None, out_bytes=No
         items[i].out = outs[i].data_ptr()
         items[i].out_capacity = outs[i].numel() * outs[i].element_size()
         items[i].out_bytes = out_bytes[i].data_ptr() if out_bytes is not None else None
+    if aux_stream is not None:
+        return int(lib().enec_compress_batch_overlapped(items, n, dt, C.c_void_p(workspace.data_ptr()),
+                                                        workspace.numel() * workspace.element_size(),
+                                                        _stream_handle(stream), C.c_void_p(aux_stream.cuda_stream)))
     return int(lib().enec_compress_batch(items, n, dt, C.c_void_p(workspace.data_ptr()),
                                          workspace.numel() * workspace.element_size(),
                                          _stream_handle(stream)))
 
 
-def make_decompress_items(stream_bufs, host_headers, outs):
+def make_decompress_items(stream_bufs, host_headers, outs, statuses=None):
     """Builds the item array for decompress_batch once (it can be reused for repeated calls).
-    Returns (items, keepalive)."""
+    statuses: None or one device-accessible int32 tensor (holding 0) per stream.  Returns (items, keepalive)."""
     n = len(stream_bufs)
     hdrs = [np.frombuffer(bytes(h[:HEADER_BYTES]), dtype=np.uint8).copy() for h in host_headers]
     items = (DecompressItem * n)()
@@ -330,21 +343,25 @@ def make_decompress_items(stream_bufs, host_headers, outs):
         items[i].host_header = hdrs[i].ctypes.data
         items[i].out = outs[i].data_ptr()
         items[i].n_elems = outs[i].numel()
+        items[i].status = statuses[i].data_ptr() if statuses is not None else None
     return items, hdrs
 
 
-def decompress_batch(stream_bufs, host_headers, outs, stream=None, items=None) -> int:
+def decompress_batch(stream_bufs, host_headers, outs, stream=None, items=None, aux_stream=None, statuses=None) -> int:
     keep = None
     if items is None:
-        items, keep = make_decompress_items(stream_bufs, host_headers, outs)
+        items, keep = make_decompress_items(stream_bufs, host_headers, outs, statuses)
+    if aux_stream is not None:
+        return int(lib().enec_decompress_batch_overlapped(items, len(items), _stream_handle(stream),
+                                                          C.c_void_p(aux_stream.cuda_stream)))
     return int(lib().enec_decompress_batch(items, len(items), _stream_handle(stream)))
 
 
 def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int | None = None, lengths=None,
          block_size: int = 0):
     """-> (b, n, m, L) [, histogram]; synchronous.  lengths: candidate group lengths for Eq. 4's joint
-    search of (m, L), e.g. (8, 16, 32); None keeps the paper's L = 16.  Lengths that the block size the
-    tensor will be compressed with does not admit (128 L <= block size <= 2048 L) are left out."""
+    search of (m, L), e.g. (8, 16, 32); None keeps the paper's L = 16.  block_size: the data-block size the
+    tensor will be compressed with (0 = the default for its length)."""
     p = Params()
     hist = np.zeros(256, dtype=np.uint64)
     dt = dtype_of(src, dtype)
@@ -353,10 +370,8 @@ def tune(src, workspace, stream=None, want_histogram: bool = False, dtype: int |
                            C.c_void_p(workspace.data_ptr()),
                            workspace.numel() * workspace.element_size(), _stream_handle(stream)),
            "enec_tune")
-    if lengths is not None:
-        B = block_size or default_block_size(src.numel())
-        lengths = [v for v in lengths if 128 * v <= B <= 2048 * v] or [16]
-    prm = p.astuple() if lengths is None else tune_histogram(hist, dt, lengths)
+    prm = p.astuple() if lengths is None else tune_histogram(hist, dt, lengths,
+                                                             block_size or default_block_size(src.numel()))
     return (prm, hist) if want_histogram else prm
 
 
@@ -442,6 +457,7 @@ class Pipeline:
             items[i].stream_bytes = host_streams[i].numel()
             items[i].out = outs[i].data_ptr()
             items[i].n_elems = outs[i].numel()
+            items[i].status = None
         return int(lib().enec_pipeline_prefetch_from_host(self._h, slot, items, n))
 
     def acquire(self, slot: int, consumer_stream=None) -> int:

@@ -176,22 +176,37 @@ def test_workspace_is_reusable_and_results_are_deterministic(gpu, oracle):
         assert rc == 0 and nbytes == sb.size and np.array_equal(out[:nbytes], sb), f"run {i}"
         rc, out, nbytes, _ = gpu.compress(small, ps, 16384, src=src_s)
         assert rc == 0 and nbytes == ss.size and np.array_equal(out[:nbytes], ss), f"run {i}"
-    # the ticket counter of every class has come back to the base the next call will read
+    # every class's control word is [tag of the last call | ticket 0], the same tag everywhere; nobody gave up
     ws_host = gpu.ws.cpu().numpy()
-    ctl = ws_host[:1024].view(np.uint32).reshape(8, 32)
-    assert (ctl[:, 0] == ctl[:, 1]).all()
-    assert len(set(ctl[:, 2].tolist())) == 1
+    ctl = ws_host[:1024].view(np.uint64).reshape(8, 16)
+    assert (ctl[:, 0] & np.uint64(0xFFFFFF) == 0).all()
+    assert len(set(ctl[:, 0].tolist())) == 1 and int(ctl[0, 0]) >> 24 >= 12
+    assert ctl[0, 1] == 0
     # every group accumulator (the first ninth of the state words) is back to zero
     words = ws_host[STATE_AT:STATE_AT + (ws_host.size - STATE_AT) // 8 * 8].view(np.uint64)
     assert (words[:words.size // 9] == 0).all()
 
 
+def _test_library_compress(enec, src, n, params, out, ws, size):
+    """enec_compress of libenec_test.so (the library built with ENEC_TEST_HOOKS: it reads ENEC_SPIN_LIMIT)."""
+    import ctypes as C
+    import os
+    path = os.path.join(os.path.dirname(enec.LIB_PATH), "libenec_test.so")
+    assert os.path.exists(path), "build libenec_test.so with `python -m paper_2604_03298_amd.build`"
+    L = C.CDLL(path)
+    L.enec_compress.restype = C.c_int
+    L.enec_compress.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_uint32, C.POINTER(enec.Params), C.c_void_p,
+                                C.c_size_t, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    return L.enec_compress(src.data_ptr(), n, 0, 0, C.byref(enec.Params(*params)), out.data_ptr(), out.numel(),
+                           size.data_ptr(), ws.data_ptr(), ws.numel(), None)
+
+
 def test_dirty_workspace_ends_in_a_status_not_in_a_hang(gpu, oracle, monkeypatch):
     """A workspace left dirty (a process died in the middle of a call) must not hang the scan: the
     waits are bounded and the stream header then says ENEC_E_HIP.  The bound is shortened through
-    the library's test aid so that the kernel gives up after microseconds."""
+    the test build of the library so that the kernel gives up after microseconds."""
     torch, enec = gpu.torch, gpu.enec
-    w = W.gaussian(40 * 16384, 0.02, 83)
+    w = W.gaussian(400 * 16384, 0.02, 83)               # more than 256 blocks: the scan goes through group words
     p = oracle.tune(w)
     src = gpu.to_dev(w)
     ws = enec.new_workspace(w.size)
@@ -199,8 +214,9 @@ def test_dirty_workspace_ends_in_a_status_not_in_a_hang(gpu, oracle, monkeypatch
     words[:words.numel() // 9] = 100 << 48            # accumulators claim 100 blocks too many: no group ever completes
     out = torch.zeros(enec.compress_bound(w.size), dtype=torch.uint8, device="cuda")
     size = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
     monkeypatch.setenv("ENEC_SPIN_LIMIT", "200")
-    assert enec.compress(src, p, out, ws, out_bytes=size) == 0
+    assert _test_library_compress(enec, src, w.size, p, out, ws, size) == 0
     torch.cuda.synchronize()
     monkeypatch.delenv("ENEC_SPIN_LIMIT")
     info = enec.stream_info(out[:64].cpu().numpy())
@@ -210,6 +226,43 @@ def test_dirty_workspace_ends_in_a_status_not_in_a_hang(gpu, oracle, monkeypatch
     torch.cuda.synchronize()
     s_o = oracle.compress(w, p, 16384)[1]
     assert int(size.item()) == s_o.size and np.array_equal(out[:s_o.size].cpu().numpy(), s_o)
+
+
+def test_a_wait_given_up_anywhere_shows_in_the_header(gpu, oracle, monkeypatch):
+    """With a bound of one poll, blocks in the middle of a tensor give up on predecessors that publish a moment
+    later, while the last block may find everything in place.  Whoever gives up leaves a mark that the writer of
+    the header sees: a run ends either with status 0 and the oracle's stream, or with ENEC_E_HIP and size 0,
+    never with status 0 and a misplaced payload.  (Every kernel exits normally; nothing hangs or faults.)"""
+    torch, enec = gpu.torch, gpu.enec
+    w = W.gaussian(2000 * 16384 + 77, 0.02, 84)
+    p = oracle.tune(w)
+    s_o = oracle.compress(w, p, 16384)[1]
+    ref = torch.from_numpy(s_o).cuda()
+    src = gpu.to_dev(w)
+    ws = enec.new_workspace(w.size)
+    out = torch.zeros(enec.compress_bound(w.size), dtype=torch.uint8, device="cuda")
+    size = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+    monkeypatch.setenv("ENEC_SPIN_LIMIT", "1")
+    outcomes = []
+    for _ in range(8):
+        out.zero_()
+        assert _test_library_compress(enec, src, w.size, p, out, ws, size) == 0
+        torch.cuda.synchronize()
+        info = enec.stream_info(out[:64].cpu().numpy())
+        if info["status"] == 0:
+            assert int(size.item()) == s_o.size and torch.equal(out[:s_o.size], ref)
+        else:
+            assert info["status"] == enec.E_HIP and info["total_bytes"] == 0 and int(size.item()) == 0
+            enec.workspace_init(ws)        # a call that gave up may leave accumulators behind
+            torch.cuda.synchronize()
+        outcomes.append(info["status"])
+    monkeypatch.delenv("ENEC_SPIN_LIMIT")
+    # and the ordinary library on the same workspace afterwards
+    enec.workspace_init(ws)
+    assert enec.compress(src, p, out, ws, out_bytes=size) == 0
+    torch.cuda.synchronize()
+    assert int(size.item()) == s_o.size and torch.equal(out[:s_o.size], ref), outcomes
 
 
 def test_back_to_back_calls_without_sync(gpu, oracle):
@@ -403,13 +456,21 @@ def test_damaged_offset_table_skips_blocks_and_stays_in_bounds(gpu, oracle):
         else:
             t[k + 1] = t[k] + np.uint64(4 * B)
         damaged[how] = (k, t)
+    # the undamaged stream leaves the status word alone (device memory and pinned host memory)
+    for status in (torch.zeros(1, dtype=torch.int32, device="cuda"), torch.zeros(1, dtype=torch.int32).pin_memory()):
+        out = torch.full((w.size,), 0x5A5A, dtype=torch.int16, device="cuda")
+        assert enec.decompress_with_header(torch.from_numpy(s).cuda(), s[:64].tobytes(), out, status=status) == 0
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0 and np.array_equal(out.cpu().numpy().view(np.uint16), w)
     for how, (k, t) in damaged.items():
         bad = s.copy()
         bad[64:64 + 8 * (nb + 1)] = t.view(np.uint8)
         buf = torch.from_numpy(bad).cuda()
         out = torch.full((w.size + 64,), 0x5A5A, dtype=torch.int16, device="cuda")
-        assert enec.decompress_with_header(buf, bad[:64].tobytes(), out, n_elems=w.size) == 0
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        assert enec.decompress_with_header(buf, bad[:64].tobytes(), out, n_elems=w.size, status=status) == 0
         torch.cuda.synchronize()
+        assert int(status.item()) == enec.E_FORMAT, how          # the caller is told that blocks were skipped
         got = out.cpu().numpy().view(np.uint16)
         assert (got[w.size:] == 0x5A5A).all(), how
         # entry k starts block k and ends block k - 1; entry k + 1 ends block k and starts block k + 1
@@ -499,3 +560,52 @@ def test_tensor_beyond_4_gib_sampled_against_the_oracle(gpu, oracle):
         ob = oracle.payload_base(w.size, B)
         got = out[base + int(table[k0]):base + int(table[k0 + cnt])].cpu().numpy()
         assert got.size == s.size - ob and np.array_equal(got, s[ob:]), k0
+
+
+def test_overlapped_batches_with_an_auxiliary_stream(gpu, oracle):
+    """A layer's tiny tensors (one data block each, tuples of their own) are launched on the caller's second
+    stream, beside the launch of the matrices: same streams as the oracle's, same round trip, also when the
+    calls are repeated back to back without synchronisation, and also when the batch has only tiny tensors or none."""
+    torch, enec = gpu.torch, gpu.enec
+    tensors = [W.layer_matrix(512, 1376, 24), W.norm_vector(4096, 27), W.layer_matrix(1376, 512, 26),
+               W.norm_vector(4096, 28), W.gaussian(3000, 0.5, 29), W.gaussian(16384, 0.02, 30)]
+    params = [oracle.tune(t) for t in tensors]
+    assert len({p[:3] for p in params}) >= 3
+    refs = [oracle.compress(t, p, oracle.default_block(t.size))[1] for t, p in zip(tensors, params)]
+    srcs = [gpu.to_dev(t) for t in tensors]
+    aux = torch.cuda.Stream()
+    for pick in (list(range(6)), [1, 3, 4], [0, 2]):
+        outs = [torch.full((enec.compress_bound(tensors[i].size),), 0xA5, dtype=torch.uint8, device="cuda") for i in pick]
+        sizes = torch.zeros(len(pick), dtype=torch.int64, device="cuda")
+        for rep in range(3):
+            rc = enec.compress_batch([srcs[i] for i in pick], [params[i] for i in pick], outs, gpu.ws,
+                                     out_bytes=[sizes[j:j + 1] for j in range(len(pick))], aux_stream=aux)
+            assert rc == 0, enec.strerror(rc)
+        torch.cuda.synchronize()
+        for j, i in enumerate(pick):
+            assert int(sizes[j]) == refs[i].size, (pick, i)
+            assert np.array_equal(outs[j].cpu().numpy()[:refs[i].size], refs[i]), (pick, i)
+        backs = [torch.full((tensors[i].size,), 0x5A5A, dtype=torch.int16, device="cuda") for i in pick]
+        status = [torch.zeros(1, dtype=torch.int32, device="cuda") for _ in pick]
+        for rep in range(3):
+            rc = enec.decompress_batch(outs, [refs[i][:64] for i in pick], backs, aux_stream=aux, statuses=status)
+            assert rc == 0, enec.strerror(rc)
+        torch.cuda.synchronize()
+        for j, i in enumerate(pick):
+            assert int(status[j].item()) == 0
+            assert np.array_equal(backs[j].cpu().numpy().view(np.uint16), tensors[i]), (pick, i)
+    # the auxiliary stream must be another stream
+    assert enec.compress_batch(srcs[:1], params[:1], outs[:1], gpu.ws, aux_stream=torch.cuda.current_stream()) == enec.E_ARG
+
+
+def test_header_mismatch_sets_the_status_word(gpu, oracle):
+    torch, enec = gpu.torch, gpu.enec
+    w = W.gaussian(5 * 16384, 0.02, 97)
+    s = oracle.compress(w, oracle.tune(w), 16384)[1]
+    other = s.copy()
+    other[24] ^= 1                                   # a header with another b: valid in itself, not the stream's
+    out = torch.full((w.size,), 0x5A5A, dtype=torch.int16, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert enec.decompress_with_header(torch.from_numpy(s).cuda(), other[:64].tobytes(), out, status=status) == 0
+    torch.cuda.synchronize()
+    assert int(status.item()) == enec.E_FORMAT and (out == 0x5A5A).all()

@@ -156,6 +156,13 @@ def test_damaged_tuples_and_offsets_skip_blocks(gpu, oracle):
             bad[64 + 8 * k:64 + 8 * k + 8] = np.frombuffer(np.uint64(1 << 40).tobytes(), np.uint8)
         rc, d, rest = gpu.decompress(bad, w.size, BF16)
         assert rc == 0 and (rest == 0x5A5A).all()
+        # the status word tells the caller that blocks were left undecoded
+        torch, enec = gpu.torch, gpu.enec
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        back = torch.full((w.size,), 0x5A5A, dtype=torch.int16, device="cuda")
+        assert enec.decompress_with_header(torch.from_numpy(bad).cuda(), bad[:64].tobytes(), back, status=status) == 0
+        torch.cuda.synchronize()
+        assert int(status.item()) == enec.E_FORMAT, what
         touched = {k, k - 1} if what == "offset" else {k}
         for j in range(8):
             blk = d[j * B:(j + 1) * B]

@@ -85,6 +85,15 @@ def test_host_tuner_matches_oracle(enec, oracle, ref):
             assert enec.tune_histogram(h, lengths=lengths) == oracle.tune_hist_groups(h, 8, lengths)[0]
     with pytest.raises(Exception):
         enec.tune_histogram(hists[0], lengths=(4,))
+    # the library drops the lengths the block size does not admit (128 L <= B <= 2048 L): L = 32 needs B >= 4096,
+    # L = 8 needs B <= 16384, and 16 stands in when nothing is left
+    for h in hists[:30]:
+        assert enec.tune_histogram(h, lengths=(8, 16, 32), block_size=2048) == oracle.tune_hist_groups(h, 8, (8, 16))[0]
+        assert enec.tune_histogram(h, lengths=(8, 16, 32), block_size=32768) == oracle.tune_hist_groups(h, 8, (16, 32))[0]
+        assert enec.tune_histogram(h, lengths=(8,), block_size=32768) == oracle.tune_hist(h)[0]
+        assert enec.tune_histogram(h, lengths=(32,), block_size=2048) == oracle.tune_hist(h)[0]
+    with pytest.raises(Exception):
+        enec.tune_histogram(hists[0], lengths=(8, 16), block_size=3000)
 
 
 def test_stream_info_parses_oracle_headers(enec, oracle):
@@ -118,9 +127,9 @@ def test_null_and_misaligned_arguments_are_rejected_on_the_host(enec):
         q = enec.Params(*bad)
         assert L.enec_compress(fake, 10, 0, 0, ctypes.byref(q), fake, 1 << 20, None, fake, 1 << 20, None) == enec.E_PARAMS
     hdr = (ctypes.c_uint8 * 64)()
-    assert L.enec_decompress_with_header(fake, 1 << 20, hdr, fake, 10, None) == enec.E_FORMAT
-    assert L.enec_decompress_with_header(None, 1 << 20, hdr, fake, 10, None) == enec.E_ARG
-    assert L.enec_decompress_with_header(fake, 1 << 20, None, fake, 10, None) == enec.E_ARG
+    assert L.enec_decompress_with_header(fake, 1 << 20, hdr, fake, 10, None, None) == enec.E_FORMAT
+    assert L.enec_decompress_with_header(None, 1 << 20, hdr, fake, 10, None, None) == enec.E_ARG
+    assert L.enec_decompress_with_header(fake, 1 << 20, None, fake, 10, None, None) == enec.E_ARG
     assert L.enec_decompress(fake, 10, fake, 10, None) == enec.E_FORMAT
     assert L.enec_workspace_init(None, 16, None) == enec.E_ARG
     assert L.enec_workspace_init(fake, 17, None) == enec.E_ARG
