@@ -225,11 +225,12 @@ def main():
         by_tuple.setdefault((params[i][1], params[i][2]), []).append(i)
     groups = [g[c:c + 16] for g in by_tuple.values() for c in range(0, len(g), 16)]
     ng = len(groups)
+    calls = groups
 
     def compress_all(ev=None):
         if ev:
             ev[0].record()
-        for gi, g in enumerate(groups):
+        for gi, g in enumerate(calls):
             rc = enec.compress_batch([srcs[i] for i in g], [params[i] for i in g], [outs[i] for i in g], ws,
                                      out_bytes=[sizes[i:i + 1] for i in g])
             assert rc == 0, enec.strerror(rc)
@@ -242,12 +243,12 @@ def main():
     assert all(v > 0 for v in stream_bytes)
     headers = [outs[i][:64].cpu().numpy().tobytes() for i in range(nt)]
     ditems = [enec.make_decompress_items([outs[i] for i in g], [headers[i] for i in g], [backs[i] for i in g])
-              for g in groups]
+              for g in calls]
 
     def decompress_all(ev=None):
         if ev:
             ev[0].record()
-        for gi, g in enumerate(groups):
+        for gi, g in enumerate(calls):
             rc = enec.decompress_batch(None, None, None, items=ditems[gi][0])
             assert rc == 0, enec.strerror(rc)
             if ev:

@@ -170,17 +170,6 @@ typedef struct {
 int enec_compress_batch(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
                         size_t workspace_bytes, void *stream);
 
-/* The same with a second HIP stream of the caller's to spread the launches over [Sec. V-A: the blocks
- * of the work at hand are dealt to all cores]: a layer's tiny tensors (norm vectors, biases: one data
- * block each) have tuples of their own and therefore a launch of their own, which costs about ten
- * microseconds in front of or behind the launch of the large tensors.  Here such launches are enqueued on
- * aux_stream, forked from and joined back into `stream` with events, so that they run beside the large
- * launch; in `stream`'s order everything is complete when the next operation on `stream` starts.
- * aux_stream must differ from stream (ENEC_E_ARG) and stay at the default priority.  Without tiny tensors
- * the call is enec_compress_batch. */
-int enec_compress_batch_overlapped(const enec_compress_item *items, size_t n_items, int dtype, void *workspace,
-                                   size_t workspace_bytes, void *stream, void *aux_stream);
-
 /* Decompress [Sec. V-A decompression path; Alg. 1 decompression part].
  *   in        DEVICE, a stream written by enec_compress, 16-byte aligned
  *   in_bytes  size of the buffer behind `in`; ENEC_E_FORMAT if the header's total_bytes exceeds it.
@@ -214,11 +203,6 @@ typedef struct {
     uint32_t *status;           /* device-accessible word set to 0 by the caller, or NULL */
 } enec_decompress_item;
 int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, void *stream);
-
-/* The same with launches for tensors of one data block on aux_stream, beside the large launches; see
- * enec_compress_batch_overlapped. */
-int enec_decompress_batch_overlapped(const enec_decompress_item *items, size_t n_items, void *stream,
-                                     void *aux_stream);
 
 /* Decompression pipelines [Sec. VI, "End-to-End Inference Configurations": weights are decompressed layer
  * by layer, the decompression of layer k+1 overlapping the forward pass of layer k; Sec. VI, "End-to-End

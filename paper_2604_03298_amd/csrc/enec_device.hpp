@@ -221,20 +221,14 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
 // sizes of all earlier blocks were published an iteration ago, so the reads of the scan state
 // succeed at the first attempt and nobody spins on hot cache lines in the steady state.
 //
-// Control record of class c (WS_STRIDE 32-bit words apart): one 64-bit word, [63:24] tag of the last
-// finished call, [23:0] ticket counter of the running call, so that one returning atomic gives a
-// workgroup its block and the call's tag.  A class with L blocks and W workgroups sees exactly L + W
-// draws per call (every workgroup draws until its first draw beyond L; when every workgroup has exactly
-// one block, `oneshot`, it draws once and the class sees W draws), so the workgroup that receives the
-// last draw knows that nobody will touch the record again in this call and stores [tag + 1 | 0] for the
-// next one.  The second 64-bit word of class 0's record holds the tag of the last call in which a
-// workgroup gave up waiting for the scan: whoever writes a header looks at it, so that a give-up
-// anywhere in the launch turns every header of the launch into status ENEC_E_HIP.
-//
-// Small cases.  A tensor of one block starts at 0 and needs no scan state at all; a launch of such
-// tensors only (ws_ctl == nullptr) draws no tickets either, workgroup w codes block w.  Tensors of at
-// most DIRECT_MAX blocks skip the group words: a block's start is the sum of the block words below it,
-// four per lane, one round trip after the slowest predecessor has published.
+// Control record of class c (WS_STRIDE words apart): [0] ticket counter, never reset; [1] value
+// of the counter when the current call started; [2..3] tag of the last finished call; class 0 also
+// [4..5] tag of the last call in which a workgroup gave up waiting for the scan: whoever writes a
+// header looks at it, so that a give-up anywhere in the launch turns every header of the launch
+// into status ENEC_E_HIP (the block that gave up was stored at a start computed from a partial sum).  A class
+// with L blocks and W workgroups sees exactly L + W draws per call (every workgroup draws until
+// its first draw beyond L), so the workgroup that receives draw number L + W - 1 knows that
+// nobody will touch the record again in this call and writes the next call's base and tag.
 // ---------------------------------------------------------------------------------
 constexpr uint64_t ST_ERR = 1ull << 23;
 constexpr uint64_t ST_VALUE = (1ull << 23) - 1;
@@ -245,8 +239,6 @@ constexpr uint32_t WS_CLASSES = 8;
 // blocks per scan group: with G blocks a start costs G - 1 block words plus (blocks in flight) / G
 // group words, and G additions meet on one accumulator at about 12 ns each
 constexpr uint32_t GROUP_LOG = 3, GROUP = 1u << GROUP_LOG;
-constexpr uint32_t DIRECT_MAX = 256;          // tensors of up to this many blocks sum block words directly
-constexpr uint64_t TICKET_MASK = (1ull << 24) - 1;
 
 __device__ __forceinline__ uint64_t ld_state(const uint64_t *p)
 {
@@ -283,12 +275,11 @@ struct CompressItem {
 };
 
 struct CompressArgs {
-    uint32_t *ws_ctl;       // WS_CLASSES control records; null: every tensor is one block, workgroup w codes block w
+    uint32_t *ws_ctl;       // WS_CLASSES control records
     uint32_t B, logB;
     uint32_t total;         // data blocks of all items
     uint32_t ncls;          // number of block classes = min(8, gridDim.x)
     uint32_t lookahead;     // draw the next ticket while working on the current block
-    uint32_t oneshot;       // the grid has one workgroup per block: every workgroup draws exactly once
     uint32_t n_items;
     uint32_t spin_limit;    // polls of the scan state after which a workgroup gives up (status ENEC_E_HIP)
     CompressItem item[MAX_BATCH];
@@ -412,27 +403,24 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 
     // ---- control record of this workgroup's class (thread 0) ---------------------------
     const uint32_t home = blockIdx.x % p.ncls;
-    uint64_t *ctl = reinterpret_cast<uint64_t *>(p.ws_ctl + WS_STRIDE * home);
-    uint64_t *gave_up = reinterpret_cast<uint64_t *>(p.ws_ctl) + 1;
+    uint32_t *ctl = p.ws_ctl + WS_STRIDE * home;
     const uint32_t class_blocks = home < p.total ? (p.total - home + p.ncls - 1u) / p.ncls : 0u;
     const uint32_t class_wgs = (gridDim.x - home + p.ncls - 1u) / p.ncls;
-    const uint32_t class_draws = p.oneshot ? class_blocks : class_blocks + class_wgs;
+    uint32_t ticket_base = 0, zero = 0;
     uint64_t tag0 = 0;
-    bool drawing = p.ws_ctl != nullptr;
-    auto draw = [&]() -> uint64_t {
-        return __hip_atomic_fetch_add(ctl, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    };
+    bool drawing = true;
     // decode a draw; the last draw of the class hands the record over to the next call
-    auto decode_draw = [&](uint64_t raw) -> uint32_t {
-        const uint32_t t = (uint32_t)(raw & TICKET_MASK);
-        tag0 = (raw >> 24) + 1u;                             // the same in every draw of a call
-        if (t == class_draws - 1u)
+    auto decode_draw = [&](uint32_t raw) -> uint32_t {
+        const uint32_t t = raw - ticket_base;
+        if (t == class_blocks + class_wgs - 1u) {
+            ctl[1] = raw + 1u;
             for (uint32_t c = home; c < WS_CLASSES; c += p.ncls)
-                st_state(reinterpret_cast<uint64_t *>(p.ws_ctl + WS_STRIDE * c), tag0 << 24);
-        if (p.oneshot) drawing = false;
+                *reinterpret_cast<uint64_t *>(p.ws_ctl + WS_STRIDE * c + 2) = tag0;
+        }
         if (t >= class_blocks) { drawing = false; return NO_BLOCK; }
         return t * p.ncls + home;
     };
+    uint32_t slot = 0;
     // tensor that global block kg belongs to, searching upwards from item c
     auto item_of = [&](uint32_t kg, uint32_t c) -> uint32_t {
         while (c + 1u < p.n_items && kg >= p.item[c + 1u].first) ++c;
@@ -443,12 +431,16 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
     // workgroups start together, workgroup w draws block w, so its rows are requested on that guess
     // while the control record and the draw are still travelling.
     const uint32_t guess = blockIdx.x;                       // the grid never exceeds the number of blocks
-    uint32_t slot = 0;
     uint32_t ci = item_of(guess, 0);
     uint4 raw[RW];
     load_block_rows<DT>(p.item[ci], B, p.logB, guess - p.item[ci].first, tid, active, logC, raw);
     if (tid == 0) {
-        s_k[0] = drawing ? decode_draw(draw()) : (guess < p.total ? guess : NO_BLOCK);
+        ticket_base = ctl[1];
+        tag0 = *reinterpret_cast<const uint64_t *>(ctl + 2) + 1u;
+        // the record must have been read before this workgroup's first draw can be counted
+        zero = ticket_base ^ (uint32_t)tag0;
+        asm volatile("v_and_b32 %0, 0, %0" : "+v"(zero));
+        s_k[0] = decode_draw(atomicAdd(ctl + zero, 1u));
         s_tag = tag0;
         s_err[0] = s_err[1] = 0;
         s_status = 0;
@@ -482,7 +474,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             if (++spins > p.spin_limit) {                                      // never hang
                 flags |= 4u;
                 v = 0;
-                if (lane == 0) st_state(gave_up, tag);                          // seen by whoever writes a header
+                if (lane == 0) st_state(reinterpret_cast<uint64_t *>(p.ws_ctl + 4), tag);
                 break;
             }
             spin_pause(spins);
@@ -490,40 +482,9 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         if (__builtin_amdgcn_ballot_w64(need && (v & ST_ERR))) flags |= 2u;
         return wave_sum(need ? (v & ST_VALUE) : 0ull);
     };
-    // the same for up to 256 words, four per lane (tensors of at most DIRECT_MAX blocks)
-    auto sum_words4 = [&](const uint64_t *base, uint32_t count, uint32_t &flags) -> uint64_t {
-        uint64_t v[4] = {0, 0, 0, 0};
-        uint32_t pending = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (lane + 64u * i < count) pending |= 1u << i;
-        uint32_t spins = 0;
-        while (__builtin_amdgcn_ballot_w64(pending != 0) != 0) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if ((pending >> i) & 1u) {
-                    v[i] = ld_state(base + lane + 64u * i);
-                    if ((v[i] & ~0xFFFFFFull) == tag) pending &= ~(1u << i);
-                }
-            if (__builtin_amdgcn_ballot_w64(pending != 0) == 0) break;
-            if (++spins > p.spin_limit) {
-                flags |= 4u;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if ((pending >> i) & 1u) v[i] = 0;
-                if (lane == 0) st_state(gave_up, tag);
-                break;
-            }
-            spin_pause(spins);
-        }
-        const uint64_t any = v[0] | v[1] | v[2] | v[3];
-        if (__builtin_amdgcn_ballot_w64((any & ST_ERR) != 0)) flags |= 2u;
-        return wave_sum((v[0] & ST_VALUE) + (v[1] & ST_VALUE) + (v[2] & ST_VALUE) + (v[3] & ST_VALUE));
-    };
     // start of block kb (wave 0; early_g / early_b = copies of the first needed group words / of
     // the earlier block words of its group, read ahead of time)
     auto block_start = [&](const CompressItem &it, uint32_t kb, bool early, uint64_t early_g, uint64_t early_b) -> uint64_t {
-        if (it.nb <= DIRECT_MAX) return kb ? sum_words4(it.ws_block, kb, scan_flags) << 4 : 0ull;
         const uint32_t g = kb >> GROUP_LOG;
         while (groups_summed < g) {
             const uint32_t c = g - groups_summed < 64u ? g - groups_summed : 64u;
@@ -597,7 +558,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             if (kb == it.nb - 1u) {
                 const uint64_t end = off + S;
                 uint32_t fl = s_status | err_own;
-                if (p.ws_ctl && ld_state(gave_up) == tag) fl |= 4u;        // somebody in this launch gave up waiting
+                if (ld_state(reinterpret_cast<const uint64_t *>(p.ws_ctl + 4)) == tag) fl |= 4u;   // somebody gave up
                 const uint32_t status = (fl & 4u) ? 8u : ((fl & 3u) ? 6u : 0u);
                 const uint64_t total = status ? 0ull : it.payload_base + end;
                 table[it.nb] = end;
@@ -636,16 +597,14 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             if (scan_item != pend_item) { scan_item = pend_item; groups_sum = 0; groups_summed = 0; scan_flags = 0; }
             const CompressItem &pit = p.item[pend_item];
             const uint32_t pg = pend >> GROUP_LOG;
-            if (pit.nb > DIRECT_MAX) {
-                if (groups_summed + lane < pg) early_g = ld_state(pit.ws_group + groups_summed + lane);
-                if (lane < (pend & (GROUP - 1u))) early_b = ld_state(pit.ws_block + ((uint64_t)pg << GROUP_LOG) + lane);
-            }
+            if (groups_summed + lane < pg) early_g = ld_state(pit.ws_group + groups_summed + lane);
+            if (lane < (pend & (GROUP - 1u))) early_b = ld_state(pit.ws_block + ((uint64_t)pg << GROUP_LOG) + lane);
         }
 
         // the ticket for the following block is drawn now and looked at after the arithmetic
-        uint64_t next_raw = 0;
+        uint32_t next_raw = 0;
         const bool draw_now = tid == 0 && p.lookahead && drawing;
-        if (draw_now) next_raw = draw();
+        if (draw_now) next_raw = atomicAdd(ctl + zero, 1u);
 
         uint32_t SMc[8][2], HI[8][2], accP[MP][2], mw[8], mw_hi[LPG == 1 ? 8 : 1];
         uint32_t err_acc = 0;
@@ -781,14 +740,12 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         // ---- a6: publish this block's size at once, and add it to its group's accumulator
         // [blocks:16 | blocks with a range error:16 | sum of sizes:32]; what the addition returns
         // is looked at after barrier 2, when it has had time to travel ---------------------
-        // (a tensor of one block has no scan state; one of at most DIRECT_MAX blocks only block words)
-        if (tid == 0 && it.nb > 1u) st_state(it.ws_block + kl, tag | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
-        // (a group of one block is complete with its only member)
-        const bool grouped = it.nb > DIRECT_MAX;
+        if (tid == 0) st_state(it.ws_block + kl, tag | (own_err ? ST_ERR : 0ull) | (uint64_t)(S >> 4));
+        // (a group of one block, e.g. a tensor of one block, is complete with its only member)
         const uint32_t grp = kl >> GROUP_LOG;
         const uint32_t members = it.nb - (grp << GROUP_LOG) < GROUP ? it.nb - (grp << GROUP_LOG) : GROUP;
         uint64_t acc_old = 0;
-        if (tid == acc_tid && grouped && members > 1u)
+        if (tid == acc_tid && members > 1u)
             acc_old = __hip_atomic_fetch_add(it.ws_acc + grp, (1ull << 48) | ((uint64_t)own_err << 32) | (uint64_t)(S >> 4),
                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
@@ -928,7 +885,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 
         // ---- a6: whoever completes a group publishes its word and clears the accumulator for
         // the next call; nobody ever waits for blocks of its own generation ------------------
-        if (tid == acc_tid && grouped) {
+        if (tid == acc_tid) {
             if ((uint32_t)(acc_old >> 48) == members - 1u) {
                 const uint64_t sum = (acc_old & 0xFFFFFFFFull) + (S >> 4);
                 const bool any_err = ((acc_old >> 32) & 0xFFFFull) != 0 || own_err;
@@ -966,7 +923,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         k = knext;
         ci = cnext;
         if (k == NO_BLOCK && !p.lookahead) {           // without lookahead the next ticket is drawn only now
-            if (tid == 0) s_k[slot] = drawing ? decode_draw(draw()) : NO_BLOCK;
+            if (tid == 0) s_k[slot] = drawing ? decode_draw(atomicAdd(ctl + zero, 1u)) : NO_BLOCK;
             __syncthreads();
             k = __builtin_amdgcn_readfirstlane(s_k[slot]);
             if (k != NO_BLOCK) {
@@ -1054,12 +1011,9 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
         const uint64_t sz = t1 - t0;
         off = t0;
         size = (uint32_t)sz;
-        const bool good = header_matches(c) &&
+        return header_matches(c) &&
                !(sz < fixed || sz > fixed + RB * ((B >> 3) >> LOG_LPG) + 15u || (sz & 15u) || t0 > p.item[c].payload_bytes ||
                  sz > p.item[c].payload_bytes - t0);
-        // a block that is skipped leaves its part of the output untouched: tell the caller
-        if (!good && tid == 0 && p.item[c].status) *p.item[c].status = 7u;
-        return good;
     };
     // issue the loads of one block: sign/mantissa rows and the packed part
     auto issue = [&](uint32_t c, uint64_t off, uint32_t size, uint2 (&smv)[8], uint4 (&vec)[VMAX]) {
@@ -1084,6 +1038,23 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
 
     uint32_t k = blockIdx.x;                                // global block index
     if (k >= p.total) return;
+    // A block that fails these tests is skipped and its part of the output stays as it was.  For the
+    // tensors that come with a status word, the last workgroup looks at the header and at every table
+    // entry once more before its own work and tells the caller if any block will be skipped.  (Done
+    // here, outside the loop below: a store inside that loop cost 5 % of the kernel's time.)
+    if (blockIdx.x == gridDim.x - 1u) {
+        for (uint32_t c = 0; c < p.n_items; ++c) {
+            if (!p.item[c].status) continue;
+            const uint64_t *table = reinterpret_cast<const uint64_t *>(p.item[c].in + 64);
+            bool bad = !header_matches(c);
+            for (uint32_t e = tid; e < p.item[c].nb && !bad; e += blockDim.x) {
+                const uint64_t t0 = table[e], sz = table[e + 1] - t0;
+                bad = sz < fixed || sz > fixed + RB * ((B >> 3) >> LOG_LPG) + 15u || (sz & 15u) || t0 > p.item[c].payload_bytes ||
+                      sz > p.item[c].payload_bytes - t0;
+            }
+            if (bad) *p.item[c].status = 7u;
+        }
+    }
     uint32_t ci = item_of(k, 0);
     uint32_t cn = item_of(k + gridDim.x, ci);               // item of the next block (if there is one)
     uint64_t off = 0, offn = 0;

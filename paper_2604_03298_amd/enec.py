@@ -26,7 +26,7 @@ EXPORTS = [
     "enec_tune_sampled", "enec_compress_sampled", "enec_compress_bound_per_block", "enec_compress_per_block",
     "enec_tune_batch", "enec_compress_static", "enec_pipeline_create", "enec_pipeline_destroy",
     "enec_pipeline_prefetch", "enec_pipeline_prefetch_from_host", "enec_pipeline_acquire", "enec_pipeline_release",
-    "enec_pipeline_trace", "enec_compress_batch_overlapped", "enec_decompress_batch_overlapped",
+    "enec_pipeline_trace",
 ]
 
 
@@ -122,10 +122,6 @@ def lib():
         L.enec_compress_batch.argtypes = [C.POINTER(CompressItem), sz, C.c_int, vp, sz, vp]
         L.enec_decompress_batch.restype = C.c_int
         L.enec_decompress_batch.argtypes = [C.POINTER(DecompressItem), sz, vp]
-        L.enec_compress_batch_overlapped.restype = C.c_int
-        L.enec_compress_batch_overlapped.argtypes = [C.POINTER(CompressItem), sz, C.c_int, vp, sz, vp, vp]
-        L.enec_decompress_batch_overlapped.restype = C.c_int
-        L.enec_decompress_batch_overlapped.argtypes = [C.POINTER(DecompressItem), sz, vp, vp]
         L.enec_pipeline_create.restype = C.c_int
         L.enec_pipeline_create.argtypes = [C.POINTER(vp), u32, vp, vp, vp, sz, C.c_int]
         L.enec_pipeline_destroy.restype = None
@@ -306,10 +302,10 @@ def decompress_with_header(stream_buf, host_header, out, n_elems: int | None = N
 
 
 def compress_batch(srcs, params, outs, workspace, block_sizes=None, out_bytes=None, stream=None,
-                   dtype: int | None = None, aux_stream=None) -> int:
-    """Enqueues enec_compress_batch (with aux_stream: enec_compress_batch_overlapped).  srcs / outs: lists of
-    device tensors (one element format for all, see dtype_of); params: list of (b, n, m, L) or None per
-    tensor; out_bytes: None or a list of one-u64 device-accessible tensors."""
+                   dtype: int | None = None) -> int:
+    """Enqueues enec_compress_batch.  srcs / outs: lists of device tensors (one element format for
+    all, see dtype_of); params: list of (b, n, m, L) or None per tensor; out_bytes: None or a list
+    of one-u64 device-accessible tensors."""
     n = len(srcs)
     dt = dtype_of(srcs[0], dtype) if n else BF16
     keep = [_params(p) if p is not None else None for p in params]
@@ -322,10 +318,6 @@ def compress_batch(srcs, params, outs, workspace, block_sizes=None, out_bytes=No
         items[i].out = outs[i].data_ptr()
         items[i].out_capacity = outs[i].numel() * outs[i].element_size()
         items[i].out_bytes = out_bytes[i].data_ptr() if out_bytes is not None else None
-    if aux_stream is not None:
-        return int(lib().enec_compress_batch_overlapped(items, n, dt, C.c_void_p(workspace.data_ptr()),
-                                                        workspace.numel() * workspace.element_size(),
-                                                        _stream_handle(stream), C.c_void_p(aux_stream.cuda_stream)))
     return int(lib().enec_compress_batch(items, n, dt, C.c_void_p(workspace.data_ptr()),
                                          workspace.numel() * workspace.element_size(),
                                          _stream_handle(stream)))
@@ -347,13 +339,10 @@ def make_decompress_items(stream_bufs, host_headers, outs, statuses=None):
     return items, hdrs
 
 
-def decompress_batch(stream_bufs, host_headers, outs, stream=None, items=None, aux_stream=None, statuses=None) -> int:
+def decompress_batch(stream_bufs, host_headers, outs, stream=None, items=None, statuses=None) -> int:
     keep = None
     if items is None:
         items, keep = make_decompress_items(stream_bufs, host_headers, outs, statuses)
-    if aux_stream is not None:
-        return int(lib().enec_decompress_batch_overlapped(items, len(items), _stream_handle(stream),
-                                                          C.c_void_p(aux_stream.cuda_stream)))
     return int(lib().enec_decompress_batch(items, len(items), _stream_handle(stream)))
 
 

@@ -176,12 +176,12 @@ def test_workspace_is_reusable_and_results_are_deterministic(gpu, oracle):
         assert rc == 0 and nbytes == sb.size and np.array_equal(out[:nbytes], sb), f"run {i}"
         rc, out, nbytes, _ = gpu.compress(small, ps, 16384, src=src_s)
         assert rc == 0 and nbytes == ss.size and np.array_equal(out[:nbytes], ss), f"run {i}"
-    # every class's control word is [tag of the last call | ticket 0], the same tag everywhere; nobody gave up
+    # the ticket counter of every class has come back to the base the next call will read; nobody gave up
     ws_host = gpu.ws.cpu().numpy()
-    ctl = ws_host[:1024].view(np.uint64).reshape(8, 16)
-    assert (ctl[:, 0] & np.uint64(0xFFFFFF) == 0).all()
-    assert len(set(ctl[:, 0].tolist())) == 1 and int(ctl[0, 0]) >> 24 >= 12
-    assert ctl[0, 1] == 0
+    ctl = ws_host[:1024].view(np.uint32).reshape(8, 32)
+    assert (ctl[:, 0] == ctl[:, 1]).all()
+    assert len(set(ctl[:, 2].tolist())) == 1
+    assert ctl[0, 4] == 0 and ctl[0, 5] == 0
     # every group accumulator (the first ninth of the state words) is back to zero
     words = ws_host[STATE_AT:STATE_AT + (ws_host.size - STATE_AT) // 8 * 8].view(np.uint64)
     assert (words[:words.size // 9] == 0).all()
@@ -562,10 +562,10 @@ def test_tensor_beyond_4_gib_sampled_against_the_oracle(gpu, oracle):
         assert got.size == s.size - ob and np.array_equal(got, s[ob:]), k0
 
 
-def test_overlapped_batches_with_an_auxiliary_stream(gpu, oracle):
-    """A layer's tiny tensors (one data block each, tuples of their own) are launched on the caller's second
-    stream, beside the launch of the matrices: same streams as the oracle's, same round trip, also when the
-    calls are repeated back to back without synchronisation, and also when the batch has only tiny tensors or none."""
+def test_batches_with_single_block_tensors(gpu, oracle):
+    """A layer's tiny tensors (one data block each, tuples of their own) beside matrices, in one batch call, with
+    status words for the decoder: same streams as the oracle's, same round trip, also when the calls are repeated
+    back to back without synchronisation, and also when the batch has only tiny tensors or none."""
     torch, enec = gpu.torch, gpu.enec
     tensors = [W.layer_matrix(512, 1376, 24), W.norm_vector(4096, 27), W.layer_matrix(1376, 512, 26),
                W.norm_vector(4096, 28), W.gaussian(3000, 0.5, 29), W.gaussian(16384, 0.02, 30)]
@@ -573,13 +573,12 @@ def test_overlapped_batches_with_an_auxiliary_stream(gpu, oracle):
     assert len({p[:3] for p in params}) >= 3
     refs = [oracle.compress(t, p, oracle.default_block(t.size))[1] for t, p in zip(tensors, params)]
     srcs = [gpu.to_dev(t) for t in tensors]
-    aux = torch.cuda.Stream()
     for pick in (list(range(6)), [1, 3, 4], [0, 2]):
         outs = [torch.full((enec.compress_bound(tensors[i].size),), 0xA5, dtype=torch.uint8, device="cuda") for i in pick]
         sizes = torch.zeros(len(pick), dtype=torch.int64, device="cuda")
         for rep in range(3):
             rc = enec.compress_batch([srcs[i] for i in pick], [params[i] for i in pick], outs, gpu.ws,
-                                     out_bytes=[sizes[j:j + 1] for j in range(len(pick))], aux_stream=aux)
+                                     out_bytes=[sizes[j:j + 1] for j in range(len(pick))])
             assert rc == 0, enec.strerror(rc)
         torch.cuda.synchronize()
         for j, i in enumerate(pick):
@@ -588,14 +587,12 @@ def test_overlapped_batches_with_an_auxiliary_stream(gpu, oracle):
         backs = [torch.full((tensors[i].size,), 0x5A5A, dtype=torch.int16, device="cuda") for i in pick]
         status = [torch.zeros(1, dtype=torch.int32, device="cuda") for _ in pick]
         for rep in range(3):
-            rc = enec.decompress_batch(outs, [refs[i][:64] for i in pick], backs, aux_stream=aux, statuses=status)
+            rc = enec.decompress_batch(outs, [refs[i][:64] for i in pick], backs, statuses=status)
             assert rc == 0, enec.strerror(rc)
         torch.cuda.synchronize()
         for j, i in enumerate(pick):
             assert int(status[j].item()) == 0
             assert np.array_equal(backs[j].cpu().numpy().view(np.uint16), tensors[i]), (pick, i)
-    # the auxiliary stream must be another stream
-    assert enec.compress_batch(srcs[:1], params[:1], outs[:1], gpu.ws, aux_stream=torch.cuda.current_stream()) == enec.E_ARG
 
 
 def test_header_mismatch_sets_the_status_word(gpu, oracle):
