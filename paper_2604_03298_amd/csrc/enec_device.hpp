@@ -168,14 +168,36 @@ __device__ __forceinline__ uint32_t quad_or(uint32_t v)
     return v;
 }
 
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane)
+// inclusive prefix sum over the 64 lanes with data-parallel-primitive moves: four shifts inside
+// each row of 16 lanes, then the last lane of a row is broadcast into the next row (rows 1 and 3)
+// and the last lane of the lower half into the upper half.  Six dependent VALU operations; the
+// same through ds_bpermute (__shfl_up) is six round trips to the LDS crossbar.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t /*lane*/)
 {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        uint32_t o = __shfl_up(v, d, 64);
-        if (lane >= (uint32_t)d) v += o;
-    }
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111 /* row_shr:1 */, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112 /* row_shr:2 */, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114 /* row_shr:4 */, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118 /* row_shr:8 */, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142 /* row_bcast:15 */, 0xA, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143 /* row_bcast:31 */, 0xC, 0xF, false);
     return v;
+}
+
+// Value of `v` in lane `idx`.  A thread's group of row t lies in mask word (index of the group) / 32;
+// for groups of 16 and 32 elements that word index is the same for all lanes of a wave (it depends
+// on t and on the wave's number only), so one v_readlane with a scalar index fetches it; for groups
+// of 8 the two halves of a wave look at different words and the LDS crossbar is asked.
+template <int LPG>
+__device__ __forceinline__ uint32_t mask_word_lane(uint32_t v, uint32_t idx)
+{
+    if constexpr (LPG == 1) return (uint32_t)__shfl((int)v, (int)idx, 64);
+    else return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)__builtin_amdgcn_readfirstlane((int)idx));
+}
+
+// sum over the 64 lanes of values whose total fits 32 bits, in every lane
+__device__ __forceinline__ uint32_t wave_sum32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan(v, 0), 63);
 }
 
 __device__ __forceinline__ uint64_t wave_sum(uint64_t v)
@@ -480,7 +502,8 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
             spin_pause(spins);
         }
         if (__builtin_amdgcn_ballot_w64(need && (v & ST_ERR))) flags |= 2u;
-        return wave_sum(need ? (v & ST_VALUE) : 0ull);
+        // at most 64 sizes below 2^23 units of 16 bytes: the sum fits 32 bits
+        return wave_sum32(need ? (uint32_t)(v & ST_VALUE) : 0u);
     };
     // start of block kb (wave 0; early_g / early_b = copies of the first needed group words / of
     // the earlier block words of its group, read ahead of time)
@@ -733,7 +756,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
         const uint32_t my_pc = __popc(my_word);
         const uint32_t my_incl = wave_incl_scan(my_pc, lane);
         const uint32_t my_excl = my_incl - my_pc;
-        const uint32_t cnt = __shfl(my_incl, 63, 64);
+        const uint32_t cnt = (uint32_t)__builtin_amdgcn_readlane((int)my_incl, 63);
         const uint32_t own_err = s_err[slot] & 1u;
         const uint32_t S = (fixed + RB * cnt + 15u) & ~15u;
 
@@ -783,8 +806,8 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
                     const uint32_t g = ((uint32_t)t << (logC - 3)) + tid;
-                    const uint32_t wv = __shfl(my_word, g >> 5, 64);
-                    const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+                    const uint32_t wv = mask_word_lane<LPG>(my_word, g >> 5);
+                    const uint32_t pre = mask_word_lane<LPG>(my_excl, g >> 5);
                     if (active && ((wv >> (g & 31u)) & 1u)) {
                         const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
                         uint8_t *dst = img_high + RB * rank;
@@ -810,8 +833,13 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                     F[2] = par ? own0 : rcv0;
                     F[3] = par ? own1 : rcv1;
                     const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
-                    const uint32_t wv = __shfl(my_word, g >> 5, 64);
-                    const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+                    // even and odd lanes look at the groups of two rows: two wave-uniform word indices
+                    const uint32_t w_even = (((2u * u) << (logC - 4)) + (tid >> 1)) >> 5;
+                    const uint32_t w_odd = (((2u * u + 1u) << (logC - 4)) + (tid >> 1)) >> 5;
+                    const uint32_t wv_e = mask_word_lane<LPG>(my_word, w_even), wv_o = mask_word_lane<LPG>(my_word, w_odd);
+                    const uint32_t pre_e = mask_word_lane<LPG>(my_excl, w_even), pre_o = mask_word_lane<LPG>(my_excl, w_odd);
+                    const uint32_t wv = par ? wv_o : wv_e;
+                    const uint32_t pre = par ? pre_o : pre_e;
                     const uint32_t bit = (wv >> (g & 31u)) & 1u;
                     if (active && bit) {
                         const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
@@ -842,8 +870,8 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
                     const uint32_t g = ((uint32_t)t << (logC - 5)) + (tid >> 2);
-                    const uint32_t wv = __shfl(my_word, g >> 5, 64);
-                    const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+                    const uint32_t wv = mask_word_lane<LPG>(my_word, g >> 5);
+                    const uint32_t pre = mask_word_lane<LPG>(my_excl, g >> 5);
                     if (active && ((wv >> (g & 31u)) & 1u)) {
                         const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
                         uint32_t P[AP];
@@ -1148,8 +1176,8 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
                 if (A > 0) {
                     constexpr HHTable TH = HH<A>::table;
                     const uint32_t g = ((uint32_t)t << (logC - 3 - LOG_LPG)) + (tid >> LOG_LPG);
-                    const uint32_t wv = __shfl(my_word, g >> 5, 64);
-                    const uint32_t pre = __shfl(my_excl, g >> 5, 64);
+                    const uint32_t wv = mask_word_lane<LPG>(my_word, g >> 5);
+                    const uint32_t pre = mask_word_lane<LPG>(my_excl, g >> 5);
                     if ((wv >> (g & 31u)) & 1u) {
                         const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
                         const uint8_t *rec8 = img_high + RB * rank;
