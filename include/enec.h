@@ -298,7 +298,7 @@ int enec_compress_sampled(const void *in, size_t n_elems, int dtype, uint32_t bl
                           size_t workspace_bytes, void *stream);
 
 /* One tuple per data block.  The paper tunes one (b, n, m) per tensor [Sec. V-E] and reports that
- * tensors differ [Table VI]; here the same search (Eq. 1-4, L = 16) runs inside the compress kernel
+ * tensors differ [Table VI]; here the same search (Eq. 1-4) runs inside the compress kernel
  * on the exponents of each data block's own elements, and the block is coded with what it finds, so
  * no exponent is ever out of range and a tensor whose blocks differ in kind or scale is coded as
  * well as its parts would be.  Stream layout: as described at the top, with
@@ -308,7 +308,7 @@ int enec_compress_sampled(const void *in, size_t n_elems, int dtype, uint32_t bl
  * enec_decompress, enec_decompress_with_header and enec_decompress_batch read such streams as any
  * other (a launch of its own per stream).  Arguments as for enec_compress, without params;
  * group_length = 8, 16, 32 or 0 (= 16) is the group length the blocks are coded with (ENEC_E_PARAMS if
- * the block size does not admit it; the search itself evaluates Eq. 4 with L = 16, as enec_tune does);
+ * the block size does not admit it; the search evaluates Eq. 4, 1/L + n + (m - n) p(m)^L, with that length);
  * out_capacity >= enec_compress_bound_per_block(n_elems, dtype, block_size) (0 for an invalid dtype
  * or block size).  The workspace is used as by enec_compress and must not be shared with a call
  * that is still running.  Asynchronous. */

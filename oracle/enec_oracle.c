@@ -568,7 +568,8 @@ static int compress_core(const void *in, size_t n_elems, int dtype, uint32_t B, 
             uint64_t hist[256];
             const uint8_t *src = (const uint8_t *)in + first * orc_elem_bytes(dtype);
             orc_histogram_dt(src, count, dtype, hist);
-            orc_tune_hist_e(hist, E, t, NULL, NULL);
+            /* phase 3 with the group length the block is coded with: Eq. 4 is 1/L + n + (m - n) p(m)^L */
+            orc_tune_hist_groups(hist, E, L, t, NULL, NULL);
             b = t[0]; n = t[1]; m = t[2];
             tuples[4 * k] = t[0]; tuples[4 * k + 1] = t[1]; tuples[4 * k + 2] = t[2];
         }

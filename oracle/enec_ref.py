@@ -205,7 +205,7 @@ def compress(words, params, B, dtype=0, per_block=False):
             hist = [0] * 256
             for part in parts:
                 hist[part[0]] += 1
-            b, n, m, _ = tune_hist(hist, E)[0]
+            b, n, m, _ = tune_hist_groups(hist, E, (L,))[0]      # Eq. 4 with the coding group length
             tuples += bytes([b, n, m, 0])
         a = n - m
         rb = a * L // 8                  # a record without the pad byte Alg. 2 adds to an odd count

@@ -488,7 +488,8 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
     }
     __syncthreads();
     const uint32_t b = (uint32_t)s_best & 0xFFu, n = ((uint32_t)s_best >> 8) & 0xFFu;
-    // ---- phase 3: Eq. 4 for every m, in IEEE double, p^16 by four squarings ----
+    // ---- phase 3: Eq. 4 for every m with the group length the block is coded with, 1/L + n + (m - n) p^L,
+    // in IEEE double, p^L by three to five squarings ----
     if (tid <= n) {
         const uint32_t nmask = (1u << n) - 1u;
         uint32_t cnt = 0;
@@ -496,8 +497,11 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
         for (uint32_t x = xl; x <= xh; ++x)
             if (((b - x) & nmask) < (1u << tid)) cnt += s_hist[x];
         const double q = (double)cnt / (double)real;
-        const double q2 = q * q, q4 = q2 * q2, q8 = q4 * q4, q16 = q8 * q8;
-        s_bexp[tid] = (1.0 / 16.0 + (double)n) + ((double)tid - (double)n) * q16;
+        const double q2 = q * q, q4 = q2 * q2;
+        double qL = q4 * q4;                                   // p^8
+        if constexpr (LPG >= 2) qL = qL * qL;                  // p^16
+        if constexpr (LPG == 4) qL = qL * qL;                  // p^32
+        s_bexp[tid] = (1.0 / (double)(8 * LPG) + (double)n) + ((double)tid - (double)n) * qL;
     }
     __syncthreads();
     if (tid == 0) {

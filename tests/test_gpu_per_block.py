@@ -239,6 +239,12 @@ def test_group_lengths_8_and_32(gpu, oracle, L):
         w = _mixed16(11, B, 500 + B + L)
         _check(gpu, oracle, w, BF16, B, f"L={L} B={B}", L)
         _check(gpu, oracle, w[:w.size - B // 3 - 1], BF16, B, f"L={L} B={B} ragged", L)
+    # blocks of two scales: Eq. 4 gives them another m at L = 32 than at L = 16, so the kernel's search must use
+    # the length the block is coded with
+    two = np.concatenate([np.concatenate([W.gaussian(2048, 0.02, 10 + i), W.gaussian(2048, 0.005, 20 + i)]) for i in range(5)])
+    s_two = _check(gpu, oracle, two, BF16, 4096, f"L={L} two scales", L)
+    if L == 32:
+        assert any(t[2] != oracle.tune(two[k * 4096:(k + 1) * 4096])[2] for k, t in enumerate(oracle.block_tuples(s_two)))
     w = _mixed16(7, 16384, 77 + L, FP16)
     _check(gpu, oracle, w, FP16, 16384, f"fp16 L={L}", L)
     parts = [W.gaussian_fp32(16384 * 2, 0.02, 1), np.zeros(16384, np.uint32), W.gaussian_fp32(16384 + 99, 300.0, 2)]

@@ -89,7 +89,7 @@ def test_every_payload_is_the_one_tuple_codec_on_that_block(oracle, dtype, L):
     for k in range(nb):
         blk = w[k * B:(k + 1) * B]
         b, n, m = tuples[k]
-        assert (b, n, m, 16) == oracle.tune(blk, dtype)                 # the tensor tuner on the block alone
+        assert (b, n, m, L) == oracle.tune(blk, dtype, lengths=(L,))    # the tensor tuner on the block alone, Eq. 4 at this L
         rc1, one = oracle.compress(blk, (b, n, m, L), B, dtype=dtype)   # one-block stream of the pinned codec
         assert rc1 == oracle.OK
         pb1 = oracle.payload_base(blk.size, B, dtype)
@@ -140,3 +140,31 @@ def test_empty_and_bound(oracle):
     rc, s = oracle.compress_per_block(w, 2048, BF16, 8)
     assert rc == oracle.OK and s.size <= oracle.compress_bound_pb(w.size, 2048)
     assert oracle.compress_bound_pb(w.size, 2048) == oracle.compress_bound(w.size, 2048) + 16
+
+
+@pytest.mark.parametrize("L", [8, 16, 32])
+def test_block_thresholds_minimise_eq4_at_the_coding_length_and_the_bits_spent(oracle, L):
+    """Eq. 4 is 1/L + n + (m - n) p(m)^L: a block that is coded with groups of L elements takes the m that
+    minimises it at that L.  Checked without the oracle's tuner: histogram by numpy, p(m) by counting, the power
+    by Python's `**`; and against what the codec really spends when every other m is tried on the block."""
+    B = 4096
+    w = np.concatenate([W.gaussian(B, 0.02, 31), W.gaussian(B, 0.3, 32), W.gaussian(B, 1e-4, 33),
+                        W.layer_matrix(1, B, 24), W.gaussian(B // 2, 0.02, 1), W.gaussian(B // 2, 0.005, 2),
+                        W.gaussian(B - 700, 0.02, 34)])
+    rc, s = oracle.compress_per_block(w, B, BF16, L)
+    assert rc == oracle.OK
+    tuples = oracle.block_tuples(s)
+    picked_other_than_16 = False
+    for k, (b, n, m) in enumerate(tuples):
+        blk = w[k * B:(k + 1) * B]
+        x = ((blk >> 7) & 0xFF).astype(np.int64)
+        y = (b - x) % (1 << n)
+        bits = [1.0 / L + n + (mm - n) * (np.count_nonzero(y < (1 << mm)) / blk.size) ** L for mm in range(n + 1)]
+        assert bits[m] <= min(bits) + 1e-12 and all(bits[mm] > bits[m] for mm in range(m)), (k, m, bits)
+        # the bytes the codec spends on this block with every m: the chosen one is the smallest (Gaussian blocks are
+        # close enough to independent draws for Eq. 4's expectation to rank the candidates as the real sizes do)
+        spent = [oracle.compress(blk, (b, n, mm, L), B)[1].size for mm in range(n + 1)]
+        assert spent[m] <= min(spent) * 1.003, (k, m, spent)
+        picked_other_than_16 |= m != oracle.tune(blk)[2]
+    if L == 32:
+        assert picked_other_than_16         # the block of two scales takes m = 4 here, Eq. 4 at L = 16 would give 3
