@@ -327,6 +327,242 @@ struct DecompressArgs {
     DecompressItem item[MAX_BATCH];
 };
 
+// ---------------------------------------------------------------------------------
+// a5: one record per masked group (Sec. V-B: the high n - m bits of a group that needs them, packed by
+// Alg. 2 with N = L), written into the LDS image at the group's rank among the block's masked groups.
+// HI[t][h] = high parts of this thread's eight elements of row t in byte lanes; my_word / my_excl = the
+// wave's copy of the mask words and of their exclusive popcount prefix.  Shared by the kernels for one
+// tuple per tensor and for one tuple per data block.
+// ---------------------------------------------------------------------------------
+template <int A, int LPG>
+__device__ __forceinline__ void pack_records(const uint32_t (&HI)[8][2], uint32_t my_word, uint32_t my_excl,
+                                             uint8_t *img_high, uint32_t logC, uint32_t tid, bool active)
+{
+    constexpr HHTable TH = HH<A>::table;
+    constexpr uint32_t RB = A * LPG;                     // bytes of one record: (n - m) L / 8
+    if constexpr (LPG == 1) {
+        // A group is this lane's 8 elements of a row, and Alg. 2 with N = 8 is the column map
+        // itself.  The lane's 8 x 8 bytes (row = group, byte = element) are transposed, so that
+        // one register holds the same element of four groups and the eight groups are packed at
+        // once in byte lanes; A normalized bytes per group are then joined (byte i with byte
+        // i + ceil(A/2)), the pad byte of an odd count is dropped.
+        constexpr int HALF = (A + 1) / 2;
+        uint32_t T[8][2];                 // T[element][k]: groups 4k .. 4k+3
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t r0 = HI[4 * k][h], r1 = HI[4 * k + 1][h], r2 = HI[4 * k + 2][h], r3 = HI[4 * k + 3][h];
+                const uint32_t lo01 = byte_perm(r1, r0, 0x05010400u), hi01 = byte_perm(r1, r0, 0x07030602u);
+                const uint32_t lo23 = byte_perm(r3, r2, 0x05010400u), hi23 = byte_perm(r3, r2, 0x07030602u);
+                T[4 * h][k] = byte_perm(lo23, lo01, 0x05040100u);
+                T[4 * h + 1][k] = byte_perm(lo23, lo01, 0x07060302u);
+                T[4 * h + 2][k] = byte_perm(hi23, hi01, 0x05040100u);
+                T[4 * h + 3][k] = byte_perm(hi23, hi01, 0x07060302u);
+            }
+        uint32_t P[A + 1][2];            // normalized byte q of groups 4k .. 4k+3 (P[A] = the pad)
+#pragma unroll
+        for (int q = 0; q <= A; ++q) P[q][0] = P[q][1] = 0;
+#pragma unroll
+        for (int f = 0; f < TH.count; ++f)
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+                P[TH.plane[f]][k] |= shl_or_shr(T[TH.row[f]][k], TH.shift[f]) & (TH.dmask[f] * 0x01010101u);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const uint32_t g = ((uint32_t)t << (logC - 3)) + tid;
+            const uint32_t wv = mask_word_lane<LPG>(my_word, g >> 5);
+            const uint32_t pre = mask_word_lane<LPG>(my_excl, g >> 5);
+            if (active && ((wv >> (g & 31u)) & 1u)) {
+                const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+                uint8_t *dst = img_high + RB * rank;
+#pragma unroll
+                for (int j = 0; j < A; ++j)
+                    dst[j] = (uint8_t)(P[(j & 1) ? (j >> 1) + HALF : (j >> 1)][t >> 2] >> (8 * (t & 3)));
+            }
+        }
+    } else if constexpr (LPG == 2) {
+        const uint32_t par = tid & 1u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            // even lanes pack the group of row 2u, odd lanes the group of row 2u+1
+            const uint32_t own0 = par ? HI[2 * u + 1][0] : HI[2 * u][0];
+            const uint32_t own1 = par ? HI[2 * u + 1][1] : HI[2 * u][1];
+            const uint32_t snd0 = par ? HI[2 * u][0] : HI[2 * u + 1][0];
+            const uint32_t snd1 = par ? HI[2 * u][1] : HI[2 * u + 1][1];
+            const uint32_t rcv0 = swap_pair(snd0);
+            const uint32_t rcv1 = swap_pair(snd1);
+            uint32_t F[4];
+            F[0] = par ? rcv0 : own0;
+            F[1] = par ? rcv1 : own1;
+            F[2] = par ? own0 : rcv0;
+            F[3] = par ? own1 : rcv1;
+            const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
+            // even and odd lanes look at the groups of two rows: two wave-uniform word indices
+            const uint32_t w_even = (((2u * u) << (logC - 4)) + (tid >> 1)) >> 5;
+            const uint32_t w_odd = (((2u * u + 1u) << (logC - 4)) + (tid >> 1)) >> 5;
+            const uint32_t wv_e = mask_word_lane<LPG>(my_word, w_even), wv_o = mask_word_lane<LPG>(my_word, w_odd);
+            const uint32_t pre_e = mask_word_lane<LPG>(my_excl, w_even), pre_o = mask_word_lane<LPG>(my_excl, w_odd);
+            const uint32_t wv = par ? wv_o : wv_e;
+            const uint32_t pre = par ? pre_o : pre_e;
+            const uint32_t bit = (wv >> (g & 31u)) & 1u;
+            if (active && bit) {
+                const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+                // the group's 16 values are 2 columns of 8 rows: row r = bytes (2r, 2r+1)
+                uint32_t P[A];
+#pragma unroll
+                for (int q = 0; q < A; ++q) P[q] = 0;
+#pragma unroll
+                for (int f = 0; f < TH.count; ++f) {
+                    const int r = TH.row[f];
+                    const uint32_t s = shl_or_shr(F[r >> 1], TH.shift[f] - 16 * (r & 1));
+                    P[TH.plane[f]] |= s & (TH.dmask[f] * 0x0101u);
+                }
+                // normalized byte j = byte (j & 1) of P[j >> 1]; stream word i = nb[i] | nb[i + A] << 8
+                uint16_t *dst = reinterpret_cast<uint16_t *>(img_high + 2u * A * rank);
+#pragma unroll
+                for (int i = 0; i < A; ++i) {
+                    const uint32_t lo = (P[i >> 1] >> (8 * (i & 1))) & 0xFFu;
+                    const uint32_t hi = (P[(i + A) >> 1] >> (8 * ((i + A) & 1))) & 0xFFu;
+                    dst[i] = (uint16_t)(lo | (hi << 8));
+                }
+            }
+        }
+    } else {
+        // a group is the 32 elements of a quad: seen as 8 rows of 4 columns (element i = row i / 4,
+        // column i % 4) Alg. 2's folds again stay inside a column; lane j holds rows 2j and 2j+1
+        const uint32_t j = tid & 3u;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const uint32_t g = ((uint32_t)t << (logC - 5)) + (tid >> 2);
+            const uint32_t wv = mask_word_lane<LPG>(my_word, g >> 5);
+            const uint32_t pre = mask_word_lane<LPG>(my_excl, g >> 5);
+            if (active && ((wv >> (g & 31u)) & 1u)) {
+                const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+                uint32_t P[A];
+#pragma unroll
+                for (int q = 0; q < A; ++q) P[q] = 0;
+#pragma unroll
+                for (int f = 0; f < TH.count; ++f) {
+                    const int r = TH.row[f];
+                    const uint32_t c = shl_or_shr(HI[t][r & 1], TH.shift[f]) & (TH.dmask[f] * 0x01010101u);
+                    P[TH.plane[f]] |= ((uint32_t)(r >> 1) == j) ? c : 0u;
+                }
+#pragma unroll
+                for (int q = 0; q < A; ++q) P[q] = quad_or(P[q]);
+                if (j == 0) {
+                    // normalized byte 4q + c = byte c of P[q]; stream word i = nb[i] | nb[i + 2A] << 8
+                    uint32_t *dst = reinterpret_cast<uint32_t *>(img_high + RB * rank);
+#pragma unroll
+                    for (int k = 0; k < A; ++k) {
+                        const int i0 = 2 * k, i1 = 2 * k + 1, h0 = i0 + 2 * A, h1 = i1 + 2 * A;
+                        const uint32_t b0 = (P[i0 >> 2] >> (8 * (i0 & 3))) & 0xFFu;
+                        const uint32_t b1 = (P[h0 >> 2] >> (8 * (h0 & 3))) & 0xFFu;
+                        const uint32_t b2 = (P[i1 >> 2] >> (8 * (i1 & 3))) & 0xFFu;
+                        const uint32_t b3 = (P[h1 >> 2] >> (8 * (h1 & 3))) & 0xFFu;
+                        dst[k] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// d3: the inverse for row t: the high parts of this thread's eight elements (zero if the group has no record)
+template <int A, int LPG>
+__device__ __forceinline__ void unpack_record_row(const uint8_t *img_high, uint32_t my_word, uint32_t my_excl,
+                                                  uint32_t logC, uint32_t tid, int t, uint32_t &h0, uint32_t &h1)
+{
+    constexpr HHTable TH = HH<A>::table;
+    constexpr int LOG_LPG = LPG == 4 ? 2 : LPG - 1;
+    constexpr uint32_t RB = A * LPG;
+    h0 = h1 = 0;
+    const uint32_t g = ((uint32_t)t << (logC - 3 - LOG_LPG)) + (tid >> LOG_LPG);
+    const uint32_t wv = mask_word_lane<LPG>(my_word, g >> 5);
+    const uint32_t pre = mask_word_lane<LPG>(my_excl, g >> 5);
+    if ((wv >> (g & 31u)) & 1u) {
+        const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
+        const uint8_t *rec8 = img_high + RB * rank;
+        if constexpr (LPG == 1) {
+            // this lane's 8 elements are the group: stream byte j is normalized byte j/2
+            // (even j) or j/2 + ceil(A/2) (odd j), the dropped pad byte is zero
+            constexpr int HALF = (A + 1) / 2;
+            uint32_t P[A + 1];
+#pragma unroll
+            for (int q = 0; q <= A; ++q) P[q] = 0;
+#pragma unroll
+            for (int j = 0; j < A; ++j) P[(j & 1) ? (j >> 1) + HALF : (j >> 1)] = rec8[j];
+            uint32_t h[2] = {0u, 0u};
+#pragma unroll
+            for (int f = 0; f < TH.count; ++f) {
+                const int r = TH.row[f];
+                const uint32_t smask = TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
+                                                        : (TH.dmask[f] << (-TH.shift[f]));
+                h[r >> 2] |= (shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask) << (8 * (r & 3));
+            }
+            h0 = h[0];
+            h1 = h[1];
+        } else if constexpr (LPG == 2) {
+            const uint32_t par = tid & 1u;
+            const uint16_t *rec = reinterpret_cast<const uint16_t *>(rec8);
+            uint32_t nbyte[2 * A];
+#pragma unroll
+            for (int i = 0; i < A; ++i) {
+                const uint32_t w = rec[i];
+                nbyte[i] = w & 0xFFu;
+                nbyte[i + A] = w >> 8;
+            }
+            uint32_t P[A];
+#pragma unroll
+            for (int q = 0; q < A; ++q) P[q] = 0;
+#pragma unroll
+            for (int j = 0; j < 2 * A; ++j) P[j >> 1] |= nbyte[j] << (8 * (j & 1));
+            uint32_t E[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) E[r] = 0;
+#pragma unroll
+            for (int f = 0; f < TH.count; ++f) {
+                const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
+                                                        : (TH.dmask[f] << (-TH.shift[f]))) * 0x0101u;
+                E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
+            }
+            // this lane's 8 elements are rows 4*par .. 4*par+3 of the two-column view
+            h0 = par ? (E[4] | (E[5] << 16)) : (E[0] | (E[1] << 16));
+            h1 = par ? (E[6] | (E[7] << 16)) : (E[2] | (E[3] << 16));
+        } else {
+            // the quad's group as 8 rows of 4 columns: stream word i = normalized byte i |
+            // normalized byte i + 2A << 8, normalized byte 4q + c = byte c of plane q
+            const uint32_t *rec = reinterpret_cast<const uint32_t *>(rec8);
+            uint32_t nbyte[4 * A];
+#pragma unroll
+            for (int k = 0; k < A; ++k) {
+                const uint32_t w = rec[k];
+                nbyte[2 * k] = w & 0xFFu;
+                nbyte[2 * k + 2 * A] = (w >> 8) & 0xFFu;
+                nbyte[2 * k + 1] = (w >> 16) & 0xFFu;
+                nbyte[2 * k + 1 + 2 * A] = w >> 24;
+            }
+            uint32_t P[A];
+#pragma unroll
+            for (int q = 0; q < A; ++q)
+                P[q] = nbyte[4 * q] | (nbyte[4 * q + 1] << 8) | (nbyte[4 * q + 2] << 16) | (nbyte[4 * q + 3] << 24);
+            uint32_t E[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) E[r] = 0;
+#pragma unroll
+            for (int f = 0; f < TH.count; ++f) {
+                const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
+                                                        : (TH.dmask[f] << (-TH.shift[f]))) * 0x01010101u;
+                E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
+            }
+            // lane j of the quad holds rows 2j and 2j+1
+            const uint32_t j = tid & 3u;
+            h0 = j == 0 ? E[0] : (j == 1 ? E[2] : (j == 2 ? E[4] : E[6]));
+            h1 = j == 0 ? E[1] : (j == 1 ? E[3] : (j == 2 ? E[5] : E[7]));
+        }
+    }
+}
+
 // a1: 128-bit loads of the 8 rows of data block k (pad elements beyond the tensor's end); a
 // thread's 8 elements of a row are one vector (16-bit formats) or two (fp32)
 template <int DT>
@@ -773,135 +1009,7 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         // ---- a5: one record per masked group ------------------------------------------
-        if (A > 0) {
-            constexpr HHTable TH = HH<A>::table;
-            if constexpr (LPG == 1) {
-                // A group is this lane's 8 elements of a row, and Alg. 2 with N = 8 is the column map
-                // itself.  The lane's 8 x 8 bytes (row = group, byte = element) are transposed, so that
-                // one register holds the same element of four groups and the eight groups are packed at
-                // once in byte lanes; A normalized bytes per group are then joined (byte i with byte
-                // i + ceil(A/2)), the pad byte of an odd count is dropped.
-                constexpr int HALF = (A + 1) / 2;
-                uint32_t T[8][2];                 // T[element][k]: groups 4k .. 4k+3
-#pragma unroll
-                for (int k = 0; k < 2; ++k)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const uint32_t r0 = HI[4 * k][h], r1 = HI[4 * k + 1][h], r2 = HI[4 * k + 2][h], r3 = HI[4 * k + 3][h];
-                        const uint32_t lo01 = byte_perm(r1, r0, 0x05010400u), hi01 = byte_perm(r1, r0, 0x07030602u);
-                        const uint32_t lo23 = byte_perm(r3, r2, 0x05010400u), hi23 = byte_perm(r3, r2, 0x07030602u);
-                        T[4 * h][k] = byte_perm(lo23, lo01, 0x05040100u);
-                        T[4 * h + 1][k] = byte_perm(lo23, lo01, 0x07060302u);
-                        T[4 * h + 2][k] = byte_perm(hi23, hi01, 0x05040100u);
-                        T[4 * h + 3][k] = byte_perm(hi23, hi01, 0x07060302u);
-                    }
-                uint32_t P[AP + 1][2];            // normalized byte q of groups 4k .. 4k+3 (P[A] = the pad)
-#pragma unroll
-                for (int q = 0; q <= AP; ++q) P[q][0] = P[q][1] = 0;
-#pragma unroll
-                for (int f = 0; f < TH.count; ++f)
-#pragma unroll
-                    for (int k = 0; k < 2; ++k)
-                        P[TH.plane[f]][k] |= shl_or_shr(T[TH.row[f]][k], TH.shift[f]) & (TH.dmask[f] * 0x01010101u);
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const uint32_t g = ((uint32_t)t << (logC - 3)) + tid;
-                    const uint32_t wv = mask_word_lane<LPG>(my_word, g >> 5);
-                    const uint32_t pre = mask_word_lane<LPG>(my_excl, g >> 5);
-                    if (active && ((wv >> (g & 31u)) & 1u)) {
-                        const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                        uint8_t *dst = img_high + RB * rank;
-#pragma unroll
-                        for (int j = 0; j < A; ++j)
-                            dst[j] = (uint8_t)(P[(j & 1) ? (j >> 1) + HALF : (j >> 1)][t >> 2] >> (8 * (t & 3)));
-                    }
-                }
-            } else if constexpr (LPG == 2) {
-                const uint32_t par = tid & 1u;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    // even lanes pack the group of row 2u, odd lanes the group of row 2u+1
-                    const uint32_t own0 = par ? HI[2 * u + 1][0] : HI[2 * u][0];
-                    const uint32_t own1 = par ? HI[2 * u + 1][1] : HI[2 * u][1];
-                    const uint32_t snd0 = par ? HI[2 * u][0] : HI[2 * u + 1][0];
-                    const uint32_t snd1 = par ? HI[2 * u][1] : HI[2 * u + 1][1];
-                    const uint32_t rcv0 = swap_pair(snd0);
-                    const uint32_t rcv1 = swap_pair(snd1);
-                    uint32_t F[4];
-                    F[0] = par ? rcv0 : own0;
-                    F[1] = par ? rcv1 : own1;
-                    F[2] = par ? own0 : rcv0;
-                    F[3] = par ? own1 : rcv1;
-                    const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
-                    // even and odd lanes look at the groups of two rows: two wave-uniform word indices
-                    const uint32_t w_even = (((2u * u) << (logC - 4)) + (tid >> 1)) >> 5;
-                    const uint32_t w_odd = (((2u * u + 1u) << (logC - 4)) + (tid >> 1)) >> 5;
-                    const uint32_t wv_e = mask_word_lane<LPG>(my_word, w_even), wv_o = mask_word_lane<LPG>(my_word, w_odd);
-                    const uint32_t pre_e = mask_word_lane<LPG>(my_excl, w_even), pre_o = mask_word_lane<LPG>(my_excl, w_odd);
-                    const uint32_t wv = par ? wv_o : wv_e;
-                    const uint32_t pre = par ? pre_o : pre_e;
-                    const uint32_t bit = (wv >> (g & 31u)) & 1u;
-                    if (active && bit) {
-                        const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                        // the group's 16 values are 2 columns of 8 rows: row r = bytes (2r, 2r+1)
-                        uint32_t P[AP];
-#pragma unroll
-                        for (int q = 0; q < AP; ++q) P[q] = 0;
-#pragma unroll
-                        for (int f = 0; f < TH.count; ++f) {
-                            const int r = TH.row[f];
-                            const uint32_t s = shl_or_shr(F[r >> 1], TH.shift[f] - 16 * (r & 1));
-                            P[TH.plane[f]] |= s & (TH.dmask[f] * 0x0101u);
-                        }
-                        // normalized byte j = byte (j & 1) of P[j >> 1]; stream word i = nb[i] | nb[i + A] << 8
-                        uint16_t *dst = reinterpret_cast<uint16_t *>(img_high + 2u * A * rank);
-#pragma unroll
-                        for (int i = 0; i < A; ++i) {
-                            const uint32_t lo = (P[i >> 1] >> (8 * (i & 1))) & 0xFFu;
-                            const uint32_t hi = (P[(i + A) >> 1] >> (8 * ((i + A) & 1))) & 0xFFu;
-                            dst[i] = (uint16_t)(lo | (hi << 8));
-                        }
-                    }
-                }
-            } else {
-                // a group is the 32 elements of a quad: seen as 8 rows of 4 columns (element i = row i / 4,
-                // column i % 4) Alg. 2's folds again stay inside a column; lane j holds rows 2j and 2j+1
-                const uint32_t j = tid & 3u;
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const uint32_t g = ((uint32_t)t << (logC - 5)) + (tid >> 2);
-                    const uint32_t wv = mask_word_lane<LPG>(my_word, g >> 5);
-                    const uint32_t pre = mask_word_lane<LPG>(my_excl, g >> 5);
-                    if (active && ((wv >> (g & 31u)) & 1u)) {
-                        const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                        uint32_t P[AP];
-#pragma unroll
-                        for (int q = 0; q < AP; ++q) P[q] = 0;
-#pragma unroll
-                        for (int f = 0; f < TH.count; ++f) {
-                            const int r = TH.row[f];
-                            const uint32_t c = shl_or_shr(HI[t][r & 1], TH.shift[f]) & (TH.dmask[f] * 0x01010101u);
-                            P[TH.plane[f]] |= ((uint32_t)(r >> 1) == j) ? c : 0u;
-                        }
-#pragma unroll
-                        for (int q = 0; q < A; ++q) P[q] = quad_or(P[q]);
-                        if (j == 0) {
-                            // normalized byte 4q + c = byte c of P[q]; stream word i = nb[i] | nb[i + 2A] << 8
-                            uint32_t *dst = reinterpret_cast<uint32_t *>(img_high + RB * rank);
-#pragma unroll
-                            for (int k = 0; k < A; ++k) {
-                                const int i0 = 2 * k, i1 = 2 * k + 1, h0 = i0 + 2 * A, h1 = i1 + 2 * A;
-                                const uint32_t b0 = (P[i0 >> 2] >> (8 * (i0 & 3))) & 0xFFu;
-                                const uint32_t b1 = (P[h0 >> 2] >> (8 * (h0 & 3))) & 0xFFu;
-                                const uint32_t b2 = (P[i1 >> 2] >> (8 * (i1 & 3))) & 0xFFu;
-                                const uint32_t b3 = (P[h1 >> 2] >> (8 * (h1 & 3))) & 0xFFu;
-                                dst[k] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
-                            }
-                        }
-                    }
-                }
-            }
-        }
+        if constexpr (A > 0) pack_records<A, LPG>(HI, my_word, my_excl, img_high, logC, tid, active);
 
         // ---- a6 (wave 0): the start of the block stored in this iteration -----------------
         if (wave == 0 && pend != NO_BLOCK) {
@@ -1173,96 +1281,11 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
                     }
                 }
                 // d2/d3: high bits of masked groups, found through the mask prefix
-                if (A > 0) {
-                    constexpr HHTable TH = HH<A>::table;
-                    const uint32_t g = ((uint32_t)t << (logC - 3 - LOG_LPG)) + (tid >> LOG_LPG);
-                    const uint32_t wv = mask_word_lane<LPG>(my_word, g >> 5);
-                    const uint32_t pre = mask_word_lane<LPG>(my_excl, g >> 5);
-                    if ((wv >> (g & 31u)) & 1u) {
-                        const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                        const uint8_t *rec8 = img_high + RB * rank;
-                        if constexpr (LPG == 1) {
-                            // this lane's 8 elements are the group: stream byte j is normalized byte j/2
-                            // (even j) or j/2 + ceil(A/2) (odd j), the dropped pad byte is zero
-                            constexpr int HALF = (A + 1) / 2;
-                            uint32_t P[AP + 1];
-#pragma unroll
-                            for (int q = 0; q <= AP; ++q) P[q] = 0;
-#pragma unroll
-                            for (int j = 0; j < A; ++j) P[(j & 1) ? (j >> 1) + HALF : (j >> 1)] = rec8[j];
-                            uint32_t h[2] = {0u, 0u};
-#pragma unroll
-                            for (int f = 0; f < TH.count; ++f) {
-                                const int r = TH.row[f];
-                                const uint32_t smask = TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
-                                                                        : (TH.dmask[f] << (-TH.shift[f]));
-                                h[r >> 2] |= (shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask) << (8 * (r & 3));
-                            }
-                            Y[0] |= h[0] << M;
-                            Y[1] |= h[1] << M;
-                        } else if constexpr (LPG == 2) {
-                            const uint32_t par = tid & 1u;
-                            const uint16_t *rec = reinterpret_cast<const uint16_t *>(rec8);
-                            uint32_t nbyte[2 * AP];
-#pragma unroll
-                            for (int i = 0; i < A; ++i) {
-                                const uint32_t w = rec[i];
-                                nbyte[i] = w & 0xFFu;
-                                nbyte[i + A] = w >> 8;
-                            }
-                            uint32_t P[AP];
-#pragma unroll
-                            for (int q = 0; q < A; ++q) P[q] = 0;
-#pragma unroll
-                            for (int j = 0; j < 2 * A; ++j) P[j >> 1] |= nbyte[j] << (8 * (j & 1));
-                            uint32_t E[8];
-#pragma unroll
-                            for (int r = 0; r < 8; ++r) E[r] = 0;
-#pragma unroll
-                            for (int f = 0; f < TH.count; ++f) {
-                                const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
-                                                                        : (TH.dmask[f] << (-TH.shift[f]))) * 0x0101u;
-                                E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
-                            }
-                            // this lane's 8 elements are rows 4*par .. 4*par+3 of the two-column view
-                            const uint32_t h0 = par ? (E[4] | (E[5] << 16)) : (E[0] | (E[1] << 16));
-                            const uint32_t h1 = par ? (E[6] | (E[7] << 16)) : (E[2] | (E[3] << 16));
-                            Y[0] |= h0 << M;
-                            Y[1] |= h1 << M;
-                        } else {
-                            // the quad's group as 8 rows of 4 columns: stream word i = normalized byte i |
-                            // normalized byte i + 2A << 8, normalized byte 4q + c = byte c of plane q
-                            const uint32_t *rec = reinterpret_cast<const uint32_t *>(rec8);
-                            uint32_t nbyte[4 * AP];
-#pragma unroll
-                            for (int k = 0; k < A; ++k) {
-                                const uint32_t w = rec[k];
-                                nbyte[2 * k] = w & 0xFFu;
-                                nbyte[2 * k + 2 * A] = (w >> 8) & 0xFFu;
-                                nbyte[2 * k + 1] = (w >> 16) & 0xFFu;
-                                nbyte[2 * k + 1 + 2 * A] = w >> 24;
-                            }
-                            uint32_t P[AP];
-#pragma unroll
-                            for (int q = 0; q < A; ++q)
-                                P[q] = nbyte[4 * q] | (nbyte[4 * q + 1] << 8) | (nbyte[4 * q + 2] << 16) | (nbyte[4 * q + 3] << 24);
-                            uint32_t E[8];
-#pragma unroll
-                            for (int r = 0; r < 8; ++r) E[r] = 0;
-#pragma unroll
-                            for (int f = 0; f < TH.count; ++f) {
-                                const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f])
-                                                                        : (TH.dmask[f] << (-TH.shift[f]))) * 0x01010101u;
-                                E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
-                            }
-                            // lane j of the quad holds rows 2j and 2j+1
-                            const uint32_t j = tid & 3u;
-                            const uint32_t h0 = j == 0 ? E[0] : (j == 1 ? E[2] : (j == 2 ? E[4] : E[6]));
-                            const uint32_t h1 = j == 0 ? E[1] : (j == 1 ? E[3] : (j == 2 ? E[5] : E[7]));
-                            Y[0] |= h0 << M;
-                            Y[1] |= h1 << M;
-                        }
-                    }
+                if constexpr (A > 0) {
+                    uint32_t h0, h1;
+                    unpack_record_row<A, LPG>(img_high, my_word, my_excl, logC, tid, t, h0, h1);
+                    Y[0] |= h0 << M;
+                    Y[1] |= h1 << M;
                 }
                 // d4: x = b - sext_n(y) = (b + 2^(n-1)) - (y ^ 2^(n-1)); recombine with sign/mantissa
                 uint32_t o[4];

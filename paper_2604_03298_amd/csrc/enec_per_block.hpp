@@ -78,225 +78,16 @@ __device__ __forceinline__ void pb_unpack_low(const uint8_t *img_low, uint32_t B
     }
 }
 
-// Alg. 2 over the high parts of every masked group; rank = position of the record among the block's
-// records.  LPG = lanes per group:
-//   1 (L = 8)   a group is this lane's 8 elements of a row: the lane's 8 x 8 bytes are transposed and
-//               its eight groups are packed at once in byte lanes; the pad byte of an odd count is dropped
-//   2 (L = 16)  the 16 elements of two neighbouring lanes in one row, seen as 8 rows of 2 columns; even
-//               lanes pack the group of row 2u, odd lanes that of row 2u + 1
-//   4 (L = 32)  the 32 elements of a quad, seen as 8 rows of 4 columns; lane j holds rows 2j and 2j + 1,
-//               contributes them under a predicate, two DPP ORs per plane assemble the record
-template <int A, int LPG>
-__device__ __forceinline__ void pb_pack_records(const uint32_t (&HI)[8][2], uint32_t my_word, uint32_t my_excl,
-                                                uint8_t *img_high, uint32_t logC, uint32_t tid, bool active)
-{
-    constexpr HHTable TH = HH<A>::table;
-    constexpr uint32_t RB = A * LPG;
-    if constexpr (LPG == 1) {
-        constexpr int HALF = (A + 1) / 2;
-        uint32_t T[8][2];                 // T[element][k]: groups 4k .. 4k+3
-#pragma unroll
-        for (int k = 0; k < 2; ++k)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t r0 = HI[4 * k][h], r1 = HI[4 * k + 1][h], r2 = HI[4 * k + 2][h], r3 = HI[4 * k + 3][h];
-                const uint32_t lo01 = byte_perm(r1, r0, 0x05010400u), hi01 = byte_perm(r1, r0, 0x07030602u);
-                const uint32_t lo23 = byte_perm(r3, r2, 0x05010400u), hi23 = byte_perm(r3, r2, 0x07030602u);
-                T[4 * h][k] = byte_perm(lo23, lo01, 0x05040100u);
-                T[4 * h + 1][k] = byte_perm(lo23, lo01, 0x07060302u);
-                T[4 * h + 2][k] = byte_perm(hi23, hi01, 0x05040100u);
-                T[4 * h + 3][k] = byte_perm(hi23, hi01, 0x07060302u);
-            }
-        uint32_t P[A + 1][2];             // normalized byte q of groups 4k .. 4k+3 (P[A] = the pad)
-#pragma unroll
-        for (int q = 0; q <= A; ++q) P[q][0] = P[q][1] = 0;
-#pragma unroll
-        for (int f = 0; f < TH.count; ++f)
-#pragma unroll
-            for (int k = 0; k < 2; ++k)
-                P[TH.plane[f]][k] |= shl_or_shr(T[TH.row[f]][k], TH.shift[f]) & (TH.dmask[f] * 0x01010101u);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const uint32_t g = ((uint32_t)t << (logC - 3)) + tid;
-            const uint32_t wv = __shfl(my_word, g >> 5, 64);
-            const uint32_t pre = __shfl(my_excl, g >> 5, 64);
-            if (active && ((wv >> (g & 31u)) & 1u)) {
-                const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                uint8_t *dst = img_high + RB * rank;
-#pragma unroll
-                for (int j = 0; j < A; ++j)
-                    dst[j] = (uint8_t)(P[(j & 1) ? (j >> 1) + HALF : (j >> 1)][t >> 2] >> (8 * (t & 3)));
-            }
-        }
-    } else if constexpr (LPG == 2) {
-        const uint32_t par = tid & 1u;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t own0 = par ? HI[2 * u + 1][0] : HI[2 * u][0];
-            const uint32_t own1 = par ? HI[2 * u + 1][1] : HI[2 * u][1];
-            const uint32_t snd0 = par ? HI[2 * u][0] : HI[2 * u + 1][0];
-            const uint32_t snd1 = par ? HI[2 * u][1] : HI[2 * u + 1][1];
-            const uint32_t rcv0 = swap_pair(snd0);
-            const uint32_t rcv1 = swap_pair(snd1);
-            uint32_t F[4];
-            F[0] = par ? rcv0 : own0;
-            F[1] = par ? rcv1 : own1;
-            F[2] = par ? own0 : rcv0;
-            F[3] = par ? own1 : rcv1;
-            const uint32_t g = ((2u * u + par) << (logC - 4)) + (tid >> 1);
-            const uint32_t wv = __shfl(my_word, g >> 5, 64);
-            const uint32_t pre = __shfl(my_excl, g >> 5, 64);
-            if (active && ((wv >> (g & 31u)) & 1u)) {
-                const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                uint32_t P[A];
-#pragma unroll
-                for (int q = 0; q < A; ++q) P[q] = 0;
-#pragma unroll
-                for (int f = 0; f < TH.count; ++f) {
-                    const int r = TH.row[f];
-                    const uint32_t s = shl_or_shr(F[r >> 1], TH.shift[f] - 16 * (r & 1));
-                    P[TH.plane[f]] |= s & (TH.dmask[f] * 0x0101u);
-                }
-                // normalized byte j = byte (j & 1) of P[j >> 1]; stream word i = nb[i] | nb[i + A] << 8
-                uint16_t *dst = reinterpret_cast<uint16_t *>(img_high + RB * rank);
-#pragma unroll
-                for (int i = 0; i < A; ++i) {
-                    const uint32_t lo = (P[i >> 1] >> (8 * (i & 1))) & 0xFFu;
-                    const uint32_t hi = (P[(i + A) >> 1] >> (8 * ((i + A) & 1))) & 0xFFu;
-                    dst[i] = (uint16_t)(lo | (hi << 8));
-                }
-            }
-        }
-    } else {
-        const uint32_t j = tid & 3u;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const uint32_t g = ((uint32_t)t << (logC - 5)) + (tid >> 2);
-            const uint32_t wv = __shfl(my_word, g >> 5, 64);
-            const uint32_t pre = __shfl(my_excl, g >> 5, 64);
-            if (active && ((wv >> (g & 31u)) & 1u)) {
-                const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-                uint32_t P[A];
-#pragma unroll
-                for (int q = 0; q < A; ++q) P[q] = 0;
-#pragma unroll
-                for (int f = 0; f < TH.count; ++f) {
-                    const int r = TH.row[f];
-                    const uint32_t c = shl_or_shr(HI[t][r & 1], TH.shift[f]) & (TH.dmask[f] * 0x01010101u);
-                    P[TH.plane[f]] |= ((uint32_t)(r >> 1) == j) ? c : 0u;
-                }
-#pragma unroll
-                for (int q = 0; q < A; ++q) P[q] = quad_or(P[q]);
-                if (j == 0) {
-                    // normalized byte 4q + c = byte c of P[q]; stream word i = nb[i] | nb[i + 2A] << 8
-                    uint32_t *dst = reinterpret_cast<uint32_t *>(img_high + RB * rank);
-#pragma unroll
-                    for (int k = 0; k < A; ++k) {
-                        const int i0 = 2 * k, i1 = 2 * k + 1, h0 = i0 + 2 * A, h1 = i1 + 2 * A;
-                        const uint32_t b0 = (P[i0 >> 2] >> (8 * (i0 & 3))) & 0xFFu;
-                        const uint32_t b1 = (P[h0 >> 2] >> (8 * (h0 & 3))) & 0xFFu;
-                        const uint32_t b2 = (P[i1 >> 2] >> (8 * (i1 & 3))) & 0xFFu;
-                        const uint32_t b3 = (P[h1 >> 2] >> (8 * (h1 & 3))) & 0xFFu;
-                        dst[k] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
-                    }
-                }
-            }
-        }
-    }
-}
-
-// the inverse for this thread's 8 rows: HI[t][h] = high parts (zero for groups without a record)
+// The records of the masked groups are packed and unpacked by pack_records / unpack_record_row of
+// enec_device.hpp, the functions the kernels for one tuple per tensor use.
 template <int A, int LPG>
 __device__ __forceinline__ void pb_unpack_records(const uint8_t *img_high, uint32_t my_word, uint32_t my_excl,
                                                   uint32_t logC, uint32_t tid, uint32_t (&HI)[8][2])
 {
-    constexpr HHTable TH = HH<A>::table;
-    constexpr int LOG_LPG = LPG == 4 ? 2 : LPG - 1;
-    constexpr uint32_t RB = A * LPG;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        HI[t][0] = HI[t][1] = 0;
-        const uint32_t g = ((uint32_t)t << (logC - 3 - LOG_LPG)) + (tid >> LOG_LPG);
-        const uint32_t wv = __shfl(my_word, g >> 5, 64);
-        const uint32_t pre = __shfl(my_excl, g >> 5, 64);
-        if ((wv >> (g & 31u)) & 1u) {
-            const uint32_t rank = pre + __popc(wv & ((1u << (g & 31u)) - 1u));
-            const uint8_t *rec8 = img_high + RB * rank;
-            if constexpr (LPG == 1) {
-                // stream byte j is normalized byte j/2 (even j) or j/2 + ceil(A/2) (odd j); the dropped pad byte is zero
-                constexpr int HALF = (A + 1) / 2;
-                uint32_t P[A + 1];
-#pragma unroll
-                for (int q = 0; q <= A; ++q) P[q] = 0;
-#pragma unroll
-                for (int j = 0; j < A; ++j) P[(j & 1) ? (j >> 1) + HALF : (j >> 1)] = rec8[j];
-                uint32_t h[2] = {0u, 0u};
-#pragma unroll
-                for (int f = 0; f < TH.count; ++f) {
-                    const int r = TH.row[f];
-                    const uint32_t smask = TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f]) : (TH.dmask[f] << (-TH.shift[f]));
-                    h[r >> 2] |= (shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask) << (8 * (r & 3));
-                }
-                HI[t][0] = h[0];
-                HI[t][1] = h[1];
-            } else if constexpr (LPG == 2) {
-                const uint32_t par = tid & 1u;
-                const uint16_t *rec = reinterpret_cast<const uint16_t *>(rec8);
-                uint32_t nbyte[2 * A];
-#pragma unroll
-                for (int i = 0; i < A; ++i) {
-                    const uint32_t w = rec[i];
-                    nbyte[i] = w & 0xFFu;
-                    nbyte[i + A] = w >> 8;
-                }
-                uint32_t P[A];
-#pragma unroll
-                for (int q = 0; q < A; ++q) P[q] = 0;
-#pragma unroll
-                for (int j = 0; j < 2 * A; ++j) P[j >> 1] |= nbyte[j] << (8 * (j & 1));
-                uint32_t E[8];
-#pragma unroll
-                for (int r = 0; r < 8; ++r) E[r] = 0;
-#pragma unroll
-                for (int f = 0; f < TH.count; ++f) {
-                    const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f]) : (TH.dmask[f] << (-TH.shift[f]))) * 0x0101u;
-                    E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
-                }
-                // this lane's 8 elements are rows 4 par .. 4 par + 3 of the two-column view
-                HI[t][0] = par ? (E[4] | (E[5] << 16)) : (E[0] | (E[1] << 16));
-                HI[t][1] = par ? (E[6] | (E[7] << 16)) : (E[2] | (E[3] << 16));
-            } else {
-                // stream word i = normalized byte i | normalized byte i + 2A << 8, normalized byte 4q + c = byte c of plane q
-                const uint32_t *rec = reinterpret_cast<const uint32_t *>(rec8);
-                uint32_t nbyte[4 * A];
-#pragma unroll
-                for (int k = 0; k < A; ++k) {
-                    const uint32_t w = rec[k];
-                    nbyte[2 * k] = w & 0xFFu;
-                    nbyte[2 * k + 2 * A] = (w >> 8) & 0xFFu;
-                    nbyte[2 * k + 1] = (w >> 16) & 0xFFu;
-                    nbyte[2 * k + 1 + 2 * A] = w >> 24;
-                }
-                uint32_t P[A];
-#pragma unroll
-                for (int q = 0; q < A; ++q)
-                    P[q] = nbyte[4 * q] | (nbyte[4 * q + 1] << 8) | (nbyte[4 * q + 2] << 16) | (nbyte[4 * q + 3] << 24);
-                uint32_t E[8];
-#pragma unroll
-                for (int r = 0; r < 8; ++r) E[r] = 0;
-#pragma unroll
-                for (int f = 0; f < TH.count; ++f) {
-                    const uint32_t smask = (TH.shift[f] >= 0 ? (TH.dmask[f] >> TH.shift[f]) : (TH.dmask[f] << (-TH.shift[f]))) * 0x01010101u;
-                    E[TH.row[f]] |= shl_or_shr(P[TH.plane[f]], -TH.shift[f]) & smask;
-                }
-                // lane j of the quad holds rows 2j and 2j+1
-                const uint32_t j = tid & 3u;
-                HI[t][0] = j == 0 ? E[0] : (j == 1 ? E[2] : (j == 2 ? E[4] : E[6]));
-                HI[t][1] = j == 0 ? E[1] : (j == 1 ? E[3] : (j == 2 ? E[5] : E[7]));
-            }
-        }
-    }
+    for (int t = 0; t < 8; ++t) unpack_record_row<A, LPG>(img_high, my_word, my_excl, logC, tid, t, HI[t][0], HI[t][1]);
 }
+
 
 // Eq. 1: bits needed for the window [l, h] around b, capped by the exponent field
 __device__ __forceinline__ uint32_t pb_width_for(uint32_t b, uint32_t l, uint32_t h, uint32_t E)
@@ -608,14 +399,14 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
     if (tid == 0) st_state(p.words + k, PB_SIZE | (uint64_t)(S >> 4));
 
     switch (a) {
-    case 1: pb_pack_records<1, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 2: pb_pack_records<2, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 3: pb_pack_records<3, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 4: pb_pack_records<4, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 5: pb_pack_records<5, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 6: pb_pack_records<6, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 7: pb_pack_records<7, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 8: pb_pack_records<8, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 1: pack_records<1, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 2: pack_records<2, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 3: pack_records<3, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 4: pack_records<4, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 5: pack_records<5, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 6: pack_records<6, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 7: pack_records<7, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 8: pack_records<8, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
     default: break;
     }
 
