@@ -769,14 +769,15 @@ __global__ void __launch_bounds__(512) ENEC_COMPRESS_OCCUPANCY compress_kernel(c
                            uint32_t err_own) {
         const uint64_t off = s_off;
         uint8_t *dst = it.out + it.payload_base + off;
-        if (active) {
+        if constexpr (SM_IN_LDS) {
+            // the plane waits in LDS in element order and leaves as 128-bit vectors (four per thread
+            // instead of eight 64-bit stores of the thread's own bytes; measured neutral, within 1 %)
+            for (uint32_t v = tid; v < (B >> 4); v += blockDim.x)
+                *reinterpret_cast<uint4 *>(dst + 16u * v) = *reinterpret_cast<const uint4 *>(sm_wait + 16u * v);
+        } else if (active) {
 #pragma unroll
             for (int t = 0; t < 8; ++t)
-                if constexpr (SM_IN_LDS)
-                    *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) =
-                        *reinterpret_cast<const uint2 *>(sm_wait + ((size_t)t << logC) + 8u * tid);
-                else
-                    *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SMp[t][0], SMp[t][1]);
+                *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SMp[t][0], SMp[t][1]);
         }
         for (uint32_t v = tid; v < (mask_bytes >> 4); v += blockDim.x)
             *reinterpret_cast<uint4 *>(dst + B + 16u * v) = *reinterpret_cast<const uint4 *>(img + 16u * v);
