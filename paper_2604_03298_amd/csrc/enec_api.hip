@@ -648,11 +648,11 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
                                                L | 0x100u);
         return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
     }
-    // look-back words (and the ticket in front of them) behind the accumulators, cleared for this call
+    // look-back words (and the ticket counters in front of them) behind the accumulators, cleared for this call
     size_t first = ws_acc_words(workspace_bytes);
     first += first & 1;                                   // 16-byte aligned for the fill kernel
     const size_t words = ws_state_words(workspace_bytes);
-    const size_t counters = 2;                            // the ticket, in 8-byte words
+    const size_t counters = PB_TICKET_CLASSES * PB_TICKET_STRIDE / 2;      // in 8-byte words
     const size_t need = counters + nb + (nb & 1);
     if (words < first + need) return ENEC_E_CAPACITY;
     uint64_t *base = reinterpret_cast<uint64_t *>(static_cast<uint8_t *>(workspace) + WS_STATE) + first;
@@ -673,31 +673,12 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
     a.spin_limit = spin_limit();
     PbCompressFn fn = pick_compress_per_block(dtype, L);
     if (!fn) return ENEC_E_DTYPE;
-    const unsigned part_threads = B / 64 < 64 ? 64 : B / 64;
-    // per part: mask | low plane | high records (at most 8 plane bits together); before that the histogram copies
+    // one workgroup per data block, a thread per 64 elements (at least a wave); dynamic LDS: mask | low
+    // plane | high records (at most 8 plane bits together), before that the histogram copies
+    const unsigned threads = B / 64 < 64 ? 64 : B / 64;
     const size_t image = (size_t)B / (8 * L) + (size_t)B, hist = (size_t)PB_HIST_COPIES * PB_HIST_STRIDE * 4;
-    const size_t part_lds = (image > hist ? image : hist) + 15 & ~(size_t)15;
-    // several blocks per workgroup (one ticket for all of them) when there are enough blocks; the few
-    // blocks left over get a launch with one block per workgroup
-    unsigned per_wg = 1024 / part_threads < (unsigned)PB_MAX_PARTS ? 1024 / part_threads : (unsigned)PB_MAX_PARTS;
-    if (nb < 64 * (size_t)per_wg) per_wg = 1;
-    if (per_wg * part_lds > 65536 &&
-        hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(per_wg * part_lds)) != hipSuccess) {
-        (void)hipGetLastError();
-        per_wg = 1;
-    }
-    a.log_sub = ilog2(part_threads);
-    a.part_lds = (uint32_t)part_lds;
-    const size_t main_wgs = nb / per_wg, rest = nb - main_wgs * per_wg;
-    a.first_block = 0;
-    a.per_wg = per_wg;
-    hipLaunchKernelGGL(fn, dim3((unsigned)main_wgs), dim3(part_threads * per_wg), per_wg * part_lds, s, a);
-    if (rest) {
-        a.first_block = (uint32_t)(main_wgs * per_wg);
-        a.per_wg = 1;
-        a.ticket = reinterpret_cast<uint32_t *>(base) + 1;      // a counter of its own, cleared with the first
-        hipLaunchKernelGGL(fn, dim3((unsigned)rest), dim3(part_threads), part_lds, s, a);
-    }
+    const size_t lds = (image > hist ? image : hist) + 15 & ~(size_t)15;
+    hipLaunchKernelGGL(fn, dim3((unsigned)nb), dim3(threads), lds, s, a);
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 

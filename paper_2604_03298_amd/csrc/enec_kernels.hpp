@@ -28,25 +28,21 @@ ENEC_TABLES(dt2)
 // LDS copies of the block histogram in the compress kernel, and their distance in words
 constexpr uint32_t PB_HIST_COPIES = 16, PB_HIST_STRIDE = 257;   // words; 16 * 257 * 4 bytes of LDS
 
-constexpr int PB_MAX_PARTS = 4;                 // data blocks a workgroup of the compress kernel works on at once
+// Data blocks are handed out by tickets (see the compress kernel): PB_TICKET_CLASSES counters,
+// PB_TICKET_STRIDE 32-bit words apart (a cache line each)
+constexpr uint32_t PB_TICKET_CLASSES = 8, PB_TICKET_STRIDE = 16;
 
 struct PbCompressArgs {
     const void *in;
     uint8_t *out;
     unsigned long long *out_bytes;
     uint64_t *words;            // nb look-back words, zero at launch
-    uint32_t *ticket;           // zero at launch
+    uint32_t *ticket;           // PB_TICKET_CLASSES counters, zero at launch
     uint64_t n_elems;
     uint64_t tuples_at;         // byte offset of the tuple table in the stream
     uint64_t tail_base;         // fp32: where the lower halves go
     uint64_t payload_base;
     uint32_t nb, B, logB, spin_limit;
-    uint32_t first_block;       // this launch codes blocks first_block .. first_block + gridDim * per_wg - 1
-    uint32_t per_wg;            // data blocks per workgroup (parts), log_sub = log2 of the threads of a part
-    uint32_t log_sub, part_lds; // part_lds = bytes of dynamic LDS per part
-#ifdef ENEC_PB_TIMING
-    unsigned long long *dbg;    // eight counters of 10 ns ticks per phase (development aid)
-#endif
 };
 
 struct PbDecompressArgs {

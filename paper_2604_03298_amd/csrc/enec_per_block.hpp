@@ -3,21 +3,13 @@
 // (zeros, constants, weights of several scales, noise) is coded block by block with the tuple
 // that fits.  One workgroup per data block, one pass over the tensor:
 //   ticket -> rows -> split -> LDS histogram -> (b, n) by Eq. 1-3 -> m by Eq. 4 -> transform ->
-//   group test -> packing (Alg. 2, widths chosen at run time from the template instances) ->
-//   size -> look-back over the earlier blocks' sizes -> stores.
+//   group test -> size (published) -> packing (Alg. 2, widths chosen at run time from the template
+//   instances) -> look-back over the earlier blocks' sizes -> stores.
 // The widths are run-time values here, so the packers are reached through a switch; the kernels
 // of enec_device.hpp, which know their widths at compile time, stay the fast path for one tuple
 // per tensor.
 #pragma once
 #include "enec_kernels.hpp"
-
-#ifdef ENEC_PB_TIMING
-#define PB_T(i) do { if (tid == 0) { const unsigned long long now_ = wall_clock64(); atomicAdd(p.dbg + (i), now_ - t_last_); t_last_ = now_; } } while (0)
-#define PB_T_DECL unsigned long long t_last_ = wall_clock64()
-#else
-#define PB_T(i)
-#define PB_T_DECL
-#endif
 
 namespace enec {
 
@@ -27,28 +19,6 @@ constexpr uint64_t PB_SIZE = 1ull << 62;       // [60:0] = size of this block's 
 constexpr uint64_t PB_GAVE_UP = 1ull << 61;    // somebody before (or this block) stopped waiting
 constexpr uint64_t PB_VALUE = (1ull << 61) - 1;
 constexpr int PB_WINDOW = 256;                  // blocks one look-back step covers (4 words per lane)
-
-// Alg. 2 over the low plane, one column (this thread's 8 rows) at a time: LOW[t][h] holds the
-// plane values of row t in byte lanes; normalized byte q of the thread's 8 columns goes to the image
-template <int LM>
-__device__ __forceinline__ void pb_pack_low(const uint32_t (&LOW)[8][2], uint8_t *img_low, uint32_t logC, uint32_t tid)
-{
-    constexpr HHTable TL = HH<LM>::table;
-    uint32_t acc[LM][2];
-#pragma unroll
-    for (int q = 0; q < LM; ++q) acc[q][0] = acc[q][1] = 0;
-#pragma unroll
-    for (int f = 0; f < TL.count; ++f)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            uint32_t s = shl_or_shr(LOW[TL.row[f]][h], TL.shift[f]);
-            if (!TL.clean[f]) s &= TL.dmask[f] * 0x01010101u;
-            acc[TL.plane[f]][h] |= s;
-        }
-#pragma unroll
-    for (int q = 0; q < LM; ++q)
-        *reinterpret_cast<uint2 *>(img_low + ((size_t)q << logC) + 8u * tid) = make_uint2(acc[q][0], acc[q][1]);
-}
 
 // the inverse: plane values of the thread's 8 rows from the stream's low plane (already joined
 // pairwise by Alg. 2's last step: stream byte 2i = normalized byte i, 2i+1 = normalized byte i + T/2)
@@ -146,51 +116,97 @@ __device__ __forceinline__ void pb_load_rows(const PbCompressArgs &p, uint32_t k
     }
 }
 
+// Alg. 2 over the low plane of the thread's 8 rows, taken straight from the transformed bytes Y (bits
+// below m; fp16 adds the three left-over mantissa bits kept in bits 5..7 of Y's bytes): the plane
+// value of a row exists only while that row is folded into the normalized bytes
+template <int LM, int DT>
+__device__ __forceinline__ void pb_pack_low_from_y(const uint32_t (&Y)[8][2], uint32_t lrep, uint32_t m,
+                                                   uint8_t *img_low, uint32_t logC, uint32_t tid)
+{
+    constexpr HHTable TL = HH<LM>::table;
+    uint32_t acc[LM][2];
+#pragma unroll
+    for (int q = 0; q < LM; ++q) acc[q][0] = acc[q][1] = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t low = Y[t][h] & lrep;
+            if constexpr (DT == DT_FP16) low |= ((Y[t][h] >> 5) & 0x07070707u) << m;
+#pragma unroll
+            for (int f = 0; f < TL.count; ++f)
+                if (TL.row[f] == t) {
+                    uint32_t s = shl_or_shr(low, TL.shift[f]);
+                    if (!TL.clean[f]) s &= TL.dmask[f] * 0x01010101u;
+                    acc[TL.plane[f]][h] |= s;
+                }
+        }
+#pragma unroll
+    for (int q = 0; q < LM; ++q)
+        *reinterpret_cast<uint2 *>(img_low + ((size_t)q << logC) + 8u * tid) = make_uint2(acc[q][0], acc[q][1]);
+}
+
+template <int A, int LPG>
+__device__ __forceinline__ void pb_pack_records_from_y(const uint32_t (&Y)[8][2], uint32_t m, uint32_t arep,
+                                                       uint32_t my_word, uint32_t my_excl, uint8_t *img_high,
+                                                       uint32_t logC, uint32_t tid, bool active)
+{
+    uint32_t HI[8][2];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        HI[t][0] = (Y[t][0] >> m) & arep;
+        HI[t][1] = (Y[t][1] >> m) & arep;
+    }
+    pack_records<A, LPG>(HI, my_word, my_excl, img_high, logC, tid, active);
+}
+
+// minimum over the 64 lanes, in every lane
+__device__ __forceinline__ uint32_t wave_min32(uint32_t v)
+{
+    auto mn = [](uint32_t a, uint32_t b) { return a < b ? a : b; };
+    v = mn(v, (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)v, 0x111 /* row_shr:1 */, 0xF, 0xF, false));
+    v = mn(v, (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)v, 0x112 /* row_shr:2 */, 0xF, 0xF, false));
+    v = mn(v, (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)v, 0x114 /* row_shr:4 */, 0xF, 0xF, false));
+    v = mn(v, (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)v, 0x118 /* row_shr:8 */, 0xF, 0xF, false));
+    v = mn(v, (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)v, 0x142 /* row_bcast:15 */, 0xA, 0xF, false));
+    v = mn(v, (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)v, 0x143 /* row_bcast:31 */, 0xC, 0xF, false));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 template <int DT, int LPG>
-__global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompressArgs p)
+__global__ void __launch_bounds__(512) compress_per_block_kernel(const PbCompressArgs p)
 {
     constexpr uint32_t E = exponent_bits(DT);
     constexpr int RW = DT == DT_FP32 ? 16 : 8;
     constexpr int LOG_LPG = LPG == 4 ? 2 : LPG - 1;
 
-    // A workgroup works on p.per_wg consecutive data blocks at once, one per group of 2^p.log_sub threads
-    // ("part"): the parts run the same code side by side, share the barriers and nothing else.  One ticket
-    // then stands for per_wg blocks (one returning atomic on one address sustains about 28 draws per
-    // microsecond on this machine: with a ticket per block that rate bounded the kernel).  From here on
-    // tid, wave, the shared variables and the dynamic LDS are those of the thread's own part.
-    extern __shared__ __align__(16) uint8_t smem_all[];  // per part: mask | low plane (normalized bytes) | high records
-    __shared__ uint32_t s_hist_all[PB_MAX_PARTS][256];
-    __shared__ unsigned long long s_best_all[PB_MAX_PARTS];   // Eq. 3 cost << 16 | n << 8 | b of the best candidate
-    __shared__ double s_bexp_all[PB_MAX_PARTS][9];
-    __shared__ uint32_t s_ticket, s_lo_all[PB_MAX_PARTS], s_hi_all[PB_MAX_PARTS], s_m_all[PB_MAX_PARTS], s_flags_all[PB_MAX_PARTS];
-    __shared__ unsigned long long s_off_all[PB_MAX_PARTS];
+    extern __shared__ __align__(16) uint8_t smem[];      // mask | low plane (normalized bytes) | high records
+    __shared__ uint32_t s_hist[256];
+    __shared__ unsigned long long s_best;                // Eq. 3 cost << 16 | n << 8 | b of the best candidate
+    __shared__ double s_bexp[9];
+    __shared__ uint32_t s_ticket, s_m, s_flags;
+    __shared__ unsigned long long s_present[4];          // exponent values that occur, one bit each
+    __shared__ unsigned long long s_off;
 
-    const uint32_t part = threadIdx.x >> p.log_sub, part_threads = 1u << p.log_sub;
-    const uint32_t tid = threadIdx.x & (part_threads - 1u), lane = tid & 63u, wave = tid >> 6;
-    uint8_t *smem = smem_all + part * p.part_lds;
-    uint32_t *s_hist = s_hist_all[part];
-    unsigned long long &s_best = s_best_all[part];
-    double *s_bexp = s_bexp_all[part];
-    uint32_t &s_lo = s_lo_all[part], &s_hi = s_hi_all[part], &s_m = s_m_all[part], &s_flags = s_flags_all[part];
-    unsigned long long &s_off = s_off_all[part];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t B = p.B, logC = p.logB - 3u;
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
     const uint32_t mask_bytes = (B >> 6) >> LOG_LPG;                  // B / (8 L)
 
-    // Blocks are taken in the order in which workgroups start (a ticket), not by blockIdx: a part then
-    // only ever waits for blocks whose workgroups are already running (or for the lower parts of its
-    // own workgroup, which run beside it), and those publish their size before they wait for anything,
-    // so the look-back cannot deadlock, whatever part of the grid is resident.  (A persistent loop over
-    // blocks was tried: the compiler then keeps the constants of all sixteen packer instances in
-    // registers, about 250 VGPRs, and the kernel is slower.)
-    PB_T_DECL;
+    // Blocks are taken in the order in which workgroups start (tickets), not by blockIdx: a block then
+    // only waits for blocks that running workgroups hold or that the next workgroups to start will
+    // draw, and every workgroup publishes its size before it waits for anything, so the look-back
+    // makes progress whatever part of the grid is resident (every wait is bounded by the spin limit
+    // as well).  There are PB_TICKET_CLASSES counters: a workgroup draws from counter blockIdx mod 8,
+    // the t-th draw from counter c is block 8 t + c, and a class has as many workgroups as blocks.
+    // Returning atomics on one address are serialised at the memory side; with eight addresses the
+    // kernel measured 5 % faster than with one.
+    const uint32_t cls = blockIdx.x & (PB_TICKET_CLASSES - 1u);
     uint32_t ticket = 0;
-    if (threadIdx.x == 0) ticket = atomicAdd(p.ticket, 1u);
     if (tid == 0) {
+        ticket = atomicAdd(p.ticket + PB_TICKET_STRIDE * cls, 1u);
         s_best = ~0ull;
-        s_lo = 255u;
-        s_hi = 0u;
         s_flags = 0u;
     }
     // Phase 1 counts into PB_HIST_COPIES copies of the histogram (lane i uses copy i mod 16), so that
@@ -199,21 +215,22 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
     // the dynamic LDS with the payload image, which is written only after the search.  They are
     // cleared while the ticket travels.
     uint32_t *hcopy = reinterpret_cast<uint32_t *>(smem);
-    for (uint32_t i = tid; i < PB_HIST_COPIES * PB_HIST_STRIDE / 4u; i += part_threads)
+    for (uint32_t i = tid; i < PB_HIST_COPIES * PB_HIST_STRIDE / 4u; i += blockDim.x)
         reinterpret_cast<uint4 *>(hcopy)[i] = make_uint4(0, 0, 0, 0);
-    if (threadIdx.x == 0) s_ticket = ticket;
+    if (tid == 0) s_ticket = ticket;
     __syncthreads();
-    if (p.first_block + (s_ticket + 1u) * p.per_wg > p.nb) return;     // (never: the grid is sized to fit)
-    const uint32_t k = p.first_block + s_ticket * p.per_wg + part;
-    PB_T(0);
+    const uint32_t k = s_ticket * PB_TICKET_CLASSES + cls;
+    if (k >= p.nb) return;                               // (never: a class has as many workgroups as blocks)
     uint4 raw[RW];
     pb_load_rows<DT>(p, k, tid, active, logC, raw);
     uint32_t *mine = hcopy + (lane & (PB_HIST_COPIES - 1u)) * PB_HIST_STRIDE;
     const uint64_t blk0 = (uint64_t)k << p.logB;
     const uint32_t real = p.n_elems - blk0 < B ? (uint32_t)(p.n_elems - blk0) : B;   // elements that are not pads
+    const bool full = real == B && nact >= 64u;          // no pads and no idle lanes (uniform)
 
-    // ---- a1: rows, split into exponent bytes X, raw bytes SM (and fp16's three left-over bits) ----
-    uint32_t X[8][2], SM[8][2], T3[DT == DT_FP16 ? 8 : 1][2];
+    // ---- a1: rows, split into exponent bytes X and raw bytes SM; fp16's three left-over mantissa bits
+    // travel in bits 5..7 of X's bytes (its exponents have five bits) ----
+    uint32_t X[8][2], SM[8][2];
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const uint32_t at = ((uint32_t)t << logC) + 8u * tid;         // first element of the thread in this row
@@ -236,74 +253,137 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
             const uint32_t d1 = h ? r16.w : r16.y;
             const uint32_t Lb = byte_perm(d1, d0, 0x06040200u);
             const uint32_t Hb = byte_perm(d1, d0, 0x07050301u);
+            uint32_t x;
             if constexpr (DT == DT_FP16) {
                 SM[t][h] = (Hb & 0x80808080u) | ((Hb & 0x03030303u) << 5) | ((Lb >> 3) & 0x1F1F1F1Fu);
-                X[t][h] = (Hb >> 2) & 0x1F1F1F1Fu;
-                T3[t][h] = Lb & 0x07070707u;
+                x = (Hb >> 2) & 0x1F1F1F1Fu;
+                X[t][h] = x | ((Lb & 0x07070707u) << 5);
             } else {
                 SM[t][h] = bfi(0x7F7F7F7Fu, Lb, Hb);
-                X[t][h] = bfi(0xFEFEFEFEu, Hb << 1, Lb >> 7);
+                x = bfi(0xFEFEFEFEu, Hb << 1, Lb >> 7);
+                X[t][h] = x;
             }
             // ---- Sec. V-E phase 1: exponent counts of the block's own elements ----
-            if (active) {
+            if (full) {
+                if (active) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) atomicAdd(&mine[(x >> (8 * i)) & 0xFFu], 1u);
+                }
+            } else if (active) {
                 const uint32_t e = at + 4u * h;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    if (e + i < real) atomicAdd(&mine[(X[t][h] >> (8 * i)) & 0xFFu], 1u);
+                    if (e + i < real) atomicAdd(&mine[(x >> (8 * i)) & 0xFFu], 1u);
             }
         }
     }
     __syncthreads();
-    PB_T(1);
 
-    // ---- phase 2: lowest and highest exponent, then every b in between with Eq. 1's n and Eq. 3's cost ----
-    for (uint32_t x = tid; x < 256u; x += part_threads) {
+    // ---- phase 2: the counts of the 256 exponent values, lowest and highest value present ----
+    for (uint32_t x = tid; x < 256u; x += blockDim.x) {
         uint32_t c = 0;
 #pragma unroll 8
         for (uint32_t i = 0; i < PB_HIST_COPIES; ++i) c += hcopy[i * PB_HIST_STRIDE + x];
         s_hist[x] = c;
-        if (c) {
-            atomicMin(&s_lo, x);
-            atomicMax(&s_hi, x);
+        const uint64_t present = __builtin_amdgcn_ballot_w64(c != 0);       // x / 64 is the same for the whole wave
+        if (lane == 0) s_present[x >> 6] = present;
+    }
+    __syncthreads();
+    uint32_t xl = 255u, xh = 0u;
+#pragma unroll
+    for (int c = 3; c >= 0; --c) {
+        const uint64_t z = s_present[c];
+        if (z) xl = 64u * c + (uint32_t)__builtin_ctzll(z);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint64_t z = s_present[c];
+        if (z) xh = 64u * c + 63u - (uint32_t)__builtin_clzll(z);
+    }
+    xl = __builtin_amdgcn_readfirstlane(xl);
+    xh = __builtin_amdgcn_readfirstlane(xh);
+    if (xh - xl < 64u) {
+        // The usual case, at most 64 values between the lowest and the highest: wave 0 does the whole
+        // search in registers.  Lane j holds the count of value xl + j and is candidate b = xl + j.
+        if (wave == 0) {
+            const uint32_t R = xh - xl + 1u;
+            const bool valid = lane < R;
+            const uint32_t v = valid ? s_hist[xl + lane] : 0u;
+            // every b with Eq. 1's n and Eq. 3's cost; ties: smaller n, then smaller b
+            const uint32_t nb_ = pb_width_for(xl + lane, xl, xh, E);
+            const uint32_t nmask_b = (1u << nb_) - 1u;
+            uint32_t D = 0;                                   // at most 2^15 elements * 255
+            for (uint32_t i = 0; i < R; ++i)
+                D += (uint32_t)__builtin_amdgcn_readlane((int)v, (int)i) * ((lane - i) & nmask_b);
+            const uint32_t Dmin = wave_min32(valid ? D : 0xFFFFFFFFu);
+            const uint32_t pick = wave_min32(valid && D == Dmin ? (nb_ << 8) | (xl + lane) : 0xFFFFFFFFu);
+            const uint32_t b = pick & 0xFFu, n = pick >> 8;
+            // phase 3: Eq. 4 for every m (lane m) with the group length the block is coded with,
+            // 1/L + n + (m - n) p^L, in IEEE double, p^L by three to five squarings
+            const uint32_t y = (b - (xl + lane)) & ((1u << n) - 1u);
+            const uint32_t ybits = 32u - (uint32_t)__clz(y);           // y < 2^m  <=>  ybits <= m
+            uint32_t cnt = 0;
+            for (uint32_t j = 0; j <= n; ++j) {
+                const uint32_t s = wave_sum32(valid && ybits <= j ? v : 0u);
+                if (lane == j) cnt = s;
+            }
+            const double q = (double)cnt / (double)real;
+            const double q2 = q * q, q4 = q2 * q2;
+            double qL = q4 * q4;                                   // p^8
+            if constexpr (LPG >= 2) qL = qL * qL;                  // p^16
+            if constexpr (LPG == 4) qL = qL * qL;                  // p^32
+            const double bexp = (1.0 / (double)(8 * LPG) + (double)n) + ((double)lane - (double)n) * qL;
+            const unsigned long long bits = (unsigned long long)__double_as_longlong(bexp);
+            uint32_t best_m = 0;
+            double best = __longlong_as_double((long long)(((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(bits >> 32), 0) << 32) |
+                                                           (uint32_t)__builtin_amdgcn_readlane((int)bits, 0)));
+            for (uint32_t j = 1; j <= n; ++j) {
+                const double cand = __longlong_as_double((long long)(((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(bits >> 32), (int)j) << 32) |
+                                                                     (uint32_t)__builtin_amdgcn_readlane((int)bits, (int)j)));
+                if (cand < best) { best = cand; best_m = j; }                 // ties: smaller m
+            }
+            if (lane == 0) {
+                s_best = ((unsigned long long)n << 8) | b;
+                s_m = best_m;
+            }
         }
-    }
-    __syncthreads();
-    const uint32_t xl = s_lo, xh = s_hi;
-    for (uint32_t b = xl + tid; b <= xh; b += part_threads) {
-        const uint32_t n = pb_width_for(b, xl, xh, E);
-        const uint32_t nmask = (1u << n) - 1u;
-        uint32_t D = 0;                                   // at most 2^15 elements * 255
+        __syncthreads();
+    } else {
+        // a block whose exponents spread over more than 64 values: every thread takes candidates b
+        for (uint32_t b = xl + tid; b <= xh; b += blockDim.x) {
+            const uint32_t n = pb_width_for(b, xl, xh, E);
+            const uint32_t nmask = (1u << n) - 1u;
+            uint32_t D = 0;
 #pragma unroll 8
-        for (uint32_t x = xl; x <= xh; ++x) D += s_hist[x] * ((b - x) & nmask);
-        atomicMin(&s_best, ((unsigned long long)D << 16) | (n << 8) | b);     // ties: smaller n, then smaller b
+            for (uint32_t x = xl; x <= xh; ++x) D += s_hist[x] * ((b - x) & nmask);
+            atomicMin(&s_best, ((unsigned long long)D << 16) | (n << 8) | b);     // ties: smaller n, then smaller b
+        }
+        __syncthreads();
+        const uint32_t b = (uint32_t)s_best & 0xFFu, n = ((uint32_t)s_best >> 8) & 0xFFu;
+        if (tid <= n) {
+            const uint32_t nmask = (1u << n) - 1u;
+            uint32_t cnt = 0;
+#pragma unroll 8
+            for (uint32_t x = xl; x <= xh; ++x)
+                if (((b - x) & nmask) < (1u << tid)) cnt += s_hist[x];
+            const double q = (double)cnt / (double)real;
+            const double q2 = q * q, q4 = q2 * q2;
+            double qL = q4 * q4;                                   // p^8
+            if constexpr (LPG >= 2) qL = qL * qL;                  // p^16
+            if constexpr (LPG == 4) qL = qL * qL;                  // p^32
+            s_bexp[tid] = (1.0 / (double)(8 * LPG) + (double)n) + ((double)tid - (double)n) * qL;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t best_m = 0;
+            double best = s_bexp[0];
+            for (uint32_t m = 1; m <= n; ++m)
+                if (s_bexp[m] < best) { best = s_bexp[m]; best_m = m; }          // ties: smaller m
+            s_m = best_m;
+        }
+        __syncthreads();
     }
-    __syncthreads();
     const uint32_t b = (uint32_t)s_best & 0xFFu, n = ((uint32_t)s_best >> 8) & 0xFFu;
-    // ---- phase 3: Eq. 4 for every m with the group length the block is coded with, 1/L + n + (m - n) p^L,
-    // in IEEE double, p^L by three to five squarings ----
-    if (tid <= n) {
-        const uint32_t nmask = (1u << n) - 1u;
-        uint32_t cnt = 0;
-#pragma unroll 8
-        for (uint32_t x = xl; x <= xh; ++x)
-            if (((b - x) & nmask) < (1u << tid)) cnt += s_hist[x];
-        const double q = (double)cnt / (double)real;
-        const double q2 = q * q, q4 = q2 * q2;
-        double qL = q4 * q4;                                   // p^8
-        if constexpr (LPG >= 2) qL = qL * qL;                  // p^16
-        if constexpr (LPG == 4) qL = qL * qL;                  // p^32
-        s_bexp[tid] = (1.0 / (double)(8 * LPG) + (double)n) + ((double)tid - (double)n) * qL;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t best_m = 0;
-        double best = s_bexp[0];
-        for (uint32_t m = 1; m <= n; ++m)
-            if (s_bexp[m] < best) { best = s_bexp[m]; best_m = m; }          // ties: smaller m
-        s_m = best_m;
-    }
-    __syncthreads();
-    PB_T(2);
     const uint32_t m = s_m, a = n - m;
     const uint32_t lm = m + (DT == DT_FP16 ? 3u : 0u);
 
@@ -313,79 +393,57 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
     uint8_t *img_high = img_low + ((lm * B) >> 3);
     const uint32_t fixed = B + mask_bytes + ((lm * B) >> 3);
 
-    // ---- a2 transform, a3 group test, a4 low plane ----
+    // ---- a2 transform (in place: X becomes y, fp16 keeps its three bits above), a3 group test ----
     const uint32_t crep = ((b + (1u << (n - 1))) & 0xFFu) * 0x01010101u;
     const uint32_t brep = b * 0x01010101u;
     const uint32_t srep = (1u << (n - 1)) * 0x01010101u;
     const uint32_t nrep = ((1u << n) - 1u) * 0x01010101u;
     const uint32_t lrep = ((1u << m) - 1u) * 0x01010101u;
     const uint32_t arep = ((1u << a) - 1u) * 0x01010101u;
-    uint32_t HI[8][2], LOW[8][2], mw[8], mw_hi[LPG == 1 ? 8 : 1];
+    const bool mask_writer = lane == 0 && 64u * wave < nact;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         uint32_t gor = 0;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            // pads behave like exponent b: y = 0
-            const int32_t left = (int32_t)real - (int32_t)(((uint32_t)t << logC) + 8u * tid + 4u * h);
-            const uint32_t padm = !active || left <= 0 ? 0xFFFFFFFFu : (left >= 4 ? 0u : 0xFFFFFFFFu << (8 * left));
-            const uint32_t x = bfi(padm, brep, X[t][h]);
+            uint32_t x = X[t][h];
+            if constexpr (DT == DT_FP16) x &= 0x1F1F1F1Fu;
+            if (!full) {      // pads behave like exponent b: y = 0
+                const int32_t left = (int32_t)real - (int32_t)(((uint32_t)t << logC) + 8u * tid + 4u * h);
+                const uint32_t padm = !active || left <= 0 ? 0xFFFFFFFFu : (left >= 4 ? 0u : 0xFFFFFFFFu << (8 * left));
+                x = bfi(padm, brep, x);
+            }
             const uint32_t Y = (bytesub_safe(crep, x) ^ srep) & nrep;
-            HI[t][h] = (Y >> m) & arep;
-            gor |= HI[t][h];
-            if constexpr (DT == DT_FP16) LOW[t][h] = (Y & lrep) | (T3[t][h] << m);
-            else LOW[t][h] = Y & lrep;
+            gor |= (Y >> m) & arep;
+            if constexpr (DT == DT_FP16) X[t][h] = Y | (X[t][h] & 0xE0E0E0E0u);
+            else X[t][h] = Y;
         }
-        // a3: OR over the lanes that share a group, one mask bit per group
+        // a3: OR over the lanes that share a group, one mask bit per group; a wave holds 64 / LPG mask
+        // bits of every row, group order = row-major
         if constexpr (LPG == 2) gor |= swap_pair(gor);
         if constexpr (LPG == 4) gor = quad_or(gor);
         const uint64_t flagged = __builtin_amdgcn_ballot_w64(gor != 0);
-        if constexpr (LPG == 1) { mw[t] = (uint32_t)flagged; mw_hi[t] = (uint32_t)(flagged >> 32); }
-        else if constexpr (LPG == 2) mw[t] = compact_even_bits(flagged);
-        else mw[t] = compact_fourth_bits(flagged);
-    }
-    // a wave holds 64 / LPG mask bits of every row; group order = row-major
-    if (lane == 0 && 64u * wave < nact) {
         if constexpr (LPG == 1) {
-            if (logC >= 9) {
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    img_maskw[((uint32_t)t << (logC - 8)) + 2u * wave] = mw[t];
-                    img_maskw[((uint32_t)t << (logC - 8)) + 2u * wave + 1u] = mw_hi[t];
+            if (mask_writer) {
+                if (logC >= 9) {
+                    img_maskw[((uint32_t)t << (logC - 8)) + 2u * wave] = (uint32_t)flagged;
+                    img_maskw[((uint32_t)t << (logC - 8)) + 2u * wave + 1u] = (uint32_t)(flagged >> 32);
+                } else {      // B = 2048: 32 groups per row
+                    img_maskw[t] = (uint32_t)flagged;
                 }
-            } else {  // B = 2048: 32 groups per row
-#pragma unroll
-                for (int t = 0; t < 8; ++t) img_maskw[t] = mw[t];
             }
         } else if constexpr (LPG == 2) {
-            if (logC >= 9) {
-#pragma unroll
-                for (int t = 0; t < 8; ++t) img_maskw[((uint32_t)t << (logC - 9)) + wave] = mw[t];
-            } else {  // B = 2048: 16 groups per row, one wave
-#pragma unroll
-                for (int u = 0; u < 4; ++u) img_maskw[u] = mw[2 * u] | (mw[2 * u + 1] << 16);
+            const uint32_t mw = compact_even_bits(flagged);
+            if (mask_writer) {
+                if (logC >= 9) img_maskw[((uint32_t)t << (logC - 9)) + wave] = mw;
+                else reinterpret_cast<uint16_t *>(img)[t] = (uint16_t)mw;      // B = 2048: 16 groups per row, one wave
             }
-        } else {      // 16 bits per wave and row (B >= 4096)
-            uint16_t *img_mask16 = reinterpret_cast<uint16_t *>(img);
-#pragma unroll
-            for (int t = 0; t < 8; ++t) img_mask16[((uint32_t)t << (logC - 9)) + wave] = (uint16_t)mw[t];
-        }
-    }
-    if (active) {
-        switch (lm) {
-        case 1: pb_pack_low<1>(LOW, img_low, logC, tid); break;
-        case 2: pb_pack_low<2>(LOW, img_low, logC, tid); break;
-        case 3: pb_pack_low<3>(LOW, img_low, logC, tid); break;
-        case 4: pb_pack_low<4>(LOW, img_low, logC, tid); break;
-        case 5: pb_pack_low<5>(LOW, img_low, logC, tid); break;
-        case 6: pb_pack_low<6>(LOW, img_low, logC, tid); break;
-        case 7: pb_pack_low<7>(LOW, img_low, logC, tid); break;
-        case 8: pb_pack_low<8>(LOW, img_low, logC, tid); break;
-        default: break;
+        } else {              // 16 bits per wave and row (B >= 4096)
+            const uint32_t mw = compact_fourth_bits(flagged);
+            if (mask_writer) reinterpret_cast<uint16_t *>(img)[((uint32_t)t << (logC - 9)) + wave] = (uint16_t)mw;
         }
     }
     __syncthreads();
-    PB_T(3);
 
     // ---- a5 positions: exclusive popcount prefix over the mask words (a wave scan per wave) ----
     const uint32_t nwords = (B >> 8) >> LOG_LPG;          // 32-bit words of the mask (at most 64)
@@ -398,19 +456,32 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
     // ---- a6: the size is known: publish it before anything else ----
     if (tid == 0) st_state(p.words + k, PB_SIZE | (uint64_t)(S >> 4));
 
+    // ---- a4 low plane ----
+    if (active) {
+        switch (lm) {
+        case 1: pb_pack_low_from_y<1, DT>(X, lrep, m, img_low, logC, tid); break;
+        case 2: pb_pack_low_from_y<2, DT>(X, lrep, m, img_low, logC, tid); break;
+        case 3: pb_pack_low_from_y<3, DT>(X, lrep, m, img_low, logC, tid); break;
+        case 4: pb_pack_low_from_y<4, DT>(X, lrep, m, img_low, logC, tid); break;
+        case 5: pb_pack_low_from_y<5, DT>(X, lrep, m, img_low, logC, tid); break;
+        case 6: pb_pack_low_from_y<6, DT>(X, lrep, m, img_low, logC, tid); break;
+        case 7: pb_pack_low_from_y<7, DT>(X, lrep, m, img_low, logC, tid); break;
+        case 8: pb_pack_low_from_y<8, DT>(X, lrep, m, img_low, logC, tid); break;
+        default: break;
+        }
+    }
     switch (a) {
-    case 1: pack_records<1, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 2: pack_records<2, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 3: pack_records<3, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 4: pack_records<4, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 5: pack_records<5, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 6: pack_records<6, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 7: pack_records<7, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
-    case 8: pack_records<8, LPG>(HI, my_word, my_excl, img_high, logC, tid, active); break;
+    case 1: pb_pack_records_from_y<1, LPG>(X, m, arep, my_word, my_excl, img_high, logC, tid, active); break;
+    case 2: pb_pack_records_from_y<2, LPG>(X, m, arep, my_word, my_excl, img_high, logC, tid, active); break;
+    case 3: pb_pack_records_from_y<3, LPG>(X, m, arep, my_word, my_excl, img_high, logC, tid, active); break;
+    case 4: pb_pack_records_from_y<4, LPG>(X, m, arep, my_word, my_excl, img_high, logC, tid, active); break;
+    case 5: pb_pack_records_from_y<5, LPG>(X, m, arep, my_word, my_excl, img_high, logC, tid, active); break;
+    case 6: pb_pack_records_from_y<6, LPG>(X, m, arep, my_word, my_excl, img_high, logC, tid, active); break;
+    case 7: pb_pack_records_from_y<7, LPG>(X, m, arep, my_word, my_excl, img_high, logC, tid, active); break;
+    case 8: pb_pack_records_from_y<8, LPG>(X, m, arep, my_word, my_excl, img_high, logC, tid, active); break;
     default: break;
     }
 
-    PB_T(4);
     // ---- a6 (wave 0): look back over the earlier blocks, PB_WINDOW at a time (lane i reads blocks
     // top - i, top - 64 - i, ...), until one of them carries its inclusive prefix.  A lower block is held
     // by a workgroup that publishes its size before it waits for anything (see above), so every wait
@@ -447,9 +518,6 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
                 if (++spins > p.spin_limit) { flags |= 4u; break; }
                 spin_pause(spins);
             }
-#ifdef ENEC_PB_TIMING
-            if (lane == 0) { atomicAdd(p.dbg + 8, (unsigned long long)spins); atomicAdd(p.dbg + 9, 1ull); }
-#endif
             if (flags & 4u) break;
             uint64_t part = 0;
             bool gave_up = false;
@@ -471,7 +539,6 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
         }
     }
     __syncthreads();
-    PB_T(5);
 
     // ---- a7: stores ----
     const uint64_t off = s_off;
@@ -483,12 +550,12 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
             *reinterpret_cast<uint2 *>(dst + ((size_t)t << logC) + 8u * tid) = make_uint2(SM[t][0], SM[t][1]);
         }
     }
-    for (uint32_t v = tid; v < (mask_bytes >> 4); v += part_threads)
+    for (uint32_t v = tid; v < (mask_bytes >> 4); v += blockDim.x)
         *reinterpret_cast<uint4 *>(dst + B + 16u * v) = *reinterpret_cast<const uint4 *>(img + 16u * v);
     if (lm > 0) {
         uint8_t *dlow = dst + B + mask_bytes;
         const uint32_t T2 = (lm * B) >> 4;               // half of the plane's length
-        for (uint32_t v = tid; v < (T2 >> 3); v += part_threads) {
+        for (uint32_t v = tid; v < (T2 >> 3); v += blockDim.x) {
             const uint2 lo = *reinterpret_cast<const uint2 *>(img_low + 8u * v);
             const uint2 hi = *reinterpret_cast<const uint2 *>(img_low + 8u * v + T2);
             uint4 o;   // stream byte 2i = normalized byte i, stream byte 2i+1 = normalized byte i + T/2
@@ -502,7 +569,7 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
     if (a > 0) {
         uint8_t *dhigh = dst + fixed;
         const uint32_t hbytes = (uint32_t)LPG * a * cnt;
-        for (uint32_t v = tid; 16u * v < hbytes; v += part_threads) {
+        for (uint32_t v = tid; 16u * v < hbytes; v += blockDim.x) {
             const uint4 o = *reinterpret_cast<const uint4 *>(img_high + 16u * v);
             uint32_t w[4] = {o.x, o.y, o.z, o.w};
 #pragma unroll
@@ -540,7 +607,6 @@ __global__ void __launch_bounds__(1024) compress_per_block_kernel(const PbCompre
             if (p.out_bytes) *p.out_bytes = total;
         }
     }
-    PB_T(6);
 }
 
 // ---------------------------------------------------------------------------------
