@@ -674,11 +674,13 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
     PbCompressFn fn = pick_compress_per_block(dtype, L);
     if (!fn) return ENEC_E_DTYPE;
     // one workgroup per data block, a thread per 64 elements (at least a wave); dynamic LDS: mask | low
-    // plane | high records (at most 8 plane bits together), before that the histogram copies
+    // plane | high records (at most 8 plane bits together), before that the histogram copies; behind
+    // it the raw bytes of the rows that do not wait in registers
     const unsigned threads = B / 64 < 64 ? 64 : B / 64;
     const size_t image = (size_t)B / (8 * L) + (size_t)B, hist = (size_t)PB_HIST_COPIES * PB_HIST_STRIDE * 4;
     const size_t lds = (image > hist ? image : hist) + 15 & ~(size_t)15;
-    hipLaunchKernelGGL(fn, dim3((unsigned)nb), dim3(threads), lds, s, a);
+    a.park_at = (uint32_t)lds;
+    hipLaunchKernelGGL(fn, dim3((unsigned)nb), dim3(threads), lds + (size_t)(8 - PB_SM_REG_ROWS) * threads * 8, s, a);
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
 }
 

@@ -43,7 +43,9 @@ struct PbCompressArgs {
     uint64_t tail_base;         // fp32: where the lower halves go
     uint64_t payload_base;
     uint32_t nb, B, logB, spin_limit;
+    uint32_t park_at;           // byte offset in the dynamic LDS where raw bytes wait (behind the image)
 };
+constexpr int PB_SM_REG_ROWS = 4;               // rows of a thread's raw bytes kept in registers; the other rows wait in LDS
 
 struct PbDecompressArgs {
     const uint8_t *in;
