@@ -189,7 +189,6 @@ compress_per_block_kernel(const PbCompressArgs p)
     extern __shared__ __align__(16) uint8_t smem[];      // mask | low plane (normalized bytes) | high records
     __shared__ uint32_t s_hist[256];
     __shared__ unsigned long long s_best;                // Eq. 3 cost << 16 | n << 8 | b of the best candidate
-    __shared__ double s_bexp[9];
     __shared__ uint32_t s_ticket, s_m, s_flags;
     __shared__ unsigned long long s_present[4];          // exponent values that occur, one bit each
     __shared__ unsigned long long s_off;
@@ -316,6 +315,27 @@ compress_per_block_kernel(const PbCompressArgs p)
     }
     xl = __builtin_amdgcn_readfirstlane(xl);
     xh = __builtin_amdgcn_readfirstlane(xh);
+    // Eq. 4 for every m (lane m holds the count of elements whose y fits m bits) with the group length
+    // the block is coded with, 1/L + n + (m - n) p^L, in IEEE double, p^L by three to five squarings;
+    // the smallest value wins, ties go to the smaller m (one wave)
+    auto choose_m = [&](uint32_t cnt, uint32_t n) -> uint32_t {
+        const double q = (double)cnt / (double)real;
+        const double q2 = q * q, q4 = q2 * q2;
+        double qL = q4 * q4;                                   // p^8
+        if constexpr (LPG >= 2) qL = qL * qL;                  // p^16
+        if constexpr (LPG == 4) qL = qL * qL;                  // p^32
+        const double bexp = (1.0 / (double)(8 * LPG) + (double)n) + ((double)lane - (double)n) * qL;
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(bexp);
+        uint32_t best_m = 0;
+        double best = __longlong_as_double((long long)(((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(bits >> 32), 0) << 32) |
+                                                       (uint32_t)__builtin_amdgcn_readlane((int)bits, 0)));
+        for (uint32_t j = 1; j <= n; ++j) {
+            const double cand = __longlong_as_double((long long)(((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(bits >> 32), (int)j) << 32) |
+                                                                 (uint32_t)__builtin_amdgcn_readlane((int)bits, (int)j)));
+            if (cand < best) { best = cand; best_m = j; }                 // ties: smaller m
+        }
+        return best_m;
+    };
     if (xh - xl < 64u) {
         // The usual case, at most 64 values between the lowest and the highest: wave 0 does the whole
         // search in registers.  Lane j holds the count of value xl + j and is candidate b = xl + j.
@@ -328,12 +348,11 @@ compress_per_block_kernel(const PbCompressArgs p)
             const uint32_t nmask_b = (1u << nb_) - 1u;
             uint32_t D = 0;                                   // at most 2^15 elements * 255
             for (uint32_t i = 0; i < R; ++i)
-                D += (uint32_t)__builtin_amdgcn_readlane((int)v, (int)i) * ((lane - i) & nmask_b);
+                D += __umul24((uint32_t)__builtin_amdgcn_readlane((int)v, (int)i), (lane - i) & nmask_b);
             const uint32_t Dmin = wave_min32(valid ? D : 0xFFFFFFFFu);
             const uint32_t pick = wave_min32(valid && D == Dmin ? (nb_ << 8) | (xl + lane) : 0xFFFFFFFFu);
             const uint32_t b = pick & 0xFFu, n = pick >> 8;
-            // phase 3: Eq. 4 for every m (lane m) with the group length the block is coded with,
-            // 1/L + n + (m - n) p^L, in IEEE double, p^L by three to five squarings
+            // phase 3: lane m counts the elements whose y fits m bits
             const uint32_t y = (b - (xl + lane)) & ((1u << n) - 1u);
             const uint32_t ybits = 32u - (uint32_t)__clz(y);           // y < 2^m  <=>  ybits <= m
             uint32_t cnt = 0;
@@ -341,21 +360,7 @@ compress_per_block_kernel(const PbCompressArgs p)
                 const uint32_t s = wave_sum32(valid && ybits <= j ? v : 0u);
                 if (lane == j) cnt = s;
             }
-            const double q = (double)cnt / (double)real;
-            const double q2 = q * q, q4 = q2 * q2;
-            double qL = q4 * q4;                                   // p^8
-            if constexpr (LPG >= 2) qL = qL * qL;                  // p^16
-            if constexpr (LPG == 4) qL = qL * qL;                  // p^32
-            const double bexp = (1.0 / (double)(8 * LPG) + (double)n) + ((double)lane - (double)n) * qL;
-            const unsigned long long bits = (unsigned long long)__double_as_longlong(bexp);
-            uint32_t best_m = 0;
-            double best = __longlong_as_double((long long)(((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(bits >> 32), 0) << 32) |
-                                                           (uint32_t)__builtin_amdgcn_readlane((int)bits, 0)));
-            for (uint32_t j = 1; j <= n; ++j) {
-                const double cand = __longlong_as_double((long long)(((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(bits >> 32), (int)j) << 32) |
-                                                                     (uint32_t)__builtin_amdgcn_readlane((int)bits, (int)j)));
-                if (cand < best) { best = cand; best_m = j; }                 // ties: smaller m
-            }
+            const uint32_t best_m = choose_m(cnt, n);
             if (lane == 0) {
                 s_best = ((unsigned long long)n << 8) | b;
                 s_m = best_m;
@@ -363,37 +368,54 @@ compress_per_block_kernel(const PbCompressArgs p)
         }
         __syncthreads();
     } else {
-        // a block whose exponents spread over more than 64 values: every thread takes candidates b
-        for (uint32_t b = xl + tid; b <= xh; b += blockDim.x) {
-            const uint32_t n = pb_width_for(b, xl, xh, E);
-            const uint32_t nmask = (1u << n) - 1u;
-            uint32_t D = 0;
-#pragma unroll 8
-            for (uint32_t x = xl; x <= xh; ++x) D += s_hist[x] * ((b - x) & nmask);
-            atomicMin(&s_best, ((unsigned long long)D << 16) | (n << 8) | b);     // ties: smaller n, then smaller b
+        // A block whose exponents spread over more than 64 values.  Lane j of a wave holds the counts of
+        // the values j, 64 + j, 128 + j and 192 + j; wave w takes the candidates b = xl + 64 w + j (and
+        // further ones if the workgroup has fewer than four waves); the waves' best meet in s_best.
+        // Eq. 1 gives n = 7 or 8 for every b of such a block (the wider side of the window has at least
+        // 32 values).  With n fixed, Eq. 3's cost D_n(b) = sum_x count[x] ((b - x) mod 2^n) obeys
+        //   D_n(b + 1) - D_n(b) = N - 2^n H_n[(b + 1) mod 2^n],   H_n = the counts folded modulo 2^n,
+        // (every term grows by one, the ones that wrap fall by 2^n - 1), so the 64 costs of a wave come
+        // from D_n of its first candidate, a sum over the lanes, and a prefix sum of H_n over the lanes.
+        uint32_t hv[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) hv[c] = s_hist[64 * c + lane];
+        for (uint32_t b0 = xl + 64u * wave; b0 <= xh; b0 += blockDim.x) {
+            const uint32_t bb = b0 + lane;
+            const bool valid = bb <= xh;
+            const uint32_t nb_ = pb_width_for(bb, xl, xh, E);
+            const uint32_t h0 = s_hist[bb & 255u], h1 = s_hist[(bb + 128u) & 255u];
+            uint32_t D = 0xFFFFFFFFu;                         // costs are at most 2^15 elements * 255
+#pragma unroll
+            for (uint32_t nn = 7; nn <= 8; ++nn) {
+                const uint32_t mask = (1u << nn) - 1u;
+                uint32_t t = 0;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) t += __umul24(hv[c], (b0 - (64u * c + lane)) & mask);
+                const uint32_t first = wave_sum32(t);                       // D_nn(b0)
+                const uint32_t g = nn == 8 ? h0 : h0 + h1;                  // H_nn[b mod 2^nn]
+                const uint32_t upto = wave_incl_scan(g, lane) - (uint32_t)__builtin_amdgcn_readlane((int)g, 0);
+                if (nb_ == nn) D = first + lane * real - (upto << nn);
+            }
+            const uint32_t Dmin = wave_min32(valid ? D : 0xFFFFFFFFu);
+            const uint32_t pick = wave_min32(valid && D == Dmin ? (nb_ << 8) | bb : 0xFFFFFFFFu);
+            if (lane == 0) atomicMin(&s_best, ((unsigned long long)Dmin << 16) | pick);   // ties: smaller n, then smaller b
         }
         __syncthreads();
-        const uint32_t b = (uint32_t)s_best & 0xFFu, n = ((uint32_t)s_best >> 8) & 0xFFu;
-        if (tid <= n) {
-            const uint32_t nmask = (1u << n) - 1u;
+        if (wave == 0) {
+            const uint32_t b = (uint32_t)s_best & 0xFFu, n = ((uint32_t)s_best >> 8) & 0xFFu;
+            uint32_t ybits[4];                                     // y < 2^m  <=>  ybits <= m
+#pragma unroll
+            for (int c = 0; c < 4; ++c) ybits[c] = 32u - (uint32_t)__clz((b - (64u * c + lane)) & ((1u << n) - 1u));
             uint32_t cnt = 0;
-#pragma unroll 8
-            for (uint32_t x = xl; x <= xh; ++x)
-                if (((b - x) & nmask) < (1u << tid)) cnt += s_hist[x];
-            const double q = (double)cnt / (double)real;
-            const double q2 = q * q, q4 = q2 * q2;
-            double qL = q4 * q4;                                   // p^8
-            if constexpr (LPG >= 2) qL = qL * qL;                  // p^16
-            if constexpr (LPG == 4) qL = qL * qL;                  // p^32
-            s_bexp[tid] = (1.0 / (double)(8 * LPG) + (double)n) + ((double)tid - (double)n) * qL;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t best_m = 0;
-            double best = s_bexp[0];
-            for (uint32_t m = 1; m <= n; ++m)
-                if (s_bexp[m] < best) { best = s_bexp[m]; best_m = m; }          // ties: smaller m
-            s_m = best_m;
+            for (uint32_t j = 0; j <= n; ++j) {
+                uint32_t t = 0;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) t += ybits[c] <= j ? hv[c] : 0u;
+                const uint32_t s = wave_sum32(t);
+                if (lane == j) cnt = s;
+            }
+            const uint32_t best_m = choose_m(cnt, n);
+            if (lane == 0) s_m = best_m;
         }
         __syncthreads();
     }

@@ -302,9 +302,9 @@ def test_tensor_beyond_4_gib_sampled_against_the_oracle(gpu, oracle):
 
 
 @pytest.mark.parametrize("L", [8, 16, 32])
-def test_four_blocks_per_workgroup_all_formats(gpu, oracle, L):
-    """Enough data blocks (>= 256) for the launch in which a workgroup works on four blocks side by side, plus a few left
-    over for the second launch; every element format and group length."""
+def test_a_few_hundred_blocks_all_formats(gpu, oracle, L):
+    """More data blocks than ticket counters and a count that is no multiple of eight, a ragged last block; every
+    element format and group length."""
     B = 16384
     w = _mixed16(261, B, 900 + L)
     _check(gpu, oracle, w[:w.size - 77], BF16, B, f"bf16 L={L}", L)
@@ -314,7 +314,29 @@ def test_four_blocks_per_workgroup_all_formats(gpu, oracle, L):
     _check(gpu, oracle, f, FP32, B, f"fp32 L={L}", L)
 
 
-def test_two_blocks_per_workgroup_at_the_largest_block_size(gpu, oracle):
+def test_the_largest_block_size(gpu, oracle):
     w = _mixed16(131, 32768, 77)
     _check(gpu, oracle, w, BF16, 32768, "B=32768, 131 blocks")
     _check(gpu, oracle, w, BF16, 32768, "B=32768, 131 blocks, L=32", 32)
+
+
+@pytest.mark.parametrize("span", [64, 65, 80, 100, 127, 128, 129, 200, 256])
+def test_blocks_whose_exponents_spread_over_many_values(gpu, oracle, span):
+    """Exponents uniform over `span` consecutive values: from 65 values on the kernel searches (b, n) with the
+    incremental form of Eq. 3's cost, and Eq. 1 gives n = 7 for central b when the spread allows it."""
+    B = 16384
+    rng = np.random.default_rng(span)
+    blocks = []
+    for k in range(6):
+        lo = int(rng.integers(0, 257 - span))
+        e = rng.integers(lo, lo + span, B).astype(np.uint16)
+        if k == 1:        # the same spread, most elements on one value
+            e[rng.random(B) < 0.9] = lo + span // 3
+        if k == 2:        # only the two ends and a few values in between
+            e = np.where(rng.random(B) < 0.5, lo, lo + span - 1).astype(np.uint16)
+            e[:16] = rng.integers(lo, lo + span, 16)
+        blocks.append((rng.integers(0, 2, B).astype(np.uint16) << 15) | (e << 7) | rng.integers(0, 128, B).astype(np.uint16))
+    w = np.concatenate(blocks)
+    _check(gpu, oracle, w, BF16, B, f"bf16 span={span}")
+    f = (w.astype(np.uint32) << 16) | rng.integers(0, 65536, w.size).astype(np.uint32)
+    _check(gpu, oracle, f, FP32, B, f"fp32 span={span}")
