@@ -317,6 +317,26 @@ int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t 
                             void *out, size_t out_capacity, uint64_t *out_bytes, void *workspace,
                             size_t workspace_bytes, void *stream);
 
+/* enec_compress_per_block for several tensors at once [Sec. V-E, per data block]: tensors of one block
+ * size share a launch (up to 16 tensors each, in the order given), whose workgroups take the data
+ * blocks of all of them, so that small tensors cost no launch of their own and the device does not
+ * drain between tensors.  Every field of an item means what the argument of the same name means for
+ * enec_compress_per_block; dtype and group_length hold for all items.  The streams written are the
+ * ones enec_compress_per_block writes.  The workspace must hold enec_workspace_bytes(sum of the
+ * items' n_elems, smallest block size among them) (ENEC_E_CAPACITY otherwise); ENEC_E_ARG also if
+ * the tensors have more than 2^32 - 1 data blocks together.  Every argument is checked before
+ * anything is enqueued.  Asynchronous. */
+typedef struct {
+    const void *in;             /* DEVICE */
+    size_t n_elems;
+    uint32_t block_size;        /* 0 = default */
+    void *out;                  /* DEVICE */
+    size_t out_capacity;
+    uint64_t *out_bytes;        /* device-accessible, or NULL */
+} enec_per_block_item;
+int enec_compress_per_block_batch(const enec_per_block_item *items, size_t n_items, int dtype, uint32_t group_length,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
 /* Host-only search of Sec. V-E phases 2-3 on a given 256-bin exponent histogram (HOST); dtype
  * fixes the cap of Eq. 1's width (the exponent field: 8 bits, fp16: 5). */
 int enec_tune_histogram(const uint64_t *histogram, int dtype, enec_params *params);

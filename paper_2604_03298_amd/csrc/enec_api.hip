@@ -627,61 +627,108 @@ size_t enec_compress_bound_per_block(size_t n_elems, int dtype, uint32_t block_s
     return bound + tuple_table_bytes(n_elems, B);
 }
 
-int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t block_size, uint32_t group_length,
-                            void *out, size_t out_capacity, uint64_t *out_bytes, void *workspace,
-                            size_t workspace_bytes, void *stream)
+int enec_compress_per_block_batch(const enec_per_block_item *items, size_t n_items, int dtype, uint32_t group_length,
+                                  void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(dtype)) return ENEC_E_DTYPE;
-    if (!out || !workspace || (!in && n_elems) || !aligned16(in) || !aligned16(out) || !aligned16(workspace) ||
-        n_elems > MAX_ELEMS)
-        return ENEC_E_ARG;
-    const uint32_t B = block_size ? block_size : enec_default_block_size(n_elems);
-    if (!block_ok(B)) return ENEC_E_BLOCK;
+    if ((!items && n_items) || !workspace || !aligned16(workspace)) return ENEC_E_ARG;
     const unsigned L = group_length ? group_length : 16u;
-    if (!group_ok(L) || !group_fits_block(L, B)) return ENEC_E_PARAMS;
-    if (out_capacity < enec_compress_bound_per_block(n_elems, dtype, B)) return ENEC_E_CAPACITY;
-    if (out_bytes && !device_accessible(out_bytes)) return ENEC_E_ARG;
-    const size_t nb = num_blocks(n_elems, B);
+    if (!group_ok(L)) return ENEC_E_PARAMS;
     hipStream_t s = (hipStream_t)stream;
-    if (nb == 0) {
-        compress_empty_kernel<<<1, 64, 0, s>>>(static_cast<uint8_t *>(out), out_bytes, B, 0, 0, 0, (uint32_t)dtype,
-                                               L | 0x100u);
-        return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+    // every argument is checked before anything is enqueued
+    std::vector<uint32_t> Bs(n_items);
+    size_t need = PB_TICKET_CLASSES * PB_TICKET_STRIDE / 2;      // the ticket counters, in 8-byte words
+    uint64_t blocks = 0;
+    for (size_t i = 0; i < n_items; ++i) {
+        const enec_per_block_item &it = items[i];
+        if (!it.out || (!it.in && it.n_elems) || !aligned16(it.in) || !aligned16(it.out) || it.n_elems > MAX_ELEMS)
+            return ENEC_E_ARG;
+        const uint32_t B = it.block_size ? it.block_size : enec_default_block_size(it.n_elems);
+        if (!block_ok(B)) return ENEC_E_BLOCK;
+        if (!group_fits_block(L, B)) return ENEC_E_PARAMS;
+        if (it.out_capacity < enec_compress_bound_per_block(it.n_elems, dtype, B)) return ENEC_E_CAPACITY;
+        if (it.out_bytes && !device_accessible(it.out_bytes)) return ENEC_E_ARG;
+        Bs[i] = B;
+        const size_t nb = num_blocks(it.n_elems, B);
+        need += nb + (nb & 1);                                   // look-back words, an even number per tensor
+        blocks += nb;
     }
-    // look-back words (and the ticket counters in front of them) behind the accumulators, cleared for this call
+    if (blocks > 0xFFFFFFFFull) return ENEC_E_ARG;               // block numbers are 32 bits wide
+    // ticket counters and look-back words behind the accumulators, cleared for this call
     size_t first = ws_acc_words(workspace_bytes);
-    first += first & 1;                                   // 16-byte aligned for the fill kernel
-    const size_t words = ws_state_words(workspace_bytes);
-    const size_t counters = PB_TICKET_CLASSES * PB_TICKET_STRIDE / 2;      // in 8-byte words
-    const size_t need = counters + nb + (nb & 1);
-    if (words < first + need) return ENEC_E_CAPACITY;
+    first += first & 1;                                          // 16-byte aligned for the fill kernel
+    if (ws_state_words(workspace_bytes) < first + need) return ENEC_E_CAPACITY;
+    PbCompressFn fn = pick_compress_per_block(dtype, L);
+    if (!fn) return ENEC_E_DTYPE;
     uint64_t *base = reinterpret_cast<uint64_t *>(static_cast<uint8_t *>(workspace) + WS_STATE) + first;
     const uint64_t nvec = need / 2;
     const unsigned fill_grid = (unsigned)((nvec + 255) / 256 < 1024 ? (nvec + 255) / 256 : 1024);
     fill_zero_kernel<<<fill_grid, 256, 0, s>>>(reinterpret_cast<uint4 *>(base), nvec);
-    PbCompressArgs a;
-    a.in = in;
-    a.out = static_cast<uint8_t *>(out);
-    a.out_bytes = reinterpret_cast<unsigned long long *>(out_bytes);
-    a.ticket = reinterpret_cast<uint32_t *>(base);
-    a.words = base + counters;
-    a.n_elems = n_elems;
-    a.tuples_at = table_end(n_elems, B);
-    a.tail_base = a.tuples_at + tuple_table_bytes(n_elems, B);
-    a.payload_base = payload_base(n_elems, B, dtype) + tuple_table_bytes(n_elems, B);
-    a.nb = (uint32_t)nb; a.B = B; a.logB = ilog2(B);
-    a.spin_limit = spin_limit();
-    PbCompressFn fn = pick_compress_per_block(dtype, L);
-    if (!fn) return ENEC_E_DTYPE;
-    // one workgroup per data block, a thread per 64 elements (at least a wave); dynamic LDS: mask | low
-    // plane | high records (at most 8 plane bits together), before that the histogram copies; behind
-    // it the raw bytes of the rows that do not wait in registers
-    const unsigned threads = B / 64 < 64 ? 64 : B / 64;
-    const size_t image = (size_t)B / (8 * L) + (size_t)B, hist = (size_t)PB_HIST_COPIES * PB_HIST_STRIDE * 4;
-    const size_t lds = (image > hist ? image : hist) + 15 & ~(size_t)15;
-    a.park_at = (uint32_t)lds;
-    hipLaunchKernelGGL(fn, dim3((unsigned)nb), dim3(threads), lds + (size_t)(8 - PB_SM_REG_ROWS) * threads * 8, s, a);
+    uint64_t *words = base + PB_TICKET_CLASSES * PB_TICKET_STRIDE / 2;
+    uint64_t next_block = 0;        // the data blocks of the call are numbered through, launch after launch
+    std::vector<char> done(n_items, 0);
+    for (size_t i0 = 0; i0 < n_items; ++i0) {
+        if (done[i0]) continue;
+        const enec_per_block_item &it0 = items[i0];
+        if (it0.n_elems == 0) {     // a header and an empty table
+            compress_empty_kernel<<<1, 64, 0, s>>>(static_cast<uint8_t *>(it0.out), it0.out_bytes, Bs[i0], 0, 0, 0,
+                                                   (uint32_t)dtype, L | 0x100u);
+            done[i0] = 1;
+            continue;
+        }
+        // one launch for up to MAX_BATCH tensors of this block size, in the order given
+        const uint32_t B = Bs[i0];
+        PbCompressArgs a;
+        a.ticket = reinterpret_cast<uint32_t *>(base);
+        a.n_items = 0;
+        a.first_block = (uint32_t)next_block;
+        a.B = B; a.logB = ilog2(B);
+        a.spin_limit = spin_limit();
+        for (size_t i = i0; i < n_items && a.n_items < (uint32_t)MAX_BATCH; ++i) {
+            const enec_per_block_item &it = items[i];
+            if (done[i] || Bs[i] != B || it.n_elems == 0) continue;
+            const size_t nb = num_blocks(it.n_elems, B);
+            PbCompressItem &d = a.item[a.n_items++];
+            d.in = it.in;
+            d.out = static_cast<uint8_t *>(it.out);
+            d.out_bytes = reinterpret_cast<unsigned long long *>(it.out_bytes);
+            d.words = words;
+            d.n_elems = it.n_elems;
+            d.tuples_at = table_end(it.n_elems, B);
+            d.tail_base = d.tuples_at + tuple_table_bytes(it.n_elems, B);
+            d.payload_base = payload_base(it.n_elems, B, dtype) + tuple_table_bytes(it.n_elems, B);
+            d.nb = (uint32_t)nb;
+            d.first = (uint32_t)next_block;
+            words += nb + (nb & 1);
+            next_block += nb;
+            done[i] = 1;
+        }
+        for (uint32_t i = a.n_items; i < (uint32_t)MAX_BATCH; ++i) a.item[i] = a.item[0];
+        a.n_blocks = (uint32_t)(next_block - a.first_block);
+        // one workgroup per data block, a thread per 64 elements (at least a wave); dynamic LDS: mask | low
+        // plane | high records (at most 8 plane bits together), before that the histogram copies; behind
+        // it the raw bytes of the rows that do not wait in registers
+        const unsigned threads = B / 64 < 64 ? 64 : B / 64;
+        const size_t image = (size_t)B / (8 * L) + (size_t)B, hist = (size_t)PB_HIST_COPIES * PB_HIST_STRIDE * 4;
+        const size_t lds = (image > hist ? image : hist) + 15 & ~(size_t)15;
+        a.park_at = (uint32_t)lds;
+        hipLaunchKernelGGL(fn, dim3(a.n_blocks), dim3(threads), lds + (size_t)(8 - PB_SM_REG_ROWS) * threads * 8, s, a);
+    }
     return hipGetLastError() == hipSuccess ? ENEC_OK : ENEC_E_HIP;
+}
+
+int enec_compress_per_block(const void *in, size_t n_elems, int dtype, uint32_t block_size, uint32_t group_length,
+                            void *out, size_t out_capacity, uint64_t *out_bytes, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    enec_per_block_item it;
+    it.in = in;
+    it.n_elems = n_elems;
+    it.block_size = block_size;
+    it.out = out;
+    it.out_capacity = out_capacity;
+    it.out_bytes = out_bytes;
+    return enec_compress_per_block_batch(&it, 1, dtype, group_length, workspace, workspace_bytes, stream);
 }
 
 int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, void *stream)

@@ -32,17 +32,26 @@ constexpr uint32_t PB_HIST_COPIES = 16, PB_HIST_STRIDE = 257;   // words; 16 * 2
 // PB_TICKET_STRIDE 32-bit words apart (a cache line each)
 constexpr uint32_t PB_TICKET_CLASSES = 8, PB_TICKET_STRIDE = 16;
 
-struct PbCompressArgs {
+struct PbCompressItem {         // one tensor of a launch
     const void *in;
     uint8_t *out;
     unsigned long long *out_bytes;
     uint64_t *words;            // nb look-back words, zero at launch
-    uint32_t *ticket;           // PB_TICKET_CLASSES counters, zero at launch
     uint64_t n_elems;
     uint64_t tuples_at;         // byte offset of the tuple table in the stream
     uint64_t tail_base;         // fp32: where the lower halves go
     uint64_t payload_base;
-    uint32_t nb, B, logB, spin_limit;
+    uint32_t nb;
+    uint32_t first;             // number of its first data block; the blocks of a call are numbered through
+};
+
+struct PbCompressArgs {
+    PbCompressItem item[MAX_BATCH];
+    uint32_t *ticket;           // PB_TICKET_CLASSES counters, zero before the call's first launch
+    uint32_t n_items;
+    uint32_t first_block;       // this launch codes blocks first_block .. first_block + n_blocks - 1
+    uint32_t n_blocks;
+    uint32_t B, logB, spin_limit;
     uint32_t park_at;           // byte offset in the dynamic LDS where raw bytes wait (behind the image)
 };
 constexpr int PB_SM_REG_ROWS = 4;               // rows of a thread's raw bytes kept in registers; the other rows wait in LDS

@@ -71,18 +71,18 @@ __device__ __forceinline__ uint32_t pb_width_for(uint32_t b, uint32_t l, uint32_
 // a1: the 8 rows of data block k as 128-bit vectors (a thread's 8 elements of a row are one vector,
 // two for fp32); elements beyond the tensor's end read as zero words
 template <int DT>
-__device__ __forceinline__ void pb_load_rows(const PbCompressArgs &p, uint32_t k, uint32_t tid, bool active,
+__device__ __forceinline__ void pb_load_rows(const void *src, uint64_t n_elems, uint32_t B, uint32_t logB, uint32_t k, uint32_t tid, bool active,
                                              uint32_t logC, uint4 (&raw)[DT == DT_FP32 ? 16 : 8])
 {
-    const uint64_t blk0 = (uint64_t)k << p.logB;
-    const uint32_t real = p.n_elems - blk0 < p.B ? (uint32_t)(p.n_elems - blk0) : p.B;
+    const uint64_t blk0 = (uint64_t)k << logB;
+    const uint32_t real = n_elems - blk0 < B ? (uint32_t)(n_elems - blk0) : B;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const uint32_t at = ((uint32_t)t << logC) + 8u * tid;         // first element of the thread in this row
         if constexpr (DT == DT_FP32) {
             uint4 u = make_uint4(0, 0, 0, 0), v = make_uint4(0, 0, 0, 0);
             if (active && at < real) {
-                const uint32_t *in = reinterpret_cast<const uint32_t *>(p.in) + blk0 + at;
+                const uint32_t *in = reinterpret_cast<const uint32_t *>(src) + blk0 + at;
                 if (at + 8u <= real) {
                     u = *reinterpret_cast<const uint4 *>(in);
                     v = *reinterpret_cast<const uint4 *>(in + 4);
@@ -100,7 +100,7 @@ __device__ __forceinline__ void pb_load_rows(const PbCompressArgs &p, uint32_t k
         } else {
             uint4 r = make_uint4(0, 0, 0, 0);
             if (active && at < real) {
-                const uint16_t *in = reinterpret_cast<const uint16_t *>(p.in) + blk0 + at;
+                const uint16_t *in = reinterpret_cast<const uint16_t *>(src) + blk0 + at;
                 if (at + 8u <= real) {
                     r = *reinterpret_cast<const uint4 *>(in);
                 } else {
@@ -173,10 +173,10 @@ __device__ __forceinline__ uint32_t wave_min32(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-// waves per SIMD the compress kernel is built for: bf16 with groups of 16 fits six without spilling,
-// the other instances would spill the raw bytes (which are reloaded when the block is stored, after
-// they have left the L2) and stay at five
-#define PB_COMPRESS_WAVES ((DT == DT_BF16 && LPG == 2) ? 6 : 5)
+// waves per SIMD the compress kernel is built for: six where the instance fits 80 registers without
+// spilling (fp16, and bf16 with groups of 16), five elsewhere: a spill here parks raw bytes in scratch
+// memory, and they are reloaded when the block is stored, after they have left the L2
+#define PB_COMPRESS_WAVES ((DT == DT_FP32 || (DT == DT_BF16 && LPG != 2)) ? 5 : 6)
 
 template <int DT, int LPG>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(PB_COMPRESS_WAVES, PB_COMPRESS_WAVES)))
@@ -207,7 +207,7 @@ compress_per_block_kernel(const PbCompressArgs p)
     // the t-th draw from counter c is block 8 t + c, and a class has as many workgroups as blocks.
     // Returning atomics on one address are serialised at the memory side; with eight addresses the
     // kernel measured 5 % faster than with one.
-    const uint32_t cls = blockIdx.x & (PB_TICKET_CLASSES - 1u);
+    const uint32_t cls = (p.first_block + blockIdx.x) & (PB_TICKET_CLASSES - 1u);
     uint32_t ticket = 0;
     if (tid == 0) {
         ticket = atomicAdd(p.ticket + PB_TICKET_STRIDE * cls, 1u);
@@ -224,13 +224,19 @@ compress_per_block_kernel(const PbCompressArgs p)
         reinterpret_cast<uint4 *>(hcopy)[i] = make_uint4(0, 0, 0, 0);
     if (tid == 0) s_ticket = ticket;
     __syncthreads();
-    const uint32_t k = s_ticket * PB_TICKET_CLASSES + cls;
-    if (k >= p.nb) return;                               // (never: a class has as many workgroups as blocks)
+    // the tensor this block belongs to (the blocks of the call's tensors are numbered through)
+    const uint32_t kg = __builtin_amdgcn_readfirstlane(s_ticket * PB_TICKET_CLASSES + cls);
+    if (kg - p.first_block >= p.n_blocks) return;        // (never: a class has as many workgroups as blocks)
+    uint32_t ti = 0;
+    for (uint32_t i = 1; i < p.n_items; ++i)
+        if (kg >= p.item[i].first) ti = i;
+    const PbCompressItem &it = p.item[ti];
+    const uint32_t k = kg - it.first;
     uint4 raw[RW];
-    pb_load_rows<DT>(p, k, tid, active, logC, raw);
+    pb_load_rows<DT>(it.in, it.n_elems, B, p.logB, k, tid, active, logC, raw);
     uint32_t *mine = hcopy + (lane & (PB_HIST_COPIES - 1u)) * PB_HIST_STRIDE;
     const uint64_t blk0 = (uint64_t)k << p.logB;
-    const uint32_t real = p.n_elems - blk0 < B ? (uint32_t)(p.n_elems - blk0) : B;   // elements that are not pads
+    const uint32_t real = it.n_elems - blk0 < B ? (uint32_t)(it.n_elems - blk0) : B;   // elements that are not pads
     const bool full = real == B && nact >= 64u;          // no pads and no idle lanes (uniform)
 
     // ---- a1: rows, split into exponent bytes X and raw bytes SM; fp16's three left-over mantissa bits
@@ -251,7 +257,7 @@ compress_per_block_kernel(const PbCompressArgs p)
                              byte_perm(v.y, v.x, 0x07060302u), byte_perm(v.w, v.z, 0x07060302u));
             // the lower halves leave at once (pads have zero lower halves; the region is padded to 16 bytes)
             if (active && at < real)
-                *reinterpret_cast<uint4 *>(p.out + p.tail_base + 2u * (blk0 + at)) =
+                *reinterpret_cast<uint4 *>(it.out + it.tail_base + 2u * (blk0 + at)) =
                     make_uint4(byte_perm(u.y, u.x, 0x05040100u), byte_perm(u.w, u.z, 0x05040100u),
                                byte_perm(v.y, v.x, 0x05040100u), byte_perm(v.w, v.z, 0x05040100u));
         } else {
@@ -490,7 +496,7 @@ compress_per_block_kernel(const PbCompressArgs p)
     const uint32_t cnt = __shfl(my_incl, 63, 64);
     const uint32_t S = (fixed + (uint32_t)LPG * a * cnt + 15u) & ~15u;
     // ---- a6: the size is known: publish it before anything else ----
-    if (tid == 0) st_state(p.words + k, PB_SIZE | (uint64_t)(S >> 4));
+    if (tid == 0) st_state(it.words + k, PB_SIZE | (uint64_t)(S >> 4));
 
     // ---- a4 low plane ----
     if (active) {
@@ -535,7 +541,7 @@ compress_per_block_kernel(const PbCompressArgs p)
             for (;;) {
 #pragma unroll
                 for (int w = 0; w < PB_WINDOW / 64; ++w)
-                    if (!ok[w]) v[w] = ld_state(p.words + (top - 64 * w - (int64_t)lane));
+                    if (!ok[w]) v[w] = ld_state(it.words + (top - 64 * w - (int64_t)lane));
                 // the nearest block with a prefix; everything above it must be there
                 bool missing = false;
                 first_w = PB_WINDOW / 64;
@@ -571,14 +577,14 @@ compress_per_block_kernel(const PbCompressArgs p)
         if (lane == 0) {
             s_off = sum << 4;
             s_flags = flags;
-            st_state(p.words + k, PB_PREFIX | ((flags & 4u) ? PB_GAVE_UP : 0ull) | (sum + (S >> 4)));
+            st_state(it.words + k, PB_PREFIX | ((flags & 4u) ? PB_GAVE_UP : 0ull) | (sum + (S >> 4)));
         }
     }
     __syncthreads();
 
     // ---- a7: stores ----
     const uint64_t off = s_off;
-    uint8_t *dst = p.out + p.payload_base + off;
+    uint8_t *dst = it.out + it.payload_base + off;
     if (active) {
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
@@ -620,29 +626,29 @@ compress_per_block_kernel(const PbCompressArgs p)
         }
     }
     if (tid == 0) {
-        uint64_t *table = reinterpret_cast<uint64_t *>(p.out + 64);
+        uint64_t *table = reinterpret_cast<uint64_t *>(it.out + 64);
         table[k] = off;
-        *reinterpret_cast<uint32_t *>(p.out + p.tuples_at + 4u * k) = b | (n << 8) | (m << 16);
-        if (k == p.nb - 1u) {
+        *reinterpret_cast<uint32_t *>(it.out + it.tuples_at + 4u * k) = b | (n << 8) | (m << 16);
+        if (k == it.nb - 1u) {
             const uint64_t end = off + S;
             const uint32_t status = (s_flags & 4u) ? 8u : 0u;
-            const uint64_t total = status ? 0ull : p.payload_base + end;
-            table[p.nb] = end;
-            if (((uint64_t)(p.nb + 1u) & 1ull)) table[p.nb + 1u] = 0;          // pad up to the tuple table
-            for (uint32_t i = p.nb; i < ((p.nb + 3u) & ~3u); ++i)              // pad behind the tuple table
-                *reinterpret_cast<uint32_t *>(p.out + p.tuples_at + 4u * i) = 0;
-            uint32_t *h = reinterpret_cast<uint32_t *>(p.out);
+            const uint64_t total = status ? 0ull : it.payload_base + end;
+            table[it.nb] = end;
+            if (((uint64_t)(it.nb + 1u) & 1ull)) table[it.nb + 1u] = 0;          // pad up to the tuple table
+            for (uint32_t i = it.nb; i < ((it.nb + 3u) & ~3u); ++i)              // pad behind the tuple table
+                *reinterpret_cast<uint32_t *>(it.out + it.tuples_at + 4u * i) = 0;
+            uint32_t *h = reinterpret_cast<uint32_t *>(it.out);
             h[0] = 0x43454E45u;                                                // "ENEC"
             h[1] = 1u | ((uint32_t)DT << 16) | ((8u * LPG) << 24);             // version, dtype, L
-            h[2] = (uint32_t)p.n_elems; h[3] = (uint32_t)(p.n_elems >> 32);
-            h[4] = B; h[5] = p.nb;
+            h[2] = (uint32_t)it.n_elems; h[3] = (uint32_t)(it.n_elems >> 32);
+            h[4] = B; h[5] = it.nb;
             h[6] = E << 24;                                                    // (b, n, m) = 0: see the tuple table
             h[7] = status;
             h[8] = (uint32_t)total; h[9] = (uint32_t)(total >> 32);
             h[10] = 1u;                                                        // one tuple per block
 #pragma unroll
             for (int i = 11; i < 16; ++i) h[i] = 0;
-            if (p.out_bytes) *p.out_bytes = total;
+            if (it.out_bytes) *it.out_bytes = total;
         }
     }
 }

@@ -23,7 +23,7 @@ EXPORTS = [
     "enec_workspace_bytes", "enec_workspace_init", "enec_compress", "enec_decompress",
     "enec_decompress_with_header", "enec_tune", "enec_tune_histogram", "enec_stream_info",
     "enec_copy", "enec_compress_batch", "enec_decompress_batch", "enec_tune_histogram_groups",
-    "enec_tune_sampled", "enec_compress_sampled", "enec_compress_bound_per_block", "enec_compress_per_block",
+    "enec_tune_sampled", "enec_compress_sampled", "enec_compress_bound_per_block", "enec_compress_per_block", "enec_compress_per_block_batch",
     "enec_tune_batch", "enec_compress_static", "enec_pipeline_create", "enec_pipeline_destroy",
     "enec_pipeline_prefetch", "enec_pipeline_prefetch_from_host", "enec_pipeline_acquire", "enec_pipeline_release",
     "enec_pipeline_trace",
@@ -50,6 +50,11 @@ class CompressItem(C.Structure):
 class DecompressItem(C.Structure):
     _fields_ = [("src", C.c_void_p), ("in_bytes", C.c_size_t), ("host_header", C.c_void_p),
                 ("out", C.c_void_p), ("n_elems", C.c_size_t), ("status", C.c_void_p)]
+
+
+class PerBlockItem(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("n_elems", C.c_size_t), ("block_size", C.c_uint32), ("out", C.c_void_p),
+                ("out_capacity", C.c_size_t), ("out_bytes", C.c_void_p)]
 
 
 class OffloadItem(C.Structure):
@@ -102,6 +107,8 @@ def lib():
         L.enec_compress_bound_per_block.argtypes = [sz, C.c_int, C.c_uint32]
         L.enec_compress_per_block.restype = C.c_int
         L.enec_compress_per_block.argtypes = [vp, sz, C.c_int, C.c_uint32, C.c_uint32, vp, sz, vp, vp, sz, vp]
+        L.enec_compress_per_block_batch.restype = C.c_int
+        L.enec_compress_per_block_batch.argtypes = [C.POINTER(PerBlockItem), sz, C.c_int, C.c_uint32, vp, sz, vp]
         L.enec_tune_batch.restype = C.c_int
         L.enec_tune_batch.argtypes = [C.POINTER(TuneItem), sz, C.c_int, C.c_uint32, C.POINTER(Params), u64p, vp, sz, vp]
         L.enec_tune_sampled.restype = C.c_int
@@ -281,6 +288,25 @@ def compress_per_block(src, out, workspace, block_size: int = 0, out_bytes=None,
         C.c_void_p(src.data_ptr()), n, dt, block_size, group_length, C.c_void_p(out.data_ptr()),
         out.numel() * out.element_size(), ob, C.c_void_p(workspace.data_ptr()),
         workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+def compress_per_block_batch(srcs, outs, workspace, out_bytes=None, stream=None, dtype: int | None = None,
+                             block_sizes=None, group_length: int = 0) -> int:
+    """Enqueues enec_compress_per_block_batch: the tensors of one block size share a launch.  out_bytes: None or
+    one device int64 tensor (or None) per tensor; block_sizes: None (defaults) or one block size per tensor."""
+    n = len(srcs)
+    items = (PerBlockItem * max(n, 1))()
+    for i in range(n):
+        items[i].src = srcs[i].data_ptr()
+        items[i].n_elems = srcs[i].numel()
+        items[i].block_size = block_sizes[i] if block_sizes is not None else 0
+        items[i].out = outs[i].data_ptr()
+        items[i].out_capacity = outs[i].numel() * outs[i].element_size()
+        ob = out_bytes[i] if out_bytes is not None else None
+        items[i].out_bytes = ob.data_ptr() if ob is not None else None
+    dt = dtype_of(srcs[0], dtype) if n else (BF16 if dtype is None else dtype)
+    return int(lib().enec_compress_per_block_batch(items, n, dt, group_length, C.c_void_p(workspace.data_ptr()),
+                                                   workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 
 
 def decompress(stream_buf, out, n_elems: int | None = None, stream=None) -> int:

@@ -80,17 +80,17 @@ def run_group(torch, enec, name, srcs, reps=5, dtype=0, lengths=None):
 
 
 def run_per_block(torch, enec, name, srcs, reps=5, dtype=0):
-    """The same measurement for streams with one tuple per data block (one launch per tensor)."""
+    """The same measurement for streams with one tuple per data block (all tensors in one batched call)."""
     n_el = [s.numel() for s in srcs]
     raw = srcs[0].element_size() * sum(n_el)
-    ws = enec.new_workspace(max(n_el))
+    ws = enec.new_workspace(sum(n_el), block_size=min(enec.default_block_size(n) for n in n_el))
     outs = [torch.empty(enec.compress_bound_per_block(n, dtype=dtype), dtype=torch.uint8, device="cuda") for n in n_el]
     sizes = torch.zeros(len(srcs), dtype=torch.int64, device="cuda")
+    szl = [sizes[i:i + 1] for i in range(len(srcs))]
 
     def comp():
-        for i, s in enumerate(srcs):
-            rc = enec.compress_per_block(s, outs[i], ws, out_bytes=sizes[i:i + 1], dtype=dtype)
-            assert rc == 0, enec.strerror(rc)
+        rc = enec.compress_per_block_batch(srcs, outs, ws, out_bytes=szl, dtype=dtype)
+        assert rc == 0, enec.strerror(rc)
 
     comp()
     torch.cuda.synchronize()

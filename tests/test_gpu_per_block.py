@@ -340,3 +340,78 @@ def test_blocks_whose_exponents_spread_over_many_values(gpu, oracle, span):
     _check(gpu, oracle, w, BF16, B, f"bf16 span={span}")
     f = (w.astype(np.uint32) << 16) | rng.integers(0, 65536, w.size).astype(np.uint32)
     _check(gpu, oracle, f, FP32, B, f"fp32 span={span}")
+
+
+def _batch(gpu, ws_list, dtype, Bs=None, L=0, workspace=None):
+    """enec_compress_per_block_batch on the tensors of ws_list; returns rc and, per tensor, (stream bytes, size, bound)."""
+    torch, enec = gpu.torch, gpu.enec
+    srcs = [gpu.to_dev(w, dtype) for w in ws_list]
+    caps = [enec.compress_bound_per_block(w.size, dtype=dtype, block_size=(Bs[i] if Bs else 0)) for i, w in enumerate(ws_list)]
+    outs = [torch.full((c + 64,), 0xA5, dtype=torch.uint8, device="cuda") for c in caps]
+    sizes = torch.full((len(ws_list),), -1, dtype=torch.int64, device="cuda")
+    items_n = [w.size for w in ws_list]
+    # the binding takes numel() of the tensors: empty tensors travel as 8-element dummies, so pass views of the right length
+    srcs = [s[:n] for s, n in zip(srcs, items_n)]
+    rc = enec.compress_per_block_batch(srcs, outs, gpu.ws if workspace is None else workspace,
+                                       out_bytes=[sizes[i:i + 1] for i in range(len(ws_list))], dtype=dtype,
+                                       block_sizes=Bs, group_length=L)
+    torch.cuda.synchronize()
+    return rc, [(o.cpu().numpy(), int(s), c) for o, s, c in zip(outs, sizes.cpu(), caps)]
+
+
+@pytest.mark.parametrize("L", [8, 16, 32])
+def test_batch_of_tensors_equals_the_oracle_tensor_by_tensor(gpu, oracle, L):
+    """Several tensors in one call: different lengths (one block, many blocks, a ragged tail, empty), two block
+    sizes (two launches) and more than 16 tensors of one block size (a launch holds 16); every stream is the
+    oracle's, byte for byte, and nothing is written past a tensor's bound."""
+    B = 16384
+    ws_list = [_mixed16(37, B, 1), _mixed16(1, B, 2)[:5000], _mixed16(300, B, 3)[:300 * B - 77], np.zeros(0, np.uint16),
+               _mixed16(9, 4096, 4), W.gaussian(8 * B, 0.02, 5), _mixed16(2, 4096, 6)[:4097]]
+    ws_list += [_mixed16(1 + (i % 3), B, 10 + i) for i in range(17)]
+    Bs = [B, B, B, B, 4096, B, 4096] + [B] * 17
+    rc, res = _batch(gpu, ws_list, BF16, Bs, L)
+    assert rc == 0
+    for i, (w, (out, nbytes, cap)) in enumerate(zip(ws_list, res)):
+        rc_o, s_o = oracle.compress_per_block(w, Bs[i], BF16, L)
+        assert rc_o == oracle.OK
+        assert nbytes == s_o.size, f"tensor {i}: size {nbytes} vs oracle {s_o.size}"
+        assert np.array_equal(out[:nbytes], s_o), f"tensor {i}: stream differs from the oracle's"
+        assert (out[cap:] == 0xA5).all(), f"tensor {i}: wrote past the bound"
+
+
+def test_batch_default_block_sizes_and_other_formats(gpu, oracle):
+    """Block size 0 = each tensor's default (small tensors get smaller blocks, hence a launch of their own); fp16 and
+    fp32 batches."""
+    ws_list = [W.gaussian(100000, 0.02, 1), W.gaussian(4096, 0.5, 2), W.gaussian(3000, 0.02, 3), W.gaussian(70000, 0.1, 4)]
+    rc, res = _batch(gpu, ws_list, BF16)
+    assert rc == 0
+    for w, (out, nbytes, cap) in zip(ws_list, res):
+        rc_o, s_o = oracle.compress_per_block(w, oracle.default_block(w.size), BF16, 16)
+        assert rc_o == oracle.OK and nbytes == s_o.size and np.array_equal(out[:nbytes], s_o)
+    hs = [_mixed16(5, 16384, 31, FP16), _mixed16(3, 16384, 32, FP16)[:40000]]
+    rc, res = _batch(gpu, hs, FP16, [16384, 16384])
+    assert rc == 0
+    for w, (out, nbytes, cap) in zip(hs, res):
+        rc_o, s_o = oracle.compress_per_block(w, 16384, FP16, 16)
+        assert rc_o == oracle.OK and nbytes == s_o.size and np.array_equal(out[:nbytes], s_o)
+    fs = [W.gaussian_fp32(5 * 16384 + 3, 0.02, 1), W.gaussian_fp32(16384, 3.0, 2)]
+    rc, res = _batch(gpu, fs, FP32, [16384, 16384])
+    assert rc == 0
+    for w, (out, nbytes, cap) in zip(fs, res):
+        rc_o, s_o = oracle.compress_per_block(w, 16384, FP32, 16)
+        assert rc_o == oracle.OK and nbytes == s_o.size and np.array_equal(out[:nbytes], s_o)
+
+
+def test_batch_host_checks(gpu):
+    torch, enec = gpu.torch, gpu.enec
+    w = gpu.to_dev(W.gaussian(16384 * 4, 0.02, 1), BF16)
+    good = torch.empty(enec.compress_bound_per_block(w.numel()), dtype=torch.uint8, device="cuda")
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    assert enec.compress_per_block_batch([w, w], [good, small], gpu.ws) == 5          # capacity: nothing is enqueued
+    assert enec.compress_per_block_batch([w], [good], gpu.ws, block_sizes=[3000]) == 3    # block size
+    assert enec.compress_per_block_batch([w], [good], gpu.ws, block_sizes=[2048], group_length=32) == 4   # L does not fit
+    tiny_ws = torch.zeros(enec.workspace_bytes(2048) // 8, dtype=torch.int64, device="cuda")
+    big = gpu.to_dev(W.gaussian(16384 * 4096, 0.02, 2), BF16)
+    out = torch.empty(enec.compress_bound_per_block(big.numel()), dtype=torch.uint8, device="cuda")
+    assert enec.compress_per_block_batch([big], [out], tiny_ws) == 5                  # workspace too small
+    assert enec.compress_per_block_batch([], [], gpu.ws) == 0
