@@ -306,7 +306,7 @@ int enec_compress_sampled(const void *in, size_t n_elems, int dtype, uint32_t bl
  *   the tuples, 4 bytes per block (b, n, m, 0), zero-padded to a multiple of 16, between the offset
  *   table and the fp32 region / the payloads.
  * enec_decompress, enec_decompress_with_header and enec_decompress_batch read such streams as any
- * other (a launch of its own per stream).  Arguments as for enec_compress, without params;
+ * other (in a batch, such streams of one element format, group length and block size share a launch).  Arguments as for enec_compress, without params;
  * group_length = 8, 16, 32 or 0 (= 16) is the group length the blocks are coded with (ENEC_E_PARAMS if
  * the block size does not admit it; the search evaluates Eq. 4, 1/L + n + (m - n) p(m)^L, with that length);
  * out_capacity >= enec_compress_bound_per_block(n_elems, dtype, block_size) (0 for an invalid dtype

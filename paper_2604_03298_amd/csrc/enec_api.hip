@@ -762,25 +762,40 @@ int enec_decompress_batch(const enec_decompress_item *items, size_t n_items, voi
         for (size_t i = 0; i < n_items; ++i) {
             if (done[i]) continue;
             if (hdr[i].nb == 0) { done[i] = 1; continue; }
-            if (hdr[i].per_block) {                      // its tuples are in the stream: a launch of its own
-                const Header &h = hdr[i];
+            if (hdr[i].per_block) {
+                // streams with one tuple per block: those of one element format, group length and block size
+                // share a launch (up to MAX_BATCH each); their tuples are read from the streams
+                const Header &h0 = hdr[i];
                 PbDecompressArgs a;
-                a.in = static_cast<const uint8_t *>(items[i].in);
-                a.out = items[i].out;
-                a.n_elems = items[i].n_elems;
-                a.tuples_at = table_end(a.n_elems, h.B);
-                a.tail_base = a.tuples_at + tuple_table_bytes(a.n_elems, h.B);
-                a.payload_base = payload_base(a.n_elems, h.B, h.dtype) + tuple_table_bytes(a.n_elems, h.B);
-                a.payload_bytes = h.total - a.payload_base;
-                a.nb = h.nb; a.B = h.B; a.logB = ilog2(h.B);
-                a.status = items[i].status;
-                std::memcpy(a.hdr, items[i].host_header, sizeof a.hdr);
-                PbDecompressFn fn = pick_decompress_per_block(h.dtype, h.prm.L);
+                a.n_items = 0;
+                a.n_blocks = 0;
+                a.B = h0.B; a.logB = ilog2(h0.B);
+                for (size_t j = i; j < n_items && a.n_items < (uint32_t)MAX_BATCH; ++j) {
+                    const Header &h = hdr[j];
+                    if (done[j] || h.nb == 0 || !h.per_block || h.B != h0.B || h.dtype != h0.dtype || h.prm.L != h0.prm.L ||
+                        (uint64_t)a.n_blocks + h.nb > 0xFFFFFFFFull)
+                        continue;
+                    PbDecompressItem &d = a.item[a.n_items++];
+                    d.in = static_cast<const uint8_t *>(items[j].in);
+                    d.out = items[j].out;
+                    d.n_elems = items[j].n_elems;
+                    d.tuples_at = table_end(d.n_elems, h.B);
+                    d.tail_base = d.tuples_at + tuple_table_bytes(d.n_elems, h.B);
+                    d.payload_base = payload_base(d.n_elems, h.B, h.dtype) + tuple_table_bytes(d.n_elems, h.B);
+                    d.payload_bytes = h.total - d.payload_base;
+                    d.nb = h.nb;
+                    d.first = a.n_blocks;
+                    d.status = items[j].status;
+                    std::memcpy(d.hdr, items[j].host_header, sizeof d.hdr);
+                    a.n_blocks += h.nb;
+                    done[j] = 1;
+                }
+                for (uint32_t j = a.n_items; j < (uint32_t)MAX_BATCH; ++j) a.item[j] = a.item[0];
+                PbDecompressFn fn = pick_decompress_per_block(h0.dtype, h0.prm.L);
                 if (!fn) return ENEC_E_FORMAT;
-                const unsigned threads = h.B / 64 < 64 ? 64 : h.B / 64;
-                const size_t lds = (size_t)h.B / (8 * h.prm.L) + h.B + 16;     // the packed part of the widest block
-                hipLaunchKernelGGL(fn, dim3(h.nb), dim3(threads), lds, s, a);
-                done[i] = 1;
+                const unsigned threads = h0.B / 64 < 64 ? 64 : h0.B / 64;
+                const size_t lds = (size_t)h0.B / (8 * h0.prm.L) + h0.B + 16;     // the packed part of the widest block
+                hipLaunchKernelGGL(fn, dim3(a.n_blocks), dim3(threads), lds, s, a);
                 continue;
             }
             DecompressArgs a;

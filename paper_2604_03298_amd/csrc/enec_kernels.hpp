@@ -56,14 +56,21 @@ struct PbCompressArgs {
 };
 constexpr int PB_SM_REG_ROWS = 4;               // rows of a thread's raw bytes kept in registers; the other rows wait in LDS
 
-struct PbDecompressArgs {
+struct PbDecompressItem {       // one stream of a launch
     const uint8_t *in;
     void *out;
     uint64_t n_elems;
     uint64_t tuples_at, tail_base, payload_base, payload_bytes;
-    uint32_t nb, B, logB;
-    uint32_t hdr[11];           // the header the launch was configured from
+    uint32_t nb;
+    uint32_t first;             // number of its first data block among the blocks of the launch
     uint32_t *status;           // device-accessible or null: set to 7 (format error) when a block is left undecoded
+    uint32_t hdr[11];           // the header the launch was configured from
+};
+
+struct PbDecompressArgs {
+    PbDecompressItem item[MAX_BATCH];
+    uint32_t n_items, n_blocks;
+    uint32_t B, logB;
 };
 
 using PbCompressFn = void (*)(const PbCompressArgs);

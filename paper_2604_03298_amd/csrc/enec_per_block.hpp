@@ -668,17 +668,22 @@ __global__ void __launch_bounds__(512) decompress_per_block_kernel(const PbDecom
     const uint32_t nact = B >> 6;
     const bool active = tid < nact;
     const uint32_t mask_bytes = (B >> 6) >> LOG_LPG;                  // B / (8 L)
-    const uint32_t k = blockIdx.x;
-    if (k >= p.nb) return;
+    // the stream this block belongs to (the blocks of the launch's streams are numbered through)
+    if (blockIdx.x >= p.n_blocks) return;
+    uint32_t ti = 0;
+    for (uint32_t i = 1; i < p.n_items; ++i)
+        if (blockIdx.x >= p.item[i].first) ti = i;
+    const PbDecompressItem &it = p.item[ti];
+    const uint32_t k = blockIdx.x - it.first;
 
     // d1: header as configured, tuple, offsets
-    const uint32_t *hd = reinterpret_cast<const uint32_t *>(p.in);
+    const uint32_t *hd = reinterpret_cast<const uint32_t *>(it.in);
     bool same = true;
 #pragma unroll
-    for (int i = 0; i < 11; ++i) same &= (hd[i] == p.hdr[i]);
-    const uint32_t tup = *reinterpret_cast<const uint32_t *>(p.in + p.tuples_at + 4u * k);
+    for (int i = 0; i < 11; ++i) same &= (hd[i] == it.hdr[i]);
+    const uint32_t tup = *reinterpret_cast<const uint32_t *>(it.in + it.tuples_at + 4u * k);
     const uint32_t b = tup & 0xFFu, n = (tup >> 8) & 0xFFu, m = (tup >> 16) & 0xFFu;
-    const uint64_t *table = reinterpret_cast<const uint64_t *>(p.in + 64);
+    const uint64_t *table = reinterpret_cast<const uint64_t *>(it.in + 64);
     const uint64_t t0 = table[k], t1 = table[k + 1];
     // a block that is skipped (damaged header, tuple or table entry) leaves its part of the output
     // untouched: the caller is told through the status word
@@ -686,11 +691,11 @@ __global__ void __launch_bounds__(512) decompress_per_block_kernel(const PbDecom
     const uint32_t fixed = B + mask_bytes + ((lm * B) >> 3);
     const uint64_t sz = t1 - t0;
     if (!same || n < 1u || n > E || m > n || b >= (1u << E) ||
-        sz < fixed || sz > fixed + (uint32_t)LPG * a * ((B >> 3) >> LOG_LPG) + 15u || ((sz | t0) & 15u) || t0 > p.payload_bytes || sz > p.payload_bytes - t0) {
-        if (tid == 0 && p.status) *p.status = 7u;
+        sz < fixed || sz > fixed + (uint32_t)LPG * a * ((B >> 3) >> LOG_LPG) + 15u || ((sz | t0) & 15u) || t0 > it.payload_bytes || sz > it.payload_bytes - t0) {
+        if (tid == 0 && it.status) *it.status = 7u;
         return;
     }
-    const uint8_t *src = p.in + p.payload_base + t0;
+    const uint8_t *src = it.in + it.payload_base + t0;
     const uint32_t nvec = ((uint32_t)sz - B) >> 4;
     for (uint32_t v = tid; v < nvec; v += blockDim.x)
         *reinterpret_cast<uint4 *>(smem + 16u * v) = *reinterpret_cast<const uint4 *>(src + B + 16u * v);
@@ -766,8 +771,8 @@ __global__ void __launch_bounds__(512) decompress_per_block_kernel(const PbDecom
             o[2 * h + 1] = byte_perm(Hi, Lo, 0x07030602u);
         }
         if constexpr (DT == DT_FP32) {
-            if (e0 < p.n_elems) {
-                const uint4 tl = *reinterpret_cast<const uint4 *>(p.in + p.tail_base + 2u * e0);   // region padded to 16 bytes
+            if (e0 < it.n_elems) {
+                const uint4 tl = *reinterpret_cast<const uint4 *>(it.in + it.tail_base + 2u * e0);   // region padded to 16 bytes
                 const uint32_t lo[4] = {tl.x, tl.y, tl.z, tl.w};
                 uint32_t w[8];
 #pragma unroll
@@ -775,24 +780,24 @@ __global__ void __launch_bounds__(512) decompress_per_block_kernel(const PbDecom
                     w[2 * i] = byte_perm(o[i], lo[i], 0x05040100u);
                     w[2 * i + 1] = byte_perm(o[i], lo[i], 0x07060302u);
                 }
-                uint32_t *out32 = reinterpret_cast<uint32_t *>(p.out);
-                if (e0 + 8 <= p.n_elems) {
+                uint32_t *out32 = reinterpret_cast<uint32_t *>(it.out);
+                if (e0 + 8 <= it.n_elems) {
                     *reinterpret_cast<uint4 *>(out32 + e0) = make_uint4(w[0], w[1], w[2], w[3]);
                     *reinterpret_cast<uint4 *>(out32 + e0 + 4) = make_uint4(w[4], w[5], w[6], w[7]);
                 } else {
 #pragma unroll
                     for (int i = 0; i < 8; ++i)
-                        if (e0 + i < p.n_elems) out32[e0 + i] = w[i];
+                        if (e0 + i < it.n_elems) out32[e0 + i] = w[i];
                 }
             }
         } else {
-            uint16_t *out16 = reinterpret_cast<uint16_t *>(p.out);
-            if (e0 + 8 <= p.n_elems) {
+            uint16_t *out16 = reinterpret_cast<uint16_t *>(it.out);
+            if (e0 + 8 <= it.n_elems) {
                 *reinterpret_cast<uint4 *>(out16 + e0) = make_uint4(o[0], o[1], o[2], o[3]);
-            } else if (e0 < p.n_elems) {
+            } else if (e0 < it.n_elems) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
-                    if (e0 + i < p.n_elems) out16[e0 + i] = (uint16_t)(o[i >> 1] >> (16 * (i & 1)));
+                    if (e0 + i < it.n_elems) out16[e0 + i] = (uint16_t)(o[i >> 1] >> (16 * (i & 1)));
             }
         }
     }

@@ -415,3 +415,32 @@ def test_batch_host_checks(gpu):
     out = torch.empty(enec.compress_bound_per_block(big.numel()), dtype=torch.uint8, device="cuda")
     assert enec.compress_per_block_batch([big], [out], tiny_ws) == 5                  # workspace too small
     assert enec.compress_per_block_batch([], [], gpu.ws) == 0
+
+
+def test_batch_decompress_of_many_per_block_streams(gpu, oracle):
+    """More than 16 streams with one tuple per block in one decompress call (a launch holds 16), a second block size,
+    an empty tensor and one damaged stream: its status word alone is set, its damaged block alone is left undecoded."""
+    torch, enec = gpu.torch, gpu.enec
+    B = 4096
+    ws = [_mixed16(1 + (i * 7) % 13, B, 60 + i)[:(1 + (i * 7) % 13) * B - (i % 3) * 11] for i in range(19)]
+    ws += [_mixed16(3, 16384, 90), np.zeros(0, np.uint16)]
+    Bs = [B] * 19 + [16384, 16384]
+    streams = [oracle.compress_per_block(w, b)[1] for w, b in zip(ws, Bs)]
+    bad = 7
+    at = oracle.table_end(ws[bad].size, B)
+    streams[bad] = streams[bad].copy()
+    streams[bad][at + 4 * 2 + 1] = 0                      # n = 0 in the tuple of block 2
+    bufs = [torch.from_numpy(s).cuda() for s in streams]
+    outs = [torch.full((max(w.size, 8),), 0x5A5A, dtype=torch.int16, device="cuda")[:w.size] for w in ws]
+    statuses = [torch.zeros(1, dtype=torch.int32, device="cuda") for _ in ws]
+    assert enec.decompress_batch(bufs, [s[:64].tobytes() for s in streams], outs, statuses=statuses) == 0
+    torch.cuda.synchronize()
+    for i, (w, o) in enumerate(zip(ws, outs)):
+        got = o.cpu().numpy().view(np.uint16)
+        if i == bad:
+            assert int(statuses[i].item()) == enec.E_FORMAT
+            assert (got[2 * B:3 * B] == 0x5A5A).all()
+            assert np.array_equal(got[:2 * B], w[:2 * B]) and np.array_equal(got[3 * B:], w[3 * B:])
+        else:
+            assert int(statuses[i].item()) == 0, i
+            assert np.array_equal(got, w), i
