@@ -378,7 +378,9 @@ int enec_tune_batch(const enec_tune_item *items, size_t n_items, int dtype, uint
             if (it.n_elems == 0) continue;
             const uint64_t nvec = it.n_elems * elem_bytes(dtype) / 16;
             uint64_t want = (nvec / every + 255) / 256;
-            const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+            // at most two workgroups per CU: every workgroup ends with one global atomic per exponent value it
+            // has seen, and those, a few addresses for the whole grid, were half of the kernel's time at 2048
+            const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 512 ? 512 : want));
             unsigned long long *slot = dhist + 256 * j;
             if (dtype == ENEC_FP32) histogram_kernel<DT_FP32><<<grid, 256, 0, s>>>(it.in, it.n_elems, slot, every);
             else if (dtype == ENEC_FP16) histogram_kernel<DT_FP16><<<grid, 256, 0, s>>>(it.in, it.n_elems, slot, every);

@@ -1358,11 +1358,12 @@ template <int DT>
 __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_t n_elems, unsigned long long *hist,
                                                         uint32_t every)
 {
-    // sixteen copies of the histogram, lane i of every wave counts into copy i mod 16: lanes with equal
+    // 32 copies of the histogram, lane i of every wave counts into copy i mod 32: lanes with equal
     // exponents, the normal case, would otherwise queue up on one LDS word; the copies are 257 words
-    // apart, which puts the same bin of all copies into different banks.  (More copies do not help:
-    // the LDS atomic unit itself, at one to two lanes per clock and CU, is what bounds this kernel.)
-    constexpr uint32_t COPIES = 16, STRIDE = 257;
+    // apart, which puts the same bin of all copies into different banks.  (Measured on this machine:
+    // LDS atomics run at 7.2 lanes per clock and CU when no two lanes of an instruction share a bank
+    // beyond the two that must, 4.6 with sixteen copies and Gaussian weights, 0.5 on one address.)
+    constexpr uint32_t COPIES = 32, STRIDE = 257;
     __shared__ uint32_t s_h[COPIES * STRIDE];
     const uint32_t tid = threadIdx.x;
     for (uint32_t i = tid; i < COPIES * STRIDE; i += 256) s_h[i] = 0;
@@ -1371,16 +1372,12 @@ __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_
     constexpr uint32_t PER_VEC = DT == DT_FP32 ? 4u : 8u;        // elements in 16 bytes
     const uint64_t nvec = n_elems / PER_VEC;
     const uint64_t stride = (uint64_t)gridDim.x * 256u;
-    // the LDS counters cannot overflow: each thread adds at most 8 per iteration and the
-    // launch keeps iterations * 256 * 8 below 2^32
+    // the LDS counters cannot overflow: a workgroup counts at most 2^34 / 512 elements
     // the sample: chunks of SAMPLE_CHUNK elements whose number is a multiple of `every`
     constexpr uint32_t LOG_VPC = DT == DT_FP32 ? 10u : 9u;      // 16-byte vectors in a chunk
     const uint64_t chunks = (nvec + (1u << LOG_VPC) - 1u) >> LOG_VPC;
     const uint64_t picked = ((chunks + every - 1u) / every) << LOG_VPC;
-    for (uint64_t sv = (uint64_t)blockIdx.x * 256u + tid; sv < picked; sv += stride) {
-        const uint64_t v = (((sv >> LOG_VPC) * every) << LOG_VPC) + (sv & ((1u << LOG_VPC) - 1u));
-        if (v >= nvec) continue;
-        const uint4 q = reinterpret_cast<const uint4 *>(in_)[v];
+    auto count = [&](const uint4 q) {
         const uint32_t d[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -1394,6 +1391,27 @@ __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_
                 atomicAdd(&mine[(d[i] >> 23) & 0xFFu], 1u);
             }
         }
+    };
+    auto vec_of = [&](uint64_t sv) { return (((sv >> LOG_VPC) * every) << LOG_VPC) + (sv & ((1u << LOG_VPC) - 1u)); };
+    // four vectors of a thread travel together
+    uint64_t sv = (uint64_t)blockIdx.x * 256u + tid;
+    for (; sv + 3u * stride < picked; sv += 4u * stride) {
+        uint4 q[4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t v = vec_of(sv + u * stride);
+            ok[u] = v < nvec;
+            q[u] = ok[u] ? reinterpret_cast<const uint4 *>(in_)[v] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (ok[u]) count(q[u]);
+    }
+    for (; sv < picked; sv += stride) {
+        const uint64_t v = vec_of(sv);
+        if (v >= nvec) continue;
+        count(reinterpret_cast<const uint4 *>(in_)[v]);
     }
     if (blockIdx.x == 0 && tid < (uint32_t)(n_elems % PER_VEC) && ((nvec * PER_VEC) / SAMPLE_CHUNK) % every == 0) {
         const uint64_t e = nvec * PER_VEC + tid;
