@@ -373,18 +373,35 @@ int enec_tune_batch(const enec_tune_item *items, size_t n_items, int dtype, uint
     for (size_t first = 0; first < n_items; first += WS_HIST_SLOTS) {
         const size_t count = n_items - first < WS_HIST_SLOTS ? n_items - first : WS_HIST_SLOTS;
         fill_zero_kernel<<<(unsigned)count, 256, 0, s>>>(reinterpret_cast<uint4 *>(dhist), count * 256 * 8 / 16);
+        // One launch for the sixteen: a workgroup per 256 vectors of the sample, but no more than 512
+        // workgroups in all, shared out by size (every workgroup ends with one global atomic per exponent
+        // value it has seen: with 2048 workgroups per tensor those few addresses were half of the time).
+        HistogramArgs a;
+        a.n_items = 0;
+        a.every = every;
+        uint64_t want_all = 0;
+        for (size_t j = 0; j < count; ++j)
+            want_all += (items[first + j].n_elems * elem_bytes(dtype) / 16 / every + 255) / 256;
+        uint32_t grid = 0;
         for (size_t j = 0; j < count; ++j) {
             const enec_tune_item &it = items[first + j];
             if (it.n_elems == 0) continue;
-            const uint64_t nvec = it.n_elems * elem_bytes(dtype) / 16;
-            uint64_t want = (nvec / every + 255) / 256;
-            // at most two workgroups per CU: every workgroup ends with one global atomic per exponent value it
-            // has seen, and those, a few addresses for the whole grid, were half of the kernel's time at 2048
-            const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 512 ? 512 : want));
-            unsigned long long *slot = dhist + 256 * j;
-            if (dtype == ENEC_FP32) histogram_kernel<DT_FP32><<<grid, 256, 0, s>>>(it.in, it.n_elems, slot, every);
-            else if (dtype == ENEC_FP16) histogram_kernel<DT_FP16><<<grid, 256, 0, s>>>(it.in, it.n_elems, slot, every);
-            else histogram_kernel<DT_BF16><<<grid, 256, 0, s>>>(it.in, it.n_elems, slot, every);
+            const uint64_t want = (it.n_elems * elem_bytes(dtype) / 16 / every + 255) / 256;
+            uint64_t share = want_all > 512 ? want * 512 / want_all : want;
+            if (share < 1) share = 1;
+            HistogramItem &d = a.item[a.n_items++];
+            d.in = it.in;
+            d.n_elems = it.n_elems;
+            d.hist = dhist + 256 * j;
+            d.first = grid;
+            d.count = (uint32_t)share;
+            grid += d.count;
+        }
+        if (grid) {
+            for (uint32_t j = a.n_items; j < (uint32_t)MAX_BATCH; ++j) a.item[j] = a.item[0];
+            if (dtype == ENEC_FP32) histogram_kernel<DT_FP32><<<grid, 256, 0, s>>>(a);
+            else if (dtype == ENEC_FP16) histogram_kernel<DT_FP16><<<grid, 256, 0, s>>>(a);
+            else histogram_kernel<DT_BF16><<<grid, 256, 0, s>>>(a);
         }
         if (hipMemcpyAsync(host.data(), dhist, count * 256 * 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
             hipStreamSynchronize(s) != hipSuccess) {

@@ -1354,10 +1354,28 @@ __global__ void __launch_bounds__(512) decompress_kernel(const DecompressArgs p)
 // ---------------------------------------------------------------------------------
 constexpr uint32_t SAMPLE_CHUNK = 4096;     // elements; the sample is taken in whole chunks
 
+struct HistogramItem {          // one tensor of a launch
+    const void *in;
+    uint64_t n_elems;
+    unsigned long long *hist;   // 256 counters, zero at launch
+    uint32_t first, count;      // its workgroups: first .. first + count - 1
+};
+struct HistogramArgs {
+    HistogramItem item[MAX_BATCH];
+    uint32_t n_items, every;
+};
+
 template <int DT>
-__global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_t n_elems, unsigned long long *hist,
-                                                        uint32_t every)
+__global__ void __launch_bounds__(256) histogram_kernel(const HistogramArgs p)
 {
+    uint32_t ti = 0;
+    for (uint32_t i = 1; i < p.n_items; ++i)
+        if (blockIdx.x >= p.item[i].first) ti = i;
+    const void *in_ = p.item[ti].in;
+    const uint64_t n_elems = p.item[ti].n_elems;
+    unsigned long long *hist = p.item[ti].hist;
+    const uint32_t every = p.every;
+    const uint32_t wg = blockIdx.x - p.item[ti].first, wgs = p.item[ti].count;    // this tensor's share of the grid
     // 32 copies of the histogram, lane i of every wave counts into copy i mod 32: lanes with equal
     // exponents, the normal case, would otherwise queue up on one LDS word; the copies are 257 words
     // apart, which puts the same bin of all copies into different banks.  (Measured on this machine:
@@ -1371,7 +1389,7 @@ __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_
     uint32_t *mine = s_h + (tid & (COPIES - 1u)) * STRIDE;
     constexpr uint32_t PER_VEC = DT == DT_FP32 ? 4u : 8u;        // elements in 16 bytes
     const uint64_t nvec = n_elems / PER_VEC;
-    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    const uint64_t stride = (uint64_t)wgs * 256u;
     // the LDS counters cannot overflow: a workgroup counts at most 2^34 / 512 elements
     // the sample: chunks of SAMPLE_CHUNK elements whose number is a multiple of `every`
     constexpr uint32_t LOG_VPC = DT == DT_FP32 ? 10u : 9u;      // 16-byte vectors in a chunk
@@ -1394,7 +1412,7 @@ __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_
     };
     auto vec_of = [&](uint64_t sv) { return (((sv >> LOG_VPC) * every) << LOG_VPC) + (sv & ((1u << LOG_VPC) - 1u)); };
     // four vectors of a thread travel together
-    uint64_t sv = (uint64_t)blockIdx.x * 256u + tid;
+    uint64_t sv = (uint64_t)wg * 256u + tid;
     for (; sv + 3u * stride < picked; sv += 4u * stride) {
         uint4 q[4];
         bool ok[4];
@@ -1413,7 +1431,7 @@ __global__ void __launch_bounds__(256) histogram_kernel(const void *in_, uint64_
         if (v >= nvec) continue;
         count(reinterpret_cast<const uint4 *>(in_)[v]);
     }
-    if (blockIdx.x == 0 && tid < (uint32_t)(n_elems % PER_VEC) && ((nvec * PER_VEC) / SAMPLE_CHUNK) % every == 0) {
+    if (wg == 0 && tid < (uint32_t)(n_elems % PER_VEC) && ((nvec * PER_VEC) / SAMPLE_CHUNK) % every == 0) {
         const uint64_t e = nvec * PER_VEC + tid;
         uint32_t x;
         if constexpr (DT == DT_FP32) x = (reinterpret_cast<const uint32_t *>(in_)[e] >> 23) & 0xFFu;
