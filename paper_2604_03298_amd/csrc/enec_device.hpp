@@ -27,10 +27,10 @@
 #include <stdint.h>
 
 // Three waves per SIMD for the compression kernel: the register budget (168) that lets three
-// workgroups of 256 threads share a CU.  The fp32 instances (twice the row registers) and the
-// instances for group lengths 8 and 32 (larger record packers) spill at that budget and run
-// faster with two (measured: L = 8 layer 0.25 -> 0.21 ms, L = 32 on 2 x 90 MB 0.133 -> 0.102 ms;
-// L = 16 is faster with three, 0.082 against 0.091 ms).
+// workgroups of 256 threads share a CU.  The 16-bit formats fit it once the waiting block's
+// sign/mantissa bytes are parked in LDS (all group lengths; the layer with L = 8: 0.177 -> 0.154 ms,
+// with L = 32: 0.207 -> 0.181 ms against two waves with the bytes in registers).  The fp32 instances
+// (twice the row registers) spill at that budget and run faster with two.
 #ifndef ENEC_COMPRESS_OCCUPANCY
 #define ENEC_COMPRESS_WAVES (compress_sm_in_lds(DT, LPG) ? 3 : 2)
 #define ENEC_COMPRESS_OCCUPANCY __attribute__((amdgpu_waves_per_eu(ENEC_COMPRESS_WAVES, ENEC_COMPRESS_WAVES)))
@@ -41,9 +41,9 @@ namespace enec {
 constexpr int DT_BF16 = 0, DT_FP16 = 1, DT_FP32 = 2;
 constexpr int low_plane_bits(int m, int dt) { return m + (dt == DT_FP16 ? 3 : 0); }
 constexpr uint32_t exponent_bits(int dt) { return dt == DT_FP16 ? 5u : 8u; }
-// the compress instances that run three waves per SIMD (16-bit formats with group length 16) and
-// therefore park the waiting block's sign/mantissa bytes in LDS; the others get two waves
-constexpr bool compress_sm_in_lds(int dt, int lpg) { return dt != DT_FP32 && lpg == 2; }
+// the compress instances that run three waves per SIMD (the 16-bit formats) and therefore park the
+// waiting block's sign/mantissa bytes in LDS; the others get two waves
+constexpr bool compress_sm_in_lds(int dt, int /*lpg*/) { return dt != DT_FP32; }
 
 // ---------------------------------------------------------------------------------
 // Compile-time bit map of Alg. 2 for one column (8 values of W bits -> W bytes).
