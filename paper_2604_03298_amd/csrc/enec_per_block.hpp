@@ -203,8 +203,10 @@ compress_per_block_kernel(const PbCompressArgs p)
     // only waits for blocks that running workgroups hold or that the next workgroups to start will
     // draw, and every workgroup publishes its size before it waits for anything, so the look-back
     // makes progress whatever part of the grid is resident (every wait is bounded by the spin limit
-    // as well).  There are PB_TICKET_CLASSES counters: a workgroup draws from counter blockIdx mod 8,
-    // the t-th draw from counter c is block 8 t + c, and a class has as many workgroups as blocks.
+    // as well).  There are PB_TICKET_CLASSES counters: the blocks of a call's launches are numbered
+    // through, workgroup w of a launch draws from counter (the launch's first block + w) mod 8, the
+    // t-th draw from counter c is block 8 t + c, and every launch has as many workgroups of a class
+    // as blocks of it (the counters go on counting from one launch of the call to the next).
     // Returning atomics on one address are serialised at the memory side; with eight addresses the
     // kernel measured 5 % faster than with one.
     const uint32_t cls = (p.first_block + blockIdx.x) & (PB_TICKET_CLASSES - 1u);
