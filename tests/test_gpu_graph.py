@@ -64,7 +64,7 @@ def test_one_tuple_per_block_replays_from_a_graph(oracle):
     from paper_2604_03298_amd import enec
     enec.lib()
     rng = np.random.default_rng(5)
-    # 262 data blocks: 65 workgroups of four blocks and a second launch for the two left over
+    # 262 data blocks, one workgroup each (no multiple of the eight ticket counters), the last one ragged
     t = np.concatenate([W.gaussian(256 * 16384, 0.02, 1), np.zeros(16384, np.uint16),
                         rng.integers(0, 65536, 16384).astype(np.uint16), W.gaussian(3 * 16384 + 55, 0.2, 2)])
     want = oracle.compress_per_block(t, 16384)[1]
