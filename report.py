@@ -1,7 +1,8 @@
 """Runs the codec on all five synthetic configurations on one MI355X and prints one JSON line per
 configuration (throughput on uncompressed bytes, ratio, fraction of the 8 TB/s HBM peak in bytes
-moved).  `python report.py [--configs 1,2,2j,3a,3b,4,5,fp16,fp32]`.
-2j is configuration 2 tuned with the group length searched together with m (Eq. 4); the last two are the
+moved).  `python report.py [--configs 1,2,2j,2p,3a,3p,3b,4,4p,5,fp16,fp32]`.
+2j is configuration 2 tuned with the group length searched together with m (Eq. 4); 2p, 3p and 4p are configuration 2,
+configuration 3a and four tensors of configuration 4 with one tuple per data block; the last two are the
 seven matrix shapes of configuration 2 as fp16 / fp32 tensors, N(0, 0.02^2).
 
 Tensors of configurations 1-3 come from the seeded numpy generators of `workloads.py` (the ones the
@@ -128,7 +129,7 @@ def run_per_block(torch, enec, name, srcs, reps=5, dtype=0):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--configs", default="1,2,2j,2p,3a,3p,3b,4,5,fp16,fp32")
+    ap.add_argument("--configs", default="1,2,2j,2p,3a,3p,3b,4,4p,5,fp16,fp32")
     args = ap.parse_args()
     want = args.configs.split(",")
     import torch
@@ -161,6 +162,11 @@ def main():
     if "4" in want:
         srcs = [W.config4_device(torch, i) for i in range(32)]
         print(json.dumps(run_group(torch, enec, "4: 32 tensors 8192x28672", srcs, reps=3)[0]), flush=True)
+        del srcs
+        torch.cuda.empty_cache()
+    if "4p" in want:      # four of these tensors (1.9 GB) with one tuple per data block
+        srcs = [W.config4_device(torch, i) for i in range(4)]
+        print(json.dumps(run_per_block(torch, enec, "4p: 4 tensors 8192x28672, one tuple per data block", srcs, reps=5)), flush=True)
         del srcs
         torch.cuda.empty_cache()
     if "5" in want:
